@@ -1,0 +1,381 @@
+"""Pins for the CPU oracle: each oracle function is checked against something other
+than itself -- the code tables the paper prints (tests/golden/), float64 / exact
+rational brute force, closed forms, invariants and hand-worked rows.  CPU only.
+"""
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2410_16144_amd import synth
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+
+
+def _rows(name):
+    out = []
+    with open(os.path.join(GOLDEN, name)) as f:
+        for line in f:
+            line = line.strip()
+            if line and not line.startswith("#"):
+                out.append(line.split())
+    return out
+
+
+# ---------------------------------------------------------------- Table 1 (I2_S)
+
+def test_i2s_code_table_matches_paper_table1():
+    rows = _rows("table1_i2s.txt")
+    assert len(rows) == 3
+    for w, code in rows:
+        assert oracle.i2s_encode(int(w)) == int(code, 2)
+        assert oracle.i2s_decode(int(code, 2)) == int(w)
+
+
+def test_i2s_rejects_what_table1_does_not_list():
+    assert oracle.i2s_decode(3) == -2          # code 11 is unused
+    for bad in (-2, 2, 5, -128, 127):
+        assert oracle.i2s_encode(bad) == -1
+
+
+@pytest.mark.parametrize("N,K", [(1, 1), (3, 4), (5, 7), (9, 67), (16, 128), (2, 1001)])
+def test_i2s_pack_roundtrip_and_bit_positions(N, K):
+    rng = synth.rng_for(11 + N * 1000 + K)
+    w = synth.ternary_weights(rng, N, K)
+    packed, bad = oracle.i2s_pack(w)
+    assert bad == 0
+    assert packed.shape == (N, (K + 3) // 4)
+    back, bad2 = oracle.i2s_unpack(packed, K)
+    assert bad2 == 0
+    assert np.array_equal(back, w)
+    # bit positions, re-derived independently: weight k sits at bits 2(k%4) of byte k//4
+    for n in range(min(N, 3)):
+        for k in range(K):
+            code = (int(packed[n, k // 4]) >> (2 * (k % 4))) & 3
+            assert code == int(w[n, k]) + 1
+    # 2 bits per weight: 4 weights per byte
+    assert packed.size == N * ((K + 3) // 4)
+
+
+def test_i2s_pack_counts_non_ternary_and_stores_zero():
+    w = np.array([[1, 0, -1, 2, -3, 1]], np.int8)
+    packed, bad = oracle.i2s_pack(w)
+    assert bad == 2
+    back, _ = oracle.i2s_unpack(packed, 6)
+    assert back.tolist() == [[1, 0, -1, 0, 0, 1]]
+
+
+def test_i2s_unpack_flags_unused_code():
+    packed = np.array([[0b11_10_01_00]], np.uint8)   # codes (k=0..3): 0,1,2,3
+    back, bad = oracle.i2s_unpack(packed, 4)
+    assert bad == 1
+    assert back.tolist() == [[-1, 0, 1, 0]]
+
+
+# ---------------------------------------------------------------- Tables 2, 3 (TL1, TL2)
+
+def test_tl1_index_matches_paper_table2():
+    rows = _rows("table2_tl1.txt")
+    assert len(rows) == 9
+    seen = set()
+    for w0, w1, idx in rows:
+        assert oracle.tl1_index(int(w0), int(w1)) == int(idx, 2)
+        seen.add(int(idx, 2))
+    assert seen == set(range(9))
+
+
+def test_tl2_code_matches_paper_table3_printed_rows():
+    rows = _rows("table3_tl2.txt")
+    assert len(rows) == 9
+    for w0, w1, w2, sign, idx in rows:
+        assert oracle.tl2_code(int(w0), int(w1), int(w2)) == (int(sign), int(idx, 2))
+
+
+def test_tl2_code_is_a_bijection_on_27_triples():
+    # 27 triples -> 1 + 2*13 distinct (sign, idx) codes; negation flips only the sign
+    codes = {}
+    for a in (-1, 0, 1):
+        for b in (-1, 0, 1):
+            for c in (-1, 0, 1):
+                s, i = oracle.tl2_code(a, b, c)
+                assert 0 <= i <= 13 and s in (0, 1)
+                assert (s, i) not in codes
+                codes[(s, i)] = (a, b, c)
+                s2, i2 = oracle.tl2_code(-a, -b, -c)
+                assert i2 == i and (i == 0 or s2 == 1 - s)
+    assert len(codes) == 27
+    # 5 bits per 3 weights vs TL1's 4 bits per 2 weights: one sixth smaller (Section 2)
+    assert Fraction(5, 3) == Fraction(2) * (1 - Fraction(1, 6))
+
+
+# ---------------------------------------------------------------- activation quantizer
+
+def test_quant_hand_worked_row():
+    # amax = 4, inv = 31.75 exactly; products 31.75, -63.5, 15.875, 127
+    x = np.array([[1.0, -2.0, 0.5, 4.0]], np.float32)
+    q, a, s = oracle.quant_act(x)
+    assert q.tolist() == [[32, -64, 16, 127]]
+    assert a[0] == np.float32(4.0) / np.float32(127.0)
+    assert s[0] == 32 - 64 + 16 + 127
+
+
+def test_quant_ties_round_half_to_even():
+    # amax = 127 -> inv = 1 exactly, so the products are the inputs themselves
+    x = np.array([[127.0, 62.5, -61.5, 0.5, 1.5, 2.5, -0.5, -2.5]], np.float32)
+    q, a, _ = oracle.quant_act(x)
+    assert q.tolist() == [[127, 62, -62, 0, 2, 2, 0, -2]]   # half-away would give 63,-62,1,2,3,-1,-3
+    assert a[0] == np.float32(1.0)
+
+
+def test_quant_zero_row_and_mixed_rows():
+    x = np.zeros((3, 9), np.float32)
+    x[1] = np.arange(9, dtype=np.float32) - 4
+    q, a, s = oracle.quant_act(x)
+    assert not q[0].any() and not q[2].any()
+    assert a[0] == 0.0 and a[2] == 0.0 and s[0] == 0 and s[2] == 0
+    assert q[1].tolist() == [-127, -95, -64, -32, 0, 32, 64, 95, 127]  # 31.75*k: 95.25->95, 63.5->64 (even)
+    assert a[1] == np.float32(4.0) / np.float32(127.0)
+
+
+def test_quant_tiny_absmax_is_a_zero_token():
+    # 127/amax overflows fp32 for amax < ~3.7e-37: defined as an all-zero token
+    x = np.array([[1e-38, -5e-39, 0.0, 2e-40]], np.float32)
+    q, a, s = oracle.quant_act(x)
+    assert not q.any() and a[0] == 0.0 and s[0] == 0
+    # just above the threshold the ordinary rule applies
+    x2 = np.array([[1e-36, -5e-37, 0.0]], np.float32)
+    q2, a2, _ = oracle.quant_act(x2)
+    assert q2[0, 0] == 127 and q2[0, 2] == 0 and int(q2[0, 1]) in (-63, -64)
+    assert a2[0] == np.float32(1e-36) / np.float32(127.0)
+
+
+def _exact_checks(x32, q, a_scale):
+    """Exact-rational brute force: q must be round_half_even(x*127/amax) wherever the exact
+    value is farther from a rounding boundary than the two fp32 roundings can move it."""
+    checked = 0
+    for m in range(x32.shape[0]):
+        row = [Fraction(float(v)) for v in x32[m]]
+        amax = max(abs(v) for v in row)
+        if amax == 0:
+            assert not q[m].any()
+            continue
+        assert Fraction(float(a_scale[m])) == Fraction(float(np.float32(float(amax)) / np.float32(127)))
+        for k, v in enumerate(row):
+            r = v * 127 / amax
+            lo = r.numerator // r.denominator          # floor
+            frac = r - lo
+            dist_to_half = abs(frac - Fraction(1, 2))
+            slack = abs(r) * Fraction(1, 2 ** 21) + Fraction(1, 2 ** 100)
+            if dist_to_half > slack:
+                expect = lo + (1 if frac > Fraction(1, 2) else 0)
+                assert int(q[m, k]) == expect, (m, k, float(r))
+                checked += 1
+    return checked
+
+
+@pytest.mark.parametrize("seed,outliers", [(1, 0.0), (2, 0.01), (3, 0.2)])
+def test_quant_matches_exact_rational_arithmetic(seed, outliers):
+    rng = synth.rng_for(seed)
+    x = synth.activations(rng, 4, 97, outlier_frac=outliers)
+    q, a, s = oracle.quant_act(x)
+    n = _exact_checks(x, q, a)
+    assert n >= 4 * 97 - 4          # practically every element is decidable
+    assert np.array_equal(s, q.astype(np.int64).sum(axis=1))
+
+
+def test_quant_absmax_properties():
+    rng = synth.rng_for(7)
+    x = synth.activations(rng, 16, 333, outlier_frac=0.01)
+    q, a, s = oracle.quant_act(x)
+    assert q.dtype == np.int8 and a.dtype == np.float32 and s.dtype == np.int32
+    for m in range(16):
+        j = int(np.argmax(np.abs(x[m])))
+        assert abs(int(q[m, j])) == 127 and np.sign(q[m, j]) == np.sign(x[m, j])
+        assert np.abs(q[m].astype(np.int32)).max() == 127
+        assert q[m].min() >= -127                      # -128 is unreachable
+        amax = np.float64(np.abs(x[m]).max())
+        assert abs(np.float64(a[m]) * 127 - amax) <= amax * 2.0 ** -23
+        err = np.abs(q[m].astype(np.float64) * np.float64(a[m]) - x[m].astype(np.float64))
+        assert err.max() <= 0.5 * np.float64(a[m]) * (1 + 1e-5)
+
+
+def test_quant_sign_flip_and_power_of_two_scaling():
+    rng = synth.rng_for(8)
+    x = synth.activations(rng, 5, 200)
+    q, a, s = oracle.quant_act(x)
+    qn, an, sn = oracle.quant_act(-x)
+    assert np.array_equal(qn, -q) and np.array_equal(an, a) and np.array_equal(sn, -s)
+    for t in (-7, 3, 20):
+        qt, at, _ = oracle.quant_act(x * np.float32(2.0 ** t))
+        assert np.array_equal(qt, q)
+        assert np.array_equal(at, a * np.float32(2.0 ** t))
+
+
+def test_bf16_widening_and_bf16_quant():
+    import torch
+    assert oracle.bf16_to_f32(np.array([0x3F80, 0xC000, 0x3F00, 0x0000, 0x4049], np.uint16)).tolist() == \
+        [1.0, -2.0, 0.5, 0.0, 3.140625]
+    rng = synth.rng_for(9)
+    x = synth.activations(rng, 3, 130, outlier_frac=0.02)
+    bits = synth.to_bf16_bits(x)
+    # widening agrees with torch's bf16 -> fp32 conversion
+    t = torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).float().numpy()
+    assert np.array_equal(oracle.bf16_to_f32(bits), t)
+    # the generator's rounding agrees with torch's fp32 -> bf16 (RNE)
+    tb = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(bits, tb)
+    # quantizing bf16 bits == quantizing their exact fp32 widening
+    q1, a1, s1 = oracle.quant_act(bits)
+    q2, a2, s2 = oracle.quant_act(t)
+    assert np.array_equal(q1, q2) and np.array_equal(a1, a2) and np.array_equal(s1, s2)
+
+
+# ---------------------------------------------------------------- product + dequant
+
+@pytest.mark.parametrize("M,K,N,seed", [(1, 1, 1, 0), (1, 5, 3, 1), (2, 67, 9, 2), (3, 64, 7, 3), (3, 33, 8, 4)])
+def test_brute_force_float64_matmul(M, K, N, seed):
+    rng = synth.rng_for(100 + seed)
+    w = synth.ternary_weights(rng, N, K)
+    w_scale = synth.draw_w_scale(rng)
+    x = synth.activations(rng, M, K)
+    r = oracle.bitlinear(x, w, w_scale)
+    q64 = r["q"].astype(np.int64)
+    # integer part: plain int64 matmul (library routine on the transposed operand)
+    assert np.array_equal(r["acc"], (q64 @ w.astype(np.int64).T).astype(np.int32))
+    # full-precision product of the dequantized operands
+    ref = (r["q"].astype(np.float64) * r["a_scale"].astype(np.float64)[:, None]) @ \
+          (w.astype(np.float64) * np.float64(w_scale)).T
+    assert np.allclose(r["out"], ref, rtol=1e-6, atol=0.0)
+    assert np.array_equal(r["out"] == 0, r["acc"] == 0)
+    # and the product approximates the unquantized one to within the quantization step
+    full = x.astype(np.float64) @ (w.astype(np.float64) * np.float64(w_scale)).T
+    bound = 0.5 * r["a_scale"].astype(np.float64)[:, None] * np.abs(w).sum(axis=1)[None, :] * float(w_scale)
+    assert np.all(np.abs(r["out"] - full) <= bound * (1 + 1e-5) + 1e-30)
+
+
+def test_operand_orientation_is_x_times_w_transposed():
+    # N != K and an asymmetric W: a transposed operand cannot pass
+    w = np.array([[1, 0, 0], [0, -1, 1]], np.int8)        # N=2, K=3
+    q = np.array([[10, 20, 30]], np.int8)
+    assert oracle.matmul_i32(q, w).tolist() == [[10, 10]]
+    assert oracle.matmul_i32_cols(q, w, [1]).tolist() == [[10]]
+
+
+def test_zero_invariants():
+    rng = synth.rng_for(20)
+    w = synth.ternary_weights(rng, 6, 40)
+    x = synth.activations(rng, 2, 40)
+    r = oracle.bitlinear(x, np.zeros_like(w), np.float32(0.03))
+    assert not r["acc"].any() and not r["out"].any()
+    r = oracle.bitlinear(np.zeros_like(x), w, np.float32(0.03))
+    assert not r["q"].any() and not r["a_scale"].any() and not r["acc"].any() and not r["out"].any()
+    x[1] = 0
+    r = oracle.bitlinear(x, w, np.float32(0.03))
+    assert not r["out"][1].any() and r["out"][0].any()
+
+
+def test_sign_flip_invariants():
+    rng = synth.rng_for(21)
+    w = synth.ternary_weights(rng, 11, 75)
+    x = synth.activations(rng, 3, 75)
+    s = np.float32(0.02)
+    r = oracle.bitlinear(x, w, s)
+    rw = oracle.bitlinear(x, -w, s)
+    rx = oracle.bitlinear(-x, w, s)
+    assert np.array_equal(rw["acc"], -r["acc"]) and np.array_equal(rw["out"], -r["out"])
+    assert np.array_equal(rx["q"], -r["q"]) and np.array_equal(rx["a_scale"], r["a_scale"])
+    assert np.array_equal(rx["acc"], -r["acc"]) and np.array_equal(rx["out"], -r["out"])
+
+
+def test_closed_forms():
+    rng = synth.rng_for(22)
+    K, N, M = 50, 50, 2
+    q = rng.integers(-127, 128, size=(M, K), dtype=np.int8)
+    # all +1: every output is the row sum of q
+    acc = oracle.matmul_i32(q, np.ones((N, K), np.int8))
+    assert np.array_equal(acc, np.repeat(q.astype(np.int32).sum(1)[:, None], N, axis=1))
+    # one-hot rows pick single activations; negative one-hot negates
+    perm = rng.permutation(K)
+    onehot = np.zeros((N, K), np.int8)
+    onehot[np.arange(N), perm] = 1
+    assert np.array_equal(oracle.matmul_i32(q, onehot), q[:, perm].astype(np.int32))
+    assert np.array_equal(oracle.matmul_i32(q, -onehot), -q[:, perm].astype(np.int32))
+    # row = sign(q): sum of |q|
+    wsgn = np.sign(q[0]).astype(np.int8)[None, :]
+    assert oracle.matmul_i32(q[:1], wsgn)[0, 0] == np.abs(q[0].astype(np.int32)).sum()
+    # permuting K in both operands changes nothing
+    w = synth.ternary_weights(rng, N, K)
+    assert np.array_equal(oracle.matmul_i32(q[:, perm], w[:, perm]), oracle.matmul_i32(q, w))
+    # extreme magnitudes: K*127 with all-(+127) activations
+    big = oracle.matmul_i32(np.full((1, 4096), 127, np.int8), np.ones((1, 4096), np.int8))
+    assert big[0, 0] == 127 * 4096
+
+
+def test_matmul_cols_matches_full():
+    rng = synth.rng_for(23)
+    w = synth.ternary_weights(rng, 40, 90)
+    q = rng.integers(-127, 128, size=(3, 90), dtype=np.int8)
+    idx = np.array([0, 39, 7, 7, 21])
+    assert np.array_equal(oracle.matmul_i32_cols(q, w, idx), oracle.matmul_i32(q, w)[:, idx])
+
+
+def test_dequant_definition():
+    acc = np.array([[0, 1, -3, 1 << 22]], np.int32)
+    a = np.array([0.5], np.float32)
+    out = oracle.dequant(acc, np.float32(0.25), a)           # scale product = 2^-3: exact
+    assert out.tolist() == [[0.0, 0.125, -0.375, float(1 << 19)]]
+    rng = synth.rng_for(24)
+    acc = rng.integers(-(1 << 22), 1 << 22, size=(4, 33), dtype=np.int32)
+    a = rng.uniform(0.001, 0.3, size=4).astype(np.float32)
+    ws = np.float32(0.0371)
+    out = oracle.dequant(acc, ws, a)
+    ref = acc.astype(np.float64) * np.float64(ws) * a.astype(np.float64)[:, None]
+    assert np.allclose(out, ref, rtol=3 * 2.0 ** -24, atol=0)
+
+
+# ---------------------------------------------------------------- the paper's LUT kernels agree
+
+@pytest.mark.parametrize("K", [1, 2, 3, 7, 64, 65, 129, 200])
+def test_tl1_and_tl2_lookup_kernels_equal_the_plain_product(K):
+    # Table 7 of the paper: I2_S, TL1 and TL2 are all lossless -> identical accumulators
+    rng = synth.rng_for(300 + K)
+    N = 13
+    w = synth.ternary_weights(rng, N, K)
+    q = rng.integers(-127, 128, size=(1, K), dtype=np.int8)
+    plain = oracle.matmul_i32(q, w)[0]
+    assert np.array_equal(oracle.tl1_gemv_i32(q[0], w), plain)
+    assert np.array_equal(oracle.tl2_gemv_i32(q[0], w), plain)
+
+
+# ---------------------------------------------------------------- absmean ternarization
+
+def test_absmean_definition():
+    rng = synth.rng_for(30)
+    wf = (rng.standard_normal((37, 53)) * 0.02).astype(np.float32)
+    wt, s = oracle.absmean_ternarize(wf)
+    assert s == np.float32(np.abs(wf.astype(np.float64)).mean())
+    assert set(np.unique(wt).tolist()) <= {-1, 0, 1}
+    d = np.float64(s) + 1e-5
+    mag = np.abs(wf.astype(np.float64))
+    assert np.all(wt[mag < 0.5 * d * (1 - 1e-6)] == 0)
+    sel = mag > 0.5 * d * (1 + 1e-6)
+    assert np.array_equal(wt[sel], np.sign(wf[sel]).astype(np.int8))
+    assert np.all(np.abs(wt[mag > 1.5 * d]) == 1)          # clipped, not 2
+
+
+def test_absmean_constructed_case_recovers_ternary():
+    rng = synth.rng_for(31)
+    t = synth.ternary_weights(rng, 20, 50, p_zero=0.4)
+    c = np.float32(0.02)
+    wt, s = oracle.absmean_ternarize(t.astype(np.float32) * c)
+    p = np.count_nonzero(t) / t.size
+    assert abs(float(s) - float(c) * p) <= 1e-8
+    assert np.array_equal(wt, t)
+    wt0, s0 = oracle.absmean_ternarize(np.zeros((4, 4), np.float32))
+    assert s0 == 0 and not wt0.any()
+
+
+def test_oracle_reports_threads():
+    assert oracle.num_threads() >= 1
