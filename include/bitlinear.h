@@ -1,0 +1,205 @@
+/*
+ * bitlinear.h -- C ABI of the MI355X (gfx950) BitLinear library.
+ *
+ * The library computes the BitNet b1.58 BitLinear product that the ternary
+ * kernels of arXiv 2410.16144 (Section 2) accelerate:
+ *
+ *     out[m,n] = ( sum_k q[m,k] * W[n,k] ) * w_scale * a_scale[m]
+ *
+ * with W in {-1,0,+1}^{N x K} stored as 2-bit codes (Table 1: -1->00, 0->01,
+ * +1->10), q the per-token absmax int8 quantization of the activations, the
+ * sum taken exactly in int32 and one fp32 dequantization multiply at the end.
+ *
+ * General rules for every entry point
+ *   - Pointers named *_dev are DEVICE pointers owned by the caller (allocate
+ *     them any way you like, e.g. hipMalloc or a torch tensor's data_ptr()).
+ *     Pointers without that suffix are HOST pointers, read during the call.
+ *   - The library never allocates or frees device memory, never synchronizes
+ *     and owns no stream: all work is enqueued on `stream` (a hipStream_t
+ *     passed as void*; NULL = the default stream) and the call returns at
+ *     once.  Results are valid once the stream reaches that point.
+ *   - Every call returns a bl_status.  Arguments are validated on the host
+ *     BEFORE any HIP call, so a bad call has no effect on the device.
+ *     A failed launch is reported as BL_ERR_HIP.
+ *   - Nothing here is thread-hostile; calls that touch the same buffers on
+ *     different streams race like any other GPU work.
+ */
+#ifndef BITLINEAR_H
+#define BITLINEAR_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    BL_OK = 0,
+    BL_ERR_NULL = 1,        /* a required pointer is NULL                         */
+    BL_ERR_SHAPE = 2,       /* N, K, M or a stride is out of range                */
+    BL_ERR_M_RANGE = 3,     /* bl_gemv / bl_gemv_batch called with M outside 1..8 */
+    BL_ERR_BUF_SMALL = 4,   /* descriptor's byte count does not match its shape   */
+    BL_ERR_ALIGN = 5,       /* a pointer is not aligned as documented             */
+    BL_ERR_DTYPE = 6,       /* unknown bl_dtype                                   */
+    BL_ERR_LAYOUT = 7,      /* descriptor version is not BL_LAYOUT_VERSION        */
+    BL_ERR_HIP = 8,         /* the HIP runtime refused the launch                 */
+    BL_ERR_COUNT = 9        /* bl_gemv_batch: count outside 1..BL_MAX_BATCH       */
+} bl_status;
+
+typedef enum { BL_F32 = 0, BL_BF16 = 1 } bl_dtype;
+
+#define BL_LAYOUT_VERSION 1
+#define BL_TILE_N 64        /* rows (output features) per packed tile            */
+#define BL_TILE_K 64        /* K extent per packed tile                           */
+#define BL_MAX_K 1048576    /* keeps every int32 partial sum far from overflow    */
+#define BL_MAX_GEMV_M 8
+#define BL_MAX_BATCH 8
+#define BL_MAX_GEMM_M 4194304
+
+/*
+ * Host-side description of one packed ternary matrix.  Plain data; copy it,
+ * store it next to the blob.  The packed blob itself is position independent.
+ *
+ * Packed layout (version 1), chosen for 64-lane wavefronts: the matrix is
+ * padded to Np x Kp (multiples of 64; padding weights are 0) and cut into
+ * tiles of 64 rows x 64 k.  Tile (rb, kc) is the 1 KiB block at byte offset
+ * ((rb * (Kp/64)) + kc) * 1024.  Inside a tile, the 16 bytes at offset 16*r
+ * belong to row 64*rb + r (one 128-bit load per lane, 1 KiB per wavefront);
+ * they are four little-endian 32-bit words s = 0..3, word s covering
+ * k = 64*kc + 16*s + t, t = 0..15, with the code (w+1) of k-offset t = 4j + b
+ * stored at bits [8b + 2j, 8b + 2j + 1].  Hence (word >> 2j) & 0x03030303 is
+ * four byte-wide codes for four consecutive k, aligned with one 32-bit word
+ * of int8 activations.
+ */
+typedef struct {
+    int32_t  version;   /* BL_LAYOUT_VERSION                                   */
+    int32_t  reserved;  /* 0                                                   */
+    int64_t  N;         /* output features (rows of W)                         */
+    int64_t  K;         /* input features (columns of W)                       */
+    int64_t  Np;        /* N rounded up to BL_TILE_N                           */
+    int64_t  Kp;        /* K rounded up to BL_TILE_K; also the row stride of q */
+    uint64_t bytes;     /* size of the packed blob = Np * Kp / 4               */
+    float    w_scale;   /* per-matrix (absmean) scale, used in the dequant     */
+    float    reserved2; /* 0                                                   */
+} bl_packed_desc;
+
+/* K rounded up to the layout's K tile: the row stride (in bytes) of quantized
+ * activations.  Returns -1 if K is outside 1..BL_MAX_K. */
+int64_t bl_padded_k(int64_t K);
+
+/* N rounded up to the layout's row tile.  Returns -1 if N < 1. */
+int64_t bl_padded_n(int64_t N);
+
+/* Fill *d for an N x K ternary matrix with dequantization scale w_scale.
+ * Errors: BL_ERR_NULL, BL_ERR_SHAPE (N < 1, K outside 1..BL_MAX_K). */
+bl_status bl_packed_desc_init(int64_t N, int64_t K, float w_scale, bl_packed_desc *d);
+
+/*
+ * Offline weight transformation (Section 2, I2_S: every weight becomes a
+ * 2-bit value, Table 1) into the tiled layout described above.
+ *   w_dev         [N,K] int8, row-major, values in {-1,0,+1}
+ *   d             host descriptor from bl_packed_desc_init
+ *   packed_dev    d->bytes bytes, 16-byte aligned; fully overwritten
+ *   bad_count_dev optional int32 counter (caller zeroes it): incremented once
+ *                 per input that is not ternary; such inputs are packed as 0
+ * Errors: BL_ERR_NULL, BL_ERR_LAYOUT, BL_ERR_SHAPE, BL_ERR_BUF_SMALL,
+ *         BL_ERR_ALIGN, BL_ERR_HIP.
+ */
+bl_status bl_pack_ternary(const int8_t *w_dev, const bl_packed_desc *d, void *packed_dev,
+                          int32_t *bad_count_dev, void *stream);
+
+/* Inverse of bl_pack_ternary ("the 2-bit weights are unpacked to the original
+ * values", Table 1): writes w_dev [N,K] int8.  The unused code 11 decodes to 0.
+ * For tests and round trips; not on the hot path. */
+bl_status bl_unpack_ternary(const void *packed_dev, const bl_packed_desc *d, int8_t *w_dev,
+                            void *stream);
+
+/*
+ * Per-token absmax quantization of activations to int8 (the BitNet b1.58
+ * quantizer the paper builds on).  For each row m, in fp32 with every
+ * operation rounded to nearest-even on its own:
+ *     amax = max_k |x[m,k]|;  inv = 127 / amax;
+ *     q[m,k] = clip(round_half_even(x[m,k] * inv), -128, 127);
+ *     a_scale[m] = amax / 127;   q_sum[m] = sum_k q[m,k].
+ * A row whose inv is not finite (amax = 0 or below ~3.7e-37) gives q = 0,
+ * a_scale = 0, q_sum = 0.  NaN/Inf inputs are undefined behaviour.
+ *   x_dev       [M, ldx] fp32 or bf16 (dt), ldx >= K in elements; aligned to
+ *               its element size (16-byte alignment enables vector loads)
+ *   q_dev       [M, Kp] int8, Kp = bl_padded_k(K), 16-byte aligned; columns
+ *               K..Kp-1 are written as 0
+ *   a_scale_dev [M] fp32
+ *   q_sum_dev   [M] int32, may be NULL (bl_gemv and bl_gemm need it)
+ * Errors: BL_ERR_NULL, BL_ERR_DTYPE, BL_ERR_SHAPE (M < 1, K out of range,
+ *         ldx < K), BL_ERR_ALIGN, BL_ERR_HIP.
+ */
+bl_status bl_quant_act(const void *x_dev, bl_dtype dt, int64_t M, int64_t K, int64_t ldx,
+                       int8_t *q_dev, float *a_scale_dev, int32_t *q_sum_dev, void *stream);
+
+/*
+ * Decode product, 1 <= M <= 8 tokens (Section 2, I2_S: codes are turned back
+ * into weights in registers and a plain multiply-add GEMV follows):
+ *     acc[m,n] = sum_k q[m,k] * W[n,k]   (int32, exact)
+ *     out[m,n] = (float)acc[m,n] * (w_scale * a_scale[m])
+ * Streams the packed weights exactly once, whatever M is.
+ *   packed_dev  blob written by bl_pack_ternary for descriptor d
+ *   q_dev, a_scale_dev, q_sum_dev   as written by bl_quant_act ([M,Kp], [M], [M])
+ *   out_dev     [M,N] fp32 row-major
+ *   acc_dev     optional [M,N] int32 row-major: the exact accumulators
+ * Errors: BL_ERR_NULL, BL_ERR_LAYOUT, BL_ERR_SHAPE, BL_ERR_BUF_SMALL,
+ *         BL_ERR_M_RANGE, BL_ERR_ALIGN, BL_ERR_HIP.
+ */
+bl_status bl_gemv(const void *packed_dev, const bl_packed_desc *d, const int8_t *q_dev,
+                  const float *a_scale_dev, const int32_t *q_sum_dev, int64_t M,
+                  float *out_dev, int32_t *acc_dev, void *stream);
+
+/* One problem of a grouped decode launch: the arguments of bl_gemv. */
+typedef struct {
+    const void           *packed_dev;
+    const bl_packed_desc *desc;        /* host pointer */
+    const int8_t         *q_dev;
+    const float          *a_scale_dev;
+    const int32_t        *q_sum_dev;
+    float                *out_dev;
+    int32_t              *acc_dev;     /* may be NULL */
+} bl_gemv_item;
+
+/*
+ * `count` independent bl_gemv problems (1..BL_MAX_BATCH, all with the same M)
+ * in ONE kernel launch: e.g. the Q/K/V projections or gate/up of a decoder
+ * layer (Appendix A shapes), which share their input.  Each item is
+ * validated like a bl_gemv call; results are identical to `count` separate
+ * calls.  `items` is a host array, read during the call.
+ * Extra error: BL_ERR_COUNT.
+ */
+bl_status bl_gemv_batch(const bl_gemv_item *items, int32_t count, int64_t M, void *stream);
+
+/*
+ * Prefill product, 1 <= M <= BL_MAX_GEMM_M: the same mathematics as bl_gemv,
+ * computed as a dense contraction on the int8 matrix cores.  Arguments as
+ * for bl_gemv (M outside the range: BL_ERR_SHAPE).
+ */
+bl_status bl_gemm(const void *packed_dev, const bl_packed_desc *d, const int8_t *q_dev,
+                  const float *a_scale_dev, const int32_t *q_sum_dev, int64_t M,
+                  float *out_dev, int32_t *acc_dev, void *stream);
+
+/*
+ * Launch-shape override for experiments and sweeps; process-wide, not thread-safe, never
+ * changes results.  Keys: "gemv_waves" = waves per workgroup of the decode kernel
+ * (1, 2, 4, 8, 16; 0 = automatic).  Errors: BL_ERR_NULL, BL_ERR_SHAPE (unknown key/value).
+ */
+bl_status bl_set_tuning(const char *key, int32_t value);
+
+/* Static, never-NULL description of a status code. */
+const char *bl_status_str(bl_status s);
+
+/* Text of the HIP error behind the calling thread's most recent BL_ERR_HIP ("no error" if
+ * the thread's last launch succeeded).  Static string owned by the HIP runtime. */
+const char *bl_last_hip_error(void);
+
+/* Library version string (static). */
+const char *bl_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BITLINEAR_H */

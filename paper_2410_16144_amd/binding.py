@@ -1,0 +1,169 @@
+"""ctypes binding of libbitlinear.so: the same names and arguments as include/bitlinear.h.
+
+Argument marshalling only.  Device pointers are plain integers (e.g. tensor.data_ptr()),
+the stream is a hipStream_t handle as an integer (0 = default stream).  Every wrapper raises
+BitLinearError on a non-zero status.  There is no fallback of any kind: if the shared
+library has not been built, loading raises.
+"""
+import ctypes
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libbitlinear.so")
+
+BL_OK = 0
+BL_ERR_NULL, BL_ERR_SHAPE, BL_ERR_M_RANGE, BL_ERR_BUF_SMALL, BL_ERR_ALIGN = 1, 2, 3, 4, 5
+BL_ERR_DTYPE, BL_ERR_LAYOUT, BL_ERR_HIP, BL_ERR_COUNT = 6, 7, 8, 9
+BL_F32, BL_BF16 = 0, 1
+BL_LAYOUT_VERSION = 1
+BL_TILE_N = 64
+BL_TILE_K = 64
+BL_MAX_K = 1048576
+BL_MAX_GEMV_M = 8
+BL_MAX_BATCH = 8
+BL_MAX_GEMM_M = 4194304
+
+# every symbol include/bitlinear.h declares
+DECLARED_SYMBOLS = (
+    "bl_padded_k", "bl_padded_n", "bl_packed_desc_init", "bl_pack_ternary", "bl_unpack_ternary",
+    "bl_quant_act", "bl_gemv", "bl_gemv_batch", "bl_gemm", "bl_set_tuning", "bl_status_str", "bl_last_hip_error", "bl_version",
+)
+
+
+class BitLinearError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = int(status)
+        detail = ""
+        if self.status == BL_ERR_HIP:
+            detail = ": " + lib().bl_last_hip_error().decode()
+        super().__init__("%s failed: status %d (%s%s)" % (where, self.status, status_str(self.status), detail))
+
+
+class PackedDesc(ctypes.Structure):
+    """Mirror of bl_packed_desc."""
+    _fields_ = [("version", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("N", ctypes.c_int64), ("K", ctypes.c_int64), ("Np", ctypes.c_int64), ("Kp", ctypes.c_int64),
+                ("bytes", ctypes.c_uint64), ("w_scale", ctypes.c_float), ("reserved2", ctypes.c_float)]
+
+
+class GemvItem(ctypes.Structure):
+    """Mirror of bl_gemv_item."""
+    _fields_ = [("packed_dev", ctypes.c_void_p), ("desc", ctypes.POINTER(PackedDesc)),
+                ("q_dev", ctypes.c_void_p), ("a_scale_dev", ctypes.c_void_p), ("q_sum_dev", ctypes.c_void_p),
+                ("out_dev", ctypes.c_void_p), ("acc_dev", ctypes.c_void_p)]
+
+
+_lib = None
+
+
+def lib():
+    """Load the shared library (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(
+            "libbitlinear.so is not built (%s). Run `python -c 'import __graft_entry__ as g; g.build()'` "
+            "or `python paper_2410_16144_amd/build.py`. There is no CPU fallback." % LIB_PATH)
+    # PyTorch first: its wheel carries the HIP runtime this library is linked against, and the
+    # process must hold exactly one HIP runtime (streams and allocations are per runtime).
+    import torch  # noqa: F401
+    l = ctypes.CDLL(LIB_PATH)
+    vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32
+    dp = ctypes.POINTER(PackedDesc)
+    l.bl_padded_k.argtypes = [i64]
+    l.bl_padded_k.restype = i64
+    l.bl_padded_n.argtypes = [i64]
+    l.bl_padded_n.restype = i64
+    l.bl_packed_desc_init.argtypes = [i64, i64, ctypes.c_float, dp]
+    l.bl_pack_ternary.argtypes = [vp, dp, vp, vp, vp]
+    l.bl_unpack_ternary.argtypes = [vp, dp, vp, vp]
+    l.bl_quant_act.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, vp, vp, vp]
+    l.bl_gemv.argtypes = [vp, dp, vp, vp, vp, i64, vp, vp, vp]
+    l.bl_gemv_batch.argtypes = [ctypes.POINTER(GemvItem), i32, i64, vp]
+    l.bl_gemm.argtypes = [vp, dp, vp, vp, vp, i64, vp, vp, vp]
+    l.bl_set_tuning.argtypes = [ctypes.c_char_p, i32]
+    l.bl_status_str.argtypes = [ctypes.c_int]
+    l.bl_status_str.restype = ctypes.c_char_p
+    l.bl_version.restype = ctypes.c_char_p
+    l.bl_last_hip_error.restype = ctypes.c_char_p
+    for name in ("bl_packed_desc_init", "bl_pack_ternary", "bl_unpack_ternary", "bl_quant_act", "bl_gemv",
+                 "bl_gemv_batch", "bl_gemm", "bl_set_tuning"):
+        getattr(l, name).restype = ctypes.c_int
+    _lib = l
+    return l
+
+
+def _check(status, where):
+    if status != BL_OK:
+        raise BitLinearError(status, where)
+
+
+def status_str(status: int) -> str:
+    return lib().bl_status_str(int(status)).decode()
+
+
+def version() -> str:
+    return lib().bl_version().decode()
+
+
+def bl_padded_k(K: int) -> int:
+    return int(lib().bl_padded_k(K))
+
+
+def bl_padded_n(N: int) -> int:
+    return int(lib().bl_padded_n(N))
+
+
+def bl_packed_desc_init(N: int, K: int, w_scale: float) -> PackedDesc:
+    d = PackedDesc()
+    _check(lib().bl_packed_desc_init(N, K, float(w_scale), ctypes.byref(d)), "bl_packed_desc_init")
+    return d
+
+
+def bl_pack_ternary(w_dev: int, desc: PackedDesc, packed_dev: int, bad_count_dev: int = 0, stream: int = 0):
+    _check(lib().bl_pack_ternary(w_dev, ctypes.byref(desc), packed_dev, bad_count_dev or None, stream or None),
+           "bl_pack_ternary")
+
+
+def bl_unpack_ternary(packed_dev: int, desc: PackedDesc, w_dev: int, stream: int = 0):
+    _check(lib().bl_unpack_ternary(packed_dev, ctypes.byref(desc), w_dev, stream or None), "bl_unpack_ternary")
+
+
+def bl_quant_act(x_dev: int, dtype: int, M: int, K: int, ldx: int, q_dev: int, a_scale_dev: int,
+                 q_sum_dev: int = 0, stream: int = 0):
+    _check(lib().bl_quant_act(x_dev, dtype, M, K, ldx, q_dev, a_scale_dev, q_sum_dev or None, stream or None),
+           "bl_quant_act")
+
+
+def bl_gemv(packed_dev: int, desc: PackedDesc, q_dev: int, a_scale_dev: int, q_sum_dev: int, M: int,
+            out_dev: int, acc_dev: int = 0, stream: int = 0):
+    _check(lib().bl_gemv(packed_dev, ctypes.byref(desc), q_dev, a_scale_dev, q_sum_dev, M, out_dev,
+                         acc_dev or None, stream or None), "bl_gemv")
+
+
+def make_gemv_items(items):
+    """items: iterable of (packed_dev, desc, q_dev, a_scale_dev, q_sum_dev, out_dev, acc_dev) -> ctypes array.
+    The PackedDesc objects must outlive the array."""
+    items = list(items)
+    arr = (GemvItem * len(items))()
+    for i, (packed, desc, q, a, s, out, acc) in enumerate(items):
+        arr[i] = GemvItem(packed, ctypes.pointer(desc), q, a, s, out, acc or None)
+    return arr
+
+
+def bl_gemv_batch(items, M: int, stream: int = 0):
+    """items: a ctypes GemvItem array from make_gemv_items (or an iterable of tuples)."""
+    if not isinstance(items, ctypes.Array):
+        items = make_gemv_items(items)
+    _check(lib().bl_gemv_batch(items, len(items), M, stream or None), "bl_gemv_batch")
+
+
+def bl_gemm(packed_dev: int, desc: PackedDesc, q_dev: int, a_scale_dev: int, q_sum_dev: int, M: int,
+            out_dev: int, acc_dev: int = 0, stream: int = 0):
+    _check(lib().bl_gemm(packed_dev, ctypes.byref(desc), q_dev, a_scale_dev, q_sum_dev, M, out_dev,
+                         acc_dev or None, stream or None), "bl_gemm")
+
+
+def bl_set_tuning(key: str, value: int):
+    _check(lib().bl_set_tuning(key.encode(), int(value)), "bl_set_tuning")

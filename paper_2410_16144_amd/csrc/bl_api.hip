@@ -1,0 +1,192 @@
+// C-ABI entry points: host-side validation, then one kernel launch each.
+// No entry point allocates, frees or synchronizes.
+#include <string.h>
+
+#include "bl_internal.hpp"
+
+namespace {
+
+inline bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+bl_status check_desc(const bl_packed_desc* d) {
+    if (!d) return BL_ERR_NULL;
+    if (d->version != BL_LAYOUT_VERSION) return BL_ERR_LAYOUT;
+    if (d->N < 1 || d->K < 1 || d->K > BL_MAX_K || d->N > INT32_MAX - BL_TILE_N) return BL_ERR_SHAPE;
+    if (d->Np != bl_padded_n(d->N) || d->Kp != bl_padded_k(d->K)) return BL_ERR_SHAPE;
+    if (d->bytes != (uint64_t)d->Np * (uint64_t)d->Kp / 4) return BL_ERR_BUF_SMALL;
+    return BL_OK;
+}
+
+bl_status check_product_args(const void* packed, const bl_packed_desc* d, const int8_t* q, const float* a_scale,
+                             const int32_t* q_sum, int64_t M, const float* out, const int32_t* acc) {
+    if (!packed || !d || !q || !a_scale || !q_sum || !out) return BL_ERR_NULL;
+    bl_status s = check_desc(d);
+    if (s != BL_OK) return s;
+    if (M < 1 || M > INT32_MAX / 2) return BL_ERR_SHAPE;
+    if (!aligned(packed, 16) || !aligned(q, 16) || !aligned(a_scale, 4) || !aligned(q_sum, 4) ||
+        !aligned(out, 4) || (acc && !aligned(acc, 4)))
+        return BL_ERR_ALIGN;
+    return BL_OK;
+}
+
+bl::GemvProblem make_problem(const void* packed, const bl_packed_desc* d, const int8_t* q, const float* a_scale,
+                             const int32_t* q_sum, float* out, int32_t* acc) {
+    bl::GemvProblem p;
+    p.packed = static_cast<const uint4*>(packed);
+    p.q = reinterpret_cast<const int32_t*>(q);
+    p.a_scale = a_scale;
+    p.q_sum = q_sum;
+    p.out = out;
+    p.acc = acc;
+    p.N = (int32_t)d->N;
+    p.KC = (int32_t)(d->Kp / BL_TILE_K);
+    p.row_blocks = (int32_t)(d->Np / BL_TILE_N);
+    p.w_scale = d->w_scale;
+    return p;
+}
+
+thread_local hipError_t t_last_hip_error = hipSuccess;
+
+inline bl_status hip_status(hipError_t e) {
+    t_last_hip_error = e;
+    return e == hipSuccess ? BL_OK : BL_ERR_HIP;
+}
+
+// hipGetLastError() reports the most recent error of ANY earlier HIP call on this thread, also
+// other libraries' (benign, already handled) ones.  Drop those so that the check after our launch
+// sees only our launch.
+inline void drop_stale_hip_error() { (void)hipGetLastError(); }
+
+}  // namespace
+
+extern "C" {
+
+int64_t bl_padded_k(int64_t K) {
+    if (K < 1 || K > BL_MAX_K) return -1;
+    return (K + BL_TILE_K - 1) / BL_TILE_K * BL_TILE_K;
+}
+
+int64_t bl_padded_n(int64_t N) {
+    if (N < 1 || N > INT32_MAX - BL_TILE_N) return -1;
+    return (N + BL_TILE_N - 1) / BL_TILE_N * BL_TILE_N;
+}
+
+bl_status bl_packed_desc_init(int64_t N, int64_t K, float w_scale, bl_packed_desc* d) {
+    if (!d) return BL_ERR_NULL;
+    if (bl_padded_n(N) < 0 || bl_padded_k(K) < 0) return BL_ERR_SHAPE;
+    memset(d, 0, sizeof *d);
+    d->version = BL_LAYOUT_VERSION;
+    d->N = N;
+    d->K = K;
+    d->Np = bl_padded_n(N);
+    d->Kp = bl_padded_k(K);
+    d->bytes = (uint64_t)d->Np * (uint64_t)d->Kp / 4;
+    d->w_scale = w_scale;
+    return BL_OK;
+}
+
+bl_status bl_pack_ternary(const int8_t* w_dev, const bl_packed_desc* d, void* packed_dev, int32_t* bad_count_dev,
+                          void* stream) {
+    if (!w_dev || !d || !packed_dev) return BL_ERR_NULL;
+    bl_status s = check_desc(d);
+    if (s != BL_OK) return s;
+    if (!aligned(packed_dev, 16) || (bad_count_dev && !aligned(bad_count_dev, 4))) return BL_ERR_ALIGN;
+    drop_stale_hip_error();
+    return hip_status(bl::launch_pack(w_dev, d->N, d->K, d->Np, d->Kp, static_cast<uint32_t*>(packed_dev),
+                                      bad_count_dev, static_cast<hipStream_t>(stream)));
+}
+
+bl_status bl_unpack_ternary(const void* packed_dev, const bl_packed_desc* d, int8_t* w_dev, void* stream) {
+    if (!w_dev || !d || !packed_dev) return BL_ERR_NULL;
+    bl_status s = check_desc(d);
+    if (s != BL_OK) return s;
+    if (!aligned(packed_dev, 16)) return BL_ERR_ALIGN;
+    drop_stale_hip_error();
+    return hip_status(bl::launch_unpack(static_cast<const uint32_t*>(packed_dev), d->N, d->K, d->Np, d->Kp, w_dev,
+                                        static_cast<hipStream_t>(stream)));
+}
+
+bl_status bl_quant_act(const void* x_dev, bl_dtype dt, int64_t M, int64_t K, int64_t ldx, int8_t* q_dev,
+                       float* a_scale_dev, int32_t* q_sum_dev, void* stream) {
+    if (!x_dev || !q_dev || !a_scale_dev) return BL_ERR_NULL;
+    if (dt != BL_F32 && dt != BL_BF16) return BL_ERR_DTYPE;
+    int64_t Kp = bl_padded_k(K);
+    if (M < 1 || M > INT32_MAX / 2 || Kp < 0 || ldx < K) return BL_ERR_SHAPE;
+    if (!aligned(x_dev, dt == BL_F32 ? 4 : 2) || !aligned(q_dev, 16) || !aligned(a_scale_dev, 4) ||
+        (q_sum_dev && !aligned(q_sum_dev, 4)))
+        return BL_ERR_ALIGN;
+    drop_stale_hip_error();
+    return hip_status(bl::launch_quant(x_dev, dt == BL_BF16, M, K, ldx, Kp, q_dev, a_scale_dev, q_sum_dev,
+                                       static_cast<hipStream_t>(stream)));
+}
+
+bl_status bl_gemv(const void* packed_dev, const bl_packed_desc* d, const int8_t* q_dev, const float* a_scale_dev,
+                  const int32_t* q_sum_dev, int64_t M, float* out_dev, int32_t* acc_dev, void* stream) {
+    bl_gemv_item it = {packed_dev, d, q_dev, a_scale_dev, q_sum_dev, out_dev, acc_dev};
+    return bl_gemv_batch(&it, 1, M, stream);
+}
+
+bl_status bl_gemv_batch(const bl_gemv_item* items, int32_t count, int64_t M, void* stream) {
+    if (!items) return BL_ERR_NULL;
+    if (count < 1 || count > BL_MAX_BATCH) return BL_ERR_COUNT;
+    if (M < 1 || M > BL_MAX_GEMV_M) return BL_ERR_M_RANGE;
+    bl::GemvBatch b;
+    memset(&b, 0, sizeof b);
+    int64_t blocks = 0;
+    for (int i = 0; i < count; ++i) {
+        const bl_gemv_item& it = items[i];
+        bl_status s = check_product_args(it.packed_dev, it.desc, it.q_dev, it.a_scale_dev, it.q_sum_dev, M,
+                                         it.out_dev, it.acc_dev);
+        if (s != BL_OK) return s;
+        b.p[i] = make_problem(it.packed_dev, it.desc, it.q_dev, it.a_scale_dev, it.q_sum_dev, it.out_dev, it.acc_dev);
+        b.first_block[i] = (int32_t)blocks;
+        blocks += b.p[i].row_blocks;
+        if (blocks > INT32_MAX / 2) return BL_ERR_SHAPE;
+    }
+    for (int i = count; i <= BL_MAX_BATCH; ++i) b.first_block[i] = (int32_t)blocks;
+    b.count = count;
+    drop_stale_hip_error();
+    return hip_status(bl::launch_gemv(b, (int)M, static_cast<hipStream_t>(stream)));
+}
+
+bl_status bl_gemm(const void* packed_dev, const bl_packed_desc* d, const int8_t* q_dev, const float* a_scale_dev,
+                  const int32_t* q_sum_dev, int64_t M, float* out_dev, int32_t* acc_dev, void* stream) {
+    bl_status s = check_product_args(packed_dev, d, q_dev, a_scale_dev, q_sum_dev, M, out_dev, acc_dev);
+    if (s != BL_OK) return s;
+    if (M > BL_MAX_GEMM_M) return BL_ERR_SHAPE;
+    bl::GemvProblem p = make_problem(packed_dev, d, q_dev, a_scale_dev, q_sum_dev, out_dev, acc_dev);
+    drop_stale_hip_error();
+    return hip_status(bl::launch_gemm(p, M, static_cast<hipStream_t>(stream)));
+}
+
+const char* bl_status_str(bl_status s) {
+    switch (s) {
+        case BL_OK: return "ok";
+        case BL_ERR_NULL: return "a required pointer is NULL";
+        case BL_ERR_SHAPE: return "shape or stride out of range";
+        case BL_ERR_M_RANGE: return "M outside 1..8 for the decode product";
+        case BL_ERR_BUF_SMALL: return "descriptor byte count does not match its shape";
+        case BL_ERR_ALIGN: return "pointer not aligned as documented";
+        case BL_ERR_DTYPE: return "unknown activation dtype";
+        case BL_ERR_LAYOUT: return "unknown packed layout version";
+        case BL_ERR_HIP: return "HIP launch failed";
+        case BL_ERR_COUNT: return "batch count outside 1..8";
+    }
+    return "unknown status";
+}
+
+bl_status bl_set_tuning(const char* key, int32_t value) {
+    if (!key) return BL_ERR_NULL;
+    if (strcmp(key, "gemv_waves") == 0) {
+        if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8 && value != 16) return BL_ERR_SHAPE;
+        bl::set_gemv_waves(value);
+        return BL_OK;
+    }
+    return BL_ERR_SHAPE;
+}
+
+const char* bl_last_hip_error(void) { return hipGetErrorString(t_last_hip_error); }
+
+const char* bl_version(void) { return "bitlinear-gfx950 0.1 (layout 1)"; }
+
+}  // extern "C"

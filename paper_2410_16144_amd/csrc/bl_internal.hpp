@@ -1,0 +1,53 @@
+// Internal declarations shared by the library's translation units (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "bitlinear.h"
+
+namespace bl {
+
+constexpr int kTileN = BL_TILE_N;            // rows per packed tile = lanes per wavefront
+constexpr int kTileK = BL_TILE_K;            // k per packed tile
+constexpr int kTileBytes = kTileN * kTileK / 4;  // 1 KiB: one 128-bit load per lane
+constexpr int kWave = 64;
+
+// One decode problem as the kernel sees it (all device pointers).
+struct GemvProblem {
+    const uint4*   packed;
+    const int32_t* q;        // int8 activations viewed as 32-bit words, row stride Kp/4 words
+    const float*   a_scale;
+    const int32_t* q_sum;
+    float*         out;
+    int32_t*       acc;      // may be null
+    int32_t        N;
+    int32_t        KC;       // Kp / 64: tiles along K
+    int32_t        row_blocks;  // Np / 64
+    float          w_scale;
+};
+
+struct GemvBatch {
+    GemvProblem p[BL_MAX_BATCH];
+    int32_t     first_block[BL_MAX_BATCH + 1];  // prefix sum of row_blocks
+    int32_t     count;
+};
+
+// Launchers (each returns the hipError_t of its launch).
+hipError_t launch_pack(const int8_t* w, int64_t N, int64_t K, int64_t Np, int64_t Kp, uint32_t* packed,
+                       int32_t* bad_count, hipStream_t s);
+hipError_t launch_unpack(const uint32_t* packed, int64_t N, int64_t K, int64_t Np, int64_t Kp, int8_t* w,
+                         hipStream_t s);
+hipError_t launch_quant(const void* x, int is_bf16, int64_t M, int64_t K, int64_t ldx, int64_t Kp, int8_t* q,
+                        float* a_scale, int32_t* q_sum, hipStream_t s);
+hipError_t launch_gemv(const GemvBatch& b, int M, hipStream_t s);
+hipError_t launch_gemm(const GemvProblem& p, int64_t M, hipStream_t s);
+
+// Launch-shape overrides for experiments (0 = choose automatically).
+void set_gemv_waves(int waves);
+
+// ---- device helpers -------------------------------------------------------------------
+
+// Four byte-wide codes (0,1,2) for k-offsets 4j..4j+3 of a packed word.
+__device__ __forceinline__ uint32_t codes_of(uint32_t word, int j) { return (word >> (2 * j)) & 0x03030303u; }
+
+}  // namespace bl

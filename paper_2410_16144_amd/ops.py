@@ -1,0 +1,126 @@
+"""Torch-tensor conveniences over the C ABI: allocate outputs, pass data_ptr() and the current
+stream.  No arithmetic happens here; every step runs in the library's HIP kernels."""
+from dataclasses import dataclass
+from typing import Optional
+
+import torch
+
+from . import binding as B
+
+
+def _stream() -> int:
+    return int(torch.cuda.current_stream().cuda_stream)
+
+
+@dataclass
+class PackedWeight:
+    blob: torch.Tensor          # uint8 [desc.bytes], device
+    desc: B.PackedDesc
+
+    @property
+    def N(self):
+        return int(self.desc.N)
+
+    @property
+    def K(self):
+        return int(self.desc.K)
+
+    @property
+    def packed_bytes(self) -> int:
+        """Unpadded 2-bit size N*K/4: the algorithmic bytes of one decode product."""
+        return self.N * self.K // 4
+
+
+def pack_ternary(w: torch.Tensor, w_scale: float, bad_count: Optional[torch.Tensor] = None) -> PackedWeight:
+    """w: [N,K] int8 device tensor in {-1,0,+1} -> PackedWeight (bl_pack_ternary)."""
+    assert w.is_cuda and w.dtype == torch.int8 and w.dim() == 2 and w.is_contiguous()
+    N, K = w.shape
+    desc = B.bl_packed_desc_init(N, K, w_scale)
+    blob = torch.empty(int(desc.bytes), dtype=torch.uint8, device=w.device)
+    B.bl_pack_ternary(w.data_ptr(), desc, blob.data_ptr(), bad_count.data_ptr() if bad_count is not None else 0,
+                      _stream())
+    return PackedWeight(blob, desc)
+
+
+def unpack_ternary(pw: PackedWeight) -> torch.Tensor:
+    w = torch.empty((pw.N, pw.K), dtype=torch.int8, device=pw.blob.device)
+    B.bl_unpack_ternary(pw.blob.data_ptr(), pw.desc, w.data_ptr(), _stream())
+    return w
+
+
+@dataclass
+class QuantAct:
+    q: torch.Tensor         # int8 [M, Kp]
+    a_scale: torch.Tensor   # fp32 [M]
+    q_sum: torch.Tensor     # int32 [M]
+    K: int
+
+    @property
+    def M(self):
+        return int(self.q.shape[0])
+
+
+def alloc_quant(M: int, K: int, device) -> QuantAct:
+    Kp = B.bl_padded_k(K)
+    return QuantAct(torch.empty((M, Kp), dtype=torch.int8, device=device),
+                    torch.empty((M,), dtype=torch.float32, device=device),
+                    torch.empty((M,), dtype=torch.int32, device=device), K)
+
+
+def quant_act(x: torch.Tensor, out: Optional[QuantAct] = None) -> QuantAct:
+    """x: [M,K] fp32 or bf16 device tensor (last dim contiguous) -> QuantAct (bl_quant_act)."""
+    assert x.is_cuda and x.dim() == 2 and x.stride(1) == 1
+    if x.dtype == torch.float32:
+        dt = B.BL_F32
+    elif x.dtype == torch.bfloat16:
+        dt = B.BL_BF16
+    else:
+        raise TypeError("activations must be float32 or bfloat16")
+    M, K = x.shape
+    if out is None:
+        out = alloc_quant(M, K, x.device)
+    B.bl_quant_act(x.data_ptr(), dt, M, K, x.stride(0), out.q.data_ptr(), out.a_scale.data_ptr(),
+                   out.q_sum.data_ptr(), _stream())
+    return out
+
+
+def _product(fn, pw: PackedWeight, qa: QuantAct, out, want_acc):
+    M = qa.M
+    assert qa.K == pw.K
+    if out is None:
+        out = torch.empty((M, pw.N), dtype=torch.float32, device=pw.blob.device)
+    acc = torch.empty((M, pw.N), dtype=torch.int32, device=pw.blob.device) if want_acc else None
+    fn(pw.blob.data_ptr(), pw.desc, qa.q.data_ptr(), qa.a_scale.data_ptr(), qa.q_sum.data_ptr(), M,
+       out.data_ptr(), acc.data_ptr() if acc is not None else 0, _stream())
+    return (out, acc) if want_acc else out
+
+
+def gemv(pw: PackedWeight, qa: QuantAct, out: Optional[torch.Tensor] = None, want_acc: bool = False):
+    """Decode product, M <= 8 (bl_gemv).  Returns out [M,N] fp32 (and acc int32 if want_acc)."""
+    return _product(B.bl_gemv, pw, qa, out, want_acc)
+
+
+def gemm(pw: PackedWeight, qa: QuantAct, out: Optional[torch.Tensor] = None, want_acc: bool = False):
+    """Prefill product (bl_gemm)."""
+    return _product(B.bl_gemm, pw, qa, out, want_acc)
+
+
+class GemvGroup:
+    """A prepared grouped decode launch (bl_gemv_batch): fixed weights, activations and outputs."""
+
+    def __init__(self, weights, acts, outs=None, want_acc=False):
+        assert 1 <= len(weights) <= B.BL_MAX_BATCH and len(weights) == len(acts)
+        self.M = acts[0].M
+        dev = weights[0].blob.device
+        self.weights, self.acts = list(weights), list(acts)
+        self.outs = list(outs) if outs is not None else [
+            torch.empty((self.M, w.N), dtype=torch.float32, device=dev) for w in weights]
+        self.accs = [torch.empty((self.M, w.N), dtype=torch.int32, device=dev) for w in weights] if want_acc else None
+        self.items = B.make_gemv_items(
+            (w.blob.data_ptr(), w.desc, a.q.data_ptr(), a.a_scale.data_ptr(), a.q_sum.data_ptr(), o.data_ptr(),
+             self.accs[i].data_ptr() if want_acc else 0)
+            for i, (w, a, o) in enumerate(zip(self.weights, self.acts, self.outs)))
+
+    def launch(self):
+        B.bl_gemv_batch(self.items, self.M, _stream())
+        return self.outs

@@ -1,0 +1,109 @@
+"""Host-side logic of the C ABI: exported symbols, descriptor arithmetic and argument
+validation.  No kernel is launched (validation runs before any HIP call), so this runs on a
+machine without a GPU.
+"""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2410_16144_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "bitlinear.h")).read()
+    body = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(bl_[a-z0-9_]+)\s*\(", body))
+    assert declared == set(B.DECLARED_SYMBOLS)
+    lib = B.lib()
+    for name in sorted(declared):
+        assert hasattr(lib, name), name
+    assert "gfx950" in B.version()
+
+
+def test_struct_layout_matches_header():
+    assert ctypes.sizeof(B.PackedDesc) == 56
+    assert B.PackedDesc.bytes.offset == 40 and B.PackedDesc.w_scale.offset == 48
+    assert ctypes.sizeof(B.GemvItem) == 56
+
+
+def test_padding_and_descriptor():
+    assert B.bl_padded_k(1) == 64 and B.bl_padded_k(64) == 64 and B.bl_padded_k(65) == 128
+    assert B.bl_padded_k(0) == -1 and B.bl_padded_k(B.BL_MAX_K + 1) == -1 and B.bl_padded_k(B.BL_MAX_K) == B.BL_MAX_K
+    assert B.bl_padded_n(1) == 64 and B.bl_padded_n(8640) == 8640 and B.bl_padded_n(0) == -1
+    d = B.bl_packed_desc_init(3200, 8640, 0.02)
+    assert (d.version, d.N, d.K, d.Np, d.Kp, d.bytes) == (1, 3200, 8640, 3200, 8640, 3200 * 8640 // 4)
+    d = B.bl_packed_desc_init(70, 100, 1.0)
+    assert (d.Np, d.Kp, d.bytes) == (128, 128, 128 * 128 // 4)
+    for n, k in ((0, 64), (64, 0), (-1, 5), (5, B.BL_MAX_K + 1)):
+        with pytest.raises(B.BitLinearError) as e:
+            B.bl_packed_desc_init(n, k, 1.0)
+        assert e.value.status == B.BL_ERR_SHAPE
+
+
+def _st(fn, *a):
+    with pytest.raises(B.BitLinearError) as e:
+        fn(*a)
+    return e.value.status
+
+
+def test_argument_validation_happens_before_any_launch():
+    d = B.bl_packed_desc_init(128, 128, 0.5)
+    P = 0x10000  # a fake, well-aligned "device pointer": never dereferenced because validation fails first
+    # nulls
+    assert _st(B.bl_pack_ternary, 0, d, P) == B.BL_ERR_NULL
+    assert _st(B.bl_pack_ternary, P, d, 0) == B.BL_ERR_NULL
+    assert _st(B.bl_unpack_ternary, 0, d, P) == B.BL_ERR_NULL
+    assert _st(B.bl_quant_act, 0, B.BL_F32, 1, 128, 128, P, P, P) == B.BL_ERR_NULL
+    assert _st(B.bl_gemv, P, d, P, P, 0, 1, P) == B.BL_ERR_NULL          # q_sum is required
+    assert _st(B.bl_gemm, P, d, 0, P, P, 1, P) == B.BL_ERR_NULL
+    # M range
+    assert _st(B.bl_gemv, P, d, P, P, P, 9, P) == B.BL_ERR_M_RANGE
+    assert _st(B.bl_gemv, P, d, P, P, P, 0, P) == B.BL_ERR_M_RANGE
+    assert _st(B.bl_gemm, P, d, P, P, P, 0, P) == B.BL_ERR_SHAPE
+    assert _st(B.bl_gemm, P, d, P, P, P, B.BL_MAX_GEMM_M + 1, P) == B.BL_ERR_SHAPE
+    # alignment
+    assert _st(B.bl_pack_ternary, P, d, P + 4) == B.BL_ERR_ALIGN
+    assert _st(B.bl_gemv, P + 8, d, P, P, P, 1, P) == B.BL_ERR_ALIGN
+    assert _st(B.bl_gemv, P, d, P + 4, P, P, 1, P) == B.BL_ERR_ALIGN
+    assert _st(B.bl_gemv, P, d, P, P + 2, P, 1, P) == B.BL_ERR_ALIGN
+    assert _st(B.bl_quant_act, P + 2, B.BL_F32, 1, 128, 128, P, P, P) == B.BL_ERR_ALIGN
+    assert _st(B.bl_quant_act, P + 1, B.BL_BF16, 1, 128, 128, P, P, P) == B.BL_ERR_ALIGN
+    assert _st(B.bl_quant_act, P, B.BL_F32, 1, 128, 128, P + 8, P, P) == B.BL_ERR_ALIGN
+    # dtype / shapes
+    assert _st(B.bl_quant_act, P, 7, 1, 128, 128, P, P, P) == B.BL_ERR_DTYPE
+    assert _st(B.bl_quant_act, P, B.BL_F32, 0, 128, 128, P, P, P) == B.BL_ERR_SHAPE
+    assert _st(B.bl_quant_act, P, B.BL_F32, 1, 128, 100, P, P, P) == B.BL_ERR_SHAPE   # ldx < K
+    assert _st(B.bl_quant_act, P, B.BL_F32, 1, 0, 0, P, P, P) == B.BL_ERR_SHAPE
+    # descriptor tampering
+    bad = B.bl_packed_desc_init(128, 128, 0.5)
+    bad.version = 2
+    assert _st(B.bl_gemv, P, bad, P, P, P, 1, P) == B.BL_ERR_LAYOUT
+    bad = B.bl_packed_desc_init(128, 128, 0.5)
+    bad.bytes -= 1
+    assert _st(B.bl_pack_ternary, P, bad, P) == B.BL_ERR_BUF_SMALL
+    bad = B.bl_packed_desc_init(128, 128, 0.5)
+    bad.Kp = 192
+    assert _st(B.bl_gemm, P, bad, P, P, P, 1, P) == B.BL_ERR_SHAPE
+    # batch count
+    items = B.make_gemv_items([(P, d, P, P, P, P, 0)])
+    assert B.lib().bl_gemv_batch(items, 0, 1, None) == B.BL_ERR_COUNT
+    assert B.lib().bl_gemv_batch(items, 9, 1, None) == B.BL_ERR_COUNT
+    assert B.lib().bl_gemv_batch(None, 1, 1, None) == B.BL_ERR_NULL
+    # tuning hook
+    assert _st(B.bl_set_tuning, "nonsense", 1) == B.BL_ERR_SHAPE
+    assert _st(B.bl_set_tuning, "gemv_waves", 3) == B.BL_ERR_SHAPE
+    B.bl_set_tuning("gemv_waves", 0)
+
+
+def test_status_strings():
+    seen = set()
+    for s in range(0, 10):
+        txt = B.status_str(s)
+        assert txt and txt != "unknown status"
+        seen.add(txt)
+    assert len(seen) == 10
+    assert B.status_str(99) == "unknown status"

@@ -1,0 +1,291 @@
+"""GPU parity: every C-ABI entry point against the CPU oracle, element by element, on the same
+seeded inputs.  int8 activations, scales and int32 accumulators must be bit-identical; fp32
+outputs within 1e-6 relative (and exactly 0 where the accumulator is 0).
+"""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2410_16144_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+REL_TOL = 1e-6   # product of the two scales, three roundings at most
+
+
+@pytest.fixture(scope="module")
+def dev():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    return torch.device("cuda:0")
+
+
+@pytest.fixture(scope="module")
+def ops():
+    from paper_2410_16144_amd import ops as _ops
+    from paper_2410_16144_amd import binding
+    binding.lib()   # fails loudly if the library is not built
+    return _ops
+
+
+def _to_dev_bf16(bits, dev):
+    return torch.from_numpy(bits.view(np.int16)).to(dev).view(torch.bfloat16)
+
+
+def _check_out(out_gpu, acc_ref, w_scale, a_scale_ref):
+    ref = oracle.dequant(acc_ref, w_scale, a_scale_ref)
+    got = out_gpu.cpu().numpy()
+    assert got.shape == ref.shape
+    denom = np.maximum(np.abs(ref), 1e-30)
+    assert np.all(np.abs(got - ref) <= REL_TOL * denom), float(np.max(np.abs(got - ref) / denom))
+    assert np.array_equal(got == 0, ref == 0)
+
+
+def decode_blob_host(blob, N, K):
+    """Independent reading of the documented version-1 layout (see include/bitlinear.h)."""
+    Np, Kp = (N + 63) // 64 * 64, (K + 63) // 64 * 64
+    words = np.frombuffer(blob.tobytes(), dtype="<u4").reshape(Np // 64, Kp // 64, 64, 4)  # rb, kc, r, s
+    w = np.zeros((Np, Kp), np.int8)
+    w5 = w.reshape(Np // 64, 64, Kp // 64, 4, 16)                                          # rb, r, kc, s, t
+    for t in range(16):
+        j, b = t // 4, t % 4
+        codes = (words >> np.uint32(8 * b + 2 * j)) & np.uint32(3)
+        assert codes.max() <= 2
+        w5[:, :, :, :, t] = (codes.astype(np.int8) - 1).transpose(0, 2, 1, 3)
+    return w[:N, :K], w
+
+
+# ------------------------------------------------------------------ pack / unpack
+
+@pytest.mark.parametrize("N,K", [(64, 64), (1, 1), (70, 100), (130, 1000), (257, 4097 - 64), (1536, 1536),
+                                 (3200, 8640)])
+def test_pack_unpack_roundtrip_and_documented_layout(dev, ops, N, K):
+    rng = synth.rng_for(N * 7 + K)
+    w = synth.ternary_weights(rng, N, K, p_zero=0.4)
+    wd = torch.from_numpy(w).to(dev)
+    pw = ops.pack_ternary(wd, 0.02)
+    assert pw.blob.numel() == ((N + 63) // 64 * 64) * ((K + 63) // 64 * 64) // 4
+    back = ops.unpack_ternary(pw)
+    assert torch.equal(back, wd)
+    got, padded = decode_blob_host(pw.blob.cpu().numpy(), N, K)
+    assert np.array_equal(got, w)
+    padded[:N, :K] = 0
+    assert not padded.any()                       # padding is weight 0 (code 01)
+
+
+def test_pack_counts_non_ternary(dev, ops):
+    w = synth.ternary_weights(synth.rng_for(3), 100, 200)
+    w[5, 7] = 2
+    w[99, 199] = -128
+    w[0, 0] = 127
+    bad = torch.zeros(1, dtype=torch.int32, device=dev)
+    pw = ops.pack_ternary(torch.from_numpy(w).to(dev), 1.0, bad_count=bad)
+    assert int(bad.item()) == 3
+    w[5, 7] = w[99, 199] = w[0, 0] = 0
+    assert np.array_equal(ops.unpack_ternary(pw).cpu().numpy(), w)
+
+
+# ------------------------------------------------------------------ activation quantizer
+
+def _quant_both(ops, dev, x_np, bf16):
+    if bf16:
+        bits = synth.to_bf16_bits(x_np)
+        ref = oracle.quant_act(bits)
+        xd = _to_dev_bf16(bits, dev)
+    else:
+        ref = oracle.quant_act(x_np)
+        xd = torch.from_numpy(x_np).to(dev)
+    qa = ops.quant_act(xd)
+    return qa, ref
+
+
+def _assert_quant_equal(qa, ref, K):
+    q_ref, a_ref, s_ref = ref
+    q = qa.q.cpu().numpy()
+    assert np.array_equal(q[:, :K], q_ref)
+    assert not q[:, K:].any()
+    assert np.array_equal(qa.a_scale.cpu().numpy().view(np.uint32), a_ref.view(np.uint32))
+    assert np.array_equal(qa.q_sum.cpu().numpy(), s_ref)
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("M,K,outl", [(1, 1536, 0.0), (1, 3200, 0.01), (3, 8640, 0.01), (8, 4096, 0.0),
+                                      (5, 100, 0.0), (2, 1001, 0.05), (1, 7, 0.0), (64, 11008, 0.0),
+                                      (1, 33792, 0.0)])
+def test_quant_act_bit_exact(dev, ops, M, K, outl, bf16):
+    rng = synth.rng_for(M * 100003 + K)
+    x = synth.activations(rng, M, K, outlier_frac=outl)
+    qa, ref = _quant_both(ops, dev, x, bf16)
+    _assert_quant_equal(qa, ref, K)
+
+
+def test_quant_act_edge_rows(dev, ops):
+    K = 256
+    x = np.zeros((8, K), np.float32)
+    rng = synth.rng_for(77)
+    x[1] = rng.standard_normal(K).astype(np.float32)
+    x[2, :8] = [127.0, 62.5, -61.5, 0.5, 1.5, 2.5, -0.5, -2.5]        # exact ties (inv = 1)
+    x[3] = 1e-38                                                      # absmax too small: zero token
+    x[3, 5] = -2e-40
+    x[4, :5] = [5e-37, -2.5e-37, 8e-39, -1e-45, 4e-39]                # denormal inputs, finite inv (2.54e38)
+    x[5] = x[1] * np.float32(2.0 ** 40)
+    x[6] = -x[1]
+    x[7, 100] = -3.0                                                  # single non-zero
+    qa, ref = _quant_both(ops, dev, x, False)
+    _assert_quant_equal(qa, ref, K)
+    q = qa.q.cpu().numpy()
+    assert q[2, :8].tolist() == [127, 62, -62, 0, 2, 2, 0, -2]
+    assert not q[0].any() and not q[3].any() and float(qa.a_scale[3]) == 0.0
+    assert q[4, :5].tolist() == [127, -63, 2, 0, 1]                    # denormals are not flushed
+    assert np.array_equal(q[5], q[1]) and np.array_equal(q[6], -q[1])
+    assert q[7, 100] == -127 and int(qa.q_sum[7]) == -127
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_quant_act_strided_and_unaligned_input(dev, ops, bf16):
+    # ldx > K, and a base pointer that is only element-aligned: takes the scalar path
+    M, K, ldx = 4, 520, 777
+    rng = synth.rng_for(123)
+    full = synth.activations(rng, M, ldx + 1)
+    if bf16:
+        bits = synth.to_bf16_bits(full)
+        big = _to_dev_bf16(bits, dev)
+        view = big.reshape(-1)[1:1 + M * ldx].reshape(M, ldx)[:, :K]
+        ref = oracle.quant_act(np.ascontiguousarray(bits.reshape(-1)[1:1 + M * ldx].reshape(M, ldx)[:, :K]))
+    else:
+        big = torch.from_numpy(full).to(dev)
+        view = big.reshape(-1)[1:1 + M * ldx].reshape(M, ldx)[:, :K]
+        ref = oracle.quant_act(np.ascontiguousarray(full.reshape(-1)[1:1 + M * ldx].reshape(M, ldx)[:, :K]))
+    qa = ops.quant_act(view)
+    _assert_quant_equal(qa, ref, K)
+
+
+# ------------------------------------------------------------------ decode product
+
+def _problem(seed, M, K, N, p_zero=None, outl=0.0, bf16=True):
+    rng = synth.rng_for(seed)
+    w = synth.ternary_weights(rng, N, K, p_zero=p_zero)
+    w_scale = synth.draw_w_scale(rng)
+    x = synth.activations(rng, M, K, outlier_frac=outl)
+    return w, w_scale, (synth.to_bf16_bits(x) if bf16 else x)
+
+
+def _run_product(ops, dev, kind, w, w_scale, x, waves=None):
+    from paper_2410_16144_amd import binding
+    pw = ops.pack_ternary(torch.from_numpy(w).to(dev), float(w_scale))
+    xd = _to_dev_bf16(x, dev) if x.dtype == np.uint16 else torch.from_numpy(x).to(dev)
+    qa = ops.quant_act(xd)
+    if waves is not None:
+        binding.bl_set_tuning("gemv_waves", waves)
+    try:
+        out, acc = (ops.gemv if kind == "gemv" else ops.gemm)(pw, qa, want_acc=True)
+    finally:
+        if waves is not None:
+            binding.bl_set_tuning("gemv_waves", 0)
+    torch.cuda.synchronize()
+    return pw, qa, out, acc
+
+
+def _assert_product(ops, dev, kind, w, w_scale, x, waves=None):
+    q_ref, a_ref, s_ref = oracle.quant_act(x)
+    acc_ref = oracle.matmul_i32(q_ref, w)
+    pw, qa, out, acc = _run_product(ops, dev, kind, w, w_scale, x, waves)
+    _assert_quant_equal(qa, (q_ref, a_ref, s_ref), w.shape[1])
+    assert np.array_equal(acc.cpu().numpy(), acc_ref)
+    _check_out(out, acc_ref, w_scale, a_ref)
+    return pw, qa, out, acc
+
+
+@pytest.mark.parametrize("M", [1, 2, 3, 4, 5, 6, 7, 8])
+def test_gemv_parity_all_m(dev, ops, M):
+    w, s, x = _problem(500 + M, M, 1536, 320)
+    _assert_product(ops, dev, "gemv", w, s, x)
+
+
+@pytest.mark.parametrize("N,K", [(64, 64), (1, 1), (70, 100), (200, 1000), (1536, 1536), (257, 3200),
+                                 (3200, 8640), (129, 64 * 37)])
+@pytest.mark.parametrize("M", [1, 4])
+def test_gemv_parity_shapes(dev, ops, N, K, M):
+    w, s, x = _problem(N * 31 + K + M, M, K, N, p_zero=0.4, outl=0.01)
+    _assert_product(ops, dev, "gemv", w, s, x)
+
+
+@pytest.mark.parametrize("waves", [1, 2, 4, 8, 16])
+def test_gemv_parity_every_launch_shape(dev, ops, waves):
+    w, s, x = _problem(900 + waves, 2, 64 * 37, 192)
+    _assert_product(ops, dev, "gemv", w, s, x, waves=waves)
+    w, s, x = _problem(901 + waves, 1, 64 * 3, 128)      # fewer K tiles than waves
+    _assert_product(ops, dev, "gemv", w, s, x, waves=waves)
+
+
+def test_gemv_fp32_activations_config1(dev, ops):
+    # config 1: M=1, K=N=1536, uniform ternary, scale 0.02, fp32 N(0,1), seed 0
+    rng = synth.rng_for(synth.seed_for(1))
+    w = synth.ternary_weights(rng, 1536, 1536)
+    x = synth.activations(rng, 1, 1536)
+    _assert_product(ops, dev, "gemv", w, np.float32(0.02), x)
+
+
+def test_gemv_invariants_and_determinism(dev, ops):
+    w, s, x = _problem(42, 3, 1024, 256)
+    pw, qa, out, acc = _run_product(ops, dev, "gemv", w, s, x)
+    for _ in range(3):
+        _, _, out2, acc2 = _run_product(ops, dev, "gemv", w, s, x)
+        assert torch.equal(acc, acc2) and torch.equal(out, out2)
+    _, _, outn, accn = _run_product(ops, dev, "gemv", -w, s, x)
+    assert torch.equal(accn, -acc) and torch.equal(outn, -out)
+    _, _, outz, accz = _run_product(ops, dev, "gemv", np.zeros_like(w), s, x)
+    assert not accz.any() and not outz.any()
+    xz = np.zeros_like(x)
+    _, qz, outz, accz = _run_product(ops, dev, "gemv", w, s, xz)
+    assert not qz.q.any() and not outz.any() and not accz.any()
+    ones = np.ones_like(w)
+    _, qa1, _, acc1 = _run_product(ops, dev, "gemv", ones, s, x)
+    assert torch.equal(acc1, qa1.q_sum[:, None].expand(-1, w.shape[0]))
+
+
+def test_gemv_batch_equals_separate_calls(dev, ops):
+    shapes = [(320, 640), (320, 640), (128, 640), (640, 320), (64, 64), (200, 1000), (1000, 200)]
+    M = 2
+    weights, acts, refs = [], [], []
+    for i, (N, K) in enumerate(shapes):
+        w, s, x = _problem(700 + i, M, K, N)
+        pw = ops.pack_ternary(torch.from_numpy(w).to(dev), float(s))
+        qa = ops.quant_act(_to_dev_bf16(x, dev))
+        weights.append(pw)
+        acts.append(qa)
+        refs.append(ops.gemv(pw, qa, want_acc=True))
+    grp = ops.GemvGroup(weights, acts, want_acc=True)
+    outs = grp.launch()
+    torch.cuda.synchronize()
+    for i in range(len(shapes)):
+        assert torch.equal(outs[i], refs[i][0]) and torch.equal(grp.accs[i], refs[i][1])
+        q_ref = acts[i].q.cpu().numpy()[:, :shapes[i][1]]
+        w_ref = ops.unpack_ternary(weights[i]).cpu().numpy()
+        assert np.array_equal(grp.accs[i].cpu().numpy(), oracle.matmul_i32(np.ascontiguousarray(q_ref), w_ref))
+
+
+# ------------------------------------------------------------------ prefill product
+
+@pytest.mark.parametrize("M,N,K", [(1, 64, 64), (7, 70, 100), (33, 200, 1000), (128, 256, 512), (130, 320, 1536),
+                                   (300, 1000, 832), (512, 192, 4096)])
+def test_gemm_parity(dev, ops, M, N, K):
+    w, s, x = _problem(M * 13 + N + K, M, K, N, p_zero=0.4, outl=0.01)
+    _assert_product(ops, dev, "gemm", w, s, x)
+
+
+def test_gemm_equals_gemv_for_small_m(dev, ops):
+    w, s, x = _problem(4242, 8, 1536, 448)
+    _, _, out_v, acc_v = _run_product(ops, dev, "gemv", w, s, x)
+    _, _, out_m, acc_m = _run_product(ops, dev, "gemm", w, s, x)
+    assert torch.equal(acc_v, acc_m) and torch.equal(out_v, out_m)
+
+
+def test_gemm_determinism(dev, ops):
+    w, s, x = _problem(4243, 200, 1024, 320)
+    _, _, out, acc = _run_product(ops, dev, "gemm", w, s, x)
+    for _ in range(2):
+        _, _, out2, acc2 = _run_product(ops, dev, "gemm", w, s, x)
+        assert torch.equal(acc, acc2) and torch.equal(out, out2)
