@@ -173,6 +173,35 @@ typedef struct {
  */
 bl_status bl_gemv_batch(const bl_gemv_item *items, int32_t count, int64_t M, void *stream);
 
+/* One problem of the fused decode launch. */
+typedef struct {
+    const void           *x_dev;        /* [M, ldx] activations, fp32 or bf16                  */
+    bl_dtype              dt;
+    int64_t               ldx;          /* row stride of x in elements, >= K                   */
+    const void           *packed_dev;
+    const bl_packed_desc *desc;         /* host pointer                                        */
+    float                *out_dev;      /* [M,N] fp32                                          */
+    int32_t              *acc_dev;      /* optional [M,N] int32                                */
+    int8_t               *q_dev;        /* optional [M,Kp]: receives the quantized activations */
+    float                *a_scale_dev;  /* optional [M]                                        */
+    int32_t              *q_sum_dev;    /* optional [M]                                        */
+} bl_decode_item;
+
+/*
+ * Fused decode: bl_quant_act followed by bl_gemv for `count` problems
+ * (1..BL_MAX_BATCH, same M in 1..8) in ONE kernel launch.  Every workgroup
+ * quantizes its token rows into on-chip memory while its first weight tiles
+ * are already in flight, so the int8 activations never travel through HBM
+ * and the separate quantization launch disappears.  Results (q, a_scale,
+ * q_sum, acc, out) are bit-identical to the two-call sequence.
+ * Limit: M * Kp (+ 5 KiB per token) must fit the kernel's 128 KiB of
+ * on-chip memory, else BL_ERR_SHAPE; use the two-call sequence then.
+ * Pointer alignment as for bl_quant_act / bl_gemv.
+ * Errors: BL_ERR_NULL, BL_ERR_COUNT, BL_ERR_M_RANGE, BL_ERR_DTYPE,
+ *         BL_ERR_LAYOUT, BL_ERR_SHAPE, BL_ERR_BUF_SMALL, BL_ERR_ALIGN, BL_ERR_HIP.
+ */
+bl_status bl_decode_batch(const bl_decode_item *items, int32_t count, int64_t M, void *stream);
+
 /*
  * Prefill product, 1 <= M <= BL_MAX_GEMM_M: the same mathematics as bl_gemv,
  * computed as a dense contraction on the int8 matrix cores.  Arguments as
@@ -184,8 +213,8 @@ bl_status bl_gemm(const void *packed_dev, const bl_packed_desc *d, const int8_t 
 
 /*
  * Launch-shape override for experiments and sweeps; process-wide, not thread-safe, never
- * changes results.  Keys: "gemv_waves" = waves per workgroup of the decode kernel
- * (1, 2, 4, 8, 16; 0 = automatic).  Errors: BL_ERR_NULL, BL_ERR_SHAPE (unknown key/value).
+ * changes results.  Keys: "gemv_waves" = waves of the decode kernel that share one
+ * 64-row block (1, 2, 4, 8, 16; 0 = automatic).  Errors: BL_ERR_NULL, BL_ERR_SHAPE (unknown key/value).
  */
 bl_status bl_set_tuning(const char *key, int32_t value);
 

@@ -26,7 +26,7 @@ BL_MAX_GEMM_M = 4194304
 # every symbol include/bitlinear.h declares
 DECLARED_SYMBOLS = (
     "bl_padded_k", "bl_padded_n", "bl_packed_desc_init", "bl_pack_ternary", "bl_unpack_ternary",
-    "bl_quant_act", "bl_gemv", "bl_gemv_batch", "bl_gemm", "bl_set_tuning", "bl_status_str", "bl_last_hip_error", "bl_version",
+    "bl_quant_act", "bl_gemv", "bl_gemv_batch", "bl_decode_batch", "bl_gemm", "bl_set_tuning", "bl_status_str", "bl_last_hip_error", "bl_version",
 )
 
 
@@ -51,6 +51,14 @@ class GemvItem(ctypes.Structure):
     _fields_ = [("packed_dev", ctypes.c_void_p), ("desc", ctypes.POINTER(PackedDesc)),
                 ("q_dev", ctypes.c_void_p), ("a_scale_dev", ctypes.c_void_p), ("q_sum_dev", ctypes.c_void_p),
                 ("out_dev", ctypes.c_void_p), ("acc_dev", ctypes.c_void_p)]
+
+
+class DecodeItem(ctypes.Structure):
+    """Mirror of bl_decode_item."""
+    _fields_ = [("x_dev", ctypes.c_void_p), ("dt", ctypes.c_int), ("ldx", ctypes.c_int64),
+                ("packed_dev", ctypes.c_void_p), ("desc", ctypes.POINTER(PackedDesc)),
+                ("out_dev", ctypes.c_void_p), ("acc_dev", ctypes.c_void_p), ("q_dev", ctypes.c_void_p),
+                ("a_scale_dev", ctypes.c_void_p), ("q_sum_dev", ctypes.c_void_p)]
 
 
 _lib = None
@@ -81,6 +89,7 @@ def lib():
     l.bl_quant_act.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, vp, vp, vp]
     l.bl_gemv.argtypes = [vp, dp, vp, vp, vp, i64, vp, vp, vp]
     l.bl_gemv_batch.argtypes = [ctypes.POINTER(GemvItem), i32, i64, vp]
+    l.bl_decode_batch.argtypes = [ctypes.POINTER(DecodeItem), i32, i64, vp]
     l.bl_gemm.argtypes = [vp, dp, vp, vp, vp, i64, vp, vp, vp]
     l.bl_set_tuning.argtypes = [ctypes.c_char_p, i32]
     l.bl_status_str.argtypes = [ctypes.c_int]
@@ -88,7 +97,7 @@ def lib():
     l.bl_version.restype = ctypes.c_char_p
     l.bl_last_hip_error.restype = ctypes.c_char_p
     for name in ("bl_packed_desc_init", "bl_pack_ternary", "bl_unpack_ternary", "bl_quant_act", "bl_gemv",
-                 "bl_gemv_batch", "bl_gemm", "bl_set_tuning"):
+                 "bl_gemv_batch", "bl_decode_batch", "bl_gemm", "bl_set_tuning"):
         getattr(l, name).restype = ctypes.c_int
     _lib = l
     return l
@@ -157,6 +166,24 @@ def bl_gemv_batch(items, M: int, stream: int = 0):
     if not isinstance(items, ctypes.Array):
         items = make_gemv_items(items)
     _check(lib().bl_gemv_batch(items, len(items), M, stream or None), "bl_gemv_batch")
+
+
+def make_decode_items(items):
+    """items: iterable of (x_dev, dtype, ldx, packed_dev, desc, out_dev, acc_dev, q_dev, a_scale_dev, q_sum_dev)
+    -> ctypes array.  The PackedDesc objects must outlive the array."""
+    items = list(items)
+    arr = (DecodeItem * len(items))()
+    for i, (x, dt, ldx, packed, desc, out, acc, q, a, s) in enumerate(items):
+        arr[i] = DecodeItem(x, dt, ldx, packed, ctypes.pointer(desc), out, acc or None, q or None, a or None,
+                            s or None)
+    return arr
+
+
+def bl_decode_batch(items, M: int, stream: int = 0):
+    """items: a ctypes DecodeItem array from make_decode_items (or an iterable of tuples)."""
+    if not isinstance(items, ctypes.Array):
+        items = make_decode_items(items)
+    _check(lib().bl_decode_batch(items, len(items), M, stream or None), "bl_decode_batch")
 
 
 def bl_gemm(packed_dev: int, desc: PackedDesc, q_dev: int, a_scale_dev: int, q_sum_dev: int, M: int,

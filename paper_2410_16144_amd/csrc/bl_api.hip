@@ -126,27 +126,76 @@ bl_status bl_gemv(const void* packed_dev, const bl_packed_desc* d, const int8_t*
     return bl_gemv_batch(&it, 1, M, stream);
 }
 
+static bl::DecodeProblem make_decode_problem(const void* packed, const bl_packed_desc* d, float* out, int32_t* acc) {
+    bl::DecodeProblem p;
+    memset(&p, 0, sizeof p);
+    p.packed = static_cast<const uint4*>(packed);
+    p.out = out;
+    p.acc = acc;
+    p.N = (int32_t)d->N;
+    p.K = (int32_t)d->K;
+    p.KC = (int32_t)(d->Kp / BL_TILE_K);
+    p.row_blocks = (int32_t)(d->Np / BL_TILE_N);
+    p.w_scale = d->w_scale;
+    return p;
+}
+
 bl_status bl_gemv_batch(const bl_gemv_item* items, int32_t count, int64_t M, void* stream) {
     if (!items) return BL_ERR_NULL;
     if (count < 1 || count > BL_MAX_BATCH) return BL_ERR_COUNT;
     if (M < 1 || M > BL_MAX_GEMV_M) return BL_ERR_M_RANGE;
-    bl::GemvBatch b;
+    bl::DecodeBatch b;
     memset(&b, 0, sizeof b);
-    int64_t blocks = 0;
     for (int i = 0; i < count; ++i) {
         const bl_gemv_item& it = items[i];
         bl_status s = check_product_args(it.packed_dev, it.desc, it.q_dev, it.a_scale_dev, it.q_sum_dev, M,
                                          it.out_dev, it.acc_dev);
         if (s != BL_OK) return s;
-        b.p[i] = make_problem(it.packed_dev, it.desc, it.q_dev, it.a_scale_dev, it.q_sum_dev, it.out_dev, it.acc_dev);
-        b.first_block[i] = (int32_t)blocks;
-        blocks += b.p[i].row_blocks;
-        if (blocks > INT32_MAX / 2) return BL_ERR_SHAPE;
+        b.p[i] = make_decode_problem(it.packed_dev, it.desc, it.out_dev, it.acc_dev);
+        b.p[i].q = reinterpret_cast<const int32_t*>(it.q_dev);
+        b.p[i].a_scale = it.a_scale_dev;
+        b.p[i].q_sum = it.q_sum_dev;
     }
-    for (int i = count; i <= BL_MAX_BATCH; ++i) b.first_block[i] = (int32_t)blocks;
     b.count = count;
+    bl::plan_decode(b);
     drop_stale_hip_error();
-    return hip_status(bl::launch_gemv(b, (int)M, static_cast<hipStream_t>(stream)));
+    return hip_status(bl::launch_decode(b, (int)M, false, static_cast<hipStream_t>(stream)));
+}
+
+bl_status bl_decode_batch(const bl_decode_item* items, int32_t count, int64_t M, void* stream) {
+    if (!items) return BL_ERR_NULL;
+    if (count < 1 || count > BL_MAX_BATCH) return BL_ERR_COUNT;
+    if (M < 1 || M > BL_MAX_GEMV_M) return BL_ERR_M_RANGE;
+    bl::DecodeBatch b;
+    memset(&b, 0, sizeof b);
+    int64_t max_Kp = 0;
+    for (int i = 0; i < count; ++i) {
+        const bl_decode_item& it = items[i];
+        if (!it.x_dev || !it.packed_dev || !it.desc || !it.out_dev) return BL_ERR_NULL;
+        if (it.dt != BL_F32 && it.dt != BL_BF16) return BL_ERR_DTYPE;
+        bl_status s = check_desc(it.desc);
+        if (s != BL_OK) return s;
+        if (it.ldx < it.desc->K) return BL_ERR_SHAPE;
+        if (!aligned(it.x_dev, it.dt == BL_F32 ? 4 : 2) || !aligned(it.packed_dev, 16) || !aligned(it.out_dev, 4) ||
+            (it.acc_dev && !aligned(it.acc_dev, 4)) || (it.q_dev && !aligned(it.q_dev, 16)) ||
+            (it.a_scale_dev && !aligned(it.a_scale_dev, 4)) || (it.q_sum_dev && !aligned(it.q_sum_dev, 4)))
+            return BL_ERR_ALIGN;
+        bl::DecodeProblem& p = b.p[i];
+        p = make_decode_problem(it.packed_dev, it.desc, it.out_dev, it.acc_dev);
+        p.x = it.x_dev;
+        p.ldx = it.ldx;
+        p.q_out = it.q_dev;
+        p.a_scale_out = it.a_scale_dev;
+        p.q_sum_out = it.q_sum_dev;
+        const bool vec = (it.desc->K % 8 == 0) && (it.ldx % 8 == 0) && aligned(it.x_dev, 16);
+        p.x_flags = (it.dt == BL_BF16 ? 1 : 0) | (vec ? 2 : 0);
+        if (it.desc->Kp > max_Kp) max_Kp = it.desc->Kp;
+    }
+    if (bl::decode_lds_bytes((int)M, max_Kp, true) > (size_t)bl::kMaxDecodeLds) return BL_ERR_SHAPE;
+    b.count = count;
+    bl::plan_decode(b);
+    drop_stale_hip_error();
+    return hip_status(bl::launch_decode(b, (int)M, true, static_cast<hipStream_t>(stream)));
 }
 
 bl_status bl_gemm(const void* packed_dev, const bl_packed_desc* d, const int8_t* q_dev, const float* a_scale_dev,

@@ -1,23 +1,30 @@
-// bl_gemv / bl_gemv_batch: the decode product (1..8 tokens) over 2-bit packed ternary weights
-// (Section 2 of arXiv 2410.16144, I2_S: codes back to weights in registers, then multiply-add).
+// bl_gemv / bl_gemv_batch / bl_decode_batch: the decode product (1..8 tokens) over 2-bit packed
+// ternary weights (Section 2 of arXiv 2410.16144, I2_S: codes back to weights in registers, then
+// multiply-add), optionally fused with the per-token absmax int8 quantization of its input.
 //
-// Mapping.  One workgroup owns one 64-row block of one matrix; lane r of every wave owns row r.
-// The workgroup's waves take the K tiles of that row block round-robin.  Per tile a wave issues
-// ONE 128-bit load per lane (1 KiB, fully coalesced) for the weights; the matching 64 int8
-// activations are the same for all lanes, so they are fetched with scalar loads and fed to the
-// dot instruction as scalar operands.  No cross-lane reduction is needed at all: partial sums
-// of the waves meet once in LDS at the end.
+// Mapping.  A workgroup is 16 waves.  Lane r of a wave owns row r of a 64-row block; the K tiles
+// of a row block are dealt round-robin to a group of G = 1,2,4,8 or 16 waves (G chosen per matrix
+// so that a wave gets about 8 tiles), so a workgroup covers 16/G row blocks.  Per tile a wave
+// issues ONE 128-bit load per lane (1 KiB, fully coalesced), 8 tiles in flight at a time.
+// The tile's 64 int8 activations are the same for all lanes: in the plain kernel they arrive by
+// scalar loads and feed v_dot4_i32_i8 as scalar operands; in the fused kernel the workgroup first
+// quantizes its token row into LDS (while its first weight tiles are already in flight) and the
+// activations are LDS broadcast reads.  There is no cross-lane reduction: the G partial sums of
+// a row meet once in LDS at the end.
 //
-// Arithmetic.  Codes c = w+1 in {0,1,2} are used as they are: sum_k q*w = sum_k q*c - sum_k q,
-// and sum_k q comes from bl_quant_act.  A packed word holds 16 codes; masking with 0x03030303
-// gives four byte codes, masking with 0x0c0c0c0c gives four codes times 4 (still int8), so a
-// word costs 1 shift + 4 ands + 4 v_dot4_i32_i8 per token, with the x4 group kept in its own
-// accumulator and divided out exactly at the end.
-#include "bl_internal.hpp"
+// Arithmetic.  Codes c = w+1 in {0,1,2} are used as they are: sum_k q*w = sum_k q*c - sum_k q.
+// A packed word holds 16 codes; masking with 0x03030303 gives four byte codes, masking with
+// 0x0c0c0c0c gives four codes times 4 (still int8), so a word costs 1 shift + 4 ands + 4 dot4 per
+// token, the x4 group being kept in its own accumulator and divided out exactly at the end.
+#include "bl_quant_device.hpp"
 
 namespace bl {
 
 namespace {
+
+constexpr int kWaves = 16;            // waves per workgroup
+constexpr int kThreads = kWaves * kWave;
+constexpr int kInFlight = 8;          // weight tiles a wave keeps in flight
 
 template <int M>
 struct Acc {
@@ -25,10 +32,10 @@ struct Acc {
     int hi[M];  // sums of q * (4 * code)
 };
 
-// One 64x64 tile: w = this lane's 16 bytes (4 words), qk = tile's activations (16 words per token row).
-template <int M>
-__device__ __forceinline__ void tile_mac(const uint4& w, const int32_t* __restrict__ qk, int q_stride_words,
-                                         Acc<M>& a) {
+// One 64x64 tile: w = this lane's 16 bytes, qk = the tile's activations of token 0 (16 words),
+// q_stride_words = distance between token rows.  Works for global (scalar loads) and LDS pointers.
+template <int M, typename QPtr>
+__device__ __forceinline__ void tile_mac(const uint4& w, QPtr qk, int q_stride_words, Acc<M>& a) {
     const uint32_t word[4] = {w.x, w.y, w.z, w.w};
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
@@ -40,96 +47,181 @@ __device__ __forceinline__ void tile_mac(const uint4& w, const int32_t* __restri
         const int c3 = (int)(e & 0x0c0c0c0cu);  // k-offsets 12..15 (x4)
 #pragma unroll
         for (int m = 0; m < M; ++m) {
-            const int32_t* qm = qk + m * q_stride_words + 4 * s;
-            a.lo[m] = __builtin_amdgcn_sdot4(c0, qm[0], a.lo[m], false);
-            a.hi[m] = __builtin_amdgcn_sdot4(c1, qm[1], a.hi[m], false);
-            a.lo[m] = __builtin_amdgcn_sdot4(c2, qm[2], a.lo[m], false);
-            a.hi[m] = __builtin_amdgcn_sdot4(c3, qm[3], a.hi[m], false);
+            const int4 qv = *reinterpret_cast<const int4*>(qk + m * q_stride_words + 4 * s);
+            a.lo[m] = __builtin_amdgcn_sdot4(c0, qv.x, a.lo[m], false);
+            a.hi[m] = __builtin_amdgcn_sdot4(c1, qv.y, a.hi[m], false);
+            a.lo[m] = __builtin_amdgcn_sdot4(c2, qv.z, a.lo[m], false);
+            a.hi[m] = __builtin_amdgcn_sdot4(c3, qv.w, a.hi[m], false);
         }
     }
 }
 
-template <int M, int WAVES, int UNROLL>
-__global__ __launch_bounds__(WAVES* kWave) void gemv_kernel(const GemvBatch b) {
-    __shared__ int red[WAVES > 1 ? WAVES : 1][M][kWave];
+// Quantize M token rows into LDS; returns per-token scale and sum(q) in s_scale / s_qsum (LDS).
+template <int M, bool BF16, bool VEC>
+__device__ __forceinline__ void quantize_rows_to_lds(const DecodeProblem& p, int8_t* lds_q, float* s_f, int* s_i,
+                                                     int tid, int lane, int wave) {
+    const int K = p.K, Kp = p.KC * kTileK;
+    const char* x = static_cast<const char*>(p.x);
+    const int64_t row_bytes = p.ldx * (BF16 ? 2 : 4);
+    float amax[M];
+#pragma unroll
+    for (int m = 0; m < M; ++m) amax[m] = wave_max(thread_absmax<BF16, VEC>(x + m * row_bytes, K, tid, kThreads));
+    if (lane == 0) {
+#pragma unroll
+        for (int m = 0; m < M; ++m) s_f[m * kWaves + wave] = amax[m];
+    }
+    __syncthreads();
+    int sum[M];
+#pragma unroll
+    for (int m = 0; m < M; ++m) {
+        float am = s_f[m * kWaves];
+#pragma unroll
+        for (int w = 1; w < kWaves; ++w) am = fmaxf(am, s_f[m * kWaves + w]);
+        float inv, scale;
+        quant_scales(am, inv, scale);
+        sum[m] = wave_sum(thread_quantize<BF16, VEC>(x + m * row_bytes, K, Kp, inv, lds_q + m * Kp, tid, kThreads));
+        if (tid == 0) s_f[M * kWaves + m] = scale;
+    }
+    if (lane == 0) {
+#pragma unroll
+        for (int m = 0; m < M; ++m) s_i[m * kWaves + wave] = sum[m];
+    }
+    __syncthreads();
+}
+
+template <int M, bool FUSED>
+__global__ __launch_bounds__(kThreads, 8) void decode_kernel(const DecodeBatch b) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 
     // which problem does this workgroup belong to (uniform)
     const int blk = blockIdx.x;
     int pi = 0;
 #pragma unroll
-    for (int i = 1; i < BL_MAX_BATCH; ++i) pi += (blk >= b.first_block[i]) ? 1 : 0;
-    const GemvProblem& p = b.p[pi];
-    const int rb = blk - b.first_block[pi];
+    for (int i = 1; i < BL_MAX_BATCH; ++i) pi += (i < b.count && blk >= b.p[i].first_wg) ? 1 : 0;
+    const DecodeProblem& p = b.p[pi];
+    const int wg = blk - p.first_wg;
 
-    const int lane = threadIdx.x & (kWave - 1);
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wlog2 = p.wlog2, G = 1 << wlog2;
+    const int ks = wave & (G - 1);
+    const int rb = wg * (kWaves >> wlog2) + (wave >> wlog2);
+    const bool active = rb < p.row_blocks;
     const int KC = p.KC;
-    const int qsw = KC * (kTileK / 4);  // activation row stride in words
-    const uint4* __restrict__ wp = p.packed + (int64_t)rb * KC * kWave + lane;
-    const int32_t* __restrict__ q = p.q;
+    const int Kp = KC * kTileK;
+    const uint4* __restrict__ wp = p.packed + (int64_t)(active ? rb : 0) * KC * kWave + lane;
+
+    // LDS carve-up: [quantized activations (fused only)] [partial sums] [small per-token scalars]
+    int8_t* lds_q = reinterpret_cast<int8_t*>(smem);
+    int* red = reinterpret_cast<int*>(smem + (FUSED ? M * Kp : 0));
+    float* s_f = reinterpret_cast<float*>(red + kWaves * M * kWave);   // [M][16] maxima, then [M] scales
+    int* s_i = reinterpret_cast<int*>(s_f + M * kWaves + M);           // [M][16] partial sum(q)
+
+    // first batch of weight tiles goes in flight before anything else
+    uint4 w[kInFlight];
+    auto load_batch = [&](int kc0) {
+#pragma unroll
+        for (int u = 0; u < kInFlight; ++u) {
+            const int k = kc0 + u * G;
+            w[u] = wp[(int64_t)(k < KC ? k : KC - 1) * kWave];   // clamped: always a valid tile
+        }
+    };
+    if (active) load_batch(ks);
+
+    if constexpr (FUSED) {
+        const bool bf16 = p.x_flags & 1, vec = p.x_flags & 2;
+        if (bf16) {
+            if (vec) quantize_rows_to_lds<M, true, true>(p, lds_q, s_f, s_i, tid, lane, wave);
+            else quantize_rows_to_lds<M, true, false>(p, lds_q, s_f, s_i, tid, lane, wave);
+        } else {
+            if (vec) quantize_rows_to_lds<M, false, true>(p, lds_q, s_f, s_i, tid, lane, wave);
+            else quantize_rows_to_lds<M, false, false>(p, lds_q, s_f, s_i, tid, lane, wave);
+        }
+        if (wg == 0 && p.q_out) {   // optional copy-out of the quantized activations
+            for (int i = tid; i < M * Kp / 4; i += kThreads)
+                reinterpret_cast<int32_t*>(p.q_out)[i] = reinterpret_cast<const int32_t*>(lds_q)[i];
+        }
+    }
 
     Acc<M> a;
 #pragma unroll
     for (int m = 0; m < M; ++m) a.lo[m] = a.hi[m] = 0;
 
-    int kc = wave;
-    for (; kc + (UNROLL - 1) * WAVES < KC; kc += UNROLL * WAVES) {
-        uint4 w[UNROLL];
+    if (active) {
+        for (int kc0 = ks;;) {
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) w[u] = wp[(int64_t)(kc + u * WAVES) * kWave];
-#pragma unroll
-        for (int u = 0; u < UNROLL; ++u) tile_mac<M>(w[u], q + (kc + u * WAVES) * (kTileK / 4), qsw, a);
-    }
-    for (; kc < KC; kc += WAVES) {
-        uint4 w = wp[(int64_t)kc * kWave];
-        tile_mac<M>(w, q + kc * (kTileK / 4), qsw, a);
+            for (int u = 0; u < kInFlight; ++u) {
+                const int k = kc0 + u * G;
+                if (k < KC) {
+                    if constexpr (FUSED) tile_mac<M>(w[u], reinterpret_cast<const int32_t*>(lds_q) + k * 16, Kp / 4, a);
+                    else tile_mac<M>(w[u], p.q + k * 16, Kp / 4, a);
+                }
+                __builtin_amdgcn_sched_barrier(0);   // keep the activation reads of later tiles from piling up in registers
+            }
+            kc0 += G * kInFlight;
+            if (kc0 >= KC) break;
+            load_batch(kc0);
+        }
     }
 
-    int part[M];
 #pragma unroll
-    for (int m = 0; m < M; ++m) part[m] = a.lo[m] + (a.hi[m] >> 2);  // hi is an exact multiple of 4
+    for (int m = 0; m < M; ++m) red[(wave * M + m) * kWave + lane] = a.lo[m] + (a.hi[m] >> 2);  // hi: exact multiple of 4
+    __syncthreads();
 
     const int row = rb * kTileN + lane;
-    if constexpr (WAVES == 1) {
-        if (row < p.N) {
+    for (int m = ks; m < M; m += G) {
+        int qsum;
+        float scale;
+        if constexpr (FUSED) {
+            qsum = 0;
 #pragma unroll
-            for (int m = 0; m < M; ++m) {
-                const int v = part[m] - p.q_sum[m];
-                p.out[(int64_t)m * p.N + row] = (float)v * (p.w_scale * p.a_scale[m]);
-                if (p.acc) p.acc[(int64_t)m * p.N + row] = v;
+            for (int w16 = 0; w16 < kWaves; ++w16) qsum += s_i[m * kWaves + w16];
+            scale = s_f[M * kWaves + m];
+            if (wg == 0 && wave == m % G && lane == 0) {
+                if (p.a_scale_out) p.a_scale_out[m] = scale;
+                if (p.q_sum_out) p.q_sum_out[m] = qsum;
             }
+        } else {
+            qsum = p.q_sum[m];
+            scale = p.a_scale[m];
         }
-    } else {
-#pragma unroll
-        for (int m = 0; m < M; ++m) red[wave][m][lane] = part[m];
-        __syncthreads();
-        for (int m = wave; m < M; m += WAVES) {
-            int v = -p.q_sum[m];
-#pragma unroll
-            for (int w = 0; w < WAVES; ++w) v += red[w][m][lane];
-            if (row < p.N) {
-                p.out[(int64_t)m * p.N + row] = (float)v * (p.w_scale * p.a_scale[m]);
-                if (p.acc) p.acc[(int64_t)m * p.N + row] = v;
-            }
+        int v = -qsum;
+        for (int g = 0; g < G; ++g) v += red[((wave - ks + g) * M + m) * kWave + lane];
+        if (active && row < p.N) {
+            p.out[(int64_t)m * p.N + row] = (float)v * (p.w_scale * scale);
+            if (p.acc) p.acc[(int64_t)m * p.N + row] = v;
         }
     }
 }
 
-template <int M, int WAVES>
-hipError_t launch_mw(const GemvBatch& b, int blocks, hipStream_t s) {
-    gemv_kernel<M, WAVES, 4><<<dim3((unsigned)blocks), dim3(WAVES * kWave), 0, s>>>(b);
+template <int M, bool FUSED>
+hipError_t launch_one(const DecodeBatch& b, size_t lds_bytes, hipStream_t s) {
+    static bool attr_set = false;   // raise the dynamic-LDS ceiling once per kernel (host-side setting only)
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_kernel<M, FUSED>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDecodeLds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    decode_kernel<M, FUSED><<<dim3((unsigned)b.total_wgs), dim3(kThreads), lds_bytes, s>>>(b);
     return hipGetLastError();
 }
 
-template <int M>
-hipError_t launch_m(const GemvBatch& b, int blocks, int waves, hipStream_t s) {
-    switch (waves) {
-        case 1: return launch_mw<M, 1>(b, blocks, s);
-        case 2: return launch_mw<M, 2>(b, blocks, s);
-        case 4: return launch_mw<M, 4>(b, blocks, s);
-        case 8: return launch_mw<M, 8>(b, blocks, s);
-        default: return launch_mw<M, 16>(b, blocks, s);
+template <bool FUSED>
+hipError_t launch_m(const DecodeBatch& b, int M, size_t lds, hipStream_t s) {
+    switch (M) {
+        case 1: return launch_one<1, FUSED>(b, lds, s);
+        case 2: return launch_one<2, FUSED>(b, lds, s);
+        case 3: return launch_one<3, FUSED>(b, lds, s);
+        case 4: return launch_one<4, FUSED>(b, lds, s);
+        case 5: return launch_one<5, FUSED>(b, lds, s);
+        case 6: return launch_one<6, FUSED>(b, lds, s);
+        case 7: return launch_one<7, FUSED>(b, lds, s);
+        case 8: return launch_one<8, FUSED>(b, lds, s);
     }
+    return hipErrorInvalidValue;
 }
 
 int g_force_waves = 0;
@@ -138,26 +230,35 @@ int g_force_waves = 0;
 
 void set_gemv_waves(int waves) { g_force_waves = waves; }
 
-hipError_t launch_gemv(const GemvBatch& b, int M, hipStream_t s) {
-    const int blocks = b.first_block[BL_MAX_BATCH];
-    int min_kc = b.p[0].KC;
-    for (int i = 1; i < b.count; ++i) min_kc = b.p[i].KC < min_kc ? b.p[i].KC : min_kc;
-    // Enough waves to cover the chip several times over, but never more waves than K tiles.
-    int waves = 16;
-    while (waves > 1 && ((int64_t)blocks * (waves / 2) >= 4096 || waves > min_kc)) waves /= 2;
-    if (g_force_waves == 1 || g_force_waves == 2 || g_force_waves == 4 || g_force_waves == 8 || g_force_waves == 16)
-        waves = g_force_waves;
-    switch (M) {
-        case 1: return launch_m<1>(b, blocks, waves, s);
-        case 2: return launch_m<2>(b, blocks, waves, s);
-        case 3: return launch_m<3>(b, blocks, waves, s);
-        case 4: return launch_m<4>(b, blocks, waves, s);
-        case 5: return launch_m<5>(b, blocks, waves, s);
-        case 6: return launch_m<6>(b, blocks, waves, s);
-        case 7: return launch_m<7>(b, blocks, waves, s);
-        case 8: return launch_m<8>(b, blocks, waves, s);
+size_t decode_lds_bytes(int M, int64_t max_Kp, bool fused) {
+    return (size_t)(fused ? M * max_Kp : 0) + (size_t)kWaves * M * kWave * 4 + (size_t)(2 * M * kWaves + M) * 4;
+}
+
+// Fill in the launch geometry: waves per row block for each problem and the workgroup prefix.
+void plan_decode(DecodeBatch& b) {
+    int total = 0;
+    for (int i = 0; i < b.count; ++i) {
+        DecodeProblem& p = b.p[i];
+        int g = 1, lg = 0;
+        while (g < kWaves && g * kInFlight < p.KC) { g *= 2; ++lg; }   // about 8 tiles per wave
+        if (g_force_waves) {
+            lg = 0;
+            while ((1 << lg) < g_force_waves) ++lg;
+        }
+        p.wlog2 = lg;
+        p.first_wg = total;
+        const int rbs_per_wg = kWaves >> lg;
+        total += (p.row_blocks + rbs_per_wg - 1) / rbs_per_wg;
     }
-    return hipErrorInvalidValue;
+    b.total_wgs = total;
+}
+
+hipError_t launch_decode(const DecodeBatch& b, int M, bool fused, hipStream_t s) {
+    int64_t max_Kp = 0;
+    for (int i = 0; i < b.count; ++i) max_Kp = (int64_t)b.p[i].KC * kTileK > max_Kp ? (int64_t)b.p[i].KC * kTileK : max_Kp;
+    const size_t lds = decode_lds_bytes(M, max_Kp, fused);
+    if (lds > (size_t)kMaxDecodeLds) return hipErrorInvalidValue;
+    return fused ? launch_m<true>(b, M, lds, s) : launch_m<false>(b, M, lds, s);
 }
 
 }  // namespace bl

@@ -26,11 +26,33 @@ struct GemvProblem {
     float          w_scale;
 };
 
-struct GemvBatch {
-    GemvProblem p[BL_MAX_BATCH];
-    int32_t     first_block[BL_MAX_BATCH + 1];  // prefix sum of row_blocks
-    int32_t     count;
+// One decode problem with its launch geometry; the fused form also carries the raw activations.
+struct DecodeProblem {
+    const uint4*   packed;
+    const int32_t* q;            // plain form: int8 activations as 32-bit words, row stride Kp/4
+    const float*   a_scale;      // plain form
+    const int32_t* q_sum;        // plain form
+    float*         out;
+    int32_t*       acc;          // may be null
+    const void*    x;            // fused form: [M, ldx] fp32 or bf16
+    int64_t        ldx;
+    int8_t*        q_out;        // fused form, optional copies of the quantizer's results
+    float*         a_scale_out;
+    int32_t*       q_sum_out;
+    int32_t        N, K, KC, row_blocks;
+    float          w_scale;
+    int32_t        x_flags;      // bit 0: bf16, bit 1: 128-bit vector loads allowed
+    int32_t        wlog2;        // log2(waves that share one row block)
+    int32_t        first_wg;     // first workgroup of this problem in the grid
 };
+
+struct DecodeBatch {
+    DecodeProblem p[BL_MAX_BATCH];
+    int32_t       count;
+    int32_t       total_wgs;
+};
+
+constexpr int kMaxDecodeLds = 128 * 1024;   // dynamic LDS ceiling of the decode kernels
 
 // Launchers (each returns the hipError_t of its launch).
 hipError_t launch_pack(const int8_t* w, int64_t N, int64_t K, int64_t Np, int64_t Kp, uint32_t* packed,
@@ -39,7 +61,9 @@ hipError_t launch_unpack(const uint32_t* packed, int64_t N, int64_t K, int64_t N
                          hipStream_t s);
 hipError_t launch_quant(const void* x, int is_bf16, int64_t M, int64_t K, int64_t ldx, int64_t Kp, int8_t* q,
                         float* a_scale, int32_t* q_sum, hipStream_t s);
-hipError_t launch_gemv(const GemvBatch& b, int M, hipStream_t s);
+void plan_decode(DecodeBatch& b);
+size_t decode_lds_bytes(int M, int64_t max_Kp, bool fused);
+hipError_t launch_decode(const DecodeBatch& b, int M, bool fused, hipStream_t s);
 hipError_t launch_gemm(const GemvProblem& p, int64_t M, hipStream_t s);
 
 // Launch-shape overrides for experiments (0 = choose automatically).

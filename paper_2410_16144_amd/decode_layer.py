@@ -33,12 +33,26 @@ class DecodeLayer:
         # dependency-ordered grouping of a real decoder layer: [q,k,v] [o] [gate,up] [down]
         self.groups_dep = [ops.GemvGroup(self.weights[a:b], acts[a:b], self.outs[a:b])
                            for a, b in ((0, 3), (3, 4), (4, 6), (6, 7))]
+        # fused quantize+multiply launches: everything at once, and in dependency order
+        in_x = [self.xs[INPUT_OF[p.name]] for p in self.projs]
+        self.fused_all = ops.DecodeGroup(self.weights, in_x, self.outs)
+        self.fused_dep = [ops.DecodeGroup(self.weights[a:b], in_x[a:b], self.outs[a:b])
+                          for a, b in ((0, 3), (3, 4), (4, 6), (6, 7))]
         self.packed_bytes = sum(p.packed_bytes for p in self.projs)
 
     # -- the hot path ------------------------------------------------------------------
     def quantize(self):
         for x, qa in zip(self.xs, self.qas):
             ops.quant_act(x, qa)
+
+    def step_fused(self):
+        """One launch: every workgroup quantizes its input row on chip, then multiplies."""
+        self.fused_all.launch()
+
+    def step_fused_dependency_ordered(self):
+        """Four fused launches in the order a real layer's data dependencies allow."""
+        for g in self.fused_dep:
+            g.launch()
 
     def step_single_launch(self):
         """4 activation quantizations, then all 7 products in one grouped launch."""

@@ -124,3 +124,39 @@ class GemvGroup:
     def launch(self):
         B.bl_gemv_batch(self.items, self.M, _stream())
         return self.outs
+
+
+def _dtype_code(x: torch.Tensor) -> int:
+    if x.dtype == torch.float32:
+        return B.BL_F32
+    if x.dtype == torch.bfloat16:
+        return B.BL_BF16
+    raise TypeError("activations must be float32 or bfloat16")
+
+
+class DecodeGroup:
+    """A prepared fused decode launch (bl_decode_batch): quantization + product of up to 8
+    BitLinears in one kernel.  `xs[i]` is the [M,K_i] input of `weights[i]` (inputs may repeat)."""
+
+    def __init__(self, weights, xs, outs=None, want_acc=False, want_quant=False):
+        assert 1 <= len(weights) <= B.BL_MAX_BATCH and len(weights) == len(xs)
+        self.M = int(xs[0].shape[0])
+        dev = weights[0].blob.device
+        self.weights, self.xs = list(weights), list(xs)
+        for w, x in zip(self.weights, self.xs):
+            assert x.is_cuda and x.dim() == 2 and x.stride(1) == 1 and x.shape == (self.M, w.K)
+        self.outs = list(outs) if outs is not None else [
+            torch.empty((self.M, w.N), dtype=torch.float32, device=dev) for w in weights]
+        self.accs = [torch.empty((self.M, w.N), dtype=torch.int32, device=dev) for w in weights] if want_acc else None
+        self.quants = [alloc_quant(self.M, w.K, dev) for w in weights] if want_quant else None
+        self.items = B.make_decode_items(
+            (x.data_ptr(), _dtype_code(x), x.stride(0), w.blob.data_ptr(), w.desc, o.data_ptr(),
+             self.accs[i].data_ptr() if want_acc else 0,
+             self.quants[i].q.data_ptr() if want_quant else 0,
+             self.quants[i].a_scale.data_ptr() if want_quant else 0,
+             self.quants[i].q_sum.data_ptr() if want_quant else 0)
+            for i, (w, x, o) in enumerate(zip(self.weights, self.xs, self.outs)))
+
+    def launch(self):
+        B.bl_decode_batch(self.items, self.M, _stream())
+        return self.outs

@@ -267,6 +267,82 @@ def test_gemv_batch_equals_separate_calls(dev, ops):
         assert np.array_equal(grp.accs[i].cpu().numpy(), oracle.matmul_i32(np.ascontiguousarray(q_ref), w_ref))
 
 
+# ------------------------------------------------------------------ fused decode
+
+def _assert_fused(ops, dev, problems, M):
+    """problems: list of (w, w_scale, x) with x either fp32 or bf16 bits; all with the same M."""
+    weights, xs = [], []
+    for w, s, x in problems:
+        weights.append(ops.pack_ternary(torch.from_numpy(w).to(dev), float(s)))
+        xs.append(_to_dev_bf16(x, dev) if x.dtype == np.uint16 else torch.from_numpy(x).to(dev))
+    grp = ops.DecodeGroup(weights, xs, want_acc=True, want_quant=True)
+    outs = grp.launch()
+    torch.cuda.synchronize()
+    for i, (w, s, x) in enumerate(problems):
+        q_ref, a_ref, s_ref = oracle.quant_act(x)
+        _assert_quant_equal(grp.quants[i], (q_ref, a_ref, s_ref), w.shape[1])
+        acc_ref = oracle.matmul_i32(q_ref, w)
+        assert np.array_equal(grp.accs[i].cpu().numpy(), acc_ref)
+        _check_out(outs[i], acc_ref, s, a_ref)
+    return grp
+
+
+@pytest.mark.parametrize("M", [1, 2, 3, 4, 5, 6, 7, 8])
+def test_fused_decode_parity_all_m(dev, ops, M):
+    _assert_fused(ops, dev, [_problem(1500 + M, M, 1536, 320, outl=0.01)], M)
+
+
+@pytest.mark.parametrize("bf16", [True, False])
+@pytest.mark.parametrize("N,K", [(64, 64), (1, 1), (70, 100), (200, 1000), (257, 3200), (3200, 8640), (129, 64 * 37),
+                                 (192, 33792)])
+def test_fused_decode_parity_shapes(dev, ops, N, K, bf16):
+    _assert_fused(ops, dev, [_problem(N * 17 + K, 1, K, N, p_zero=0.4, outl=0.01, bf16=bf16)], 1)
+
+
+def test_fused_decode_batch_of_seven_mixed_shapes(dev, ops):
+    shapes = [(320, 640), (320, 640), (128, 640), (640, 320), (64, 64), (200, 1000), (1000, 200)]
+    for M in (1, 3):
+        _assert_fused(ops, dev, [_problem(1700 + i + M, M, K, N, outl=0.01) for i, (N, K) in enumerate(shapes)], M)
+
+
+def test_fused_decode_edge_rows_and_strided_input(dev, ops):
+    K, N, M = 520, 130, 4
+    rng = synth.rng_for(1800)
+    w = synth.ternary_weights(rng, N, K)
+    x = np.zeros((M, K), np.float32)
+    x[1] = rng.standard_normal(K).astype(np.float32)
+    x[2, :8] = [127.0, 62.5, -61.5, 0.5, 1.5, 2.5, -0.5, -2.5]
+    x[3] = 1e-38
+    _assert_fused(ops, dev, [(w, np.float32(0.03), x)], M)
+    # strided, only element-aligned input: the scalar load path
+    ldx = 777
+    full = synth.activations(rng, M, ldx + 1)
+    big = torch.from_numpy(full).to(dev)
+    view = big.reshape(-1)[1:1 + M * ldx].reshape(M, ldx)[:, :K]
+    pw = ops.pack_ternary(torch.from_numpy(w).to(dev), 0.03)
+    grp = ops.DecodeGroup([pw], [view], want_acc=True, want_quant=True)
+    grp.launch()
+    torch.cuda.synchronize()
+    xh = np.ascontiguousarray(full.reshape(-1)[1:1 + M * ldx].reshape(M, ldx)[:, :K])
+    q_ref, a_ref, s_ref = oracle.quant_act(xh)
+    _assert_quant_equal(grp.quants[0], (q_ref, a_ref, s_ref), K)
+    assert np.array_equal(grp.accs[0].cpu().numpy(), oracle.matmul_i32(q_ref, w))
+
+
+def test_fused_decode_equals_two_call_sequence(dev, ops):
+    w, s, x = _problem(1900, 2, 2048, 512, outl=0.01)
+    pw = ops.pack_ternary(torch.from_numpy(w).to(dev), float(s))
+    xd = _to_dev_bf16(x, dev)
+    qa = ops.quant_act(xd)
+    out2, acc2 = ops.gemv(pw, qa, want_acc=True)
+    grp = ops.DecodeGroup([pw], [xd], want_acc=True, want_quant=True)
+    out1 = grp.launch()[0]
+    torch.cuda.synchronize()
+    assert torch.equal(out1, out2) and torch.equal(grp.accs[0], acc2)
+    assert torch.equal(grp.quants[0].q, qa.q) and torch.equal(grp.quants[0].a_scale, qa.a_scale)
+    assert torch.equal(grp.quants[0].q_sum, qa.q_sum)
+
+
 # ------------------------------------------------------------------ prefill product
 
 @pytest.mark.parametrize("M,N,K", [(1, 64, 64), (7, 70, 100), (33, 200, 1000), (128, 256, 512), (130, 320, 1536),
