@@ -214,7 +214,9 @@ bl_status bl_gemm(const void *packed_dev, const bl_packed_desc *d, const int8_t 
 /*
  * Launch-shape override for experiments and sweeps; process-wide, not thread-safe, never
  * changes results.  Keys: "gemv_waves" = waves of the decode kernel that share one
- * 64-row block (1, 2, 4, 8, 16; 0 = automatic).  Errors: BL_ERR_NULL, BL_ERR_SHAPE (unknown key/value).
+ * 64-row block (1, 2, 4, 8, 16; 0 = automatic); "decode_path" = 0 automatic
+ * (dot-product kernel for M = 1, matrix-core kernel for M >= 2), 1 = always the
+ * dot-product kernel, 2 = always the matrix-core kernel.  Errors: BL_ERR_NULL, BL_ERR_SHAPE (unknown key/value).
  */
 bl_status bl_set_tuning(const char *key, int32_t value);
 

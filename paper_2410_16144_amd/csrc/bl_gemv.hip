@@ -196,42 +196,216 @@ __global__ __launch_bounds__(kThreads, 8) void decode_kernel(const DecodeBatch b
     }
 }
 
+
+// ---------------------------------------------------------------------------------------------
+// 2..8 tokens: the same streaming structure, but the products run on the matrix cores.
+// With M tokens the dot4 formulation costs 20 + 16*M vector ops per tile and becomes VALU-bound
+// beyond M = 2; v_mfma_i32_16x16x64_i8 (A = 16 token rows x 64 k, B = 64 k x 16 weight rows)
+// takes the products off the vector ALU, which is left with unpacking only (32 ops per tile).
+// A tile's four packed words of lane r (row r, k-pieces 0..3) are regrouped by a 4x4 transpose
+// of 16-lane blocks (two v_permlane32_swap + two v_permlane16_swap) so that lane (j, g) holds
+// k-piece g of row 16t+j: the B-operand shape for the t-th group of 16 weight rows.
+// ---------------------------------------------------------------------------------------------
+typedef int v4i __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ void regroup16(const uint4& w, uint32_t (&t)[4]) {
+    auto s02 = __builtin_amdgcn_permlane32_swap(w.x, w.z, false, false);
+    auto s13 = __builtin_amdgcn_permlane32_swap(w.y, w.w, false, false);
+    auto a = __builtin_amdgcn_permlane16_swap(s02[0], s13[0], false, false);
+    auto c = __builtin_amdgcn_permlane16_swap(s02[1], s13[1], false, false);
+    t[0] = a[0]; t[1] = a[1]; t[2] = c[0]; t[3] = c[1];
+}
+
+__device__ __forceinline__ v4i expand_codes(uint32_t word) {
+    v4i r;
+    r[0] = (int)(word & 0x03030303u);
+    r[1] = (int)((word >> 2) & 0x03030303u);
+    r[2] = (int)((word >> 4) & 0x03030303u);
+    r[3] = (int)((word >> 6) & 0x03030303u);
+    return r;
+}
+
+constexpr int kMfmaRedBytes = kWaves * 16 * 32 * 4;   // per wave: 16 accumulator registers x 32 useful lanes
+
 template <int M, bool FUSED>
+__global__ __launch_bounds__(kThreads) void decode_mfma_kernel(const DecodeBatch b) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int blk = blockIdx.x;
+    int pi = 0;
+#pragma unroll
+    for (int i = 1; i < BL_MAX_BATCH; ++i) pi += (i < b.count && blk >= b.p[i].first_wg) ? 1 : 0;
+    const DecodeProblem& p = b.p[pi];
+    const int wg = blk - p.first_wg;
+
+    const int wlog2 = p.wlog2, G = 1 << wlog2;
+    const int ks = wave & (G - 1);
+    const int rb = wg * (kWaves >> wlog2) + (wave >> wlog2);
+    const bool active = rb < p.row_blocks;
+    const int KC = p.KC;
+    const int Kp = KC * kTileK;
+    const uint4* __restrict__ wp = p.packed + (int64_t)(active ? rb : 0) * KC * kWave + lane;
+
+    int8_t* lds_q = reinterpret_cast<int8_t*>(smem);
+    int* red = reinterpret_cast<int*>(smem + (FUSED ? M * Kp : 0));
+    float* s_f = reinterpret_cast<float*>(red + kMfmaRedBytes / 4);
+    int* s_i = reinterpret_cast<int*>(s_f + M * kWaves + M);
+
+    // this lane's share of the A operand: token row (lane % 16), k-piece (lane / 16)
+    const int mrow = lane & 15, piece = lane >> 4;
+    const bool has_row = mrow < M;
+    const int a_off = (has_row ? mrow : 0) * Kp + piece * 16;   // byte offset inside the activation matrix
+
+    uint4 w[kInFlight];
+    v4i av[kInFlight];
+    auto load_batch = [&](int kc0) {
+#pragma unroll
+        for (int u = 0; u < kInFlight; ++u) {
+            const int k = kc0 + u * G;
+            const int kk = k < KC ? k : KC - 1;   // clamped: always a valid tile
+            w[u] = wp[(int64_t)kk * kWave];
+            if constexpr (!FUSED) {
+                av[u] = v4i{0, 0, 0, 0};
+                if (has_row) av[u] = *reinterpret_cast<const v4i*>(reinterpret_cast<const int8_t*>(p.q) + a_off + kk * kTileK);
+            }
+        }
+    };
+    if (active) load_batch(ks);
+
+    if constexpr (FUSED) {
+        const bool bf16 = p.x_flags & 1, vec = p.x_flags & 2;
+        if (bf16) {
+            if (vec) quantize_rows_to_lds<M, true, true>(p, lds_q, s_f, s_i, tid, lane, wave);
+            else quantize_rows_to_lds<M, true, false>(p, lds_q, s_f, s_i, tid, lane, wave);
+        } else {
+            if (vec) quantize_rows_to_lds<M, false, true>(p, lds_q, s_f, s_i, tid, lane, wave);
+            else quantize_rows_to_lds<M, false, false>(p, lds_q, s_f, s_i, tid, lane, wave);
+        }
+        if (wg == 0 && p.q_out) {
+            for (int i = tid; i < M * Kp / 4; i += kThreads)
+                reinterpret_cast<int32_t*>(p.q_out)[i] = reinterpret_cast<const int32_t*>(lds_q)[i];
+        }
+    }
+
+    v4i acc[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) acc[t] = v4i{0, 0, 0, 0};
+
+    if (active) {
+        for (int kc0 = ks;;) {
+#pragma unroll
+            for (int u = 0; u < kInFlight; ++u) {
+                const int k = kc0 + u * G;
+                if (k < KC) {
+                    v4i a_op;
+                    if constexpr (FUSED) {
+                        a_op = v4i{0, 0, 0, 0};
+                        if (has_row) a_op = *reinterpret_cast<const v4i*>(lds_q + a_off + k * kTileK);
+                    } else {
+                        a_op = av[u];
+                    }
+                    uint32_t t[4];
+                    regroup16(w[u], t);
+#pragma unroll
+                    for (int g = 0; g < 4; ++g)
+                        acc[g] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a_op, expand_codes(t[g]), acc[g], 0, 0, 0);
+                }
+            }
+            kc0 += G * kInFlight;
+            if (kc0 >= KC) break;
+            load_batch(kc0);
+        }
+    }
+
+    // accumulator register r of group t, lane (j, g): token 4g + r, weight row 16t + j.  Tokens < 8 live in lanes 0..31.
+    if (lane < 32) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) red[(wave * 16 + t * 4 + r) * 32 + lane] = acc[t][r];
+    }
+    __syncthreads();
+
+    if (active && lane < 32) {
+        for (int idx = ks; idx < 16; idx += G) {
+            const int t = idx >> 2, r = idx & 3;
+            const int m = 4 * (lane >> 4) + r;
+            const int n = rb * kTileN + 16 * t + (lane & 15);
+            if (m < M && n < p.N) {
+                int qsum;
+                float scale;
+                if constexpr (FUSED) {
+                    qsum = 0;
+#pragma unroll
+                    for (int w16 = 0; w16 < kWaves; ++w16) qsum += s_i[m * kWaves + w16];
+                    scale = s_f[M * kWaves + m];
+                } else {
+                    qsum = p.q_sum[m];
+                    scale = p.a_scale[m];
+                }
+                int v = -qsum;
+                for (int g = 0; g < G; ++g) v += red[((wave - ks + g) * 16 + idx) * 32 + lane];
+                p.out[(int64_t)m * p.N + n] = (float)v * (p.w_scale * scale);
+                if (p.acc) p.acc[(int64_t)m * p.N + n] = v;
+            }
+        }
+    }
+    if constexpr (FUSED) {
+        if (wg == 0 && tid < M) {   // optional copy-out of the quantizer's scalars
+            int qsum = 0;
+            for (int w16 = 0; w16 < kWaves; ++w16) qsum += s_i[tid * kWaves + w16];
+            if (p.a_scale_out) p.a_scale_out[tid] = s_f[M * kWaves + tid];
+            if (p.q_sum_out) p.q_sum_out[tid] = qsum;
+        }
+    }
+}
+
+template <int M, bool FUSED, bool MFMA>
 hipError_t launch_one(const DecodeBatch& b, size_t lds_bytes, hipStream_t s) {
     static bool attr_set = false;   // raise the dynamic-LDS ceiling once per kernel (host-side setting only)
+    const void* fn = MFMA ? reinterpret_cast<const void*>(&decode_mfma_kernel<M, FUSED>)
+                          : reinterpret_cast<const void*>(&decode_kernel<M, FUSED>);
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&decode_kernel<M, FUSED>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDecodeLds);
+        hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDecodeLds);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    decode_kernel<M, FUSED><<<dim3((unsigned)b.total_wgs), dim3(kThreads), lds_bytes, s>>>(b);
+    if constexpr (MFMA) decode_mfma_kernel<M, FUSED><<<dim3((unsigned)b.total_wgs), dim3(kThreads), lds_bytes, s>>>(b);
+    else decode_kernel<M, FUSED><<<dim3((unsigned)b.total_wgs), dim3(kThreads), lds_bytes, s>>>(b);
     return hipGetLastError();
 }
 
-template <bool FUSED>
+template <bool FUSED, bool MFMA>
 hipError_t launch_m(const DecodeBatch& b, int M, size_t lds, hipStream_t s) {
     switch (M) {
-        case 1: return launch_one<1, FUSED>(b, lds, s);
-        case 2: return launch_one<2, FUSED>(b, lds, s);
-        case 3: return launch_one<3, FUSED>(b, lds, s);
-        case 4: return launch_one<4, FUSED>(b, lds, s);
-        case 5: return launch_one<5, FUSED>(b, lds, s);
-        case 6: return launch_one<6, FUSED>(b, lds, s);
-        case 7: return launch_one<7, FUSED>(b, lds, s);
-        case 8: return launch_one<8, FUSED>(b, lds, s);
+        case 1: return launch_one<1, FUSED, MFMA>(b, lds, s);
+        case 2: return launch_one<2, FUSED, MFMA>(b, lds, s);
+        case 3: return launch_one<3, FUSED, MFMA>(b, lds, s);
+        case 4: return launch_one<4, FUSED, MFMA>(b, lds, s);
+        case 5: return launch_one<5, FUSED, MFMA>(b, lds, s);
+        case 6: return launch_one<6, FUSED, MFMA>(b, lds, s);
+        case 7: return launch_one<7, FUSED, MFMA>(b, lds, s);
+        case 8: return launch_one<8, FUSED, MFMA>(b, lds, s);
     }
     return hipErrorInvalidValue;
 }
 
 int g_force_waves = 0;
+int g_force_path = 0;   // 0 auto, 1 dot4, 2 mfma
+
+bool use_mfma(int M) { return g_force_path ? g_force_path == 2 : M >= 2; }
 
 }  // namespace
 
 void set_gemv_waves(int waves) { g_force_waves = waves; }
+void set_decode_path(int path) { g_force_path = path; }
 
 size_t decode_lds_bytes(int M, int64_t max_Kp, bool fused) {
-    return (size_t)(fused ? M * max_Kp : 0) + (size_t)kWaves * M * kWave * 4 + (size_t)(2 * M * kWaves + M) * 4;
+    const size_t red = use_mfma(M) ? (size_t)kMfmaRedBytes : (size_t)kWaves * M * kWave * 4;
+    return (size_t)(fused ? M * max_Kp : 0) + red + (size_t)(2 * M * kWaves + M) * 4;
 }
 
 // Fill in the launch geometry: waves per row block for each problem and the workgroup prefix.
@@ -258,7 +432,8 @@ hipError_t launch_decode(const DecodeBatch& b, int M, bool fused, hipStream_t s)
     for (int i = 0; i < b.count; ++i) max_Kp = (int64_t)b.p[i].KC * kTileK > max_Kp ? (int64_t)b.p[i].KC * kTileK : max_Kp;
     const size_t lds = decode_lds_bytes(M, max_Kp, fused);
     if (lds > (size_t)kMaxDecodeLds) return hipErrorInvalidValue;
-    return fused ? launch_m<true>(b, M, lds, s) : launch_m<false>(b, M, lds, s);
+    if (use_mfma(M)) return fused ? launch_m<true, true>(b, M, lds, s) : launch_m<false, true>(b, M, lds, s);
+    return fused ? launch_m<true, false>(b, M, lds, s) : launch_m<false, false>(b, M, lds, s);
 }
 
 }  // namespace bl

@@ -110,6 +110,8 @@ def test_argument_validation_happens_before_any_launch():
     assert _st(B.bl_set_tuning, "nonsense", 1) == B.BL_ERR_SHAPE
     assert _st(B.bl_set_tuning, "gemv_waves", 3) == B.BL_ERR_SHAPE
     B.bl_set_tuning("gemv_waves", 0)
+    assert _st(B.bl_set_tuning, "decode_path", 3) == B.BL_ERR_SHAPE
+    B.bl_set_tuning("decode_path", 0)
 
 
 def test_status_strings():

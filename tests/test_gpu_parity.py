@@ -198,8 +198,21 @@ def _assert_product(ops, dev, kind, w, w_scale, x, waves=None):
     return pw, qa, out, acc
 
 
+@pytest.fixture
+def decode_path():
+    """Force the dot-product (1) or matrix-core (2) decode kernel for one test, then restore."""
+    from paper_2410_16144_amd import binding
+
+    def force(path):
+        binding.bl_set_tuning("decode_path", path)
+    yield force
+    binding.bl_set_tuning("decode_path", 0)
+
+
+@pytest.mark.parametrize("path", [0, 1, 2])
 @pytest.mark.parametrize("M", [1, 2, 3, 4, 5, 6, 7, 8])
-def test_gemv_parity_all_m(dev, ops, M):
+def test_gemv_parity_all_m(dev, ops, decode_path, M, path):
+    decode_path(path)
     w, s, x = _problem(500 + M, M, 1536, 320)
     _assert_product(ops, dev, "gemv", w, s, x)
 
@@ -287,9 +300,19 @@ def _assert_fused(ops, dev, problems, M):
     return grp
 
 
+@pytest.mark.parametrize("path", [0, 1, 2])
 @pytest.mark.parametrize("M", [1, 2, 3, 4, 5, 6, 7, 8])
-def test_fused_decode_parity_all_m(dev, ops, M):
+def test_fused_decode_parity_all_m(dev, ops, decode_path, M, path):
+    decode_path(path)
     _assert_fused(ops, dev, [_problem(1500 + M, M, 1536, 320, outl=0.01)], M)
+
+
+@pytest.mark.parametrize("M", [2, 8])
+@pytest.mark.parametrize("N,K", [(70, 100), (200, 1000), (4096, 11008), (129, 64 * 37)])
+def test_matrix_core_decode_shapes(dev, ops, N, K, M):
+    prob = _problem(N * 19 + K + M, M, K, N, p_zero=0.4, outl=0.01)
+    _assert_product(ops, dev, "gemv", *prob)
+    _assert_fused(ops, dev, [prob], M)
 
 
 @pytest.mark.parametrize("bf16", [True, False])
