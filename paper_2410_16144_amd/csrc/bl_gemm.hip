@@ -5,15 +5,19 @@
 // v_mfma_i32_32x32x32_i8:  D[m][n] += sum_k A[m][k] * B[k][n],  A = int8 activations,
 // B = weight codes (w+1) as int8; sum_k q is subtracted in the epilogue.
 //
-// Tiling.  Workgroup = 4 waves = 128 tokens x 256 weight rows; each wave owns 128 x 64, i.e.
-// 4 x 2 MFMA tiles (128 accumulator registers).  K advances one packed tile (64) per step:
-//   - activations: the 128 x 64 int8 tile goes global -> registers -> LDS (double buffered,
-//     rows padded to 80 bytes so the 128-bit operand reads are bank-conflict free);
+// Tiling.  Workgroup = 4 waves side by side along N = (32*MB) tokens x (256*NB) weight rows; each
+// wave owns (32*MB) x (64*NB), i.e. MB x 2NB MFMA tiles.  K advances one packed tile (64) per step:
+//   - activations: the (32*MB) x 64 int8 tile goes global -> registers -> LDS through a 3-stage
+//     ring (rows padded to 80 bytes so the 128-bit operand reads are bank-conflict free).  With
+//     three stages the operands of step i+1 are read from LDS while the MFMAs of step i run, and
+//     one barrier per step is enough;
 //   - weights: each wave loads its own packed 64 x 64 tile straight into registers (one 128-bit
-//     load per lane).  Lane r holds row r; v_permlane32_swap regroups two 16-k pieces so that
-//     lanes 0-31 / 32-63 hold k-halves of the same 32 rows -- exactly the MFMA B-operand shape --
-//     and 7 VALU ops expand a word of codes into the 16 int8 of one operand.  Weights never
-//     touch LDS, and stay 2 bits wide all the way from HBM into the register file.
+//     load per lane, two steps ahead).  Lane r holds row r; v_permlane32_swap regroups two 16-k
+//     pieces so that lanes 0-31 / 32-63 hold k-halves of the same 32 rows -- exactly the MFMA
+//     B-operand shape -- and 7 VALU ops expand a word of codes into the 16 int8 of one operand.
+//     Weights never touch LDS and stay 2 bits wide all the way from HBM into the register file.
+// The loop body is branch-free (out-of-range rows and row blocks are clamped to valid memory and
+// their results dropped in the epilogue) so that the accumulators never leave their registers.
 #include "bl_internal.hpp"
 
 namespace bl {
@@ -23,10 +27,9 @@ namespace {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
-constexpr int kBM = 128;          // tokens per workgroup
 constexpr int kWavesN = 4;        // waves along N
 constexpr int kLdsRow = 80;       // bytes per activation row in LDS (64 + 16 pad)
-constexpr int kMB = kBM / 32;     // MFMA tiles along M per wave
+constexpr int kStages = 3;
 
 __device__ __forceinline__ v4i expand_codes(uint32_t word) {
     v4i r;
@@ -37,86 +40,123 @@ __device__ __forceinline__ v4i expand_codes(uint32_t word) {
     return r;
 }
 
-__global__ __launch_bounds__(256) void gemm_kernel(const GemvProblem p, const int M) {
-    __shared__ __attribute__((aligned(16))) uint8_t lds[2][kBM * kLdsRow];
+template <int MB, int NB>
+__global__ __launch_bounds__(256, 2) void gemm_kernel(const GemvProblem p, const int M) {
+    constexpr int BM = 32 * MB;
+    constexpr int kStageBytes = BM * kLdsRow;
+    constexpr int NLD = (BM + 63) / 64;   // 16-byte pieces each thread moves per step (256 threads x 16 B = 64 rows)
+    __shared__ __attribute__((aligned(16))) uint8_t lds[kStages * kStageBytes];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int KC = p.KC;
-    const int m0 = blockIdx.y * kBM;
-    const int rb = blockIdx.x * kWavesN + wave;       // this wave's 64-row block of W
-    const bool wave_active = rb < p.row_blocks;
+    const int m0 = blockIdx.y * BM;
+    const int rb0 = (blockIdx.x * kWavesN + wave) * NB;   // this wave's first 64-row block of W (it owns NB of them)
     const int64_t qs = (int64_t)KC * kTileK;          // activation row stride in bytes
     const uint8_t* qbase = reinterpret_cast<const uint8_t*>(p.q);
 
-    // global -> LDS staging of the activation tile: thread t moves rows t/4 and t/4 + 64, 16 bytes at column 16*(t%4)
+    // global -> LDS staging: thread t moves 16 bytes at column 16*(t%4) of rows t/4 (+64)
     const int a_row = tid >> 2, a_col = (tid & 3) * 16;
-    auto load_a = [&](int kc, uint4 (&v)[2]) {
+    const uint8_t* a_src[NLD];
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int m = m0 + a_row + 64 * i;
-            v[i] = make_uint4(0, 0, 0, 0);
-            if (m < M) v[i] = *reinterpret_cast<const uint4*>(qbase + (int64_t)m * qs + kc * kTileK + a_col);
-        }
-    };
-    auto store_a = [&](int buf, const uint4 (&v)[2]) {
+    for (int i = 0; i < NLD; ++i) {
+        const int m = min(m0 + a_row + 64 * i, M - 1);   // clamped rows compute garbage that is never stored
+        a_src[i] = qbase + (int64_t)m * qs + a_col;
+    }
+    struct Staged { uint4 v[NLD]; };   // passed by value so that it lives in registers
+    auto gload = [&](int kc) {
+        const int k = min(kc, KC - 1);
+        Staged t;
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
-            *reinterpret_cast<uint4*>(&lds[buf][(a_row + 64 * i) * kLdsRow + a_col]) = v[i];
+        for (int i = 0; i < NLD; ++i) t.v[i] = *reinterpret_cast<const uint4*>(a_src[i] + k * kTileK);
+        return t;
     };
-    const uint4* wp = p.packed + (int64_t)(wave_active ? rb : 0) * KC * kWave + lane;
+    auto lstore = [&](int stage, const Staged t) {
+#pragma unroll
+        for (int i = 0; i < NLD; ++i)
+            if (BM >= 64 || a_row < BM)
+                *reinterpret_cast<uint4*>(&lds[stage * kStageBytes + (a_row + 64 * i) * kLdsRow + a_col]) = t.v[i];
+    };
+    const int op_row = lane & 31, op_g = lane >> 5;
+    const int a_read = op_row * kLdsRow + op_g * 16;
+    auto lread = [&](int stage, v4i (&a)[2][MB]) {
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+                a[ks][mb] = *reinterpret_cast<const v4i*>(&lds[stage * kStageBytes + mb * 32 * kLdsRow + a_read + ks * 32]);
+    };
+    struct WTiles { uint4 v[NB]; };    // by value: registers
+    const uint4* wp[NB];
+#pragma unroll
+    for (int j = 0; j < NB; ++j)   // row blocks beyond the matrix are clamped to a valid one and dropped in the epilogue
+        wp[j] = p.packed + (int64_t)min(rb0 + j, p.row_blocks - 1) * KC * kWave + lane;
+    auto wload = [&](int kc) {
+        WTiles t;
+#pragma unroll
+        for (int j = 0; j < NB; ++j) t.v[j] = wp[j][(int64_t)min(kc, KC - 1) * kWave];
+        return t;
+    };
 
-    v16i c[kMB][2];
+    v16i c[MB][2 * NB];
 #pragma unroll
-    for (int i = 0; i < kMB; ++i)
+    for (int i = 0; i < MB; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < 2 * NB; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) c[i][j][r] = 0;
 
-    uint4 a_next[2];
-    load_a(0, a_next);
-    uint4 w_cur = wp[0];
-    store_a(0, a_next);
+    // prologue: stages 0 and 1 filled, operands of step 0 in registers, tile of step 2 in flight
+    lstore(0, gload(0));
+    lstore(1, gload(1));
+    WTiles w_cur = wload(0), w_nxt = wload(1);
     __syncthreads();
+    v4i a0[2][MB], a1[2][MB];
+    lread(0, a0);
+    Staged g = gload(2);
 
-    const int op_row = lane & 31, op_g = lane >> 5;
-    for (int kc = 0; kc < KC; ++kc) {
-        const int buf = kc & 1;
-        uint4 w_next = w_cur;
-        const bool more = kc + 1 < KC;
-        if (more) {
-            load_a(kc + 1, a_next);
-            w_next = wp[(int64_t)(kc + 1) * kWave];
-        }
-        if (wave_active) {
-            // regroup: after the swaps, x0/x1 hold rows 0-31 / 32-63 for k 0..31, y0/y1 for k 32..63
-            auto s01 = __builtin_amdgcn_permlane32_swap(w_cur.x, w_cur.y, false, false);
-            auto s23 = __builtin_amdgcn_permlane32_swap(w_cur.z, w_cur.w, false, false);
-            const uint32_t bw[2][2] = {{s01[0], s01[1]}, {s23[0], s23[1]}};  // [kstep][n-block]
+    // one K step: MFMAs on (a_use, w_cur) while the operands of the next step and later tiles are fetched
+    auto step = [&](int kc, v4i (&a_use)[2][MB], v4i (&a_load)[2][MB]) {
+        const WTiles w_nn = wload(kc + 2);
+        const int st = kc % kStages;
+        const int st1 = st + 1 == kStages ? 0 : st + 1;
+        const int st2 = st1 + 1 == kStages ? 0 : st1 + 1;
+        lread(st1, a_load);      // written one step ago, published by the barrier that ended that step
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+            // after the swaps: [0] = rows 0-31, [1] = rows 32-63 of the tile; s01 covers k 0..31, s23 covers k 32..63
+            auto s01 = __builtin_amdgcn_permlane32_swap(w_cur.v[j].x, w_cur.v[j].y, false, false);
+            auto s23 = __builtin_amdgcn_permlane32_swap(w_cur.v[j].z, w_cur.v[j].w, false, false);
+            const uint32_t bw[2][2] = {{s01[0], s01[1]}, {s23[0], s23[1]}};
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks) {
                 const v4i b0 = expand_codes(bw[ks][0]);
                 const v4i b1 = expand_codes(bw[ks][1]);
 #pragma unroll
-                for (int mb = 0; mb < kMB; ++mb) {
-                    const v4i av = *reinterpret_cast<const v4i*>(
-                        &lds[buf][(mb * 32 + op_row) * kLdsRow + ks * 32 + op_g * 16]);
-                    c[mb][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(av, b0, c[mb][0], 0, 0, 0);
-                    c[mb][1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(av, b1, c[mb][1], 0, 0, 0);
+                for (int mb = 0; mb < MB; ++mb) {
+                    c[mb][2 * j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a_use[ks][mb], b0, c[mb][2 * j], 0, 0, 0);
+                    c[mb][2 * j + 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a_use[ks][mb], b1, c[mb][2 * j + 1], 0, 0, 0);
                 }
             }
         }
-        if (more) store_a(buf ^ 1, a_next);
+        lstore(st2, g);          // tile of step kc+2, loaded one step ago; stage st2 was last read two steps ago
+        g = gload(kc + 3);
         __syncthreads();
-        w_cur = w_next;
-    }
+        w_cur = w_nxt;
+        w_nxt = w_nn;
+    };
 
-    if (!wave_active) return;
+    int kc = 0;
+    for (; kc + 1 < KC; kc += 2) {
+        step(kc, a0, a1);
+        step(kc + 1, a1, a0);
+    }
+    if (kc < KC) step(kc, a0, a1);
+
     // epilogue: register r of a 32x32 tile holds row 8*(r/4) + 4*(lane/32) + r%4, column lane%32
 #pragma unroll
-    for (int mb = 0; mb < kMB; ++mb) {
+    for (int mb = 0; mb < MB; ++mb) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int m = m0 + mb * 32 + 8 * (r >> 2) + 4 * op_g + (r & 3);
@@ -124,8 +164,8 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemvProblem p, const in
                 const int qsum = p.q_sum[m];
                 const float sc = p.w_scale * p.a_scale[m];
 #pragma unroll
-                for (int nb = 0; nb < 2; ++nb) {
-                    const int n = rb * kTileN + nb * 32 + op_row;
+                for (int nb = 0; nb < 2 * NB; ++nb) {
+                    const int n = rb0 * kTileN + nb * 32 + op_row;   // n >= N covers padding rows and clamped row blocks
                     if (n < p.N) {
                         const int v = c[mb][nb][r] - qsum;
                         p.out[(int64_t)m * p.N + n] = (float)v * sc;
@@ -137,13 +177,27 @@ __global__ __launch_bounds__(256) void gemm_kernel(const GemvProblem p, const in
     }
 }
 
+int g_force_mb = 0;
+
 }  // namespace
 
+void set_gemm_mb(int mb) { g_force_mb = mb; }
+
 hipError_t launch_gemm(const GemvProblem& p, int64_t M, hipStream_t s) {
-    const int64_t gx = (p.row_blocks + kWavesN - 1) / kWavesN;
-    const int64_t gy = (M + kBM - 1) / kBM;
+    // wave tile = (32*MB) tokens x (64*NB) weight rows; workgroup = 4 waves along N
+    // 64-token tiles when that still gives every CU at least two workgroups, else 32-token tiles
+    int mb = ((M + 63) / 64) * ((p.row_blocks + kWavesN - 1) / kWavesN) >= 512 ? 2 : 1, nb = 1;
+    if (g_force_mb) { mb = g_force_mb / 10; nb = g_force_mb % 10; }
+    const int64_t gx = (p.row_blocks + kWavesN * nb - 1) / (kWavesN * nb);
+    const int64_t gy = (M + 32 * mb - 1) / (32 * mb);
     if (gy > 65535) return hipErrorInvalidValue;
-    gemm_kernel<<<dim3((unsigned)gx, (unsigned)gy), dim3(256), 0, s>>>(p, (int)M);
+    const dim3 grid((unsigned)gx, (unsigned)gy), block(256);
+    if (mb == 2 && nb == 1) gemm_kernel<2, 1><<<grid, block, 0, s>>>(p, (int)M);
+    else if (mb == 4 && nb == 1) gemm_kernel<4, 1><<<grid, block, 0, s>>>(p, (int)M);
+    else if (mb == 2 && nb == 2) gemm_kernel<2, 2><<<grid, block, 0, s>>>(p, (int)M);
+    else if (mb == 1 && nb == 2) gemm_kernel<1, 2><<<grid, block, 0, s>>>(p, (int)M);
+    else if (mb == 1 && nb == 1) gemm_kernel<1, 1><<<grid, block, 0, s>>>(p, (int)M);
+    else return hipErrorInvalidValue;
     return hipGetLastError();
 }
 

@@ -68,6 +68,7 @@ hipError_t launch_gemm(const GemvProblem& p, int64_t M, hipStream_t s);
 
 // Launch-shape overrides for experiments (0 = choose automatically).
 void set_gemv_waves(int waves);
+void set_gemm_mb(int mb);         // 0 automatic, 2 = 64-token tiles, 4 = 128-token tiles
 void set_decode_path(int path);   // 0 automatic, 1 dot-product kernel, 2 matrix-core kernel
 
 // ---- device helpers -------------------------------------------------------------------

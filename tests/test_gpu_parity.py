@@ -375,6 +375,18 @@ def test_gemm_parity(dev, ops, M, N, K):
     _assert_product(ops, dev, "gemm", w, s, x)
 
 
+@pytest.mark.parametrize("tile", [11, 12, 21, 22, 41])
+def test_gemm_parity_every_wave_tile(dev, ops, tile):
+    from paper_2410_16144_amd import binding
+    binding.bl_set_tuning("gemm_mb", tile)
+    try:
+        for M, N, K in ((200, 1000, 832), (33, 200, 1000), (257, 704, 64 * 5)):
+            w, s, x = _problem(M * 11 + N + K + tile, M, K, N, p_zero=0.4, outl=0.01)
+            _assert_product(ops, dev, "gemm", w, s, x)
+    finally:
+        binding.bl_set_tuning("gemm_mb", 0)
+
+
 def test_gemm_equals_gemv_for_small_m(dev, ops):
     w, s, x = _problem(4242, 8, 1536, 448)
     _, _, out_v, acc_v = _run_product(ops, dev, "gemv", w, s, x)
