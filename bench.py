@@ -3,14 +3,16 @@
 
 Default workload: the 3B-shape decoder layer at M=1 (hidden 3200, FFN 8640; ternary weights with
 P(0)=0.4, per-matrix scale; bf16 activations ~N(0,1) with 1% outliers x20).  One "step" is one pass
-of the decode hot path over one layer: the per-token absmax int8 quantization of the layer's four
-inputs and its 7 ternary x int8 GEMVs.  Successive steps walk through `--layers` distinct layers
-(>= 1 GiB of packed weights in total) so that every step streams its weights from HBM, not from the
-256 MB Infinity Cache.  Inputs are resident in HBM before the timed region starts.
+of the decode hot path over one layer: the per-token absmax int8 quantization of the layer's inputs
+and its 7 ternary x int8 GEMVs, issued as ONE fused launch (bl_decode_batch).  Successive steps walk
+through `--layers` distinct layers (>= 1 GiB of packed weights in total) so that every step streams
+its weights from HBM, not from the 256 MB Infinity Cache.  Inputs are resident in HBM before the
+timed region starts; the K timed steps are replayed from one HIP graph so that host launch overhead
+is outside the measurement.
 
 Prints ONE JSON line (metric = packed-weight GB/s of the decode GEMVs) with the dominant kernel's
-roofline and the CPU oracle timed beside it.  Extra sections (prefill TOPS, 100B-shape decode,
-dependency-ordered launch variants) are nested under "extra".
+roofline and the CPU oracle timed beside it.  Other launch variants, the 7B- and 100B-shape decode
+layers and the prefill GEMM (TOPS against the int8 MFMA peak) are nested under "extra".
 """
 import argparse
 import json
@@ -36,11 +38,14 @@ def parse_args():
     ap.add_argument("--no-extra", action="store_true", help="skip the extra sections")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
+    ap.add_argument("--full-100b", action="store_true",
+                    help="extra: build all 80 layers of the 100B-shape model (37 GB packed) and time a whole token")
+    ap.add_argument("--only", default="", help="run only one extra section (copy|prefill|decode7b|decode100b) and print it")
     return ap.parse_args()
 
 
 def timed(torch, fn):
-    """Run fn() bracketed by synchronize + events on the current stream; returns milliseconds."""
+    """Run fn() bracketed by synchronize + events on the current stream; returns (event ms, wall ms)."""
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
@@ -79,23 +84,24 @@ def run_steps(torch, step_fns, count, use_graph):
 
 
 def check_layer_against_oracle(torch, np, oracle, layer, host):
-    """Bit-exact q / acc and 1e-6 outputs for every projection of one layer."""
+    """Fused launch of one layer vs the oracle: bit-exact q / scales / acc, outputs within 1e-6."""
     from paper_2410_16144_amd import ops
     from paper_2410_16144_amd.decode_layer import INPUT_OF
-    layer.step_single_launch()
+    in_x = [layer.xs[INPUT_OF[p.name]] for p in layer.projs]
+    grp = ops.DecodeGroup(layer.weights, in_x, want_acc=True, want_quant=True)
+    outs = grp.launch()
+    layer.step_fused()
     torch.cuda.synchronize()
     refs_q = [oracle.quant_act(b) for b in host["x_bits"]]
     for i, p in enumerate(layer.projs):
         q, a, s = refs_q[INPUT_OF[p.name]]
-        qa = layer.qas[INPUT_OF[p.name]]
-        assert np.array_equal(qa.q.cpu().numpy()[:, :p.K], q), "q mismatch " + p.name
-        _, acc = ops.gemv(layer.weights[i], qa, want_acc=True)
+        assert np.array_equal(grp.quants[i].q.cpu().numpy()[:, :p.K], q), "q mismatch " + p.name
+        assert np.array_equal(grp.quants[i].a_scale.cpu().numpy(), a), "a_scale mismatch " + p.name
         acc_ref = oracle.matmul_i32(q, host["w"][i])
-        assert np.array_equal(acc.cpu().numpy(), acc_ref), "acc mismatch " + p.name
+        assert np.array_equal(grp.accs[i].cpu().numpy(), acc_ref), "acc mismatch " + p.name
         ref = oracle.dequant(acc_ref, host["w_scale"][i], a)
-        got = layer.outs[i].cpu().numpy()
-        assert np.all(np.abs(got - ref) <= 1e-6 * np.abs(ref)), "out mismatch " + p.name
-    return refs_q
+        for got in (outs[i].cpu().numpy(), layer.outs[i].cpu().numpy()):
+            assert np.all(np.abs(got - ref) <= 1e-6 * np.abs(ref)), "out mismatch " + p.name
 
 
 def cpu_baseline(np, oracle, host, projs, packed_bytes, seconds):
@@ -124,6 +130,20 @@ def cpu_baseline(np, oracle, host, projs, packed_bytes, seconds):
                       "2-bit byte count as the GPU value" % (n, dt)}
 
 
+def extra_copy(torch):
+    """A plain device-to-device copy of known size (torch's copy kernel): the practical HBM rate
+    of this box, and the calibration launch for the FETCH_SIZE / WRITE_SIZE counters."""
+    dev = torch.device("cuda:0")
+    n = 1 << 30
+    src = torch.empty(n, dtype=torch.uint8, device=dev).fill_(3)
+    dst = torch.empty_like(src)
+    for _ in range(2):
+        dst.copy_(src)
+    ms, _ = timed(torch, lambda: [dst.copy_(src) for _ in range(10)])
+    us = ms * 1e3 / 10
+    return {"bytes_read": n, "bytes_written": n, "us": round(us, 1), "GBps_read_plus_write": round(2 * n / us / 1e3, 1)}
+
+
 def extra_prefill(torch, M, K, N, iters=20):
     from paper_2410_16144_amd import ops, synth
     dev = torch.device("cuda:0")
@@ -141,23 +161,62 @@ def extra_prefill(torch, M, K, N, iters=20):
     us = ms * 1e3 / iters
     tops = 2.0 * M * K * N / us / 1e6
     msq, _ = timed(torch, lambda: [ops.quant_act(x, qa) for _ in range(iters)])
-    return {"workload": "prefill M=%d K=%d N=%d" % (M, K, N), "gemm_us": round(us, 2), "tops": round(tops, 1),
-            "frac_of_int8_mfma_peak": round(tops / INT8_PEAK_TOPS, 4), "quant_act_us": round(msq * 1e3 / iters, 2)}
+    usq = msq * 1e3 / iters
+    return {"workload": "prefill M=%d K=%d N=%d" % (M, K, N), "gemm_us": round(us, 2), "quant_act_us": round(usq, 2),
+            "roofline": {"bound": "mfma", "achieved": round(tops / 1e3, 4), "peak": INT8_PEAK_TOPS / 1e3,
+                         "unit": "POP/s", "frac": round(tops / INT8_PEAK_TOPS, 4), "ops_per_launch": 2 * M * K * N},
+            "tops_including_quant_act": round(2.0 * M * K * N / (us + usq) / 1e6, 1)}
 
 
 def extra_decode_shape(torch, name, hidden, ffn, M, layers, steps, use_graph):
+    """Layer decode on another model shape: fused launch for M=1; for M>1 one bl_quant_act per
+    input followed by one grouped matrix-core GEMV launch (both variants reported)."""
     from paper_2410_16144_amd.decode_layer import make_layer
     dev = torch.device("cuda:0")
     ls = [make_layer(5, i, hidden, ffn, M, dev, None, 0.0)[0] for i in range(layers)]
-    fns = [l.step_single_launch for l in ls]
-    for f in fns:
-        f()
-    ms, _, mode = run_steps(torch, fns, steps, use_graph)
-    us = ms * 1e3 / steps
-    gbs = ls[0].packed_bytes / us / 1e3
-    return {"workload": "%s layer decode M=%d (hidden %d, ffn %d), %d distinct layers" % (name, M, hidden, ffn, layers),
-            "us_per_layer": round(us, 2), "GBps": round(gbs, 1), "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
-            "launch": mode}
+    pb = ls[0].packed_bytes
+    res = {"workload": "%s layer decode M=%d (hidden %d, ffn %d), %d distinct layers rotated"
+                       % (name, M, hidden, ffn, layers), "packed_bytes_per_layer": pb}
+    for label, attr in (("fused_1_launch", "step_fused"), ("quant_x4_plus_grouped_gemv", "step_single_launch"),
+                        ("grouped_gemv_only", None)):
+        fns = [getattr(l, attr) if attr else l.group_all.launch for l in ls]
+        for f in fns[:2]:
+            f()
+        ms, _, mode = run_steps(torch, fns, steps, use_graph)
+        us = ms * 1e3 / steps
+        res[label] = {"us_per_layer": round(us, 2), "GBps": round(pb / us / 1e3, 1),
+                      "frac_of_hbm_peak": round(pb / us / 1e3 / HBM_PEAK_GBS, 4)}
+    res["launch"] = mode
+    return res
+
+
+def extra_full_100b(torch, use_graph):
+    """All 80 layers of the 100B-shape model resident (36.99 GB packed); one token = 80 fused launches."""
+    from paper_2410_16144_amd.decode_layer import make_layer
+    dev = torch.device("cuda:0")
+    ls = []
+    for i in range(80):
+        ls.append(make_layer(5, i, 12288, 33792, 1, dev, None, 0.0)[0])
+        torch.cuda.synchronize()
+    total = sum(l.packed_bytes for l in ls)
+    out = {"workload": "100B-shape token decode, M=1: 80 layers x 7 GEMVs, all weights resident", "packed_bytes": total}
+    for label, attr in (("fused", "step_fused"), ("quant_plus_grouped_gemv", "step_single_launch")):
+        fns = [getattr(l, attr) for l in ls]
+        for f in fns:
+            f()
+        ms, _, _ = run_steps(torch, fns, 80 * 3, use_graph)
+        out[label] = {"ms_per_token": round(ms / 3, 4), "GBps": round(total / (ms / 3) / 1e6, 1),
+                      "frac_of_hbm_peak": round(total / (ms / 3) / 1e6 / HBM_PEAK_GBS, 4)}
+    return out
+
+
+def load_traffic(kernel_key):
+    """HBM traffic per launch measured offline with rocprofv3 --pmc (see profiles/): committed numbers."""
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    if not os.path.exists(path):
+        return None
+    with open(path) as f:
+        return json.load(f).get(kernel_key)
 
 
 def main():
@@ -175,8 +234,19 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
     use_graph = not args.no_graph
-    hidden, ffn, M = 3200, 8640, 1
 
+    if args.only:
+        sect = {"copy": lambda: extra_copy(torch),
+                "prefill": lambda: [extra_prefill(torch, m, k, n) for m in (512, 2048)
+                                    for (k, n) in ((4096, 11008), (11008, 4096))],
+                "decode7b": lambda: [extra_decode_shape(torch, "7B-shape", 4096, 11008, m, 24, 480, use_graph)
+                                     for m in (1, 4, 8)],
+                "decode100b": lambda: extra_decode_shape(torch, "100B-shape", 12288, 33792, 1, 6, 120, use_graph),
+                }[args.only]()
+        print(json.dumps({args.only: sect}))
+        return
+
+    hidden, ffn, M = 3200, 8640, 1
     # layer 0 is drawn on the host so that the oracle sees the same bits; the rest on the device
     layer0, host = make_layer(2, 0, hidden, ffn, M, dev, 0.4, 0.01, host=True)
     layers = [layer0] + [make_layer(2, i, hidden, ffn, M, dev, 0.4, 0.01)[0] for i in range(1, args.layers)]
@@ -187,30 +257,26 @@ def main():
     check_layer_against_oracle(torch, np, oracle, layer0, host)
 
     # ---- the timed region: exactly --steps steps after --warmup untimed ones
-    fns = [l.step_single_launch for l in layers]
+    fns = [l.step_fused for l in layers]
     for i in range(args.warmup):
         fns[i % len(fns)]()
     ms, wall_ms, mode = run_steps(torch, fns, args.steps, use_graph)
     ms_per_step = ms / args.steps
     value = packed_bytes / (ms_per_step * 1e-3) / 1e9
-
-    # ---- dominant kernel (the grouped decode GEMV): average launch duration over back-to-back launches
-    gfns = [l.group_all.launch for l in layers]
-    kms, _, _ = run_steps(torch, gfns, args.steps, use_graph)
-    kernel_us = kms * 1e3 / args.steps
-    achieved = packed_bytes / kernel_us / 1e3
+    # the step IS one launch of the dominant kernel, so its average launch duration is the step time
+    kernel_us = ms_per_step * 1e3
     result = {
         "metric": "ternary x int8 GEMV packed-weight GB/s", "value": round(value, 1), "unit": "GB/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 6),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
-        "config": {"workload": "3B-shape decoder layer decode, M=1: 4 bl_quant_act + 7 ternary GEMVs "
-                               "(hidden 3200, ffn 8640) per step, %d distinct layers rotated (%.2f GB packed)"
-                               % (len(layers), packed_bytes * len(layers) / 1e9),
+        "config": {"workload": "3B-shape decoder layer decode, M=1: absmax int8 quantization of the layer's inputs + "
+                               "7 ternary GEMVs (hidden 3200, ffn 8640) per step in one fused launch, %d distinct "
+                               "layers rotated (%.2f GB packed)" % (len(layers), packed_bytes * len(layers) / 1e9),
                    "launch": mode, "packed_bytes_per_step": packed_bytes,
                    "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4), "wall_ms_timed_region": round(wall_ms, 3)},
-        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-                     "kernel": "gemv_kernel (grouped launch of the layer's 7 GEMVs)",
+        "roofline": {"bound": "hbm", "achieved": round(value, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(value / HBM_PEAK_GBS, 4), "traffic": load_traffic("decode_kernel_3b_layer_m1"),
+                     "kernel": "decode_kernel<1, true> (fused quantize + 7 GEMVs of one layer per launch)",
                      "avg_launch_us": round(kernel_us, 3), "bytes_per_launch": packed_bytes},
     }
 
@@ -219,17 +285,29 @@ def main():
 
     if not args.no_extra:
         extra = {}
-        dms, _, _ = run_steps(torch, [l.step_dependency_ordered for l in layers], args.steps, use_graph)
-        extra["dependency_ordered_step_us"] = round(dms * 1e3 / args.steps, 3)
-        sms, _, _ = run_steps(torch, [l.step_separate for l in layers], args.steps, use_graph)
-        extra["one_launch_per_gemv_step_us"] = round(sms * 1e3 / args.steps, 3)
-        del layers, fns, gfns, layer0
+        variants = {}
+        for label, attr in (("fused_dependency_ordered_4_launches", "step_fused_dependency_ordered"),
+                            ("quant_x4_plus_grouped_gemv", "step_single_launch"),
+                            ("quant_x4_plus_7_gemv_launches", "step_separate")):
+            vms, _, _ = run_steps(torch, [getattr(l, attr) for l in layers], args.steps, use_graph)
+            variants[label] = {"us_per_step": round(vms * 1e3 / args.steps, 3),
+                               "GBps": round(packed_bytes / (vms / args.steps) / 1e6, 1)}
+        gms, _, _ = run_steps(torch, [l.group_all.launch for l in layers], args.steps, use_graph)
+        variants["grouped_gemv_kernel_only"] = {"us_per_step": round(gms * 1e3 / args.steps, 3),
+                                                "GBps": round(packed_bytes / (gms / args.steps) / 1e6, 1)}
+        extra["decode_3b_launch_variants"] = variants
+        del layers, fns, layer0
+        torch.cuda.empty_cache()
+        extra["copy_1GiB"] = extra_copy(torch)
         torch.cuda.empty_cache()
         extra["decode_7b"] = [extra_decode_shape(torch, "7B-shape", 4096, 11008, m, 24, 480, use_graph)
                               for m in (1, 4, 8)]
         torch.cuda.empty_cache()
-        extra["decode_100b"] = extra_decode_shape(torch, "100B-shape", 12288, 33792, 1, 4, 80, use_graph)
+        extra["decode_100b_layer"] = extra_decode_shape(torch, "100B-shape", 12288, 33792, 1, 6, 120, use_graph)
         torch.cuda.empty_cache()
+        if args.full_100b:
+            extra["decode_100b_token"] = extra_full_100b(torch, use_graph)
+            torch.cuda.empty_cache()
         extra["prefill"] = [extra_prefill(torch, m, k, n) for m in (512, 2048)
                             for (k, n) in ((4096, 11008), (11008, 4096))]
         result["extra"] = extra
