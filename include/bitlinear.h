@@ -194,6 +194,8 @@ typedef struct {
  * are already in flight, so the int8 activations never travel through HBM
  * and the separate quantization launch disappears.  Results (q, a_scale,
  * q_sum, acc, out) are bit-identical to the two-call sequence.
+ * All items of one launch must have the same activation dtype (else
+ * BL_ERR_DTYPE).
  * Limit: M * Kp (+ 5 KiB per token) must fit the kernel's 128 KiB of
  * on-chip memory, else BL_ERR_SHAPE; use the two-call sequence then.
  * Pointer alignment as for bl_quant_act / bl_gemv.

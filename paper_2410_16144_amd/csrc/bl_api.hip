@@ -173,6 +173,7 @@ bl_status bl_decode_batch(const bl_decode_item* items, int32_t count, int64_t M,
         const bl_decode_item& it = items[i];
         if (!it.x_dev || !it.packed_dev || !it.desc || !it.out_dev) return BL_ERR_NULL;
         if (it.dt != BL_F32 && it.dt != BL_BF16) return BL_ERR_DTYPE;
+        if (it.dt != items[0].dt) return BL_ERR_DTYPE;   // one activation dtype per launch
         bl_status s = check_desc(it.desc);
         if (s != BL_OK) return s;
         if (it.ldx < it.desc->K) return BL_ERR_SHAPE;

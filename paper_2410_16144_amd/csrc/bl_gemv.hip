@@ -56,7 +56,8 @@ __device__ __forceinline__ void tile_mac(const uint4& w, QPtr qk, int q_stride_w
     }
 }
 
-// Quantize M token rows into LDS; returns per-token scale and sum(q) in s_scale / s_qsum (LDS).
+// Quantize M token rows into LDS; per-token scale and partial sums of q are left in s_f / s_i (LDS).
+// General form: the row is read twice (the second read hits L1/L2).
 template <int M, bool BF16, bool VEC>
 __device__ __forceinline__ void quantize_rows_to_lds(const DecodeProblem& p, int8_t* lds_q, float* s_f, int* s_i,
                                                      int tid, int lane, int wave) {
@@ -89,7 +90,45 @@ __device__ __forceinline__ void quantize_rows_to_lds(const DecodeProblem& p, int
     __syncthreads();
 }
 
-template <int M, bool FUSED>
+// One token whose row fits two 8-element vectors per thread (K <= 16384, vector-loadable): the raw
+// inputs are loaded by the caller BEFORE the weight tiles (loads retire in order, so waiting for x
+// then leaves the 8 weight loads in flight) and stay in registers between the two passes.
+template <bool BF16>
+__device__ __forceinline__ void quantize_row_from_regs(const Raw8<BF16>& r0, const Raw8<BF16>& r1, bool h0, bool h1,
+                                                       int K, int Kp, int8_t* lds_q, float* s_f, int* s_i, int tid,
+                                                       int lane, int wave) {
+    float am;
+    {
+        float v[8];
+        unpack_raw8<BF16>(r0, v);
+        am = h0 ? absmax8(v) : 0.0f;
+        unpack_raw8<BF16>(r1, v);
+        am = fmaxf(am, h1 ? absmax8(v) : 0.0f);
+    }
+    am = wave_max(am);
+    if (lane == 0) s_f[wave] = am;
+    __syncthreads();
+    am = s_f[0];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) am = fmaxf(am, s_f[w]);
+    float inv, scale;
+    quant_scales(am, inv, scale);
+    int sum = 0;
+    {
+        float v[8];
+        unpack_raw8<BF16>(r0, v);
+        if (h0) sum += quantize8(v, inv, lds_q + tid * 8);
+        unpack_raw8<BF16>(r1, v);
+        if (h1) sum += quantize8(v, inv, lds_q + (tid + kThreads) * 8);
+    }
+    for (int k = K + tid; k < Kp; k += kThreads) lds_q[k] = 0;
+    sum = wave_sum(sum);
+    if (tid == 0) s_f[kWaves] = scale;
+    if (lane == 0) s_i[wave] = sum;
+    __syncthreads();
+}
+
+template <int M, bool FUSED, bool XBF16>   // XBF16: dtype of the raw activations (fused form only)
 __global__ __launch_bounds__(kThreads, 8) void decode_kernel(const DecodeBatch b) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
@@ -121,23 +160,39 @@ __global__ __launch_bounds__(kThreads, 8) void decode_kernel(const DecodeBatch b
 
     // first batch of weight tiles goes in flight before anything else
     uint4 w[kInFlight];
-    auto load_batch = [&](int kc0) {
+    auto load_part = [&](int kc0, int first, int last) {
 #pragma unroll
         for (int u = 0; u < kInFlight; ++u) {
-            const int k = kc0 + u * G;
-            w[u] = wp[(int64_t)(k < KC ? k : KC - 1) * kWave];   // clamped: always a valid tile
+            if (u >= first && u < last) {
+                const int k = kc0 + u * G;
+                w[u] = wp[(int64_t)(k < KC ? k : KC - 1) * kWave];   // clamped: always a valid tile
+            }
         }
     };
-    if (active) load_batch(ks);
-
-    if constexpr (FUSED) {
-        const bool bf16 = p.x_flags & 1, vec = p.x_flags & 2;
-        if (bf16) {
-            if (vec) quantize_rows_to_lds<M, true, true>(p, lds_q, s_f, s_i, tid, lane, wave);
-            else quantize_rows_to_lds<M, true, false>(p, lds_q, s_f, s_i, tid, lane, wave);
+    auto load_batch = [&](int kc0) { load_part(kc0, 0, kInFlight); };
+    if constexpr (!FUSED) {
+        load_batch(ks);   // waves without a row block load (valid) block 0: no branch, exact wait counts
+    } else {
+        const bool vec = p.x_flags & 2;
+        bool fast = false;
+        if constexpr (M == 1) fast = vec && p.K <= 2 * kThreads * 8;   // uniform
+        if (fast) {
+            if constexpr (M == 1) {
+                const int k0 = tid * 8, k1 = k0 + kThreads * 8;
+                const bool h0 = k0 < p.K, h1 = k1 < p.K;
+                const Raw8<XBF16> r0 = load_raw8<XBF16>(p.x, h0 ? k0 : 0), r1 = load_raw8<XBF16>(p.x, h1 ? k1 : 0);
+                // half of the weight tiles go in flight behind the activations (loads retire in order, so the
+                // quantizer's wait for x leaves them outstanding); the other half follows the quantizer, which
+                // keeps its register footprint small
+                load_part(ks, 0, kInFlight / 2);
+                quantize_row_from_regs<XBF16>(r0, r1, h0, h1, p.K, Kp, lds_q, s_f, s_i, tid, lane, wave);
+                load_part(ks, kInFlight / 2, kInFlight);
+            }
         } else {
-            if (vec) quantize_rows_to_lds<M, false, true>(p, lds_q, s_f, s_i, tid, lane, wave);
-            else quantize_rows_to_lds<M, false, false>(p, lds_q, s_f, s_i, tid, lane, wave);
+            // general form: quantize first (its loads would otherwise have to wait for the weight tiles too)
+            if (vec) quantize_rows_to_lds<M, XBF16, true>(p, lds_q, s_f, s_i, tid, lane, wave);
+            else quantize_rows_to_lds<M, XBF16, false>(p, lds_q, s_f, s_i, tid, lane, wave);
+            load_batch(ks);   // waves without a row block load (valid) block 0: no branch, exact wait counts
         }
         if (wg == 0 && p.q_out) {   // optional copy-out of the quantized activations
             for (int i = tid; i < M * Kp / 4; i += kThreads)
@@ -227,7 +282,7 @@ __device__ __forceinline__ v4i expand_codes(uint32_t word) {
 
 constexpr int kMfmaRedBytes = kWaves * 16 * 32 * 4;   // per wave: 16 accumulator registers x 32 useful lanes
 
-template <int M, bool FUSED>
+template <int M, bool FUSED, bool XBF16>
 __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(const DecodeBatch b) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
@@ -273,17 +328,11 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(const DecodeBatch
             }
         }
     };
-    if (active) load_batch(ks);
+    load_batch(ks);   // waves without a row block load (valid) block 0: no branch, exact wait counts
 
     if constexpr (FUSED) {
-        const bool bf16 = p.x_flags & 1, vec = p.x_flags & 2;
-        if (bf16) {
-            if (vec) quantize_rows_to_lds<M, true, true>(p, lds_q, s_f, s_i, tid, lane, wave);
-            else quantize_rows_to_lds<M, true, false>(p, lds_q, s_f, s_i, tid, lane, wave);
-        } else {
-            if (vec) quantize_rows_to_lds<M, false, true>(p, lds_q, s_f, s_i, tid, lane, wave);
-            else quantize_rows_to_lds<M, false, false>(p, lds_q, s_f, s_i, tid, lane, wave);
-        }
+        if (p.x_flags & 2) quantize_rows_to_lds<M, XBF16, true>(p, lds_q, s_f, s_i, tid, lane, wave);
+        else quantize_rows_to_lds<M, XBF16, false>(p, lds_q, s_f, s_i, tid, lane, wave);
         if (wg == 0 && p.q_out) {
             for (int i = tid; i < M * Kp / 4; i += kThreads)
                 reinterpret_cast<int32_t*>(p.q_out)[i] = reinterpret_cast<const int32_t*>(lds_q)[i];
@@ -363,32 +412,33 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(const DecodeBatch
     }
 }
 
-template <int M, bool FUSED, bool MFMA>
+template <int M, bool FUSED, bool MFMA, bool XBF16>
 hipError_t launch_one(const DecodeBatch& b, size_t lds_bytes, hipStream_t s) {
     static bool attr_set = false;   // raise the dynamic-LDS ceiling once per kernel (host-side setting only)
-    const void* fn = MFMA ? reinterpret_cast<const void*>(&decode_mfma_kernel<M, FUSED>)
-                          : reinterpret_cast<const void*>(&decode_kernel<M, FUSED>);
+    const void* fn = MFMA ? reinterpret_cast<const void*>(&decode_mfma_kernel<M, FUSED, XBF16>)
+                          : reinterpret_cast<const void*>(&decode_kernel<M, FUSED, XBF16>);
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDecodeLds);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    if constexpr (MFMA) decode_mfma_kernel<M, FUSED><<<dim3((unsigned)b.total_wgs), dim3(kThreads), lds_bytes, s>>>(b);
-    else decode_kernel<M, FUSED><<<dim3((unsigned)b.total_wgs), dim3(kThreads), lds_bytes, s>>>(b);
+    const dim3 grid((unsigned)b.total_wgs), block(kThreads);
+    if constexpr (MFMA) decode_mfma_kernel<M, FUSED, XBF16><<<grid, block, lds_bytes, s>>>(b);
+    else decode_kernel<M, FUSED, XBF16><<<grid, block, lds_bytes, s>>>(b);
     return hipGetLastError();
 }
 
-template <bool FUSED, bool MFMA>
+template <bool FUSED, bool MFMA, bool XBF16>
 hipError_t launch_m(const DecodeBatch& b, int M, size_t lds, hipStream_t s) {
     switch (M) {
-        case 1: return launch_one<1, FUSED, MFMA>(b, lds, s);
-        case 2: return launch_one<2, FUSED, MFMA>(b, lds, s);
-        case 3: return launch_one<3, FUSED, MFMA>(b, lds, s);
-        case 4: return launch_one<4, FUSED, MFMA>(b, lds, s);
-        case 5: return launch_one<5, FUSED, MFMA>(b, lds, s);
-        case 6: return launch_one<6, FUSED, MFMA>(b, lds, s);
-        case 7: return launch_one<7, FUSED, MFMA>(b, lds, s);
-        case 8: return launch_one<8, FUSED, MFMA>(b, lds, s);
+        case 1: return launch_one<1, FUSED, MFMA, XBF16>(b, lds, s);
+        case 2: return launch_one<2, FUSED, MFMA, XBF16>(b, lds, s);
+        case 3: return launch_one<3, FUSED, MFMA, XBF16>(b, lds, s);
+        case 4: return launch_one<4, FUSED, MFMA, XBF16>(b, lds, s);
+        case 5: return launch_one<5, FUSED, MFMA, XBF16>(b, lds, s);
+        case 6: return launch_one<6, FUSED, MFMA, XBF16>(b, lds, s);
+        case 7: return launch_one<7, FUSED, MFMA, XBF16>(b, lds, s);
+        case 8: return launch_one<8, FUSED, MFMA, XBF16>(b, lds, s);
     }
     return hipErrorInvalidValue;
 }
@@ -432,8 +482,13 @@ hipError_t launch_decode(const DecodeBatch& b, int M, bool fused, hipStream_t s)
     for (int i = 0; i < b.count; ++i) max_Kp = (int64_t)b.p[i].KC * kTileK > max_Kp ? (int64_t)b.p[i].KC * kTileK : max_Kp;
     const size_t lds = decode_lds_bytes(M, max_Kp, fused);
     if (lds > (size_t)kMaxDecodeLds) return hipErrorInvalidValue;
-    if (use_mfma(M)) return fused ? launch_m<true, true>(b, M, lds, s) : launch_m<false, true>(b, M, lds, s);
-    return fused ? launch_m<true, false>(b, M, lds, s) : launch_m<false, false>(b, M, lds, s);
+    const bool bf16 = b.p[0].x_flags & 1;   // the fused form requires one activation dtype per launch
+    if (use_mfma(M)) {
+        if (!fused) return launch_m<false, true, true>(b, M, lds, s);
+        return bf16 ? launch_m<true, true, true>(b, M, lds, s) : launch_m<true, true, false>(b, M, lds, s);
+    }
+    if (!fused) return launch_m<false, false, true>(b, M, lds, s);
+    return bf16 ? launch_m<true, false, true>(b, M, lds, s) : launch_m<true, false, false>(b, M, lds, s);
 }
 
 }  // namespace bl

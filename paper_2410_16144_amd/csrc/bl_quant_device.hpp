@@ -8,17 +8,29 @@ namespace bl {
 
 __device__ __forceinline__ float bf16_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
 
-__device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
-    return v;
+// Wave-wide reductions on the vector ALU's data-parallel-primitive lane moves (no LDS round trips):
+// four steps reduce each row of 16 lanes, four v_readlane pick up the rows.  The result is uniform.
+#define BL_DPP(x, ctrl) __builtin_amdgcn_update_dpp(0, (x), (ctrl), 0xf, 0xf, false)
+__device__ __forceinline__ float wave_max(float v) {   // v >= 0: compare the bit patterns as integers
+    int x = __float_as_int(v);
+    x = max(x, BL_DPP(x, 0xB1));    // quad_perm [1,0,3,2]
+    x = max(x, BL_DPP(x, 0x4E));    // quad_perm [2,3,0,1]
+    x = max(x, BL_DPP(x, 0x141));   // row_half_mirror
+    x = max(x, BL_DPP(x, 0x140));   // row_mirror
+    const int a = __builtin_amdgcn_readlane(x, 0), b = __builtin_amdgcn_readlane(x, 16);
+    const int c = __builtin_amdgcn_readlane(x, 32), d = __builtin_amdgcn_readlane(x, 48);
+    return __int_as_float(max(max(a, b), max(c, d)));
 }
 
-__device__ __forceinline__ int wave_sum(int v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-    return v;
+__device__ __forceinline__ int wave_sum(int x) {
+    x += BL_DPP(x, 0xB1);
+    x += BL_DPP(x, 0x4E);
+    x += BL_DPP(x, 0x141);
+    x += BL_DPP(x, 0x140);
+    return __builtin_amdgcn_readlane(x, 0) + __builtin_amdgcn_readlane(x, 16) + __builtin_amdgcn_readlane(x, 32) +
+           __builtin_amdgcn_readlane(x, 48);
 }
+#undef BL_DPP
 
 // q = clip(round_half_even(v * inv), -128, 127)
 __device__ __forceinline__ int quant_one(float v, float inv) {
@@ -53,6 +65,64 @@ __device__ __forceinline__ void load8(const void* row, int k, float (&v)[8]) {
         v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
         v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
     }
+}
+
+// The same 8 elements as raw bits (kept in registers between the absmax and the quantize pass).
+template <bool BF16>
+struct Raw8 {
+    uint4 a, b;   // bf16: a only; fp32: a, b
+};
+
+template <bool BF16>
+__device__ __forceinline__ Raw8<BF16> load_raw8(const void* row, int k) {
+    Raw8<BF16> r;
+    if constexpr (BF16) {
+        r.a = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(row) + k);
+        r.b = r.a;
+    } else {
+        const uint4* p = reinterpret_cast<const uint4*>(static_cast<const float*>(row) + k);
+        r.a = p[0];
+        r.b = p[1];
+    }
+    return r;
+}
+
+template <bool BF16>
+__device__ __forceinline__ void unpack_raw8(const Raw8<BF16>& r, float (&v)[8]) {
+    if constexpr (BF16) {
+        const uint32_t w[4] = {r.a.x, r.a.y, r.a.z, r.a.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            v[2 * i] = bf16_to_f32(w[i] & 0xffffu);
+            v[2 * i + 1] = bf16_to_f32(w[i] >> 16);
+        }
+    } else {
+        const uint32_t w[8] = {r.a.x, r.a.y, r.a.z, r.a.w, r.b.x, r.b.y, r.b.z, r.b.w};
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = __uint_as_float(w[i]);
+    }
+}
+
+__device__ __forceinline__ float absmax8(const float (&v)[8]) {
+    float m = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) m = fmaxf(m, fabsf(v[i]));
+    return m;
+}
+
+// Quantize 8 values and store them as 8 bytes at q8; returns their sum.
+__device__ __forceinline__ int quantize8(const float (&v)[8], float inv, int8_t* q8) {
+    uint32_t lo = 0, hi = 0;
+    int sum = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int a = quant_one(v[i], inv), b = quant_one(v[4 + i], inv);
+        sum += a + b;
+        lo |= (uint32_t)(a & 0xff) << (8 * i);
+        hi |= (uint32_t)(b & 0xff) << (8 * i);
+    }
+    *reinterpret_cast<uint2*>(q8) = make_uint2(lo, hi);
+    return sum;
 }
 
 template <bool BF16>
