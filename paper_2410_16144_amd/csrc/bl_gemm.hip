@@ -7,12 +7,12 @@
 //
 // Tiling.  Workgroup = 4 waves side by side along N = (32*MB) tokens x (256*NB) weight rows; each
 // wave owns (32*MB) x (64*NB), i.e. MB x 2NB MFMA tiles.  K advances one packed tile (64) per step:
-//   - activations: the (32*MB) x 64 int8 tile goes global -> registers -> LDS through a 3-stage
-//     ring (rows padded to 80 bytes so the 128-bit operand reads are bank-conflict free).  With
-//     three stages the operands of step i+1 are read from LDS while the MFMAs of step i run, and
-//     one barrier per step is enough;
+//   - activations: the (32*MB) x 64 int8 tile goes global -> registers (three steps ahead) -> LDS
+//     through a 3-stage ring (rows padded to 80 bytes so the 128-bit operand reads are
+//     bank-conflict free).  With three stages the operands of step i+1 are read from LDS while
+//     the MFMAs of step i run, and one barrier per step is enough;
 //   - weights: each wave loads its own packed 64 x 64 tile straight into registers (one 128-bit
-//     load per lane, two steps ahead).  Lane r holds row r; v_permlane32_swap regroups two 16-k
+//     load per lane, four steps ahead).  Lane r holds row r; v_permlane32_swap regroups two 16-k
 //     pieces so that lanes 0-31 / 32-63 hold k-halves of the same 32 rows -- exactly the MFMA
 //     B-operand shape -- and 7 VALU ops expand a word of codes into the 16 int8 of one operand.
 //     Weights never touch LDS and stay 2 bits wide all the way from HBM into the register file.
@@ -28,7 +28,10 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int kWavesN = 4;        // waves along N
-constexpr int kLdsRow = 80;       // bytes per activation row in LDS (64 + 16 pad)
+#ifndef BL_LDS_ROW
+#define BL_LDS_ROW 80
+#endif
+constexpr int kLdsRow = BL_LDS_ROW;   // bytes per activation row in LDS (64 + 16 pad)
 constexpr int kStages = 3;
 
 __device__ __forceinline__ v4i expand_codes(uint32_t word) {
@@ -80,12 +83,11 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemvProblem p, const
     };
     const int op_row = lane & 31, op_g = lane >> 5;
     const int a_read = op_row * kLdsRow + op_g * 16;
-    auto lread = [&](int stage, v4i (&a)[2][MB]) {
+    // operands of one 32-k half step: MB registers quadruples
+    auto lread_half = [&](int stage, int ks, v4i (&a)[MB]) {
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb)
-                a[ks][mb] = *reinterpret_cast<const v4i*>(&lds[stage * kStageBytes + mb * 32 * kLdsRow + a_read + ks * 32]);
+        for (int mb = 0; mb < MB; ++mb)
+            a[mb] = *reinterpret_cast<const v4i*>(&lds[stage * kStageBytes + mb * 32 * kLdsRow + a_read + ks * 32]);
     };
     struct WTiles { uint4 v[NB]; };    // by value: registers
     const uint4* wp[NB];
@@ -107,52 +109,66 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemvProblem p, const
 #pragma unroll
             for (int r = 0; r < 16; ++r) c[i][j][r] = 0;
 
-    // prologue: stages 0 and 1 filled, operands of step 0 in registers, tile of step 2 in flight
+    // prologue: LDS stages 0 and 1 filled, first-half operands of step 0 in registers; activation tiles of
+    // steps 2..3 and weight tiles of steps 0..2 in flight
     lstore(0, gload(0));
     lstore(1, gload(1));
-    WTiles w_cur = wload(0), w_nxt = wload(1);
+    WTiles w_cur = wload(0), w1 = wload(1), w2 = wload(2);
+    Staged g0 = gload(2), g1 = gload(3);
     __syncthreads();
-    v4i a0[2][MB], a1[2][MB];
-    lread(0, a0);
-    Staged g = gload(2);
+    v4i a_lo0[MB], a_lo1[MB], a_hi[MB];
+    lread_half(0, 0, a_lo0);
 
-    // one K step: MFMAs on (a_use, w_cur) while the operands of the next step and later tiles are fetched
-    auto step = [&](int kc, v4i (&a_use)[2][MB], v4i (&a_load)[2][MB]) {
-        const WTiles w_nn = wload(kc + 2);
-        const int st = kc % kStages;
-        const int st1 = st + 1 == kStages ? 0 : st + 1;
-        const int st2 = st1 + 1 == kStages ? 0 : st1 + 1;
-        lread(st1, a_load);      // written one step ago, published by the barrier that ended that step
+    // One K step in two 32-k halves.  While the MFMAs of the first half run, the second half's operands are read
+    // from the current LDS stage; while the second half runs, the first-half operands of the NEXT step are read
+    // from the next stage (published by the barrier that ended the previous step).
+    int st = 0;
+    auto step = [&](int kc, v4i (&a_lo)[MB], v4i (&a_lo_next)[MB]) {
+        const int st1 = st == kStages - 1 ? 0 : st + 1;
+        const int st2 = st1 == kStages - 1 ? 0 : st1 + 1;
+        lstore(st2, g0);         // tile of step kc+2 (loaded two steps ago); stage st2 was last read two steps ago
+        lread_half(st, 1, a_hi);
+        g0 = g1;
+        g1 = gload(kc + 4);
+        const WTiles w_new = wload(kc + 3);
+        __builtin_amdgcn_sched_barrier(0);   // keep the fetches above the MFMAs they overlap with
 #pragma unroll
         for (int j = 0; j < NB; ++j) {
-            // after the swaps: [0] = rows 0-31, [1] = rows 32-63 of the tile; s01 covers k 0..31, s23 covers k 32..63
+            // after the swap: [0] = rows 0-31, [1] = rows 32-63 of the tile, k 0..31
             auto s01 = __builtin_amdgcn_permlane32_swap(w_cur.v[j].x, w_cur.v[j].y, false, false);
-            auto s23 = __builtin_amdgcn_permlane32_swap(w_cur.v[j].z, w_cur.v[j].w, false, false);
-            const uint32_t bw[2][2] = {{s01[0], s01[1]}, {s23[0], s23[1]}};
+            const v4i b0 = expand_codes(s01[0]), b1 = expand_codes(s01[1]);
 #pragma unroll
-            for (int ks = 0; ks < 2; ++ks) {
-                const v4i b0 = expand_codes(bw[ks][0]);
-                const v4i b1 = expand_codes(bw[ks][1]);
-#pragma unroll
-                for (int mb = 0; mb < MB; ++mb) {
-                    c[mb][2 * j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a_use[ks][mb], b0, c[mb][2 * j], 0, 0, 0);
-                    c[mb][2 * j + 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a_use[ks][mb], b1, c[mb][2 * j + 1], 0, 0, 0);
-                }
+            for (int mb = 0; mb < MB; ++mb) {
+                c[mb][2 * j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a_lo[mb], b0, c[mb][2 * j], 0, 0, 0);
+                c[mb][2 * j + 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a_lo[mb], b1, c[mb][2 * j + 1], 0, 0, 0);
             }
         }
-        lstore(st2, g);          // tile of step kc+2, loaded one step ago; stage st2 was last read two steps ago
-        g = gload(kc + 3);
+        __builtin_amdgcn_sched_barrier(0);
+        lread_half(st1, 0, a_lo_next);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+            auto s23 = __builtin_amdgcn_permlane32_swap(w_cur.v[j].z, w_cur.v[j].w, false, false);   // k 32..63
+            const v4i b0 = expand_codes(s23[0]), b1 = expand_codes(s23[1]);
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) {
+                c[mb][2 * j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a_hi[mb], b0, c[mb][2 * j], 0, 0, 0);
+                c[mb][2 * j + 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a_hi[mb], b1, c[mb][2 * j + 1], 0, 0, 0);
+            }
+        }
         __syncthreads();
-        w_cur = w_nxt;
-        w_nxt = w_nn;
+        w_cur = w1;
+        w1 = w2;
+        w2 = w_new;
+        st = st1;
     };
 
     int kc = 0;
     for (; kc + 1 < KC; kc += 2) {
-        step(kc, a0, a1);
-        step(kc + 1, a1, a0);
+        step(kc, a_lo0, a_lo1);
+        step(kc + 1, a_lo1, a_lo0);
     }
-    if (kc < KC) step(kc, a0, a1);
+    if (kc < KC) step(kc, a_lo0, a_lo1);
 
     // epilogue: register r of a 32x32 tile holds row 8*(r/4) + 4*(lane/32) + r%4, column lane%32
 #pragma unroll
