@@ -157,7 +157,6 @@ bl_status bl_gemv_batch(const bl_gemv_item* items, int32_t count, int64_t M, voi
         b.p[i].q_sum = it.q_sum_dev;
     }
     b.count = count;
-    bl::plan_decode(b);
     drop_stale_hip_error();
     return hip_status(bl::launch_decode(b, (int)M, false, static_cast<hipStream_t>(stream)));
 }
@@ -194,7 +193,6 @@ bl_status bl_decode_batch(const bl_decode_item* items, int32_t count, int64_t M,
     }
     if (bl::decode_lds_bytes((int)M, max_Kp, true) > (size_t)bl::kMaxDecodeLds) return BL_ERR_SHAPE;
     b.count = count;
-    bl::plan_decode(b);
     drop_stale_hip_error();
     return hip_status(bl::launch_decode(b, (int)M, true, static_cast<hipStream_t>(stream)));
 }
@@ -230,6 +228,11 @@ bl_status bl_set_tuning(const char* key, int32_t value) {
     if (strcmp(key, "gemv_waves") == 0) {
         if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8 && value != 16) return BL_ERR_SHAPE;
         bl::set_gemv_waves(value);
+        return BL_OK;
+    }
+    if (strcmp(key, "decode_stage") == 0) {
+        if (value < 0 || value > 1) return BL_ERR_SHAPE;
+        bl::set_decode_stage(value);
         return BL_OK;
     }
     if (strcmp(key, "gemm_mb") == 0) {

@@ -280,11 +280,20 @@ __device__ __forceinline__ v4i expand_codes(uint32_t word) {
     return r;
 }
 
+constexpr int kMaxStagedBytes = 64 * 1024;            // largest activation matrix the plain matrix-core kernel copies into LDS
+constexpr int kMfmaInFlightDirect = 4;                 // ... when it is prefetched from global memory with the tiles
+constexpr int kMfmaInFlightLds = 6;                    // weight tiles in flight when the A operand is in LDS
 constexpr int kMfmaRedBytes = kWaves * 16 * 32 * 4;   // per wave: 16 accumulator registers x 32 useful lanes
 
-template <int M, bool FUSED, bool XBF16>
-__global__ __launch_bounds__(kThreads) void decode_mfma_kernel(const DecodeBatch b) {
+// QMODE: where the int8 activations (the A operand) come from
+//   0 = straight from global memory, prefetched with the weight tiles (any size)
+//   1 = copied once per workgroup from global memory into LDS (when M*Kp fits)
+//   2 = quantized by the workgroup into LDS (fused form)
+template <int M, int QMODE, bool XBF16>
+__global__ __launch_bounds__(kThreads, 8) void decode_mfma_kernel(const DecodeBatch b) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    constexpr bool kLdsQ = QMODE != 0;
+    constexpr int U = kLdsQ ? kMfmaInFlightLds : kMfmaInFlightDirect;   // weight tiles in flight per wave
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
@@ -305,7 +314,7 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(const DecodeBatch
     const uint4* __restrict__ wp = p.packed + (int64_t)(active ? rb : 0) * KC * kWave + lane;
 
     int8_t* lds_q = reinterpret_cast<int8_t*>(smem);
-    int* red = reinterpret_cast<int*>(smem + (FUSED ? M * Kp : 0));
+    int* red = reinterpret_cast<int*>(smem + (kLdsQ ? M * Kp : 0));
     float* s_f = reinterpret_cast<float*>(red + kMfmaRedBytes / 4);
     int* s_i = reinterpret_cast<int*>(s_f + M * kWaves + M);
 
@@ -314,23 +323,44 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(const DecodeBatch
     const bool has_row = mrow < M;
     const int a_off = (has_row ? mrow : 0) * Kp + piece * 16;   // byte offset inside the activation matrix
 
-    uint4 w[kInFlight];
-    v4i av[kInFlight];
+    uint4 w[U];
+    v4i av[kLdsQ ? 1 : U];
     auto load_batch = [&](int kc0) {
 #pragma unroll
-        for (int u = 0; u < kInFlight; ++u) {
+        for (int u = 0; u < U; ++u) {
             const int k = kc0 + u * G;
             const int kk = k < KC ? k : KC - 1;   // clamped: always a valid tile
             w[u] = wp[(int64_t)kk * kWave];
-            if constexpr (!FUSED) {
+            if constexpr (!kLdsQ) {
                 av[u] = v4i{0, 0, 0, 0};
                 if (has_row) av[u] = *reinterpret_cast<const v4i*>(reinterpret_cast<const int8_t*>(p.q) + a_off + kk * kTileK);
             }
         }
     };
-    load_batch(ks);   // waves without a row block load (valid) block 0: no branch, exact wait counts
 
-    if constexpr (FUSED) {
+    if constexpr (QMODE == 1) {
+        // activations first (loads retire in order: waiting for them leaves the weight tiles in flight)
+        const uint4* src = reinterpret_cast<const uint4*>(p.q);
+        const int n16 = M * Kp / 16;
+        constexpr int kMaxCopy = kMaxStagedBytes / 16 / kThreads;   // 16-byte vectors per thread
+        uint4 stage[kMaxCopy];
+#pragma unroll
+        for (int i = 0; i < kMaxCopy; ++i) {
+            const int idx = tid + i * kThreads;
+            stage[i] = src[idx < n16 ? idx : 0];
+        }
+        load_batch(ks);
+#pragma unroll
+        for (int i = 0; i < kMaxCopy; ++i) {
+            const int idx = tid + i * kThreads;
+            if (idx < n16) reinterpret_cast<uint4*>(lds_q)[idx] = stage[i];
+        }
+        __syncthreads();
+    } else {
+        load_batch(ks);   // waves without a row block load (valid) block 0: no branch, exact wait counts
+    }
+
+    if constexpr (QMODE == 2) {
         if (p.x_flags & 2) quantize_rows_to_lds<M, XBF16, true>(p, lds_q, s_f, s_i, tid, lane, wave);
         else quantize_rows_to_lds<M, XBF16, false>(p, lds_q, s_f, s_i, tid, lane, wave);
         if (wg == 0 && p.q_out) {
@@ -346,11 +376,11 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(const DecodeBatch
     if (active) {
         for (int kc0 = ks;;) {
 #pragma unroll
-            for (int u = 0; u < kInFlight; ++u) {
+            for (int u = 0; u < U; ++u) {
                 const int k = kc0 + u * G;
                 if (k < KC) {
                     v4i a_op;
-                    if constexpr (FUSED) {
+                    if constexpr (kLdsQ) {
                         a_op = v4i{0, 0, 0, 0};
                         if (has_row) a_op = *reinterpret_cast<const v4i*>(lds_q + a_off + k * kTileK);
                     } else {
@@ -363,7 +393,7 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(const DecodeBatch
                         acc[g] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a_op, expand_codes(t[g]), acc[g], 0, 0, 0);
                 }
             }
-            kc0 += G * kInFlight;
+            kc0 += G * U;
             if (kc0 >= KC) break;
             load_batch(kc0);
         }
@@ -386,7 +416,7 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(const DecodeBatch
             if (m < M && n < p.N) {
                 int qsum;
                 float scale;
-                if constexpr (FUSED) {
+                if constexpr (QMODE == 2) {
                     qsum = 0;
 #pragma unroll
                     for (int w16 = 0; w16 < kWaves; ++w16) qsum += s_i[m * kWaves + w16];
@@ -402,7 +432,7 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(const DecodeBatch
             }
         }
     }
-    if constexpr (FUSED) {
+    if constexpr (QMODE == 2) {
         if (wg == 0 && tid < M) {   // optional copy-out of the quantizer's scalars
             int qsum = 0;
             for (int w16 = 0; w16 < kWaves; ++w16) qsum += s_i[tid * kWaves + w16];
@@ -412,39 +442,47 @@ __global__ __launch_bounds__(kThreads) void decode_mfma_kernel(const DecodeBatch
     }
 }
 
-template <int M, bool FUSED, bool MFMA, bool XBF16>
-hipError_t launch_one(const DecodeBatch& b, size_t lds_bytes, hipStream_t s) {
-    static bool attr_set = false;   // raise the dynamic-LDS ceiling once per kernel (host-side setting only)
-    const void* fn = MFMA ? reinterpret_cast<const void*>(&decode_mfma_kernel<M, FUSED, XBF16>)
-                          : reinterpret_cast<const void*>(&decode_kernel<M, FUSED, XBF16>);
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDecodeLds);
+template <typename Kernel>
+hipError_t launch_kernel(Kernel kernel, bool& attr_set, const DecodeBatch& b, size_t lds_bytes, hipStream_t s) {
+    if (!attr_set) {   // raise the dynamic-LDS ceiling once per kernel (a host-side setting, no allocation)
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDecodeLds);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    const dim3 grid((unsigned)b.total_wgs), block(kThreads);
-    if constexpr (MFMA) decode_mfma_kernel<M, FUSED, XBF16><<<grid, block, lds_bytes, s>>>(b);
-    else decode_kernel<M, FUSED, XBF16><<<grid, block, lds_bytes, s>>>(b);
+    kernel<<<dim3((unsigned)b.total_wgs), dim3(kThreads), lds_bytes, s>>>(b);
     return hipGetLastError();
 }
 
-template <bool FUSED, bool MFMA, bool XBF16>
+// KIND: 0 = dot-product kernel, plain; 1 = dot-product kernel, fused; 2..4 = matrix-core kernel with QMODE 0..2
+template <int M, int KIND, bool XBF16>
+hipError_t launch_one(const DecodeBatch& b, size_t lds_bytes, hipStream_t s) {
+    static bool attr_set = false;
+    if constexpr (KIND == 0) return launch_kernel(&decode_kernel<M, false, true>, attr_set, b, lds_bytes, s);
+    else if constexpr (KIND == 1) return launch_kernel(&decode_kernel<M, true, XBF16>, attr_set, b, lds_bytes, s);
+    else if constexpr (KIND == 2) return launch_kernel(&decode_mfma_kernel<M, 0, true>, attr_set, b, lds_bytes, s);
+    else if constexpr (KIND == 3) return launch_kernel(&decode_mfma_kernel<M, 1, true>, attr_set, b, lds_bytes, s);
+    else return launch_kernel(&decode_mfma_kernel<M, 2, XBF16>, attr_set, b, lds_bytes, s);
+}
+
+template <int KIND, bool XBF16>
 hipError_t launch_m(const DecodeBatch& b, int M, size_t lds, hipStream_t s) {
     switch (M) {
-        case 1: return launch_one<1, FUSED, MFMA, XBF16>(b, lds, s);
-        case 2: return launch_one<2, FUSED, MFMA, XBF16>(b, lds, s);
-        case 3: return launch_one<3, FUSED, MFMA, XBF16>(b, lds, s);
-        case 4: return launch_one<4, FUSED, MFMA, XBF16>(b, lds, s);
-        case 5: return launch_one<5, FUSED, MFMA, XBF16>(b, lds, s);
-        case 6: return launch_one<6, FUSED, MFMA, XBF16>(b, lds, s);
-        case 7: return launch_one<7, FUSED, MFMA, XBF16>(b, lds, s);
-        case 8: return launch_one<8, FUSED, MFMA, XBF16>(b, lds, s);
+        case 1: return launch_one<1, KIND, XBF16>(b, lds, s);
+        case 2: return launch_one<2, KIND, XBF16>(b, lds, s);
+        case 3: return launch_one<3, KIND, XBF16>(b, lds, s);
+        case 4: return launch_one<4, KIND, XBF16>(b, lds, s);
+        case 5: return launch_one<5, KIND, XBF16>(b, lds, s);
+        case 6: return launch_one<6, KIND, XBF16>(b, lds, s);
+        case 7: return launch_one<7, KIND, XBF16>(b, lds, s);
+        case 8: return launch_one<8, KIND, XBF16>(b, lds, s);
     }
     return hipErrorInvalidValue;
 }
 
 int g_force_waves = 0;
 int g_force_path = 0;   // 0 auto, 1 dot4, 2 mfma
+int g_force_stage = 0;  // 1: never stage the activations in LDS (matrix-core kernel, plain form)
 
 bool use_mfma(int M) { return g_force_path ? g_force_path == 2 : M >= 2; }
 
@@ -452,19 +490,24 @@ bool use_mfma(int M) { return g_force_path ? g_force_path == 2 : M >= 2; }
 
 void set_gemv_waves(int waves) { g_force_waves = waves; }
 void set_decode_path(int path) { g_force_path = path; }
+void set_decode_stage(int v) { g_force_stage = v; }
 
-size_t decode_lds_bytes(int M, int64_t max_Kp, bool fused) {
+// LDS bytes of one launch; q_in_lds: the quantized activations live in LDS (fused, or staged copy)
+static size_t lds_bytes_for(int M, int64_t max_Kp, bool q_in_lds) {
     const size_t red = use_mfma(M) ? (size_t)kMfmaRedBytes : (size_t)kWaves * M * kWave * 4;
-    return (size_t)(fused ? M * max_Kp : 0) + red + (size_t)(2 * M * kWaves + M) * 4;
+    return (size_t)(q_in_lds ? M * max_Kp : 0) + red + (size_t)(2 * M * kWaves + M) * 4;
 }
 
-// Fill in the launch geometry: waves per row block for each problem and the workgroup prefix.
-void plan_decode(DecodeBatch& b) {
+size_t decode_lds_bytes(int M, int64_t max_Kp, bool fused) { return lds_bytes_for(M, max_Kp, fused); }
+
+// Fill in the launch geometry: waves per row block for each problem (so that a wave gets about one
+// batch of `tiles_per_wave` tiles) and the workgroup prefix.
+static void plan_decode(DecodeBatch& b, int tiles_per_wave) {
     int total = 0;
     for (int i = 0; i < b.count; ++i) {
         DecodeProblem& p = b.p[i];
         int g = 1, lg = 0;
-        while (g < kWaves && g * kInFlight < p.KC) { g *= 2; ++lg; }   // about 8 tiles per wave
+        while (g < kWaves && g * tiles_per_wave < p.KC) { g *= 2; ++lg; }
         if (g_force_waves) {
             lg = 0;
             while ((1 << lg) < g_force_waves) ++lg;
@@ -477,18 +520,31 @@ void plan_decode(DecodeBatch& b) {
     b.total_wgs = total;
 }
 
-hipError_t launch_decode(const DecodeBatch& b, int M, bool fused, hipStream_t s) {
+hipError_t launch_decode(const DecodeBatch& batch, int M, bool fused, hipStream_t s) {
+    DecodeBatch b = batch;
     int64_t max_Kp = 0;
     for (int i = 0; i < b.count; ++i) max_Kp = (int64_t)b.p[i].KC * kTileK > max_Kp ? (int64_t)b.p[i].KC * kTileK : max_Kp;
-    const size_t lds = decode_lds_bytes(M, max_Kp, fused);
-    if (lds > (size_t)kMaxDecodeLds) return hipErrorInvalidValue;
     const bool bf16 = b.p[0].x_flags & 1;   // the fused form requires one activation dtype per launch
     if (use_mfma(M)) {
-        if (!fused) return launch_m<false, true, true>(b, M, lds, s);
-        return bf16 ? launch_m<true, true, true>(b, M, lds, s) : launch_m<true, true, false>(b, M, lds, s);
+        if (fused) {
+            const size_t lds = lds_bytes_for(M, max_Kp, true);
+            if (lds > (size_t)kMaxDecodeLds) return hipErrorInvalidValue;
+            plan_decode(b, kMfmaInFlightLds);
+            return bf16 ? launch_m<4, true>(b, M, lds, s) : launch_m<4, false>(b, M, lds, s);
+        }
+        // plain form: stage the activations in LDS when they fit, else fetch them per tile from global memory
+        if ((size_t)M * max_Kp <= (size_t)kMaxStagedBytes && g_force_stage != 1) {
+            plan_decode(b, kMfmaInFlightLds);
+            return launch_m<3, true>(b, M, lds_bytes_for(M, max_Kp, true), s);
+        }
+        plan_decode(b, kMfmaInFlightDirect);
+        return launch_m<2, true>(b, M, lds_bytes_for(M, max_Kp, false), s);
     }
-    if (!fused) return launch_m<false, false, true>(b, M, lds, s);
-    return bf16 ? launch_m<true, false, true>(b, M, lds, s) : launch_m<true, false, false>(b, M, lds, s);
+    const size_t lds = lds_bytes_for(M, max_Kp, fused);
+    if (lds > (size_t)kMaxDecodeLds) return hipErrorInvalidValue;
+    plan_decode(b, kInFlight);
+    if (!fused) return launch_m<0, true>(b, M, lds, s);
+    return bf16 ? launch_m<1, true>(b, M, lds, s) : launch_m<1, false>(b, M, lds, s);
 }
 
 }  // namespace bl

@@ -61,7 +61,6 @@ hipError_t launch_unpack(const uint32_t* packed, int64_t N, int64_t K, int64_t N
                          hipStream_t s);
 hipError_t launch_quant(const void* x, int is_bf16, int64_t M, int64_t K, int64_t ldx, int64_t Kp, int8_t* q,
                         float* a_scale, int32_t* q_sum, hipStream_t s);
-void plan_decode(DecodeBatch& b);
 size_t decode_lds_bytes(int M, int64_t max_Kp, bool fused);
 hipError_t launch_decode(const DecodeBatch& b, int M, bool fused, hipStream_t s);
 hipError_t launch_gemm(const GemvProblem& p, int64_t M, hipStream_t s);
@@ -69,6 +68,7 @@ hipError_t launch_gemm(const GemvProblem& p, int64_t M, hipStream_t s);
 // Launch-shape overrides for experiments (0 = choose automatically).
 void set_gemv_waves(int waves);
 void set_gemm_mb(int mb);         // 0 automatic, 2 = 64-token tiles, 4 = 128-token tiles
+void set_decode_stage(int v);     // 1: the matrix-core decode kernel never stages activations in LDS
 void set_decode_path(int path);   // 0 automatic, 1 dot-product kernel, 2 matrix-core kernel
 
 // ---- device helpers -------------------------------------------------------------------

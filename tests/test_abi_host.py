@@ -111,6 +111,8 @@ def test_argument_validation_happens_before_any_launch():
     assert _st(B.bl_set_tuning, "gemv_waves", 3) == B.BL_ERR_SHAPE
     B.bl_set_tuning("gemv_waves", 0)
     assert _st(B.bl_set_tuning, "decode_path", 3) == B.BL_ERR_SHAPE
+    assert _st(B.bl_set_tuning, "decode_stage", 2) == B.BL_ERR_SHAPE
+    B.bl_set_tuning("decode_stage", 0)
     assert _st(B.bl_set_tuning, "gemm_mb", 7) == B.BL_ERR_SHAPE
     B.bl_set_tuning("gemm_mb", 0)
     B.bl_set_tuning("decode_path", 0)

@@ -307,12 +307,21 @@ def test_fused_decode_parity_all_m(dev, ops, decode_path, M, path):
     _assert_fused(ops, dev, [_problem(1500 + M, M, 1536, 320, outl=0.01)], M)
 
 
+@pytest.mark.parametrize("stage", [0, 1])
 @pytest.mark.parametrize("M", [2, 8])
 @pytest.mark.parametrize("N,K", [(70, 100), (200, 1000), (4096, 11008), (129, 64 * 37)])
-def test_matrix_core_decode_shapes(dev, ops, N, K, M):
-    prob = _problem(N * 19 + K + M, M, K, N, p_zero=0.4, outl=0.01)
-    _assert_product(ops, dev, "gemv", *prob)
-    _assert_fused(ops, dev, [prob], M)
+def test_matrix_core_decode_shapes(dev, ops, N, K, M, stage):
+    # stage 0: activations copied into LDS when they fit (M*Kp <= 64 KiB), else fetched per tile;
+    # stage 1: always fetched per tile
+    from paper_2410_16144_amd import binding
+    binding.bl_set_tuning("decode_stage", stage)
+    try:
+        prob = _problem(N * 19 + K + M, M, K, N, p_zero=0.4, outl=0.01)
+        _assert_product(ops, dev, "gemv", *prob)
+        if stage == 0:
+            _assert_fused(ops, dev, [prob], M)
+    finally:
+        binding.bl_set_tuning("decode_stage", 0)
 
 
 @pytest.mark.parametrize("bf16", [True, False])
