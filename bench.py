@@ -144,7 +144,7 @@ def extra_copy(torch):
     return {"bytes_read": n, "bytes_written": n, "us": round(us, 1), "GBps_read_plus_write": round(2 * n / us / 1e3, 1)}
 
 
-def extra_prefill(torch, M, K, N, iters=20):
+def extra_prefill(torch, M, K, N, use_graph=True, iters=20):
     from paper_2410_16144_amd import ops, synth
     dev = torch.device("cuda:0")
     w = synth.ternary_weights_device(4000 + M + K, N, K, dev)
@@ -157,12 +157,13 @@ def extra_prefill(torch, M, K, N, iters=20):
     out = torch.empty((M, N), dtype=torch.float32, device=dev)
     for _ in range(3):
         ops.gemm(pw, qa, out)
-    ms, _ = timed(torch, lambda: [ops.gemm(pw, qa, out) for _ in range(iters)])
+    ms, _, mode = run_steps(torch, [lambda: ops.gemm(pw, qa, out)], iters, use_graph)
     us = ms * 1e3 / iters
     tops = 2.0 * M * K * N / us / 1e6
-    msq, _ = timed(torch, lambda: [ops.quant_act(x, qa) for _ in range(iters)])
+    msq, _, _ = run_steps(torch, [lambda: ops.quant_act(x, qa)], iters, use_graph)
     usq = msq * 1e3 / iters
     return {"workload": "prefill M=%d K=%d N=%d" % (M, K, N), "gemm_us": round(us, 2), "quant_act_us": round(usq, 2),
+            "launch": mode,
             "roofline": {"bound": "mfma", "achieved": round(tops / 1e3, 4), "peak": INT8_PEAK_TOPS / 1e3,
                          "unit": "POP/s", "frac": round(tops / INT8_PEAK_TOPS, 4), "ops_per_launch": 2 * M * K * N},
             "tops_including_quant_act": round(2.0 * M * K * N / (us + usq) / 1e6, 1)}
@@ -237,7 +238,7 @@ def main():
 
     if args.only:
         sect = {"copy": lambda: extra_copy(torch),
-                "prefill": lambda: [extra_prefill(torch, m, k, n) for m in (512, 2048)
+                "prefill": lambda: [extra_prefill(torch, m, k, n, use_graph) for m in (512, 2048)
                                     for (k, n) in ((4096, 11008), (11008, 4096))],
                 "decode7b": lambda: [extra_decode_shape(torch, "7B-shape", 4096, 11008, m, 24, 480, use_graph)
                                      for m in (1, 4, 8)],
@@ -308,7 +309,7 @@ def main():
         if args.full_100b:
             extra["decode_100b_token"] = extra_full_100b(torch, use_graph)
             torch.cuda.empty_cache()
-        extra["prefill"] = [extra_prefill(torch, m, k, n) for m in (512, 2048)
+        extra["prefill"] = [extra_prefill(torch, m, k, n, use_graph) for m in (512, 2048)
                             for (k, n) in ((4096, 11008), (11008, 4096))]
         result["extra"] = extra
 
