@@ -76,8 +76,14 @@ def run_steps(torch, step_fns, count, use_graph):
         with torch.cuda.graph(g, stream=side):
             eager()
     torch.cuda.synchronize()
-    g.replay()                      # first replay pays one-time upload costs
-    torch.cuda.synchronize()
+    # untimed replays: the first pays one-time upload costs, and the GPU needs some tens of milliseconds of
+    # sustained work to reach its steady clocks (a 2 ms burst of the prefill kernel measures 25 % slower)
+    t0 = time.perf_counter()
+    for _ in range(50):
+        g.replay()
+        torch.cuda.synchronize()
+        if time.perf_counter() - t0 > 0.05:
+            break
     ms, wall = timed(torch, g.replay)
     del g
     return ms, wall, "hip-graph"
@@ -144,7 +150,7 @@ def extra_copy(torch):
     return {"bytes_read": n, "bytes_written": n, "us": round(us, 1), "GBps_read_plus_write": round(2 * n / us / 1e3, 1)}
 
 
-def extra_prefill(torch, M, K, N, use_graph=True, iters=20):
+def extra_prefill(torch, M, K, N, use_graph=True, iters=100):
     from paper_2410_16144_amd import ops, synth
     dev = torch.device("cuda:0")
     w = synth.ternary_weights_device(4000 + M + K, N, K, dev)

@@ -49,6 +49,8 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemvProblem p, const
     constexpr int kStageBytes = BM * kLdsRow;
     constexpr int NLD = (BM + 63) / 64;   // 16-byte pieces each thread moves per step (256 threads x 16 B = 64 rows)
     __shared__ __attribute__((aligned(16))) uint8_t lds[kStages * kStageBytes];
+    __shared__ float s_scale[BM];   // w_scale * a_scale[m] of the workgroup's tokens (read in the epilogue)
+    __shared__ int s_qsum[BM];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -109,6 +111,11 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemvProblem p, const
 #pragma unroll
             for (int r = 0; r < 16; ++r) c[i][j][r] = 0;
 
+    if (tid < BM) {   // published by the prologue's barrier
+        const int m = min(m0 + tid, M - 1);
+        s_scale[tid] = p.w_scale * p.a_scale[m];
+        s_qsum[tid] = p.q_sum[m];
+    }
     // prologue: LDS stages 0 and 1 filled, first-half operands of step 0 in registers; activation tiles of
     // steps 2..3 and weight tiles of steps 0..2 in flight
     lstore(0, gload(0));
@@ -175,10 +182,11 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemvProblem p, const
     for (int mb = 0; mb < MB; ++mb) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            const int m = m0 + mb * 32 + 8 * (r >> 2) + 4 * op_g + (r & 3);
+            const int ml = mb * 32 + 8 * (r >> 2) + 4 * op_g + (r & 3);
+            const int m = m0 + ml;
             if (m < M) {
-                const int qsum = p.q_sum[m];
-                const float sc = p.w_scale * p.a_scale[m];
+                const int qsum = s_qsum[ml];
+                const float sc = s_scale[ml];
 #pragma unroll
                 for (int nb = 0; nb < 2 * NB; ++nb) {
                     const int n = rb0 * kTileN + nb * 32 + op_row;   // n >= N covers padding rows and clamped row blocks
@@ -201,8 +209,10 @@ void set_gemm_mb(int mb) { g_force_mb = mb; }
 
 hipError_t launch_gemm(const GemvProblem& p, int64_t M, hipStream_t s) {
     // wave tile = (32*MB) tokens x (64*NB) weight rows; workgroup = 4 waves along N
-    // 64-token tiles when that still gives every CU at least two workgroups, else 32-token tiles
-    int mb = ((M + 63) / 64) * ((p.row_blocks + kWavesN - 1) / kWavesN) >= 512 ? 2 : 1, nb = 1;
+    // 64 x 128 wave tiles (half the LDS traffic per MFMA) when the grid still gives every CU two workgroups,
+    // else 64 x 64
+    const int64_t tiles_m = (M + 63) / 64;
+    int mb = 2, nb = tiles_m * ((p.row_blocks + 2 * kWavesN - 1) / (2 * kWavesN)) >= 512 ? 2 : 1;
     if (g_force_mb) { mb = g_force_mb / 10; nb = g_force_mb % 10; }
     const int64_t gx = (p.row_blocks + kWavesN * nb - 1) / (kWavesN * nb);
     const int64_t gy = (M + 32 * mb - 1) / (32 * mb);
