@@ -55,6 +55,8 @@ typedef enum { BL_F32 = 0, BL_BF16 = 1 } bl_dtype;
 #define BL_MAX_GEMV_M 8
 #define BL_MAX_BATCH 8
 #define BL_MAX_GEMM_M 4194304
+#define BL_MAX_SPLIT_WGS 2048   /* most workgroups of a work-balanced decode launch     */
+#define BL_WORKSPACE_BYTES (BL_MAX_SPLIT_WGS * 64 * 8)   /* 1 MiB, see bl_gemv_batch   */
 
 /*
  * Host-side description of one packed ternary matrix.  Plain data; copy it,
@@ -169,9 +171,22 @@ typedef struct {
  * layer (Appendix A shapes), which share their input.  Each item is
  * validated like a bl_gemv call; results are identical to `count` separate
  * calls.  `items` is a host array, read during the call.
- * Extra error: BL_ERR_COUNT.
+ *
+ * `workspace_dev` (may be NULL): BL_WORKSPACE_BYTES of device memory, 256-byte
+ * aligned, owned by the caller, ALL ZERO before its first use.  With it, a
+ * one-token launch of medium size is work-balanced: every workgroup streams
+ * the same number of weight tiles, and a 64-row block whose tiles fall to two
+ * or more workgroups is finished through the workspace (exact integer partial
+ * sums, so results do not change by a bit).  Every launch leaves the workspace
+ * all zero again, so one buffer serves any number of successive launches on a
+ * stream; launches that may run at the same time (different streams) must not
+ * share one, and a buffer whose launch was aborted must be zeroed again.
+ * Without it, or when balancing would not pay (M > 1, tiny or very large
+ * launches), whole row blocks are dealt to workgroups and nothing is shared.
+ * Extra errors: BL_ERR_COUNT; BL_ERR_ALIGN for a misaligned workspace.
  */
-bl_status bl_gemv_batch(const bl_gemv_item *items, int32_t count, int64_t M, void *stream);
+bl_status bl_gemv_batch(const bl_gemv_item *items, int32_t count, int64_t M, void *workspace_dev,
+                        void *stream);
 
 /* One problem of the fused decode launch. */
 typedef struct {
@@ -195,14 +210,15 @@ typedef struct {
  * and the separate quantization launch disappears.  Results (q, a_scale,
  * q_sum, acc, out) are bit-identical to the two-call sequence.
  * All items of one launch must have the same activation dtype (else
- * BL_ERR_DTYPE).
+ * BL_ERR_DTYPE).  `workspace_dev`: as for bl_gemv_batch (may be NULL).
  * Limit: M * Kp (+ 5 KiB per token) must fit the kernel's 128 KiB of
  * on-chip memory, else BL_ERR_SHAPE; use the two-call sequence then.
  * Pointer alignment as for bl_quant_act / bl_gemv.
  * Errors: BL_ERR_NULL, BL_ERR_COUNT, BL_ERR_M_RANGE, BL_ERR_DTYPE,
  *         BL_ERR_LAYOUT, BL_ERR_SHAPE, BL_ERR_BUF_SMALL, BL_ERR_ALIGN, BL_ERR_HIP.
  */
-bl_status bl_decode_batch(const bl_decode_item *items, int32_t count, int64_t M, void *stream);
+bl_status bl_decode_batch(const bl_decode_item *items, int32_t count, int64_t M, void *workspace_dev,
+                          void *stream);
 
 /*
  * Prefill product, 1 <= M <= BL_MAX_GEMM_M: the same mathematics as bl_gemv,
@@ -216,13 +232,19 @@ bl_status bl_gemm(const void *packed_dev, const bl_packed_desc *d, const int8_t 
 /*
  * Launch-shape override for experiments and sweeps; process-wide, not thread-safe, never
  * changes results.  Keys: "gemv_waves" = waves of the decode kernel that share one
- * 64-row block (1, 2, 4, 8, 16; 0 = automatic); "decode_path" = 0 automatic
+ * 64-row block (1, 2, 4, 8, 16; 0 = automatic); "decode_split" = work-balanced one-token launches: -1 never,
+ * 0 automatic (by launch size), n = 1..8 always with n workgroups per compute unit when a
+ * workspace is given and the launch has at least 32 n tiles per compute unit; "decode_path" = 0 automatic
  * (dot-product kernel for M = 1, matrix-core kernel for M >= 2), 1 = always the
  * dot-product kernel, 2 = always the matrix-core kernel; "decode_stage" = 1 keeps the matrix-core kernel
  * from staging the quantized activations in on-chip memory (0 = stage when they fit); "gemm_mb" = wave tile of the prefill kernel as
  * 10*MB + NB, i.e. (32*MB) tokens x (64*NB) weight rows: 11, 12, 21, 22, 41 (0 = automatic).  Errors: BL_ERR_NULL, BL_ERR_SHAPE (unknown key/value).
  */
 bl_status bl_set_tuning(const char *key, int32_t value);
+
+/* Host-side counters for tests and tools.  Keys: "split_launches" = decode launches so far
+ * that took the work-balanced form.  Unknown key or NULL: -1. */
+int64_t bl_get_stat(const char *key);
 
 /* Static, never-NULL description of a status code. */
 const char *bl_status_str(bl_status s);

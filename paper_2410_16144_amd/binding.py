@@ -21,12 +21,14 @@ BL_TILE_K = 64
 BL_MAX_K = 1048576
 BL_MAX_GEMV_M = 8
 BL_MAX_BATCH = 8
+BL_MAX_SPLIT_WGS = 2048
+BL_WORKSPACE_BYTES = BL_MAX_SPLIT_WGS * 64 * 8
 BL_MAX_GEMM_M = 4194304
 
 # every symbol include/bitlinear.h declares
 DECLARED_SYMBOLS = (
     "bl_padded_k", "bl_padded_n", "bl_packed_desc_init", "bl_pack_ternary", "bl_unpack_ternary",
-    "bl_quant_act", "bl_gemv", "bl_gemv_batch", "bl_decode_batch", "bl_gemm", "bl_set_tuning", "bl_status_str", "bl_last_hip_error", "bl_version",
+    "bl_quant_act", "bl_gemv", "bl_gemv_batch", "bl_decode_batch", "bl_gemm", "bl_set_tuning", "bl_get_stat", "bl_status_str", "bl_last_hip_error", "bl_version",
 )
 
 
@@ -88,10 +90,12 @@ def lib():
     l.bl_unpack_ternary.argtypes = [vp, dp, vp, vp]
     l.bl_quant_act.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, vp, vp, vp]
     l.bl_gemv.argtypes = [vp, dp, vp, vp, vp, i64, vp, vp, vp]
-    l.bl_gemv_batch.argtypes = [ctypes.POINTER(GemvItem), i32, i64, vp]
-    l.bl_decode_batch.argtypes = [ctypes.POINTER(DecodeItem), i32, i64, vp]
+    l.bl_gemv_batch.argtypes = [ctypes.POINTER(GemvItem), i32, i64, vp, vp]
+    l.bl_decode_batch.argtypes = [ctypes.POINTER(DecodeItem), i32, i64, vp, vp]
     l.bl_gemm.argtypes = [vp, dp, vp, vp, vp, i64, vp, vp, vp]
     l.bl_set_tuning.argtypes = [ctypes.c_char_p, i32]
+    l.bl_get_stat.argtypes = [ctypes.c_char_p]
+    l.bl_get_stat.restype = i64
     l.bl_status_str.argtypes = [ctypes.c_int]
     l.bl_status_str.restype = ctypes.c_char_p
     l.bl_version.restype = ctypes.c_char_p
@@ -161,11 +165,11 @@ def make_gemv_items(items):
     return arr
 
 
-def bl_gemv_batch(items, M: int, stream: int = 0):
+def bl_gemv_batch(items, M: int, workspace_dev: int = 0, stream: int = 0):
     """items: a ctypes GemvItem array from make_gemv_items (or an iterable of tuples)."""
     if not isinstance(items, ctypes.Array):
         items = make_gemv_items(items)
-    _check(lib().bl_gemv_batch(items, len(items), M, stream or None), "bl_gemv_batch")
+    _check(lib().bl_gemv_batch(items, len(items), M, workspace_dev or None, stream or None), "bl_gemv_batch")
 
 
 def make_decode_items(items):
@@ -179,11 +183,11 @@ def make_decode_items(items):
     return arr
 
 
-def bl_decode_batch(items, M: int, stream: int = 0):
+def bl_decode_batch(items, M: int, workspace_dev: int = 0, stream: int = 0):
     """items: a ctypes DecodeItem array from make_decode_items (or an iterable of tuples)."""
     if not isinstance(items, ctypes.Array):
         items = make_decode_items(items)
-    _check(lib().bl_decode_batch(items, len(items), M, stream or None), "bl_decode_batch")
+    _check(lib().bl_decode_batch(items, len(items), M, workspace_dev or None, stream or None), "bl_decode_batch")
 
 
 def bl_gemm(packed_dev: int, desc: PackedDesc, q_dev: int, a_scale_dev: int, q_sum_dev: int, M: int,
@@ -194,3 +198,7 @@ def bl_gemm(packed_dev: int, desc: PackedDesc, q_dev: int, a_scale_dev: int, q_s
 
 def bl_set_tuning(key: str, value: int):
     _check(lib().bl_set_tuning(key.encode(), int(value)), "bl_set_tuning")
+
+
+def bl_get_stat(key: str) -> int:
+    return int(lib().bl_get_stat(key.encode()))

@@ -123,7 +123,7 @@ bl_status bl_quant_act(const void* x_dev, bl_dtype dt, int64_t M, int64_t K, int
 bl_status bl_gemv(const void* packed_dev, const bl_packed_desc* d, const int8_t* q_dev, const float* a_scale_dev,
                   const int32_t* q_sum_dev, int64_t M, float* out_dev, int32_t* acc_dev, void* stream) {
     bl_gemv_item it = {packed_dev, d, q_dev, a_scale_dev, q_sum_dev, out_dev, acc_dev};
-    return bl_gemv_batch(&it, 1, M, stream);
+    return bl_gemv_batch(&it, 1, M, nullptr, stream);
 }
 
 static bl::DecodeProblem make_decode_problem(const void* packed, const bl_packed_desc* d, float* out, int32_t* acc) {
@@ -140,12 +140,14 @@ static bl::DecodeProblem make_decode_problem(const void* packed, const bl_packed
     return p;
 }
 
-bl_status bl_gemv_batch(const bl_gemv_item* items, int32_t count, int64_t M, void* stream) {
+bl_status bl_gemv_batch(const bl_gemv_item* items, int32_t count, int64_t M, void* workspace_dev, void* stream) {
     if (!items) return BL_ERR_NULL;
     if (count < 1 || count > BL_MAX_BATCH) return BL_ERR_COUNT;
     if (M < 1 || M > BL_MAX_GEMV_M) return BL_ERR_M_RANGE;
+    if (workspace_dev && !aligned(workspace_dev, 256)) return BL_ERR_ALIGN;
     bl::DecodeBatch b;
     memset(&b, 0, sizeof b);
+    b.ws = static_cast<unsigned long long*>(workspace_dev);
     for (int i = 0; i < count; ++i) {
         const bl_gemv_item& it = items[i];
         bl_status s = check_product_args(it.packed_dev, it.desc, it.q_dev, it.a_scale_dev, it.q_sum_dev, M,
@@ -161,12 +163,14 @@ bl_status bl_gemv_batch(const bl_gemv_item* items, int32_t count, int64_t M, voi
     return hip_status(bl::launch_decode(b, (int)M, false, static_cast<hipStream_t>(stream)));
 }
 
-bl_status bl_decode_batch(const bl_decode_item* items, int32_t count, int64_t M, void* stream) {
+bl_status bl_decode_batch(const bl_decode_item* items, int32_t count, int64_t M, void* workspace_dev, void* stream) {
     if (!items) return BL_ERR_NULL;
     if (count < 1 || count > BL_MAX_BATCH) return BL_ERR_COUNT;
     if (M < 1 || M > BL_MAX_GEMV_M) return BL_ERR_M_RANGE;
+    if (workspace_dev && !aligned(workspace_dev, 256)) return BL_ERR_ALIGN;
     bl::DecodeBatch b;
     memset(&b, 0, sizeof b);
+    b.ws = static_cast<unsigned long long*>(workspace_dev);
     int64_t max_Kp = 0;
     for (int i = 0; i < count; ++i) {
         const bl_decode_item& it = items[i];
@@ -240,12 +244,22 @@ bl_status bl_set_tuning(const char* key, int32_t value) {
         bl::set_gemm_mb(value);
         return BL_OK;
     }
+    if (strcmp(key, "decode_split") == 0) {
+        if (value < -1 || value > 8) return BL_ERR_SHAPE;
+        bl::set_decode_split(value);
+        return BL_OK;
+    }
     if (strcmp(key, "decode_path") == 0) {
         if (value < 0 || value > 2) return BL_ERR_SHAPE;
         bl::set_decode_path(value);
         return BL_OK;
     }
     return BL_ERR_SHAPE;
+}
+
+int64_t bl_get_stat(const char* key) {
+    if (key && strcmp(key, "split_launches") == 0) return bl::split_launches();
+    return -1;
 }
 
 const char* bl_last_hip_error(void) { return hipGetErrorString(t_last_hip_error); }

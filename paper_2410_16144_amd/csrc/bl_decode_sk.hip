@@ -1,0 +1,272 @@
+// Work-balanced decode product for one token: every workgroup streams the same number of weight
+// tiles, whatever the shapes of the matrices in the launch (Section 2 of arXiv 2410.16144, I2_S
+// form: codes back to weights in registers, multiply-add against int8 activations).
+//
+// The launch has a fixed number of workgroups (a multiple of the compute-unit count).  Each matrix
+// gets a share of them in proportion to its tile count; inside a matrix, the tiles, in memory
+// order (row block major, then K), are cut into equal contiguous chunks, one per workgroup, and
+// the chunk is cut again into 16 contiguous pieces, one per wave.  A piece may begin and end in
+// the middle of a row block:
+//   * inside the workgroup the pieces of one row block meet in LDS (integer adds);
+//   * a row block cut by a chunk boundary is finished through the caller's workspace: per row one
+//     64-bit word, the tile count in its high bits and the signed partial sum in its low 40 bits,
+//     so ONE returning atomic add per row both deposits a partial sum and tells the depositor
+//     whether it was the last one; the last one writes the output and stores zero back.
+// Integer addition is exact and order-free, so the result is bit-identical to the unsplit kernel.
+#include "bl_decode_device.hpp"
+
+namespace bl {
+
+namespace {
+
+constexpr int kSkMaxRb = 32;   // row blocks one chunk may touch (LDS: 256 bytes each)
+constexpr int kSumBits = 40;   // low bits of a workspace word that hold the partial sum
+
+template <int U, bool FUSED, bool XBF16>
+__global__ __launch_bounds__(kThreads, 8) void decode_sk_kernel(const DecodeBatch b) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int blk = blockIdx.x;
+    int pi = 0;
+#pragma unroll
+    for (int i = 1; i < BL_MAX_BATCH; ++i) pi += (i < b.count && blk >= b.p[i].first_wg) ? 1 : 0;
+    const DecodeProblem& p = b.p[pi];
+
+    const int KC = p.KC, Kp = KC * kTileK;
+    const int T = p.row_blocks * KC;                           // tiles of this matrix
+    const int a = min((blk - p.first_wg) * p.chunk, T);        // this workgroup's tiles [a, e)
+    const int e = min(a + p.chunk, T);
+    if (a >= e) return;                                        // uniform: a workgroup without work
+    const int per_wave = (e - a + kWaves - 1) / kWaves;
+    const int t_wave = min(a + wave * per_wave, e);            // this wave's tiles [t_wave, t_wave + mine)
+    const int mine = min(per_wave, e - t_wave);
+    const int rb0 = a / KC, rb1 = (e - 1) / KC;                // row blocks the chunk touches
+
+    int8_t* lds_q = reinterpret_cast<int8_t*>(smem);
+    int* red = reinterpret_cast<int*>(smem + (FUSED ? Kp : 0));    // [row block - rb0][64]
+    float* s_f = reinterpret_cast<float*>(red + kSkMaxRb * kWave);  // [16] maxima, then the scale
+    int* s_i = reinterpret_cast<int*>(s_f + kWaves + 1);            // [16] partial sum(q)
+
+    for (int i = tid; i < (rb1 - rb0 + 1) * kWave; i += kThreads) red[i] = 0;
+
+    const uint4* __restrict__ wp = p.packed + lane;
+    uint4 w[U];
+    auto load_part = [&](int i0, int first, int last) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (u >= first && u < last) {
+                const int t = t_wave + i0 + u;
+                w[u] = wp[(int64_t)(t < T ? t : T - 1) * kWave];   // clamped: always a valid tile
+            }
+        }
+    };
+    auto load_batch = [&](int i0) { load_part(i0, 0, U); };
+    constexpr int kEarly = U > 4 ? U / 2 : U;   // tiles that go in flight ahead of the quantizer (register budget)
+
+    int qsum = 0;
+    float scale = 0.0f;
+    if constexpr (!FUSED) {
+        load_batch(0);
+        qsum = p.q_sum[0];
+        scale = p.a_scale[0];
+        __syncthreads();   // red is zero before the first deposit
+    } else {
+        const bool vec = p.x_flags & 2;
+        if (vec && p.K <= 2 * kThreads * 8) {
+            // raw activations first: loads retire in order, so the quantizer's wait leaves the tiles in flight
+            const int k0 = tid * 8, k1 = k0 + kThreads * 8;
+            const bool h0 = k0 < p.K, h1 = k1 < p.K;
+            const Raw8<XBF16> r0 = load_raw8<XBF16>(p.x, h0 ? k0 : 0), r1 = load_raw8<XBF16>(p.x, h1 ? k1 : 0);
+            load_part(0, 0, kEarly);
+            quantize_row_from_regs<XBF16>(r0, r1, h0, h1, p.K, Kp, lds_q, s_f, s_i, tid, lane, wave);
+            load_part(0, kEarly, U);
+        } else {
+            if (vec) quantize_rows_to_lds<1, XBF16, true>(p, lds_q, s_f, s_i, tid, lane, wave);
+            else quantize_rows_to_lds<1, XBF16, false>(p, lds_q, s_f, s_i, tid, lane, wave);
+            load_batch(0);
+        }
+#pragma unroll
+        for (int w16 = 0; w16 < kWaves; ++w16) qsum += s_i[w16];
+        scale = s_f[kWaves];
+        if (blk == p.first_wg) {   // optional copy-out of the quantizer's results
+            if (p.q_out) {
+                for (int i = tid; i < Kp / 4; i += kThreads)
+                    reinterpret_cast<int32_t*>(p.q_out)[i] = reinterpret_cast<const int32_t*>(lds_q)[i];
+            }
+            if (tid == 0) {
+                if (p.a_scale_out) p.a_scale_out[0] = scale;
+                if (p.q_sum_out) p.q_sum_out[0] = qsum;
+            }
+        }
+    }
+
+    Acc<1> acc;
+    acc.lo[0] = acc.hi[0] = 0;
+    int rb = min(t_wave, T - 1) / KC;
+    int kc = t_wave - rb * KC;
+    auto deposit = [&]() {
+        __hip_atomic_fetch_add(&red[(rb - rb0) * kWave + lane], acc.lo[0] + (acc.hi[0] >> 2), __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_WORKGROUP);   // hi: exact multiple of 4
+        acc.lo[0] = acc.hi[0] = 0;
+    };
+    if (mine > 0) {
+        for (int i0 = 0;;) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (i0 + u < mine) {
+                    if (kc == KC) {   // the piece runs on into the next row block
+                        deposit();
+                        ++rb;
+                        kc = 0;
+                    }
+                    if constexpr (FUSED) tile_mac<1>(w[u], reinterpret_cast<const int32_t*>(lds_q) + kc * 16, Kp / 4, acc);
+                    else tile_mac<1>(w[u], p.q + kc * 16, Kp / 4, acc);
+                    ++kc;
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            i0 += U;
+            if (i0 >= mine) break;
+            load_batch(i0);
+        }
+        deposit();
+    }
+    __syncthreads();
+
+    for (int r = rb0 + wave; r <= rb1; r += kWaves) {
+        const int v = red[(r - rb0) * kWave + lane];
+        const int t_first = r * KC, t_end = t_first + KC;
+        int total = v;
+        bool last = true;
+        if (t_first < a || t_end > e) {   // uniform: the row block is shared with other workgroups
+            const int cnt = min(e, t_end) - max(a, t_first);
+            unsigned long long* slot = b.ws + (int64_t)(p.first_wg + t_first / p.chunk) * kWave + lane;
+            const unsigned long long add = ((unsigned long long)cnt << kSumBits) + (unsigned long long)(long long)v;
+            const unsigned long long now =
+                __hip_atomic_fetch_add(slot, add, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + add;
+            const long long sum = (long long)(now << (64 - kSumBits)) >> (64 - kSumBits);
+            last = (long long)((now - (unsigned long long)sum) >> kSumBits) == KC;
+            total = (int)sum;
+            if (last) __hip_atomic_store(slot, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        const int row = r * kTileN + lane;
+        if (last && row < p.N) {
+            total -= qsum;
+            p.out[row] = (float)total * (p.w_scale * scale);
+            if (p.acc) p.acc[row] = total;
+        }
+    }
+}
+
+template <int U, bool FUSED, bool XBF16>
+hipError_t launch_sk(const DecodeBatch& b, size_t lds, hipStream_t s) {
+    static bool attr_set = false;
+    auto kernel = &decode_sk_kernel<U, FUSED, XBF16>;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDecodeLds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    kernel<<<dim3((unsigned)b.total_wgs), dim3(kThreads), lds, s>>>(b);
+    return hipGetLastError();
+}
+
+int g_split = 0;   // -1 never, 0 automatic, n > 0: n workgroups per compute unit
+int64_t g_split_launches = 0;
+
+int compute_units() {
+    static int cus = 0;
+    if (!cus) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+            return 0;
+        cus = n;
+    }
+    return cus;
+}
+
+}  // namespace
+
+void set_decode_split(int v) { g_split = v; }
+int64_t split_launches() { return g_split_launches; }
+
+// Plans the balanced launch.  Returns false when the balanced form does not apply (the caller then
+// uses the row-block kernels): tiny launches, shapes whose chunks would touch too many row blocks.
+bool plan_decode_split(DecodeBatch& b, bool fused, int& tiles_per_wave) {
+    if (g_split < 0 || !b.ws) return false;
+    const int cus = compute_units();
+    if (cus <= 0) return false;
+    int64_t T[BL_MAX_BATCH], total = 0;
+    for (int i = 0; i < b.count; ++i) {
+        T[i] = (int64_t)b.p[i].row_blocks * b.p[i].KC;
+        if (T[i] > (1 << 30)) return false;
+        total += T[i];
+    }
+    // Measured on MI355X (decoder layers of 0.7B to 100B shapes): equal shares pay off between about 100 and 400
+    // tiles per compute unit; below, the launch is latency-bound either way, above, many small workgroups
+    // dispatched as others finish adapt better to compute units that stream at different speeds.
+    const int64_t per_cu = total / cus;
+    int mult = g_split;
+    if (mult == 0) {
+        if (per_cu > 400 || per_cu < (fused ? 100 : 32)) return false;
+        mult = (!fused && per_cu <= 250) ? 2 : 1;
+    }
+    const int grid = cus * mult;
+    if (grid > BL_MAX_SPLIT_WGS || b.count > grid) return false;
+    if (total < (int64_t)grid * kWaves * 2) return false;   // under two tiles per wave: nothing to balance
+    int g[BL_MAX_BATCH], used = 0;
+    for (int i = 0; i < b.count; ++i) {
+        g[i] = (int)(T[i] * grid / total);
+        if (g[i] < 1) g[i] = 1;
+        used += g[i];
+    }
+    auto chunk = [&](int i) { return (T[i] + g[i] - 1) / g[i]; };
+    while (used < grid) {   // hand the remaining workgroups to the matrices with the largest chunks
+        int best = 0;
+        for (int i = 1; i < b.count; ++i)
+            if (chunk(i) > chunk(best)) best = i;
+        ++g[best];
+        ++used;
+    }
+    while (used > grid) {   // rounding up to one workgroup overshot: take from the smallest chunks
+        int best = -1;
+        for (int i = 0; i < b.count; ++i)
+            if (g[i] > 1 && (best < 0 || chunk(i) < chunk(best))) best = i;
+        if (best < 0) return false;
+        --g[best];
+        --used;
+    }
+    int first = 0;
+    int64_t max_chunk = 0;
+    for (int i = 0; i < b.count; ++i) {
+        const int64_t c = chunk(i);
+        if (c / b.p[i].KC + 2 > kSkMaxRb) return false;
+        b.p[i].chunk = (int32_t)c;
+        b.p[i].first_wg = first;
+        first += g[i];
+        if (c > max_chunk) max_chunk = c;
+    }
+    b.total_wgs = grid;
+    ++g_split_launches;
+    tiles_per_wave = (int)((max_chunk + kWaves - 1) / kWaves);
+    return true;
+}
+
+hipError_t launch_decode_split(const DecodeBatch& b, int tiles_per_wave, bool fused, hipStream_t s) {
+    int64_t max_Kp = 0;
+    for (int i = 0; i < b.count; ++i) max_Kp = (int64_t)b.p[i].KC * kTileK > max_Kp ? (int64_t)b.p[i].KC * kTileK : max_Kp;
+    const size_t lds = (size_t)(fused ? max_Kp : 0) + (size_t)kSkMaxRb * kWave * 4 + (size_t)(2 * kWaves + 1) * 4;
+    if (lds > (size_t)kMaxDecodeLds) return hipErrorInvalidValue;
+    const bool bf16 = b.p[0].x_flags & 1;
+    const bool small = tiles_per_wave <= 4;
+    if (!fused) return small ? launch_sk<4, false, true>(b, lds, s) : launch_sk<8, false, true>(b, lds, s);
+    if (bf16) return small ? launch_sk<4, true, true>(b, lds, s) : launch_sk<8, true, true>(b, lds, s);
+    return small ? launch_sk<4, true, false>(b, lds, s) : launch_sk<8, true, false>(b, lds, s);
+}
+
+}  // namespace bl

@@ -44,12 +44,14 @@ struct DecodeProblem {
     int32_t        x_flags;      // bit 0: bf16, bit 1: 128-bit vector loads allowed
     int32_t        wlog2;        // log2(waves that share one row block)
     int32_t        first_wg;     // first workgroup of this problem in the grid
+    int32_t        chunk;        // balanced form: tiles per workgroup
 };
 
 struct DecodeBatch {
     DecodeProblem p[BL_MAX_BATCH];
     int32_t       count;
     int32_t       total_wgs;
+    unsigned long long* ws;      // balanced form: the caller's workspace (zero between launches), or null
 };
 
 constexpr int kMaxDecodeLds = 128 * 1024;   // dynamic LDS ceiling of the decode kernels
@@ -63,13 +65,17 @@ hipError_t launch_quant(const void* x, int is_bf16, int64_t M, int64_t K, int64_
                         float* a_scale, int32_t* q_sum, hipStream_t s);
 size_t decode_lds_bytes(int M, int64_t max_Kp, bool fused);
 hipError_t launch_decode(const DecodeBatch& b, int M, bool fused, hipStream_t s);
+bool plan_decode_split(DecodeBatch& b, bool fused, int& tiles_per_wave);   // false: the balanced form does not apply
+hipError_t launch_decode_split(const DecodeBatch& b, int tiles_per_wave, bool fused, hipStream_t s);
 hipError_t launch_gemm(const GemvProblem& p, int64_t M, hipStream_t s);
 
 // Launch-shape overrides for experiments (0 = choose automatically).
 void set_gemv_waves(int waves);
 void set_gemm_mb(int mb);         // 0 automatic, 2 = 64-token tiles, 4 = 128-token tiles
 void set_decode_stage(int v);     // 1: the matrix-core decode kernel never stages activations in LDS
-void set_decode_path(int path);   // 0 automatic, 1 dot-product kernel, 2 matrix-core kernel
+void set_decode_split(int v);     // -1 never split row blocks over workgroups, 0 automatic, n: n workgroups per compute unit
+void set_decode_path(int path);
+int64_t split_launches();        // work-balanced decode launches so far (host-side count)   // 0 automatic, 1 dot-product kernel, 2 matrix-core kernel
 
 // ---- device helpers -------------------------------------------------------------------
 

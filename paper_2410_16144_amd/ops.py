@@ -105,11 +105,36 @@ def gemm(pw: PackedWeight, qa: QuantAct, out: Optional[torch.Tensor] = None, wan
     return _product(B.bl_gemm, pw, qa, out, want_acc)
 
 
+_workspaces = {}
+
+
+def workspace(device) -> torch.Tensor:
+    """The zero-filled workspace of the work-balanced decode launches, one per device.  Launches that
+    may overlap in time (different streams) must not share one: give those groups a tensor of their own."""
+    key = torch.device(device).index or 0
+    ws = _workspaces.get(key)
+    if ws is None:
+        ws = _workspaces[key] = torch.zeros(B.BL_WORKSPACE_BYTES, dtype=torch.uint8, device=device)
+    return ws
+
+
+def _workspace_ptr(use_workspace, device) -> int:
+    """use_workspace: True = the device's shared workspace, False = none, or a zero-filled uint8 tensor."""
+    if use_workspace is True:
+        return workspace(device).data_ptr()
+    if use_workspace is False or use_workspace is None:
+        return 0
+    assert use_workspace.is_cuda and use_workspace.numel() * use_workspace.element_size() >= B.BL_WORKSPACE_BYTES
+    return use_workspace.data_ptr()
+
+
 class GemvGroup:
     """A prepared grouped decode launch (bl_gemv_batch): fixed weights, activations and outputs."""
 
-    def __init__(self, weights, acts, outs=None, want_acc=False):
+    def __init__(self, weights, acts, outs=None, want_acc=False, use_workspace=True):
         assert 1 <= len(weights) <= B.BL_MAX_BATCH and len(weights) == len(acts)
+        self.use_workspace = use_workspace
+        self.workspace_ptr = _workspace_ptr(use_workspace, weights[0].blob.device)
         self.M = acts[0].M
         dev = weights[0].blob.device
         self.weights, self.acts = list(weights), list(acts)
@@ -122,7 +147,7 @@ class GemvGroup:
             for i, (w, a, o) in enumerate(zip(self.weights, self.acts, self.outs)))
 
     def launch(self):
-        B.bl_gemv_batch(self.items, self.M, _stream())
+        B.bl_gemv_batch(self.items, self.M, self.workspace_ptr, _stream())
         return self.outs
 
 
@@ -138,8 +163,10 @@ class DecodeGroup:
     """A prepared fused decode launch (bl_decode_batch): quantization + product of up to 8
     BitLinears in one kernel.  `xs[i]` is the [M,K_i] input of `weights[i]` (inputs may repeat)."""
 
-    def __init__(self, weights, xs, outs=None, want_acc=False, want_quant=False):
+    def __init__(self, weights, xs, outs=None, want_acc=False, want_quant=False, use_workspace=True):
         assert 1 <= len(weights) <= B.BL_MAX_BATCH and len(weights) == len(xs)
+        self.use_workspace = use_workspace
+        self.workspace_ptr = _workspace_ptr(use_workspace, weights[0].blob.device)
         self.M = int(xs[0].shape[0])
         dev = weights[0].blob.device
         self.weights, self.xs = list(weights), list(xs)
@@ -158,5 +185,5 @@ class DecodeGroup:
             for i, (w, x, o) in enumerate(zip(self.weights, self.xs, self.outs)))
 
     def launch(self):
-        B.bl_decode_batch(self.items, self.M, _stream())
+        B.bl_decode_batch(self.items, self.M, self.workspace_ptr, _stream())
         return self.outs

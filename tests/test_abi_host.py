@@ -91,22 +91,29 @@ def test_argument_validation_happens_before_any_launch():
     assert _st(B.bl_gemm, P, bad, P, P, P, 1, P) == B.BL_ERR_SHAPE
     # batch count
     items = B.make_gemv_items([(P, d, P, P, P, P, 0)])
-    assert B.lib().bl_gemv_batch(items, 0, 1, None) == B.BL_ERR_COUNT
-    assert B.lib().bl_gemv_batch(items, 9, 1, None) == B.BL_ERR_COUNT
-    assert B.lib().bl_gemv_batch(None, 1, 1, None) == B.BL_ERR_NULL
+    assert B.lib().bl_gemv_batch(items, 0, 1, None, None) == B.BL_ERR_COUNT
+    assert B.lib().bl_gemv_batch(items, 9, 1, None, None) == B.BL_ERR_COUNT
+    assert B.lib().bl_gemv_batch(None, 1, 1, None, None) == B.BL_ERR_NULL
     # fused decode
     ditems = B.make_decode_items([(P, B.BL_BF16, 128, P, d, P, 0, 0, 0, 0)])
     lib = B.lib()
-    assert lib.bl_decode_batch(ditems, 1, 9, None) == B.BL_ERR_M_RANGE
-    assert lib.bl_decode_batch(ditems, 0, 1, None) == B.BL_ERR_COUNT
-    assert lib.bl_decode_batch(None, 1, 1, None) == B.BL_ERR_NULL
-    assert lib.bl_decode_batch(B.make_decode_items([(0, B.BL_BF16, 128, P, d, P, 0, 0, 0, 0)]), 1, 1, None) == B.BL_ERR_NULL
-    assert lib.bl_decode_batch(B.make_decode_items([(P, 5, 128, P, d, P, 0, 0, 0, 0)]), 1, 1, None) == B.BL_ERR_DTYPE
-    assert lib.bl_decode_batch(B.make_decode_items([(P, B.BL_BF16, 64, P, d, P, 0, 0, 0, 0)]), 1, 1, None) == B.BL_ERR_SHAPE
-    assert lib.bl_decode_batch(B.make_decode_items([(P + 1, B.BL_BF16, 128, P, d, P, 0, 0, 0, 0)]), 1, 1, None) == B.BL_ERR_ALIGN
+    assert lib.bl_decode_batch(ditems, 1, 9, None, None) == B.BL_ERR_M_RANGE
+    assert lib.bl_decode_batch(ditems, 0, 1, None, None) == B.BL_ERR_COUNT
+    assert lib.bl_decode_batch(None, 1, 1, None, None) == B.BL_ERR_NULL
+    assert lib.bl_decode_batch(B.make_decode_items([(0, B.BL_BF16, 128, P, d, P, 0, 0, 0, 0)]), 1, 1, None, None) == B.BL_ERR_NULL
+    assert lib.bl_decode_batch(B.make_decode_items([(P, 5, 128, P, d, P, 0, 0, 0, 0)]), 1, 1, None, None) == B.BL_ERR_DTYPE
+    assert lib.bl_decode_batch(B.make_decode_items([(P, B.BL_BF16, 64, P, d, P, 0, 0, 0, 0)]), 1, 1, None, None) == B.BL_ERR_SHAPE
+    assert lib.bl_decode_batch(B.make_decode_items([(P + 1, B.BL_BF16, 128, P, d, P, 0, 0, 0, 0)]), 1, 1, None, None) == B.BL_ERR_ALIGN
     big = B.bl_packed_desc_init(64, 65536, 1.0)    # 8 tokens x 64 KiB of activations exceed on-chip memory
-    assert lib.bl_decode_batch(B.make_decode_items([(P, B.BL_BF16, 65536, P, big, P, 0, 0, 0, 0)]), 1, 8, None) == B.BL_ERR_SHAPE
+    assert lib.bl_decode_batch(B.make_decode_items([(P, B.BL_BF16, 65536, P, big, P, 0, 0, 0, 0)]), 1, 8, None, None) == B.BL_ERR_SHAPE
+    # workspace alignment
+    assert B.lib().bl_gemv_batch(items, 1, 1, P + 64, None) == B.BL_ERR_ALIGN
+    assert lib.bl_decode_batch(ditems, 1, 1, P + 16, None) == B.BL_ERR_ALIGN
     # tuning hook
+    assert _st(B.bl_set_tuning, "decode_split", 9) == B.BL_ERR_SHAPE
+    assert _st(B.bl_set_tuning, "decode_split", -2) == B.BL_ERR_SHAPE
+    B.bl_set_tuning("decode_split", 0)
+    assert B.bl_get_stat("nonsense") == -1 and B.bl_get_stat("split_launches") >= 0
     assert _st(B.bl_set_tuning, "nonsense", 1) == B.BL_ERR_SHAPE
     assert _st(B.bl_set_tuning, "gemv_waves", 3) == B.BL_ERR_SHAPE
     B.bl_set_tuning("gemv_waves", 0)

@@ -375,6 +375,95 @@ def test_fused_decode_equals_two_call_sequence(dev, ops):
     assert torch.equal(grp.quants[0].q_sum, qa.q_sum)
 
 
+# ------------------------------------------------------------------ work-balanced decode (workspace)
+
+@pytest.fixture
+def decode_split():
+    """Force the work-balanced one-token launch with n workgroups per compute unit, then restore."""
+    from paper_2410_16144_amd import binding
+
+    def force(n):
+        binding.bl_set_tuning("decode_split", n)
+    yield force
+    binding.bl_set_tuning("decode_split", 0)
+
+
+def _assert_split(ops, dev, problems, expect_split):
+    """Plain and fused one-token launches with a workspace against the oracle; the workspace must be
+    all zero again afterwards, and a second launch on the same workspace must give the same bits."""
+    from paper_2410_16144_amd import binding
+    ws = ops.workspace(dev)
+    assert not ws.any()
+    weights, xs, acts = [], [], []
+    for w, s, x in problems:
+        weights.append(ops.pack_ternary(torch.from_numpy(w).to(dev), float(s)))
+        xs.append(_to_dev_bf16(x, dev) if x.dtype == np.uint16 else torch.from_numpy(x).to(dev))
+        acts.append(ops.quant_act(xs[-1]))
+    before = binding.bl_get_stat("split_launches")
+    plain = ops.GemvGroup(weights, acts, want_acc=True)
+    plain.launch()
+    fused = ops.DecodeGroup(weights, xs, want_acc=True, want_quant=True)
+    fused.launch()
+    torch.cuda.synchronize()
+    assert binding.bl_get_stat("split_launches") - before == (2 if expect_split else 0)
+    assert not ws.any()
+    for i, (w, s, x) in enumerate(problems):
+        q_ref, a_ref, s_ref = oracle.quant_act(x)
+        acc_ref = oracle.matmul_i32(q_ref, w)
+        _assert_quant_equal(fused.quants[i], (q_ref, a_ref, s_ref), w.shape[1])
+        for grp in (plain, fused):
+            assert np.array_equal(grp.accs[i].cpu().numpy(), acc_ref)
+            _check_out(grp.outs[i], acc_ref, s, a_ref)
+    first = [o.clone() for o in fused.outs]
+    for o in fused.outs:
+        o.zero_()
+    fused.launch()
+    fused.launch()
+    torch.cuda.synchronize()
+    assert all(torch.equal(a, b) for a, b in zip(first, fused.outs)) and not ws.any()
+    # without a workspace: the row-block kernels, same bits
+    nows = ops.DecodeGroup(weights, xs, use_workspace=False)
+    nows.launch()
+    torch.cuda.synchronize()
+    assert all(torch.equal(a, b) for a, b in zip(first, nows.outs))
+
+
+@pytest.mark.parametrize("bf16", [True, False])
+@pytest.mark.parametrize("n,N,K", [(1, 4100, 8200),     # every row block shared by about four workgroups
+                                   (1, 33000, 1100),    # short rows: whole row blocks inside a chunk
+                                   (2, 8200, 8200),
+                                   (1, 321, 64 * 1800)])  # 6 row blocks, each spread over about 42 workgroups
+def test_split_decode_single_matrix(dev, ops, decode_split, n, N, K, bf16):
+    decode_split(n)
+    _assert_split(ops, dev, [_problem(N + 3 * K + n, 1, K, N, p_zero=0.4, outl=0.01, bf16=bf16)], True)
+
+
+@pytest.mark.parametrize("n", [1, 2])
+def test_split_decode_batch_mixed_shapes(dev, ops, decode_split, n):
+    decode_split(n)
+    shapes = [(2000, 4000), (1000, 9000), (5000, 3000), (700, 6000), (64, 64), (2000, 4000), (130, 12000)]
+    scale = 2 if n == 2 else 1
+    _assert_split(ops, dev, [_problem(2100 + i, 1, K, N * scale, outl=0.01) for i, (N, K) in enumerate(shapes)], True)
+
+
+def test_split_decode_falls_back_when_it_does_not_apply(dev, ops, decode_split):
+    decode_split(1)
+    # K = 64: a chunk would touch more row blocks than the kernel keeps partial sums for
+    _assert_split(ops, dev, [_problem(2200, 1, 64, 64 * 9000)], False)
+    # too small to be worth balancing
+    _assert_split(ops, dev, [_problem(2201, 1, 1536, 1536)], False)
+    decode_split(-1)
+    _assert_split(ops, dev, [_problem(2202, 1, 8200, 4100)], False)
+
+
+def test_split_decode_layer_shape_automatic(dev, ops):
+    # a 3B-shape layer (Appendix A structure) is in the range where the automatic choice balances
+    from paper_2410_16144_amd import binding
+    projs = synth.layer_projections(3200, 8640)
+    problems = [_problem(2300 + i, 1, p.K, p.N, p_zero=0.4, outl=0.01) for i, p in enumerate(projs)]
+    _assert_split(ops, dev, problems, True)
+
+
 # ------------------------------------------------------------------ prefill product
 
 @pytest.mark.parametrize("M,N,K", [(1, 64, 64), (7, 70, 100), (33, 200, 1000), (128, 256, 512), (130, 320, 1536),
