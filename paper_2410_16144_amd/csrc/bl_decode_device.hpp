@@ -40,32 +40,89 @@ __device__ __forceinline__ void tile_mac(const uint4& w, QPtr qk, int q_stride_w
 }
 
 // Quantize M token rows into LDS; per-token scale and partial sums of q are left in s_f / s_i (LDS).
-// General form: the row is read twice (the second read hits L1/L2).
+// General form: the rows are read twice (the second read hits L1/L2).  Both passes walk the rows R at a
+// time with the R loads of a step issued together, so a pass costs one memory round trip per step
+// instead of one per row.
 template <int M, bool BF16, bool VEC>
 __device__ __forceinline__ void quantize_rows_to_lds(const DecodeProblem& p, int8_t* lds_q, float* s_f, int* s_i,
                                                      int tid, int lane, int wave) {
     const int K = p.K, Kp = p.KC * kTileK;
     const char* x = static_cast<const char*>(p.x);
     const int64_t row_bytes = p.ldx * (BF16 ? 2 : 4);
+    constexpr int R = !VEC ? 1 : M < (BF16 ? 4 : 2) ? M : (BF16 ? 4 : 2);   // rows whose vectors are in registers together
     float amax[M];
 #pragma unroll
-    for (int m = 0; m < M; ++m) amax[m] = wave_max(thread_absmax<BF16, VEC>(x + m * row_bytes, K, tid, kThreads));
+    for (int m = 0; m < M; ++m) amax[m] = 0.0f;
+    if constexpr (VEC) {
+        for (int k = tid * 8; k < K; k += kThreads * 8) {
+#pragma unroll
+            for (int m0 = 0; m0 < M; m0 += R) {
+                Raw8<BF16> r[R];
+#pragma unroll
+                for (int j = 0; j < R; ++j)
+                    if (m0 + j < M) r[j] = load_raw8<BF16>(x + (m0 + j) * row_bytes, k);
+#pragma unroll
+                for (int j = 0; j < R; ++j) {
+                    if (m0 + j < M) {
+                        float v[8];
+                        unpack_raw8<BF16>(r[j], v);
+                        amax[m0 + j] = fmaxf(amax[m0 + j], absmax8(v));
+                    }
+                }
+            }
+        }
+    } else {
+#pragma unroll
+        for (int m = 0; m < M; ++m) amax[m] = thread_absmax<BF16, false>(x + m * row_bytes, K, tid, kThreads);
+    }
+#pragma unroll
+    for (int m = 0; m < M; ++m) amax[m] = wave_max(amax[m]);
     if (lane == 0) {
 #pragma unroll
         for (int m = 0; m < M; ++m) s_f[m * kWaves + wave] = amax[m];
     }
     __syncthreads();
-    int sum[M];
+    float inv[M];
 #pragma unroll
     for (int m = 0; m < M; ++m) {
         float am = s_f[m * kWaves];
 #pragma unroll
         for (int w = 1; w < kWaves; ++w) am = fmaxf(am, s_f[m * kWaves + w]);
-        float inv, scale;
-        quant_scales(am, inv, scale);
-        sum[m] = wave_sum(thread_quantize<BF16, VEC>(x + m * row_bytes, K, Kp, inv, lds_q + m * Kp, tid, kThreads));
+        float scale;
+        quant_scales(am, inv[m], scale);
         if (tid == 0) s_f[M * kWaves + m] = scale;
     }
+    int sum[M];
+#pragma unroll
+    for (int m = 0; m < M; ++m) sum[m] = 0;
+    if constexpr (VEC) {
+        for (int k = tid * 8; k < K; k += kThreads * 8) {
+#pragma unroll
+            for (int m0 = 0; m0 < M; m0 += R) {
+                Raw8<BF16> r[R];
+#pragma unroll
+                for (int j = 0; j < R; ++j)
+                    if (m0 + j < M) r[j] = load_raw8<BF16>(x + (m0 + j) * row_bytes, k);
+#pragma unroll
+                for (int j = 0; j < R; ++j) {
+                    if (m0 + j < M) {
+                        float v[8];
+                        unpack_raw8<BF16>(r[j], v);
+                        sum[m0 + j] += quantize8(v, inv[m0 + j], lds_q + (m0 + j) * Kp + k);
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int m = 0; m < M; ++m)
+            for (int k = K + tid; k < Kp; k += kThreads) lds_q[m * Kp + k] = 0;   // layout padding
+    } else {
+#pragma unroll
+        for (int m = 0; m < M; ++m)
+            sum[m] = thread_quantize<BF16, false>(x + m * row_bytes, K, Kp, inv[m], lds_q + m * Kp, tid, kThreads);
+    }
+#pragma unroll
+    for (int m = 0; m < M; ++m) sum[m] = wave_sum(sum[m]);
     if (lane == 0) {
 #pragma unroll
         for (int m = 0; m < M; ++m) s_i[m * kWaves + wave] = sum[m];

@@ -188,6 +188,8 @@ __global__ __launch_bounds__(kThreads, 8) void decode_mfma_kernel(const DecodeBa
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     constexpr bool kLdsQ = QMODE != 0;
     constexpr int U = kLdsQ ? kMfmaInFlightLds : kMfmaInFlightDirect;   // weight tiles in flight per wave
+    // fused form with many tokens: the quantizer's own registers leave no room for tiles in flight beside it
+    constexpr bool kTilesAfterQuant = QMODE == 2 && M > 4;
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
@@ -250,13 +252,14 @@ __global__ __launch_bounds__(kThreads, 8) void decode_mfma_kernel(const DecodeBa
             if (idx < n16) reinterpret_cast<uint4*>(lds_q)[idx] = stage[i];
         }
         __syncthreads();
-    } else {
+    } else if constexpr (!kTilesAfterQuant) {
         load_batch(ks);   // waves without a row block load (valid) block 0: no branch, exact wait counts
     }
 
     if constexpr (QMODE == 2) {
         if (p.x_flags & 2) quantize_rows_to_lds<M, XBF16, true>(p, lds_q, s_f, s_i, tid, lane, wave);
         else quantize_rows_to_lds<M, XBF16, false>(p, lds_q, s_f, s_i, tid, lane, wave);
+        if constexpr (kTilesAfterQuant) load_batch(ks);
         if (wg == 0 && p.q_out) {
             for (int i = tid; i < M * Kp / 4; i += kThreads)
                 reinterpret_cast<int32_t*>(p.q_out)[i] = reinterpret_cast<const int32_t*>(lds_q)[i];
