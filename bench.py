@@ -40,7 +40,7 @@ def parse_args():
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
     ap.add_argument("--full-100b", action="store_true",
                     help="extra: build all 80 layers of the 100B-shape model (37 GB packed) and time a whole token")
-    ap.add_argument("--only", default="", help="run only one extra section (copy|prefill|decode7b|decode100b) and print it")
+    ap.add_argument("--only", default="", help="run only one extra section (copy|prefill|decode7b|decode100b|paper100b|config1) and print it")
     return ap.parse_args()
 
 
@@ -57,7 +57,7 @@ def timed(torch, fn):
     return e0.elapsed_time(e1), wall
 
 
-def run_steps(torch, step_fns, count, use_graph):
+def run_steps(torch, step_fns, count, use_graph, stats=None):
     """Time exactly `count` steps (step i = step_fns[i % len]).  With use_graph the steps are
     captured once into a HIP graph (one replay = all `count` steps) so that host launch overhead
     is out of the timed region; the replay itself is what is timed."""
@@ -85,6 +85,11 @@ def run_steps(torch, step_fns, count, use_graph):
         if time.perf_counter() - t0 > 0.05:
             break
     ms, wall = timed(torch, g.replay)
+    if stats is not None:   # further replays of the same K steps: spread of the per-step time
+        more = sorted([ms] + [timed(torch, g.replay)[0] for _ in range(4)])
+        stats.update({"replays": len(more), "ms_per_step_min": round(more[0] / count, 6),
+                      "ms_per_step_median": round(more[len(more) // 2] / count, 6),
+                      "ms_per_step_max": round(more[-1] / count, 6)})
     del g
     return ms, wall, "hip-graph"
 
@@ -197,6 +202,33 @@ def extra_decode_shape(torch, name, hidden, ffn, M, layers, steps, use_graph):
     return res
 
 
+def extra_config1(torch, use_graph):
+    """The smallest case: one 1536x1536 matrix (0.59 MB packed), fp32 activations, M=1.  Launch-latency
+    bound; reported cold (rotating through 1 GiB of copies) and cache-resident (one copy)."""
+    from paper_2410_16144_amd import ops, synth
+    dev = torch.device("cuda:0")
+    N = K = 1536
+    nb = N * K // 4
+    copies = (1 << 30) // nb // 8 + 1    # 8 distinct matrices, each stored this many times: over 1 GiB in all
+    base = [ops.pack_ternary(synth.ternary_weights_device(100 + i, N, K, dev), 0.02) for i in range(8)]
+    pws = [ops.PackedWeight(b.blob.clone(), b.desc) for _ in range(copies) for b in base]
+    x = torch.randn((1, K), device=dev, dtype=torch.float32)
+    qa = ops.quant_act(x)
+    out = torch.empty((1, N), dtype=torch.float32, device=dev)
+    plain = [ops.GemvGroup([pw], [qa], [out]) for pw in pws]
+    fused = [ops.DecodeGroup([pw], [x], [out]) for pw in pws]
+    res = {"workload": "one 1536x1536 matrix, M=1, fp32 activations (%d copies = %.1f GiB rotated when cold)"
+                       % (len(pws), len(pws) * nb / 2**30), "packed_bytes": nb}
+    steps = 2 * len(pws)
+    for label, fns in (("gemv_cold", [g.launch for g in plain]), ("gemv_cache_resident", [plain[0].launch]),
+                       ("fused_cold", [g.launch for g in fused]), ("fused_cache_resident", [fused[0].launch])):
+        fns[0]()
+        ms, _, _ = run_steps(torch, fns, steps, use_graph)
+        us = ms * 1e3 / steps
+        res[label] = {"us": round(us, 2), "GBps": round(nb / us / 1e3, 1)}
+    return res
+
+
 def extra_full_100b(torch, use_graph):
     """All 80 layers of the 100B-shape model resident (36.99 GB packed); one token = 80 fused launches."""
     from paper_2410_16144_amd.decode_layer import make_layer
@@ -249,6 +281,8 @@ def main():
                 "decode7b": lambda: [extra_decode_shape(torch, "7B-shape", 4096, 11008, m, 24, 480, use_graph)
                                      for m in (1, 4, 8)],
                 "decode100b": lambda: extra_decode_shape(torch, "100B-shape", 12288, 33792, 1, 6, 120, use_graph),
+                "paper100b": lambda: extra_decode_shape(torch, "Appendix-A 100B", 8192, 45568, 1, 6, 120, use_graph),
+                "config1": lambda: extra_config1(torch, use_graph),
                 }[args.only]()
         print(json.dumps({args.only: sect}))
         return
@@ -267,7 +301,8 @@ def main():
     fns = [l.step_fused for l in layers]
     for i in range(args.warmup):
         fns[i % len(fns)]()
-    ms, wall_ms, mode = run_steps(torch, fns, args.steps, use_graph)
+    spread = {}
+    ms, wall_ms, mode = run_steps(torch, fns, args.steps, use_graph, spread)
     ms_per_step = ms / args.steps
     value = packed_bytes / (ms_per_step * 1e-3) / 1e9
     # the step IS one launch of the dominant kernel, so its average launch duration is the step time
@@ -280,10 +315,12 @@ def main():
                                "7 ternary GEMVs (hidden 3200, ffn 8640) per step in one fused launch, %d distinct "
                                "layers rotated (%.2f GB packed)" % (len(layers), packed_bytes * len(layers) / 1e9),
                    "launch": mode, "packed_bytes_per_step": packed_bytes,
-                   "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4), "wall_ms_timed_region": round(wall_ms, 3)},
+                   "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4), "wall_ms_timed_region": round(wall_ms, 3),
+                   "spread_over_replays": spread},
         "roofline": {"bound": "hbm", "achieved": round(value, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(value / HBM_PEAK_GBS, 4), "traffic": load_traffic("decode_kernel_3b_layer_m1"),
-                     "kernel": "decode_kernel<1, true> (fused quantize + 7 GEMVs of one layer per launch)",
+                     "kernel": "decode_sk_kernel<8, true, true> (fused quantize + 7 GEMVs of one layer per launch, "
+                               "equal tile shares per workgroup)",
                      "avg_launch_us": round(kernel_us, 3), "bytes_per_launch": packed_bytes},
     }
 
@@ -311,6 +348,10 @@ def main():
                               for m in (1, 4, 8)]
         torch.cuda.empty_cache()
         extra["decode_100b_layer"] = extra_decode_shape(torch, "100B-shape", 12288, 33792, 1, 6, 120, use_graph)
+        torch.cuda.empty_cache()
+        extra["decode_paper_100b_layer"] = extra_decode_shape(torch, "Appendix-A 100B", 8192, 45568, 1, 6, 120, use_graph)
+        torch.cuda.empty_cache()
+        extra["config1_1536"] = extra_config1(torch, use_graph)
         torch.cuda.empty_cache()
         if args.full_100b:
             extra["decode_100b_token"] = extra_full_100b(torch, use_graph)

@@ -398,9 +398,11 @@ static size_t lds_bytes_for(int M, int64_t max_Kp, bool q_in_lds) {
 size_t decode_lds_bytes(int M, int64_t max_Kp, bool fused) { return lds_bytes_for(M, max_Kp, fused); }
 
 // Fill in the launch geometry: waves per row block for each problem (so that a wave gets about one
-// batch of `tiles_per_wave` tiles) and the workgroup prefix.
+// batch of `tiles_per_wave` tiles) and the workgroup prefix.  Problems are put in order of falling
+// work per workgroup: workgroups are dispatched in index order, so the long ones start first and
+// the short ones fill in behind them instead of the other way round.
 static void plan_decode(DecodeBatch& b, int tiles_per_wave) {
-    int total = 0;
+    int64_t work[BL_MAX_BATCH];
     for (int i = 0; i < b.count; ++i) {
         DecodeProblem& p = b.p[i];
         int g = 1, lg = 0;
@@ -410,8 +412,24 @@ static void plan_decode(DecodeBatch& b, int tiles_per_wave) {
             while ((1 << lg) < g_force_waves) ++lg;
         }
         p.wlog2 = lg;
+        work[i] = (int64_t)(kWaves >> lg) * p.KC;   // tiles per workgroup
+    }
+    for (int i = 1; i < b.count; ++i) {   // insertion sort, stable
+        const DecodeProblem p = b.p[i];
+        const int64_t w = work[i];
+        int j = i;
+        for (; j > 0 && work[j - 1] < w; --j) {
+            b.p[j] = b.p[j - 1];
+            work[j] = work[j - 1];
+        }
+        b.p[j] = p;
+        work[j] = w;
+    }
+    int total = 0;
+    for (int i = 0; i < b.count; ++i) {
+        DecodeProblem& p = b.p[i];
         p.first_wg = total;
-        const int rbs_per_wg = kWaves >> lg;
+        const int rbs_per_wg = kWaves >> p.wlog2;
         total += (p.row_blocks + rbs_per_wg - 1) / rbs_per_wg;
     }
     b.total_wgs = total;
