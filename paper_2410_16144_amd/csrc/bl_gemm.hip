@@ -6,7 +6,10 @@
 // B = weight codes (w+1) as int8; sum_k q is subtracted in the epilogue.
 //
 // Tiling.  Workgroup = 4 waves side by side along N = (32*MB) tokens x (256*NB) weight rows; each
-// wave owns (32*MB) x (64*NB), i.e. MB x 2NB MFMA tiles.  K advances one packed tile (64) per step:
+// wave owns (32*MB) x (64*NB), i.e. MB x 2NB MFMA tiles.  (Variant WK = 2 for small M x N, where
+// that grid would leave compute units idle: 2 waves along N x 2 along K, the two K groups take
+// alternate packed tiles and add their accumulators through LDS at the end, so the workgroup tile
+// is half as wide and the grid twice as large.)  K advances one packed tile (64) per step:
 //   - activations: the (32*MB) x 64 int8 tile goes global -> registers (three steps ahead) -> LDS
 //     through a 3-stage ring (rows padded to 80 bytes so the 128-bit operand reads are
 //     bank-conflict free).  With three stages the operands of step i+1 are read from LDS while
@@ -27,7 +30,7 @@ namespace {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
-constexpr int kWavesN = 4;        // waves along N
+constexpr int kWaves = 4;         // waves per workgroup
 #ifndef BL_LDS_ROW
 #define BL_LDS_ROW 80
 #endif
@@ -43,12 +46,17 @@ __device__ __forceinline__ v4i expand_codes(uint32_t word) {
     return r;
 }
 
-template <int MB, int NB>
+template <int MB, int NB, int WK>
 __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemvProblem p, const int M) {
+    static_assert(WK == 1 || (WK == 2 && MB % 2 == 0), "K groups exchange halves of the token tile");
+    constexpr int WN = kWaves / WK;       // waves along N
     constexpr int BM = 32 * MB;
-    constexpr int kStageBytes = BM * kLdsRow;
-    constexpr int NLD = (BM + 63) / 64;   // 16-byte pieces each thread moves per step (256 threads x 16 B = 64 rows)
-    __shared__ __attribute__((aligned(16))) uint8_t lds[kStages * kStageBytes];
+    constexpr int kTileBytesA = BM * kLdsRow;
+    constexpr int kStageBytes = WK * kTileBytesA;   // one activation tile per K group
+    constexpr int NLD = (BM + 63) / 64;   // 16-byte pieces each thread moves per tile (256 threads x 16 B = 64 rows)
+    constexpr int kExchangeBytes = WK == 1 ? 0 : WN * MB * 2 * NB * 16 * 64 * 4;
+    constexpr int kLdsBytes = kStages * kStageBytes > kExchangeBytes ? kStages * kStageBytes : kExchangeBytes;
+    __shared__ __attribute__((aligned(16))) uint8_t lds[kLdsBytes];
     __shared__ float s_scale[BM];   // w_scale * a_scale[m] of the workgroup's tokens (read in the epilogue)
     __shared__ int s_qsum[BM];
 
@@ -56,8 +64,10 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemvProblem p, const
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int KC = p.KC;
+    const int steps = (KC + WK - 1) / WK;             // step i covers packed tiles WK*i .. WK*i + WK-1, one per K group
+    const int wave_n = wave % WN, kg = wave / WN;     // position along N, K group
     const int m0 = blockIdx.y * BM;
-    const int rb0 = (blockIdx.x * kWavesN + wave) * NB;   // this wave's first 64-row block of W (it owns NB of them)
+    const int rb0 = (blockIdx.x * WN + wave_n) * NB;  // this wave's first 64-row block of W (it owns NB of them)
     const int64_t qs = (int64_t)KC * kTileK;          // activation row stride in bytes
     const uint8_t* qbase = reinterpret_cast<const uint8_t*>(p.q);
 
@@ -69,22 +79,34 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemvProblem p, const
         const int m = min(m0 + a_row + 64 * i, M - 1);   // clamped rows compute garbage that is never stored
         a_src[i] = qbase + (int64_t)m * qs + a_col;
     }
-    struct Staged { uint4 v[NLD]; };   // passed by value so that it lives in registers
-    auto gload = [&](int kc) {
-        const int k = min(kc, KC - 1);
+    struct Staged { uint4 v[WK * NLD]; };   // passed by value so that it lives in registers
+    auto gload = [&](int step_i) {
         Staged t;
 #pragma unroll
-        for (int i = 0; i < NLD; ++i) t.v[i] = *reinterpret_cast<const uint4*>(a_src[i] + k * kTileK);
+        for (int g = 0; g < WK; ++g) {
+            const int kc = step_i * WK + g;
+            const int k = min(kc, KC - 1);
+#pragma unroll
+            for (int i = 0; i < NLD; ++i) {
+                t.v[g * NLD + i] = *reinterpret_cast<const uint4*>(a_src[i] + k * kTileK);
+                // a K group's tile beyond the last one must add nothing (only an odd tile count with WK = 2 gets here
+                // inside the loop; reads beyond the loop's end are never used)
+                if (WK > 1 && kc >= KC) t.v[g * NLD + i] = make_uint4(0, 0, 0, 0);
+            }
+        }
         return t;
     };
     auto lstore = [&](int stage, const Staged t) {
 #pragma unroll
-        for (int i = 0; i < NLD; ++i)
-            if (BM >= 64 || a_row < BM)
-                *reinterpret_cast<uint4*>(&lds[stage * kStageBytes + (a_row + 64 * i) * kLdsRow + a_col]) = t.v[i];
+        for (int g = 0; g < WK; ++g)
+#pragma unroll
+            for (int i = 0; i < NLD; ++i)
+                if (BM >= 64 || a_row < BM)
+                    *reinterpret_cast<uint4*>(&lds[stage * kStageBytes + g * kTileBytesA + (a_row + 64 * i) * kLdsRow + a_col]) =
+                        t.v[g * NLD + i];
     };
     const int op_row = lane & 31, op_g = lane >> 5;
-    const int a_read = op_row * kLdsRow + op_g * 16;
+    const int a_read = kg * kTileBytesA + op_row * kLdsRow + op_g * 16;
     // operands of one 32-k half step: MB registers quadruples
     auto lread_half = [&](int stage, int ks, v4i (&a)[MB]) {
 #pragma unroll
@@ -96,10 +118,10 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemvProblem p, const
 #pragma unroll
     for (int j = 0; j < NB; ++j)   // row blocks beyond the matrix are clamped to a valid one and dropped in the epilogue
         wp[j] = p.packed + (int64_t)min(rb0 + j, p.row_blocks - 1) * KC * kWave + lane;
-    auto wload = [&](int kc) {
+    auto wload = [&](int step_i) {
         WTiles t;
 #pragma unroll
-        for (int j = 0; j < NB; ++j) t.v[j] = wp[j][(int64_t)min(kc, KC - 1) * kWave];
+        for (int j = 0; j < NB; ++j) t.v[j] = wp[j][(int64_t)min(step_i * WK + kg, KC - 1) * kWave];
         return t;
     };
 
@@ -171,15 +193,43 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemvProblem p, const
     };
 
     int kc = 0;
-    for (; kc + 1 < KC; kc += 2) {
+    for (; kc + 1 < steps; kc += 2) {
         step(kc, a_lo0, a_lo1);
         step(kc + 1, a_lo1, a_lo0);
     }
-    if (kc < KC) step(kc, a_lo0, a_lo1);
+    if (kc < steps) step(kc, a_lo0, a_lo1);
+
+    if constexpr (WK == 2) {
+        // the two K groups swap halves of the token tile: group g keeps the 32-token blocks mb with mb % 2 == g and
+        // adds the other group's accumulators for them (the loop's last barrier has released the staging ring)
+        int* ex = reinterpret_cast<int*>(lds);
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+            if ((mb & 1) != kg) {
+#pragma unroll
+                for (int nb = 0; nb < 2 * NB; ++nb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        ex[(((wave_n * MB + mb) * 2 * NB + nb) * 16 + r) * 64 + lane] = c[mb][nb][r];
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+            if ((mb & 1) == kg) {
+#pragma unroll
+                for (int nb = 0; nb < 2 * NB; ++nb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        c[mb][nb][r] += ex[(((wave_n * MB + mb) * 2 * NB + nb) * 16 + r) * 64 + lane];
+            }
+        }
+    }
 
     // epilogue: register r of a 32x32 tile holds row 8*(r/4) + 4*(lane/32) + r%4, column lane%32
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
+        if (WK == 2 && (mb & 1) != kg) continue;   // the other K group finishes this block
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int ml = mb * 32 + 8 * (r >> 2) + 4 * op_g + (r & 3);
@@ -208,21 +258,28 @@ int g_force_mb = 0;
 void set_gemm_mb(int mb) { g_force_mb = mb; }
 
 hipError_t launch_gemm(const GemvProblem& p, int64_t M, hipStream_t s) {
-    // wave tile = (32*MB) tokens x (64*NB) weight rows; workgroup = 4 waves along N
-    // 64 x 128 wave tiles (half the LDS traffic per MFMA) when the grid still gives every CU two workgroups,
-    // else 64 x 64
+    // wave tile = (32*MB) tokens x (64*NB) weight rows; workgroup = 4 waves, 4/WK along N and WK along K.
+    // Choice by workgroup count: 64 x 128 wave tiles (half the LDS traffic per MFMA) when the grid still gives
+    // every compute unit two workgroups; 64 x 64 otherwise; and the K-split form when even that grid would
+    // leave compute units without work.  Forced value: 100*WK' + 10*MB + NB with WK' = 0 for WK = 1, 1 for WK = 2.
     const int64_t tiles_m = (M + 63) / 64;
-    int mb = 2, nb = tiles_m * ((p.row_blocks + 2 * kWavesN - 1) / (2 * kWavesN)) >= 512 ? 2 : 1;
-    if (g_force_mb) { mb = g_force_mb / 10; nb = g_force_mb % 10; }
-    const int64_t gx = (p.row_blocks + kWavesN * nb - 1) / (kWavesN * nb);
+    const auto wgs = [&](int wn, int nb) { return tiles_m * ((p.row_blocks + wn * nb - 1) / (wn * nb)); };
+    int mb = 2, nb = 1, wk = 1;
+    if (wgs(4, 2) >= 512) nb = 2;
+    else if (wgs(4, 1) < 256) wk = 2;
+    if (g_force_mb) { wk = g_force_mb / 100 + 1; mb = g_force_mb / 10 % 10; nb = g_force_mb % 10; }
+    const int wn = kWaves / wk;
+    const int64_t gx = (p.row_blocks + wn * nb - 1) / (wn * nb);
     const int64_t gy = (M + 32 * mb - 1) / (32 * mb);
     if (gy > 65535) return hipErrorInvalidValue;
     const dim3 grid((unsigned)gx, (unsigned)gy), block(256);
-    if (mb == 2 && nb == 1) gemm_kernel<2, 1><<<grid, block, 0, s>>>(p, (int)M);
-    else if (mb == 4 && nb == 1) gemm_kernel<4, 1><<<grid, block, 0, s>>>(p, (int)M);
-    else if (mb == 2 && nb == 2) gemm_kernel<2, 2><<<grid, block, 0, s>>>(p, (int)M);
-    else if (mb == 1 && nb == 2) gemm_kernel<1, 2><<<grid, block, 0, s>>>(p, (int)M);
-    else if (mb == 1 && nb == 1) gemm_kernel<1, 1><<<grid, block, 0, s>>>(p, (int)M);
+    if (wk == 2 && mb == 2 && nb == 1) gemm_kernel<2, 1, 2><<<grid, block, 0, s>>>(p, (int)M);
+    else if (wk == 2) return hipErrorInvalidValue;
+    else if (mb == 2 && nb == 1) gemm_kernel<2, 1, 1><<<grid, block, 0, s>>>(p, (int)M);
+    else if (mb == 4 && nb == 1) gemm_kernel<4, 1, 1><<<grid, block, 0, s>>>(p, (int)M);
+    else if (mb == 2 && nb == 2) gemm_kernel<2, 2, 1><<<grid, block, 0, s>>>(p, (int)M);
+    else if (mb == 1 && nb == 2) gemm_kernel<1, 2, 1><<<grid, block, 0, s>>>(p, (int)M);
+    else if (mb == 1 && nb == 1) gemm_kernel<1, 1, 1><<<grid, block, 0, s>>>(p, (int)M);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }
