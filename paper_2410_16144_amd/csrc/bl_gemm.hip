@@ -148,9 +148,43 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemvProblem p, const
     v4i a_lo0[MB], a_lo1[MB], a_hi[MB];
     lread_half(0, 0, a_lo0);
 
+    // B operands of one 32-k half step: per packed tile, after v_permlane32_swap, [0] = rows 0-31 and [1] = rows
+    // 32-63 of the tile.  They are expanded one half step AHEAD of the MFMAs that use them, so that the vector
+    // ALU work of the expansion has independent matrix work to hide under.
+    struct BOps { v4i v[NB][2]; };
+    auto unpack_half = [&](const WTiles& w, int half) {
+        BOps b;
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+            auto s = half ? __builtin_amdgcn_permlane32_swap(w.v[j].z, w.v[j].w, false, false)    // k 32..63
+                          : __builtin_amdgcn_permlane32_swap(w.v[j].x, w.v[j].y, false, false);   // k 0..31
+            b.v[j][0] = expand_codes(s[0]);
+            b.v[j][1] = expand_codes(s[1]);
+        }
+        return b;
+    };
+    auto mfma_half = [&](const v4i (&a)[MB], const BOps& b) {
+#pragma unroll
+        for (int j = 0; j < NB; ++j)
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) {
+                c[mb][2 * j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[mb], b.v[j][0], c[mb][2 * j], 0, 0, 0);
+                c[mb][2 * j + 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[mb], b.v[j][1], c[mb][2 * j + 1], 0, 0, 0);
+            }
+    };
+    // scheduling hint for one half step: each MFMA is followed by a share of the independent vector ALU work
+    auto interleave = [&]() {
+#pragma unroll
+        for (int i = 0; i < 2 * NB * MB; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                   // one MFMA
+            __builtin_amdgcn_sched_group_barrier(0x002, (16 * NB + 2 * NB * MB - 1) / (2 * NB * MB) + 1, 0);   // VALU
+        }
+    };
+    BOps b_lo = unpack_half(w_cur, 0);
+
     // One K step in two 32-k halves.  While the MFMAs of the first half run, the second half's operands are read
-    // from the current LDS stage; while the second half runs, the first-half operands of the NEXT step are read
-    // from the next stage (published by the barrier that ended the previous step).
+    // from the current LDS stage and expanded; while the second half runs, the first-half operands of the NEXT
+    // step are read from the next stage (published by the barrier that ended the previous step) and expanded.
     int st = 0;
     auto step = [&](int kc, v4i (&a_lo)[MB], v4i (&a_lo_next)[MB]) {
         const int st1 = st == kStages - 1 ? 0 : st + 1;
@@ -161,30 +195,16 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemvProblem p, const
         g1 = gload(kc + 4);
         const WTiles w_new = wload(kc + 3);
         __builtin_amdgcn_sched_barrier(0);   // keep the fetches above the MFMAs they overlap with
-#pragma unroll
-        for (int j = 0; j < NB; ++j) {
-            // after the swap: [0] = rows 0-31, [1] = rows 32-63 of the tile, k 0..31
-            auto s01 = __builtin_amdgcn_permlane32_swap(w_cur.v[j].x, w_cur.v[j].y, false, false);
-            const v4i b0 = expand_codes(s01[0]), b1 = expand_codes(s01[1]);
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb) {
-                c[mb][2 * j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a_lo[mb], b0, c[mb][2 * j], 0, 0, 0);
-                c[mb][2 * j + 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a_lo[mb], b1, c[mb][2 * j + 1], 0, 0, 0);
-            }
-        }
+        const BOps b_hi = unpack_half(w_cur, 1);
+        mfma_half(a_lo, b_lo);
+        interleave();
         __builtin_amdgcn_sched_barrier(0);
         lread_half(st1, 0, a_lo_next);
         __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int j = 0; j < NB; ++j) {
-            auto s23 = __builtin_amdgcn_permlane32_swap(w_cur.v[j].z, w_cur.v[j].w, false, false);   // k 32..63
-            const v4i b0 = expand_codes(s23[0]), b1 = expand_codes(s23[1]);
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb) {
-                c[mb][2 * j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a_hi[mb], b0, c[mb][2 * j], 0, 0, 0);
-                c[mb][2 * j + 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a_hi[mb], b1, c[mb][2 * j + 1], 0, 0, 0);
-            }
-        }
+        b_lo = unpack_half(w1, 0);
+        mfma_half(a_hi, b_hi);
+        interleave();
+        __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
         w_cur = w1;
         w1 = w2;
