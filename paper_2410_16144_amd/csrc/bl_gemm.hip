@@ -11,9 +11,9 @@
 // alternate packed tiles and add their accumulators through LDS at the end, so the workgroup tile
 // is half as wide and the grid twice as large.)  K advances one packed tile (64) per step:
 //   - activations: the (32*MB) x 64 int8 tile goes global -> registers (three steps ahead) -> LDS
-//     through a 3-stage ring (rows padded to 80 bytes so the 128-bit operand reads are
-//     bank-conflict free).  With three stages the operands of step i+1 are read from LDS while
-//     the MFMAs of step i run, and one barrier per step is enough;
+//     through a ring of stages (rows padded to 80 bytes so the 128-bit operand reads are
+//     bank-conflict free).  With at least three stages the operands of step i+1 are read from
+//     LDS while the MFMAs of step i run, and one barrier per step is enough;
 //   - weights: each wave loads its own packed 64 x 64 tile straight into registers (one 128-bit
 //     load per lane, four steps ahead).  Lane r holds row r; v_permlane32_swap regroups two 16-k
 //     pieces so that lanes 0-31 / 32-63 hold k-halves of the same 32 rows -- exactly the MFMA
@@ -21,6 +21,8 @@
 //     Weights never touch LDS and stay 2 bits wide all the way from HBM into the register file.
 // The loop body is branch-free (out-of-range rows and row blocks are clamped to valid memory and
 // their results dropped in the epilogue) so that the accumulators never leave their registers.
+#include <type_traits>
+
 #include "bl_internal.hpp"
 
 namespace bl {
@@ -35,7 +37,7 @@ constexpr int kWaves = 4;         // waves per workgroup
 #define BL_LDS_ROW 80
 #endif
 constexpr int kLdsRow = BL_LDS_ROW;   // bytes per activation row in LDS (64 + 16 pad)
-constexpr int kStages = 3;
+constexpr int kStages = 4;       // LDS ring; 4 = the period of every register ring below, so the loop unrolls by 4 without copies
 
 __device__ __forceinline__ v4i expand_codes(uint32_t word) {
     v4i r;
@@ -142,11 +144,17 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemvProblem p, const
     // steps 2..3 and weight tiles of steps 0..2 in flight
     lstore(0, gload(0));
     lstore(1, gload(1));
-    WTiles w_cur = wload(0), w1 = wload(1), w2 = wload(2);
-    Staged g0 = gload(2), g1 = gload(3);
+    // register rings, indexed by (step mod ring size) with compile-time phases: no copies when the loop advances
+    WTiles w[4];     // packed weight tiles of steps i .. i+3
+    Staged g[2];     // activation tiles of steps i+2, i+3 on their way to LDS
+    w[0] = wload(0);
+    w[1] = wload(1);
+    w[2] = wload(2);
+    g[0] = gload(2);
+    g[1] = gload(3);
     __syncthreads();
-    v4i a_lo0[MB], a_lo1[MB], a_hi[MB];
-    lread_half(0, 0, a_lo0);
+    v4i a_lo[2][MB], a_hi[MB];
+    lread_half(0, 0, a_lo[0]);
 
     // B operands of one 32-k half step: per packed tile, after v_permlane32_swap, [0] = rows 0-31 and [1] = rows
     // 32-63 of the tile.  They are expanded one half step AHEAD of the MFMAs that use them, so that the vector
@@ -180,44 +188,48 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemvProblem p, const
             __builtin_amdgcn_sched_group_barrier(0x002, (16 * NB + 2 * NB * MB - 1) / (2 * NB * MB) + 1, 0);   // VALU
         }
     };
-    BOps b_lo = unpack_half(w_cur, 0);
+    BOps b_lo = unpack_half(w[0], 0);
 
     // One K step in two 32-k halves.  While the MFMAs of the first half run, the second half's operands are read
     // from the current LDS stage and expanded; while the second half runs, the first-half operands of the NEXT
     // step are read from the next stage (published by the barrier that ended the previous step) and expanded.
-    int st = 0;
-    auto step = [&](int kc, v4i (&a_lo)[MB], v4i (&a_lo_next)[MB]) {
-        const int st1 = st == kStages - 1 ? 0 : st + 1;
-        const int st2 = st1 == kStages - 1 ? 0 : st1 + 1;
-        lstore(st2, g0);         // tile of step kc+2 (loaded two steps ago); stage st2 was last read two steps ago
+    // P = step mod 4 picks the ring slots at compile time.
+    auto step = [&](auto phase, int kc) {
+        constexpr int P = decltype(phase)::value;
+        constexpr int st = P % kStages, st1 = (P + 1) % kStages, st2 = (P + 2) % kStages;
+        lstore(st2, g[P % 2]);   // tile of step kc+2 (loaded two steps ago); stage st2 was last read two steps ago
         lread_half(st, 1, a_hi);
-        g0 = g1;
-        g1 = gload(kc + 4);
-        const WTiles w_new = wload(kc + 3);
+        g[P % 2] = gload(kc + 4);
+        w[(P + 3) % 4] = wload(kc + 3);
         __builtin_amdgcn_sched_barrier(0);   // keep the fetches above the MFMAs they overlap with
-        const BOps b_hi = unpack_half(w_cur, 1);
-        mfma_half(a_lo, b_lo);
+        const BOps b_hi = unpack_half(w[P], 1);
+        mfma_half(a_lo[P % 2], b_lo);
         interleave();
         __builtin_amdgcn_sched_barrier(0);
-        lread_half(st1, 0, a_lo_next);
+        lread_half(st1, 0, a_lo[(P + 1) % 2]);
         __builtin_amdgcn_sched_barrier(0);
-        b_lo = unpack_half(w1, 0);
+        b_lo = unpack_half(w[(P + 1) % 4], 0);
         mfma_half(a_hi, b_hi);
         interleave();
         __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
-        w_cur = w1;
-        w1 = w2;
-        w2 = w_new;
-        st = st1;
     };
+    using P0 = std::integral_constant<int, 0>;
+    using P1 = std::integral_constant<int, 1>;
+    using P2 = std::integral_constant<int, 2>;
+    using P3 = std::integral_constant<int, 3>;
+    static_assert(kStages == 4, "the unrolled loop assumes every ring has period 4");
 
     int kc = 0;
-    for (; kc + 1 < steps; kc += 2) {
-        step(kc, a_lo0, a_lo1);
-        step(kc + 1, a_lo1, a_lo0);
+    for (; kc + 4 <= steps; kc += 4) {
+        step(P0{}, kc);
+        step(P1{}, kc + 1);
+        step(P2{}, kc + 2);
+        step(P3{}, kc + 3);
     }
-    if (kc < steps) step(kc, a_lo0, a_lo1);
+    if (kc < steps) step(P0{}, kc);
+    if (kc + 1 < steps) step(P1{}, kc + 1);
+    if (kc + 2 < steps) step(P2{}, kc + 2);
 
     if constexpr (WK == 2) {
         // the two K groups swap halves of the token tile: group g keeps the 32-token blocks mb with mb % 2 == g and
