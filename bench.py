@@ -173,8 +173,19 @@ def extra_prefill(torch, M, K, N, use_graph=True, iters=100):
     tops = 2.0 * M * K * N / us / 1e6
     msq, _, _ = run_steps(torch, [lambda: ops.quant_act(x, qa)], iters, use_graph)
     usq = msq * 1e3 / iters
+    # context only: the vendor library's dense int8 x int8 -> int32 product of the same shape (weights as int8,
+    # four times the bytes, no dequantization), through torch._int_mm
+    lib_us = None
+    try:
+        a8 = qa.q[:, :K].contiguous()
+        b8 = torch.randint(-1, 2, (N, K), device=dev, dtype=torch.int8).t()
+        torch._int_mm(a8, b8)
+        msl, _, _ = run_steps(torch, [lambda: torch._int_mm(a8, b8)], iters, False)
+        lib_us = round(msl * 1e3 / iters, 2)
+    except Exception:   # not every build of the framework has it
+        pass
     return {"workload": "prefill M=%d K=%d N=%d" % (M, K, N), "gemm_us": round(us, 2), "quant_act_us": round(usq, 2),
-            "launch": mode,
+            "launch": mode, "vendor_library_dense_int8_gemm_us": lib_us,
             "roofline": {"bound": "mfma", "achieved": round(tops / 1e3, 4), "peak": INT8_PEAK_TOPS / 1e3,
                          "unit": "POP/s", "frac": round(tops / INT8_PEAK_TOPS, 4), "ops_per_launch": 2 * M * K * N},
             "tops_including_quant_act": round(2.0 * M * K * N / (us + usq) / 1e6, 1)}

@@ -133,3 +133,39 @@ def test_config5_100b_shapes_decode_m1(dev, ops, K, N, idx):
     assert np.array_equal(acc2.cpu().numpy(), acc_ref)
     _check_out(out.cpu().numpy(), acc_ref, w_scale, a_ref)
     _check_out(out2.cpu().numpy(), acc_ref, w_scale, a_ref)
+
+
+def test_config5_100b_whole_layer_fused_launch(dev, ops):
+    """Layer 0 of the 100B-shape model, all 7 matrices in the launches bench.py times (fused and
+    grouped), every output element against the oracle."""
+    _check_layer(ops, dev, 5, 12288, 33792, (1,), None, 0.0)
+
+
+@pytest.mark.parametrize("layer_index", [1, 79])
+def test_config5_100b_device_drawn_layers_sampled_rows(dev, ops, layer_index):
+    """Layers drawn on the device (as the 37 GB benchmark model is): the weights come back through
+    bl_unpack_ternary, and 64 seeded output rows per matrix plus the first and last row are checked
+    against the oracle, which computes those rows one by one."""
+    from paper_2410_16144_amd.decode_layer import INPUT_OF, make_layer
+    layer, _ = make_layer(5, layer_index, 12288, 33792, 1, dev, None, 0.0)
+    layer.step_fused()
+    torch.cuda.synchronize()
+    fused = [o.cpu().numpy().copy() for o in layer.outs]
+    for o in layer.outs:
+        o.zero_()
+    layer.step_single_launch()
+    torch.cuda.synchronize()
+    x_bits = [x.view(torch.int16).cpu().numpy().view(np.uint16) for x in layer.xs]
+    refs_q = [oracle.quant_act(b) for b in x_bits]
+    rng = synth.rng_for(synth.seed_for(5, layer_index, 8))
+    for i, p in enumerate(layer.projs):
+        q, a, s = refs_q[INPUT_OF[p.name]]
+        rows = np.unique(np.concatenate([rng.integers(0, p.N, 64), [0, p.N - 1]]))
+        w_rows = ops.unpack_ternary(layer.weights[i])[torch.from_numpy(rows).to(dev)].cpu().numpy()
+        assert set(np.unique(w_rows)) <= {-1, 0, 1}
+        acc_ref = oracle.matmul_i32(q, np.ascontiguousarray(w_rows))
+        w_scale = np.float32(layer.weights[i].desc.w_scale)
+        for got in (fused[i], layer.outs[i].cpu().numpy()):
+            _check_out(got[:, rows], acc_ref, w_scale, a)
+    del layer
+    torch.cuda.empty_cache()
