@@ -43,6 +43,7 @@ __global__ __launch_bounds__(kThreads, 8) void decode_sk_kernel(const DecodeBatc
     const int per_wave = (e - a + kWaves - 1) / kWaves;
     const int t_wave = min(a + wave * per_wave, e);            // this wave's tiles [t_wave, t_wave + mine)
     const int mine = min(per_wave, e - t_wave);
+    const int t_last = mine > 0 ? t_wave + mine - 1 : a;
     const int rb0 = a / KC, rb1 = (e - 1) / KC;                // row blocks the chunk touches
 
     int8_t* lds_q = reinterpret_cast<int8_t*>(smem);
@@ -58,8 +59,9 @@ __global__ __launch_bounds__(kThreads, 8) void decode_sk_kernel(const DecodeBatc
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             if (u >= first && u < last) {
-                const int t = t_wave + i0 + u;
-                w[u] = wp[(int64_t)(t < T ? t : T - 1) * kWave];   // clamped: always a valid tile
+                // beyond the wave's piece: its own last tile again (a cache hit, no extra traffic); a wave without
+                // tiles loads the chunk's first tile
+                w[u] = wp[(int64_t)min(t_wave + i0 + u, t_last) * kWave];
             }
         }
     };
