@@ -240,6 +240,76 @@ def extra_config1(torch, use_graph):
     return res
 
 
+class PowerSampler:
+    """Samples the board's socket power (hwmon power1_input, microwatts) from a thread while GPU work runs."""
+
+    def __init__(self, period=0.02):
+        import glob
+        import threading
+        paths = sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input"))
+        self.path = paths[0] if paths else None
+        self.period, self.samples, self._stop = period, [], threading.Event()
+        self._thread = threading.Thread(target=self._run, daemon=True)
+
+    def read(self):
+        try:
+            with open(self.path) as f:
+                return int(f.read()) / 1e6
+        except (OSError, ValueError, TypeError):
+            return None
+
+    def _run(self):
+        while not self._stop.is_set():
+            w = self.read()
+            if w is not None:
+                self.samples.append(w)
+            time.sleep(self.period)
+
+    def __enter__(self):
+        self._thread.start()
+        return self
+
+    def __exit__(self, *exc):
+        self._stop.set()
+        self._thread.join()
+
+
+def energy_per_token(torch, fns, tokens_per_replay, seconds=3.0):
+    """Section 3's energy metric on this board: mean socket power while whole tokens are decoded back to back
+    for `seconds`, times the time per token.  Returns None where the power sensor is not readable."""
+    idle = PowerSampler().read()
+    if idle is None:
+        return None
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            for f in fns:
+                f()
+    torch.cuda.synchronize()
+    g.replay()
+    torch.cuda.synchronize()
+    with PowerSampler() as ps:
+        t0 = time.perf_counter()
+        n = 0
+        while time.perf_counter() - t0 < seconds:
+            for _ in range(20):
+                g.replay()
+            torch.cuda.synchronize()
+            n += 20
+        dt = time.perf_counter() - t0
+    del g
+    if not ps.samples:
+        return None
+    watts = sum(ps.samples) / len(ps.samples)
+    per_token = dt / (n * tokens_per_replay)
+    return {"socket_power_W_mean": round(watts, 1), "socket_power_W_max": round(max(ps.samples), 1),
+            "socket_power_W_idle_before": round(idle, 1), "power_samples": len(ps.samples),
+            "ms_per_token_wall": round(per_token * 1e3, 4), "J_per_token": round(watts * per_token, 4),
+            "note": "whole-board socket power (hwmon power1_input) x wall time per token; BitLinear products only"}
+
+
 def extra_full_100b(torch, use_graph):
     """All 80 layers of the 100B-shape model resident (36.99 GB packed); one token = 80 fused launches."""
     from paper_2410_16144_amd.decode_layer import make_layer
@@ -257,6 +327,7 @@ def extra_full_100b(torch, use_graph):
         ms, _, _ = run_steps(torch, fns, 80 * 3, use_graph)
         out[label] = {"ms_per_token": round(ms / 3, 4), "GBps": round(total / (ms / 3) / 1e6, 1),
                       "frac_of_hbm_peak": round(total / (ms / 3) / 1e6 / HBM_PEAK_GBS, 4)}
+    out["energy"] = energy_per_token(torch, [l.step_fused for l in ls], 1)
     return out
 
 
