@@ -10,10 +10,13 @@
 // that grid would leave compute units idle: 2 waves along N x 2 along K, the two K groups take
 // alternate packed tiles and add their accumulators through LDS at the end, so the workgroup tile
 // is half as wide and the grid twice as large.)  K advances one packed tile (64) per step:
-//   - activations: the (32*MB) x 64 int8 tile goes global -> registers (three steps ahead) -> LDS
-//     through a ring of stages (rows padded to 80 bytes so the 128-bit operand reads are
-//     bank-conflict free).  With at least three stages the operands of step i+1 are read from
-//     LDS while the MFMAs of step i run, and one barrier per step is enough;
+//   - activations: the (32*MB) x 64 int8 tile goes from global memory STRAIGHT into LDS
+//     (global_load_lds_dwordx4: no registers, no LDS store instruction), several steps ahead, into
+//     a ring of stages.  That instruction writes lane i's 16 bytes at base + 16 i, so the LDS
+//     image is lane-linear; the 16-byte chunks of a row are XOR-swizzled by the row number (each
+//     lane simply fetches the chunk that belongs at its position) so that the 128-bit operand
+//     reads stay bank-conflict free without padding.  One barrier per step; the wait before it
+//     names exactly how many younger loads may still be in flight;
 //   - weights: each wave loads its own packed 64 x 64 tile straight into registers (one 128-bit
 //     load per lane, four steps ahead).  Lane r holds row r; v_permlane32_swap regroups two 16-k
 //     pieces so that lanes 0-31 / 32-63 hold k-halves of the same 32 rows -- exactly the MFMA
@@ -33,11 +36,6 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int kWaves = 4;         // waves per workgroup
-#ifndef BL_LDS_ROW
-#define BL_LDS_ROW 80
-#endif
-constexpr int kLdsRow = BL_LDS_ROW;   // bytes per activation row in LDS (64 + 16 pad)
-constexpr int kStages = 4;       // LDS ring; 4 = the period of every register ring below, so the loop unrolls by 4 without copies
 
 __device__ __forceinline__ v4i expand_codes(uint32_t word) {
     v4i r;
@@ -48,14 +46,19 @@ __device__ __forceinline__ v4i expand_codes(uint32_t word) {
     return r;
 }
 
+constexpr int kXcds = 8;   // workgroup i runs on accelerator die i % 8, each die with its own L2
+
 template <int MB, int NB, int WK>
-__global__ __launch_bounds__(256, 2) void gemm_kernel(const GemvProblem p, const int M) {
+__global__ __launch_bounds__(256, 2) void gemm_kernel(const GemvProblem p, const int M, const int gx) {
     static_assert(WK == 1 || (WK == 2 && MB % 2 == 0), "K groups exchange halves of the token tile");
     constexpr int WN = kWaves / WK;       // waves along N
     constexpr int BM = 32 * MB;
-    constexpr int kTileBytesA = BM * kLdsRow;
+    constexpr int kTileBytesA = BM * kTileK;        // unpadded: 64 bytes per token row
     constexpr int kStageBytes = WK * kTileBytesA;   // one activation tile per K group
-    constexpr int NLD = (BM + 63) / 64;   // 16-byte pieces each thread moves per tile (256 threads x 16 B = 64 rows)
+    constexpr int kStages = WK == 1 ? 8 : 6;        // LDS ring (6 x 8 KiB with two K groups: static LDS ends at 64 KiB)
+    constexpr int kLead = 4;                        // the tile of step i + kLead is requested during step i
+    static_assert(kStages >= kLead + 1, "a stage is rewritten only after the barrier that ended its last read");
+    static_assert(BM <= 64, "one 4 KiB slab per 256 threads");
     constexpr int kExchangeBytes = WK == 1 ? 0 : WN * MB * 2 * NB * 16 * 64 * 4;
     constexpr int kLdsBytes = kStages * kStageBytes > kExchangeBytes ? kStages * kStageBytes : kExchangeBytes;
     __shared__ __attribute__((aligned(16))) uint8_t lds[kLdsBytes];
@@ -68,52 +71,62 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemvProblem p, const
     const int KC = p.KC;
     const int steps = (KC + WK - 1) / WK;             // step i covers packed tiles WK*i .. WK*i + WK-1, one per K group
     const int wave_n = wave % WN, kg = wave / WN;     // position along N, K group
-    const int m0 = blockIdx.y * BM;
-    const int rb0 = (blockIdx.x * WN + wave_n) * NB;  // this wave's first 64-row block of W (it owns NB of them)
+    // Workgroup index -> tile, so that the die (index % 8) depends on the N position only: every die keeps ITS
+    // slice of the packed weights in its L2 for the whole launch, and consecutive workgroups (all dies) walk through
+    // the same token rows at the same time.  The grid is padded to a multiple of 8 along N.
+    const int gxh = (gx + kXcds - 1) / kXcds;
+    const int rest = blockIdx.x / kXcds;
+    const int tile_x = (rest % gxh) * kXcds + blockIdx.x % kXcds, tile_y = rest / gxh;
+    if (tile_x >= gx) return;                         // padding workgroup (uniform)
+    const int m0 = tile_y * BM;
+    const int rb0 = (tile_x * WN + wave_n) * NB;      // this wave's first 64-row block of W (it owns NB of them)
     const int64_t qs = (int64_t)KC * kTileK;          // activation row stride in bytes
     const uint8_t* qbase = reinterpret_cast<const uint8_t*>(p.q);
 
-    // global -> LDS staging: thread t moves 16 bytes at column 16*(t%4) of rows t/4 (+64)
-    const int a_row = tid >> 2, a_col = (tid & 3) * 16;
-    const uint8_t* a_src[NLD];
+    // global -> LDS: thread t fills LDS position t of the tile (16-byte units, row t/4).  Position (row, c') holds the
+    // row's chunk c = c' ^ swizzle(row), swizzle(row) = (row / 2) % 4.
+    const int a_row = tid >> 2;
+    const int a_chunk = (tid & 3) ^ ((a_row >> 1) & 3);
+    const uint8_t* a_src = qbase + (int64_t)min(m0 + a_row, M - 1) * qs + a_chunk * 16;   // clamped rows: never stored
+    const bool a_loader = BM >= 64 || wave < BM / 16;                                      // uniform per wave
+    // The request is written as assembly on purpose: the compiler treats a global->LDS load it can see as an
+    // access that may complete out of order and answers every later dependency with a wait for ALL outstanding
+    // loads, which would undo the prefetching of both operands.  Unseen, the loads still count in vmcnt, in order
+    // (this ISA has one counter for all of them); the compiler's own waits for the weight tiles then only err on
+    // the strict side, and the wait that publishes a stage is written out in publish().
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)lds;
+    auto request_tile = [&](int step_i) {
+        if (a_loader) {
+            const int stage = step_i % kStages;
 #pragma unroll
-    for (int i = 0; i < NLD; ++i) {
-        const int m = min(m0 + a_row + 64 * i, M - 1);   // clamped rows compute garbage that is never stored
-        a_src[i] = qbase + (int64_t)m * qs + a_col;
-    }
-    struct Staged { uint4 v[WK * NLD]; };   // passed by value so that it lives in registers
-    auto gload = [&](int step_i) {
-        Staged t;
-#pragma unroll
-        for (int g = 0; g < WK; ++g) {
-            const int kc = step_i * WK + g;
-            const int k = min(kc, KC - 1);
-#pragma unroll
-            for (int i = 0; i < NLD; ++i) {
-                t.v[g * NLD + i] = *reinterpret_cast<const uint4*>(a_src[i] + k * kTileK);
-                // a K group's tile beyond the last one must add nothing (only an odd tile count with WK = 2 gets here
-                // inside the loop; reads beyond the loop's end are never used)
-                if (WK > 1 && kc >= KC) t.v[g * NLD + i] = make_uint4(0, 0, 0, 0);
+            for (int g = 0; g < WK; ++g) {
+                const int k = min(step_i * WK + g, KC - 1);   // beyond the end: a valid tile, never used
+                const uint8_t* src = a_src + (int64_t)k * kTileK;
+                const uint32_t dst = lds_base + stage * kStageBytes + g * kTileBytesA + wave * 1024;   // wave-uniform
+                // M0 carries the LDS address of this instruction and of nothing else in this kernel (no other
+                // instruction here reads M0); the compiler warns that it does not track M0 across assembly
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+                asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(src) : "memory", "m0");
+#pragma clang diagnostic pop
             }
         }
-        return t;
     };
-    auto lstore = [&](int stage, const Staged t) {
-#pragma unroll
-        for (int g = 0; g < WK; ++g)
-#pragma unroll
-            for (int i = 0; i < NLD; ++i)
-                if (BM >= 64 || a_row < BM)
-                    *reinterpret_cast<uint4*>(&lds[stage * kStageBytes + g * kTileBytesA + (a_row + 64 * i) * kLdsRow + a_col]) =
-                        t.v[g * NLD + i];
+    // The barrier that ends step i publishes the tile of step i+2, requested during step i+2-kLead; every load
+    // a thread issued in the kLead-2 steps since then may still be in flight.
+    constexpr int kYounger = (kLead - 2) * (WK + NB);
+    static_assert(kYounger < 16, "fits the low vmcnt field");
+    auto publish = [&]() {
+        __builtin_amdgcn_s_waitcnt(0x0f70 | kYounger);   // vmcnt(kYounger); LDS and scalar counters untouched
+        __builtin_amdgcn_s_barrier();
     };
     const int op_row = lane & 31, op_g = lane >> 5;
-    const int a_read = kg * kTileBytesA + op_row * kLdsRow + op_g * 16;
-    // operands of one 32-k half step: MB registers quadruples
+    const int a_read = kg * kTileBytesA + op_row * kTileK + ((op_g ^ ((op_row >> 1) & 3)) * 16);
+    // operands of one 32-k half step: MB register quadruples (the second half's chunk index differs in bit 1)
     auto lread_half = [&](int stage, int ks, v4i (&a)[MB]) {
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
-            a[mb] = *reinterpret_cast<const v4i*>(&lds[stage * kStageBytes + mb * 32 * kLdsRow + a_read + ks * 32]);
+            a[mb] = *reinterpret_cast<const v4i*>(&lds[stage * kStageBytes + mb * 32 * kTileK + (a_read ^ (ks * 32))]);
     };
     struct WTiles { uint4 v[NB]; };    // by value: registers
     const uint4* wp[NB];
@@ -123,7 +136,12 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemvProblem p, const
     auto wload = [&](int step_i) {
         WTiles t;
 #pragma unroll
-        for (int j = 0; j < NB; ++j) t.v[j] = wp[j][(int64_t)min(step_i * WK + kg, KC - 1) * kWave];
+        for (int j = 0; j < NB; ++j) {
+            t.v[j] = wp[j][(int64_t)min(step_i * WK + kg, KC - 1) * kWave];
+            // a K group's tile beyond the last one must add nothing: code 0 everywhere (only an odd tile count with
+            // WK = 2 gets here inside the loop; fetches beyond the loop's end are never used)
+            if (WK > 1 && step_i * WK + kg >= KC) t.v[j] = make_uint4(0, 0, 0, 0);
+        }
         return t;
     };
 
@@ -140,19 +158,18 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemvProblem p, const
         s_scale[tid] = p.w_scale * p.a_scale[m];
         s_qsum[tid] = p.q_sum[m];
     }
-    // prologue: LDS stages 0 and 1 filled, first-half operands of step 0 in registers; activation tiles of
-    // steps 2..3 and weight tiles of steps 0..2 in flight
-    lstore(0, gload(0));
-    lstore(1, gload(1));
-    // register rings, indexed by (step mod ring size) with compile-time phases: no copies when the loop advances
-    WTiles w[4];     // packed weight tiles of steps i .. i+3
-    Staged g[2];     // activation tiles of steps i+2, i+3 on their way to LDS
-    w[0] = wload(0);
-    w[1] = wload(1);
-    w[2] = wload(2);
-    g[0] = gload(2);
-    g[1] = gload(3);
-    __syncthreads();
+    // prologue: the first weight tiles and the activation tiles of steps 0..kLead-1 requested; wait for tiles 0 and 1
+    // Register ring of packed weight tiles, steps i .. i+kWR-1, indexed by compile-time phases.  Eight deep where the
+    // registers allow: the compiler's own wait for a weight tile (it counts the weight loads it can see) then
+    // leaves the newest 6 loads in flight, which also covers the activation tiles requested since.
+    constexpr int kWR = NB == 1 ? 8 : 4;
+    WTiles w[kWR];
+#pragma unroll
+    for (int j = 0; j < kWR - 1; ++j) w[j] = wload(j);
+#pragma unroll
+    for (int j = 0; j < kLead; ++j) request_tile(j);
+    __builtin_amdgcn_s_waitcnt(0x0f70 | ((kLead - 2) * WK));   // everything but the youngest kLead-2 tiles has landed
+    __syncthreads();                                            // also publishes s_scale / s_qsum
     v4i a_lo[2][MB], a_hi[MB];
     lread_half(0, 0, a_lo[0]);
 
@@ -193,47 +210,52 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemvProblem p, const
     // One K step in two 32-k halves.  While the MFMAs of the first half run, the second half's operands are read
     // from the current LDS stage and expanded; while the second half runs, the first-half operands of the NEXT
     // step are read from the next stage (published by the barrier that ended the previous step) and expanded.
-    // P = step mod 4 picks the ring slots at compile time.
+    // P = step mod 8 picks the register-ring slots at compile time; the LDS stage index is scalar arithmetic.
     auto step = [&](auto phase, int kc) {
         constexpr int P = decltype(phase)::value;
-        constexpr int st = P % kStages, st1 = (P + 1) % kStages, st2 = (P + 2) % kStages;
-        lstore(st2, g[P % 2]);   // tile of step kc+2 (loaded two steps ago); stage st2 was last read two steps ago
+        const int st = kc % kStages, st1 = (kc + 1) % kStages;
+        request_tile(kc + kLead);
         lread_half(st, 1, a_hi);
-        g[P % 2] = gload(kc + 4);
-        w[(P + 3) % 4] = wload(kc + 3);
+        w[(P + kWR - 1) % kWR] = wload(kc + kWR - 1);
         __builtin_amdgcn_sched_barrier(0);   // keep the fetches above the MFMAs they overlap with
-        const BOps b_hi = unpack_half(w[P], 1);
+        const BOps b_hi = unpack_half(w[P % kWR], 1);
         mfma_half(a_lo[P % 2], b_lo);
         interleave();
         __builtin_amdgcn_sched_barrier(0);
         lread_half(st1, 0, a_lo[(P + 1) % 2]);
         __builtin_amdgcn_sched_barrier(0);
-        b_lo = unpack_half(w[(P + 1) % 4], 0);
+        b_lo = unpack_half(w[(P + 1) % kWR], 0);
         mfma_half(a_hi, b_hi);
         interleave();
         __builtin_amdgcn_sched_barrier(0);
-        __syncthreads();
+        publish();
     };
-    using P0 = std::integral_constant<int, 0>;
-    using P1 = std::integral_constant<int, 1>;
-    using P2 = std::integral_constant<int, 2>;
-    using P3 = std::integral_constant<int, 3>;
-    static_assert(kStages == 4, "the unrolled loop assumes every ring has period 4");
-
+#define BL_STEP(P, KC) step(std::integral_constant<int, P>{}, KC)
     int kc = 0;
-    for (; kc + 4 <= steps; kc += 4) {
-        step(P0{}, kc);
-        step(P1{}, kc + 1);
-        step(P2{}, kc + 2);
-        step(P3{}, kc + 3);
+    for (; kc + 8 <= steps; kc += 8) {
+        BL_STEP(0, kc);
+        BL_STEP(1, kc + 1);
+        BL_STEP(2, kc + 2);
+        BL_STEP(3, kc + 3);
+        BL_STEP(4, kc + 4);
+        BL_STEP(5, kc + 5);
+        BL_STEP(6, kc + 6);
+        BL_STEP(7, kc + 7);
     }
-    if (kc < steps) step(P0{}, kc);
-    if (kc + 1 < steps) step(P1{}, kc + 1);
-    if (kc + 2 < steps) step(P2{}, kc + 2);
+    if (kc < steps) BL_STEP(0, kc);
+    if (kc + 1 < steps) BL_STEP(1, kc + 1);
+    if (kc + 2 < steps) BL_STEP(2, kc + 2);
+    if (kc + 3 < steps) BL_STEP(3, kc + 3);
+    if (kc + 4 < steps) BL_STEP(4, kc + 4);
+    if (kc + 5 < steps) BL_STEP(5, kc + 5);
+    if (kc + 6 < steps) BL_STEP(6, kc + 6);
+#undef BL_STEP
 
+    __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): the tiles requested beyond the end have landed too
     if constexpr (WK == 2) {
+        __syncthreads();
         // the two K groups swap halves of the token tile: group g keeps the 32-token blocks mb with mb % 2 == g and
-        // adds the other group's accumulators for them (the loop's last barrier has released the staging ring)
+        // adds the other group's accumulators for them (the staging ring is free now)
         int* ex = reinterpret_cast<int*>(lds);
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
@@ -303,15 +325,16 @@ hipError_t launch_gemm(const GemvProblem& p, int64_t M, hipStream_t s) {
     const int wn = kWaves / wk;
     const int64_t gx = (p.row_blocks + wn * nb - 1) / (wn * nb);
     const int64_t gy = (M + 32 * mb - 1) / (32 * mb);
-    if (gy > 65535) return hipErrorInvalidValue;
-    const dim3 grid((unsigned)gx, (unsigned)gy), block(256);
-    if (wk == 2 && mb == 2 && nb == 1) gemm_kernel<2, 1, 2><<<grid, block, 0, s>>>(p, (int)M);
+    const int64_t wgs_total = (gx + kXcds - 1) / kXcds * kXcds * gy;
+    if (wgs_total > INT32_MAX) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)wgs_total), block(256);
+    const int igx = (int)gx;
+    if (wk == 2 && mb == 2 && nb == 1) gemm_kernel<2, 1, 2><<<grid, block, 0, s>>>(p, (int)M, igx);
     else if (wk == 2) return hipErrorInvalidValue;
-    else if (mb == 2 && nb == 1) gemm_kernel<2, 1, 1><<<grid, block, 0, s>>>(p, (int)M);
-    else if (mb == 4 && nb == 1) gemm_kernel<4, 1, 1><<<grid, block, 0, s>>>(p, (int)M);
-    else if (mb == 2 && nb == 2) gemm_kernel<2, 2, 1><<<grid, block, 0, s>>>(p, (int)M);
-    else if (mb == 1 && nb == 2) gemm_kernel<1, 2, 1><<<grid, block, 0, s>>>(p, (int)M);
-    else if (mb == 1 && nb == 1) gemm_kernel<1, 1, 1><<<grid, block, 0, s>>>(p, (int)M);
+    else if (mb == 2 && nb == 1) gemm_kernel<2, 1, 1><<<grid, block, 0, s>>>(p, (int)M, igx);
+    else if (mb == 2 && nb == 2) gemm_kernel<2, 2, 1><<<grid, block, 0, s>>>(p, (int)M, igx);
+    else if (mb == 1 && nb == 2) gemm_kernel<1, 2, 1><<<grid, block, 0, s>>>(p, (int)M, igx);
+    else if (mb == 1 && nb == 1) gemm_kernel<1, 1, 1><<<grid, block, 0, s>>>(p, (int)M, igx);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }
