@@ -296,8 +296,9 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemvProblem p, const
                     const int n = rb0 * kTileN + nb * 32 + op_row;   // n >= N covers padding rows and clamped row blocks
                     if (n < p.N) {
                         const int v = c[mb][nb][r] - qsum;
-                        p.out[(int64_t)m * p.N + n] = (float)v * sc;
-                        if (p.acc) p.acc[(int64_t)m * p.N + n] = v;
+                        // streaming stores: tens of MB of output must not push the operands out of L2
+                        __builtin_nontemporal_store((float)v * sc, &p.out[(int64_t)m * p.N + n]);
+                        if (p.acc) __builtin_nontemporal_store(v, &p.acc[(int64_t)m * p.N + n]);
                     }
                 }
             }
