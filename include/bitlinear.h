@@ -234,7 +234,7 @@ bl_status bl_gemm(const void *packed_dev, const bl_packed_desc *d, const int8_t 
  * changes results.  Keys: "gemv_waves" = waves of the decode kernel that share one
  * 64-row block (1, 2, 4, 8, 16; 0 = automatic); "decode_split" = work-balanced one-token launches: -1 never,
  * 0 automatic (by launch size), n = 1..8 always with n workgroups per compute unit when a
- * workspace is given and the launch has at least 32 n tiles per compute unit; "decode_path" = 0 automatic
+ * workspace is given and the launch has at least 8 tiles per workgroup; "decode_path" = 0 automatic
  * (dot-product kernel for M = 1, matrix-core kernel for M >= 2), 1 = always the
  * dot-product kernel, 2 = always the matrix-core kernel; "decode_stage" = 1 keeps the matrix-core kernel
  * from staging the quantized activations in on-chip memory (0 = stage when they fit); "gemm_mb" = wave tile of the prefill kernel as

@@ -180,19 +180,19 @@ hipError_t launch_sk(const DecodeBatch& b, size_t lds, hipStream_t s) {
 int g_split = 0;   // -1 never, 0 automatic, n > 0: n workgroups per compute unit
 int64_t g_split_launches = 0;
 
-int compute_units() {
-    static int cus = 0;
-    if (!cus) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
-            return 0;
-        cus = n;
-    }
-    return cus;
-}
-
 }  // namespace
+
+// Compute units of the current device (cached per device); 0 if the runtime cannot tell.
+int compute_unit_count() {
+    constexpr int kMaxDevices = 64;
+    static int cached[kMaxDevices];
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 0;
+    if (cached[dev] > 0) return cached[dev];
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) return 0;
+    cached[dev] = n;
+    return n;
+}
 
 void set_decode_split(int v) { g_split = v; }
 int64_t split_launches() { return g_split_launches; }
@@ -201,7 +201,7 @@ int64_t split_launches() { return g_split_launches; }
 // uses the row-block kernels): tiny launches, shapes whose chunks would touch too many row blocks.
 bool plan_decode_split(DecodeBatch& b, bool fused, int& tiles_per_wave) {
     if (g_split < 0 || !b.ws) return false;
-    const int cus = compute_units();
+    const int cus = compute_unit_count();
     if (cus <= 0) return false;
     int64_t T[BL_MAX_BATCH], total = 0;
     for (int i = 0; i < b.count; ++i) {
@@ -215,12 +215,20 @@ bool plan_decode_split(DecodeBatch& b, bool fused, int& tiles_per_wave) {
     const int64_t per_cu = total / cus;
     int mult = g_split;
     if (mult == 0) {
-        if (per_cu > 400 || per_cu < (fused ? 100 : 32)) return false;
-        mult = (!fused && per_cu <= 250) ? 2 : 1;
+        if (per_cu > 400) return false;
+        if (per_cu < (fused ? 100 : 32)) {
+            // small launches: worth it only where whole row blocks cannot even occupy every compute unit
+            int64_t row_blocks = 0;
+            for (int i = 0; i < b.count; ++i) row_blocks += b.p[i].row_blocks;
+            if (row_blocks >= cus || per_cu < 8) return false;
+            mult = 1;
+        } else {
+            mult = (!fused && per_cu <= 250) ? 2 : 1;
+        }
     }
     const int grid = cus * mult;
     if (grid > BL_MAX_SPLIT_WGS || b.count > grid) return false;
-    if (total < (int64_t)grid * kWaves * 2) return false;   // under two tiles per wave: nothing to balance
+    if (total < (int64_t)grid * 8) return false;   // under 8 tiles per workgroup: nothing to balance
     int g[BL_MAX_BATCH], used = 0;
     for (int i = 0; i < b.count; ++i) {
         g[i] = (int)(T[i] * grid / total);

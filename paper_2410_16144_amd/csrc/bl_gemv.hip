@@ -412,8 +412,25 @@ static void plan_decode(DecodeBatch& b, int tiles_per_wave) {
             while ((1 << lg) < g_force_waves) ++lg;
         }
         p.wlog2 = lg;
-        work[i] = (int64_t)(kWaves >> lg) * p.KC;   // tiles per workgroup
     }
+    // A launch with fewer workgroups than compute units is pure latency: spread it over more units by letting
+    // more waves share a row block (shorter pieces per wave, more workgroups), widest pieces first.
+    if (!g_force_waves) {
+        const int cus = compute_unit_count();
+        for (;;) {
+            int total = 0, widest = -1;
+            for (int i = 0; i < b.count; ++i) {
+                const DecodeProblem& p = b.p[i];
+                total += (p.row_blocks + (kWaves >> p.wlog2) - 1) >> (4 - p.wlog2);
+                if (p.wlog2 < 4 && (p.KC >> (p.wlog2 + 1)) >= 1 &&   // every wave keeps at least one tile
+                    (widest < 0 || (p.KC >> p.wlog2) > (b.p[widest].KC >> b.p[widest].wlog2)))
+                    widest = i;
+            }
+            if (total >= cus || widest < 0) break;
+            ++b.p[widest].wlog2;
+        }
+    }
+    for (int i = 0; i < b.count; ++i) work[i] = (int64_t)(kWaves >> b.p[i].wlog2) * b.p[i].KC;   // tiles per workgroup
     for (int i = 1; i < b.count; ++i) {   // insertion sort, stable
         const DecodeProblem p = b.p[i];
         const int64_t w = work[i];

@@ -65,6 +65,7 @@ hipError_t launch_quant(const void* x, int is_bf16, int64_t M, int64_t K, int64_
                         float* a_scale, int32_t* q_sum, hipStream_t s);
 size_t decode_lds_bytes(int M, int64_t max_Kp, bool fused);
 hipError_t launch_decode(const DecodeBatch& b, int M, bool fused, hipStream_t s);
+int compute_unit_count();   // of the current device; 0 if unknown
 bool plan_decode_split(DecodeBatch& b, bool fused, int& tiles_per_wave);   // false: the balanced form does not apply
 hipError_t launch_decode_split(const DecodeBatch& b, int tiles_per_wave, bool fused, hipStream_t s);
 hipError_t launch_gemm(const GemvProblem& p, int64_t M, hipStream_t s);
