@@ -485,6 +485,13 @@ def test_gemm_parity_every_wave_tile(dev, ops, tile):
         binding.bl_set_tuning("gemm_mb", 0)
 
 
+def test_gemm_many_token_tiles(dev, ops):
+    # more token tiles than a 16-bit grid dimension could index, ragged in every direction
+    M, N, K = 66000 + 7, 70, 100
+    w, s, x = _problem(3100, M, K, N, p_zero=0.4)
+    _assert_product(ops, dev, "gemm", w, s, x)
+
+
 def test_gemm_equals_gemv_for_small_m(dev, ops):
     w, s, x = _problem(4242, 8, 1536, 448)
     _, _, out_v, acc_v = _run_product(ops, dev, "gemv", w, s, x)
