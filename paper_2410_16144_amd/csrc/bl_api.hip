@@ -29,9 +29,9 @@ bl_status check_product_args(const void* packed, const bl_packed_desc* d, const 
     return BL_OK;
 }
 
-bl::GemvProblem make_problem(const void* packed, const bl_packed_desc* d, const int8_t* q, const float* a_scale,
+bl::GemmProblem make_problem(const void* packed, const bl_packed_desc* d, const int8_t* q, const float* a_scale,
                              const int32_t* q_sum, float* out, int32_t* acc) {
-    bl::GemvProblem p;
+    bl::GemmProblem p;
     p.packed = static_cast<const uint4*>(packed);
     p.q = reinterpret_cast<const int32_t*>(q);
     p.a_scale = a_scale;
@@ -206,7 +206,7 @@ bl_status bl_gemm(const void* packed_dev, const bl_packed_desc* d, const int8_t*
     bl_status s = check_product_args(packed_dev, d, q_dev, a_scale_dev, q_sum_dev, M, out_dev, acc_dev);
     if (s != BL_OK) return s;
     if (M > BL_MAX_GEMM_M) return BL_ERR_SHAPE;
-    bl::GemvProblem p = make_problem(packed_dev, d, q_dev, a_scale_dev, q_sum_dev, out_dev, acc_dev);
+    bl::GemmProblem p = make_problem(packed_dev, d, q_dev, a_scale_dev, q_sum_dev, out_dev, acc_dev);
     drop_stale_hip_error();
     return hip_status(bl::launch_gemm(p, M, static_cast<hipStream_t>(stream)));
 }

@@ -49,7 +49,7 @@ __device__ __forceinline__ v4i expand_codes(uint32_t word) {
 constexpr int kXcds = 8;   // workgroup i runs on accelerator die i % 8, each die with its own L2
 
 template <int MB, int NB, int WK>
-__global__ __launch_bounds__(256, 2) void gemm_kernel(const GemvProblem p, const int M, const int gx) {
+__global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmProblem p, const int M, const int gx) {
     static_assert(WK == 1 || (WK == 2 && MB % 2 == 0), "K groups exchange halves of the token tile");
     constexpr int WN = kWaves / WK;       // waves along N
     constexpr int BM = 32 * MB;
@@ -312,7 +312,7 @@ int g_force_mb = 0;
 
 void set_gemm_mb(int mb) { g_force_mb = mb; }
 
-hipError_t launch_gemm(const GemvProblem& p, int64_t M, hipStream_t s) {
+hipError_t launch_gemm(const GemmProblem& p, int64_t M, hipStream_t s) {
     // wave tile = (32*MB) tokens x (64*NB) weight rows; workgroup = 4 waves, 4/WK along N and WK along K.
     // Choice by workgroup count: 64 x 128 wave tiles (half the LDS traffic per MFMA) when the grid still gives
     // every compute unit two workgroups; 64 x 64 otherwise; and the K-split form when even that grid would

@@ -10,7 +10,10 @@
 // scalar loads and feed v_dot4_i32_i8 as scalar operands; in the fused kernel the workgroup first
 // quantizes its token row into LDS (while its first weight tiles are already in flight) and the
 // activations are LDS broadcast reads.  There is no cross-lane reduction: the G partial sums of
-// a row meet once in LDS at the end.
+// a row meet once in LDS at the end.  These are the row-block kernels: a workgroup owns whole
+// 64-row blocks and shares nothing with other workgroups.  One-token launches of medium size
+// that come with a workspace take the work-balanced kernel of bl_decode_sk.hip instead; the
+// choice is made in launch_decode below.
 //
 // Arithmetic.  Codes c = w+1 in {0,1,2} are used as they are: sum_k q*w = sum_k q*c - sum_k q.
 // A packed word holds 16 codes; masking with 0x03030303 gives four byte codes, masking with

@@ -12,8 +12,8 @@ constexpr int kTileK = BL_TILE_K;            // k per packed tile
 constexpr int kTileBytes = kTileN * kTileK / 4;  // 1 KiB: one 128-bit load per lane
 constexpr int kWave = 64;
 
-// One decode problem as the kernel sees it (all device pointers).
-struct GemvProblem {
+// One prefill product as the kernel sees it (all device pointers).
+struct GemmProblem {
     const uint4*   packed;
     const int32_t* q;        // int8 activations viewed as 32-bit words, row stride Kp/4 words
     const float*   a_scale;
@@ -68,7 +68,7 @@ hipError_t launch_decode(const DecodeBatch& b, int M, bool fused, hipStream_t s)
 int compute_unit_count();   // of the current device; 0 if unknown
 bool plan_decode_split(DecodeBatch& b, bool fused, int& tiles_per_wave);   // false: the balanced form does not apply
 hipError_t launch_decode_split(const DecodeBatch& b, int tiles_per_wave, bool fused, hipStream_t s);
-hipError_t launch_gemm(const GemvProblem& p, int64_t M, hipStream_t s);
+hipError_t launch_gemm(const GemmProblem& p, int64_t M, hipStream_t s);
 
 // Launch-shape overrides for experiments (0 = choose automatically).
 void set_gemv_waves(int waves);
@@ -77,10 +77,5 @@ void set_decode_stage(int v);     // 1: the matrix-core decode kernel never stag
 void set_decode_split(int v);     // -1 never split row blocks over workgroups, 0 automatic, n: n workgroups per compute unit
 void set_decode_path(int path);
 int64_t split_launches();        // work-balanced decode launches so far (host-side count)   // 0 automatic, 1 dot-product kernel, 2 matrix-core kernel
-
-// ---- device helpers -------------------------------------------------------------------
-
-// Four byte-wide codes (0,1,2) for k-offsets 4j..4j+3 of a packed word.
-__device__ __forceinline__ uint32_t codes_of(uint32_t word, int j) { return (word >> (2 * j)) & 0x03030303u; }
 
 }  // namespace bl
