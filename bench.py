@@ -200,8 +200,8 @@ def extra_decode_shape(torch, name, hidden, ffn, M, layers, steps, use_graph):
     pb = ls[0].packed_bytes
     res = {"workload": "%s layer decode M=%d (hidden %d, ffn %d), %d distinct layers rotated"
                        % (name, M, hidden, ffn, layers), "packed_bytes_per_layer": pb}
-    for label, attr in (("fused_1_launch", "step_fused"), ("quant_x4_plus_grouped_gemv", "step_single_launch"),
-                        ("grouped_gemv_only", None)):
+    for label, attr in (("fused_1_launch", "step_fused"), ("grouped_quant_plus_grouped_gemv", "step_two_launches"),
+                        ("quant_x4_plus_grouped_gemv", "step_single_launch"), ("grouped_gemv_only", None)):
         fns = [getattr(l, attr) if attr else l.group_all.launch for l in ls]
         for f in fns[:2]:
             f()
@@ -413,6 +413,7 @@ def main():
         extra = {}
         variants = {}
         for label, attr in (("fused_dependency_ordered_4_launches", "step_fused_dependency_ordered"),
+                            ("grouped_quant_plus_grouped_gemv", "step_two_launches"),
                             ("quant_x4_plus_grouped_gemv", "step_single_launch"),
                             ("quant_x4_plus_7_gemv_launches", "step_separate")):
             vms, _, _ = run_steps(torch, [getattr(l, attr) for l in layers], args.steps, use_graph)

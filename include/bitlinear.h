@@ -137,6 +137,26 @@ bl_status bl_unpack_ternary(const void *packed_dev, const bl_packed_desc *d, int
 bl_status bl_quant_act(const void *x_dev, bl_dtype dt, int64_t M, int64_t K, int64_t ldx,
                        int8_t *q_dev, float *a_scale_dev, int32_t *q_sum_dev, void *stream);
 
+/* One activation matrix of a grouped quantization launch: the arguments of bl_quant_act. */
+typedef struct {
+    const void *x_dev;
+    bl_dtype    dt;
+    int64_t     M, K, ldx;
+    int8_t     *q_dev;
+    float      *a_scale_dev;
+    int32_t    *q_sum_dev;    /* may be NULL */
+} bl_quant_item;
+
+/*
+ * `count` independent bl_quant_act problems (1..BL_MAX_BATCH; shapes and
+ * dtypes may differ) in ONE kernel launch: e.g. the four inputs of a decoder
+ * layer ahead of a grouped bl_gemv_batch, the sequence to prefer over the
+ * fused launch from about 4 tokens up.  Each item is validated like a
+ * bl_quant_act call; results are identical.  `items` is a host array, read
+ * during the call.  Extra error: BL_ERR_COUNT.
+ */
+bl_status bl_quant_act_batch(const bl_quant_item *items, int32_t count, void *stream);
+
 /*
  * Decode product, 1 <= M <= 8 tokens (Section 2, I2_S: codes are turned back
  * into weights in registers and a plain multiply-add GEMV follows):

@@ -28,7 +28,7 @@ BL_MAX_GEMM_M = 4194304
 # every symbol include/bitlinear.h declares
 DECLARED_SYMBOLS = (
     "bl_padded_k", "bl_padded_n", "bl_packed_desc_init", "bl_pack_ternary", "bl_unpack_ternary",
-    "bl_quant_act", "bl_gemv", "bl_gemv_batch", "bl_decode_batch", "bl_gemm", "bl_set_tuning", "bl_get_stat", "bl_status_str", "bl_last_hip_error", "bl_version",
+    "bl_quant_act", "bl_quant_act_batch", "bl_gemv", "bl_gemv_batch", "bl_decode_batch", "bl_gemm", "bl_set_tuning", "bl_get_stat", "bl_status_str", "bl_last_hip_error", "bl_version",
 )
 
 
@@ -53,6 +53,13 @@ class GemvItem(ctypes.Structure):
     _fields_ = [("packed_dev", ctypes.c_void_p), ("desc", ctypes.POINTER(PackedDesc)),
                 ("q_dev", ctypes.c_void_p), ("a_scale_dev", ctypes.c_void_p), ("q_sum_dev", ctypes.c_void_p),
                 ("out_dev", ctypes.c_void_p), ("acc_dev", ctypes.c_void_p)]
+
+
+class QuantItem(ctypes.Structure):
+    """Mirror of bl_quant_item."""
+    _fields_ = [("x_dev", ctypes.c_void_p), ("dt", ctypes.c_int), ("M", ctypes.c_int64), ("K", ctypes.c_int64),
+                ("ldx", ctypes.c_int64), ("q_dev", ctypes.c_void_p), ("a_scale_dev", ctypes.c_void_p),
+                ("q_sum_dev", ctypes.c_void_p)]
 
 
 class DecodeItem(ctypes.Structure):
@@ -89,6 +96,7 @@ def lib():
     l.bl_pack_ternary.argtypes = [vp, dp, vp, vp, vp]
     l.bl_unpack_ternary.argtypes = [vp, dp, vp, vp]
     l.bl_quant_act.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, vp, vp, vp]
+    l.bl_quant_act_batch.argtypes = [ctypes.POINTER(QuantItem), i32, vp]
     l.bl_gemv.argtypes = [vp, dp, vp, vp, vp, i64, vp, vp, vp]
     l.bl_gemv_batch.argtypes = [ctypes.POINTER(GemvItem), i32, i64, vp, vp]
     l.bl_decode_batch.argtypes = [ctypes.POINTER(DecodeItem), i32, i64, vp, vp]
@@ -100,7 +108,7 @@ def lib():
     l.bl_status_str.restype = ctypes.c_char_p
     l.bl_version.restype = ctypes.c_char_p
     l.bl_last_hip_error.restype = ctypes.c_char_p
-    for name in ("bl_packed_desc_init", "bl_pack_ternary", "bl_unpack_ternary", "bl_quant_act", "bl_gemv",
+    for name in ("bl_packed_desc_init", "bl_pack_ternary", "bl_unpack_ternary", "bl_quant_act", "bl_quant_act_batch", "bl_gemv",
                  "bl_gemv_batch", "bl_decode_batch", "bl_gemm", "bl_set_tuning"):
         getattr(l, name).restype = ctypes.c_int
     _lib = l
@@ -147,6 +155,22 @@ def bl_quant_act(x_dev: int, dtype: int, M: int, K: int, ldx: int, q_dev: int, a
                  q_sum_dev: int = 0, stream: int = 0):
     _check(lib().bl_quant_act(x_dev, dtype, M, K, ldx, q_dev, a_scale_dev, q_sum_dev or None, stream or None),
            "bl_quant_act")
+
+
+def make_quant_items(items):
+    """items: iterable of (x_dev, dtype, M, K, ldx, q_dev, a_scale_dev, q_sum_dev) -> ctypes array."""
+    items = list(items)
+    arr = (QuantItem * len(items))()
+    for i, (x, dt, M, K, ldx, q, a, s) in enumerate(items):
+        arr[i] = QuantItem(x, dt, M, K, ldx, q, a, s or None)
+    return arr
+
+
+def bl_quant_act_batch(items, stream: int = 0):
+    """items: a ctypes QuantItem array from make_quant_items (or an iterable of tuples)."""
+    if not isinstance(items, ctypes.Array):
+        items = make_quant_items(items)
+    _check(lib().bl_quant_act_batch(items, len(items), stream or None), "bl_quant_act_batch")
 
 
 def bl_gemv(packed_dev: int, desc: PackedDesc, q_dev: int, a_scale_dev: int, q_sum_dev: int, M: int,

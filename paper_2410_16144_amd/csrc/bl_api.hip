@@ -106,18 +106,46 @@ bl_status bl_unpack_ternary(const void* packed_dev, const bl_packed_desc* d, int
                                         static_cast<hipStream_t>(stream)));
 }
 
+static bl_status fill_quant_problem(const bl_quant_item& it, bl::QuantProblem& p) {
+    if (!it.x_dev || !it.q_dev || !it.a_scale_dev) return BL_ERR_NULL;
+    if (it.dt != BL_F32 && it.dt != BL_BF16) return BL_ERR_DTYPE;
+    const int64_t Kp = bl_padded_k(it.K);
+    if (it.M < 1 || it.M > INT32_MAX / 2 || Kp < 0 || it.ldx < it.K) return BL_ERR_SHAPE;
+    if (!aligned(it.x_dev, it.dt == BL_F32 ? 4 : 2) || !aligned(it.q_dev, 16) || !aligned(it.a_scale_dev, 4) ||
+        (it.q_sum_dev && !aligned(it.q_sum_dev, 4)))
+        return BL_ERR_ALIGN;
+    const bool vec = (it.K % 8 == 0) && (it.ldx % 8 == 0) && aligned(it.x_dev, 16);
+    p.x = it.x_dev;
+    p.q = it.q_dev;
+    p.a_scale = it.a_scale_dev;
+    p.q_sum = it.q_sum_dev;
+    p.ldx = it.ldx;
+    p.M = (int32_t)it.M;
+    p.K = (int32_t)it.K;
+    p.Kp = (int32_t)Kp;
+    p.flags = (it.dt == BL_BF16 ? 1 : 0) | (vec ? 2 : 0);
+    p.first_row = 0;
+    return BL_OK;
+}
+
+bl_status bl_quant_act_batch(const bl_quant_item* items, int32_t count, void* stream) {
+    if (!items) return BL_ERR_NULL;
+    if (count < 1 || count > BL_MAX_BATCH) return BL_ERR_COUNT;
+    bl::QuantBatch b;
+    memset(&b, 0, sizeof b);
+    for (int i = 0; i < count; ++i) {
+        bl_status s = fill_quant_problem(items[i], b.p[i]);
+        if (s != BL_OK) return s;
+    }
+    b.count = count;
+    drop_stale_hip_error();
+    return hip_status(bl::launch_quant(b, static_cast<hipStream_t>(stream)));
+}
+
 bl_status bl_quant_act(const void* x_dev, bl_dtype dt, int64_t M, int64_t K, int64_t ldx, int8_t* q_dev,
                        float* a_scale_dev, int32_t* q_sum_dev, void* stream) {
-    if (!x_dev || !q_dev || !a_scale_dev) return BL_ERR_NULL;
-    if (dt != BL_F32 && dt != BL_BF16) return BL_ERR_DTYPE;
-    int64_t Kp = bl_padded_k(K);
-    if (M < 1 || M > INT32_MAX / 2 || Kp < 0 || ldx < K) return BL_ERR_SHAPE;
-    if (!aligned(x_dev, dt == BL_F32 ? 4 : 2) || !aligned(q_dev, 16) || !aligned(a_scale_dev, 4) ||
-        (q_sum_dev && !aligned(q_sum_dev, 4)))
-        return BL_ERR_ALIGN;
-    drop_stale_hip_error();
-    return hip_status(bl::launch_quant(x_dev, dt == BL_BF16, M, K, ldx, Kp, q_dev, a_scale_dev, q_sum_dev,
-                                       static_cast<hipStream_t>(stream)));
+    const bl_quant_item it = {x_dev, dt, M, K, ldx, q_dev, a_scale_dev, q_sum_dev};
+    return bl_quant_act_batch(&it, 1, stream);
 }
 
 bl_status bl_gemv(const void* packed_dev, const bl_packed_desc* d, const int8_t* q_dev, const float* a_scale_dev,

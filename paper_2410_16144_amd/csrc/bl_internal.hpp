@@ -54,6 +54,23 @@ struct DecodeBatch {
     unsigned long long* ws;      // balanced form: the caller's workspace (zero between launches), or null
 };
 
+// One activation matrix of a quantization launch.
+struct QuantProblem {
+    const void* x;
+    int8_t*     q;
+    float*      a_scale;
+    int32_t*    q_sum;        // may be null
+    int64_t     ldx;
+    int32_t     M, K, Kp;
+    int32_t     flags;        // bit 0: bf16, bit 1: 128-bit vector loads allowed
+    int32_t     first_row;    // first workgroup of this matrix in the grid
+};
+
+struct QuantBatch {
+    QuantProblem p[BL_MAX_BATCH];
+    int32_t      count;
+};
+
 constexpr int kMaxDecodeLds = 128 * 1024;   // dynamic LDS ceiling of the decode kernels
 
 // Launchers (each returns the hipError_t of its launch).
@@ -61,8 +78,7 @@ hipError_t launch_pack(const int8_t* w, int64_t N, int64_t K, int64_t Np, int64_
                        int32_t* bad_count, hipStream_t s);
 hipError_t launch_unpack(const uint32_t* packed, int64_t N, int64_t K, int64_t Np, int64_t Kp, int8_t* w,
                          hipStream_t s);
-hipError_t launch_quant(const void* x, int is_bf16, int64_t M, int64_t K, int64_t ldx, int64_t Kp, int8_t* q,
-                        float* a_scale, int32_t* q_sum, hipStream_t s);
+hipError_t launch_quant(const QuantBatch& b, hipStream_t s);
 size_t decode_lds_bytes(int M, int64_t max_Kp, bool fused);
 hipError_t launch_decode(const DecodeBatch& b, int M, bool fused, hipStream_t s);
 int compute_unit_count();   // of the current device; 0 if unknown

@@ -38,6 +38,7 @@ class DecodeLayer:
         self.fused_all = ops.DecodeGroup(self.weights, in_x, self.outs)
         self.fused_dep = [ops.DecodeGroup(self.weights[a:b], in_x[a:b], self.outs[a:b])
                           for a, b in ((0, 3), (3, 4), (4, 6), (6, 7))]
+        self.quant_all = ops.QuantGroup(self.xs, self.qas)
         self.packed_bytes = sum(p.packed_bytes for p in self.projs)
 
     # -- the hot path ------------------------------------------------------------------
@@ -53,6 +54,12 @@ class DecodeLayer:
         """Four fused launches in the order a real layer's data dependencies allow."""
         for g in self.fused_dep:
             g.launch()
+
+    def step_two_launches(self):
+        """All 4 inputs quantized in one grouped launch, then all 7 products in one grouped launch:
+        the form to prefer from about 4 tokens up, where the fused launch re-quantizes too much."""
+        self.quant_all.launch()
+        self.group_all.launch()
 
     def step_single_launch(self):
         """4 activation quantizations, then all 7 products in one grouped launch."""

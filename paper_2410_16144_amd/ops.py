@@ -84,6 +84,25 @@ def quant_act(x: torch.Tensor, out: Optional[QuantAct] = None) -> QuantAct:
     return out
 
 
+class QuantGroup:
+    """A prepared grouped quantization launch (bl_quant_act_batch): up to 8 inputs, one kernel."""
+
+    def __init__(self, xs, outs=None):
+        assert 1 <= len(xs) <= B.BL_MAX_BATCH
+        self.xs = list(xs)
+        for x in self.xs:
+            assert x.is_cuda and x.dim() == 2 and x.stride(1) == 1
+        self.outs = list(outs) if outs is not None else [
+            alloc_quant(int(x.shape[0]), int(x.shape[1]), x.device) for x in self.xs]
+        self.items = B.make_quant_items(
+            (x.data_ptr(), _dtype_code(x), int(x.shape[0]), int(x.shape[1]), x.stride(0), o.q.data_ptr(),
+             o.a_scale.data_ptr(), o.q_sum.data_ptr()) for x, o in zip(self.xs, self.outs))
+
+    def launch(self):
+        B.bl_quant_act_batch(self.items, _stream())
+        return self.outs
+
+
 def _product(fn, pw: PackedWeight, qa: QuantAct, out, want_acc):
     M = qa.M
     assert qa.K == pw.K

@@ -28,6 +28,7 @@ def test_struct_layout_matches_header():
     assert ctypes.sizeof(B.PackedDesc) == 56
     assert B.PackedDesc.bytes.offset == 40 and B.PackedDesc.w_scale.offset == 48
     assert ctypes.sizeof(B.GemvItem) == 56
+    assert ctypes.sizeof(B.QuantItem) == 64 and B.QuantItem.q_dev.offset == 40
     assert ctypes.sizeof(B.DecodeItem) == 80 and B.DecodeItem.packed_dev.offset == 24
 
 
@@ -106,6 +107,14 @@ def test_argument_validation_happens_before_any_launch():
     assert lib.bl_decode_batch(B.make_decode_items([(P + 1, B.BL_BF16, 128, P, d, P, 0, 0, 0, 0)]), 1, 1, None, None) == B.BL_ERR_ALIGN
     big = B.bl_packed_desc_init(64, 65536, 1.0)    # 8 tokens x 64 KiB of activations exceed on-chip memory
     assert lib.bl_decode_batch(B.make_decode_items([(P, B.BL_BF16, 65536, P, big, P, 0, 0, 0, 0)]), 1, 8, None, None) == B.BL_ERR_SHAPE
+    # grouped quantization
+    qitems = B.make_quant_items([(P, B.BL_BF16, 1, 128, 128, P, P, P)])
+    assert lib.bl_quant_act_batch(qitems, 0, None) == B.BL_ERR_COUNT
+    assert lib.bl_quant_act_batch(qitems, 9, None) == B.BL_ERR_COUNT
+    assert lib.bl_quant_act_batch(None, 1, None) == B.BL_ERR_NULL
+    assert lib.bl_quant_act_batch(B.make_quant_items([(P, B.BL_BF16, 1, 128, 64, P, P, P)]), 1, None) == B.BL_ERR_SHAPE
+    assert lib.bl_quant_act_batch(B.make_quant_items([(P, 7, 1, 128, 128, P, P, P)]), 1, None) == B.BL_ERR_DTYPE
+    assert lib.bl_quant_act_batch(B.make_quant_items([(P, B.BL_BF16, 1, 128, 128, P + 8, P, P)]), 1, None) == B.BL_ERR_ALIGN
     # workspace alignment
     assert B.lib().bl_gemv_batch(items, 1, 1, P + 64, None) == B.BL_ERR_ALIGN
     assert lib.bl_decode_batch(ditems, 1, 1, P + 16, None) == B.BL_ERR_ALIGN

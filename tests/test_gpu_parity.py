@@ -162,6 +162,37 @@ def test_quant_act_strided_and_unaligned_input(dev, ops, bf16):
     _assert_quant_equal(qa, ref, K)
 
 
+def test_quant_act_batch_mixed_shapes_and_dtypes(dev, ops):
+    # one launch: different M, K, dtypes, a strided element-aligned view, a zero row
+    rng = synth.rng_for(321)
+    specs = [(1, 3200, True), (4, 8640, True), (3, 100, False), (8, 4096, True), (2, 520, False), (1, 64, True),
+             (5, 1000, False), (1, 11008, True)]
+    xs, refs = [], []
+    for i, (M, K, bf16) in enumerate(specs):
+        x = synth.activations(rng, M, K, outlier_frac=0.01)
+        if i == 2:
+            x[1] = 0.0
+        if bf16:
+            bits = synth.to_bf16_bits(x)
+            refs.append(oracle.quant_act(bits))
+            xs.append(_to_dev_bf16(bits, dev))
+        elif i == 4:   # strided view with an odd offset: the scalar load path
+            ldx = 777
+            full = np.zeros(M * ldx + 1, np.float32)
+            full[1:].reshape(M, ldx)[:, :K] = x
+            big = torch.from_numpy(full).to(dev)
+            xs.append(big[1:].reshape(M, ldx)[:, :K])
+            refs.append(oracle.quant_act(x))
+        else:
+            refs.append(oracle.quant_act(x))
+            xs.append(torch.from_numpy(x).to(dev))
+    grp = ops.QuantGroup(xs)
+    outs = grp.launch()
+    torch.cuda.synchronize()
+    for (M, K, _), qa, ref in zip(specs, outs, refs):
+        _assert_quant_equal(qa, ref, K)
+
+
 # ------------------------------------------------------------------ decode product
 
 def _problem(seed, M, K, N, p_zero=None, outl=0.0, bf16=True):
