@@ -168,4 +168,50 @@ __device__ __forceinline__ void quantize_row_from_regs(const Raw8<BF16>& r0, con
     __syncthreads();
 }
 
+// Copies n16 16-byte vectors from global memory straight into LDS at byte offset lds_dst (no staging
+// registers: global_load_lds_dwordx4 writes lane i's 16 bytes at base + 16 i, which for a linear copy is exactly
+// where they belong).  Asynchronous: the loads count in vmcnt like any other, in issue order; the caller waits
+// with wait_lds_copy(younger) where `younger` is the number of vector loads it has issued since, and then
+// synchronizes the workgroup.  Written as assembly because a global->LDS load the compiler can see makes it wait
+// for ALL outstanding loads at the next dependency.  M0 carries the LDS address for this instruction only.
+__device__ __forceinline__ void copy_to_lds_async(const void* src, uint32_t lds_dst, int n16, int tid, int wave) {
+    for (int i0 = 0; i0 < n16; i0 += kThreads) {
+        const int idx = i0 + tid;
+        if (idx < n16) {
+            const char* from = static_cast<const char*>(src) + (int64_t)idx * 16;
+            const uint32_t to = lds_dst + (uint32_t)(i0 + wave * kWave) * 16;   // wave-uniform
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(to), "v"(from) : "memory", "m0");
+#pragma clang diagnostic pop
+        }
+    }
+}
+
+template <int YOUNGER>
+__device__ __forceinline__ void wait_lds_copy() {
+    static_assert(YOUNGER >= 0 && YOUNGER < 16, "fits the low vmcnt field");
+    __builtin_amdgcn_s_waitcnt(0x0f70 | YOUNGER);   // vmcnt(YOUNGER); the other counters untouched
+}
+
+// ---- matrix-core operand helpers (2..8 tokens) ----------------------------------------------
+typedef int v4i __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ void regroup16(const uint4& w, uint32_t (&t)[4]) {
+    auto s02 = __builtin_amdgcn_permlane32_swap(w.x, w.z, false, false);
+    auto s13 = __builtin_amdgcn_permlane32_swap(w.y, w.w, false, false);
+    auto a = __builtin_amdgcn_permlane16_swap(s02[0], s13[0], false, false);
+    auto c = __builtin_amdgcn_permlane16_swap(s02[1], s13[1], false, false);
+    t[0] = a[0]; t[1] = a[1]; t[2] = c[0]; t[3] = c[1];
+}
+
+__device__ __forceinline__ v4i expand_codes(uint32_t word) {
+    v4i r;
+    r[0] = (int)(word & 0x03030303u);
+    r[1] = (int)((word >> 2) & 0x03030303u);
+    r[2] = (int)((word >> 4) & 0x03030303u);
+    r[3] = (int)((word >> 6) & 0x03030303u);
+    return r;
+}
+
 }  // namespace bl

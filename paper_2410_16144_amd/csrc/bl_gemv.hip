@@ -158,25 +158,6 @@ __global__ __launch_bounds__(kThreads, 8) void decode_kernel(const DecodeBatch b
 // of 16-lane blocks (two v_permlane32_swap + two v_permlane16_swap) so that lane (j, g) holds
 // k-piece g of row 16t+j: the B-operand shape for the t-th group of 16 weight rows.
 // ---------------------------------------------------------------------------------------------
-typedef int v4i __attribute__((ext_vector_type(4)));
-
-__device__ __forceinline__ void regroup16(const uint4& w, uint32_t (&t)[4]) {
-    auto s02 = __builtin_amdgcn_permlane32_swap(w.x, w.z, false, false);
-    auto s13 = __builtin_amdgcn_permlane32_swap(w.y, w.w, false, false);
-    auto a = __builtin_amdgcn_permlane16_swap(s02[0], s13[0], false, false);
-    auto c = __builtin_amdgcn_permlane16_swap(s02[1], s13[1], false, false);
-    t[0] = a[0]; t[1] = a[1]; t[2] = c[0]; t[3] = c[1];
-}
-
-__device__ __forceinline__ v4i expand_codes(uint32_t word) {
-    v4i r;
-    r[0] = (int)(word & 0x03030303u);
-    r[1] = (int)((word >> 2) & 0x03030303u);
-    r[2] = (int)((word >> 4) & 0x03030303u);
-    r[3] = (int)((word >> 6) & 0x03030303u);
-    return r;
-}
-
 constexpr int kMaxStagedBytes = 64 * 1024;            // largest activation matrix the plain matrix-core kernel copies into LDS
 constexpr int kMfmaInFlightDirect = 4;                 // ... when it is prefetched from global memory with the tiles
 constexpr int kMfmaInFlightLds = 6;                    // weight tiles in flight when the A operand is in LDS
@@ -238,22 +219,10 @@ __global__ __launch_bounds__(kThreads, 8) void decode_mfma_kernel(const DecodeBa
     };
 
     if constexpr (QMODE == 1) {
-        // activations first (loads retire in order: waiting for them leaves the weight tiles in flight)
-        const uint4* src = reinterpret_cast<const uint4*>(p.q);
-        const int n16 = M * Kp / 16;
-        constexpr int kMaxCopy = kMaxStagedBytes / 16 / kThreads;   // 16-byte vectors per thread
-        uint4 stage[kMaxCopy];
-#pragma unroll
-        for (int i = 0; i < kMaxCopy; ++i) {
-            const int idx = tid + i * kThreads;
-            stage[i] = src[idx < n16 ? idx : 0];
-        }
+        // activations first, straight into LDS (loads retire in order: waiting for them leaves the weight tiles in flight)
+        copy_to_lds_async(p.q, (uint32_t)(uintptr_t)(__attribute__((address_space(3))) int8_t*)lds_q, M * Kp / 16, tid, wave);
         load_batch(ks);
-#pragma unroll
-        for (int i = 0; i < kMaxCopy; ++i) {
-            const int idx = tid + i * kThreads;
-            if (idx < n16) reinterpret_cast<uint4*>(lds_q)[idx] = stage[i];
-        }
+        wait_lds_copy<U>();
         __syncthreads();
     } else if constexpr (!kTilesAfterQuant) {
         load_batch(ks);   // waves without a row block load (valid) block 0: no branch, exact wait counts
