@@ -311,6 +311,34 @@ def test_gemv_batch_equals_separate_calls(dev, ops):
         assert np.array_equal(grp.accs[i].cpu().numpy(), oracle.matmul_i32(np.ascontiguousarray(q_ref), w_ref))
 
 
+def test_decode_at_the_largest_k(dev, ops):
+    """K at the ABI's limit (2^20): one row block of 16384 tiles; the longest int32 sums the library allows.
+    One token with a workspace (the row block is shared by every workgroup of the balanced launch), one token
+    without, and two tokens on the matrix cores."""
+    from paper_2410_16144_amd import binding
+    K, N = binding.BL_MAX_K, 70
+    rng = synth.rng_for(3300)
+    w = synth.ternary_weights(rng, N, K)
+    w[0] = 1            # |acc| as large as it gets: sum |q|
+    w[1] = -1
+    x = synth.activations(rng, 2, K)
+    x[0] = np.abs(x[0]) + 1.0
+    pw = ops.pack_ternary(torch.from_numpy(w).to(dev), 0.02)
+    for M, use_ws in ((1, True), (1, False), (2, True)):
+        xd = torch.from_numpy(np.ascontiguousarray(x[:M])).to(dev)
+        qa = ops.quant_act(xd)
+        grp = ops.GemvGroup([pw], [qa], want_acc=True, use_workspace=use_ws)
+        grp.launch()
+        torch.cuda.synchronize()
+        q_ref, a_ref, s_ref = oracle.quant_act(np.ascontiguousarray(x[:M]))
+        _assert_quant_equal(qa, (q_ref, a_ref, s_ref), K)
+        acc_ref = oracle.matmul_i32(q_ref, w)
+        assert np.array_equal(grp.accs[0].cpu().numpy(), acc_ref)
+        assert abs(int(acc_ref[0, 0])) > 2 ** 24     # beyond exact fp32 integers: out still within tolerance
+        _check_out(grp.outs[0], acc_ref, np.float32(0.02), a_ref)
+    assert not ops.workspace(dev).any()
+
+
 # ------------------------------------------------------------------ fused decode
 
 def _assert_fused(ops, dev, problems, M):
@@ -514,6 +542,12 @@ def test_gemm_parity_every_wave_tile(dev, ops, tile):
             _assert_product(ops, dev, "gemm", w, s, x)
     finally:
         binding.bl_set_tuning("gemm_mb", 0)
+
+
+def test_gemm_long_k(dev, ops):
+    M, N, K = 70, 130, 65536 + 64     # 1025 K steps (odd: the K-split form pads one group), ragged M and N
+    w, s, x = _problem(3200, M, K, N, p_zero=0.4, outl=0.01)
+    _assert_product(ops, dev, "gemm", w, s, x)
 
 
 def test_gemm_many_token_tiles(dev, ops):
