@@ -40,7 +40,7 @@ def parse_args():
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
     ap.add_argument("--full-100b", action="store_true",
                     help="extra: build all 80 layers of the 100B-shape model (37 GB packed) and time a whole token")
-    ap.add_argument("--only", default="", help="run only one extra section (copy|prefill|decode7b|decode100b|paper100b|config1) and print it")
+    ap.add_argument("--only", default="", help="run only one extra section (copy|prefill|decode7b|decode100b|paper100b|config1|appendixa) and print it")
     return ap.parse_args()
 
 
@@ -311,6 +311,37 @@ def energy_per_token(torch, fns, tokens_per_replay, seconds=3.0):
             "note": "whole-board socket power (hwmon power1_input) x wall time per token; BitLinear products only"}
 
 
+def extra_appendix_a(torch, use_graph):
+    """Token rate of the BitLinear products alone on the 12 model shapes of Appendix A (the paper's own unit,
+    tokens/s, on dummy weights as in the paper): one token = n_layers x 7 GEMVs with their 4 quantizations, timed
+    (a) as one fused launch per layer and (b) as the four fused launches a real layer's data dependencies allow
+    (QKV, O, gate/up, down).  Attention, norms and sampling are not part of this build and not in the figure."""
+    from paper_2410_16144_amd import synth
+    from paper_2410_16144_amd.decode_layer import make_layer
+    dev = torch.device("cuda:0")
+    rows = []
+    for name, (hidden, ffn, n_layers) in synth.PAPER_MODELS.items():
+        layer_bytes = sum(p.packed_bytes for p in synth.layer_projections(hidden, ffn))
+        count = max(2, min(n_layers, (1 << 30) // layer_bytes + 1))
+        ls = [make_layer(6, i, hidden, ffn, 1, dev, None, 0.0)[0] for i in range(count)]
+        steps = max(4 * count, 200)
+        row = {"model": name, "hidden": hidden, "ffn": ffn, "layers": n_layers, "packed_GB": round(layer_bytes * n_layers / 1e9, 3),
+               "distinct_layers_rotated": count}
+        for label, attr in (("one_launch_per_layer", "step_fused"), ("dependency_ordered", "step_fused_dependency_ordered")):
+            fns = [getattr(l, attr) for l in ls]
+            for f in fns[:2]:
+                f()
+            ms, _, _ = run_steps(torch, fns, steps, use_graph)
+            us = ms * 1e3 / steps
+            row[label] = {"us_per_layer": round(us, 2), "ms_per_token": round(us * n_layers / 1e3, 4),
+                          "tokens_per_s": round(1e6 / (us * n_layers), 1),
+                          "GBps": round(layer_bytes / us / 1e3, 1)}
+        rows.append(row)
+        del ls
+        torch.cuda.empty_cache()
+    return rows
+
+
 def extra_full_100b(torch, use_graph):
     """All 80 layers of the 100B-shape model resident (36.99 GB packed); one token = 80 fused launches."""
     from paper_2410_16144_amd.decode_layer import make_layer
@@ -366,6 +397,7 @@ def main():
                 "decode100b": lambda: extra_decode_shape(torch, "100B-shape", 12288, 33792, 1, 6, 120, use_graph),
                 "paper100b": lambda: extra_decode_shape(torch, "Appendix-A 100B", 8192, 45568, 1, 6, 120, use_graph),
                 "config1": lambda: extra_config1(torch, use_graph),
+                "appendixa": lambda: extra_appendix_a(torch, use_graph),
                 }[args.only]()
         print(json.dumps({args.only: sect}))
         return
