@@ -77,5 +77,24 @@ def build(force: bool = True, extra_flags=(), verbose: bool = False) -> str:
     return LIB
 
 
+ABI_CHECK_SRC = os.path.join(os.path.dirname(HERE), "tests", "c_abi", "abi_check.c")
+ABI_CHECK_BIN = os.path.join(os.path.dirname(HERE), "tests", "c_abi", "abi_check")
+
+
+def build_abi_check() -> str:
+    """Compile the plain-C host program of tests/c_abi with gcc and link it against the library:
+    proof that include/bitlinear.h is C, and a caller of the boundary with no Python in between.
+    It runs without PyTorch, so it takes the HIP runtime of the ROCm installation (same SONAME as
+    the one the library was linked against)."""
+    tmp = ABI_CHECK_BIN + ".tmp.%d" % os.getpid()
+    subprocess.check_call(["gcc", "-std=c11", "-O1", "-Wall", "-D__HIP_PLATFORM_AMD__", "-I", "/opt/rocm/include",
+                           "-I", INCLUDE, ABI_CHECK_SRC, "-o", tmp, "-L", HERE, "-lbitlinear",
+                           "-L", "/opt/rocm/lib", "-lamdhip64",
+                           "-Wl,-rpath,$ORIGIN/../../paper_2410_16144_amd", "-Wl,-rpath,/opt/rocm/lib"])
+    os.replace(tmp, ABI_CHECK_BIN)
+    return ABI_CHECK_BIN
+
+
 if __name__ == "__main__":
     print(build(force=True, verbose=True))
+    print(build_abi_check())
