@@ -133,38 +133,64 @@ __device__ __forceinline__ void quantize_rows_to_lds(const DecodeProblem& p, int
 // One token whose row fits two 8-element vectors per thread (K <= 16384, vector-loadable): the raw
 // inputs are loaded by the caller BEFORE the weight tiles (loads retire in order, so waiting for x
 // then leaves the 8 weight loads in flight) and stay in registers between the two passes.
+//
+// The row is held by as FEW leading waves as can hold it with two vectors per thread: the waves of a
+// workgroup issue their loads one after another, so the row's loads are at the head of the compute unit's
+// queue only if they come from its first waves; a load issued by wave 12 waits behind the weight tiles of
+// waves 0-11, and the whole workgroup waits for it at the quantizer's first barrier.
+__device__ __forceinline__ int row_threads(int K) {   // multiple of 64
+    return min(kThreads, (((K + 7) / 8 + 1) / 2 + kWave - 1) / kWave * kWave);
+}
+
+// First half, run by the waves that hold the row: this wave's absolute maximum to s_f[wave].  A workgroup barrier
+// follows (every wave takes it).
 template <bool BF16>
-__device__ __forceinline__ void quantize_row_from_regs(const Raw8<BF16>& r0, const Raw8<BF16>& r1, bool h0, bool h1,
-                                                       int K, int Kp, int8_t* lds_q, float* s_f, int* s_i, int tid,
-                                                       int lane, int wave) {
-    float am;
-    {
-        float v[8];
-        unpack_raw8<BF16>(r0, v);
-        am = h0 ? absmax8(v) : 0.0f;
-        unpack_raw8<BF16>(r1, v);
-        am = fmaxf(am, h1 ? absmax8(v) : 0.0f);
-    }
+__device__ __forceinline__ void row_absmax_to_lds(const Raw8<BF16>& r0, const Raw8<BF16>& r1, bool h0, bool h1,
+                                                  float* s_f, int lane, int wave) {
+    float v[8];
+    unpack_raw8<BF16>(r0, v);
+    float am = h0 ? absmax8(v) : 0.0f;
+    unpack_raw8<BF16>(r1, v);
+    am = fmaxf(am, h1 ? absmax8(v) : 0.0f);
     am = wave_max(am);
     if (lane == 0) s_f[wave] = am;
-    __syncthreads();
-    am = s_f[0];
-#pragma unroll
-    for (int w = 1; w < kWaves; ++w) am = fmaxf(am, s_f[w]);
+}
+
+// Second half, run by the same waves after that barrier: the row's int8 values to lds_q (the padding up to Kp
+// included), this wave's part of sum(q) to s_i[wave], the scale to s_f[kWaves].  Another barrier follows.
+template <bool BF16>
+__device__ __forceinline__ void row_quantize_to_lds(const Raw8<BF16>& r0, const Raw8<BF16>& r1, bool h0, bool h1,
+                                                    int k0, int k1, int holders, int K, int Kp, int8_t* lds_q,
+                                                    float* s_f, int* s_i, int tid, int lane, int wave) {
+    float am = s_f[0];
+    for (int w = 1; w < holders / kWave; ++w) am = fmaxf(am, s_f[w]);
     float inv, scale;
     quant_scales(am, inv, scale);
     int sum = 0;
-    {
-        float v[8];
-        unpack_raw8<BF16>(r0, v);
-        if (h0) sum += quantize8(v, inv, lds_q + tid * 8);
-        unpack_raw8<BF16>(r1, v);
-        if (h1) sum += quantize8(v, inv, lds_q + (tid + kThreads) * 8);
-    }
-    for (int k = K + tid; k < Kp; k += kThreads) lds_q[k] = 0;
+    float v[8];
+    unpack_raw8<BF16>(r0, v);
+    if (h0) sum += quantize8(v, inv, lds_q + k0);
+    unpack_raw8<BF16>(r1, v);
+    if (h1) sum += quantize8(v, inv, lds_q + k1);
+    for (int k = K + tid; k < Kp; k += holders) lds_q[k] = 0;
     sum = wave_sum(sum);
     if (tid == 0) s_f[kWaves] = scale;
     if (lane == 0) s_i[wave] = sum;
+}
+
+// Both halves with their barriers, for a caller whose waves all arrive together.  Only the waves that hold the
+// row run the arithmetic; the others go from barrier to barrier: the waves of a compute unit share four
+// instruction issuers, so sixteen waves stepping through the quantizer's few hundred instructions cost four
+// times what four waves do.  Afterwards sum(q) = s_i[0] + ... + s_i[kWaves - 1].
+template <bool BF16>
+__device__ __forceinline__ void quantize_row_from_regs(const Raw8<BF16>& r0, const Raw8<BF16>& r1, bool h0, bool h1,
+                                                       int k0, int k1, int holders, int K, int Kp, int8_t* lds_q,
+                                                       float* s_f, int* s_i, int tid, int lane, int wave) {
+    const bool holder = wave * kWave < holders;   // uniform per wave
+    if (holder) row_absmax_to_lds<BF16>(r0, r1, h0, h1, s_f, lane, wave);
+    __syncthreads();
+    if (holder) row_quantize_to_lds<BF16>(r0, r1, h0, h1, k0, k1, holders, K, Kp, lds_q, s_f, s_i, tid, lane, wave);
+    else if (lane == 0) s_i[wave] = 0;
     __syncthreads();
 }
 

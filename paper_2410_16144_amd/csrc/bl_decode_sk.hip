@@ -77,21 +77,36 @@ __global__ __launch_bounds__(kThreads, 8) void decode_sk_kernel(const DecodeBatc
         __syncthreads();   // red is zero before the first deposit
     } else {
         const bool vec = p.x_flags & 2;
+        int holding_waves = kWaves;   // waves with a part of sum(q)
         if (vec && p.K <= 2 * kThreads * 8) {
-            // raw activations first: loads retire in order, so the quantizer's wait leaves the tiles in flight
-            const int k0 = tid * 8, k1 = k0 + kThreads * 8;
-            const bool h0 = k0 < p.K, h1 = k1 < p.K;
-            const Raw8<XBF16> r0 = load_raw8<XBF16>(p.x, h0 ? k0 : 0), r1 = load_raw8<XBF16>(p.x, h1 ? k1 : 0);
-            load_part(0, 0, kEarly);
-            quantize_row_from_regs<XBF16>(r0, r1, h0, h1, p.K, Kp, lds_q, s_f, s_i, tid, lane, wave);
-            load_part(0, kEarly, U);
+            // The token row lives in the registers of the workgroup's leading waves (two vectors per thread).  Those
+            // waves ask for it first (loads retire in order, so their wait for it leaves the tiles that follow in
+            // flight).  The other waves have no part in the quantizer: they take its first barrier before they
+            // queue up their own tile loads, so that it is not held up by requests that wait for room in the
+            // compute unit's load queue, and then request all their tiles at once.  Two barriers on either path.
+            holding_waves = row_threads(p.K) / kWave;
+            if (wave < holding_waves) {
+                const int holders = holding_waves * kWave;
+                const int k0 = tid * 8, k1 = k0 + holders * 8;
+                const bool h0 = k0 < p.K, h1 = k1 < p.K;
+                const Raw8<XBF16> r0 = load_raw8<XBF16>(p.x, h0 ? k0 : 0), r1 = load_raw8<XBF16>(p.x, h1 ? k1 : 0);
+                load_part(0, 0, kEarly);
+                row_absmax_to_lds<XBF16>(r0, r1, h0, h1, s_f, lane, wave);
+                __syncthreads();
+                row_quantize_to_lds<XBF16>(r0, r1, h0, h1, k0, k1, holders, p.K, Kp, lds_q, s_f, s_i, tid, lane, wave);
+                __syncthreads();
+                load_part(0, kEarly, U);
+            } else {
+                __syncthreads();
+                load_batch(0);
+                __syncthreads();
+            }
         } else {
             if (vec) quantize_rows_to_lds<1, XBF16, true>(p, lds_q, s_f, s_i, tid, lane, wave);
             else quantize_rows_to_lds<1, XBF16, false>(p, lds_q, s_f, s_i, tid, lane, wave);
             load_batch(0);
         }
-#pragma unroll
-        for (int w16 = 0; w16 < kWaves; ++w16) qsum += s_i[w16];
+        for (int w16 = 0; w16 < holding_waves; ++w16) qsum += s_i[w16];
         scale = s_f[kWaves];
         if (blk == p.first_wg) {   // optional copy-out of the quantizer's results
             if (p.q_out) {

@@ -59,7 +59,7 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmProblem p, const
     constexpr int kLead = 4;                        // the tile of step i + kLead is requested during step i
     static_assert(kStages >= kLead + 1, "a stage is rewritten only after the barrier that ended its last read");
     static_assert(BM <= 64, "one 4 KiB slab per 256 threads");
-    constexpr int kExchangeBytes = WK == 1 ? 0 : WN * MB * 2 * NB * 16 * 64 * 4;
+    constexpr int kExchangeBytes = WK == 1 ? 0 : WN * (MB / 2) * 2 * NB * 16 * 64 * 4;   // one direction at a time
     constexpr int kLdsBytes = kStages * kStageBytes > kExchangeBytes ? kStages * kStageBytes : kExchangeBytes;
     __shared__ __attribute__((aligned(16))) uint8_t lds[kLdsBytes];
     __shared__ float s_scale[BM];   // w_scale * a_scale[m] of the workgroup's tokens (read in the epilogue)
@@ -253,29 +253,31 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmProblem p, const
 
     __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): the tiles requested beyond the end have landed too
     if constexpr (WK == 2) {
-        __syncthreads();
         // the two K groups swap halves of the token tile: group g keeps the 32-token blocks mb with mb % 2 == g and
-        // adds the other group's accumulators for them (the staging ring is free now)
+        // adds the other group's accumulators for them (the staging ring is free now).  One direction at a time, so
+        // that the exchange area is half as large.
         int* ex = reinterpret_cast<int*>(lds);
 #pragma unroll
-        for (int mb = 0; mb < MB; ++mb) {
-            if ((mb & 1) != kg) {
+        for (int dir = 0; dir < 2; ++dir) {   // dir = the K group that receives
+            __syncthreads();
+            if (kg != dir) {
 #pragma unroll
-                for (int nb = 0; nb < 2 * NB; ++nb)
+                for (int mb = dir; mb < MB; mb += 2)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        ex[(((wave_n * MB + mb) * 2 * NB + nb) * 16 + r) * 64 + lane] = c[mb][nb][r];
+                    for (int nb = 0; nb < 2 * NB; ++nb)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r)
+                            ex[(((wave_n * (MB / 2) + mb / 2) * 2 * NB + nb) * 16 + r) * 64 + lane] = c[mb][nb][r];
             }
-        }
-        __syncthreads();
+            __syncthreads();
+            if (kg == dir) {
 #pragma unroll
-        for (int mb = 0; mb < MB; ++mb) {
-            if ((mb & 1) == kg) {
+                for (int mb = dir; mb < MB; mb += 2)
 #pragma unroll
-                for (int nb = 0; nb < 2 * NB; ++nb)
+                    for (int nb = 0; nb < 2 * NB; ++nb)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        c[mb][nb][r] += ex[(((wave_n * MB + mb) * 2 * NB + nb) * 16 + r) * 64 + lane];
+                        for (int r = 0; r < 16; ++r)
+                            c[mb][nb][r] += ex[(((wave_n * (MB / 2) + mb / 2) * 2 * NB + nb) * 16 + r) * 64 + lane];
             }
         }
     }
@@ -331,6 +333,7 @@ hipError_t launch_gemm(const GemmProblem& p, int64_t M, hipStream_t s) {
     const dim3 grid((unsigned)wgs_total), block(256);
     const int igx = (int)gx;
     if (wk == 2 && mb == 2 && nb == 1) gemm_kernel<2, 1, 2><<<grid, block, 0, s>>>(p, (int)M, igx);
+    else if (wk == 2 && mb == 2 && nb == 2) gemm_kernel<2, 2, 2><<<grid, block, 0, s>>>(p, (int)M, igx);
     else if (wk == 2) return hipErrorInvalidValue;
     else if (mb == 2 && nb == 1) gemm_kernel<2, 1, 1><<<grid, block, 0, s>>>(p, (int)M, igx);
     else if (mb == 2 && nb == 2) gemm_kernel<2, 2, 1><<<grid, block, 0, s>>>(p, (int)M, igx);

@@ -75,14 +75,19 @@ __global__ __launch_bounds__(kThreads, 8) void decode_kernel(const DecodeBatch b
         if constexpr (M == 1) fast = vec && p.K <= 2 * kThreads * 8;   // uniform
         if (fast) {
             if constexpr (M == 1) {
-                const int k0 = tid * 8, k1 = k0 + kThreads * 8;
-                const bool h0 = k0 < p.K, h1 = k1 < p.K;
-                const Raw8<XBF16> r0 = load_raw8<XBF16>(p.x, h0 ? k0 : 0), r1 = load_raw8<XBF16>(p.x, h1 ? k1 : 0);
+                const int holders = row_threads(p.K);
+                const int k0 = tid * 8, k1 = k0 + holders * 8;
+                const bool h0 = tid < holders && k0 < p.K, h1 = tid < holders && k1 < p.K;
+                Raw8<XBF16> r0 = {}, r1 = {};
+                if (tid < holders) {   // uniform per wave
+                    r0 = load_raw8<XBF16>(p.x, h0 ? k0 : 0);
+                    r1 = load_raw8<XBF16>(p.x, h1 ? k1 : 0);
+                }
                 // half of the weight tiles go in flight behind the activations (loads retire in order, so the
                 // quantizer's wait for x leaves them outstanding); the other half follows the quantizer, which
                 // keeps its register footprint small
                 load_part(ks, 0, kInFlight / 2);
-                quantize_row_from_regs<XBF16>(r0, r1, h0, h1, p.K, Kp, lds_q, s_f, s_i, tid, lane, wave);
+                quantize_row_from_regs<XBF16>(r0, r1, h0, h1, k0, k1, holders, p.K, Kp, lds_q, s_f, s_i, tid, lane, wave);
                 load_part(ks, kInFlight / 2, kInFlight);
             }
         } else {
