@@ -88,10 +88,10 @@ hipError_t launch_gemm(const GemmProblem& p, int64_t M, hipStream_t s);
 
 // Launch-shape overrides for experiments (0 = choose automatically).
 void set_gemv_waves(int waves);
-void set_gemm_mb(int mb);         // 0 automatic, 2 = 64-token tiles, 4 = 128-token tiles
+void set_gemm_mb(int mb);         // 0 automatic, else 100*(WK-1) + 10*MB + NB (see launch_gemm)
 void set_decode_stage(int v);     // 1: the matrix-core decode kernel never stages activations in LDS
 void set_decode_split(int v);     // -1 never split row blocks over workgroups, 0 automatic, n: n workgroups per compute unit
-void set_decode_path(int path);
-int64_t split_launches();        // work-balanced decode launches so far (host-side count)   // 0 automatic, 1 dot-product kernel, 2 matrix-core kernel
+void set_decode_path(int path);   // 0 automatic, 1 dot-product kernel, 2 matrix-core kernel
+int64_t split_launches();         // work-balanced decode launches so far (host-side count)
 
 }  // namespace bl
