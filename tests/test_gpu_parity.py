@@ -497,6 +497,19 @@ def test_split_decode_single_matrix(dev, ops, decode_split, n, N, K, bf16):
     _assert_split(ops, dev, [_problem(N + 3 * K + n, 1, K, N, p_zero=0.4, outl=0.01, bf16=bf16)], True)
 
 
+@pytest.mark.parametrize("bf16", [True, False])
+@pytest.mark.parametrize("N,K", [(8197, 1016), (8200, 1024), (8200, 1032),   # one wave holds the row / just not
+                                 (4100, 2056), (1300, 8192 + 8),            # 3 and 9 holding waves
+                                 (700, 16384),                              # all 16 waves hold it, both vectors full
+                                 (700, 16384 + 8)])                         # one vector too long: the two-pass quantizer
+def test_fused_decode_row_holder_boundaries(dev, ops, decode_split, N, K, bf16):
+    # the fused one-token kernels keep the token row in the registers of as few leading waves as can hold it;
+    # the cases sit on both sides of every change in that number, in the balanced and (inside _assert_split, without
+    # a workspace) the row-block kernel
+    decode_split(1)
+    _assert_split(ops, dev, [_problem(3 * N + K, 1, K, N, p_zero=0.4, outl=0.01, bf16=bf16)], True)
+
+
 @pytest.mark.parametrize("n", [1, 2])
 def test_split_decode_batch_mixed_shapes(dev, ops, decode_split, n):
     decode_split(n)
