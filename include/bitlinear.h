@@ -258,7 +258,7 @@ bl_status bl_gemm(const void *packed_dev, const bl_packed_desc *d, const int8_t 
  * (dot-product kernel for M = 1, matrix-core kernel for M >= 2), 1 = always the
  * dot-product kernel, 2 = always the matrix-core kernel; "decode_stage" = 1 keeps the matrix-core kernel
  * from staging the quantized activations in on-chip memory (0 = stage when they fit); "gemm_mb" = wave tile of the prefill kernel as
- * 10*MB + NB, i.e. (32*MB) tokens x (64*NB) weight rows: 11, 12, 21, 22, or 121 / 122 for the K-split forms of 21 / 22 (0 = automatic).  Errors: BL_ERR_NULL, BL_ERR_SHAPE (unknown key/value).
+ * 10*MB + H, i.e. (32*MB) tokens x (32*H) weight rows: 12, 14, 22, 23, 24, or 122 / 124 for the K-split forms of 22 / 24 (0 = automatic).  Errors: BL_ERR_NULL, BL_ERR_SHAPE (unknown key/value).
  */
 bl_status bl_set_tuning(const char *key, int32_t value);
 

@@ -268,7 +268,7 @@ bl_status bl_set_tuning(const char* key, int32_t value) {
         return BL_OK;
     }
     if (strcmp(key, "gemm_mb") == 0) {
-        if (value != 0 && value != 11 && value != 12 && value != 21 && value != 22 && value != 121 && value != 122)
+        if (value != 0 && value != 12 && value != 14 && value != 22 && value != 23 && value != 24 && value != 122 && value != 124)
             return BL_ERR_SHAPE;
         bl::set_gemm_mb(value);
         return BL_OK;

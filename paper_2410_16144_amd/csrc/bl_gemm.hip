@@ -5,8 +5,11 @@
 // v_mfma_i32_32x32x32_i8:  D[m][n] += sum_k A[m][k] * B[k][n],  A = int8 activations,
 // B = weight codes (w+1) as int8; sum_k q is subtracted in the epilogue.
 //
-// Tiling.  Workgroup = 4 waves side by side along N = (32*MB) tokens x (256*NB) weight rows; each
-// wave owns (32*MB) x (64*NB), i.e. MB x 2NB MFMA tiles.  (Variant WK = 2 for small M x N, where
+// Tiling.  Workgroup = 4 waves side by side along N = (32*MB) tokens x (128*H) weight rows; each
+// wave owns (32*MB) x (32*H), i.e. MB x H MFMA tiles, H = 2, 3 or 4.  (With H = 3 a wave's 96 rows are one
+// packed 64-row tile and half of another, which it shares with its neighbour: both load it, each expands
+// its own half.  The form exists for its workgroup count: where 128-row wave tiles would leave the last
+// round of workgroups mostly empty, 96-row tiles fill it.)  (Variant WK = 2 for small M x N, where
 // that grid would leave compute units idle: 2 waves along N x 2 along K, the two K groups take
 // alternate packed tiles and add their accumulators through LDS at the end, so the workgroup tile
 // is half as wide and the grid twice as large.)  K advances one packed tile (64) per step:
@@ -48,9 +51,11 @@ __device__ __forceinline__ v4i expand_codes(uint32_t word) {
 
 constexpr int kXcds = 8;   // workgroup i runs on accelerator die i % 8, each die with its own L2
 
-template <int MB, int NB, int WK>
+template <int MB, int H, int WK>
 __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmProblem p, const int M, const int gx) {
     static_assert(WK == 1 || (WK == 2 && MB % 2 == 0), "K groups exchange halves of the token tile");
+    static_assert(H >= 2 && H <= 4, "32-row blocks per wave");
+    constexpr int NT = (H + 1) / 2;       // packed 64-row tiles a wave loads per step
     constexpr int WN = kWaves / WK;       // waves along N
     constexpr int BM = 32 * MB;
     constexpr int kTileBytesA = BM * kTileK;        // unpadded: 64 bytes per token row
@@ -59,7 +64,7 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmProblem p, const
     constexpr int kLead = 4;                        // the tile of step i + kLead is requested during step i
     static_assert(kStages >= kLead + 1, "a stage is rewritten only after the barrier that ended its last read");
     static_assert(BM <= 64, "one 4 KiB slab per 256 threads");
-    constexpr int kExchangeBytes = WK == 1 ? 0 : WN * (MB / 2) * 2 * NB * 16 * 64 * 4;   // one direction at a time
+    constexpr int kExchangeBytes = WK == 1 ? 0 : WN * (MB / 2) * H * 16 * 64 * 4;   // one direction at a time
     constexpr int kLdsBytes = kStages * kStageBytes > kExchangeBytes ? kStages * kStageBytes : kExchangeBytes;
     __shared__ __attribute__((aligned(16))) uint8_t lds[kLdsBytes];
     __shared__ float s_scale[BM];   // w_scale * a_scale[m] of the workgroup's tokens (read in the epilogue)
@@ -79,7 +84,9 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmProblem p, const
     const int tile_x = (rest % gxh) * kXcds + blockIdx.x % kXcds, tile_y = rest / gxh;
     if (tile_x >= gx) return;                         // padding workgroup (uniform)
     const int m0 = tile_y * BM;
-    const int rb0 = (tile_x * WN + wave_n) * NB;      // this wave's first 64-row block of W (it owns NB of them)
+    const int row0 = (tile_x * WN + wave_n) * H * 32; // this wave's first row of W
+    const int rb0 = row0 / kTileN;                    // the packed tile that row lies in
+    const uint32_t upper_mask = (H % 2 != 0 && (row0 / 32) % 2 != 0) ? ~0u : 0u;   // uniform: the wave's rows start in the tile's upper half
     const int64_t qs = (int64_t)KC * kTileK;          // activation row stride in bytes
     const uint8_t* qbase = reinterpret_cast<const uint8_t*>(p.q);
 
@@ -114,7 +121,7 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmProblem p, const
     };
     // The barrier that ends step i publishes the tile of step i+2, requested during step i+2-kLead; every load
     // a thread issued in the kLead-2 steps since then may still be in flight.
-    constexpr int kYounger = (kLead - 2) * (WK + NB);
+    constexpr int kYounger = (kLead - 2) * (WK + NT);
     static_assert(kYounger < 16, "fits the low vmcnt field");
     auto publish = [&]() {
         __builtin_amdgcn_s_waitcnt(0x0f70 | kYounger);   // vmcnt(kYounger); LDS and scalar counters untouched
@@ -128,15 +135,15 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmProblem p, const
         for (int mb = 0; mb < MB; ++mb)
             a[mb] = *reinterpret_cast<const v4i*>(&lds[stage * kStageBytes + mb * 32 * kTileK + (a_read ^ (ks * 32))]);
     };
-    struct WTiles { uint4 v[NB]; };    // by value: registers
-    const uint4* wp[NB];
+    struct WTiles { uint4 v[NT]; };    // by value: registers
+    const uint4* wp[NT];
 #pragma unroll
-    for (int j = 0; j < NB; ++j)   // row blocks beyond the matrix are clamped to a valid one and dropped in the epilogue
+    for (int j = 0; j < NT; ++j)   // row blocks beyond the matrix are clamped to a valid one and dropped in the epilogue
         wp[j] = p.packed + (int64_t)min(rb0 + j, p.row_blocks - 1) * KC * kWave + lane;
     auto wload = [&](int step_i) {
         WTiles t;
 #pragma unroll
-        for (int j = 0; j < NB; ++j) {
+        for (int j = 0; j < NT; ++j) {
             t.v[j] = wp[j][(int64_t)min(step_i * WK + kg, KC - 1) * kWave];
             // a K group's tile beyond the last one must add nothing: code 0 everywhere (only an odd tile count with
             // WK = 2 gets here inside the loop; fetches beyond the loop's end are never used)
@@ -145,11 +152,11 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmProblem p, const
         return t;
     };
 
-    v16i c[MB][2 * NB];
+    v16i c[MB][H];
 #pragma unroll
     for (int i = 0; i < MB; ++i)
 #pragma unroll
-        for (int j = 0; j < 2 * NB; ++j)
+        for (int j = 0; j < H; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) c[i][j][r] = 0;
 
@@ -162,7 +169,7 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmProblem p, const
     // Register ring of packed weight tiles, steps i .. i+kWR-1, indexed by compile-time phases.  Eight deep where the
     // registers allow: the compiler's own wait for a weight tile (it counts the weight loads it can see) then
     // leaves the newest 6 loads in flight, which also covers the activation tiles requested since.
-    constexpr int kWR = NB == 1 ? 8 : 4;
+    constexpr int kWR = NT == 1 ? 8 : 4;
     WTiles w[kWR];
 #pragma unroll
     for (int j = 0; j < kWR - 1; ++j) w[j] = wload(j);
@@ -176,33 +183,40 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmProblem p, const
     // B operands of one 32-k half step: per packed tile, after v_permlane32_swap, [0] = rows 0-31 and [1] = rows
     // 32-63 of the tile.  They are expanded one half step AHEAD of the MFMAs that use them, so that the vector
     // ALU work of the expansion has independent matrix work to hide under.
-    struct BOps { v4i v[NB][2]; };
+    struct BOps { v4i v[H]; };         // one per 32-row block of the wave, in row order
     auto unpack_half = [&](const WTiles& w, int half) {
-        BOps b;
+        uint32_t codes[2 * NT];        // per packed tile: words of its rows 0-31 and of its rows 32-63
 #pragma unroll
-        for (int j = 0; j < NB; ++j) {
+        for (int j = 0; j < NT; ++j) {
             auto s = half ? __builtin_amdgcn_permlane32_swap(w.v[j].z, w.v[j].w, false, false)    // k 32..63
                           : __builtin_amdgcn_permlane32_swap(w.v[j].x, w.v[j].y, false, false);   // k 0..31
-            b.v[j][0] = expand_codes(s[0]);
-            b.v[j][1] = expand_codes(s[1]);
+            codes[2 * j] = s[0];
+            codes[2 * j + 1] = s[1];
+        }
+        BOps b;
+#pragma unroll
+        for (int h = 0; h < H; ++h) {
+            // an odd number of 32-row blocks: the wave's rows start at the tile's lower or upper half.  Written as a
+            // bit blend under a uniform mask (one v_bfi): a select between two elements of the array would become an
+            // indexed access and move the array out of the registers
+            if constexpr (H % 2 != 0) b.v[h] = expand_codes((codes[h + 1] & upper_mask) | (codes[h] & ~upper_mask));
+            else b.v[h] = expand_codes(codes[h]);
         }
         return b;
     };
     auto mfma_half = [&](const v4i (&a)[MB], const BOps& b) {
 #pragma unroll
-        for (int j = 0; j < NB; ++j)
+        for (int h = 0; h < H; ++h)
 #pragma unroll
-            for (int mb = 0; mb < MB; ++mb) {
-                c[mb][2 * j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[mb], b.v[j][0], c[mb][2 * j], 0, 0, 0);
-                c[mb][2 * j + 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[mb], b.v[j][1], c[mb][2 * j + 1], 0, 0, 0);
-            }
+            for (int mb = 0; mb < MB; ++mb)
+                c[mb][h] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[mb], b.v[h], c[mb][h], 0, 0, 0);
     };
     // scheduling hint for one half step: each MFMA is followed by a share of the independent vector ALU work
     auto interleave = [&]() {
 #pragma unroll
-        for (int i = 0; i < 2 * NB * MB; ++i) {
+        for (int i = 0; i < H * MB; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                   // one MFMA
-            __builtin_amdgcn_sched_group_barrier(0x002, (16 * NB + 2 * NB * MB - 1) / (2 * NB * MB) + 1, 0);   // VALU
+            __builtin_amdgcn_sched_group_barrier(0x002, (8 * H + H * MB - 1) / (H * MB) + 1, 0);   // VALU
         }
     };
     BOps b_lo = unpack_half(w[0], 0);
@@ -264,20 +278,20 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmProblem p, const
 #pragma unroll
                 for (int mb = dir; mb < MB; mb += 2)
 #pragma unroll
-                    for (int nb = 0; nb < 2 * NB; ++nb)
+                    for (int nb = 0; nb < H; ++nb)
 #pragma unroll
                         for (int r = 0; r < 16; ++r)
-                            ex[(((wave_n * (MB / 2) + mb / 2) * 2 * NB + nb) * 16 + r) * 64 + lane] = c[mb][nb][r];
+                            ex[(((wave_n * (MB / 2) + mb / 2) * H + nb) * 16 + r) * 64 + lane] = c[mb][nb][r];
             }
             __syncthreads();
             if (kg == dir) {
 #pragma unroll
                 for (int mb = dir; mb < MB; mb += 2)
 #pragma unroll
-                    for (int nb = 0; nb < 2 * NB; ++nb)
+                    for (int nb = 0; nb < H; ++nb)
 #pragma unroll
                         for (int r = 0; r < 16; ++r)
-                            c[mb][nb][r] += ex[(((wave_n * (MB / 2) + mb / 2) * 2 * NB + nb) * 16 + r) * 64 + lane];
+                            c[mb][nb][r] += ex[(((wave_n * (MB / 2) + mb / 2) * H + nb) * 16 + r) * 64 + lane];
             }
         }
     }
@@ -294,8 +308,8 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmProblem p, const
                 const int qsum = s_qsum[ml];
                 const float sc = s_scale[ml];
 #pragma unroll
-                for (int nb = 0; nb < 2 * NB; ++nb) {
-                    const int n = rb0 * kTileN + nb * 32 + op_row;   // n >= N covers padding rows and clamped row blocks
+                for (int nb = 0; nb < H; ++nb) {
+                    const int n = row0 + nb * 32 + op_row;   // n >= N covers padding rows and clamped row blocks
                     if (n < p.N) {
                         const int v = c[mb][nb][r] - qsum;
                         // streaming stores: tens of MB of output must not push the operands out of L2
@@ -315,31 +329,34 @@ int g_force_mb = 0;
 void set_gemm_mb(int mb) { g_force_mb = mb; }
 
 hipError_t launch_gemm(const GemmProblem& p, int64_t M, hipStream_t s) {
-    // wave tile = (32*MB) tokens x (64*NB) weight rows; workgroup = 4 waves, 4/WK along N and WK along K.
+    // wave tile = (32*MB) tokens x (32*H) weight rows; workgroup = 4 waves, 4/WK along N and WK along K.
     // Choice by workgroup count: 64 x 128 wave tiles (half the LDS traffic per MFMA) when the grid still gives
     // every compute unit two workgroups; 64 x 64 otherwise; and the K-split form when even that grid would
-    // leave compute units without work.  Forced value: 100*WK' + 10*MB + NB with WK' = 0 for WK = 1, 1 for WK = 2.
+    // leave compute units without work.  Forced value: 100*(WK-1) + 10*MB + H.
     const int64_t tiles_m = (M + 63) / 64;
-    const auto wgs = [&](int wn, int nb) { return tiles_m * ((p.row_blocks + wn * nb - 1) / (wn * nb)); };
-    int mb = 2, nb = 1, wk = 1;
-    if (wgs(4, 2) >= 512) nb = 2;
-    else if (wgs(4, 1) < 256) wk = 2;
-    if (g_force_mb) { wk = g_force_mb / 100 + 1; mb = g_force_mb / 10 % 10; nb = g_force_mb % 10; }
+    const int64_t rows = (int64_t)p.row_blocks * kTileN;
+    const auto wgs = [&](int wn, int h) { return tiles_m * ((rows + wn * h * 32 - 1) / (wn * h * 32)); };
+    int mb = 2, h = 2, wk = 1;
+    if (wgs(4, 4) >= 512) h = 4;
+    else if (wgs(4, 2) < 256) wk = 2;
+    if (g_force_mb) { wk = g_force_mb / 100 + 1; mb = g_force_mb / 10 % 10; h = g_force_mb % 10; }
     const int wn = kWaves / wk;
-    const int64_t gx = (p.row_blocks + wn * nb - 1) / (wn * nb);
+    const int64_t gx = (rows + wn * h * 32 - 1) / (wn * h * 32);
     const int64_t gy = (M + 32 * mb - 1) / (32 * mb);
     const int64_t wgs_total = (gx + kXcds - 1) / kXcds * kXcds * gy;
     if (wgs_total > INT32_MAX) return hipErrorInvalidValue;
     const dim3 grid((unsigned)wgs_total), block(256);
     const int igx = (int)gx;
-    if (wk == 2 && mb == 2 && nb == 1) gemm_kernel<2, 1, 2><<<grid, block, 0, s>>>(p, (int)M, igx);
-    else if (wk == 2 && mb == 2 && nb == 2) gemm_kernel<2, 2, 2><<<grid, block, 0, s>>>(p, (int)M, igx);
-    else if (wk == 2) return hipErrorInvalidValue;
-    else if (mb == 2 && nb == 1) gemm_kernel<2, 1, 1><<<grid, block, 0, s>>>(p, (int)M, igx);
-    else if (mb == 2 && nb == 2) gemm_kernel<2, 2, 1><<<grid, block, 0, s>>>(p, (int)M, igx);
-    else if (mb == 1 && nb == 2) gemm_kernel<1, 2, 1><<<grid, block, 0, s>>>(p, (int)M, igx);
-    else if (mb == 1 && nb == 1) gemm_kernel<1, 1, 1><<<grid, block, 0, s>>>(p, (int)M, igx);
-    else return hipErrorInvalidValue;
+    switch (100 * (wk - 1) + 10 * mb + h) {
+        case 12: gemm_kernel<1, 2, 1><<<grid, block, 0, s>>>(p, (int)M, igx); break;
+        case 14: gemm_kernel<1, 4, 1><<<grid, block, 0, s>>>(p, (int)M, igx); break;
+        case 22: gemm_kernel<2, 2, 1><<<grid, block, 0, s>>>(p, (int)M, igx); break;
+        case 23: gemm_kernel<2, 3, 1><<<grid, block, 0, s>>>(p, (int)M, igx); break;
+        case 24: gemm_kernel<2, 4, 1><<<grid, block, 0, s>>>(p, (int)M, igx); break;
+        case 122: gemm_kernel<2, 2, 2><<<grid, block, 0, s>>>(p, (int)M, igx); break;
+        case 124: gemm_kernel<2, 4, 2><<<grid, block, 0, s>>>(p, (int)M, igx); break;
+        default: return hipErrorInvalidValue;
+    }
     return hipGetLastError();
 }
 
