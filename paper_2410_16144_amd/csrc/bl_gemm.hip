@@ -62,6 +62,7 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmProblem p, const
     constexpr int kStageBytes = WK * kTileBytesA;   // one activation tile per K group
     constexpr int kStages = WK == 1 ? 8 : 6;        // LDS ring (6 x 8 KiB with two K groups: static LDS ends at 64 KiB)
     constexpr int kLead = 4;                        // the tile of step i + kLead is requested during step i
+    static_assert(kLead >= 3, "the prologue waits for all but the last requested tile");
     static_assert(kStages >= kLead + 1, "a stage is rewritten only after the barrier that ended its last read");
     static_assert(BM <= 64, "one 4 KiB slab per 256 threads");
     constexpr int kExchangeBytes = WK == 1 ? 0 : WN * (MB / 2) * H * 16 * 64 * 4;   // one direction at a time
@@ -120,7 +121,8 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmProblem p, const
         }
     };
     // The barrier that ends step i publishes the tile of step i+2, requested during step i+2-kLead; every load
-    // a thread issued in the kLead-2 steps since then may still be in flight.
+    // a thread issued in the kLead-2 steps since then may still be in flight (steps i >= 1; the prologue itself
+    // waits for tile 2).
     constexpr int kYounger = (kLead - 2) * (WK + NT);
     static_assert(kYounger < 16, "fits the low vmcnt field");
     auto publish = [&]() {
@@ -175,7 +177,11 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmProblem p, const
     for (int j = 0; j < kWR - 1; ++j) w[j] = wload(j);
 #pragma unroll
     for (int j = 0; j < kLead; ++j) request_tile(j);
-    __builtin_amdgcn_s_waitcnt(0x0f70 | ((kLead - 2) * WK));   // everything but the youngest kLead-2 tiles has landed
+    // Tiles 0, 1 AND 2 have landed; only the youngest may still be in flight.  Tile 2 has to be waited for here: the
+    // barrier that ends step 0 is meant to publish it, but publish() counts the loads of a steady-state step behind
+    // it (requests alternate with weight loads), and the prologue's requests come back to back, so after step 0
+    // there are NT fewer loads behind tile 2 than publish() allows to be outstanding.
+    __builtin_amdgcn_s_waitcnt(0x0f70 | ((kLead - 3) * WK));
     __syncthreads();                                            // also publishes s_scale / s_qsum
     v4i a_lo[2][MB], a_hi[MB];
     lread_half(0, 0, a_lo[0]);

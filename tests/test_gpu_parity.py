@@ -224,7 +224,19 @@ def _assert_product(ops, dev, kind, w, w_scale, x, waves=None):
     acc_ref = oracle.matmul_i32(q_ref, w)
     pw, qa, out, acc = _run_product(ops, dev, kind, w, w_scale, x, waves)
     _assert_quant_equal(qa, (q_ref, a_ref, s_ref), w.shape[1])
-    assert np.array_equal(acc.cpu().numpy(), acc_ref)
+    got = acc.cpu().numpy()
+    if not np.array_equal(got, acc_ref):
+        # say which side moved: the same launch again, the oracle again, the packed weights read back
+        bad = np.argwhere(got != acc_ref)
+        again = (ops.gemv if kind == "gemv" else ops.gemm)(pw, qa, want_acc=True)[1]
+        torch.cuda.synchronize()
+        pytest.fail("%s acc: %d of %d elements differ, first at %s (got %d, oracle %d); rows %s cols %s; "
+                    "second launch equals first: %s, equals oracle: %s; oracle repeatable: %s; unpack == w: %s"
+                    % (kind, len(bad), got.size, bad[0].tolist(), got[tuple(bad[0])], acc_ref[tuple(bad[0])],
+                       np.unique(bad[:, 0])[:8].tolist(), np.unique(bad[:, 1])[:8].tolist(),
+                       np.array_equal(again.cpu().numpy(), got), np.array_equal(again.cpu().numpy(), acc_ref),
+                       np.array_equal(oracle.matmul_i32(q_ref, w), acc_ref),
+                       np.array_equal(ops.unpack_ternary(pw).cpu().numpy(), w)))
     _check_out(out, acc_ref, w_scale, a_ref)
     return pw, qa, out, acc
 
