@@ -23,6 +23,14 @@ FLAGS = [
 ]
 
 
+# Kernel-argument preload for the decode kernels: their first seven scalar arguments arrive in registers with
+# the wave (see BL_FIRST_WG_PARAMS in csrc/bl_decode_device.hpp).  A compiler option per translation unit.
+PER_FILE_FLAGS = {
+    "bl_gemv.hip": ["-mllvm", "-amdgpu-kernarg-preload-count=7"],
+    "bl_decode_sk.hip": ["-mllvm", "-amdgpu-kernarg-preload-count=7"],
+}
+
+
 def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
@@ -55,7 +63,7 @@ def build(force: bool = True, extra_flags=(), verbose: bool = False) -> str:
 
     def compile_one(src):
         obj = os.path.join(OBJ_DIR, os.path.basename(src) + ".o")
-        cmd = [HIPCC, *FLAGS, *extra_flags, "-c", src, "-o", obj]
+        cmd = [HIPCC, *FLAGS, *PER_FILE_FLAGS.get(os.path.basename(src), []), *extra_flags, "-c", src, "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         r = subprocess.run(cmd, stderr=subprocess.PIPE, text=True)

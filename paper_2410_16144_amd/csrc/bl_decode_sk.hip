@@ -23,17 +23,14 @@ constexpr int kSkMaxRb = 32;   // row blocks one chunk may touch (LDS: 256 bytes
 constexpr int kSumBits = 40;   // low bits of a workspace word that hold the partial sum
 
 template <int U, bool FUSED, bool XBF16>
-__global__ __launch_bounds__(kThreads, 8) void decode_sk_kernel(const DecodeBatch b) {
+__global__ __launch_bounds__(kThreads, 8) void decode_sk_kernel(BL_FIRST_WG_PARAMS, const DecodeBatch b) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int blk = blockIdx.x;
-    int pi = 0;
-#pragma unroll
-    for (int i = 1; i < BL_MAX_BATCH; ++i) pi += (i < b.count && blk >= b.p[i].first_wg) ? 1 : 0;
-    const DecodeProblem& p = b.p[pi];
+    const DecodeProblem& p = b.p[BL_PROBLEM_OF(blk)];
 
     const int KC = p.KC, Kp = KC * kTileK;
     const int T = p.row_blocks * KC;                           // tiles of this matrix
@@ -188,7 +185,8 @@ hipError_t launch_sk(const DecodeBatch& b, size_t lds, hipStream_t s) {
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    kernel<<<dim3((unsigned)b.total_wgs), dim3(kThreads), lds, s>>>(b);
+    const FirstWgs first(b);
+    kernel<<<dim3((unsigned)b.total_wgs), dim3(kThreads), lds, s>>>(BL_FIRST_WG_ARGS(first), b);
     return hipGetLastError();
 }
 

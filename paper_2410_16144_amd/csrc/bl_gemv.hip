@@ -26,7 +26,7 @@ namespace bl {
 namespace {
 
 template <int M, bool FUSED, bool XBF16>   // XBF16: dtype of the raw activations (fused form only)
-__global__ __launch_bounds__(kThreads, 8) void decode_kernel(const DecodeBatch b) {
+__global__ __launch_bounds__(kThreads, 8) void decode_kernel(BL_FIRST_WG_PARAMS, const DecodeBatch b) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
     const int tid = threadIdx.x;
@@ -35,10 +35,7 @@ __global__ __launch_bounds__(kThreads, 8) void decode_kernel(const DecodeBatch b
 
     // which problem does this workgroup belong to (uniform)
     const int blk = blockIdx.x;
-    int pi = 0;
-#pragma unroll
-    for (int i = 1; i < BL_MAX_BATCH; ++i) pi += (i < b.count && blk >= b.p[i].first_wg) ? 1 : 0;
-    const DecodeProblem& p = b.p[pi];
+    const DecodeProblem& p = b.p[BL_PROBLEM_OF(blk)];
     const int wg = blk - p.first_wg;
 
     const int wlog2 = p.wlog2, G = 1 << wlog2;
@@ -173,7 +170,7 @@ constexpr int kMfmaRedBytes = kWaves * 16 * 32 * 4;   // per wave: 16 accumulato
 //   1 = copied once per workgroup from global memory into LDS (when M*Kp fits)
 //   2 = quantized by the workgroup into LDS (fused form)
 template <int M, int QMODE, bool XBF16>
-__global__ __launch_bounds__(kThreads, 8) void decode_mfma_kernel(const DecodeBatch b) {
+__global__ __launch_bounds__(kThreads, 8) void decode_mfma_kernel(BL_FIRST_WG_PARAMS, const DecodeBatch b) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     constexpr bool kLdsQ = QMODE != 0;
     constexpr int U = kLdsQ ? kMfmaInFlightLds : kMfmaInFlightDirect;   // weight tiles in flight per wave
@@ -184,10 +181,7 @@ __global__ __launch_bounds__(kThreads, 8) void decode_mfma_kernel(const DecodeBa
     const int lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int blk = blockIdx.x;
-    int pi = 0;
-#pragma unroll
-    for (int i = 1; i < BL_MAX_BATCH; ++i) pi += (i < b.count && blk >= b.p[i].first_wg) ? 1 : 0;
-    const DecodeProblem& p = b.p[pi];
+    const DecodeProblem& p = b.p[BL_PROBLEM_OF(blk)];
     const int wg = blk - p.first_wg;
 
     const int wlog2 = p.wlog2, G = 1 << wlog2;
@@ -324,7 +318,8 @@ hipError_t launch_kernel(Kernel kernel, bool& attr_set, const DecodeBatch& b, si
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    kernel<<<dim3((unsigned)b.total_wgs), dim3(kThreads), lds_bytes, s>>>(b);
+    const FirstWgs first(b);
+    kernel<<<dim3((unsigned)b.total_wgs), dim3(kThreads), lds_bytes, s>>>(BL_FIRST_WG_ARGS(first), b);
     return hipGetLastError();
 }
 
