@@ -23,11 +23,12 @@ FLAGS = [
 ]
 
 
-# Kernel-argument preload for the decode kernels: their first seven scalar arguments arrive in registers with
-# the wave (see BL_FIRST_WG_PARAMS in csrc/bl_decode_device.hpp).  A compiler option per translation unit.
+# Kernel-argument preload for the decode and quantization kernels: their first seven scalar arguments arrive in
+# registers with the wave (see BL_FIRST_WG_PARAMS in csrc/bl_internal.hpp).  A compiler option per translation unit.
 PER_FILE_FLAGS = {
     "bl_gemv.hip": ["-mllvm", "-amdgpu-kernarg-preload-count=7"],
     "bl_decode_sk.hip": ["-mllvm", "-amdgpu-kernarg-preload-count=7"],
+    "bl_quant.hip": ["-mllvm", "-amdgpu-kernarg-preload-count=7"],
 }
 
 

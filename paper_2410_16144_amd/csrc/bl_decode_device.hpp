@@ -5,20 +5,6 @@
 
 namespace bl {
 
-// Which problem of the launch a workgroup belongs to.  The first workgroup of problems 1..7 (INT32_MAX beyond the
-// launch's count) LEADS the argument list of every decode kernel as seven scalars, because these files are
-// compiled with kernel-argument preload (-amdgpu-kernarg-preload-count=7): a kernel's first scalar arguments
-// arrive in registers with the wave, so a workgroup knows its problem without a round trip to memory and the
-// scalar loads of that problem's fields go out at once -- one dependent round before the first weight tile can be
-// requested instead of two (0.4 us per launch on MI355X).  Without the compiler option, or on firmware that does
-// not preload, the same code reads them from the argument segment as before.
-#define BL_FIRST_WG_PARAMS \
-    const int fw1, const int fw2, const int fw3, const int fw4, const int fw5, const int fw6, const int fw7
-#define BL_FIRST_WG_ARGS(f) (f).v[1], (f).v[2], (f).v[3], (f).v[4], (f).v[5], (f).v[6], (f).v[7]
-#define BL_PROBLEM_OF(blk) \
-    (((blk) >= fw1) + ((blk) >= fw2) + ((blk) >= fw3) + ((blk) >= fw4) + ((blk) >= fw5) + ((blk) >= fw6) + ((blk) >= fw7))
-static_assert(BL_MAX_BATCH == 8, "seven leading arguments");
-
 struct FirstWgs {   // host side
     int v[BL_MAX_BATCH];
     explicit FirstWgs(const DecodeBatch& b) {

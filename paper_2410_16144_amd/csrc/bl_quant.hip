@@ -77,14 +77,11 @@ __device__ __forceinline__ void quant_row(const void* row, int K, int Kp, int8_t
 }
 
 // Up to BL_MAX_BATCH activation matrices in one launch: workgroup = one token row of one of them.
-__global__ __launch_bounds__(kQuantThreads) void quant_kernel(const QuantBatch b) {
+__global__ __launch_bounds__(kQuantThreads) void quant_kernel(BL_FIRST_WG_PARAMS, const QuantBatch b) {
     __shared__ float s_max[kQuantThreads / kWave];
     __shared__ int s_sum[kQuantThreads / kWave];
     const int blk = blockIdx.x;
-    int pi = 0;
-#pragma unroll
-    for (int i = 1; i < BL_MAX_BATCH; ++i) pi += (i < b.count && blk >= b.p[i].first_row) ? 1 : 0;
-    const QuantProblem& p = b.p[pi];
+    const QuantProblem& p = b.p[BL_PROBLEM_OF(blk)];
     const int64_t m = blk - p.first_row;
     const bool bf16 = p.flags & 1, vec = p.flags & 2;   // uniform
     const void* row = static_cast<const char*>(p.x) + m * p.ldx * (bf16 ? 2 : 4);
@@ -110,7 +107,9 @@ hipError_t launch_quant(const QuantBatch& batch, hipStream_t s) {
         rows += b.p[i].M;
     }
     if (rows > INT32_MAX) return hipErrorInvalidValue;
-    quant_kernel<<<dim3((unsigned)rows), dim3(kQuantThreads), 0, s>>>(b);
+    struct { int v[BL_MAX_BATCH]; } first;
+    for (int i = 0; i < BL_MAX_BATCH; ++i) first.v[i] = i < b.count ? b.p[i].first_row : INT32_MAX;
+    quant_kernel<<<dim3((unsigned)rows), dim3(kQuantThreads), 0, s>>>(BL_FIRST_WG_ARGS(first), b);
     return hipGetLastError();
 }
 
