@@ -595,3 +595,36 @@ def test_gemm_determinism(dev, ops):
     for _ in range(2):
         _, _, out2, acc2 = _run_product(ops, dev, "gemm", w, s, x)
         assert torch.equal(acc, acc2) and torch.equal(out, out2)
+
+
+def _launch_gemm(ops, pw, qa, out, acc):
+    from paper_2410_16144_amd import binding
+    binding.bl_gemm(pw.blob.data_ptr(), pw.desc, qa.q.data_ptr(), qa.a_scale.data_ptr(), qa.q_sum.data_ptr(),
+                    qa.q.shape[0], out.data_ptr(), acc.data_ptr(), torch.cuda.current_stream().cuda_stream)
+
+
+@pytest.mark.parametrize("tile", [12, 14, 22, 23, 24, 122, 124])
+def test_gemm_first_steps_under_load(dev, ops, tile):
+    """Short K (the whole product is the kernel's first few steps) and enough workgroups to keep every compute
+    unit's load queue busy, launched back to back: every launch must give the oracle's bits.  Guards the waits of
+    the activation ring's first stages, whose margin is the smallest when the memory system is busy."""
+    from paper_2410_16144_amd import binding
+    M, N, K = 1024, 2048, 192          # 3 K steps; 128 to 1024 workgroups depending on the tile
+    w, s, x = _problem(5000 + tile, M, K, N, p_zero=0.4, outl=0.01)
+    q_ref, a_ref, s_ref = oracle.quant_act(x)
+    acc_ref = torch.from_numpy(oracle.matmul_i32(q_ref, w)).to(dev)
+    pw = ops.pack_ternary(torch.from_numpy(w).to(dev), float(s))
+    qa = ops.quant_act(_to_dev_bf16(x, dev) if x.dtype == np.uint16 else torch.from_numpy(x).to(dev))
+    outs = [torch.empty((M, N), dtype=torch.float32, device=dev) for _ in range(8)]
+    accs = [torch.empty((M, N), dtype=torch.int32, device=dev) for _ in range(8)]
+    binding.bl_set_tuning("gemm_mb", tile)
+    try:
+        for rep in range(25):
+            for o, a in zip(outs, accs):
+                _launch_gemm(ops, pw, qa, o, a)
+            torch.cuda.synchronize()
+            for i, a in enumerate(accs):
+                assert torch.equal(a, acc_ref), "launch %d of round %d differs from the oracle" % (i, rep)
+    finally:
+        binding.bl_set_tuning("gemm_mb", 0)
+
