@@ -8,8 +8,9 @@
 // Tiling.  Workgroup = 4 waves side by side along N = (32*MB) tokens x (128*H) weight rows; each
 // wave owns (32*MB) x (32*H), i.e. MB x H MFMA tiles, H = 2, 3 or 4.  (With H = 3 a wave's 96 rows are one
 // packed 64-row tile and half of another, which it shares with its neighbour: both load it, each expands
-// its own half.  The form exists for its workgroup count: where 128-row wave tiles would leave the last
-// round of workgroups mostly empty, 96-row tiles fill it.)  (Variant WK = 2 for small M x N, where
+// its own half.  The form was built for its workgroup count -- where 128-row wave tiles leave the last round of
+// workgroups mostly empty, 96-row tiles fill it -- and measured no faster: the kernel runs at the chip's power
+// limit, and compute units that idle let the others clock higher.  It stays selectable.)  (Variant WK = 2 for small M x N, where
 // that grid would leave compute units idle: 2 waves along N x 2 along K, the two K groups take
 // alternate packed tiles and add their accumulators through LDS at the end, so the workgroup tile
 // is half as wide and the grid twice as large.)  K advances one packed tile (64) per step:
@@ -21,7 +22,7 @@
 //     reads stay bank-conflict free without padding.  One barrier per step; the wait before it
 //     names exactly how many younger loads may still be in flight;
 //   - weights: each wave loads its own packed 64 x 64 tile straight into registers (one 128-bit
-//     load per lane, four steps ahead).  Lane r holds row r; v_permlane32_swap regroups two 16-k
+//     load per lane, into a ring of 8 steps, 4 with two tiles per step).  Lane r holds row r; v_permlane32_swap regroups two 16-k
 //     pieces so that lanes 0-31 / 32-63 hold k-halves of the same 32 rows -- exactly the MFMA
 //     B-operand shape -- and 7 VALU ops expand a word of codes into the 16 int8 of one operand.
 //     Weights never touch LDS and stay 2 bits wide all the way from HBM into the register file.
