@@ -43,6 +43,10 @@ _lib.orc_matmul_i32_cols.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _i64, _vp]
 _lib.orc_dequant.argtypes = [_vp, _i64, _i64, _f32, _vp, _vp]
 _lib.orc_tl1_gemv_i32.argtypes = [_vp, _i64, _vp, _i64, _vp]
 _lib.orc_tl2_gemv_i32.argtypes = [_vp, _i64, _vp, _i64, _vp]
+_lib.orc_tl2_encode_rows.argtypes = [_vp, _i64, _i64, _vp]
+_lib.orc_tl2_encode_rows.restype = _i64
+_lib.orc_tl2_decode_rows.argtypes = [_vp, _i64, _i64, _vp]
+_lib.orc_tl2_decode_rows.restype = _i64
 
 
 def _p(a):
@@ -108,6 +112,24 @@ def tl2_code(w0: int, w1: int, w2: int):
     i = ctypes.c_int(0)
     _lib.orc_tl2_code(int(w0), int(w1), int(w2), ctypes.byref(s), ctypes.byref(i))
     return s.value, i.value
+
+
+def tl2_encode_rows(w):
+    """[N,K] int8 -> ([N, ceil(K/3)] uint8 codes sign << 4 | index (Table 3), bad count)."""
+    w = _c(w, np.int8)
+    n, k = w.shape
+    codes = np.empty((n, (k + 2) // 3), np.uint8)
+    bad = _lib.orc_tl2_encode_rows(_p(w), n, k, _p(codes))
+    return codes, int(bad)
+
+
+def tl2_decode_rows(codes, k: int):
+    codes = _c(codes, np.uint8)
+    n = codes.shape[0]
+    assert codes.shape[1] == (k + 2) // 3
+    w = np.empty((n, k), np.int8)
+    bad = _lib.orc_tl2_decode_rows(_p(codes), n, k, _p(w))
+    return w, int(bad)
 
 
 def bf16_to_f32(bits) -> np.ndarray:

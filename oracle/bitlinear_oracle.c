@@ -156,6 +156,51 @@ void orc_tl2_code(int w0, int w1, int w2, int *sign, int *idx) {
     *idx = v < 0 ? -v : v;
 }
 
+/*
+ * A whole matrix in TL2 codes (Table 3): row n, group g = weights 3g, 3g+1, 3g+2 of the row (zeros beyond K)
+ * becomes one byte, sign << 4 | index.  codes is [N, ceil(K/3)].  A value outside {-1,0,+1} is encoded as 0 and
+ * counted.
+ */
+int64_t orc_tl2_encode_rows(const int8_t *w, int64_t N, int64_t K, uint8_t *codes) {
+    int64_t groups = (K + 2) / 3, bad = 0;
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t g = 0; g < groups; ++g) {
+            int t[3];
+            for (int j = 0; j < 3; ++j) {
+                t[j] = (3 * g + j < K) ? w[n * K + 3 * g + j] : 0;
+                if (t[j] < -1 || t[j] > 1) { t[j] = 0; ++bad; }
+            }
+            int sign, idx;
+            orc_tl2_code(t[0], t[1], t[2], &sign, &idx);
+            codes[n * groups + g] = (uint8_t)(sign << 4 | idx);
+        }
+    return bad;
+}
+
+/*
+ * The inverse, by search: the weights of a code are the one triple among the 27 that orc_tl2_code maps to it
+ * (Table 3 is a bijection between the 27 triples and the 27 codes in use).  A code no triple maps to (index 14
+ * or 15, or sign with index 0) decodes to zeros and is counted.
+ */
+int64_t orc_tl2_decode_rows(const uint8_t *codes, int64_t N, int64_t K, int8_t *w) {
+    int64_t groups = (K + 2) / 3, bad = 0;
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t g = 0; g < groups; ++g) {
+            int code = codes[n * groups + g], found = 0, t[3] = {0, 0, 0};
+            for (int a = -1; a <= 1 && !found; ++a)
+                for (int b = -1; b <= 1 && !found; ++b)
+                    for (int c = -1; c <= 1 && !found; ++c) {
+                        int sign, idx;
+                        orc_tl2_code(a, b, c, &sign, &idx);
+                        if ((sign << 4 | idx) == code) { t[0] = a; t[1] = b; t[2] = c; found = 1; }
+                    }
+            if (!found) ++bad;
+            for (int j = 0; j < 3; ++j)
+                if (3 * g + j < K) w[n * K + 3 * g + j] = (int8_t)t[j];
+        }
+    return bad;
+}
+
 /* ------------------------------------------------------------------ */
 /* Activation side                                                     */
 /* ------------------------------------------------------------------ */

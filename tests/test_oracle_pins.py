@@ -93,6 +93,36 @@ def test_tl2_code_matches_paper_table3_printed_rows():
         assert oracle.tl2_code(int(w0), int(w1), int(w2)) == (int(sign), int(idx, 2))
 
 
+def test_tl2_rows_carry_the_table3_codes_and_round_trip():
+    # the nine printed rows of Table 3, laid side by side as one weight row: each group of three becomes the
+    # printed sign and index in one byte, sign << 4 | index
+    rows = _rows("table3_tl2.txt")
+    w = np.array([[int(v) for r in rows for v in r[:3]]], np.int8)
+    codes, bad = oracle.tl2_encode_rows(w)
+    assert bad == 0 and codes.shape == (1, 9)
+    assert codes[0].tolist() == [int(sign) << 4 | int(idx, 2) for *_, sign, idx in rows]
+    back, bad = oracle.tl2_decode_rows(codes, w.shape[1])
+    assert bad == 0 and np.array_equal(back, w)
+    # every triple, ragged K (zero padding inside the last group), several rows
+    rng = np.random.default_rng(5)
+    for K in (1, 2, 3, 4, 5, 27, 100):
+        w = rng.integers(-1, 2, size=(7, K), dtype=np.int8)
+        codes, bad = oracle.tl2_encode_rows(w)
+        assert bad == 0 and codes.shape == (7, (K + 2) // 3) and int(codes.max()) < 32
+        # by hand: v = 9 w0 + 3 w1 + w2 over the zero-padded row
+        wp = np.zeros((7, (K + 2) // 3 * 3), np.int64)
+        wp[:, :K] = w
+        v = 9 * wp[:, 0::3] + 3 * wp[:, 1::3] + wp[:, 2::3]
+        assert np.array_equal(codes, ((v < 0).astype(np.int64) << 4 | np.abs(v)).astype(np.uint8))
+        back, bad = oracle.tl2_decode_rows(codes, K)
+        assert bad == 0 and np.array_equal(back, w)
+    # values outside {-1,0,+1} are counted and encoded as 0; codes that no triple maps to are counted
+    codes, bad = oracle.tl2_encode_rows(np.array([[2, 1, -3]], np.int8))
+    assert bad == 2 and codes.tolist() == [[3]]
+    back, bad = oracle.tl2_decode_rows(np.array([[14, 16, 31]], np.uint8), 9)
+    assert bad == 3 and not back.any()
+
+
 def test_tl2_code_is_a_bijection_on_27_triples():
     # 27 triples -> 1 + 2*13 distinct (sign, idx) codes; negation flips only the sign
     codes = {}
