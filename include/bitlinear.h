@@ -249,6 +249,53 @@ bl_status bl_gemm(const void *packed_dev, const bl_packed_desc *d, const int8_t 
                   const float *a_scale_dev, const int32_t *q_sum_dev, int64_t M,
                   float *out_dev, int32_t *acc_dev, void *stream);
 
+/* ---- A 1.78-bit layout on the paper's TL2 code --------------------------
+ *
+ * Section 2 and Table 3: three ternary weights become one sign bit and a
+ * 4-bit index (index = |9 w0 + 3 w1 + w2|, sign = 1 iff that sum is negative),
+ * five bits for three weights.  Layout version 2 stores six such codes in a
+ * 32-bit word (18 weights, two bits unused: 1.78 bits per weight), in tiles of
+ * 64 rows x 72 k = 1 KiB: tile (rb, kc) at byte ((rb * Kp/72) + kc) * 1024; the
+ * 16 bytes at offset 16 r of a tile are row 64 rb + r; word s of those four
+ * holds the weights k = 72 kc + 18 s + 3 i + {0,1,2} as code i = sign << 4 |
+ * index at bits [5 i, 5 i + 4].  Padding weights are 0.  The decode product
+ * reads 11 % fewer bytes than with the 2-bit layout and spends about twice the
+ * vector instructions per weight; one token only, no fused quantization.
+ */
+#define BL_TL2_TILE_K 72
+#define BL_TL2_LAYOUT_VERSION 2
+
+/* K rounded up to BL_TL2_TILE_K; -1 if K is outside 1..BL_MAX_K. */
+int64_t bl_tl2_padded_k(int64_t K);
+
+/* Descriptor of a version-2 blob: version = BL_TL2_LAYOUT_VERSION, Kp =
+ * bl_tl2_padded_k(K), bytes = Np * Kp / 72 * 16.  Errors as bl_packed_desc_init. */
+bl_status bl_tl2_desc_init(int64_t N, int64_t K, float w_scale, bl_packed_desc *d);
+
+/* Offline transformation into the version-2 layout and its inverse; arguments
+ * and errors as for bl_pack_ternary / bl_unpack_ternary (BL_ERR_LAYOUT if the
+ * descriptor is not version 2).  Codes that Table 3 does not use decode to 0. */
+bl_status bl_tl2_pack(const int8_t *w_dev, const bl_packed_desc *d, void *packed_dev,
+                      int32_t *bad_count_dev, void *stream);
+bl_status bl_tl2_unpack(const void *packed_dev, const bl_packed_desc *d, int8_t *w_dev,
+                        void *stream);
+
+/*
+ * Decode product for ONE token over a version-2 blob:
+ *   out[n] = (sum_k q[k] * W[n,k]) * w_scale * a_scale[0]
+ *   q_dev       the token's int8 activations as bl_quant_act writes them, in a
+ *               buffer of at least bl_tl2_padded_k(K) bytes, 16-byte aligned:
+ *               the bytes from K on are read and meet zero weights, so their
+ *               values do not matter
+ *   a_scale_dev [1] fp32
+ *   out_dev     [N] fp32;  acc_dev optional [N] int32 (the exact sums)
+ * Results are identical to bl_gemv on the same weights.
+ * Errors: BL_ERR_NULL, BL_ERR_LAYOUT, BL_ERR_SHAPE, BL_ERR_BUF_SMALL,
+ *         BL_ERR_ALIGN, BL_ERR_HIP.
+ */
+bl_status bl_tl2_gemv(const void *packed_dev, const bl_packed_desc *d, const int8_t *q_dev,
+                      const float *a_scale_dev, float *out_dev, int32_t *acc_dev, void *stream);
+
 /*
  * Launch-shape override for experiments and sweeps; process-wide, not thread-safe, never
  * changes results.  Keys: "gemv_waves" = waves of the decode kernel that share one

@@ -24,11 +24,14 @@ BL_MAX_BATCH = 8
 BL_MAX_SPLIT_WGS = 2048
 BL_WORKSPACE_BYTES = BL_MAX_SPLIT_WGS * 64 * 8
 BL_MAX_GEMM_M = 4194304
+BL_TL2_TILE_K = 72
+BL_TL2_LAYOUT_VERSION = 2
 
 # every symbol include/bitlinear.h declares
 DECLARED_SYMBOLS = (
     "bl_padded_k", "bl_padded_n", "bl_packed_desc_init", "bl_pack_ternary", "bl_unpack_ternary",
     "bl_quant_act", "bl_quant_act_batch", "bl_gemv", "bl_gemv_batch", "bl_decode_batch", "bl_gemm", "bl_set_tuning", "bl_get_stat", "bl_status_str", "bl_last_hip_error", "bl_version",
+    "bl_tl2_padded_k", "bl_tl2_desc_init", "bl_tl2_pack", "bl_tl2_unpack", "bl_tl2_gemv",
 )
 
 
@@ -101,6 +104,12 @@ def lib():
     l.bl_gemv_batch.argtypes = [ctypes.POINTER(GemvItem), i32, i64, vp, vp]
     l.bl_decode_batch.argtypes = [ctypes.POINTER(DecodeItem), i32, i64, vp, vp]
     l.bl_gemm.argtypes = [vp, dp, vp, vp, vp, i64, vp, vp, vp]
+    l.bl_tl2_padded_k.argtypes = [i64]
+    l.bl_tl2_padded_k.restype = i64
+    l.bl_tl2_desc_init.argtypes = [i64, i64, ctypes.c_float, dp]
+    l.bl_tl2_pack.argtypes = [vp, dp, vp, vp, vp]
+    l.bl_tl2_unpack.argtypes = [vp, dp, vp, vp]
+    l.bl_tl2_gemv.argtypes = [vp, dp, vp, vp, vp, vp, vp]
     l.bl_set_tuning.argtypes = [ctypes.c_char_p, i32]
     l.bl_get_stat.argtypes = [ctypes.c_char_p]
     l.bl_get_stat.restype = i64
@@ -109,7 +118,8 @@ def lib():
     l.bl_version.restype = ctypes.c_char_p
     l.bl_last_hip_error.restype = ctypes.c_char_p
     for name in ("bl_packed_desc_init", "bl_pack_ternary", "bl_unpack_ternary", "bl_quant_act", "bl_quant_act_batch", "bl_gemv",
-                 "bl_gemv_batch", "bl_decode_batch", "bl_gemm", "bl_set_tuning"):
+                 "bl_gemv_batch", "bl_decode_batch", "bl_gemm", "bl_set_tuning", "bl_tl2_desc_init", "bl_tl2_pack",
+                 "bl_tl2_unpack", "bl_tl2_gemv"):
         getattr(l, name).restype = ctypes.c_int
     _lib = l
     return l
@@ -218,6 +228,31 @@ def bl_gemm(packed_dev: int, desc: PackedDesc, q_dev: int, a_scale_dev: int, q_s
             out_dev: int, acc_dev: int = 0, stream: int = 0):
     _check(lib().bl_gemm(packed_dev, ctypes.byref(desc), q_dev, a_scale_dev, q_sum_dev, M, out_dev,
                          acc_dev or None, stream or None), "bl_gemm")
+
+
+def bl_tl2_padded_k(K: int) -> int:
+    return int(lib().bl_tl2_padded_k(K))
+
+
+def bl_tl2_desc_init(N: int, K: int, w_scale: float) -> PackedDesc:
+    d = PackedDesc()
+    _check(lib().bl_tl2_desc_init(N, K, float(w_scale), ctypes.byref(d)), "bl_tl2_desc_init")
+    return d
+
+
+def bl_tl2_pack(w_dev: int, desc: PackedDesc, packed_dev: int, bad_count_dev: int = 0, stream: int = 0):
+    _check(lib().bl_tl2_pack(w_dev, ctypes.byref(desc), packed_dev, bad_count_dev or None, stream or None),
+           "bl_tl2_pack")
+
+
+def bl_tl2_unpack(packed_dev: int, desc: PackedDesc, w_dev: int, stream: int = 0):
+    _check(lib().bl_tl2_unpack(packed_dev, ctypes.byref(desc), w_dev, stream or None), "bl_tl2_unpack")
+
+
+def bl_tl2_gemv(packed_dev: int, desc: PackedDesc, q_dev: int, a_scale_dev: int, out_dev: int, acc_dev: int = 0,
+                stream: int = 0):
+    _check(lib().bl_tl2_gemv(packed_dev, ctypes.byref(desc), q_dev, a_scale_dev, out_dev, acc_dev or None,
+                             stream or None), "bl_tl2_gemv")
 
 
 def bl_set_tuning(key: str, value: int):

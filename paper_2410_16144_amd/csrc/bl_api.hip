@@ -29,6 +29,15 @@ bl_status check_product_args(const void* packed, const bl_packed_desc* d, const 
     return BL_OK;
 }
 
+bl_status check_tl2_desc(const bl_packed_desc* d) {
+    if (!d) return BL_ERR_NULL;
+    if (d->version != BL_TL2_LAYOUT_VERSION) return BL_ERR_LAYOUT;
+    if (d->N < 1 || d->K < 1 || d->K > BL_MAX_K || d->N > INT32_MAX - BL_TILE_N) return BL_ERR_SHAPE;
+    if (d->Np != bl_padded_n(d->N) || d->Kp != bl_tl2_padded_k(d->K)) return BL_ERR_SHAPE;
+    if (d->bytes != (uint64_t)d->Np * (uint64_t)(d->Kp / BL_TL2_TILE_K) * 16) return BL_ERR_BUF_SMALL;
+    return BL_OK;
+}
+
 bl::GemmProblem make_problem(const void* packed, const bl_packed_desc* d, const int8_t* q, const float* a_scale,
                              const int32_t* q_sum, float* out, int32_t* acc) {
     bl::GemmProblem p;
@@ -104,6 +113,60 @@ bl_status bl_unpack_ternary(const void* packed_dev, const bl_packed_desc* d, int
     drop_stale_hip_error();
     return hip_status(bl::launch_unpack(static_cast<const uint32_t*>(packed_dev), d->N, d->K, d->Np, d->Kp, w_dev,
                                         static_cast<hipStream_t>(stream)));
+}
+
+int64_t bl_tl2_padded_k(int64_t K) {
+    if (K < 1 || K > BL_MAX_K) return -1;
+    return (K + BL_TL2_TILE_K - 1) / BL_TL2_TILE_K * BL_TL2_TILE_K;
+}
+
+bl_status bl_tl2_desc_init(int64_t N, int64_t K, float w_scale, bl_packed_desc* d) {
+    if (!d) return BL_ERR_NULL;
+    if (bl_padded_n(N) < 0 || bl_tl2_padded_k(K) < 0) return BL_ERR_SHAPE;
+    memset(d, 0, sizeof *d);
+    d->version = BL_TL2_LAYOUT_VERSION;
+    d->N = N;
+    d->K = K;
+    d->Np = bl_padded_n(N);
+    d->Kp = bl_tl2_padded_k(K);
+    d->bytes = (uint64_t)d->Np * (uint64_t)(d->Kp / BL_TL2_TILE_K) * 16;
+    d->w_scale = w_scale;
+    return BL_OK;
+}
+
+bl_status bl_tl2_pack(const int8_t* w_dev, const bl_packed_desc* d, void* packed_dev, int32_t* bad_count_dev,
+                      void* stream) {
+    if (!w_dev || !d || !packed_dev) return BL_ERR_NULL;
+    bl_status s = check_tl2_desc(d);
+    if (s != BL_OK) return s;
+    if (!aligned(packed_dev, 16) || (bad_count_dev && !aligned(bad_count_dev, 4))) return BL_ERR_ALIGN;
+    drop_stale_hip_error();
+    return hip_status(bl::launch_tl2_pack(w_dev, d->N, d->K, d->Np, d->Kp, static_cast<uint32_t*>(packed_dev),
+                                          bad_count_dev, static_cast<hipStream_t>(stream)));
+}
+
+bl_status bl_tl2_unpack(const void* packed_dev, const bl_packed_desc* d, int8_t* w_dev, void* stream) {
+    if (!w_dev || !d || !packed_dev) return BL_ERR_NULL;
+    bl_status s = check_tl2_desc(d);
+    if (s != BL_OK) return s;
+    if (!aligned(packed_dev, 16)) return BL_ERR_ALIGN;
+    drop_stale_hip_error();
+    return hip_status(bl::launch_tl2_unpack(static_cast<const uint32_t*>(packed_dev), d->N, d->K, d->Np, d->Kp,
+                                            w_dev, static_cast<hipStream_t>(stream)));
+}
+
+bl_status bl_tl2_gemv(const void* packed_dev, const bl_packed_desc* d, const int8_t* q_dev, const float* a_scale_dev,
+                      float* out_dev, int32_t* acc_dev, void* stream) {
+    if (!packed_dev || !d || !q_dev || !a_scale_dev || !out_dev) return BL_ERR_NULL;
+    bl_status s = check_tl2_desc(d);
+    if (s != BL_OK) return s;
+    if (!aligned(packed_dev, 16) || !aligned(q_dev, 16) || !aligned(a_scale_dev, 4) || !aligned(out_dev, 4) ||
+        (acc_dev && !aligned(acc_dev, 4)))
+        return BL_ERR_ALIGN;
+    drop_stale_hip_error();
+    return hip_status(bl::launch_tl2_gemv(static_cast<const uint4*>(packed_dev), reinterpret_cast<const int32_t*>(q_dev),
+                                          a_scale_dev, out_dev, acc_dev, d->N, d->Np, d->Kp, d->w_scale,
+                                          static_cast<hipStream_t>(stream)));
 }
 
 static bl_status fill_quant_problem(const bl_quant_item& it, bl::QuantProblem& p) {

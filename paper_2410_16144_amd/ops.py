@@ -48,6 +48,43 @@ def unpack_ternary(pw: PackedWeight) -> torch.Tensor:
     return w
 
 
+def tl2_pack(w: torch.Tensor, w_scale: float, bad_count: Optional[torch.Tensor] = None) -> PackedWeight:
+    """w: [N,K] int8 device tensor in {-1,0,+1} -> PackedWeight in the 1.78-bit layout (bl_tl2_pack)."""
+    assert w.is_cuda and w.dtype == torch.int8 and w.dim() == 2 and w.is_contiguous()
+    N, K = w.shape
+    desc = B.bl_tl2_desc_init(N, K, w_scale)
+    blob = torch.empty(int(desc.bytes), dtype=torch.uint8, device=w.device)
+    B.bl_tl2_pack(w.data_ptr(), desc, blob.data_ptr(), bad_count.data_ptr() if bad_count is not None else 0, _stream())
+    return PackedWeight(blob, desc)
+
+
+def tl2_unpack(pw: PackedWeight) -> torch.Tensor:
+    w = torch.empty((pw.N, pw.K), dtype=torch.int8, device=pw.blob.device)
+    B.bl_tl2_unpack(pw.blob.data_ptr(), pw.desc, w.data_ptr(), _stream())
+    return w
+
+
+def tl2_quant_buffer(K: int, device) -> "QuantAct":
+    """Quantization outputs for ONE token whose q row is long enough for bl_tl2_gemv (bl_tl2_padded_k(K) bytes,
+    zero beyond what bl_quant_act writes)."""
+    n = max(B.bl_tl2_padded_k(K), B.bl_padded_k(K))
+    return QuantAct(torch.zeros((1, n), dtype=torch.int8, device=device),
+                    torch.empty((1,), dtype=torch.float32, device=device),
+                    torch.empty((1,), dtype=torch.int32, device=device), K)
+
+
+def tl2_gemv(pw: PackedWeight, qa: "QuantAct", out: Optional[torch.Tensor] = None, want_acc: bool = False):
+    """One-token decode product over a 1.78-bit blob (bl_tl2_gemv).  qa: from quant_act(x, tl2_quant_buffer(K, dev))."""
+    assert qa.q.shape[0] == 1 and qa.q.shape[1] >= B.bl_tl2_padded_k(pw.K)
+    dev = pw.blob.device
+    if out is None:
+        out = torch.empty((1, pw.N), dtype=torch.float32, device=dev)
+    acc = torch.empty((1, pw.N), dtype=torch.int32, device=dev) if want_acc else None
+    B.bl_tl2_gemv(pw.blob.data_ptr(), pw.desc, qa.q.data_ptr(), qa.a_scale.data_ptr(), out.data_ptr(),
+                  acc.data_ptr() if acc is not None else 0, _stream())
+    return out, acc
+
+
 @dataclass
 class QuantAct:
     q: torch.Tensor         # int8 [M, Kp]

@@ -142,3 +142,37 @@ def test_status_strings():
         seen.add(txt)
     assert len(seen) == 10
     assert B.status_str(99) == "unknown status"
+
+
+def test_tl2_descriptor_and_validation():
+    assert B.bl_tl2_padded_k(1) == 72 and B.bl_tl2_padded_k(72) == 72 and B.bl_tl2_padded_k(73) == 144
+    assert B.bl_tl2_padded_k(0) == -1 and B.bl_tl2_padded_k(B.BL_MAX_K + 1) == -1
+    d = B.bl_tl2_desc_init(3200, 8640, 0.02)            # 8640 = 120 tiles of 72
+    assert (d.version, d.N, d.K, d.Np, d.Kp, d.bytes) == (2, 3200, 8640, 3200, 8640, 3200 * 120 * 16)
+    assert d.bytes * 9 == B.bl_packed_desc_init(3200, 8640, 0.02).bytes * 8   # 16 bytes per 72 weights against 18
+    d = B.bl_tl2_desc_init(70, 100, 1.0)
+    assert (d.Np, d.Kp, d.bytes) == (128, 144, 128 * 2 * 16)
+    assert _st(B.bl_tl2_desc_init, 0, 64, 1.0) == B.BL_ERR_SHAPE
+    P = 0x10000
+    v1 = B.bl_packed_desc_init(128, 144, 0.5)
+    v2 = B.bl_tl2_desc_init(128, 144, 0.5)
+    # the two layouts do not mix
+    assert _st(B.bl_tl2_pack, P, v1, P) == B.BL_ERR_LAYOUT
+    assert _st(B.bl_tl2_gemv, P, v1, P, P, P) == B.BL_ERR_LAYOUT
+    assert _st(B.bl_gemv, P, v2, P, P, P, 1, P) == B.BL_ERR_LAYOUT
+    assert _st(B.bl_pack_ternary, P, v2, P) == B.BL_ERR_LAYOUT
+    # nulls, alignment, tampering
+    assert _st(B.bl_tl2_pack, 0, v2, P) == B.BL_ERR_NULL
+    assert _st(B.bl_tl2_unpack, P, v2, 0) == B.BL_ERR_NULL
+    assert _st(B.bl_tl2_gemv, P, v2, 0, P, P) == B.BL_ERR_NULL
+    assert _st(B.bl_tl2_gemv, P, v2, P, P, 0) == B.BL_ERR_NULL
+    assert _st(B.bl_tl2_gemv, P + 8, v2, P, P, P) == B.BL_ERR_ALIGN
+    assert _st(B.bl_tl2_gemv, P, v2, P + 4, P, P) == B.BL_ERR_ALIGN
+    assert _st(B.bl_tl2_pack, P, v2, P + 4) == B.BL_ERR_ALIGN
+    bad = B.bl_tl2_desc_init(128, 144, 0.5)
+    bad.bytes += 16
+    assert _st(B.bl_tl2_gemv, P, bad, P, P, P) == B.BL_ERR_BUF_SMALL
+    bad = B.bl_tl2_desc_init(128, 144, 0.5)
+    bad.Kp = 192
+    assert _st(B.bl_tl2_unpack, P, bad, P) == B.BL_ERR_SHAPE
+
