@@ -40,7 +40,7 @@ def parse_args():
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
     ap.add_argument("--full-100b", action="store_true",
                     help="extra: build all 80 layers of the 100B-shape model (37 GB packed) and time a whole token")
-    ap.add_argument("--only", default="", help="run only one extra section (copy|prefill|decode7b|decode100b|paper100b|config1|appendixa) and print it")
+    ap.add_argument("--only", default="", help="run only one extra section (copy|prefill|decode7b|decode100b|paper100b|config1|appendixa|tl2) and print it")
     return ap.parse_args()
 
 
@@ -222,6 +222,39 @@ def extra_decode_shape(torch, name, hidden, ffn, M, layers, steps, use_graph):
                       "frac_of_hbm_peak": round(pb / us / 1e3 / HBM_PEAK_GBS, 4)}
     res["launch"] = mode
     return res
+
+
+def extra_tl2(torch, use_graph):
+    """The 1.78-bit layout on the paper's TL2 code beside the 2-bit layout: one-token decode product of single
+    matrices (bl_tl2_gemv has no grouped launch), copies rotated so that every launch reads HBM.  Both kernels
+    compute the same bits; the time ratio is the answer to whether 11 % fewer bytes outweigh the extra table
+    lookups."""
+    from paper_2410_16144_amd import ops, synth
+    dev = torch.device("cuda:0")
+    rows = []
+    for K, N, copies in ((12288, 32768, 6), (16384, 32768, 4), (12288, 33792, 6), (8192, 45568, 6), (4096, 11008, 40)):
+        ws = [synth.ternary_weights_device(900 + i, N, K, dev) for i in range(2)]
+        two = [ops.pack_ternary(ws[i % 2], 0.02) for i in range(2)]
+        tl2 = [ops.tl2_pack(ws[i % 2], 0.02) for i in range(2)]
+        two = [ops.PackedWeight(two[i % 2].blob.clone(), two[i % 2].desc) for i in range(copies)]
+        tl2 = [ops.PackedWeight(tl2[i % 2].blob.clone(), tl2[i % 2].desc) for i in range(copies)]
+        del ws
+        x = torch.randn((1, K), device=dev, dtype=torch.float32).to(torch.bfloat16)
+        qa2 = ops.quant_act(x)
+        qa3 = ops.quant_act(x, ops.tl2_quant_buffer(K, dev))
+        out = torch.empty((1, N), dtype=torch.float32, device=dev)
+        same = torch.equal(ops.gemv(two[0], qa2), ops.tl2_gemv(tl2[0], qa3))
+        groups = [ops.GemvGroup([p], [qa2], [out]) for p in two]
+        steps = 40 * copies
+        ms2, _, _ = run_steps(torch, [g.launch for g in groups], steps, use_graph)
+        ms3, _, mode = run_steps(torch, [(lambda p=p: ops.tl2_gemv(p, qa3, out)) for p in tl2], steps, use_graph)
+        us2, us3 = ms2 * 1e3 / steps, ms3 * 1e3 / steps
+        rows.append({"K": K, "N": N, "bytes_2bit": N * K // 4, "bytes_tl2": int(tl2[0].desc.bytes),
+                     "us_2bit": round(us2, 2), "us_tl2": round(us3, 2), "tl2_speedup": round(us2 / us3, 3),
+                     "GBps_2bit": round(N * K / 4 / us2 / 1e3, 1), "GBps_tl2_own_bytes": round(tl2[0].desc.bytes / us3 / 1e3, 1),
+                     "outputs_bit_identical": bool(same), "launch": mode})
+        del two, tl2, groups
+    return rows
 
 
 def extra_config1(torch, use_graph):
@@ -408,6 +441,7 @@ def main():
                 "paper100b": lambda: extra_decode_shape(torch, "Appendix-A 100B", 8192, 45568, 1, 6, 120, use_graph),
                 "config1": lambda: extra_config1(torch, use_graph),
                 "appendixa": lambda: extra_appendix_a(torch, use_graph),
+                "tl2": lambda: extra_tl2(torch, use_graph),
                 }[args.only]()
         print(json.dumps({args.only: sect}))
         return

@@ -140,7 +140,7 @@ __global__ __launch_bounds__(kThreads, 8) void tl2_gemv_kernel(const uint4* __re
     };
     load_batch(ks);
     __syncthreads();   // the table is in place
-    int acc = 0;
+    int part[3] = {0, 0, 0};   // independent sums: the dot products of a word do not wait for one another
     for (int kc0 = ks; kc0 < KC; kc0 += G * kInFlight) {
 #pragma unroll
         for (int u = 0; u < kInFlight; ++u) {
@@ -148,16 +148,26 @@ __global__ __launch_bounds__(kThreads, 8) void tl2_gemv_kernel(const uint4* __re
             if (kc < KC) {   // uniform
                 const int32_t* __restrict__ qk = q + kc * (BL_TL2_TILE_K / 4);
                 const uint32_t word[4] = {w[u].x, w[u].y, w[u].z, w[u].w};
+                // the table entries of a word are fetched while the previous word's dot products run
+                int e[2][kGroupsPerWord];
 #pragma unroll
-                for (int s = 0; s < 4; ++s)
+                for (int i = 0; i < kGroupsPerWord; ++i) e[0][i] = lut[(word[0] >> (5 * i)) & 31];
+#pragma unroll
+                for (int s = 0; s < 4; ++s) {
+                    if (s < 3) {
+#pragma unroll
+                        for (int i = 0; i < kGroupsPerWord; ++i) e[(s + 1) & 1][i] = lut[(word[s + 1] >> (5 * i)) & 31];
+                    }
 #pragma unroll
                     for (int i = 0; i < kGroupsPerWord; ++i)
-                        acc = __builtin_amdgcn_sdot4(lut[(word[s] >> (5 * i)) & 31],
-                                                     group_activations(qk, kGroupsPerWord * s + i), acc, false);
+                        part[i % 3] = __builtin_amdgcn_sdot4(e[s & 1][i], group_activations(qk, kGroupsPerWord * s + i),
+                                                             part[i % 3], false);
+                }
             }
         }
         if (kc0 + G * kInFlight < KC) load_batch(kc0 + G * kInFlight);
     }
+    const int acc = part[0] + part[1] + part[2];
     red[wave * kWave + lane] = acc;
     __syncthreads();
     if (ks == 0 && rb < row_blocks) {

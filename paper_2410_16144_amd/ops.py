@@ -82,7 +82,7 @@ def tl2_gemv(pw: PackedWeight, qa: "QuantAct", out: Optional[torch.Tensor] = Non
     acc = torch.empty((1, pw.N), dtype=torch.int32, device=dev) if want_acc else None
     B.bl_tl2_gemv(pw.blob.data_ptr(), pw.desc, qa.q.data_ptr(), qa.a_scale.data_ptr(), out.data_ptr(),
                   acc.data_ptr() if acc is not None else 0, _stream())
-    return out, acc
+    return (out, acc) if want_acc else out
 
 
 @dataclass
