@@ -150,6 +150,34 @@ int main(int argc, char **argv) {
     print_i32("acc_fused", acc, (size_t)N);
     printf("fused_pair_equal %d\n", memcmp(acc, acc2, (size_t)N * 4) == 0);
 
+    /* the 1.78-bit layout: round trip, and the one-token product equals the 2-bit one on the same weights */
+    {
+        bl_packed_desc d2;
+        BL(bl_tl2_desc_init(N, K, w_scale, &d2));
+        const int64_t q_bytes = bl_tl2_padded_k(K) > Kp ? bl_tl2_padded_k(K) : Kp;
+        void *packed2_dev;
+        int8_t *q2_dev;
+        HIP(hipMalloc(&packed2_dev, d2.bytes));
+        HIP(hipMalloc((void **)&q2_dev, (size_t)q_bytes));
+        HIP(hipMemset(q2_dev, 0, (size_t)q_bytes));
+        HIP(hipMemset(w_back_dev, 9, (size_t)(N * K)));
+        BL(bl_tl2_pack(w_dev, &d2, packed2_dev, bad_dev, NULL));
+        BL(bl_tl2_unpack(packed2_dev, &d2, w_back_dev, NULL));
+        BL(bl_quant_act(x_dev, BL_F32, 1, K, K, q2_dev, a_scale_dev, q_sum_dev, NULL));
+        BL(bl_tl2_gemv(packed2_dev, &d2, q2_dev, a_scale_dev, out_dev, acc_dev, NULL));
+        BL(bl_gemv(packed_dev, &d, q2_dev, a_scale_dev, q_sum_dev, 1, out2_dev, acc2_dev, NULL));
+        HIP(hipDeviceSynchronize());
+        HIP(hipMemcpy(w_back, w_back_dev, (size_t)(N * K), hipMemcpyDeviceToHost));
+        HIP(hipMemcpy(acc, acc_dev, (size_t)N * 4, hipMemcpyDeviceToHost));
+        HIP(hipMemcpy(acc2, acc2_dev, (size_t)N * 4, hipMemcpyDeviceToHost));
+        HIP(hipMemcpy(out, out_dev, (size_t)N * 4, hipMemcpyDeviceToHost));
+        HIP(hipMemcpy(out2, out2_dev, (size_t)N * 4, hipMemcpyDeviceToHost));
+        printf("tl2_desc %lld %llu\n", (long long)d2.Kp, (unsigned long long)d2.bytes);
+        printf("tl2_roundtrip %d\n", memcmp(w, w_back, (size_t)(N * K)) == 0);
+        print_i32("acc_tl2", acc, (size_t)N);
+        printf("tl2_equals_gemv %d %d\n", memcmp(acc, acc2, (size_t)N * 4) == 0, memcmp(out, out2, (size_t)N * 4) == 0);
+    }
+
     /* argument errors come back as codes, before anything is launched */
     printf("err_m_range %d\n", (int)bl_gemv(packed_dev, &d, q_dev, a_scale_dev, q_sum_dev, 9, out_dev, NULL, NULL));
     printf("err_null %d\n", (int)bl_gemv(NULL, &d, q_dev, a_scale_dev, q_sum_dev, 1, out_dev, NULL, NULL));

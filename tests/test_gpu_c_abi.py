@@ -71,6 +71,11 @@ def test_c_program_matches_oracle(N, K, M):
     assert rec["gemm_equals_gemv"] == ["1", "1"]
     assert np.array_equal(_ints(rec["acc_fused"]), ref["acc"][0])
     assert rec["fused_pair_equal"] == ["1"]
+    KC3 = -(-K // 72)
+    assert _ints(rec["tl2_desc"]).tolist() == [72 * KC3, Np * KC3 * 16]
+    assert rec["tl2_roundtrip"] == ["1"]
+    assert np.array_equal(_ints(rec["acc_tl2"]), ref["acc"][0])
+    assert rec["tl2_equals_gemv"] == ["1", "1"]
     assert rec["err_m_range"] == ["3"] and rec["err_null"] == ["1"]
 
 
