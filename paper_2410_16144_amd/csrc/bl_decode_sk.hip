@@ -177,14 +177,10 @@ __global__ __launch_bounds__(kThreads, 8) void decode_sk_kernel(BL_FIRST_WG_PARA
 
 template <int U, bool FUSED, bool XBF16>
 hipError_t launch_sk(const DecodeBatch& b, size_t lds, hipStream_t s) {
-    static bool attr_set = false;
+    static LdsCeiling ceiling;
     auto kernel = &decode_sk_kernel<U, FUSED, XBF16>;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDecodeLds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    const hipError_t e = ceiling.ensure(reinterpret_cast<const void*>(kernel));
+    if (e != hipSuccess) return e;
     const FirstWgs first(b);
     kernel<<<dim3((unsigned)b.total_wgs), dim3(kThreads), lds, s>>>(BL_FIRST_WG_ARGS(first), b);
     return hipGetLastError();

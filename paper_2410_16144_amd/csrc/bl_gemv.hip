@@ -311,13 +311,9 @@ __global__ __launch_bounds__(kThreads, 8) void decode_mfma_kernel(BL_FIRST_WG_PA
 }
 
 template <typename Kernel>
-hipError_t launch_kernel(Kernel kernel, bool& attr_set, const DecodeBatch& b, size_t lds_bytes, hipStream_t s) {
-    if (!attr_set) {   // raise the dynamic-LDS ceiling once per kernel (a host-side setting, no allocation)
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDecodeLds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+hipError_t launch_kernel(Kernel kernel, LdsCeiling& ceiling, const DecodeBatch& b, size_t lds_bytes, hipStream_t s) {
+    const hipError_t e = ceiling.ensure(reinterpret_cast<const void*>(kernel));
+    if (e != hipSuccess) return e;
     const FirstWgs first(b);
     kernel<<<dim3((unsigned)b.total_wgs), dim3(kThreads), lds_bytes, s>>>(BL_FIRST_WG_ARGS(first), b);
     return hipGetLastError();
@@ -326,7 +322,7 @@ hipError_t launch_kernel(Kernel kernel, bool& attr_set, const DecodeBatch& b, si
 // KIND: 0 = dot-product kernel, plain; 1 = dot-product kernel, fused; 2..4 = matrix-core kernel with QMODE 0..2
 template <int M, int KIND, bool XBF16>
 hipError_t launch_one(const DecodeBatch& b, size_t lds_bytes, hipStream_t s) {
-    static bool attr_set = false;
+    static LdsCeiling attr_set;   // one per instantiation, i.e. per kernel
     if constexpr (KIND == 0) return launch_kernel(&decode_kernel<M, false, true>, attr_set, b, lds_bytes, s);
     else if constexpr (KIND == 1) return launch_kernel(&decode_kernel<M, true, XBF16>, attr_set, b, lds_bytes, s);
     else if constexpr (KIND == 2) return launch_kernel(&decode_mfma_kernel<M, 0, true>, attr_set, b, lds_bytes, s);

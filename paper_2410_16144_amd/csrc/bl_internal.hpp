@@ -87,6 +87,21 @@ struct QuantBatch {
 
 constexpr int kMaxDecodeLds = 128 * 1024;   // dynamic LDS ceiling of the decode kernels
 
+// Raises one kernel's dynamic-LDS ceiling to kMaxDecodeLds, once per device (the setting belongs to the device the
+// call is made on): a host-side attribute, no allocation.  One object per kernel; a repeated call from another
+// thread is harmless.
+struct LdsCeiling {
+    uint64_t done = 0;   // one bit per device ordinal below 64; other devices set the attribute on every launch
+    hipError_t ensure(const void* kernel) {
+        int dev = -1;
+        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = -1;
+        if (dev >= 0 && ((done >> dev) & 1)) return hipSuccess;
+        const hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDecodeLds);
+        if (e == hipSuccess && dev >= 0) done |= 1ull << dev;
+        return e;
+    }
+};
+
 // Launchers (each returns the hipError_t of its launch).
 hipError_t launch_pack(const int8_t* w, int64_t N, int64_t K, int64_t Np, int64_t Kp, uint32_t* packed,
                        int32_t* bad_count, hipStream_t s);
