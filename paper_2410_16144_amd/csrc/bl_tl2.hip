@@ -103,10 +103,15 @@ __global__ __launch_bounds__(256) void tl2_unpack_kernel(const uint32_t* __restr
 // activations as 18 words (wave-uniform: scalar loads, scalar shifts); the fourth byte is whatever follows and
 // meets the table entry's zero byte.
 __device__ __forceinline__ int group_activations(const int32_t* __restrict__ qk, int g) {
+    // read as 64-bit pairs (a tile's activations start at a multiple of 8 bytes): from two separate 32-bit loads
+    // the compiler would build ONE unaligned 32-bit load for a group that straddles two words, which has to be a
+    // vector load, and waiting for that one drains the weight tiles in flight
+    const int2* __restrict__ q2 = reinterpret_cast<const int2*>(qk);
     const int word = (3 * g) >> 2, off = (3 * g) & 3;
-    if (off == 0) return qk[word];
-    if (off == 1) return (int)((uint32_t)qk[word] >> 8);
-    const uint64_t pair = (uint32_t)qk[word] | ((uint64_t)(uint32_t)qk[word + 1] << 32);
+    const auto at = [&](int wd) { return (uint32_t)((wd & 1) ? q2[wd >> 1].y : q2[wd >> 1].x); };
+    if (off == 0) return (int)at(word);
+    if (off == 1) return (int)(at(word) >> 8);
+    const uint64_t pair = at(word) | ((uint64_t)at(word + 1) << 32);
     return (int)(uint32_t)(pair >> (8 * off));
 }
 
