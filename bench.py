@@ -247,14 +247,42 @@ def extra_tl2(torch, use_graph):
         groups = [ops.GemvGroup([p], [qa2], [out]) for p in two]
         steps = 40 * copies
         ms2, _, _ = run_steps(torch, [g.launch for g in groups], steps, use_graph)
-        ms3, _, mode = run_steps(torch, [(lambda p=p: ops.tl2_gemv(p, qa3, out)) for p in tl2], steps, use_graph)
+        groups3 = [ops.Tl2GemvGroup([p], [qa3], [out]) for p in tl2]
+        ms3, _, mode = run_steps(torch, [g.launch for g in groups3], steps, use_graph)
         us2, us3 = ms2 * 1e3 / steps, ms3 * 1e3 / steps
         rows.append({"K": K, "N": N, "bytes_2bit": N * K // 4, "bytes_tl2": int(tl2[0].desc.bytes),
                      "us_2bit": round(us2, 2), "us_tl2": round(us3, 2), "tl2_speedup": round(us2 / us3, 3),
                      "GBps_2bit": round(N * K / 4 / us2 / 1e3, 1), "GBps_tl2_own_bytes": round(tl2[0].desc.bytes / us3 / 1e3, 1),
                      "outputs_bit_identical": bool(same), "launch": mode})
-        del two, tl2, groups
-    return rows
+        del two, tl2, groups, groups3
+    # a whole decoder layer per launch (7 matrices, plain form: quantized activations given), both layouts
+    from paper_2410_16144_amd import decode_layer
+    layers = []
+    for name, hidden, ffn, count in (("3B-shape", 3200, 8640, 30), ("7B-shape", 4096, 11008, 20), ("100B-shape", 12288, 33792, 4)):
+        projs = synth.layer_projections(hidden, ffn)
+        xs = {K: torch.randn((1, K), device=dev, dtype=torch.float32).to(torch.bfloat16) for K in (hidden, ffn)}
+        qa2 = {K: ops.quant_act(x) for K, x in xs.items()}
+        qa3 = {K: ops.quant_act(x, ops.tl2_quant_buffer(K, dev)) for K, x in xs.items()}
+        g2, g3 = [], []
+        for c in range(count):
+            ws = [synth.ternary_weights_device(950 + 7 * (c % 2) + i, p.N, p.K, dev) for i, p in enumerate(projs)]
+            outs = [torch.empty((1, p.N), dtype=torch.float32, device=dev) for p in projs]
+            g2.append(ops.GemvGroup([ops.pack_ternary(w, 0.02) for w in ws], [qa2[p.K] for p in projs], outs))
+            g3.append(ops.Tl2GemvGroup([ops.tl2_pack(w, 0.02) for w in ws], [qa3[p.K] for p in projs], outs))
+            del ws
+        same = all(torch.equal(a.clone(), b) for a, b in zip([o.clone() for o in g2[0].launch()], g3[0].launch()))
+        steps = 20 * count
+        ms2, _, _ = run_steps(torch, [g.launch for g in g2], steps, use_graph)
+        ms3, _, mode = run_steps(torch, [g.launch for g in g3], steps, use_graph)
+        b2 = sum(p.N * p.K // 4 for p in projs)
+        b3 = sum(int(w.desc.bytes) for w in g3[0].weights)
+        layers.append({"layer": name, "bytes_2bit": b2, "bytes_tl2": b3, "us_2bit": round(ms2 * 1e3 / steps, 2),
+                       "us_tl2": round(ms3 * 1e3 / steps, 2), "tl2_speedup": round(ms2 / ms3, 3),
+                       "GBps_2bit": round(b2 / (ms2 * 1e3 / steps) / 1e3, 1),
+                       "GBps_tl2_own_bytes": round(b3 / (ms3 * 1e3 / steps) / 1e3, 1),
+                       "outputs_bit_identical": bool(same), "launch": mode})
+        del g2, g3
+    return {"single_matrices": rows, "layers_one_launch": layers}
 
 
 def extra_config1(torch, use_graph):

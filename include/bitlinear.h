@@ -260,7 +260,8 @@ bl_status bl_gemm(const void *packed_dev, const bl_packed_desc *d, const int8_t 
  * holds the weights k = 72 kc + 18 s + 3 i + {0,1,2} as code i = sign << 4 |
  * index at bits [5 i, 5 i + 4].  Padding weights are 0.  The decode product
  * reads 11 % fewer bytes than with the 2-bit layout and spends about twice the
- * vector instructions per weight; one token only, no fused quantization.
+ * vector instructions per weight (measured: a tie on 100B-shape layers, slower
+ * on smaller ones); one token only, no fused quantization.
  */
 #define BL_TL2_TILE_K 72
 #define BL_TL2_LAYOUT_VERSION 2
@@ -295,6 +296,19 @@ bl_status bl_tl2_unpack(const void *packed_dev, const bl_packed_desc *d, int8_t 
  */
 bl_status bl_tl2_gemv(const void *packed_dev, const bl_packed_desc *d, const int8_t *q_dev,
                       const float *a_scale_dev, float *out_dev, int32_t *acc_dev, void *stream);
+
+/*
+ * `count` bl_tl2_gemv problems (1..BL_MAX_BATCH) in ONE kernel launch, e.g. the
+ * seven projections of a decoder layer.  Items are bl_gemv_item with version-2
+ * descriptors; q_sum_dev is not used and may be NULL (the table yields signed
+ * weights).  `workspace_dev`: as for bl_gemv_batch (may be NULL): with it,
+ * launches of medium size are work-balanced across workgroups.  Each item is
+ * validated like a bl_tl2_gemv call; results are identical.
+ * Errors: BL_ERR_NULL, BL_ERR_COUNT, BL_ERR_LAYOUT, BL_ERR_SHAPE,
+ *         BL_ERR_BUF_SMALL, BL_ERR_ALIGN, BL_ERR_HIP.
+ */
+bl_status bl_tl2_gemv_batch(const bl_gemv_item *items, int32_t count, void *workspace_dev,
+                            void *stream);
 
 /*
  * Launch-shape override for experiments and sweeps; process-wide, not thread-safe, never

@@ -31,7 +31,7 @@ BL_TL2_LAYOUT_VERSION = 2
 DECLARED_SYMBOLS = (
     "bl_padded_k", "bl_padded_n", "bl_packed_desc_init", "bl_pack_ternary", "bl_unpack_ternary",
     "bl_quant_act", "bl_quant_act_batch", "bl_gemv", "bl_gemv_batch", "bl_decode_batch", "bl_gemm", "bl_set_tuning", "bl_get_stat", "bl_status_str", "bl_last_hip_error", "bl_version",
-    "bl_tl2_padded_k", "bl_tl2_desc_init", "bl_tl2_pack", "bl_tl2_unpack", "bl_tl2_gemv",
+    "bl_tl2_padded_k", "bl_tl2_desc_init", "bl_tl2_pack", "bl_tl2_unpack", "bl_tl2_gemv", "bl_tl2_gemv_batch",
 )
 
 
@@ -110,6 +110,7 @@ def lib():
     l.bl_tl2_pack.argtypes = [vp, dp, vp, vp, vp]
     l.bl_tl2_unpack.argtypes = [vp, dp, vp, vp]
     l.bl_tl2_gemv.argtypes = [vp, dp, vp, vp, vp, vp, vp]
+    l.bl_tl2_gemv_batch.argtypes = [ctypes.POINTER(GemvItem), i32, vp, vp]
     l.bl_set_tuning.argtypes = [ctypes.c_char_p, i32]
     l.bl_get_stat.argtypes = [ctypes.c_char_p]
     l.bl_get_stat.restype = i64
@@ -119,7 +120,7 @@ def lib():
     l.bl_last_hip_error.restype = ctypes.c_char_p
     for name in ("bl_packed_desc_init", "bl_pack_ternary", "bl_unpack_ternary", "bl_quant_act", "bl_quant_act_batch", "bl_gemv",
                  "bl_gemv_batch", "bl_decode_batch", "bl_gemm", "bl_set_tuning", "bl_tl2_desc_init", "bl_tl2_pack",
-                 "bl_tl2_unpack", "bl_tl2_gemv"):
+                 "bl_tl2_unpack", "bl_tl2_gemv", "bl_tl2_gemv_batch"):
         getattr(l, name).restype = ctypes.c_int
     _lib = l
     return l
@@ -195,7 +196,7 @@ def make_gemv_items(items):
     items = list(items)
     arr = (GemvItem * len(items))()
     for i, (packed, desc, q, a, s, out, acc) in enumerate(items):
-        arr[i] = GemvItem(packed, ctypes.pointer(desc), q, a, s, out, acc or None)
+        arr[i] = GemvItem(packed, ctypes.pointer(desc), q, a, s or None, out, acc or None)
     return arr
 
 
@@ -253,6 +254,13 @@ def bl_tl2_gemv(packed_dev: int, desc: PackedDesc, q_dev: int, a_scale_dev: int,
                 stream: int = 0):
     _check(lib().bl_tl2_gemv(packed_dev, ctypes.byref(desc), q_dev, a_scale_dev, out_dev, acc_dev or None,
                              stream or None), "bl_tl2_gemv")
+
+
+def bl_tl2_gemv_batch(items, workspace_dev: int = 0, stream: int = 0):
+    """items: a ctypes GemvItem array from make_gemv_items (q_sum_dev may be 0), or an iterable of tuples."""
+    if not isinstance(items, ctypes.Array):
+        items = make_gemv_items(items)
+    _check(lib().bl_tl2_gemv_batch(items, len(items), workspace_dev or None, stream or None), "bl_tl2_gemv_batch")
 
 
 def bl_set_tuning(key: str, value: int):

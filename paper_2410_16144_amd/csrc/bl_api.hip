@@ -155,18 +155,43 @@ bl_status bl_tl2_unpack(const void* packed_dev, const bl_packed_desc* d, int8_t*
                                             w_dev, static_cast<hipStream_t>(stream)));
 }
 
+bl_status bl_tl2_gemv_batch(const bl_gemv_item* items, int32_t count, void* workspace_dev, void* stream) {
+    if (!items) return BL_ERR_NULL;
+    if (count < 1 || count > BL_MAX_BATCH) return BL_ERR_COUNT;
+    if (workspace_dev && !aligned(workspace_dev, 256)) return BL_ERR_ALIGN;
+    bl::DecodeBatch b;
+    memset(&b, 0, sizeof b);
+    b.ws = static_cast<unsigned long long*>(workspace_dev);
+    b.layout = 2;
+    for (int i = 0; i < count; ++i) {
+        const bl_gemv_item& it = items[i];
+        if (!it.packed_dev || !it.desc || !it.q_dev || !it.a_scale_dev || !it.out_dev) return BL_ERR_NULL;
+        bl_status s = check_tl2_desc(it.desc);
+        if (s != BL_OK) return s;
+        if (!aligned(it.packed_dev, 16) || !aligned(it.q_dev, 16) || !aligned(it.a_scale_dev, 4) ||
+            !aligned(it.out_dev, 4) || (it.acc_dev && !aligned(it.acc_dev, 4)))
+            return BL_ERR_ALIGN;
+        bl::DecodeProblem& p = b.p[i];
+        p.packed = static_cast<const uint4*>(it.packed_dev);
+        p.q = reinterpret_cast<const int32_t*>(it.q_dev);
+        p.a_scale = it.a_scale_dev;
+        p.out = it.out_dev;
+        p.acc = it.acc_dev;
+        p.N = (int32_t)it.desc->N;
+        p.K = (int32_t)it.desc->K;
+        p.KC = (int32_t)(it.desc->Kp / BL_TL2_TILE_K);
+        p.row_blocks = (int32_t)(it.desc->Np / BL_TILE_N);
+        p.w_scale = it.desc->w_scale;
+    }
+    b.count = count;
+    drop_stale_hip_error();
+    return hip_status(bl::launch_decode(b, 1, false, static_cast<hipStream_t>(stream)));
+}
+
 bl_status bl_tl2_gemv(const void* packed_dev, const bl_packed_desc* d, const int8_t* q_dev, const float* a_scale_dev,
                       float* out_dev, int32_t* acc_dev, void* stream) {
-    if (!packed_dev || !d || !q_dev || !a_scale_dev || !out_dev) return BL_ERR_NULL;
-    bl_status s = check_tl2_desc(d);
-    if (s != BL_OK) return s;
-    if (!aligned(packed_dev, 16) || !aligned(q_dev, 16) || !aligned(a_scale_dev, 4) || !aligned(out_dev, 4) ||
-        (acc_dev && !aligned(acc_dev, 4)))
-        return BL_ERR_ALIGN;
-    drop_stale_hip_error();
-    return hip_status(bl::launch_tl2_gemv(static_cast<const uint4*>(packed_dev), reinterpret_cast<const int32_t*>(q_dev),
-                                          a_scale_dev, out_dev, acc_dev, d->N, d->Np, d->Kp, d->w_scale,
-                                          static_cast<hipStream_t>(stream)));
+    const bl_gemv_item it = {packed_dev, d, q_dev, a_scale_dev, nullptr, out_dev, acc_dev};
+    return bl_tl2_gemv_batch(&it, 1, nullptr, stream);
 }
 
 static bl_status fill_quant_problem(const bl_quant_item& it, bl::QuantProblem& p) {

@@ -46,6 +46,79 @@ __device__ __forceinline__ void tile_mac(const uint4& w, QPtr qk, int q_stride_w
     }
 }
 
+// ---- layout version 2: the paper's TL2 code (Table 3), six 5-bit codes per 32-bit word, 72 k per tile --------
+//
+// The paper's TL2 kernel looks up partial sums of ACTIVATION triples by weight code; that replaces multiplies, which
+// the dot-product units give for free here.  What carries over is the code: three weights in 5 bits, so the stream
+// from HBM is shorter.  The table is the other way round: 32 entries, code -> the three weights as int8 (fourth
+// byte zero), one 32-bit word each, in LDS.  32 words lie in 32 different banks, so the lookups of a wavefront
+// never conflict, whatever the codes.  Per group of three weights: a shift and a mask (table address), one LDS
+// read, one v_dot4_i32_i8 against the three activations -- 1.0 vector operation per weight against 0.56 for the
+// 2-bit layout, for 11 % fewer bytes.  Signed weights come out of the table, so there is no sum(q) correction.
+constexpr int kTl2GroupsPerWord = 6;
+constexpr int kTl2QWords = BL_TL2_TILE_K / 4;   // a tile's 72 activations as 18 words
+
+// code -> the three weights: balanced-ternary digits of the index (most significant first), negated if the sign
+// bit is set.  Codes that Table 3 does not use give zeros.
+__device__ __forceinline__ void tl2_weights(int code, int (&w)[3]) {
+    int v = code & 15;
+    const bool neg = code & 16;
+    w[0] = w[1] = w[2] = 0;
+    if (v > 13 || (neg && v == 0)) return;
+#pragma unroll
+    for (int j = 2; j >= 0; --j) {     // least significant digit first; digits are -1, 0, +1
+        int d = (v + 1) % 3 - 1;       // v mod 3 mapped to {0, 1, -1}
+        w[j] = d;
+        v = (v - d) / 3;
+    }
+    if (neg) { w[0] = -w[0]; w[1] = -w[1]; w[2] = -w[2]; }
+}
+
+// The table: threads 0..31 write one entry each; a workgroup barrier must follow before the first lookup.
+__device__ __forceinline__ void tl2_fill_table(int* lut, int tid) {
+    if (tid < 32) {
+        int t[3];
+        tl2_weights(tid, t);
+        lut[tid] = (t[0] & 0xff) | (t[1] & 0xff) << 8 | (t[2] & 0xff) << 16;
+    }
+}
+
+// The three activations that meet group g (0..23) of a tile, as the low three bytes of a word; the fourth byte is
+// whatever follows and meets the table entry's zero byte.  qk: the tile's 72 activations (wave-uniform: scalar
+// loads, scalar shifts).  They are read as 64-bit pairs (a tile's activations start at a multiple of 8 bytes): from
+// two separate 32-bit loads the compiler builds ONE unaligned 32-bit load for a group that straddles two words,
+// which has to be a vector load, and waiting for that one drains the weight tiles in flight.
+__device__ __forceinline__ int tl2_group_activations(const int32_t* __restrict__ qk, int g) {
+    const int2* __restrict__ q2 = reinterpret_cast<const int2*>(qk);
+    const int word = (3 * g) >> 2, off = (3 * g) & 3;
+    const auto at = [&](int wd) { return (uint32_t)((wd & 1) ? q2[wd >> 1].y : q2[wd >> 1].x); };
+    if (off == 0) return (int)at(word);
+    if (off == 1) return (int)(at(word) >> 8);
+    const uint64_t pair = at(word) | ((uint64_t)at(word + 1) << 32);
+    return (int)(uint32_t)(pair >> (8 * off));
+}
+
+// One 64 x 72 tile of the version-2 layout, one token: w = this lane's 16 bytes, qk = the tile's activations.
+__device__ __forceinline__ void tl2_tile_mac(const uint4& w, const int32_t* __restrict__ qk, const int* lut, int& acc) {
+    const uint32_t word[4] = {w.x, w.y, w.z, w.w};
+    int part[3] = {0, 0, 0};   // independent sums: the dot products of a word do not wait for one another
+    int e[2][kTl2GroupsPerWord];   // the table entries of a word are fetched while the previous word's dot products run
+#pragma unroll
+    for (int i = 0; i < kTl2GroupsPerWord; ++i) e[0][i] = lut[(word[0] >> (5 * i)) & 31];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        if (s < 3) {
+#pragma unroll
+            for (int i = 0; i < kTl2GroupsPerWord; ++i) e[(s + 1) & 1][i] = lut[(word[s + 1] >> (5 * i)) & 31];
+        }
+#pragma unroll
+        for (int i = 0; i < kTl2GroupsPerWord; ++i)
+            part[i % 3] = __builtin_amdgcn_sdot4(e[s & 1][i], tl2_group_activations(qk, kTl2GroupsPerWord * s + i),
+                                                 part[i % 3], false);
+    }
+    acc += part[0] + part[1] + part[2];
+}
+
 // Quantize M token rows into LDS; per-token scale and partial sums of q are left in s_f / s_i (LDS).
 // General form: the rows are read twice (the second read hits L1/L2).  Both passes walk the rows R at a
 // time with the R loads of a step issued together, so a pass costs one memory round trip per step

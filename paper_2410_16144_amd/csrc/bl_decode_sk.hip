@@ -22,9 +22,11 @@ namespace {
 constexpr int kSkMaxRb = 32;   // row blocks one chunk may touch (LDS: 256 bytes each)
 constexpr int kSumBits = 40;   // low bits of a workspace word that hold the partial sum
 
-template <int U, bool FUSED, bool XBF16>
+template <int U, bool FUSED, bool XBF16, int LAYOUT = 1>   // LAYOUT 2: TL2-coded tiles (plain form only)
 __global__ __launch_bounds__(kThreads, 8) void decode_sk_kernel(BL_FIRST_WG_PARAMS, const DecodeBatch b) {
+    static_assert(LAYOUT == 1 || (LAYOUT == 2 && !FUSED), "the TL2 layout has the plain form only");
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    __shared__ int tl2_lut[LAYOUT == 2 ? 32 : 1];
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
@@ -69,9 +71,10 @@ __global__ __launch_bounds__(kThreads, 8) void decode_sk_kernel(BL_FIRST_WG_PARA
     float scale = 0.0f;
     if constexpr (!FUSED) {
         load_batch(0);
-        qsum = p.q_sum[0];
+        if constexpr (LAYOUT == 2) tl2_fill_table(tl2_lut, tid);   // signed weights: no sum(q) correction
+        else qsum = p.q_sum[0];
         scale = p.a_scale[0];
-        __syncthreads();   // red is zero before the first deposit
+        __syncthreads();   // red is zero before the first deposit (and the TL2 table is in place)
     } else {
         const bool vec = p.x_flags & 2;
         int holding_waves = kWaves;   // waves with a part of sum(q)
@@ -136,11 +139,12 @@ __global__ __launch_bounds__(kThreads, 8) void decode_sk_kernel(BL_FIRST_WG_PARA
                         ++rb;
                         kc = 0;
                     }
-                    if constexpr (FUSED) tile_mac<1>(w[u], reinterpret_cast<const int32_t*>(lds_q) + kc * 16, Kp / 4, acc);
+                    if constexpr (LAYOUT == 2) tl2_tile_mac(w[u], p.q + kc * kTl2QWords, tl2_lut, acc.lo[0]);
+                    else if constexpr (FUSED) tile_mac<1>(w[u], reinterpret_cast<const int32_t*>(lds_q) + kc * 16, Kp / 4, acc);
                     else tile_mac<1>(w[u], p.q + kc * 16, Kp / 4, acc);
                     ++kc;
                 }
-                __builtin_amdgcn_sched_barrier(0);
+                if constexpr (LAYOUT == 1) __builtin_amdgcn_sched_barrier(0);
             }
             i0 += U;
             if (i0 >= mine) break;
@@ -175,10 +179,10 @@ __global__ __launch_bounds__(kThreads, 8) void decode_sk_kernel(BL_FIRST_WG_PARA
     }
 }
 
-template <int U, bool FUSED, bool XBF16>
+template <int U, bool FUSED, bool XBF16, int LAYOUT = 1>
 hipError_t launch_sk(const DecodeBatch& b, size_t lds, hipStream_t s) {
     static LdsCeiling ceiling;
-    auto kernel = &decode_sk_kernel<U, FUSED, XBF16>;
+    auto kernel = &decode_sk_kernel<U, FUSED, XBF16, LAYOUT>;
     const hipError_t e = ceiling.ensure(reinterpret_cast<const void*>(kernel));
     if (e != hipSuccess) return e;
     const FirstWgs first(b);
@@ -223,7 +227,11 @@ bool plan_decode_split(DecodeBatch& b, bool fused, int& tiles_per_wave) {
     // dispatched as others finish adapt better to compute units that stream at different speeds.
     const int64_t per_cu = total / cus;
     int mult = g_split;
-    if (mult == 0) {
+    if (mult == 0 && b.layout == 2 && per_cu >= 32) {
+        // TL2-coded tiles: the table lookups want as many waves per compute unit as fit, and with two workgroups per
+        // unit the balanced form stays the faster one on the largest layers too (100B-shape layer: 81 against 85 us)
+        mult = 2;
+    } else if (mult == 0) {
         if (per_cu > 400) return false;
         if (per_cu < (fused ? 100 : 32)) {
             // small launches: worth it only where whole row blocks cannot even occupy every compute unit
@@ -283,6 +291,7 @@ hipError_t launch_decode_split(const DecodeBatch& b, int tiles_per_wave, bool fu
     if (lds > (size_t)kMaxDecodeLds) return hipErrorInvalidValue;
     const bool bf16 = b.p[0].x_flags & 1;
     const bool small = tiles_per_wave <= 4;
+    if (b.layout == 2) return small ? launch_sk<4, false, true, 2>(b, lds, s) : launch_sk<8, false, true, 2>(b, lds, s);
     if (!fused) return small ? launch_sk<4, false, true>(b, lds, s) : launch_sk<8, false, true>(b, lds, s);
     if (bf16) return small ? launch_sk<4, true, true>(b, lds, s) : launch_sk<8, true, true>(b, lds, s);
     return small ? launch_sk<4, true, false>(b, lds, s) : launch_sk<8, true, false>(b, lds, s);

@@ -25,9 +25,13 @@ namespace bl {
 
 namespace {
 
-template <int M, bool FUSED, bool XBF16>   // XBF16: dtype of the raw activations (fused form only)
+// XBF16: dtype of the raw activations (fused form only).  LAYOUT 2: tiles of the TL2-coded layout (one token, plain
+// form): same streaming structure, tl2_tile_mac instead of tile_mac, no sum(q) correction.
+template <int M, bool FUSED, bool XBF16, int LAYOUT = 1>
 __global__ __launch_bounds__(kThreads, 8) void decode_kernel(BL_FIRST_WG_PARAMS, const DecodeBatch b) {
+    static_assert(LAYOUT == 1 || (LAYOUT == 2 && M == 1 && !FUSED), "the TL2 layout has the one-token plain form only");
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    __shared__ int tl2_lut[LAYOUT == 2 ? 32 : 1];
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
@@ -102,6 +106,10 @@ __global__ __launch_bounds__(kThreads, 8) void decode_kernel(BL_FIRST_WG_PARAMS,
     Acc<M> a;
 #pragma unroll
     for (int m = 0; m < M; ++m) a.lo[m] = a.hi[m] = 0;
+    if constexpr (LAYOUT == 2) {
+        tl2_fill_table(tl2_lut, tid);
+        __syncthreads();
+    }
 
     if (active) {
         for (int kc0 = ks;;) {
@@ -109,10 +117,13 @@ __global__ __launch_bounds__(kThreads, 8) void decode_kernel(BL_FIRST_WG_PARAMS,
             for (int u = 0; u < kInFlight; ++u) {
                 const int k = kc0 + u * G;
                 if (k < KC) {
-                    if constexpr (FUSED) tile_mac<M>(w[u], reinterpret_cast<const int32_t*>(lds_q) + k * 16, Kp / 4, a);
+                    if constexpr (LAYOUT == 2) tl2_tile_mac(w[u], p.q + k * kTl2QWords, tl2_lut, a.lo[0]);
+                    else if constexpr (FUSED) tile_mac<M>(w[u], reinterpret_cast<const int32_t*>(lds_q) + k * 16, Kp / 4, a);
                     else tile_mac<M>(w[u], p.q + k * 16, Kp / 4, a);
                 }
-                __builtin_amdgcn_sched_barrier(0);   // keep the activation reads of later tiles from piling up in registers
+                // keep the activation reads of later tiles from piling up in registers (the TL2 form wants the
+                // opposite: the next tile's table lookups under this tile's dot products)
+                if constexpr (LAYOUT == 1) __builtin_amdgcn_sched_barrier(0);
             }
             kc0 += G * kInFlight;
             if (kc0 >= KC) break;
@@ -138,7 +149,7 @@ __global__ __launch_bounds__(kThreads, 8) void decode_kernel(BL_FIRST_WG_PARAMS,
                 if (p.q_sum_out) p.q_sum_out[m] = qsum;
             }
         } else {
-            qsum = p.q_sum[m];
+            qsum = LAYOUT == 2 ? 0 : p.q_sum[m];
             scale = p.a_scale[m];
         }
         int v = -qsum;
@@ -422,6 +433,14 @@ static void plan_decode(DecodeBatch& b, int tiles_per_wave) {
 
 hipError_t launch_decode(const DecodeBatch& batch, int M, bool fused, hipStream_t s) {
     DecodeBatch b = batch;
+    if (b.layout == 2) {   // TL2-coded tiles: one token, plain form, dot-product kernels only
+        if (M != 1 || fused) return hipErrorInvalidValue;
+        int tiles_per_wave = 0;
+        if (plan_decode_split(b, false, tiles_per_wave)) return launch_decode_split(b, tiles_per_wave, false, s);
+        plan_decode(b, kInFlight);
+        static LdsCeiling ceiling;
+        return launch_kernel(&decode_kernel<1, false, true, 2>, ceiling, b, lds_bytes_for(1, 0, false), s);
+    }
     int64_t max_Kp = 0;
     for (int i = 0; i < b.count; ++i) max_Kp = (int64_t)b.p[i].KC * kTileK > max_Kp ? (int64_t)b.p[i].KC * kTileK : max_Kp;
     const bool bf16 = b.p[0].x_flags & 1;   // the fused form requires one activation dtype per launch

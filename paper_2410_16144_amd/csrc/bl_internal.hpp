@@ -52,6 +52,7 @@ struct DecodeBatch {
     int32_t       count;
     int32_t       total_wgs;
     unsigned long long* ws;      // balanced form: the caller's workspace (zero between launches), or null
+    int32_t       layout;        // 1: 2-bit tiles of 64 k; 2: TL2 codes, tiles of 72 k (one token, plain form only)
 };
 
 // Which problem of the launch a workgroup belongs to.  The first workgroup of problems 1..7 (INT32_MAX beyond the
@@ -118,8 +119,6 @@ hipError_t launch_tl2_pack(const int8_t* w, int64_t N, int64_t K, int64_t Np, in
                            int32_t* bad_count, hipStream_t s);
 hipError_t launch_tl2_unpack(const uint32_t* packed, int64_t N, int64_t K, int64_t Np, int64_t Kp, int8_t* w,
                              hipStream_t s);
-hipError_t launch_tl2_gemv(const uint4* packed, const int32_t* q, const float* a_scale, float* out, int32_t* acc,
-                           int64_t N, int64_t Np, int64_t Kp, float w_scale, hipStream_t s);
 
 // Launch-shape overrides for experiments (0 = choose automatically).
 void set_gemv_waves(int waves);

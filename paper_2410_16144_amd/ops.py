@@ -207,6 +207,30 @@ class GemvGroup:
         return self.outs
 
 
+class Tl2GemvGroup:
+    """A prepared grouped one-token launch over 1.78-bit blobs (bl_tl2_gemv_batch).  acts[i]: from
+    quant_act(x, tl2_quant_buffer(K, dev))."""
+
+    def __init__(self, weights, acts, outs=None, want_acc=False, use_workspace=True):
+        assert 1 <= len(weights) <= B.BL_MAX_BATCH and len(weights) == len(acts)
+        dev = weights[0].blob.device
+        self.workspace_ptr = _workspace_ptr(use_workspace, dev)
+        for w, a in zip(weights, acts):
+            assert a.q.shape[0] == 1 and a.q.shape[1] >= B.bl_tl2_padded_k(w.K)
+        self.weights, self.acts = list(weights), list(acts)
+        self.outs = list(outs) if outs is not None else [
+            torch.empty((1, w.N), dtype=torch.float32, device=dev) for w in weights]
+        self.accs = [torch.empty((1, w.N), dtype=torch.int32, device=dev) for w in weights] if want_acc else None
+        self.items = B.make_gemv_items(
+            (w.blob.data_ptr(), w.desc, a.q.data_ptr(), a.a_scale.data_ptr(), 0, o.data_ptr(),
+             self.accs[i].data_ptr() if want_acc else 0)
+            for i, (w, a, o) in enumerate(zip(self.weights, self.acts, self.outs)))
+
+    def launch(self):
+        B.bl_tl2_gemv_batch(self.items, self.workspace_ptr, _stream())
+        return self.outs
+
+
 def _dtype_code(x: torch.Tensor) -> int:
     if x.dtype == torch.float32:
         return B.BL_F32

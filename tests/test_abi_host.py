@@ -169,6 +169,12 @@ def test_tl2_descriptor_and_validation():
     assert _st(B.bl_tl2_gemv, P + 8, v2, P, P, P) == B.BL_ERR_ALIGN
     assert _st(B.bl_tl2_gemv, P, v2, P + 4, P, P) == B.BL_ERR_ALIGN
     assert _st(B.bl_tl2_pack, P, v2, P + 4) == B.BL_ERR_ALIGN
+    items = B.make_gemv_items([(P, v2, P, P, 0, P, 0)])
+    assert B.lib().bl_tl2_gemv_batch(items, 0, None, None) == B.BL_ERR_COUNT
+    assert B.lib().bl_tl2_gemv_batch(items, 9, None, None) == B.BL_ERR_COUNT
+    assert B.lib().bl_tl2_gemv_batch(None, 1, None, None) == B.BL_ERR_NULL
+    assert B.lib().bl_tl2_gemv_batch(items, 1, P + 64, None) == B.BL_ERR_ALIGN
+    assert B.lib().bl_tl2_gemv_batch(B.make_gemv_items([(P, v1, P, P, 0, P, 0)]), 1, None, None) == B.BL_ERR_LAYOUT
     bad = B.bl_tl2_desc_init(128, 144, 0.5)
     bad.bytes += 16
     assert _st(B.bl_tl2_gemv, P, bad, P, P, P) == B.BL_ERR_BUF_SMALL

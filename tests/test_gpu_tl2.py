@@ -114,3 +114,61 @@ def test_tl2_gemv_closed_forms(dev, ops):
     _, acc = ops.tl2_gemv(pw, qa, want_acc=True)
     exp = np.array([(1 if n % 2 else -1) * q[(n * 3) % K] for n in range(N)])
     assert np.array_equal(acc.cpu().numpy()[0], exp)
+
+
+def _layer_problems(shapes, seed):
+    probs = []
+    for i, (N, K) in enumerate(shapes):
+        rng = synth.rng_for(seed + i)
+        w = synth.ternary_weights(rng, N, K, p_zero=0.4)
+        bits = synth.to_bf16_bits(synth.activations(rng, 1, K, outlier_frac=0.01))
+        probs.append((w, float(synth.draw_w_scale(rng)), bits))
+    return probs
+
+
+def _assert_tl2_batch(ops, dev, probs, use_workspace, expect_split):
+    from paper_2410_16144_amd import binding
+    weights, acts = [], []
+    for w, s, bits in probs:
+        weights.append(ops.tl2_pack(torch.from_numpy(w).to(dev), s))
+        acts.append(_quantized(ops, dev, bits, w.shape[1])[1])
+    before = binding.bl_get_stat("split_launches")
+    grp = ops.Tl2GemvGroup(weights, acts, want_acc=True, use_workspace=use_workspace)
+    grp.launch()
+    torch.cuda.synchronize()
+    assert binding.bl_get_stat("split_launches") - before == (1 if expect_split else 0)
+    if use_workspace:
+        assert not ops.workspace(dev).any()          # the balanced form leaves its workspace zero
+    for i, (w, s, bits) in enumerate(probs):
+        ref = oracle.bitlinear(bits, w, np.float32(s))
+        assert np.array_equal(grp.accs[i].cpu().numpy(), ref["acc"]), i
+        got = grp.outs[i].cpu().numpy()
+        assert np.all(np.abs(got - ref["out"]) <= REL_TOL * np.abs(ref["out"])), i
+    first = [o.clone() for o in grp.outs]
+    grp.launch()
+    torch.cuda.synchronize()
+    assert all(torch.equal(a, b) for a, b in zip(first, grp.outs))
+
+
+def test_tl2_batch_of_seven_row_block_form(dev, ops):
+    shapes = [(320, 640), (320, 640), (128, 640), (640, 320), (64, 72), (200, 1000), (1000, 200)]
+    _assert_tl2_batch(ops, dev, _layer_problems(shapes, 7300), use_workspace=False, expect_split=False)
+
+
+@pytest.mark.parametrize("n", [1, 2])
+def test_tl2_batch_balanced_form(dev, ops, n):
+    from paper_2410_16144_amd import binding
+    binding.bl_set_tuning("decode_split", n)
+    try:
+        shapes = [(2000 * n, 4000), (1000 * n, 9000), (5000 * n, 3000), (700 * n, 6000), (64, 72), (2000 * n, 4000), (130, 12000)]
+        _assert_tl2_batch(ops, dev, _layer_problems(shapes, 7400 + n), use_workspace=True, expect_split=True)
+        # one matrix whose every row block is shared by several workgroups
+        _assert_tl2_batch(ops, dev, _layer_problems([(4100, 8200)], 7450 + n), use_workspace=True, expect_split=True)
+    finally:
+        binding.bl_set_tuning("decode_split", 0)
+
+
+def test_tl2_layer_shape_automatic_choice(dev, ops):
+    projs = synth.layer_projections(3200, 8640)
+    _assert_tl2_batch(ops, dev, _layer_problems([(p.N, p.K) for p in projs], 7500), use_workspace=True, expect_split=True)
+
