@@ -185,8 +185,9 @@ __global__ __launch_bounds__(kThreads, 8) void decode_mfma_kernel(BL_FIRST_WG_PA
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     constexpr bool kLdsQ = QMODE != 0;
     constexpr int U = kLdsQ ? kMfmaInFlightLds : kMfmaInFlightDirect;   // weight tiles in flight per wave
-    // fused form with many tokens: the quantizer's own registers leave no room for tiles in flight beside it
-    constexpr bool kTilesAfterQuant = QMODE == 2 && M > 4;
+    // fused form: the quantizer's own registers leave no room for tiles in flight beside it (with two to four
+    // tokens they would fit, at the price of a spill or of a longer wait in the quantizer: measured slower)
+    constexpr bool kTilesAfterQuant = QMODE == 2 && M > 1;
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
