@@ -302,7 +302,7 @@ bl_status bl_tl2_gemv(const void *packed_dev, const bl_packed_desc *d, const int
  * seven projections of a decoder layer.  Items are bl_gemv_item with version-2
  * descriptors; q_sum_dev is not used and may be NULL (the table yields signed
  * weights).  `workspace_dev`: as for bl_gemv_batch (may be NULL): with it,
- * launches of medium size are work-balanced across workgroups.  Each item is
+ * launches are work-balanced across workgroups.  Each item is
  * validated like a bl_tl2_gemv call; results are identical.
  * Errors: BL_ERR_NULL, BL_ERR_COUNT, BL_ERR_LAYOUT, BL_ERR_SHAPE,
  *         BL_ERR_BUF_SMALL, BL_ERR_ALIGN, BL_ERR_HIP.

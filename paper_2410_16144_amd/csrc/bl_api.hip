@@ -381,6 +381,6 @@ int64_t bl_get_stat(const char* key) {
 
 const char* bl_last_hip_error(void) { return hipGetErrorString(t_last_hip_error); }
 
-const char* bl_version(void) { return "bitlinear-gfx950 0.1 (layout 1)"; }
+const char* bl_version(void) { return "bitlinear-gfx950 0.2 (layouts 1, 2)"; }
 
 }  // extern "C"
