@@ -1,0 +1,136 @@
+/*
+ * bitlinear_decoder.h -- the decoder block around the BitLinear products, one token at a time.
+ *
+ * arXiv 2410.16144 reports its speed in tokens per second of WHOLE models (Section 3, the
+ * inference-speed tables) on dummy models of which Appendix A gives the shapes: hidden size,
+ * intermediate size, layers and attention heads.  The seven ternary projections of a layer are
+ * bitlinear.h's products; this header declares what stands between them so that a token can pass
+ * through a layer without leaving the GPU.  The paper does not describe these operations; they are
+ * the LLaMA-like block of BitNet b1.58 (RMSNorm, rotary position embedding, multi-head attention
+ * over a key/value cache, SiLU-gated feed-forward, residuals, no biases), with one RMSNorm in front
+ * of every activation quantizer:
+ *
+ *   y  = rmsnorm(h, g_in)           -> q, k, v = BitLinear(y)
+ *   a  = attention(rope(q), cache + {rope(k), v})
+ *   h += BitLinear_o(rmsnorm(a, g_attn))
+ *   y  = rmsnorm(h, g_post)         -> gate, up = BitLinear(y)
+ *   h += BitLinear_down(rmsnorm(silu(gate) * up, g_ffn))
+ *
+ * Conventions as in bitlinear.h: device pointers end in _dev, no entry point allocates, frees or
+ * synchronizes, `stream` is a hipStream_t (NULL = default stream), errors are bl_status codes and
+ * nothing is launched when one is returned.  All floating-point data here is fp32 except the
+ * key/value cache (bf16 bit patterns).
+ */
+#ifndef BITLINEAR_DECODER_H
+#define BITLINEAR_DECODER_H
+
+#include "bitlinear.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define BL_NORM_MAX_K 49152     /* longest row bl_norm_quant takes (the paper's largest
+                                   intermediate size, Appendix A "100B", is 45568)        */
+#define BL_ATTN_MAX_HEAD_DIM 256
+#define BL_ATTN_CHUNK 256       /* cache positions per workgroup of the attention kernel  */
+
+typedef enum bl_norm_mode {
+    BL_NORM_PLAIN = 0,      /* x = a                                                  */
+    BL_NORM_RESIDUAL = 1,   /* x = h + a (a may be NULL: x = h); h is overwritten by x */
+    BL_NORM_GATED = 2       /* x = silu(a) * b, silu(t) = t / (1 + exp(-t))            */
+} bl_norm_mode;
+
+/*
+ * One launch: for each of M token rows, form x (see bl_norm_mode), normalise
+ *   y[k] = x[k] * (1 / sqrt(mean_k(x^2) + eps)) * gamma[k]
+ * and quantize y exactly as bl_quant_act does (per-token absmax int8):
+ *   q [M, Kp] int8, a_scale [M], q_sum [M] -- ready for bl_gemv / bl_gemv_batch / bl_gemm.
+ * Fusing the three keeps the row in registers: x is read once and only q leaves the chip.
+ *   a_dev, b_dev, h_dev  [M, K] fp32, rows contiguous (stride K)
+ *   gamma_dev            [K] fp32
+ *   q_dev                [M, Kp] int8, Kp >= K a multiple of 4 (normally bl_padded_k(K) or
+ *                        bl_tl2_padded_k(K)); bytes K..Kp-1 of each row are written as zero.
+ *                        q_dev, a_scale_dev and q_sum_dev may ALL be NULL: then nothing is
+ *                        quantized (the final norm of a model).
+ *   q_sum_dev            optional
+ *   y_dev                optional [M, K] fp32: the normalised values before quantization
+ * K <= BL_NORM_MAX_K.  The sum of squares is an fp32 tree sum; y and the quantizer's decisions are
+ * single IEEE operations on it, so q equals bl_quant_act of y_dev bit for bit.
+ * Errors: BL_ERR_NULL, BL_ERR_SHAPE (M < 1, K outside 1..BL_NORM_MAX_K, Kp < K or not a multiple
+ *         of 4, unknown mode), BL_ERR_ALIGN (fp32 pointers 4 bytes, q_dev 4 bytes), BL_ERR_HIP.
+ */
+typedef struct bl_norm_quant_args {
+    int32_t      mode;          /* bl_norm_mode */
+    int32_t      M;
+    int64_t      K;
+    int64_t      Kp;
+    const float *a_dev;
+    const float *b_dev;         /* BL_NORM_GATED only */
+    float       *h_dev;         /* BL_NORM_RESIDUAL only */
+    const float *gamma_dev;
+    float        eps;
+    int8_t      *q_dev;
+    float       *a_scale_dev;
+    int32_t     *q_sum_dev;
+    float       *y_dev;
+} bl_norm_quant_args;
+
+bl_status bl_norm_quant(const bl_norm_quant_args *args, void *stream);
+
+/*
+ * Rotary table for bl_attn_decode, computed on the GPU in fp64 and rounded to fp32:
+ *   table[(p * head_dim/2 + i) * 2 + {0, 1}] = {cos, sin}(p * theta^(-2 i / head_dim)),
+ *   p = 0 .. max_pos-1, i = 0 .. head_dim/2 - 1.   table_dev: max_pos * head_dim floats.
+ * Errors: BL_ERR_NULL, BL_ERR_SHAPE (head_dim odd or outside 2..BL_ATTN_MAX_HEAD_DIM, max_pos < 1,
+ *         theta <= 0), BL_ERR_ALIGN (8 bytes), BL_ERR_HIP.
+ */
+bl_status bl_rope_table(float *table_dev, int32_t head_dim, int32_t max_pos, double theta, void *stream);
+
+/*
+ * Attention for the ONE token at position p = *pos_dev (read on the device, so a captured graph can
+ * be replayed as the position advances; 0 <= p < max_pos is the caller's responsibility -- a value
+ * outside that range makes the launch do nothing).
+ *   1. rotate the token's query and key (pairs (i, i + head_dim/2) within a head, angle from the
+ *      table's row p), round key and value to bf16 and store them as row p of the caches;
+ *   2. per head: weights softmax_j(q . k_j / sqrt(head_dim)) over cache rows j = 0 .. p, output
+ *      sum_j weight_j * v_j.
+ *   q_lin_dev, k_lin_dev, v_lin_dev   [n_heads * head_dim] fp32: the token's Q, K, V projections
+ *   k_cache_dev, v_cache_dev          [max_pos, n_heads * head_dim] bf16 bit patterns, 16-byte aligned
+ *   out_dev                           [n_heads * head_dim] fp32
+ *   scratch_dev                       bl_attn_scratch_bytes(...) bytes, 16-byte aligned; partial
+ *                                     results of the workgroups that share a head; contents need
+ *                                     not be preserved or cleared between calls
+ * Two launches: (n_heads x ceil(max_pos / BL_ATTN_CHUNK)) workgroups, each over at most
+ * BL_ATTN_CHUNK cache rows (those beyond p exit at once), then one workgroup per head that merges
+ * them.  head_dim must be a multiple of 4 (4 .. BL_ATTN_MAX_HEAD_DIM).
+ * Errors: BL_ERR_NULL, BL_ERR_SHAPE, BL_ERR_ALIGN, BL_ERR_HIP.
+ */
+typedef struct bl_attn_args {
+    const float   *q_lin_dev;
+    const float   *k_lin_dev;
+    const float   *v_lin_dev;
+    const int32_t *pos_dev;
+    const float   *rope_table_dev;
+    uint16_t      *k_cache_dev;
+    uint16_t      *v_cache_dev;
+    float         *out_dev;
+    void          *scratch_dev;
+    int32_t        n_heads;
+    int32_t        head_dim;
+    int32_t        max_pos;
+} bl_attn_args;
+
+/* Bytes of bl_attn_args.scratch_dev; 0 if a shape is out of range. */
+uint64_t bl_attn_scratch_bytes(int32_t n_heads, int32_t head_dim, int32_t max_pos);
+
+bl_status bl_attn_decode(const bl_attn_args *args, void *stream);
+
+/* *pos_dev += 1 on the device (one thread), so that the token loop's position lives in the
+ * graph's own memory.  Errors: BL_ERR_NULL, BL_ERR_ALIGN, BL_ERR_HIP. */
+bl_status bl_pos_advance(int32_t *pos_dev, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BITLINEAR_DECODER_H */

@@ -27,12 +27,18 @@ BL_MAX_GEMM_M = 4194304
 BL_TL2_TILE_K = 72
 BL_TL2_LAYOUT_VERSION = 2
 
-# every symbol include/bitlinear.h declares
+# every symbol include/bitlinear.h and include/bitlinear_decoder.h declare
 DECLARED_SYMBOLS = (
     "bl_padded_k", "bl_padded_n", "bl_packed_desc_init", "bl_pack_ternary", "bl_unpack_ternary",
     "bl_quant_act", "bl_quant_act_batch", "bl_gemv", "bl_gemv_batch", "bl_decode_batch", "bl_gemm", "bl_set_tuning", "bl_get_stat", "bl_status_str", "bl_last_hip_error", "bl_version",
     "bl_tl2_padded_k", "bl_tl2_desc_init", "bl_tl2_pack", "bl_tl2_unpack", "bl_tl2_gemv", "bl_tl2_gemv_batch",
+    "bl_norm_quant", "bl_rope_table", "bl_attn_scratch_bytes", "bl_attn_decode", "bl_pos_advance",
 )
+
+BL_NORM_MAX_K = 49152
+BL_ATTN_MAX_HEAD_DIM = 256
+BL_ATTN_CHUNK = 256
+BL_NORM_PLAIN, BL_NORM_RESIDUAL, BL_NORM_GATED = 0, 1, 2
 
 
 class BitLinearError(RuntimeError):
@@ -73,6 +79,22 @@ class DecodeItem(ctypes.Structure):
                 ("a_scale_dev", ctypes.c_void_p), ("q_sum_dev", ctypes.c_void_p)]
 
 
+class NormQuantArgs(ctypes.Structure):
+    """Mirror of bl_norm_quant_args."""
+    _fields_ = [("mode", ctypes.c_int32), ("M", ctypes.c_int32), ("K", ctypes.c_int64), ("Kp", ctypes.c_int64),
+                ("a_dev", ctypes.c_void_p), ("b_dev", ctypes.c_void_p), ("h_dev", ctypes.c_void_p),
+                ("gamma_dev", ctypes.c_void_p), ("eps", ctypes.c_float), ("q_dev", ctypes.c_void_p),
+                ("a_scale_dev", ctypes.c_void_p), ("q_sum_dev", ctypes.c_void_p), ("y_dev", ctypes.c_void_p)]
+
+
+class AttnArgs(ctypes.Structure):
+    """Mirror of bl_attn_args."""
+    _fields_ = [("q_lin_dev", ctypes.c_void_p), ("k_lin_dev", ctypes.c_void_p), ("v_lin_dev", ctypes.c_void_p),
+                ("pos_dev", ctypes.c_void_p), ("rope_table_dev", ctypes.c_void_p), ("k_cache_dev", ctypes.c_void_p),
+                ("v_cache_dev", ctypes.c_void_p), ("out_dev", ctypes.c_void_p), ("scratch_dev", ctypes.c_void_p),
+                ("n_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32), ("max_pos", ctypes.c_int32)]
+
+
 _lib = None
 
 
@@ -111,6 +133,12 @@ def lib():
     l.bl_tl2_unpack.argtypes = [vp, dp, vp, vp]
     l.bl_tl2_gemv.argtypes = [vp, dp, vp, vp, vp, vp, vp]
     l.bl_tl2_gemv_batch.argtypes = [ctypes.POINTER(GemvItem), i32, vp, vp]
+    l.bl_norm_quant.argtypes = [ctypes.POINTER(NormQuantArgs), vp]
+    l.bl_rope_table.argtypes = [vp, i32, i32, ctypes.c_double, vp]
+    l.bl_attn_scratch_bytes.argtypes = [i32, i32, i32]
+    l.bl_attn_scratch_bytes.restype = ctypes.c_uint64
+    l.bl_attn_decode.argtypes = [ctypes.POINTER(AttnArgs), vp]
+    l.bl_pos_advance.argtypes = [vp, vp]
     l.bl_set_tuning.argtypes = [ctypes.c_char_p, i32]
     l.bl_get_stat.argtypes = [ctypes.c_char_p]
     l.bl_get_stat.restype = i64
@@ -120,7 +148,8 @@ def lib():
     l.bl_last_hip_error.restype = ctypes.c_char_p
     for name in ("bl_packed_desc_init", "bl_pack_ternary", "bl_unpack_ternary", "bl_quant_act", "bl_quant_act_batch", "bl_gemv",
                  "bl_gemv_batch", "bl_decode_batch", "bl_gemm", "bl_set_tuning", "bl_tl2_desc_init", "bl_tl2_pack",
-                 "bl_tl2_unpack", "bl_tl2_gemv", "bl_tl2_gemv_batch"):
+                 "bl_tl2_unpack", "bl_tl2_gemv", "bl_tl2_gemv_batch", "bl_norm_quant", "bl_rope_table", "bl_attn_decode",
+                 "bl_pos_advance"):
         getattr(l, name).restype = ctypes.c_int
     _lib = l
     return l
@@ -261,6 +290,40 @@ def bl_tl2_gemv_batch(items, workspace_dev: int = 0, stream: int = 0):
     if not isinstance(items, ctypes.Array):
         items = make_gemv_items(items)
     _check(lib().bl_tl2_gemv_batch(items, len(items), workspace_dev or None, stream or None), "bl_tl2_gemv_batch")
+
+
+def make_norm_quant_args(mode: int, M: int, K: int, gamma_dev: int, eps: float, a_dev: int = 0, b_dev: int = 0,
+                         h_dev: int = 0, q_dev: int = 0, a_scale_dev: int = 0, q_sum_dev: int = 0, Kp: int = 0,
+                         y_dev: int = 0) -> NormQuantArgs:
+    return NormQuantArgs(mode, M, K, Kp, a_dev or None, b_dev or None, h_dev or None, gamma_dev or None, eps,
+                         q_dev or None, a_scale_dev or None, q_sum_dev or None, y_dev or None)
+
+
+def bl_norm_quant(args: NormQuantArgs, stream: int = 0):
+    _check(lib().bl_norm_quant(ctypes.byref(args), stream), "bl_norm_quant")
+
+
+def bl_rope_table(table_dev: int, head_dim: int, max_pos: int, theta: float, stream: int = 0):
+    _check(lib().bl_rope_table(table_dev, head_dim, max_pos, theta, stream), "bl_rope_table")
+
+
+def bl_attn_scratch_bytes(n_heads: int, head_dim: int, max_pos: int) -> int:
+    return int(lib().bl_attn_scratch_bytes(n_heads, head_dim, max_pos))
+
+
+def make_attn_args(q_lin_dev: int, k_lin_dev: int, v_lin_dev: int, pos_dev: int, rope_table_dev: int, k_cache_dev: int,
+                   v_cache_dev: int, out_dev: int, scratch_dev: int, n_heads: int, head_dim: int, max_pos: int) -> AttnArgs:
+    return AttnArgs(q_lin_dev or None, k_lin_dev or None, v_lin_dev or None, pos_dev or None, rope_table_dev or None,
+                    k_cache_dev or None, v_cache_dev or None, out_dev or None, scratch_dev or None, n_heads, head_dim,
+                    max_pos)
+
+
+def bl_attn_decode(args: AttnArgs, stream: int = 0):
+    _check(lib().bl_attn_decode(ctypes.byref(args), stream), "bl_attn_decode")
+
+
+def bl_pos_advance(pos_dev: int, stream: int = 0):
+    _check(lib().bl_pos_advance(pos_dev, stream), "bl_pos_advance")
 
 
 def bl_set_tuning(key: str, value: int):

@@ -327,6 +327,64 @@ bl_status bl_gemm(const void* packed_dev, const bl_packed_desc* d, const int8_t*
     return hip_status(bl::launch_gemm(p, M, static_cast<hipStream_t>(stream)));
 }
 
+bl_status bl_norm_quant(const bl_norm_quant_args* a, void* stream) {
+    if (!a || !a->gamma_dev) return BL_ERR_NULL;
+    const bool quantize = a->q_dev != nullptr;
+    if (quantize != (a->a_scale_dev != nullptr) || (!quantize && a->q_sum_dev)) return BL_ERR_NULL;
+    switch (a->mode) {
+        case BL_NORM_PLAIN: if (!a->a_dev) return BL_ERR_NULL; break;
+        case BL_NORM_RESIDUAL: if (!a->h_dev) return BL_ERR_NULL; break;
+        case BL_NORM_GATED: if (!a->a_dev || !a->b_dev) return BL_ERR_NULL; break;
+        default: return BL_ERR_SHAPE;
+    }
+    if (a->M < 1 || a->K < 1 || a->K > BL_NORM_MAX_K) return BL_ERR_SHAPE;
+    if (quantize && (a->Kp < a->K || a->Kp % 4 != 0 || a->Kp > BL_MAX_K)) return BL_ERR_SHAPE;
+    if (!aligned(a->a_dev, 4) || !aligned(a->b_dev, 4) || !aligned(a->h_dev, 4) || !aligned(a->gamma_dev, 4) ||
+        !aligned(a->q_dev, 4) || !aligned(a->a_scale_dev, 4) || !aligned(a->q_sum_dev, 4) || !aligned(a->y_dev, 4))
+        return BL_ERR_ALIGN;
+    drop_stale_hip_error();
+    return hip_status(bl::launch_norm_quant(*a, static_cast<hipStream_t>(stream)));
+}
+
+bl_status bl_rope_table(float* table_dev, int32_t head_dim, int32_t max_pos, double theta, void* stream) {
+    if (!table_dev) return BL_ERR_NULL;
+    if (head_dim < 2 || head_dim > BL_ATTN_MAX_HEAD_DIM || head_dim % 2 != 0 || max_pos < 1 || !(theta > 0.0))
+        return BL_ERR_SHAPE;
+    if (!aligned(table_dev, 8)) return BL_ERR_ALIGN;
+    drop_stale_hip_error();
+    return hip_status(bl::launch_rope_table(table_dev, head_dim, max_pos, theta, static_cast<hipStream_t>(stream)));
+}
+
+static bool attn_shape_ok(int32_t n_heads, int32_t head_dim, int32_t max_pos) {
+    return n_heads >= 1 && n_heads <= 65535 && head_dim >= 4 && head_dim <= BL_ATTN_MAX_HEAD_DIM && head_dim % 4 == 0 &&
+           max_pos >= 1 && bl::attn_chunks(max_pos) <= 65535;
+}
+
+uint64_t bl_attn_scratch_bytes(int32_t n_heads, int32_t head_dim, int32_t max_pos) {
+    if (!attn_shape_ok(n_heads, head_dim, max_pos)) return 0;
+    return (uint64_t)n_heads * (uint64_t)bl::attn_chunks(max_pos) * (uint64_t)(head_dim + 2) * sizeof(float);
+}
+
+bl_status bl_attn_decode(const bl_attn_args* a, void* stream) {
+    if (!a || !a->q_lin_dev || !a->k_lin_dev || !a->v_lin_dev || !a->pos_dev || !a->rope_table_dev || !a->k_cache_dev ||
+        !a->v_cache_dev || !a->out_dev || !a->scratch_dev)
+        return BL_ERR_NULL;
+    if (!attn_shape_ok(a->n_heads, a->head_dim, a->max_pos)) return BL_ERR_SHAPE;
+    if (!aligned(a->q_lin_dev, 4) || !aligned(a->k_lin_dev, 4) || !aligned(a->v_lin_dev, 4) || !aligned(a->pos_dev, 4) ||
+        !aligned(a->rope_table_dev, 8) || !aligned(a->k_cache_dev, 16) || !aligned(a->v_cache_dev, 16) ||
+        !aligned(a->out_dev, 4) || !aligned(a->scratch_dev, 16))
+        return BL_ERR_ALIGN;
+    drop_stale_hip_error();
+    return hip_status(bl::launch_attn_decode(*a, static_cast<hipStream_t>(stream)));
+}
+
+bl_status bl_pos_advance(int32_t* pos_dev, void* stream) {
+    if (!pos_dev) return BL_ERR_NULL;
+    if (!aligned(pos_dev, 4)) return BL_ERR_ALIGN;
+    drop_stale_hip_error();
+    return hip_status(bl::launch_pos_advance(pos_dev, static_cast<hipStream_t>(stream)));
+}
+
 const char* bl_status_str(bl_status s) {
     switch (s) {
         case BL_OK: return "ok";

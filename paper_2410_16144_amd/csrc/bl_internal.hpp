@@ -4,6 +4,7 @@
 #include <stdint.h>
 
 #include "bitlinear.h"
+#include "bitlinear_decoder.h"
 
 namespace bl {
 
@@ -119,6 +120,14 @@ hipError_t launch_tl2_pack(const int8_t* w, int64_t N, int64_t K, int64_t Np, in
                            int32_t* bad_count, hipStream_t s);
 hipError_t launch_tl2_unpack(const uint32_t* packed, int64_t N, int64_t K, int64_t Np, int64_t Kp, int8_t* w,
                              hipStream_t s);
+
+
+// The decoder block around the products (bl_decoder.hip); arguments already validated.
+hipError_t launch_norm_quant(const ::bl_norm_quant_args& a, hipStream_t s);
+hipError_t launch_rope_table(float* table, int head_dim, int max_pos, double theta, hipStream_t s);
+int attn_chunks(int max_pos);
+hipError_t launch_attn_decode(const ::bl_attn_args& a, hipStream_t s);
+hipError_t launch_pos_advance(int32_t* pos, hipStream_t s);
 
 // Launch-shape overrides for experiments (0 = choose automatically).
 void set_gemv_waves(int waves);

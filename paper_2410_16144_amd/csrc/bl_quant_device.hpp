@@ -30,6 +30,18 @@ __device__ __forceinline__ int wave_sum(int x) {
     return __builtin_amdgcn_readlane(x, 0) + __builtin_amdgcn_readlane(x, 16) + __builtin_amdgcn_readlane(x, 32) +
            __builtin_amdgcn_readlane(x, 48);
 }
+
+__device__ __forceinline__ float wave_sum_f(float v) {   // a fixed tree: the same bits on every run
+#define BL_DPP_F(x, ctrl) __int_as_float(BL_DPP(__float_as_int(x), (ctrl)))
+    v += BL_DPP_F(v, 0xB1);
+    v += BL_DPP_F(v, 0x4E);
+    v += BL_DPP_F(v, 0x141);
+    v += BL_DPP_F(v, 0x140);
+#undef BL_DPP_F
+    const int x = __float_as_int(v);
+    return (__int_as_float(__builtin_amdgcn_readlane(x, 0)) + __int_as_float(__builtin_amdgcn_readlane(x, 16))) +
+           (__int_as_float(__builtin_amdgcn_readlane(x, 32)) + __int_as_float(__builtin_amdgcn_readlane(x, 48)));
+}
 #undef BL_DPP
 
 // q = clip(round_half_even(v * inv), -128, 127)

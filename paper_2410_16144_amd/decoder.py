@@ -1,0 +1,185 @@
+"""One token through decoder layers without leaving the GPU: argument marshalling for
+include/bitlinear_decoder.h plus the launch sequence of a layer.
+
+Every arithmetic step runs in the library's kernels; this module owns buffers (torch tensors) and
+the order of the launches:
+
+    norm_quant(RESIDUAL, g_in)   h += delta of the previous layer; q1 = quantize(rmsnorm(h))
+    gemv_batch(q, k, v)          three products that share q1
+    attn_decode                  rotary embedding, cache append, attention (two launches)
+    norm_quant(PLAIN, g_attn)    q2 = quantize(rmsnorm(attention output))
+    gemv_batch(o)
+    norm_quant(RESIDUAL, g_post) h += o; q3 = quantize(rmsnorm(h))
+    gemv_batch(gate, up)         two products that share q3
+    norm_quant(GATED, g_ffn)     q4 = quantize(rmsnorm(silu(gate) * up))
+    gemv_batch(down)             -> delta for the next layer
+
+Shapes follow Appendix A of arXiv 2410.16144 (hidden size, intermediate size, layers, heads); the block
+itself is the LLaMA-like one of BitNet b1.58, which the paper does not spell out.
+"""
+from dataclasses import dataclass
+from typing import Dict, List, Optional
+
+import torch
+
+from . import binding as B
+from . import ops
+
+EPS = 1e-5
+ROPE_THETA = 10000.0
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def norm_quant(mode: int, gamma: torch.Tensor, eps: float = EPS, a: Optional[torch.Tensor] = None,
+               b: Optional[torch.Tensor] = None, h: Optional[torch.Tensor] = None, out: Optional[ops.QuantAct] = None,
+               y: Optional[torch.Tensor] = None, quantize: bool = True):
+    """bl_norm_quant on [M,K] fp32 tensors.  Returns the QuantAct (None if quantize is False)."""
+    ref = h if mode == B.BL_NORM_RESIDUAL else a
+    M, K = ref.shape
+    for t in (a, b, h, y):
+        assert t is None or (t.is_cuda and t.dtype == torch.float32 and t.shape == (M, K) and t.is_contiguous())
+    assert gamma.dtype == torch.float32 and gamma.shape == (K,) and gamma.is_contiguous()
+    if quantize and out is None:
+        out = ops.alloc_quant(M, K, ref.device)
+    ptr = lambda t: t.data_ptr() if t is not None else 0
+    args = B.make_norm_quant_args(
+        mode, M, K, gamma.data_ptr(), eps, a_dev=ptr(a), b_dev=ptr(b), h_dev=ptr(h),
+        q_dev=out.q.data_ptr() if quantize else 0, a_scale_dev=out.a_scale.data_ptr() if quantize else 0,
+        q_sum_dev=out.q_sum.data_ptr() if quantize else 0, Kp=int(out.q.shape[1]) if quantize else 0, y_dev=ptr(y))
+    B.bl_norm_quant(args, _stream())
+    return out if quantize else None
+
+
+def rope_table(head_dim: int, max_pos: int, device, theta: float = ROPE_THETA) -> torch.Tensor:
+    """[max_pos, head_dim/2, 2] fp32 (cos, sin) table (bl_rope_table)."""
+    t = torch.empty((max_pos, head_dim // 2, 2), dtype=torch.float32, device=device)
+    B.bl_rope_table(t.data_ptr(), head_dim, max_pos, theta, _stream())
+    return t
+
+
+class Attention:
+    """Key/value cache of one layer plus a prepared bl_attn_decode call."""
+
+    def __init__(self, n_heads: int, head_dim: int, max_pos: int, q_lin, k_lin, v_lin, pos: torch.Tensor,
+                 table: torch.Tensor, out: Optional[torch.Tensor] = None):
+        dev = q_lin.device
+        hidden = n_heads * head_dim
+        self.n_heads, self.head_dim, self.max_pos = n_heads, head_dim, max_pos
+        self.k_cache = torch.zeros((max_pos, hidden), dtype=torch.bfloat16, device=dev)
+        self.v_cache = torch.zeros((max_pos, hidden), dtype=torch.bfloat16, device=dev)
+        self.scratch = torch.empty(B.bl_attn_scratch_bytes(n_heads, head_dim, max_pos), dtype=torch.uint8, device=dev)
+        self.out = out if out is not None else torch.empty((1, hidden), dtype=torch.float32, device=dev)
+        for t in (q_lin, k_lin, v_lin, self.out):
+            assert t.dtype == torch.float32 and t.numel() == hidden and t.is_contiguous()
+        assert pos.dtype == torch.int32 and pos.numel() == 1 and table.shape == (max_pos, head_dim // 2, 2)
+        self._keep = (q_lin, k_lin, v_lin, pos, table)
+        self.args = B.make_attn_args(q_lin.data_ptr(), k_lin.data_ptr(), v_lin.data_ptr(), pos.data_ptr(), table.data_ptr(),
+                                     self.k_cache.data_ptr(), self.v_cache.data_ptr(), self.out.data_ptr(),
+                                     self.scratch.data_ptr(), n_heads, head_dim, max_pos)
+
+    def launch(self):
+        B.bl_attn_decode(self.args, _stream())
+        return self.out
+
+
+@dataclass
+class LayerWeights:
+    proj: Dict[str, ops.PackedWeight]     # 'q','k','v','o','gate','up','down'
+    g_in: torch.Tensor
+    g_attn: torch.Tensor
+    g_post: torch.Tensor
+    g_ffn: torch.Tensor
+
+
+class DecoderLayer:
+    """Buffers and prepared launches of one layer for one token (M = 1)."""
+
+    def __init__(self, w: LayerWeights, n_heads: int, max_pos: int, h: torch.Tensor, delta_in: Optional[torch.Tensor],
+                 pos: torch.Tensor, table: torch.Tensor, eps: float = EPS, use_workspace=True):
+        dev = h.device
+        hidden = int(h.shape[1])
+        ffn = w.proj["gate"].N
+        assert h.shape == (1, hidden) and hidden % n_heads == 0
+        self.w, self.h, self.delta_in, self.eps = w, h, delta_in, eps
+        self.q1, self.q2, self.q3 = (ops.alloc_quant(1, hidden, dev) for _ in range(3))
+        self.q4 = ops.alloc_quant(1, ffn, dev)
+        self.qkv = ops.GemvGroup([w.proj["q"], w.proj["k"], w.proj["v"]], [self.q1] * 3, use_workspace=use_workspace)
+        self.attn = Attention(n_heads, hidden // n_heads, max_pos, *self.qkv.outs, pos, table)
+        self.o = ops.GemvGroup([w.proj["o"]], [self.q2], use_workspace=use_workspace)
+        self.gate_up = ops.GemvGroup([w.proj["gate"], w.proj["up"]], [self.q3] * 2, use_workspace=use_workspace)
+        self.down = ops.GemvGroup([w.proj["down"]], [self.q4], use_workspace=use_workspace)
+        self.delta_out = self.down.outs[0]
+
+    def launch(self):
+        w = self.w
+        norm_quant(B.BL_NORM_RESIDUAL, w.g_in, self.eps, a=self.delta_in, h=self.h, out=self.q1)
+        self.qkv.launch()
+        self.attn.launch()
+        norm_quant(B.BL_NORM_PLAIN, w.g_attn, self.eps, a=self.attn.out, out=self.q2)
+        self.o.launch()
+        norm_quant(B.BL_NORM_RESIDUAL, w.g_post, self.eps, a=self.o.outs[0], h=self.h, out=self.q3)
+        self.gate_up.launch()
+        norm_quant(B.BL_NORM_GATED, w.g_ffn, self.eps, a=self.gate_up.outs[0], b=self.gate_up.outs[1], out=self.q4)
+        self.down.launch()
+        return self.delta_out
+
+
+class DecoderStack:
+    """n layers, one token per step: h (the residual stream, [1, hidden] fp32) goes in, the final-normalised
+    hidden state comes out; the position lives on the device and advances by one per step."""
+
+    def __init__(self, layers: List[LayerWeights], g_final: torch.Tensor, n_heads: int, max_pos: int, device,
+                 eps: float = EPS, theta: float = ROPE_THETA, use_workspace=True):
+        hidden = layers[0].proj["q"].K
+        self.hidden, self.n_heads, self.max_pos, self.eps = hidden, n_heads, max_pos, eps
+        self.h = torch.zeros((1, hidden), dtype=torch.float32, device=device)
+        self.y = torch.empty((1, hidden), dtype=torch.float32, device=device)
+        self.pos = torch.zeros((1,), dtype=torch.int32, device=device)
+        self.table = rope_table(hidden // n_heads, max_pos, device, theta)
+        self.g_final = g_final
+        self.layers: List[DecoderLayer] = []
+        delta = None
+        for w in layers:
+            layer = DecoderLayer(w, n_heads, max_pos, self.h, delta, self.pos, self.table, eps, use_workspace)
+            self.layers.append(layer)
+            delta = layer.delta_out
+        self.graph = None
+
+    def launch(self):
+        """All launches of one token on the current stream: the layers, the last residual add with the final
+        norm (-> self.y), the position's increment."""
+        for layer in self.layers:
+            layer.launch()
+        norm_quant(B.BL_NORM_RESIDUAL, self.g_final, self.eps, a=self.layers[-1].delta_out, h=self.h, y=self.y,
+                   quantize=False)
+        B.bl_pos_advance(self.pos.data_ptr(), _stream())
+        return self.y
+
+    def capture(self):
+        """Capture launch() into a HIP graph (no memset nodes: every launch here is a kernel).  One token is run
+        eagerly first -- kernels set their launch attributes on first use, which a capture does not allow -- and
+        the residual stream and the position are put back afterwards (the cache row it wrote is rewritten by the
+        first real token at that position)."""
+        h0, pos0 = self.h.clone(), self.pos.clone()
+        self.launch()
+        torch.cuda.synchronize()
+        self.h.copy_(h0)
+        self.pos.copy_(pos0)
+        s = torch.cuda.Stream()
+        s.wait_stream(torch.cuda.current_stream())
+        self.graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(s):
+            with torch.cuda.graph(self.graph, stream=s):
+                self.launch()
+        torch.cuda.current_stream().wait_stream(s)
+        return self.graph
+
+    def step(self):
+        if self.graph is not None:
+            self.graph.replay()
+        else:
+            self.launch()
+        return self.y

@@ -14,7 +14,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def test_library_exports_every_declared_symbol():
-    header = open(os.path.join(ROOT, "include", "bitlinear.h")).read()
+    header = "".join(open(os.path.join(ROOT, "include", h)).read() for h in sorted(os.listdir(os.path.join(ROOT, "include"))))
     body = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     declared = set(re.findall(r"\b(bl_[a-z0-9_]+)\s*\(", body))
     assert declared == set(B.DECLARED_SYMBOLS)
@@ -30,6 +30,8 @@ def test_struct_layout_matches_header():
     assert ctypes.sizeof(B.GemvItem) == 56
     assert ctypes.sizeof(B.QuantItem) == 64 and B.QuantItem.q_dev.offset == 40
     assert ctypes.sizeof(B.DecodeItem) == 80 and B.DecodeItem.packed_dev.offset == 24
+    assert ctypes.sizeof(B.NormQuantArgs) == 96 and B.NormQuantArgs.eps.offset == 56 and B.NormQuantArgs.q_dev.offset == 64
+    assert ctypes.sizeof(B.AttnArgs) == 88 and B.AttnArgs.n_heads.offset == 72
 
 
 def test_padding_and_descriptor():
@@ -182,3 +184,42 @@ def test_tl2_descriptor_and_validation():
     bad.Kp = 192
     assert _st(B.bl_tl2_unpack, P, bad, P) == B.BL_ERR_SHAPE
 
+
+
+def test_decoder_block_validation():
+    P = 0x10000  # fake aligned device pointer, never dereferenced: validation fails first
+    ok = dict(mode=B.BL_NORM_PLAIN, M=1, K=128, gamma_dev=P, eps=1e-5, a_dev=P, q_dev=P, a_scale_dev=P, q_sum_dev=P, Kp=128)
+    def norm(**kw):
+        return _st(B.bl_norm_quant, B.make_norm_quant_args(**dict(ok, **kw)))
+    assert norm(gamma_dev=0) == B.BL_ERR_NULL
+    assert norm(a_dev=0) == B.BL_ERR_NULL
+    assert norm(mode=B.BL_NORM_RESIDUAL, h_dev=0) == B.BL_ERR_NULL
+    assert norm(mode=B.BL_NORM_GATED, b_dev=0) == B.BL_ERR_NULL
+    assert norm(a_scale_dev=0) == B.BL_ERR_NULL                      # q without its scale
+    assert norm(q_dev=0, a_scale_dev=0) == B.BL_ERR_NULL             # q_sum without q
+    assert norm(mode=3) == B.BL_ERR_SHAPE
+    assert norm(M=0) == B.BL_ERR_SHAPE
+    assert norm(K=0) == B.BL_ERR_SHAPE
+    assert norm(K=B.BL_NORM_MAX_K + 1, Kp=B.BL_NORM_MAX_K + 4) == B.BL_ERR_SHAPE
+    assert norm(Kp=124) == B.BL_ERR_SHAPE
+    assert norm(Kp=130) == B.BL_ERR_SHAPE
+    assert norm(a_dev=P + 2) == B.BL_ERR_ALIGN
+    assert norm(q_dev=P + 1) == B.BL_ERR_ALIGN
+    assert _st(B.bl_rope_table, 0, 64, 16, 10000.0) == B.BL_ERR_NULL
+    assert _st(B.bl_rope_table, P, 63, 16, 10000.0) == B.BL_ERR_SHAPE
+    assert _st(B.bl_rope_table, P, 64, 0, 10000.0) == B.BL_ERR_SHAPE
+    assert _st(B.bl_rope_table, P, 64, 16, 0.0) == B.BL_ERR_SHAPE
+    assert _st(B.bl_rope_table, P + 4, 64, 16, 10000.0) == B.BL_ERR_ALIGN
+    assert B.bl_attn_scratch_bytes(32, 102, 512) == 0                # head_dim not a multiple of 4
+    assert B.bl_attn_scratch_bytes(32, 128, 513) == 32 * 3 * 130 * 4
+    assert B.bl_attn_scratch_bytes(0, 128, 512) == 0 and B.bl_attn_scratch_bytes(1, 264, 512) == 0
+    good = [P] * 9 + [4, 64, 100]
+    def attn(i, v):
+        a = list(good)
+        a[i] = v
+        return _st(B.bl_attn_decode, B.make_attn_args(*a))
+    for i in range(9):
+        assert attn(i, 0) == B.BL_ERR_NULL
+    assert attn(9, 0) == B.BL_ERR_SHAPE and attn(10, 62) == B.BL_ERR_SHAPE and attn(11, 0) == B.BL_ERR_SHAPE
+    assert attn(5, P + 8) == B.BL_ERR_ALIGN and attn(4, P + 4) == B.BL_ERR_ALIGN and attn(0, P + 1) == B.BL_ERR_ALIGN
+    assert _st(B.bl_pos_advance, 0) == B.BL_ERR_NULL and _st(B.bl_pos_advance, P + 2) == B.BL_ERR_ALIGN
