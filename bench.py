@@ -40,7 +40,8 @@ def parse_args():
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
     ap.add_argument("--full-100b", action="store_true",
                     help="extra: build all 80 layers of the 100B-shape model (37 GB packed) and time a whole token")
-    ap.add_argument("--only", default="", help="run only one extra section (copy|prefill|decode7b|decode100b|paper100b|config1|appendixa|tl2) and print it")
+    ap.add_argument("--models", default="", help="with --only tokens: comma-separated Appendix-A model names (default: all 12)")
+    ap.add_argument("--only", default="", help="run only one extra section (copy|prefill|decode7b|decode100b|paper100b|config1|appendixa|tokens|tl2) and print it")
     return ap.parse_args()
 
 
@@ -413,6 +414,40 @@ def extra_appendix_a(torch, use_graph):
     return rows
 
 
+def extra_decoder_tokens(torch, models, max_pos=512, tokens=64):
+    """Whole-model token rate in the paper's own unit (Section 3's tables: tokens/s) on Appendix A's shapes with
+    dummy weights as in the paper: every token passes through ALL layers -- norms, the seven products, rotary
+    embedding, attention over the bf16 cache, gate, residuals -- as ONE captured graph per token (10 launches
+    per layer).  No embedding lookup, output head or sampling: the paper gives no vocabulary.  Timed at a short
+    context (positions 0 .. tokens-1) and at a longer one (the last `tokens` positions below max_pos)."""
+    from paper_2410_16144_amd import decoder, synth
+    dev = torch.device("cuda:0")
+    rows = []
+    for name in models or list(synth.PAPER_MODELS):
+        hidden, ffn, n_layers = synth.PAPER_MODELS[name]
+        stack = decoder.make_stack(name, max_pos, dev)
+        stack.capture()
+        x = torch.randn((tokens, 1, hidden), device=dev, generator=torch.Generator(device=dev).manual_seed(1))
+        row = {"model": name, "hidden": hidden, "ffn": ffn, "layers": n_layers, "heads": synth.PAPER_HEADS[name],
+               "packed_GB": round(sum(p.packed_bytes for p in synth.layer_projections(hidden, ffn)) * n_layers / 1e9, 3)}
+        for label, start in (("context_0", 0), ("context_%d" % (max_pos - tokens), max_pos - tokens)):
+            def run():
+                for t in range(tokens):
+                    stack.h.copy_(x[t])
+                    stack.graph.replay()
+            stack.pos.fill_(start)
+            run()                      # untimed pass (also brings the clocks up)
+            stack.pos.fill_(start)
+            ms, _ = timed(torch, run)
+            assert int(stack.pos[0]) == start + tokens and bool(torch.isfinite(stack.y).all())
+            row[label] = {"ms_per_token": round(ms / tokens, 4), "tokens_per_s": round(tokens * 1e3 / ms, 1),
+                          "us_per_layer": round(ms * 1e3 / tokens / n_layers, 2)}
+        rows.append(row)
+        del stack
+        torch.cuda.empty_cache()
+    return rows
+
+
 def extra_full_100b(torch, use_graph):
     """All 80 layers of the 100B-shape model resident (36.99 GB packed); one token = 80 fused launches."""
     from paper_2410_16144_amd.decode_layer import make_layer
@@ -469,6 +504,7 @@ def main():
                 "paper100b": lambda: extra_decode_shape(torch, "Appendix-A 100B", 8192, 45568, 1, 6, 120, use_graph),
                 "config1": lambda: extra_config1(torch, use_graph),
                 "appendixa": lambda: extra_appendix_a(torch, use_graph),
+                "tokens": lambda: extra_decoder_tokens(torch, args.models.split(",") if args.models else None),
                 "tl2": lambda: extra_tl2(torch, use_graph),
                 }[args.only]()
         print(json.dumps({args.only: sect}))

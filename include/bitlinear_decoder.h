@@ -33,7 +33,7 @@ extern "C" {
 #define BL_NORM_MAX_K 49152     /* longest row bl_norm_quant takes (the paper's largest
                                    intermediate size, Appendix A "100B", is 45568)        */
 #define BL_ATTN_MAX_HEAD_DIM 256
-#define BL_ATTN_CHUNK 256       /* cache positions per workgroup of the attention kernel  */
+#define BL_ATTN_CHUNK 64        /* cache positions per workgroup of the attention kernel  */
 
 typedef enum bl_norm_mode {
     BL_NORM_PLAIN = 0,      /* x = a                                                  */

@@ -37,7 +37,7 @@ DECLARED_SYMBOLS = (
 
 BL_NORM_MAX_K = 49152
 BL_ATTN_MAX_HEAD_DIM = 256
-BL_ATTN_CHUNK = 256
+BL_ATTN_CHUNK = 64
 BL_NORM_PLAIN, BL_NORM_RESIDUAL, BL_NORM_GATED = 0, 1, 2
 
 

@@ -10,7 +10,7 @@
 //                       workgroup per token row, the row held in registers from its only read to the int8
 //                       store (the quantizer is the one of bl_quant_act, bit for bit);
 //   rope_table_kernel   cos / sin of every (position, frequency), fp64 arithmetic, rounded to fp32;
-//   attn_chunk_kernel   one (head, chunk of 256 cache rows) per workgroup: rotate query and key, append key and
+//   attn_chunk_kernel   one (head, chunk of 64 cache rows) per workgroup: rotate query and key, append key and
 //                       value to the bf16 cache, scores, softmax within the chunk, weighted values;
 //   attn_merge_kernel   one workgroup per head merges its chunks (the usual running-maximum rescaling);
 //   pos_advance_kernel  the token position lives in device memory, so a captured graph replays unchanged.
@@ -78,10 +78,15 @@ __global__ __launch_bounds__(kNormThreads) void norm_quant_kernel(const NormArgs
     const int K = p.K;
     const int64_t row = (int64_t)blockIdx.x * K;
     float x[NV][4];
+    // short rows: the norm weights are requested with the row, before the first barrier (one memory round trip
+    // instead of two); long rows have no registers to spare for that
+    constexpr bool kGammaEarly = NV <= 4;
+    float gam[kGammaEarly ? NV : 1][4];
     float ss = 0.0f;
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
         const int k = (tid + i * kNormThreads) * 4;
+        if constexpr (kGammaEarly) load4<VEC>(p.gamma, k, K, gam[i]);
         if constexpr (MODE == BL_NORM_PLAIN) {
             load4<VEC>(p.a + row, k, K, x[i]);
         } else if constexpr (MODE == BL_NORM_RESIDUAL) {
@@ -116,7 +121,12 @@ __global__ __launch_bounds__(kNormThreads) void norm_quant_kernel(const NormArgs
     for (int i = 0; i < NV; ++i) {
         const int k = (tid + i * kNormThreads) * 4;
         float g[4];
-        load4<VEC>(p.gamma, k, K, g);
+        if constexpr (kGammaEarly) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) g[j] = gam[i][j];
+        } else {
+            load4<VEC>(p.gamma, k, K, g);
+        }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             x[i][j] = (x[i][j] * r) * g[j];
@@ -198,7 +208,7 @@ __global__ __launch_bounds__(256) void rope_table_kernel(float2* table, int half
 constexpr int kAttnThreads = 256;
 constexpr int kAttnWaves = kAttnThreads / kWave;
 constexpr int kChunk = BL_ATTN_CHUNK;
-static_assert(kChunk == kAttnThreads, "one cache row per thread in the score pass");
+static_assert(kChunk == kWave, "the chunk's softmax runs in one wavefront");
 
 struct AttnArgs {
     const float*   q_lin;
@@ -218,36 +228,40 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float f) {   // nearest, ties to
     return (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
 }
 
-__device__ __forceinline__ float block_max(float v, float* s_red, int wave, int lane) {   // any sign
-    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off));
-    __syncthreads();   // the previous use of s_red has been read
-    if (lane == 0) s_red[wave] = v;
-    __syncthreads();
-    float m = s_red[0];
+// W bf16 values as one register vector: 128 bits for W = 8, 64 bits for W = 4.
+template <int W> struct CacheVec;
+template <> struct CacheVec<8> { typedef uint4 type; };
+template <> struct CacheVec<4> { typedef uint2 type; };
+
+template <int W>
+__device__ __forceinline__ void unpack_bf16(const typename CacheVec<W>::type& u, float (&f)[W]) {
+    const uint32_t* w = reinterpret_cast<const uint32_t*>(&u);
 #pragma unroll
-    for (int w = 1; w < kAttnWaves; ++w) m = fmaxf(m, s_red[w]);
-    return m;
+    for (int i = 0; i < W / 2; ++i) {
+        f[2 * i] = bf16_to_f32(w[i] & 0xffffu);
+        f[2 * i + 1] = bf16_to_f32(w[i] >> 16);
+    }
 }
 
-__device__ __forceinline__ float block_sum(float v, float* s_red, int wave, int lane) {
-    v = wave_sum_f(v);
-    __syncthreads();
-    if (lane == 0) s_red[wave] = v;
-    __syncthreads();
-    float t = 0.0f;
-#pragma unroll
-    for (int w = 0; w < kAttnWaves; ++w) t += s_red[w];
-    return t;
-}
-
+// One (head, chunk of 64 cache rows) per workgroup.  The chunk's keys and values (64 x head_dim bf16 each) are
+// requested first, W values per thread and request, consecutive threads on consecutive addresses of a row; while
+// they travel the query is rotated (and, in the chunk that holds the token's own row, key and value are rotated,
+// rounded and appended).  Scores: every thread multiplies its W key values with the query's and leaves the partial
+// sum in LDS, one thread per row adds the head_dim / W partials.  The chunk's softmax is one wavefront.  The
+// values go to LDS as they are; thread (element, part) then adds its rows' weighted values.
+template <int W>
 __global__ __launch_bounds__(kAttnThreads) void attn_chunk_kernel(const AttnArgs p) {
-    __shared__ float s_q[BL_ATTN_MAX_HEAD_DIM];       // rotated query, pre-scaled by 1 / sqrt(head_dim)
-    __shared__ float s_newk[BL_ATTN_MAX_HEAD_DIM];    // the token's own key and value as the cache holds them
-    __shared__ float s_newv[BL_ATTN_MAX_HEAD_DIM];
-    __shared__ float s_w[kChunk];                     // softmax numerators of the chunk's rows
-    __shared__ float s_o[kAttnThreads];               // partial weighted values, [part][element]
-    __shared__ float s_red[kAttnWaves];
-    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+    typedef typename CacheVec<W>::type vec_t;
+    constexpr int kMaxLanesPerRow = BL_ATTN_MAX_HEAD_DIM / W;                 // 32 (W = 8) or 64 (W = 4)
+    constexpr int kVecs = kChunk * kMaxLanesPerRow / kAttnThreads;            // requests per thread at most: 8 / 16
+    __shared__ __attribute__((aligned(16))) float s_q[BL_ATTN_MAX_HEAD_DIM];  // rotated query / sqrt(head_dim)
+    __shared__ __attribute__((aligned(16))) float s_newk[BL_ATTN_MAX_HEAD_DIM];   // the token's own key and value as cached
+    __shared__ __attribute__((aligned(16))) float s_newv[BL_ATTN_MAX_HEAD_DIM];
+    __shared__ float s_part[kChunk * (kMaxLanesPerRow + 1)];
+    __shared__ __attribute__((aligned(16))) uint16_t s_v[kChunk * BL_ATTN_MAX_HEAD_DIM];
+    __shared__ float s_w[kChunk];
+    __shared__ float s_o[kAttnThreads];
+    const int tid = threadIdx.x;
     const int head = blockIdx.x, chunk = blockIdx.y;
     const int d = p.head_dim, half = d / 2;
     const int hidden = p.n_heads * d;
@@ -257,8 +271,24 @@ __global__ __launch_bounds__(kAttnThreads) void attn_chunk_kernel(const AttnArgs
     if (j0 > pos) return;                               // uniform: nothing cached this far yet
     const int rows = min(kChunk, pos + 1 - j0);
     const bool owner = pos < j0 + kChunk;               // uniform: this chunk holds the token's own row
-    const float scale = 1.0f / sqrtf((float)d);
+    const int lanes_per_row = d / W;
+    const int total = kChunk * lanes_per_row;           // a multiple of 64: the guards below are uniform per wave
 
+    // rows beyond the token's are read as the token's row (always inside the cache) and never used; the token's own
+    // row may be read while this workgroup writes it and is replaced by the values kept in LDS
+    vec_t kv[kVecs], vv[kVecs];
+#pragma unroll
+    for (int i = 0; i < kVecs; ++i) {
+        const int v = tid + i * kAttnThreads;
+        if (v < total) {
+            const int row = v / lanes_per_row, c = v - row * lanes_per_row;
+            const int64_t at = (int64_t)min(j0 + row, pos) * hidden + head * d + c * W;
+            kv[i] = *reinterpret_cast<const vec_t*>(p.k_cache + at);
+            vv[i] = *reinterpret_cast<const vec_t*>(p.v_cache + at);
+        }
+    }
+
+    const float scale = 1.0f / sqrtf((float)d);
     if (tid < half) {
         const float2 cs = p.rope[(int64_t)pos * half + tid];
         const float a = p.q_lin[head * d + tid], b = p.q_lin[head * d + tid + half];
@@ -278,81 +308,103 @@ __global__ __launch_bounds__(kAttnThreads) void attn_chunk_kernel(const AttnArgs
     }
     __syncthreads();
 
-    // scores: thread t takes cache row j0 + t (its d values are contiguous)
-    float score = -INFINITY;
-    if (tid < rows) {
-        const int j = j0 + tid;
-        float acc = 0.0f;
-        if (j == pos) {
-            for (int e = 0; e < d; ++e) acc += s_q[e] * s_newk[e];
-        } else {
-            const uint16_t* krow = p.k_cache + (int64_t)j * hidden + head * d;
-            auto mac2 = [&](uint32_t pair, int e) {
-                acc += s_q[e] * bf16_to_f32(pair & 0xffffu);
-                acc += s_q[e + 1] * bf16_to_f32(pair >> 16);
-            };
-            if (d % 8 == 0) {                                   // uniform: 128-bit loads
-                for (int c = 0; c < d / 8; ++c) {
-                    const uint4 u = reinterpret_cast<const uint4*>(krow)[c];
-                    mac2(u.x, 8 * c); mac2(u.y, 8 * c + 2); mac2(u.z, 8 * c + 4); mac2(u.w, 8 * c + 6);
-                }
-            } else {                                            // head_dim % 4 == 0: 64-bit loads
-                for (int c = 0; c < d / 4; ++c) {
-                    const uint2 u = reinterpret_cast<const uint2*>(krow)[c];
-                    mac2(u.x, 4 * c); mac2(u.y, 4 * c + 2);
-                }
+#pragma unroll
+    for (int i = 0; i < kVecs; ++i) {
+        const int v = tid + i * kAttnThreads;
+        if (v < total) {
+            const int row = v / lanes_per_row, c = v - row * lanes_per_row;
+            const bool own = j0 + row == pos;
+            float k[W];
+            unpack_bf16<W>(kv[i], k);
+            float acc = 0.0f;
+#pragma unroll
+            for (int e = 0; e < W; ++e) acc += s_q[c * W + e] * (own ? s_newk[c * W + e] : k[e]);
+            s_part[row * (lanes_per_row + 1) + c] = acc;
+            // values: to LDS as cached (the token's own row from the rounded values of this launch)
+            vec_t out = vv[i];
+            if (own) {
+                uint32_t* w = reinterpret_cast<uint32_t*>(&out);
+#pragma unroll
+                for (int e = 0; e < W / 2; ++e)
+                    w[e] = (__float_as_uint(s_newv[c * W + 2 * e]) >> 16) | (__float_as_uint(s_newv[c * W + 2 * e + 1]) & 0xffff0000u);
             }
+            *reinterpret_cast<vec_t*>(s_v + row * d + c * W) = out;
         }
-        score = acc;
     }
-    const float m = block_max(score, s_red, wave, lane);
-    const float w = tid < rows ? expf(score - m) : 0.0f;
-    s_w[tid] = w;
-    const float l = block_sum(w, s_red, wave, lane);    // its barriers also publish s_w
+    __syncthreads();
 
-    // weighted values: thread (part, e) sums rows part, part + parts, ... for element e; a row's d values are
-    // consecutive 16-bit loads across the threads of a part
+    float* dst = p.scratch + ((int64_t)head * p.chunks + chunk) * (d + 2);
+    if (tid < kWave) {                                  // wave 0: one row per lane
+        float score = -INFINITY;
+        if (tid < rows) {
+            score = 0.0f;
+            for (int c = 0; c < lanes_per_row; ++c) score += s_part[tid * (lanes_per_row + 1) + c];
+        }
+        float m = score;
+        for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
+        const float w = tid < rows ? expf(score - m) : 0.0f;
+        s_w[tid] = w;
+        const float l = wave_sum_f(w);
+        if (tid == 0) {
+            dst[d] = m;
+            dst[d + 1] = l;
+        }
+    }
+    __syncthreads();
+
     const int parts = kAttnThreads / d;                 // >= 1: head_dim <= 256
     const int part = tid / d, e = tid - part * d;
     float o = 0.0f;
-    if (part < parts) {
-        for (int t = part; t < rows; t += parts) {
-            const int j = j0 + t;
-            const float v = j == pos ? s_newv[e] : bf16_to_f32(p.v_cache[(int64_t)j * hidden + head * d + e]);
-            o += s_w[t] * v;
-        }
-    }
+    if (part < parts)
+        for (int t = part; t < rows; t += parts) o += s_w[t] * bf16_to_f32(s_v[t * d + e]);
     s_o[tid] = o;
     __syncthreads();
-    float* dst = p.scratch + ((int64_t)head * p.chunks + chunk) * (d + 2);
     if (tid < d) {
         float t = 0.0f;
         for (int q = 0; q < parts; ++q) t += s_o[q * d + tid];
         dst[tid] = t;
     }
-    if (tid == 0) {
-        dst[d] = m;
-        dst[d + 1] = l;
-    }
 }
 
+// One workgroup per head: out = sum_c f_c o_c / sum_c f_c l_c with f_c = exp(m_c - max m) over the chunks that hold
+// rows 0 .. pos.  The chunks' maxima and sums are read one per thread; the factors go through LDS.
 __global__ __launch_bounds__(kAttnThreads) void attn_merge_kernel(const AttnArgs p) {
-    const int tid = threadIdx.x, head = blockIdx.x;
+    __shared__ float s_f[kAttnThreads];
+    __shared__ float s_red[kAttnWaves];
+    const int tid = threadIdx.x, head = blockIdx.x, wave = tid / kWave, lane = tid % kWave;
     const int d = p.head_dim;
     const int pos = *p.pos;
     if (pos < 0 || pos >= p.max_pos) return;            // uniform
     const int used = pos / kChunk + 1;                   // chunks that hold rows 0 .. pos
     const float* src = p.scratch + (int64_t)head * p.chunks * (d + 2);
-    if (tid >= d) return;
     float m = -INFINITY;
-    for (int c = 0; c < used; ++c) m = fmaxf(m, src[c * (d + 2) + d]);
+    for (int c = tid; c < used; c += kAttnThreads) m = fmaxf(m, src[c * (d + 2) + d]);
+    for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
+    if (lane == 0) s_red[wave] = m;
+    __syncthreads();
+    m = fmaxf(fmaxf(s_red[0], s_red[1]), fmaxf(s_red[2], s_red[3]));
+    static_assert(kAttnWaves == 4, "four partial maxima");
     float l = 0.0f, o = 0.0f;
-    for (int c = 0; c < used; ++c) {
-        const float f = expf(src[c * (d + 2) + d] - m);
-        l += f * src[c * (d + 2) + d + 1];
-        o += f * src[c * (d + 2) + tid];
+    for (int c0 = 0; c0 < used; c0 += kAttnThreads) {   // one pass unless the context exceeds 256 chunks
+        __syncthreads();                                // s_f and s_red of the previous pass have been read
+        const int c = c0 + tid;
+        float f = 0.0f, fl = 0.0f;
+        if (c < used) {
+            f = expf(src[c * (d + 2) + d] - m);
+            fl = f * src[c * (d + 2) + d + 1];
+        }
+        s_f[tid] = f;
+        fl = wave_sum_f(fl);
+        if (lane == 0) s_red[wave] = fl;
+        __syncthreads();
+        l += (s_red[0] + s_red[1]) + (s_red[2] + s_red[3]);
+        const int n = min(kAttnThreads, used - c0);
+        if (tid < d) {
+#pragma unroll 4
+            for (int i = 0; i < n; ++i) o += s_f[i] * src[(c0 + i) * (d + 2) + tid];
+        }
     }
-    p.out[head * d + tid] = o / l;
+    if (tid < d) p.out[head * d + tid] = o / l;
 }
 
 __global__ void pos_advance_kernel(int32_t* pos) {
@@ -394,7 +446,8 @@ hipError_t launch_attn_decode(const bl_attn_args& a, hipStream_t s) {
     p.k_cache = a.k_cache_dev; p.v_cache = a.v_cache_dev; p.out = a.out_dev;
     p.scratch = static_cast<float*>(a.scratch_dev);
     p.n_heads = a.n_heads; p.head_dim = a.head_dim; p.max_pos = a.max_pos; p.chunks = attn_chunks(a.max_pos);
-    attn_chunk_kernel<<<dim3((unsigned)a.n_heads, (unsigned)p.chunks), dim3(kAttnThreads), 0, s>>>(p);
+    if (a.head_dim % 8 == 0) attn_chunk_kernel<8><<<dim3((unsigned)a.n_heads, (unsigned)p.chunks), dim3(kAttnThreads), 0, s>>>(p);
+    else attn_chunk_kernel<4><<<dim3((unsigned)a.n_heads, (unsigned)p.chunks), dim3(kAttnThreads), 0, s>>>(p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     attn_merge_kernel<<<dim3((unsigned)a.n_heads), dim3(kAttnThreads), 0, s>>>(p);

@@ -183,3 +183,27 @@ class DecoderStack:
         else:
             self.launch()
         return self.y
+
+
+def make_stack(name: str, max_pos: int, device, config: int = 7, n_layers: Optional[int] = None,
+               use_workspace=True) -> DecoderStack:
+    """A dummy model of Appendix A's shape `name` (as in the paper: random ternary weights, drawn on the device from
+    the seed rule of synth.seed_for), norm weights uniform in [0.5, 1.5]."""
+    from . import synth
+    hidden, ffn, layers = synth.PAPER_MODELS[name]
+    n_layers = layers if n_layers is None else n_layers
+    ws = []
+    g = torch.Generator(device=device)
+    for i in range(n_layers):
+        proj = {}
+        for j, p in enumerate(synth.layer_projections(hidden, ffn)):
+            seed = synth.seed_for(config, i, j)
+            wd = synth.ternary_weights_device(seed, p.N, p.K, device)
+            proj[p.name] = ops.pack_ternary(wd, float(synth.draw_w_scale(synth.rng_for(seed))))
+            del wd
+        g.manual_seed(synth.seed_for(config, i, 8))
+        gam = [torch.rand(k, device=device, generator=g) + 0.5 for k in (hidden, hidden, hidden, ffn)]
+        ws.append(LayerWeights(proj, *gam))
+    g.manual_seed(synth.seed_for(config, n_layers, 8))
+    return DecoderStack(ws, torch.rand(hidden, device=device, generator=g) + 0.5, synth.PAPER_HEADS[name], max_pos, device,
+                        use_workspace=use_workspace)

@@ -32,6 +32,10 @@ PAPER_MODELS = {
     "100B": (8192, 45568, 72),
 }
 
+# num_attention_heads of the same 12 configurations (Appendix A); head size = hidden_size / heads.
+PAPER_HEADS = {"125M": 12, "350M": 16, "700M": 16, "1B": 32, "1.5B": 32, "2.5B": 20, "3.8B": 32, "7B": 32,
+               "13B": 40, "30B": 52, "70B": 64, "100B": 64}
+
 # Layer shapes of the benchmark configurations (same 7-projection structure).
 BENCH_MODELS = {
     "3B": (3200, 8640, 26),
