@@ -79,6 +79,48 @@ typedef struct bl_norm_quant_args {
 bl_status bl_norm_quant(const bl_norm_quant_args *args, void *stream);
 
 /*
+ * RMSNorm + quantizer + product in ONE launch, for one token and up to BL_MAX_BATCH matrices (e.g. Q, K, V
+ * on the same normalised row): bl_decode_batch with the norm folded into its in-kernel quantizer.
+ *
+ *   x'  = x + delta                      (delta optional)
+ *   out = BitLinear(rmsnorm(x', gamma))  = (sum_k q[k] W[n,k]) * w_scale * a_scale
+ *
+ * The norm's scalar r = 1 / sqrt(mean(x'^2) + eps) is positive and common to the row, so it passes through
+ * the absmax quantizer: the codes are those of z = x' * gamma (q = bl_quant_act(z), bit for bit) and
+ * a_scale = a_scale(z) * r.  Against quantizing y = r * z element by element, a code can differ only where
+ * y sits within fp32 rounding of a tie.
+ *   x_dev, delta_dev, gamma_dev   [K] fp32, 16-byte aligned; K a multiple of 8, K <= BL_DECODE_NORM_MAX_K
+ *   h_out_dev   optional [K] fp32: receives x' (the updated residual stream).  Must not overlap
+ *               x_dev or delta_dev: other workgroups still read those.  Give it to one item of
+ *               a launch whose items share x_dev.
+ *   packed_dev, desc, out_dev [N], acc_dev (optional), q_dev [Kp] / a_scale_dev [1] / q_sum_dev [1]
+ *               (optional copies of the quantizer's results): as in bl_decode_item with M = 1
+ *   workspace_dev: as for bl_gemv_batch (may be NULL)
+ * Errors: BL_ERR_NULL, BL_ERR_COUNT, BL_ERR_LAYOUT, BL_ERR_SHAPE (also K not a multiple of 8 or beyond
+ *         BL_DECODE_NORM_MAX_K, h_out_dev equal to x_dev or delta_dev), BL_ERR_BUF_SMALL, BL_ERR_ALIGN,
+ *         BL_ERR_HIP.
+ */
+#define BL_DECODE_NORM_MAX_K 16384
+
+typedef struct bl_decode_norm_item {
+    const float          *x_dev;
+    const float          *delta_dev;
+    float                *h_out_dev;
+    const float          *gamma_dev;
+    float                 eps;
+    const void           *packed_dev;
+    const bl_packed_desc *desc;
+    float                *out_dev;
+    int32_t              *acc_dev;
+    int8_t               *q_dev;
+    float                *a_scale_dev;
+    int32_t              *q_sum_dev;
+} bl_decode_norm_item;
+
+bl_status bl_decode_norm_batch(const bl_decode_norm_item *items, int32_t count, void *workspace_dev,
+                               void *stream);
+
+/*
  * Rotary table for bl_attn_decode, computed on the GPU in fp64 and rounded to fp32:
  *   table[(p * head_dim/2 + i) * 2 + {0, 1}] = {cos, sin}(p * theta^(-2 i / head_dim)),
  *   p = 0 .. max_pos-1, i = 0 .. head_dim/2 - 1.   table_dev: max_pos * head_dim floats.

@@ -32,13 +32,14 @@ DECLARED_SYMBOLS = (
     "bl_padded_k", "bl_padded_n", "bl_packed_desc_init", "bl_pack_ternary", "bl_unpack_ternary",
     "bl_quant_act", "bl_quant_act_batch", "bl_gemv", "bl_gemv_batch", "bl_decode_batch", "bl_gemm", "bl_set_tuning", "bl_get_stat", "bl_status_str", "bl_last_hip_error", "bl_version",
     "bl_tl2_padded_k", "bl_tl2_desc_init", "bl_tl2_pack", "bl_tl2_unpack", "bl_tl2_gemv", "bl_tl2_gemv_batch",
-    "bl_norm_quant", "bl_rope_table", "bl_attn_scratch_bytes", "bl_attn_decode", "bl_pos_advance",
+    "bl_norm_quant", "bl_rope_table", "bl_attn_scratch_bytes", "bl_attn_decode", "bl_pos_advance", "bl_decode_norm_batch",
 )
 
 BL_NORM_MAX_K = 49152
 BL_ATTN_MAX_HEAD_DIM = 256
 BL_ATTN_CHUNK = 64
 BL_NORM_PLAIN, BL_NORM_RESIDUAL, BL_NORM_GATED = 0, 1, 2
+BL_DECODE_NORM_MAX_K = 16384
 
 
 class BitLinearError(RuntimeError):
@@ -95,6 +96,14 @@ class AttnArgs(ctypes.Structure):
                 ("n_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32), ("max_pos", ctypes.c_int32)]
 
 
+class DecodeNormItem(ctypes.Structure):
+    """Mirror of bl_decode_norm_item."""
+    _fields_ = [("x_dev", ctypes.c_void_p), ("delta_dev", ctypes.c_void_p), ("h_out_dev", ctypes.c_void_p),
+                ("gamma_dev", ctypes.c_void_p), ("eps", ctypes.c_float), ("packed_dev", ctypes.c_void_p),
+                ("desc", ctypes.POINTER(PackedDesc)), ("out_dev", ctypes.c_void_p), ("acc_dev", ctypes.c_void_p),
+                ("q_dev", ctypes.c_void_p), ("a_scale_dev", ctypes.c_void_p), ("q_sum_dev", ctypes.c_void_p)]
+
+
 _lib = None
 
 
@@ -139,6 +148,7 @@ def lib():
     l.bl_attn_scratch_bytes.restype = ctypes.c_uint64
     l.bl_attn_decode.argtypes = [ctypes.POINTER(AttnArgs), vp]
     l.bl_pos_advance.argtypes = [vp, vp]
+    l.bl_decode_norm_batch.argtypes = [ctypes.POINTER(DecodeNormItem), i32, vp, vp]
     l.bl_set_tuning.argtypes = [ctypes.c_char_p, i32]
     l.bl_get_stat.argtypes = [ctypes.c_char_p]
     l.bl_get_stat.restype = i64
@@ -149,7 +159,7 @@ def lib():
     for name in ("bl_packed_desc_init", "bl_pack_ternary", "bl_unpack_ternary", "bl_quant_act", "bl_quant_act_batch", "bl_gemv",
                  "bl_gemv_batch", "bl_decode_batch", "bl_gemm", "bl_set_tuning", "bl_tl2_desc_init", "bl_tl2_pack",
                  "bl_tl2_unpack", "bl_tl2_gemv", "bl_tl2_gemv_batch", "bl_norm_quant", "bl_rope_table", "bl_attn_decode",
-                 "bl_pos_advance"):
+                 "bl_pos_advance", "bl_decode_norm_batch"):
         getattr(l, name).restype = ctypes.c_int
     _lib = l
     return l
@@ -324,6 +334,22 @@ def bl_attn_decode(args: AttnArgs, stream: int = 0):
 
 def bl_pos_advance(pos_dev: int, stream: int = 0):
     _check(lib().bl_pos_advance(pos_dev, stream), "bl_pos_advance")
+
+
+def make_decode_norm_items(items):
+    """items: iterable of (x_dev, delta_dev, h_out_dev, gamma_dev, eps, packed_dev, desc, out_dev, acc_dev, q_dev,
+    a_scale_dev, q_sum_dev); 0 for an absent optional pointer.  Returns a ctypes array that keeps the descriptors alive."""
+    items = list(items)
+    arr = (DecodeNormItem * len(items))()
+    for i, (x, dl, ho, g, eps, pk, desc, out, acc, q, a, sm) in enumerate(items):
+        arr[i] = DecodeNormItem(x or None, dl or None, ho or None, g or None, eps, pk or None, ctypes.pointer(desc),
+                                out or None, acc or None, q or None, a or None, sm or None)
+    arr._descs = [it[6] for it in items]
+    return arr
+
+
+def bl_decode_norm_batch(items, workspace_dev: int = 0, stream: int = 0):
+    _check(lib().bl_decode_norm_batch(items, len(items), workspace_dev or None, stream), "bl_decode_norm_batch")
 
 
 def bl_set_tuning(key: str, value: int):

@@ -346,6 +346,45 @@ bl_status bl_norm_quant(const bl_norm_quant_args* a, void* stream) {
     return hip_status(bl::launch_norm_quant(*a, static_cast<hipStream_t>(stream)));
 }
 
+bl_status bl_decode_norm_batch(const bl_decode_norm_item* items, int32_t count, void* workspace_dev, void* stream) {
+    if (!items) return BL_ERR_NULL;
+    if (count < 1 || count > BL_MAX_BATCH) return BL_ERR_COUNT;
+    if (workspace_dev && !aligned(workspace_dev, 256)) return BL_ERR_ALIGN;
+    bl::DecodeBatch b;
+    memset(&b, 0, sizeof b);
+    b.ws = static_cast<unsigned long long*>(workspace_dev);
+    int64_t max_Kp = 0;
+    for (int i = 0; i < count; ++i) {
+        const bl_decode_norm_item& it = items[i];
+        if (!it.x_dev || !it.gamma_dev || !it.packed_dev || !it.desc || !it.out_dev) return BL_ERR_NULL;
+        bl_status s = check_desc(it.desc);
+        if (s != BL_OK) return s;
+        if (it.desc->K % 8 != 0 || it.desc->K > BL_DECODE_NORM_MAX_K) return BL_ERR_SHAPE;
+        if (it.h_out_dev && (it.h_out_dev == it.x_dev || it.h_out_dev == it.delta_dev)) return BL_ERR_SHAPE;
+        if (!aligned(it.x_dev, 16) || !aligned(it.gamma_dev, 16) || !aligned(it.delta_dev, 16) || !aligned(it.h_out_dev, 16) ||
+            !aligned(it.packed_dev, 16) || !aligned(it.out_dev, 4) || !aligned(it.acc_dev, 4) || !aligned(it.q_dev, 16) ||
+            !aligned(it.a_scale_dev, 4) || !aligned(it.q_sum_dev, 4))
+            return BL_ERR_ALIGN;
+        bl::DecodeProblem& p = b.p[i];
+        p = make_decode_problem(it.packed_dev, it.desc, it.out_dev, it.acc_dev);
+        p.x = it.x_dev;
+        p.ldx = it.desc->K;
+        p.q_out = it.q_dev;
+        p.a_scale_out = it.a_scale_dev;
+        p.q_sum_out = it.q_sum_dev;
+        p.x_flags = 2;   // fp32, vector loads: the row lives in registers
+        p.gamma = it.gamma_dev;
+        p.delta = it.delta_dev;
+        p.h_out = it.h_out_dev;
+        p.eps = it.eps;
+        if (it.desc->Kp > max_Kp) max_Kp = it.desc->Kp;
+    }
+    if (bl::decode_lds_bytes(1, max_Kp, true) > (size_t)bl::kMaxDecodeLds) return BL_ERR_SHAPE;
+    b.count = count;
+    drop_stale_hip_error();
+    return hip_status(bl::launch_decode(b, 1, true, static_cast<hipStream_t>(stream)));
+}
+
 bl_status bl_rope_table(float* table_dev, int32_t head_dim, int32_t max_pos, double theta, void* stream) {
     if (!table_dev) return BL_ERR_NULL;
     if (head_dim < 2 || head_dim > BL_ATTN_MAX_HEAD_DIM || head_dim % 2 != 0 || max_pos < 1 || !(theta > 0.0))

@@ -258,6 +258,50 @@ __device__ __forceinline__ void row_quantize_to_lds(const Raw8<BF16>& r0, const 
     if (lane == 0) s_i[wave] = sum;
 }
 
+// RMSNorm folded into the fused quantizer (one token, fp32 row in the registers of the holder waves).  The norm's
+// scalar r = 1 / sqrt(mean(x'^2) + eps) is positive and common to the whole row, so it passes through the absmax
+// quantizer unchanged: quantize(r * z) has the codes of quantize(z) and r times its scale.  The row therefore becomes
+// z = x' * gamma with x' = x + delta (one fp32 operation each), is quantized as it is, and r multiplies the
+// activation scale -- no second pass over the row, no extra barrier.
+//
+// On entry r0 / r1 hold x; on exit they hold z.  Returns this thread's part of sum(x'^2).  write_h (uniform): also
+// store x' to p.h_out.
+__device__ __forceinline__ float norm_fold(Raw8<false>& r0, Raw8<false>& r1, const Raw8<false>& g0, const Raw8<false>& g1,
+                                           const Raw8<false>& d0, const Raw8<false>& d1, bool h0, bool h1, int k0, int k1,
+                                           bool has_delta, float* h_out) {
+    float ss = 0.0f;
+    auto one = [&](Raw8<false>& r, const Raw8<false>& g, const Raw8<false>& d, bool held, int k) {
+        float x[8], gm[8], dl[8];
+        unpack_raw8<false>(r, x);
+        unpack_raw8<false>(g, gm);
+        unpack_raw8<false>(d, dl);
+        uint32_t z[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            if (has_delta) x[i] += dl[i];
+            if (held) ss += x[i] * x[i];
+            z[i] = __float_as_uint(x[i] * gm[i]);
+        }
+        if (h_out && held) {
+            float4* dst = reinterpret_cast<float4*>(h_out + k);
+            dst[0] = make_float4(x[0], x[1], x[2], x[3]);
+            dst[1] = make_float4(x[4], x[5], x[6], x[7]);
+        }
+        r.a = make_uint4(z[0], z[1], z[2], z[3]);
+        r.b = make_uint4(z[4], z[5], z[6], z[7]);
+    };
+    one(r0, g0, d0, h0, k0);
+    one(r1, g1, d1, h1, k1);
+    return ss;
+}
+
+// The norm's scalar from the holder waves' partial sums (every thread computes the same value).
+__device__ __forceinline__ float norm_scalar(const float* s_ss, int holding_waves, int K, float eps) {
+    float total = 0.0f;
+    for (int w = 0; w < holding_waves; ++w) total += s_ss[w];
+    return 1.0f / sqrtf(total / (float)K + eps);
+}
+
 // Both halves with their barriers, for a caller whose waves all arrive together.  Only the waves that hold the
 // row run the arithmetic; the others go from barrier to barrier: the waves of a compute unit share four
 // instruction issuers, so sixteen waves stepping through the quantizer's few hundred instructions cost four

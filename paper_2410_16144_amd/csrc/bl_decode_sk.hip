@@ -49,6 +49,7 @@ __global__ __launch_bounds__(kThreads, 8) void decode_sk_kernel(BL_FIRST_WG_PARA
     int* red = reinterpret_cast<int*>(smem + (FUSED ? Kp : 0));    // [row block - rb0][64]
     float* s_f = reinterpret_cast<float*>(red + kSkMaxRb * kWave);  // [16] maxima, then the scale
     int* s_i = reinterpret_cast<int*>(s_f + kWaves + 1);            // [16] partial sum(q)
+    float* s_ss = reinterpret_cast<float*>(s_i + kWaves);           // [16] partial sums of squares (norm form)
 
     for (int i = tid; i < (rb1 - rb0 + 1) * kWave; i += kThreads) red[i] = 0;
 
@@ -89,8 +90,26 @@ __global__ __launch_bounds__(kThreads, 8) void decode_sk_kernel(BL_FIRST_WG_PARA
                 const int holders = holding_waves * kWave;
                 const int k0 = tid * 8, k1 = k0 + holders * 8;
                 const bool h0 = k0 < p.K, h1 = k1 < p.K;
-                const Raw8<XBF16> r0 = load_raw8<XBF16>(p.x, h0 ? k0 : 0), r1 = load_raw8<XBF16>(p.x, h1 ? k1 : 0);
-                load_part(0, 0, kEarly);
+                Raw8<XBF16> r0 = load_raw8<XBF16>(p.x, h0 ? k0 : 0), r1 = load_raw8<XBF16>(p.x, h1 ? k1 : 0);
+                if constexpr (!XBF16) {
+                    if (p.gamma) {   // uniform: RMSNorm folded into the quantizer
+                        const Raw8<false> g0 = load_raw8<false>(p.gamma, h0 ? k0 : 0), g1 = load_raw8<false>(p.gamma, h1 ? k1 : 0);
+                        Raw8<false> d0 = g0, d1 = g1;
+                        if (p.delta) {
+                            d0 = load_raw8<false>(p.delta, h0 ? k0 : 0);
+                            d1 = load_raw8<false>(p.delta, h1 ? k1 : 0);
+                        }
+                        load_part(0, 0, kEarly);
+                        float ss = norm_fold(r0, r1, g0, g1, d0, d1, h0, h1, k0, k1, p.delta != nullptr,
+                                             blk == p.first_wg ? p.h_out : nullptr);
+                        ss = wave_sum_f(ss);
+                        if (lane == 0) s_ss[wave] = ss;
+                    } else {
+                        load_part(0, 0, kEarly);
+                    }
+                } else {
+                    load_part(0, 0, kEarly);
+                }
                 row_absmax_to_lds<XBF16>(r0, r1, h0, h1, s_f, lane, wave);
                 __syncthreads();
                 row_quantize_to_lds<XBF16>(r0, r1, h0, h1, k0, k1, holders, p.K, Kp, lds_q, s_f, s_i, tid, lane, wave);
@@ -108,6 +127,9 @@ __global__ __launch_bounds__(kThreads, 8) void decode_sk_kernel(BL_FIRST_WG_PARA
         }
         for (int w16 = 0; w16 < holding_waves; ++w16) qsum += s_i[w16];
         scale = s_f[kWaves];
+        if constexpr (!XBF16) {
+            if (p.gamma) scale *= norm_scalar(s_ss, holding_waves, p.K, p.eps);   // uniform
+        }
         if (blk == p.first_wg) {   // optional copy-out of the quantizer's results
             if (p.q_out) {
                 for (int i = tid; i < Kp / 4; i += kThreads)
@@ -287,7 +309,7 @@ bool plan_decode_split(DecodeBatch& b, bool fused, int& tiles_per_wave) {
 hipError_t launch_decode_split(const DecodeBatch& b, int tiles_per_wave, bool fused, hipStream_t s) {
     int64_t max_Kp = 0;
     for (int i = 0; i < b.count; ++i) max_Kp = (int64_t)b.p[i].KC * kTileK > max_Kp ? (int64_t)b.p[i].KC * kTileK : max_Kp;
-    const size_t lds = (size_t)(fused ? max_Kp : 0) + (size_t)kSkMaxRb * kWave * 4 + (size_t)(2 * kWaves + 1) * 4;
+    const size_t lds = (size_t)(fused ? max_Kp : 0) + (size_t)kSkMaxRb * kWave * 4 + (size_t)(3 * kWaves + 1) * 4;
     if (lds > (size_t)kMaxDecodeLds) return hipErrorInvalidValue;
     const bool bf16 = b.p[0].x_flags & 1;
     const bool small = tiles_per_wave <= 4;

@@ -55,6 +55,7 @@ __global__ __launch_bounds__(kThreads, 8) void decode_kernel(BL_FIRST_WG_PARAMS,
     int* red = reinterpret_cast<int*>(smem + (FUSED ? M * Kp : 0));
     float* s_f = reinterpret_cast<float*>(red + kWaves * M * kWave);   // [M][16] maxima, then [M] scales
     int* s_i = reinterpret_cast<int*>(s_f + M * kWaves + M);           // [M][16] partial sum(q)
+    float* s_ss = reinterpret_cast<float*>(s_i + M * kWaves);          // [16] partial sums of squares (norm form, M = 1)
 
     // first batch of weight tiles goes in flight before anything else
     uint4 w[kInFlight];
@@ -87,7 +88,24 @@ __global__ __launch_bounds__(kThreads, 8) void decode_kernel(BL_FIRST_WG_PARAMS,
                 // half of the weight tiles go in flight behind the activations (loads retire in order, so the
                 // quantizer's wait for x leaves them outstanding); the other half follows the quantizer, which
                 // keeps its register footprint small
-                load_part(ks, 0, kInFlight / 2);
+                bool folded = false;
+                if constexpr (!XBF16) {
+                    if (p.gamma && tid < holders) {   // uniform per wave: RMSNorm folded into the quantizer
+                        const Raw8<false> g0 = load_raw8<false>(p.gamma, h0 ? k0 : 0), g1 = load_raw8<false>(p.gamma, h1 ? k1 : 0);
+                        Raw8<false> d0 = g0, d1 = g1;
+                        if (p.delta) {
+                            d0 = load_raw8<false>(p.delta, h0 ? k0 : 0);
+                            d1 = load_raw8<false>(p.delta, h1 ? k1 : 0);
+                        }
+                        load_part(ks, 0, kInFlight / 2);
+                        folded = true;
+                        float ss = norm_fold(r0, r1, g0, g1, d0, d1, h0, h1, k0, k1, p.delta != nullptr,
+                                             wg == 0 ? p.h_out : nullptr);
+                        ss = wave_sum_f(ss);
+                        if (lane == 0) s_ss[wave] = ss;
+                    }
+                }
+                if (!folded) load_part(ks, 0, kInFlight / 2);
                 quantize_row_from_regs<XBF16>(r0, r1, h0, h1, k0, k1, holders, p.K, Kp, lds_q, s_f, s_i, tid, lane, wave);
                 load_part(ks, kInFlight / 2, kInFlight);
             }
@@ -144,6 +162,9 @@ __global__ __launch_bounds__(kThreads, 8) void decode_kernel(BL_FIRST_WG_PARAMS,
 #pragma unroll
             for (int w16 = 0; w16 < kWaves; ++w16) qsum += s_i[m * kWaves + w16];
             scale = s_f[M * kWaves + m];
+            if constexpr (M == 1 && !XBF16) {
+                if (p.gamma) scale *= norm_scalar(s_ss, row_threads(p.K) / kWave, p.K, p.eps);   // uniform
+            }
             if (wg == 0 && wave == m % G && lane == 0) {
                 if (p.a_scale_out) p.a_scale_out[m] = scale;
                 if (p.q_sum_out) p.q_sum_out[m] = qsum;
@@ -372,7 +393,7 @@ void set_decode_stage(int v) { g_force_stage = v; }
 // LDS bytes of one launch; q_in_lds: the quantized activations live in LDS (fused, or staged copy)
 static size_t lds_bytes_for(int M, int64_t max_Kp, bool q_in_lds) {
     const size_t red = use_mfma(M) ? (size_t)kMfmaRedBytes : (size_t)kWaves * M * kWave * 4;
-    return (size_t)(q_in_lds ? M * max_Kp : 0) + red + (size_t)(2 * M * kWaves + M) * 4;
+    return (size_t)(q_in_lds ? M * max_Kp : 0) + red + (size_t)(2 * M * kWaves + M + kWaves) * 4;
 }
 
 size_t decode_lds_bytes(int M, int64_t max_Kp, bool fused) { return lds_bytes_for(M, max_Kp, fused); }

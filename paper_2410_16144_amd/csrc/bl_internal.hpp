@@ -46,6 +46,12 @@ struct DecodeProblem {
     int32_t        wlog2;        // log2(waves that share one row block)
     int32_t        first_wg;     // first workgroup of this problem in the grid
     int32_t        chunk;        // balanced form: tiles per workgroup
+    // fused form with RMSNorm (one token, fp32 x, K <= 16384): activations = quantize((x + delta) * gamma); the norm's
+    // scalar 1 / sqrt(mean((x + delta)^2) + eps) multiplies the activation scale instead of every element
+    const float*   gamma;        // [K]; null: no norm
+    const float*   delta;        // optional [K]
+    float*         h_out;        // optional [K]: receives x + delta (written by the problem's first workgroup)
+    float          eps;
 };
 
 struct DecodeBatch {

@@ -4,15 +4,14 @@ include/bitlinear_decoder.h plus the launch sequence of a layer.
 Every arithmetic step runs in the library's kernels; this module owns buffers (torch tensors) and
 the order of the launches:
 
-    norm_quant(RESIDUAL, g_in)   h += delta of the previous layer; q1 = quantize(rmsnorm(h))
-    gemv_batch(q, k, v)          three products that share q1
+    decode_norm_batch(q, k, v)   h' = h + delta of the previous layer; the three products of rmsnorm(h', g_in)
     attn_decode                  rotary embedding, cache append, attention (two launches)
-    norm_quant(PLAIN, g_attn)    q2 = quantize(rmsnorm(attention output))
-    gemv_batch(o)
-    norm_quant(RESIDUAL, g_post) h += o; q3 = quantize(rmsnorm(h))
-    gemv_batch(gate, up)         two products that share q3
+    decode_norm_batch(o)         the product of rmsnorm(attention output, g_attn)
+    decode_norm_batch(gate, up)  h'' = h' + o; the two products of rmsnorm(h'', g_post)
     norm_quant(GATED, g_ffn)     q4 = quantize(rmsnorm(silu(gate) * up))
     gemv_batch(down)             -> delta for the next layer
+
+(7 launches; rows too long for the folded form take bl_norm_quant + bl_gemv_batch instead: 10 launches.)
 
 Shapes follow Appendix A of arXiv 2410.16144 (hidden size, intermediate size, layers, heads); the block
 itself is the LLaMA-like one of BitNet b1.58, which the paper does not spell out.
@@ -85,6 +84,46 @@ class Attention:
         return self.out
 
 
+class NormDecodeGroup:
+    """A prepared bl_decode_norm_batch launch: RMSNorm (with an optional residual add) folded into the quantizer of
+    the products that consume the normalised row.  weights share x / delta / gamma; h_out receives x + delta."""
+
+    def __init__(self, weights, x: torch.Tensor, gamma: torch.Tensor, eps: float = EPS, delta: Optional[torch.Tensor] = None,
+                 h_out: Optional[torch.Tensor] = None, want_acc: bool = False, want_quant: bool = False, use_workspace=True):
+        assert 1 <= len(weights) <= B.BL_MAX_BATCH
+        dev = x.device
+        K = weights[0].K
+        for t in (x, delta, h_out, gamma):
+            assert t is None or (t.dtype == torch.float32 and t.numel() == K and t.is_contiguous())
+        assert all(w.K == K for w in weights)
+        self.workspace_ptr = ops._workspace_ptr(use_workspace, dev)
+        self.outs = [torch.empty((1, w.N), dtype=torch.float32, device=dev) for w in weights]
+        self.accs = [torch.empty((1, w.N), dtype=torch.int32, device=dev) for w in weights] if want_acc else None
+        self.quants = [ops.alloc_quant(1, K, dev) for _ in weights] if want_quant else None
+        self._keep = (weights, x, gamma, delta, h_out)
+        ptr = lambda t: t.data_ptr() if t is not None else 0
+        self.items = B.make_decode_norm_items(
+            (x.data_ptr(), ptr(delta), ptr(h_out) if i == 0 else 0, gamma.data_ptr(), eps, w.blob.data_ptr(), w.desc,
+             self.outs[i].data_ptr(), self.accs[i].data_ptr() if want_acc else 0,
+             self.quants[i].q.data_ptr() if want_quant else 0, self.quants[i].a_scale.data_ptr() if want_quant else 0,
+             self.quants[i].q_sum.data_ptr() if want_quant else 0)
+            for i, w in enumerate(weights))
+
+    def launch(self):
+        B.bl_decode_norm_batch(self.items, self.workspace_ptr, _stream())
+        return self.outs
+
+
+def can_fold_norm(K: int) -> bool:
+    return K % 8 == 0 and K <= B.BL_DECODE_NORM_MAX_K
+
+
+# Folding the norm into the product's quantizer saves a launch but makes every workgroup read three fp32 rows and
+# quantize for itself.  Measured on MI355X (Appendix-A shapes, whole layers): a gain of 1.5-2.7 us per layer up to
+# hidden size 1536, even at 2048, a loss beyond (7B: +7 us, 100B: +24 us per layer).
+FOLD_NORM_MAX_HIDDEN = 1536
+
+
 @dataclass
 class LayerWeights:
     proj: Dict[str, ops.PackedWeight]     # 'q','k','v','o','gate','up','down'
@@ -95,33 +134,57 @@ class LayerWeights:
 
 
 class DecoderLayer:
-    """Buffers and prepared launches of one layer for one token (M = 1)."""
+    """Buffers and prepared launches of one layer for one token (M = 1).
 
-    def __init__(self, w: LayerWeights, n_heads: int, max_pos: int, h: torch.Tensor, delta_in: Optional[torch.Tensor],
-                 pos: torch.Tensor, table: torch.Tensor, eps: float = EPS, use_workspace=True):
-        dev = h.device
-        hidden = int(h.shape[1])
+    The residual stream alternates between two buffers: a launch that folds "h += delta" into its quantizer reads
+    h and delta in every workgroup while one workgroup writes the sum, so the sum goes to the other buffer.
+    h_in: where this layer finds the stream (delta_in, if given, still to be added); h_out: where it leaves it
+    (delta_out still to be added by whoever comes next)."""
+
+    def __init__(self, w: LayerWeights, n_heads: int, max_pos: int, h_in: torch.Tensor, h_alt: torch.Tensor,
+                 delta_in: Optional[torch.Tensor], pos: torch.Tensor, table: torch.Tensor, eps: float = EPS,
+                 use_workspace=True, fold_norm: Optional[bool] = None):
+        dev = h_in.device
+        hidden = int(h_in.shape[1])
         ffn = w.proj["gate"].N
-        assert h.shape == (1, hidden) and hidden % n_heads == 0
-        self.w, self.h, self.delta_in, self.eps = w, h, delta_in, eps
-        self.q1, self.q2, self.q3 = (ops.alloc_quant(1, hidden, dev) for _ in range(3))
+        assert h_in.shape == (1, hidden) and h_alt.shape == (1, hidden) and hidden % n_heads == 0
+        self.w, self.eps, self.delta_in = w, eps, delta_in
+        self.fold = (can_fold_norm(hidden) and hidden <= FOLD_NORM_MAX_HIDDEN) if fold_norm is None else fold_norm
         self.q4 = ops.alloc_quant(1, ffn, dev)
-        self.qkv = ops.GemvGroup([w.proj["q"], w.proj["k"], w.proj["v"]], [self.q1] * 3, use_workspace=use_workspace)
-        self.attn = Attention(n_heads, hidden // n_heads, max_pos, *self.qkv.outs, pos, table)
-        self.o = ops.GemvGroup([w.proj["o"]], [self.q2], use_workspace=use_workspace)
-        self.gate_up = ops.GemvGroup([w.proj["gate"], w.proj["up"]], [self.q3] * 2, use_workspace=use_workspace)
+        if self.fold:
+            h_mid = h_alt if delta_in is not None else h_in          # the stream after "h += delta_in"
+            self.h_out = h_in if h_mid is h_alt else h_alt           # ... and after "h += o"
+            self.qkv = NormDecodeGroup([w.proj[n] for n in "qkv"], h_in, w.g_in, eps, delta=delta_in,
+                                       h_out=h_mid if delta_in is not None else None, use_workspace=use_workspace)
+            self.attn = Attention(n_heads, hidden // n_heads, max_pos, *self.qkv.outs, pos, table)
+            self.o = NormDecodeGroup([w.proj["o"]], self.attn.out, w.g_attn, eps, use_workspace=use_workspace)
+            self.gate_up = NormDecodeGroup([w.proj["gate"], w.proj["up"]], h_mid, w.g_post, eps, delta=self.o.outs[0],
+                                           h_out=self.h_out, use_workspace=use_workspace)
+        else:
+            self.h, self.h_out = h_in, h_in                           # separate norm launches update the stream in place
+            self.q1, self.q2, self.q3 = (ops.alloc_quant(1, hidden, dev) for _ in range(3))
+            self.qkv = ops.GemvGroup([w.proj[n] for n in "qkv"], [self.q1] * 3, use_workspace=use_workspace)
+            self.attn = Attention(n_heads, hidden // n_heads, max_pos, *self.qkv.outs, pos, table)
+            self.o = ops.GemvGroup([w.proj["o"]], [self.q2], use_workspace=use_workspace)
+            self.gate_up = ops.GemvGroup([w.proj["gate"], w.proj["up"]], [self.q3] * 2, use_workspace=use_workspace)
         self.down = ops.GemvGroup([w.proj["down"]], [self.q4], use_workspace=use_workspace)
         self.delta_out = self.down.outs[0]
 
     def launch(self):
         w = self.w
-        norm_quant(B.BL_NORM_RESIDUAL, w.g_in, self.eps, a=self.delta_in, h=self.h, out=self.q1)
-        self.qkv.launch()
-        self.attn.launch()
-        norm_quant(B.BL_NORM_PLAIN, w.g_attn, self.eps, a=self.attn.out, out=self.q2)
-        self.o.launch()
-        norm_quant(B.BL_NORM_RESIDUAL, w.g_post, self.eps, a=self.o.outs[0], h=self.h, out=self.q3)
-        self.gate_up.launch()
+        if self.fold:      # 7 launches: three products with the norm in their quantizer, attention (2), gate, down
+            self.qkv.launch()
+            self.attn.launch()
+            self.o.launch()
+            self.gate_up.launch()
+        else:              # 10 launches
+            norm_quant(B.BL_NORM_RESIDUAL, w.g_in, self.eps, a=self.delta_in, h=self.h, out=self.q1)
+            self.qkv.launch()
+            self.attn.launch()
+            norm_quant(B.BL_NORM_PLAIN, w.g_attn, self.eps, a=self.attn.out, out=self.q2)
+            self.o.launch()
+            norm_quant(B.BL_NORM_RESIDUAL, w.g_post, self.eps, a=self.o.outs[0], h=self.h, out=self.q3)
+            self.gate_up.launch()
         norm_quant(B.BL_NORM_GATED, w.g_ffn, self.eps, a=self.gate_up.outs[0], b=self.gate_up.outs[1], out=self.q4)
         self.down.launch()
         return self.delta_out
@@ -132,20 +195,23 @@ class DecoderStack:
     hidden state comes out; the position lives on the device and advances by one per step."""
 
     def __init__(self, layers: List[LayerWeights], g_final: torch.Tensor, n_heads: int, max_pos: int, device,
-                 eps: float = EPS, theta: float = ROPE_THETA, use_workspace=True):
+                 eps: float = EPS, theta: float = ROPE_THETA, use_workspace=True, fold_norm: Optional[bool] = None):
         hidden = layers[0].proj["q"].K
         self.hidden, self.n_heads, self.max_pos, self.eps = hidden, n_heads, max_pos, eps
-        self.h = torch.zeros((1, hidden), dtype=torch.float32, device=device)
+        self.h = torch.zeros((1, hidden), dtype=torch.float32, device=device)       # the caller writes the token's input here
+        self.h_alt = torch.zeros((1, hidden), dtype=torch.float32, device=device)
         self.y = torch.empty((1, hidden), dtype=torch.float32, device=device)
         self.pos = torch.zeros((1,), dtype=torch.int32, device=device)
         self.table = rope_table(hidden // n_heads, max_pos, device, theta)
         self.g_final = g_final
         self.layers: List[DecoderLayer] = []
-        delta = None
+        delta, h_in = None, self.h
         for w in layers:
-            layer = DecoderLayer(w, n_heads, max_pos, self.h, delta, self.pos, self.table, eps, use_workspace)
+            h_alt = self.h_alt if h_in is self.h else self.h
+            layer = DecoderLayer(w, n_heads, max_pos, h_in, h_alt, delta, self.pos, self.table, eps, use_workspace, fold_norm)
             self.layers.append(layer)
-            delta = layer.delta_out
+            delta, h_in = layer.delta_out, layer.h_out
+        self.h_last = h_in
         self.graph = None
 
     def launch(self):
@@ -153,7 +219,7 @@ class DecoderStack:
         norm (-> self.y), the position's increment."""
         for layer in self.layers:
             layer.launch()
-        norm_quant(B.BL_NORM_RESIDUAL, self.g_final, self.eps, a=self.layers[-1].delta_out, h=self.h, y=self.y,
+        norm_quant(B.BL_NORM_RESIDUAL, self.g_final, self.eps, a=self.layers[-1].delta_out, h=self.h_last, y=self.y,
                    quantize=False)
         B.bl_pos_advance(self.pos.data_ptr(), _stream())
         return self.y

@@ -32,6 +32,7 @@ def test_struct_layout_matches_header():
     assert ctypes.sizeof(B.DecodeItem) == 80 and B.DecodeItem.packed_dev.offset == 24
     assert ctypes.sizeof(B.NormQuantArgs) == 96 and B.NormQuantArgs.eps.offset == 56 and B.NormQuantArgs.q_dev.offset == 64
     assert ctypes.sizeof(B.AttnArgs) == 88 and B.AttnArgs.n_heads.offset == 72
+    assert ctypes.sizeof(B.DecodeNormItem) == 96 and B.DecodeNormItem.packed_dev.offset == 40
 
 
 def test_padding_and_descriptor():
@@ -223,3 +224,25 @@ def test_decoder_block_validation():
     assert attn(9, 0) == B.BL_ERR_SHAPE and attn(10, 62) == B.BL_ERR_SHAPE and attn(11, 0) == B.BL_ERR_SHAPE
     assert attn(5, P + 8) == B.BL_ERR_ALIGN and attn(4, P + 4) == B.BL_ERR_ALIGN and attn(0, P + 1) == B.BL_ERR_ALIGN
     assert _st(B.bl_pos_advance, 0) == B.BL_ERR_NULL and _st(B.bl_pos_advance, P + 2) == B.BL_ERR_ALIGN
+
+
+def test_decode_norm_batch_validation():
+    P = 0x10000
+    d = B.bl_packed_desc_init(128, 256, 0.5)
+    ok = [P, P, P + 0x1000, P, 1e-5, P, d, P, 0, 0, 0, 0]
+    def call(i=None, v=None, desc=None, count_items=1, ws=0):
+        a = list(ok)
+        if i is not None:
+            a[i] = v
+        if desc is not None:
+            a[6] = desc
+        return _st(B.bl_decode_norm_batch, B.make_decode_norm_items([tuple(a)] * count_items), ws)
+    for i in (0, 3, 5, 7):
+        assert call(i, 0) == B.BL_ERR_NULL
+    assert call(2, P) == B.BL_ERR_SHAPE                                   # h_out on top of x (and of delta)
+    assert call(desc=B.bl_packed_desc_init(128, 100, 0.5)) == B.BL_ERR_SHAPE            # K not a multiple of 8
+    assert call(desc=B.bl_packed_desc_init(128, B.BL_DECODE_NORM_MAX_K + 8, 0.5)) == B.BL_ERR_SHAPE
+    assert call(0, P + 8) == B.BL_ERR_ALIGN and call(3, P + 4) == B.BL_ERR_ALIGN and call(1, P + 4) == B.BL_ERR_ALIGN
+    assert call(count_items=9) == B.BL_ERR_COUNT
+    assert call(ws=P + 16) == B.BL_ERR_ALIGN
+    assert call(desc=B.bl_tl2_desc_init(128, 256, 0.5)) == B.BL_ERR_LAYOUT

@@ -273,7 +273,8 @@ def test_layer_stage_by_stage(dev, mods, hidden, ffn, n_heads, pos):
     h0, delta = synth.activations(r, 1, hidden), synth.activations(r, 1, hidden)
     h_t, pos_t = _t(h0, dev), torch.full((1,), pos, dtype=torch.int32, device=dev)
     table = dec.rope_table(hidden // n_heads, max_pos, dev)
-    layer = dec.DecoderLayer(_to_device([l], dev, dec, ops)[0], n_heads, max_pos, h_t, _t(delta, dev), pos_t, table)
+    layer = dec.DecoderLayer(_to_device([l], dev, dec, ops)[0], n_heads, max_pos, h_t, torch.empty_like(h_t), _t(delta, dev),
+                             pos_t, table, fold_norm=False)
     kc = _bf16(r.standard_normal((max_pos, hidden)))
     vc = _bf16(r.standard_normal((max_pos, hidden)))
     layer.attn.k_cache.copy_(_bits_as_bf16_tensor(synth.to_bf16_bits(kc), dev))
@@ -320,16 +321,81 @@ def test_layer_stage_by_stage(dev, mods, hidden, ffn, n_heads, pos):
     np.testing.assert_allclose(layer.delta_out.cpu().numpy()[0], _product_of(layer.q4, ffn, l["down"], l["s_down"]), rtol=1e-6)
 
 
-@pytest.mark.parametrize("hidden,ffn,n_heads,n_layers,use_graph", [(768, 3072, 12, 2, False), (1536, 4096, 16, 2, True),
-                                                                  (200, 328, 5, 3, True)])
-def test_token_loop_against_oracle(dev, mods, hidden, ffn, n_heads, n_layers, use_graph):
+# ------------------------------------------------------------------------------------------ norm folded into the product
+
+def _run_norm_decode(dev, mods, r, K, Ns, with_delta, use_workspace):
+    B, dec, ops = mods
+    ws = [synth.ternary_weights(r, N, K) for N in Ns]
+    scales = [float(synth.draw_w_scale(r)) for _ in Ns]
+    x = synth.activations(r, 1, K, outlier_frac=0.01)
+    delta = synth.activations(r, 1, K) if with_delta else None
+    gamma = r.uniform(0.5, 1.5, K).astype(np.float32)
+    pws = [ops.pack_ternary(_t(w, dev), s) for w, s in zip(ws, scales)]
+    h_out = torch.full((1, K), -7.0, device=dev) if with_delta else None
+    grp = dec.NormDecodeGroup(pws, _t(x, dev), _t(gamma, dev), 1e-5, delta=_t(delta, dev) if with_delta else None,
+                              h_out=h_out, want_acc=True, want_quant=True, use_workspace=use_workspace)
+    outs = [o.cpu().numpy()[0] for o in grp.launch()]
+    torch.cuda.synchronize()
+    return ws, scales, x, delta, gamma, grp, outs, h_out
+
+
+@pytest.mark.parametrize("K,Ns,with_delta,use_workspace", [
+    (200, (70,), True, False), (768, (768, 768, 768), True, True), (1536, (1536,), False, True),
+    (3200, (3200, 3200, 3200), True, True), (4096, (11008, 11008), True, True), (8192, (8192, 8192, 8192), True, True),
+    (8192, (8192,), False, False), (16384, (640,), True, True), (4096, (4096,), False, True), (8, (3,), True, False)])
+def test_decode_norm_batch_parity(dev, mods, K, Ns, with_delta, use_workspace):
+    """RMSNorm folded into the fused quantizer: codes, scale and sums against the oracle's quantizer on
+    z = (x + delta) * gamma formed with the same two fp32 operations; the scale carries the norm's scalar; the
+    integer sums are exact; against the textbook order (normalise, then quantize) codes differ at ties only."""
+    B, dec, ops = mods
+    ws, scales, x, delta, gamma, grp, outs, h_out = _run_norm_decode(dev, mods, _rng(71000 + K + len(Ns)), K, Ns, with_delta, use_workspace)
+    xp = x + delta if with_delta else x                                   # one fp32 addition
+    if with_delta:
+        np.testing.assert_array_equal(h_out.cpu().numpy(), xp)
+    z = xp * gamma                                                        # one fp32 product
+    q, a_z, q_sum = oracle.quant_act(z)
+    r64 = 1.0 / np.sqrt(np.mean(xp.astype(np.float64) ** 2) + 1e-5)
+    y64 = D.rmsnorm(xp[0].astype(np.float64), gamma, 1e-5)
+    for i, (w, s) in enumerate(zip(ws, scales)):
+        qa = grp.quants[i]
+        np.testing.assert_array_equal(qa.q.cpu().numpy()[:, :K], q)
+        assert not qa.q.cpu().numpy()[:, K:].any()
+        np.testing.assert_array_equal(qa.q_sum.cpu().numpy(), q_sum)
+        a_got = float(qa.a_scale[0])
+        assert abs(a_got - float(a_z[0]) * r64) <= 3e-6 * float(a_z[0]) * r64      # fp32 tree sum of K squares, root, division
+        acc = oracle.matmul_i32(q, w)
+        np.testing.assert_array_equal(grp.accs[i].cpu().numpy(), acc)
+        np.testing.assert_allclose(outs[i], oracle.dequant(acc, np.float32(s), np.float32([a_got]))[0], rtol=1e-6)
+        _codes_close(qa.q.cpu().numpy(), y64, K)
+        q_txt, a_txt, _ = oracle.quant_act(y64.astype(np.float32)[None, :])
+        if np.array_equal(q_txt, q):                                      # no tie fell the other way: the textbook product
+            want = oracle.dequant(acc, np.float32(s), a_txt)[0]
+            assert np.abs(outs[i] - want).max() <= 5e-6 * np.abs(want).max()
+
+
+def test_decode_norm_batch_zero_row(dev, mods):
+    B, dec, ops = mods
+    K, N = 1024, 300
+    pw = ops.pack_ternary(_t(synth.ternary_weights(_rng(3), N, K), dev), 0.02)
+    grp = dec.NormDecodeGroup([pw], torch.zeros((1, K), device=dev), torch.ones(K, device=dev), want_quant=True)
+    out = grp.launch()[0]
+    torch.cuda.synchronize()
+    assert not out.any() and float(grp.quants[0].a_scale[0]) == 0.0 and not grp.quants[0].q.any()
+
+
+@pytest.mark.parametrize("hidden,ffn,n_heads,n_layers,use_graph,fold", [
+    (768, 3072, 12, 2, False, True), (1536, 4096, 16, 2, True, True), (200, 328, 5, 3, True, True),
+    (768, 3072, 12, 2, False, False), (1536, 4096, 16, 3, True, False)])
+def test_token_loop_against_oracle(dev, mods, hidden, ffn, n_heads, n_layers, use_graph, fold):
     """Tokens through a small stack (125M- and 700M-shape layers of Appendix A): the final-normalised hidden state and
     the caches against the oracle's layer step, token after token; the captured graph gives the eager bits."""
     B, dec, ops = mods
     max_pos, n_tokens = 8, 5
     layers, g_final = _make_layers(61000 + hidden, hidden, ffn, n_layers)
-    stack = dec.DecoderStack(_to_device(layers, dev, dec, ops), _t(g_final, dev), n_heads, max_pos, dev)
-    eager = dec.DecoderStack(_to_device(layers, dev, dec, ops), _t(g_final, dev), n_heads, max_pos, dev) if use_graph else None
+    stack = dec.DecoderStack(_to_device(layers, dev, dec, ops), _t(g_final, dev), n_heads, max_pos, dev, fold_norm=fold)
+    assert all(l.fold == fold for l in stack.layers)
+    eager = (dec.DecoderStack(_to_device(layers, dev, dec, ops), _t(g_final, dev), n_heads, max_pos, dev, fold_norm=fold)
+             if use_graph else None)
     if use_graph:
         stack.capture()
     r = _rng(62000 + hidden)
