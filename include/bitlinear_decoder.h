@@ -32,6 +32,7 @@ extern "C" {
 
 #define BL_NORM_MAX_K 49152     /* longest row bl_norm_quant takes (the paper's largest
                                    intermediate size, Appendix A "100B", is 45568)        */
+#define BL_NORM_SCRATCH_BYTES 256 /* per token row, for bl_norm_quant_args.scratch_dev            */
 #define BL_ATTN_MAX_HEAD_DIM 256
 #define BL_ATTN_CHUNK 64        /* cache positions per workgroup of the attention kernel  */
 
@@ -43,7 +44,7 @@ typedef enum bl_norm_mode {
 
 /*
  * One launch: for each of M token rows, form x (see bl_norm_mode), normalise
- *   y[k] = x[k] * (1 / sqrt(mean_k(x^2) + eps)) * gamma[k]
+ *   y[k] = (x[k] * gamma[k]) * r,   r = 1 / sqrt(mean_k(x^2) + eps)     (two fp32 products, in this order)
  * and quantize y exactly as bl_quant_act does (per-token absmax int8):
  *   q [M, Kp] int8, a_scale [M], q_sum [M] -- ready for bl_gemv / bl_gemv_batch / bl_gemm.
  * Fusing the three keeps the row in registers: x is read once and only q leaves the chip.
@@ -55,6 +56,11 @@ typedef enum bl_norm_mode {
  *                        quantized (the final norm of a model).
  *   q_sum_dev            optional
  *   y_dev                optional [M, K] fp32: the normalised values before quantization
+ *   scratch_dev          optional, M * BL_NORM_SCRATCH_BYTES bytes, 8-byte aligned, contents free: with
+ *                        it, rows of 16384 elements or more are cut into slices of 2048, one workgroup
+ *                        each, in TWO launches (a single workgroup is bound by its compute unit on
+ *                        such rows); q_sum then accumulates by integer atomics.  Same results up to
+ *                        the order of the fp32 sum of squares.
  * K <= BL_NORM_MAX_K.  The sum of squares is an fp32 tree sum; y and the quantizer's decisions are
  * single IEEE operations on it, so q equals bl_quant_act of y_dev bit for bit.
  * Errors: BL_ERR_NULL, BL_ERR_SHAPE (M < 1, K outside 1..BL_NORM_MAX_K, Kp < K or not a multiple
@@ -74,6 +80,7 @@ typedef struct bl_norm_quant_args {
     float       *a_scale_dev;
     int32_t     *q_sum_dev;
     float       *y_dev;
+    void        *scratch_dev;
 } bl_norm_quant_args;
 
 bl_status bl_norm_quant(const bl_norm_quant_args *args, void *stream);

@@ -340,7 +340,8 @@ bl_status bl_norm_quant(const bl_norm_quant_args* a, void* stream) {
     if (a->M < 1 || a->K < 1 || a->K > BL_NORM_MAX_K) return BL_ERR_SHAPE;
     if (quantize && (a->Kp < a->K || a->Kp % 4 != 0 || a->Kp > BL_MAX_K)) return BL_ERR_SHAPE;
     if (!aligned(a->a_dev, 4) || !aligned(a->b_dev, 4) || !aligned(a->h_dev, 4) || !aligned(a->gamma_dev, 4) ||
-        !aligned(a->q_dev, 4) || !aligned(a->a_scale_dev, 4) || !aligned(a->q_sum_dev, 4) || !aligned(a->y_dev, 4))
+        !aligned(a->q_dev, 4) || !aligned(a->a_scale_dev, 4) || !aligned(a->q_sum_dev, 4) || !aligned(a->y_dev, 4) ||
+        !aligned(a->scratch_dev, 8))
         return BL_ERR_ALIGN;
     drop_stale_hip_error();
     return hip_status(bl::launch_norm_quant(*a, static_cast<hipStream_t>(stream)));

@@ -37,6 +37,7 @@ struct NormArgs {
     float*       a_scale;
     int32_t*     q_sum;
     float*       y;
+    float2*      scratch;   // wide form: per row kWideMaxSlices x (sum of squares, absmax of x * gamma)
     int32_t      K, Kp;
     float        eps;
 };
@@ -129,7 +130,7 @@ __global__ __launch_bounds__(kNormThreads) void norm_quant_kernel(const NormArgs
         }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            x[i][j] = (x[i][j] * r) * g[j];
+            x[i][j] = (x[i][j] * g[j]) * r;
             amax = fmaxf(amax, fabsf(x[i][j]));
         }
         if (p.y) store4<VEC>(p.y + row, k, K, x[i]);
@@ -189,6 +190,131 @@ hipError_t launch_norm_mode(const NormArgs& p, int M, bool vec, hipStream_t s) {
     return hipErrorInvalidValue;
 }
 static_assert(BL_NORM_MAX_K == 12 * kNormThreads * 4, "the longest row fills 12 vectors per thread");
+
+// Long rows (K >= kWideMinK, with scratch memory from the caller): one workgroup is bound by its compute unit's ALU on
+// such a row (45568 gated elements: 20 us), so the row is cut into slices of 2048 elements, one workgroup each, and the
+// work into two launches with the grid-wide reductions between them:
+//   1. x (residual add stored, or the gate), z = x * gamma; per slice sum(x^2) and max|z| to scratch; sum(q) zeroed;
+//   2. every workgroup adds up the slices' figures in the same order (so all get the same bits): r, and max|y| =
+//      max|z| * r -- rounding is monotone and r > 0, so the largest |z| gives the largest |z * r|, which is why y is
+//      defined as (x * gamma) * r in that order; then y and the codes of its slice; sum(q) by integer atomics.
+constexpr int kWideThreads = 256;
+constexpr int kWideSlice = kWideThreads * 8;
+constexpr int kWideMinK = 16384;
+constexpr int kWideMaxSlices = BL_NORM_MAX_K / kWideSlice;
+static_assert(kWideMaxSlices * sizeof(float2) <= BL_NORM_SCRATCH_BYTES, "a row's partial figures fit its scratch");
+
+template <int MODE, bool VEC>
+__device__ __forceinline__ void wide_inputs(const NormArgs& p, int64_t row, int k, int K, bool second_pass, float (&x)[4]) {
+    if constexpr (MODE == BL_NORM_PLAIN) {
+        load4<VEC>(p.a + row, k, K, x);
+    } else if constexpr (MODE == BL_NORM_RESIDUAL) {
+        load4<VEC>(p.h + row, k, K, x);
+        if (p.a && !second_pass) {     // the first launch adds and stores; the second finds the sum in h
+            float d[4];
+            load4<VEC>(p.a + row, k, K, d);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) x[j] += d[j];
+            store4<VEC>(p.h + row, k, K, x);
+        }
+    } else {
+        float g[4], u[4];
+        load4<VEC>(p.a + row, k, K, g);
+        load4<VEC>(p.b + row, k, K, u);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) x[j] = silu(g[j]) * u[j];
+    }
+}
+
+template <int MODE, bool VEC>
+__global__ __launch_bounds__(kWideThreads) void norm_wide_stats_kernel(const NormArgs p) {
+    __shared__ float s_ss[kWideThreads / kWave], s_max[kWideThreads / kWave];
+    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+    const int K = p.K, slice = blockIdx.x;
+    const int64_t row = (int64_t)blockIdx.y * K;
+    float ss = 0.0f, amax = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int k = slice * kWideSlice + (tid + i * kWideThreads) * 4;
+        float x[4], g[4];
+        load4<VEC>(p.gamma, k, K, g);
+        wide_inputs<MODE, VEC>(p, row, k, K, false, x);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            ss += x[j] * x[j];
+            amax = fmaxf(amax, fabsf(x[j] * g[j]));
+        }
+    }
+    ss = wave_sum_f(ss);
+    amax = wave_max(amax);
+    if (lane == 0) { s_ss[wave] = ss; s_max[wave] = amax; }
+    __syncthreads();
+    if (tid == 0) {
+        static_assert(kWideThreads / kWave == 4, "four partial figures");
+        p.scratch[(int64_t)blockIdx.y * kWideMaxSlices + slice] =
+            make_float2((s_ss[0] + s_ss[1]) + (s_ss[2] + s_ss[3]), fmaxf(fmaxf(s_max[0], s_max[1]), fmaxf(s_max[2], s_max[3])));
+        if (slice == 0 && p.q_sum) p.q_sum[blockIdx.y] = 0;
+    }
+}
+
+template <int MODE, bool VEC>
+__global__ __launch_bounds__(kWideThreads) void norm_wide_quant_kernel(const NormArgs p) {
+    __shared__ int s_sum[kWideThreads / kWave];
+    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+    const int K = p.K, slice = blockIdx.x, slices = gridDim.x;
+    const int64_t row = (int64_t)blockIdx.y * K;
+    const float2* part = p.scratch + (int64_t)blockIdx.y * kWideMaxSlices;
+    float total = 0.0f, amax_z = 0.0f;
+    for (int g = 0; g < slices; ++g) {      // the same order in every workgroup
+        const float2 f = part[g];
+        total += f.x;
+        amax_z = fmaxf(amax_z, f.y);
+    }
+    const float r = 1.0f / sqrtf(total / (float)K + p.eps);
+    float inv, scale;
+    quant_scales(amax_z * r, inv, scale);
+    int8_t* qrow = p.q ? p.q + (int64_t)blockIdx.y * p.Kp : nullptr;
+    int sum = 0;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int k = slice * kWideSlice + (tid + i * kWideThreads) * 4;
+        float x[4], g[4];
+        load4<VEC>(p.gamma, k, K, g);
+        wide_inputs<MODE, VEC>(p, row, k, K, true, x);
+        uint32_t word = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            x[j] = (x[j] * g[j]) * r;
+            const int v = quant_one(x[j], inv);
+            sum += v;
+            word |= (uint32_t)(v & 0xff) << (8 * j);
+        }
+        if (p.y) store4<VEC>(p.y + row, k, K, x);
+        if (qrow && k < K) *reinterpret_cast<uint32_t*>(qrow + k) = word;
+    }
+    if (!qrow) return;   // uniform
+    if (slice == slices - 1)
+        for (int k = (K + 3) / 4 * 4 + tid * 4; k < p.Kp; k += kWideThreads * 4) *reinterpret_cast<uint32_t*>(qrow + k) = 0;
+    sum = wave_sum(sum);
+    if (lane == 0) s_sum[wave] = sum;
+    __syncthreads();
+    if (tid == 0) {
+        if (p.q_sum) atomicAdd(p.q_sum + blockIdx.y, (s_sum[0] + s_sum[1]) + (s_sum[2] + s_sum[3]));
+        if (slice == 0) p.a_scale[blockIdx.y] = scale;
+    }
+}
+
+template <int MODE>
+hipError_t launch_norm_wide(const NormArgs& p, int M, bool vec, hipStream_t s) {
+    const dim3 grid((unsigned)((p.K + kWideSlice - 1) / kWideSlice), (unsigned)M), block(kWideThreads);
+    if (vec) norm_wide_stats_kernel<MODE, true><<<grid, block, 0, s>>>(p);
+    else norm_wide_stats_kernel<MODE, false><<<grid, block, 0, s>>>(p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (vec) norm_wide_quant_kernel<MODE, true><<<grid, block, 0, s>>>(p);
+    else norm_wide_quant_kernel<MODE, false><<<grid, block, 0, s>>>(p);
+    return hipGetLastError();
+}
 
 // ---------------------------------------------------------------------------------------------------------------
 // Rotary table
@@ -418,8 +544,16 @@ hipError_t launch_norm_quant(const bl_norm_quant_args& a, hipStream_t s) {
     p.a = a.a_dev; p.b = a.b_dev; p.h = a.h_dev; p.gamma = a.gamma_dev;
     p.q = a.q_dev; p.a_scale = a.a_scale_dev; p.q_sum = a.q_sum_dev; p.y = a.y_dev;
     p.K = (int32_t)a.K; p.Kp = (int32_t)a.Kp; p.eps = a.eps;
+    p.scratch = static_cast<float2*>(a.scratch_dev);
     auto ok16 = [](const void* ptr) { return (reinterpret_cast<uintptr_t>(ptr) & 15) == 0; };
     const bool vec = a.K % 4 == 0 && ok16(a.a_dev) && ok16(a.b_dev) && ok16(a.h_dev) && ok16(a.gamma_dev) && ok16(a.y_dev);
+    if (a.scratch_dev && a.K >= kWideMinK && a.M <= 65535) {
+        switch (a.mode) {
+            case BL_NORM_PLAIN: return launch_norm_wide<BL_NORM_PLAIN>(p, a.M, vec, s);
+            case BL_NORM_RESIDUAL: return launch_norm_wide<BL_NORM_RESIDUAL>(p, a.M, vec, s);
+            case BL_NORM_GATED: return launch_norm_wide<BL_NORM_GATED>(p, a.M, vec, s);
+        }
+    }
     switch (a.mode) {
         case BL_NORM_PLAIN: return launch_norm_mode<BL_NORM_PLAIN>(p, a.M, vec, s);
         case BL_NORM_RESIDUAL: return launch_norm_mode<BL_NORM_RESIDUAL>(p, a.M, vec, s);

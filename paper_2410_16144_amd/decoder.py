@@ -34,20 +34,23 @@ def _stream() -> int:
 
 def norm_quant(mode: int, gamma: torch.Tensor, eps: float = EPS, a: Optional[torch.Tensor] = None,
                b: Optional[torch.Tensor] = None, h: Optional[torch.Tensor] = None, out: Optional[ops.QuantAct] = None,
-               y: Optional[torch.Tensor] = None, quantize: bool = True):
-    """bl_norm_quant on [M,K] fp32 tensors.  Returns the QuantAct (None if quantize is False)."""
+               y: Optional[torch.Tensor] = None, quantize: bool = True, scratch: Optional[torch.Tensor] = None):
+    """bl_norm_quant on [M,K] fp32 tensors.  Returns the QuantAct (None if quantize is False).  scratch: a uint8
+    tensor of M * BL_NORM_SCRATCH_BYTES bytes lets long rows spread over several workgroups."""
     ref = h if mode == B.BL_NORM_RESIDUAL else a
     M, K = ref.shape
     for t in (a, b, h, y):
         assert t is None or (t.is_cuda and t.dtype == torch.float32 and t.shape == (M, K) and t.is_contiguous())
     assert gamma.dtype == torch.float32 and gamma.shape == (K,) and gamma.is_contiguous()
+    assert scratch is None or scratch.numel() * scratch.element_size() >= M * B.BL_NORM_SCRATCH_BYTES
     if quantize and out is None:
         out = ops.alloc_quant(M, K, ref.device)
     ptr = lambda t: t.data_ptr() if t is not None else 0
     args = B.make_norm_quant_args(
         mode, M, K, gamma.data_ptr(), eps, a_dev=ptr(a), b_dev=ptr(b), h_dev=ptr(h),
         q_dev=out.q.data_ptr() if quantize else 0, a_scale_dev=out.a_scale.data_ptr() if quantize else 0,
-        q_sum_dev=out.q_sum.data_ptr() if quantize else 0, Kp=int(out.q.shape[1]) if quantize else 0, y_dev=ptr(y))
+        q_sum_dev=out.q_sum.data_ptr() if quantize else 0, Kp=int(out.q.shape[1]) if quantize else 0, y_dev=ptr(y),
+        scratch_dev=ptr(scratch))
     B.bl_norm_quant(args, _stream())
     return out if quantize else None
 
@@ -151,6 +154,7 @@ class DecoderLayer:
         self.w, self.eps, self.delta_in = w, eps, delta_in
         self.fold = (can_fold_norm(hidden) and hidden <= FOLD_NORM_MAX_HIDDEN) if fold_norm is None else fold_norm
         self.q4 = ops.alloc_quant(1, ffn, dev)
+        self.norm_scratch = torch.empty(B.BL_NORM_SCRATCH_BYTES, dtype=torch.uint8, device=dev)
         if self.fold:
             h_mid = h_alt if delta_in is not None else h_in          # the stream after "h += delta_in"
             self.h_out = h_in if h_mid is h_alt else h_alt           # ... and after "h += o"
@@ -185,7 +189,8 @@ class DecoderLayer:
             self.o.launch()
             norm_quant(B.BL_NORM_RESIDUAL, w.g_post, self.eps, a=self.o.outs[0], h=self.h, out=self.q3)
             self.gate_up.launch()
-        norm_quant(B.BL_NORM_GATED, w.g_ffn, self.eps, a=self.gate_up.outs[0], b=self.gate_up.outs[1], out=self.q4)
+        norm_quant(B.BL_NORM_GATED, w.g_ffn, self.eps, a=self.gate_up.outs[0], b=self.gate_up.outs[1], out=self.q4,
+                   scratch=self.norm_scratch)
         self.down.launch()
         return self.delta_out
 

@@ -30,7 +30,7 @@ def test_struct_layout_matches_header():
     assert ctypes.sizeof(B.GemvItem) == 56
     assert ctypes.sizeof(B.QuantItem) == 64 and B.QuantItem.q_dev.offset == 40
     assert ctypes.sizeof(B.DecodeItem) == 80 and B.DecodeItem.packed_dev.offset == 24
-    assert ctypes.sizeof(B.NormQuantArgs) == 96 and B.NormQuantArgs.eps.offset == 56 and B.NormQuantArgs.q_dev.offset == 64
+    assert ctypes.sizeof(B.NormQuantArgs) == 104 and B.NormQuantArgs.eps.offset == 56 and B.NormQuantArgs.q_dev.offset == 64
     assert ctypes.sizeof(B.AttnArgs) == 88 and B.AttnArgs.n_heads.offset == 72
     assert ctypes.sizeof(B.DecodeNormItem) == 96 and B.DecodeNormItem.packed_dev.offset == 40
 
@@ -206,6 +206,7 @@ def test_decoder_block_validation():
     assert norm(Kp=130) == B.BL_ERR_SHAPE
     assert norm(a_dev=P + 2) == B.BL_ERR_ALIGN
     assert norm(q_dev=P + 1) == B.BL_ERR_ALIGN
+    assert norm(scratch_dev=P + 4) == B.BL_ERR_ALIGN
     assert _st(B.bl_rope_table, 0, 64, 16, 10000.0) == B.BL_ERR_NULL
     assert _st(B.bl_rope_table, P, 63, 16, 10000.0) == B.BL_ERR_SHAPE
     assert _st(B.bl_rope_table, P, 64, 0, 10000.0) == B.BL_ERR_SHAPE

@@ -46,10 +46,14 @@ def _t(a, dev):
 NORM_SHAPES = [(1, 768), (1, 3200), (1, 8640), (3, 4096), (1, 45568), (2, 67), (1, 1), (1, 1000), (5, 4100), (1, 49152)]
 
 
+WIDE_SHAPES = [(1, 16384), (1, 24576), (1, 45568), (2, 49152), (3, 16388), (1, 20001)]
+
+
 @pytest.mark.parametrize("mode", ["plain", "residual", "residual_no_delta", "gated"])
-@pytest.mark.parametrize("M,K", NORM_SHAPES)
-def test_norm_quant_parity(dev, mods, mode, M, K):
+@pytest.mark.parametrize("M,K,wide", [s + (False,) for s in NORM_SHAPES] + [s + (True,) for s in WIDE_SHAPES])
+def test_norm_quant_parity(dev, mods, mode, M, K, wide):
     B, dec, ops = mods
+    scratch = torch.empty(M * B.BL_NORM_SCRATCH_BYTES, dtype=torch.uint8, device=dev) if wide else None
     r = _rng(31000 + 7 * K + M)
     gamma = r.uniform(0.5, 1.5, K).astype(np.float32)
     a = synth.activations(r, M, K, outlier_frac=0.01)
@@ -59,18 +63,19 @@ def test_norm_quant_parity(dev, mods, mode, M, K):
     y_t = torch.empty((M, K), dtype=torch.float32, device=dev)
     qa = ops.alloc_quant(M, K, dev)
     qa.q.fill_(77)                                        # the layout's padding must be written as zero
+    qa.q_sum.fill_(12345)
     if mode == "plain":
-        dec.norm_quant(B.BL_NORM_PLAIN, _t(gamma, dev), eps, a=_t(a, dev), out=qa, y=y_t)
+        dec.norm_quant(B.BL_NORM_PLAIN, _t(gamma, dev), eps, a=_t(a, dev), out=qa, y=y_t, scratch=scratch)
         x64 = a.astype(np.float64)
     elif mode.startswith("residual"):
         h_t = _t(h, dev)
         delta = None if mode == "residual_no_delta" else _t(a, dev)
-        dec.norm_quant(B.BL_NORM_RESIDUAL, _t(gamma, dev), eps, a=delta, h=h_t, out=qa, y=y_t)
+        dec.norm_quant(B.BL_NORM_RESIDUAL, _t(gamma, dev), eps, a=delta, h=h_t, out=qa, y=y_t, scratch=scratch)
         want_h = h if delta is None else h + a            # one fp32 addition per element: exact agreement
         np.testing.assert_array_equal(h_t.cpu().numpy(), want_h)
         x64 = want_h.astype(np.float64)
     else:
-        dec.norm_quant(B.BL_NORM_GATED, _t(gamma, dev), eps, a=_t(a, dev), b=_t(b, dev), out=qa, y=y_t)
+        dec.norm_quant(B.BL_NORM_GATED, _t(gamma, dev), eps, a=_t(a, dev), b=_t(b, dev), out=qa, y=y_t, scratch=scratch)
         x64 = D.gated_ffn_input(a, b)
     torch.cuda.synchronize()
     y = y_t.cpu().numpy()
