@@ -12,6 +12,7 @@
 #include <string.h>
 
 #include "bitlinear.h"
+#include "bitlinear_decoder.h"
 
 #define HIP(call)                                                                         \
     do {                                                                                  \
@@ -176,6 +177,67 @@ int main(int argc, char **argv) {
         printf("tl2_roundtrip %d\n", memcmp(w, w_back, (size_t)(N * K)) == 0);
         print_i32("acc_tl2", acc, (size_t)N);
         printf("tl2_equals_gemv %d %d\n", memcmp(acc, acc2, (size_t)N * 4) == 0, memcmp(out, out2, (size_t)N * 4) == 0);
+    }
+
+    /* the decoder block's norm: stand-alone (norm + quantizer) and folded into the product (K % 8 == 0) */
+    {
+        float *gamma = malloc((size_t)K * 4), *gamma_dev, *y_dev, *h_out_dev;
+        for (int64_t k = 0; k < K; ++k) gamma[k] = 0.5f + (float)(lcg() % 1024) / 1024.0f;
+        HIP(hipMalloc((void **)&gamma_dev, (size_t)K * 4));
+        HIP(hipMalloc((void **)&y_dev, (size_t)K * 4));
+        HIP(hipMalloc((void **)&h_out_dev, (size_t)K * 4));
+        HIP(hipMemcpy(gamma_dev, gamma, (size_t)K * 4, hipMemcpyHostToDevice));
+        bl_norm_quant_args na;
+        memset(&na, 0, sizeof na);
+        na.mode = BL_NORM_PLAIN;
+        na.M = 1;
+        na.K = K;
+        na.Kp = Kp;
+        na.a_dev = (const float *)x_dev;
+        na.gamma_dev = gamma_dev;
+        na.eps = 1e-5f;
+        na.q_dev = q_dev;
+        na.a_scale_dev = a_scale_dev;
+        na.q_sum_dev = q_sum_dev;
+        na.y_dev = y_dev;
+        BL(bl_norm_quant(&na, NULL));
+        HIP(hipDeviceSynchronize());
+        float *y = malloc((size_t)K * 4);
+        HIP(hipMemcpy(y, y_dev, (size_t)K * 4, hipMemcpyDeviceToHost));
+        HIP(hipMemcpy(q, q_dev, (size_t)Kp, hipMemcpyDeviceToHost));
+        HIP(hipMemcpy(a_scale, a_scale_dev, 4, hipMemcpyDeviceToHost));
+        HIP(hipMemcpy(q_sum, q_sum_dev, 4, hipMemcpyDeviceToHost));
+        print_f32_bits("norm_y", y, (size_t)K);
+        printf("norm_q");
+        for (int64_t k = 0; k < Kp; ++k) printf(" %d", q[k]);
+        printf("\n");
+        print_f32_bits("norm_a_scale", a_scale, 1);
+        print_i32("norm_q_sum", q_sum, 1);
+        if (K % 8 == 0) {
+            bl_decode_norm_item ni;
+            memset(&ni, 0, sizeof ni);
+            ni.x_dev = (const float *)x_dev;
+            ni.delta_dev = (const float *)x_dev;   /* x' = 2 x */
+            ni.h_out_dev = h_out_dev;
+            ni.gamma_dev = gamma_dev;
+            ni.eps = 1e-5f;
+            ni.packed_dev = packed_dev;
+            ni.desc = &d;
+            ni.out_dev = out_dev;
+            ni.acc_dev = acc_dev;
+            ni.a_scale_dev = a_scale_dev;
+            BL(bl_decode_norm_batch(&ni, 1, ws_dev, NULL));
+            HIP(hipDeviceSynchronize());
+            HIP(hipMemcpy(acc, acc_dev, (size_t)N * 4, hipMemcpyDeviceToHost));
+            HIP(hipMemcpy(out, out_dev, (size_t)N * 4, hipMemcpyDeviceToHost));
+            HIP(hipMemcpy(a_scale, a_scale_dev, 4, hipMemcpyDeviceToHost));
+            HIP(hipMemcpy(y, h_out_dev, (size_t)K * 4, hipMemcpyDeviceToHost));
+            print_i32("fold_acc", acc, (size_t)N);
+            print_f32_bits("fold_out", out, (size_t)N);
+            print_f32_bits("fold_a_scale", a_scale, 1);
+            print_f32_bits("fold_h", y, (size_t)K);
+        }
+        printf("err_norm_null %d\n", (int)bl_norm_quant(NULL, NULL));
     }
 
     /* argument errors come back as codes, before anything is launched */

@@ -25,10 +25,11 @@ def _lcg_stream(count: int, seed: int = 20241016) -> np.ndarray:
 
 
 def _inputs(N, K, M):
-    r = _lcg_stream(N * K + M * K)
+    r = _lcg_stream(N * K + M * K + K)
     w = (r[: N * K] % 3).astype(np.int8).reshape(N, K) - 1
-    x = ((r[N * K:] % 2001).astype(np.int32) - 1000).astype(np.float32) / np.float32(256.0)
-    return w, x.reshape(M, K)
+    x = ((r[N * K: N * K + M * K] % 2001).astype(np.int32) - 1000).astype(np.float32) / np.float32(256.0)
+    gamma = np.float32(0.5) + (r[N * K + M * K:] % 1024).astype(np.float32) / np.float32(1024.0)
+    return w, x.reshape(M, K), gamma
 
 
 def _parse(text):
@@ -55,7 +56,7 @@ def test_c_program_matches_oracle(N, K, M):
     assert r.returncode == 0, r.stdout[-2000:] + r.stderr[-2000:]
     rec = _parse(r.stdout)
     assert rec["done"] == []
-    w, x = _inputs(N, K, M)
+    w, x, gamma = _inputs(N, K, M)
     ref = oracle.bitlinear(x, w, np.float32(0.03125))
     Kp, Np = -(-K // 64) * 64, -(-N // 64) * 64
     assert _ints(rec["desc"]).tolist() == [N, K, Np, Kp, Np * Kp // 4]
@@ -77,6 +78,27 @@ def test_c_program_matches_oracle(N, K, M):
     assert np.array_equal(_ints(rec["acc_tl2"]), ref["acc"][0])
     assert rec["tl2_equals_gemv"] == ["1", "1"]
     assert rec["err_m_range"] == ["3"] and rec["err_null"] == ["1"]
+    # the decoder block's norm, stand-alone: y against the fp64 formula, the codes against the oracle's quantizer on y
+    from oracle import decoder as D
+    y = _floats(rec["norm_y"])
+    want_y = D.rmsnorm(x[0].astype(np.float64), gamma, 1e-5)
+    assert np.all(np.abs(y - want_y) <= 3e-6 * np.abs(want_y).max())
+    qn, an, sn = oracle.quant_act(y[None, :])
+    got_q = _ints(rec["norm_q"])
+    assert np.array_equal(got_q[:K], qn[0]) and not got_q[K:].any()
+    assert np.array_equal(_floats(rec["norm_a_scale"]), an) and _ints(rec["norm_q_sum"]).tolist() == sn.tolist()
+    assert rec["err_norm_null"] == ["1"]
+    if K % 8 == 0:   # ... and folded into the product, on x' = x + x
+        xp = x[0] + x[0]
+        assert np.array_equal(_floats(rec["fold_h"]), xp)
+        qz, az, _ = oracle.quant_act((xp * gamma)[None, :])
+        acc = oracle.matmul_i32(qz, w)[0]
+        assert np.array_equal(_ints(rec["fold_acc"]), acc)
+        r64 = 1.0 / np.sqrt(np.mean(xp.astype(np.float64) ** 2) + 1e-5)
+        a_got = _floats(rec["fold_a_scale"])
+        assert abs(float(a_got[0]) - float(az[0]) * r64) <= 3e-6 * float(az[0]) * r64
+        want = oracle.dequant(acc[None, :], np.float32(0.03125), a_got)[0]
+        assert np.all(np.abs(_floats(rec["fold_out"]) - want) <= 1e-6 * np.abs(want))
 
 
 def test_lcg_stream_is_the_documented_recurrence():
