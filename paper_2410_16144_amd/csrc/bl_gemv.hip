@@ -27,8 +27,9 @@ namespace {
 
 // XBF16: dtype of the raw activations (fused form only).  LAYOUT 2: tiles of the TL2-coded layout (one token, plain
 // form): same streaming structure, tl2_tile_mac instead of tile_mac, no sum(q) correction.
-template <int M, bool FUSED, bool XBF16, int LAYOUT = 1>
+template <int M, bool FUSED, bool XBF16, int LAYOUT = 1, bool NORM = false>   // NORM: RMSNorm folded into the fused quantizer
 __global__ __launch_bounds__(kThreads, 8) void decode_kernel(BL_FIRST_WG_PARAMS, const DecodeBatch b) {
+    static_assert(!NORM || (M == 1 && FUSED && !XBF16 && LAYOUT == 1), "the norm is folded into the one-token fused quantizer of fp32 rows");
     static_assert(LAYOUT == 1 || (LAYOUT == 2 && M == 1 && !FUSED), "the TL2 layout has the one-token plain form only");
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     __shared__ int tl2_lut[LAYOUT == 2 ? 32 : 1];
@@ -89,25 +90,24 @@ __global__ __launch_bounds__(kThreads, 8) void decode_kernel(BL_FIRST_WG_PARAMS,
                 // quantizer's wait for x leaves them outstanding); the other half follows the quantizer, which
                 // keeps its register footprint small
                 bool folded = false;
-                if constexpr (!XBF16) {
-                    if (p.gamma && tid < holders) {   // uniform per wave: RMSNorm folded into the quantizer
+                if constexpr (NORM) {
+                    if (tid < holders) {   // uniform per wave
                         const Raw8<false> g0 = load_raw8<false>(p.gamma, h0 ? k0 : 0), g1 = load_raw8<false>(p.gamma, h1 ? k1 : 0);
                         Raw8<false> d0 = g0, d1 = g1;
                         if (p.delta) {
                             d0 = load_raw8<false>(p.delta, h0 ? k0 : 0);
                             d1 = load_raw8<false>(p.delta, h1 ? k1 : 0);
                         }
-                        load_part(ks, 0, kInFlight / 2);
-                        folded = true;
+                        folded = true;   // gamma and delta take the registers of the early tiles: none here
                         float ss = norm_fold(r0, r1, g0, g1, d0, d1, h0, h1, k0, k1, p.delta != nullptr,
                                              wg == 0 ? p.h_out : nullptr);
                         ss = wave_sum_f(ss);
                         if (lane == 0) s_ss[wave] = ss;
                     }
                 }
-                if (!folded) load_part(ks, 0, kInFlight / 2);
+                if (!folded && !NORM) load_part(ks, 0, kInFlight / 2);
                 quantize_row_from_regs<XBF16>(r0, r1, h0, h1, k0, k1, holders, p.K, Kp, lds_q, s_f, s_i, tid, lane, wave);
-                load_part(ks, kInFlight / 2, kInFlight);
+                load_part(ks, NORM ? 0 : kInFlight / 2, kInFlight);
             }
         } else {
             // general form: quantize first (its loads would otherwise have to wait for the weight tiles too)
@@ -162,9 +162,7 @@ __global__ __launch_bounds__(kThreads, 8) void decode_kernel(BL_FIRST_WG_PARAMS,
 #pragma unroll
             for (int w16 = 0; w16 < kWaves; ++w16) qsum += s_i[m * kWaves + w16];
             scale = s_f[M * kWaves + m];
-            if constexpr (M == 1 && !XBF16) {
-                if (p.gamma) scale *= norm_scalar(s_ss, row_threads(p.K) / kWave, p.K, p.eps);   // uniform
-            }
+            if constexpr (NORM) scale *= norm_scalar(s_ss, row_threads(p.K) / kWave, p.K, p.eps);
             if (wg == 0 && wave == m % G && lane == 0) {
                 if (p.a_scale_out) p.a_scale_out[m] = scale;
                 if (p.q_sum_out) p.q_sum_out[m] = qsum;
@@ -489,6 +487,11 @@ hipError_t launch_decode(const DecodeBatch& batch, int M, bool fused, hipStream_
     if (lds > (size_t)kMaxDecodeLds) return hipErrorInvalidValue;
     plan_decode(b, kInFlight);
     if (!fused) return launch_m<0, true>(b, M, lds, s);
+    if (b.p[0].gamma) {   // RMSNorm folded into the quantizer: one token, fp32 rows (checked by the entry point)
+        if (M != 1 || bf16) return hipErrorInvalidValue;
+        static LdsCeiling ceiling;
+        return launch_kernel(&decode_kernel<1, true, false, 1, true>, ceiling, b, lds, s);
+    }
     return bf16 ? launch_m<1, true>(b, M, lds, s) : launch_m<1, false>(b, M, lds, s);
 }
 

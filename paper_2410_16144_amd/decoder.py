@@ -11,7 +11,8 @@ the order of the launches:
     norm_quant(GATED, g_ffn)     q4 = quantize(rmsnorm(silu(gate) * up))
     gemv_batch(down)             -> delta for the next layer
 
-(7 launches; rows too long for the folded form take bl_norm_quant + bl_gemv_batch instead: 10 launches.)
+(7 launches; rows that the folded form does not take -- over 16384 elements or not a multiple of 8 -- go through
+bl_norm_quant + bl_gemv_batch instead: 10 launches.)
 
 Shapes follow Appendix A of arXiv 2410.16144 (hidden size, intermediate size, layers, heads); the block
 itself is the LLaMA-like one of BitNet b1.58, which the paper does not spell out.
@@ -121,12 +122,6 @@ def can_fold_norm(K: int) -> bool:
     return K % 8 == 0 and K <= B.BL_DECODE_NORM_MAX_K
 
 
-# Folding the norm into the product's quantizer saves a launch but makes every workgroup read three fp32 rows and
-# quantize for itself.  Measured on MI355X (Appendix-A shapes, whole layers): a gain of 1.5-2.7 us per layer up to
-# hidden size 1536, even at 2048, a loss beyond (7B: +7 us, 100B: +24 us per layer).
-FOLD_NORM_MAX_HIDDEN = 1536
-
-
 @dataclass
 class LayerWeights:
     proj: Dict[str, ops.PackedWeight]     # 'q','k','v','o','gate','up','down'
@@ -152,7 +147,7 @@ class DecoderLayer:
         ffn = w.proj["gate"].N
         assert h_in.shape == (1, hidden) and h_alt.shape == (1, hidden) and hidden % n_heads == 0
         self.w, self.eps, self.delta_in = w, eps, delta_in
-        self.fold = (can_fold_norm(hidden) and hidden <= FOLD_NORM_MAX_HIDDEN) if fold_norm is None else fold_norm
+        self.fold = can_fold_norm(hidden) if fold_norm is None else fold_norm
         self.q4 = ops.alloc_quant(1, ffn, dev)
         self.norm_scratch = torch.empty(B.BL_NORM_SCRATCH_BYTES, dtype=torch.uint8, device=dev)
         if self.fold:
