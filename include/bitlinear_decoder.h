@@ -147,12 +147,15 @@ bl_status bl_rope_table(float *table_dev, int32_t head_dim, int32_t max_pos, dou
  *   q_lin_dev, k_lin_dev, v_lin_dev   [n_heads * head_dim] fp32: the token's Q, K, V projections
  *   k_cache_dev, v_cache_dev          [max_pos, n_heads * head_dim] bf16 bit patterns, 16-byte aligned
  *   out_dev                           [n_heads * head_dim] fp32
- *   scratch_dev                       bl_attn_scratch_bytes(...) bytes, 16-byte aligned; partial
- *                                     results of the workgroups that share a head; contents need
- *                                     not be preserved or cleared between calls
- * Two launches: (n_heads x ceil(max_pos / BL_ATTN_CHUNK)) workgroups, each over at most
- * BL_ATTN_CHUNK cache rows (those beyond p exit at once), then one workgroup per head that merges
- * them.  head_dim must be a multiple of 4 (4 .. BL_ATTN_MAX_HEAD_DIM).
+ *   scratch_dev                       bl_attn_scratch_bytes(...) bytes, 16-byte aligned, ZERO-FILLED before
+ *                                     the first call; every call leaves it usable for the next (it holds
+ *                                     the partial results of the workgroups that share a head and one
+ *                                     ticket counter per head, which the call puts back to zero).  Calls
+ *                                     that may overlap in time must not share it.
+ * One launch: (n_heads x ceil(max_pos / BL_ATTN_CHUNK)) workgroups, each over at most BL_ATTN_CHUNK cache
+ * rows (those beyond p exit at once); the workgroup of a head that finishes last merges the head's
+ * partial results -- it is told so by the ticket it draws; no workgroup waits for another.
+ * head_dim must be a multiple of 4 (4 .. BL_ATTN_MAX_HEAD_DIM).
  * Errors: BL_ERR_NULL, BL_ERR_SHAPE, BL_ERR_ALIGN, BL_ERR_HIP.
  */
 typedef struct bl_attn_args {

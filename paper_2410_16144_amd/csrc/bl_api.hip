@@ -402,7 +402,9 @@ static bool attn_shape_ok(int32_t n_heads, int32_t head_dim, int32_t max_pos) {
 
 uint64_t bl_attn_scratch_bytes(int32_t n_heads, int32_t head_dim, int32_t max_pos) {
     if (!attn_shape_ok(n_heads, head_dim, max_pos)) return 0;
-    return (uint64_t)n_heads * (uint64_t)bl::attn_chunks(max_pos) * (uint64_t)(head_dim + 2) * sizeof(float);
+    // per (head, chunk): head_dim weighted values, the chunk's maximum and sum; then one ticket counter per head
+    return (uint64_t)n_heads * (uint64_t)bl::attn_chunks(max_pos) * (uint64_t)(head_dim + 2) * sizeof(float) +
+           (uint64_t)n_heads * sizeof(uint32_t);
 }
 
 bl_status bl_attn_decode(const bl_attn_args* a, void* stream) {

@@ -12,7 +12,7 @@
 //   rope_table_kernel   cos / sin of every (position, frequency), fp64 arithmetic, rounded to fp32;
 //   attn_chunk_kernel   one (head, chunk of 64 cache rows) per workgroup: rotate query and key, append key and
 //                       value to the bf16 cache, scores, softmax within the chunk, weighted values;
-//   attn_merge_kernel   one workgroup per head merges its chunks (the usual running-maximum rescaling);
+//                       the head's workgroup that finishes last merges its chunks (running-maximum rescaling);
 //   pos_advance_kernel  the token position lives in device memory, so a captured graph replays unchanged.
 // All of it is bandwidth- and latency-bound glue next to the weight streams; nothing here is a dense contraction.
 #include "bl_quant_device.hpp"
@@ -369,6 +369,51 @@ __device__ __forceinline__ void unpack_bf16(const typename CacheVec<W>::type& u,
     }
 }
 
+// One head's chunks merged by one workgroup: out = sum_c f_c o_c / sum_c f_c l_c with f_c = exp(m_c - max m) over the
+// chunks that hold rows 0 .. pos.  The chunks' maxima and sums are read one per thread; the factors go through LDS.
+// A value another workgroup of this launch has published (see publish below): read where it was deposited, by an
+// atomic that returns the old value and adds nothing.
+__device__ __forceinline__ float read_published(float* at) {
+    return __uint_as_float(__hip_atomic_fetch_add(reinterpret_cast<unsigned int*>(at), 0u, __ATOMIC_RELAXED,
+                                                  __HIP_MEMORY_SCOPE_AGENT));
+}
+
+template <bool ACROSS>   // ACROSS: the figures come from other workgroups of this launch
+__device__ __forceinline__ void attn_merge(const AttnArgs& p, int head, int used, float* s_f, float* s_red) {
+    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+    const int d = p.head_dim;
+    float* base = p.scratch + (int64_t)head * p.chunks * (d + 2);
+    const auto src = [&](int i) { return ACROSS ? read_published(base + i) : base[i]; };
+    float m = -INFINITY;
+    for (int c = tid; c < used; c += kAttnThreads) m = fmaxf(m, src(c * (d + 2) + d));
+    for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
+    if (lane == 0) s_red[wave] = m;
+    __syncthreads();
+    m = fmaxf(fmaxf(s_red[0], s_red[1]), fmaxf(s_red[2], s_red[3]));
+    static_assert(kAttnWaves == 4, "four partial maxima");
+    float l = 0.0f, o = 0.0f;
+    for (int c0 = 0; c0 < used; c0 += kAttnThreads) {   // one pass unless the context exceeds 256 chunks
+        __syncthreads();                                // s_f and s_red of the previous pass have been read
+        const int c = c0 + tid;
+        float f = 0.0f, fl = 0.0f;
+        if (c < used) {
+            f = expf(src(c * (d + 2) + d) - m);
+            fl = f * src(c * (d + 2) + d + 1);
+        }
+        s_f[tid] = f;
+        fl = wave_sum_f(fl);
+        if (lane == 0) s_red[wave] = fl;
+        __syncthreads();
+        l += (s_red[0] + s_red[1]) + (s_red[2] + s_red[3]);
+        const int n = min(kAttnThreads, used - c0);
+        if (tid < d) {
+#pragma unroll 4
+            for (int i = 0; i < n; ++i) o += s_f[i] * src((c0 + i) * (d + 2) + tid);
+        }
+    }
+    if (tid < d) p.out[head * d + tid] = o / l;
+}
+
 // One (head, chunk of 64 cache rows) per workgroup.  The chunk's keys and values (64 x head_dim bf16 each) are
 // requested first, W values per thread and request, consecutive threads on consecutive addresses of a row; while
 // they travel the query is rotated (and, in the chunk that holds the token's own row, key and value are rotated,
@@ -459,7 +504,22 @@ __global__ __launch_bounds__(kAttnThreads) void attn_chunk_kernel(const AttnArgs
     }
     __syncthreads();
 
+    // The head's chunks are merged by whichever of its workgroups finishes last.  Nobody waits for anybody: every
+    // workgroup DEPOSITS its figures with atomics that return the old value (so their completion can be waited for,
+    // and they are performed where every compute unit's atomics meet, not in a cache of this die), then draws a
+    // ticket from the head's counter the same way; the one that draws the last ticket reads all deposits, again with
+    // returning atomics, merges, and puts the counter back to zero for the next launch.  Data that crosses
+    // workgroups inside this launch travels through atomics only -- no cache write-back or invalidation is involved
+    // (a device-wide fence here cost 8-35 us per layer).
+    const int used = pos / kChunk + 1;                  // workgroups of this head that get this far
+    const bool alone = used == 1;                       // uniform
     float* dst = p.scratch + ((int64_t)head * p.chunks + chunk) * (d + 2);
+    unsigned int sink = 0;
+    const auto publish = [&](float* at, float v) {
+        if (alone) *at = v;
+        else sink ^= __hip_atomic_exchange(reinterpret_cast<unsigned int*>(at), __float_as_uint(v), __ATOMIC_RELAXED,
+                                           __HIP_MEMORY_SCOPE_AGENT);
+    };
     if (tid < kWave) {                                  // wave 0: one row per lane
         float score = -INFINITY;
         if (tid < rows) {
@@ -472,8 +532,8 @@ __global__ __launch_bounds__(kAttnThreads) void attn_chunk_kernel(const AttnArgs
         s_w[tid] = w;
         const float l = wave_sum_f(w);
         if (tid == 0) {
-            dst[d] = m;
-            dst[d + 1] = l;
+            publish(dst + d, m);
+            publish(dst + d + 1, l);
         }
     }
     __syncthreads();
@@ -488,49 +548,22 @@ __global__ __launch_bounds__(kAttnThreads) void attn_chunk_kernel(const AttnArgs
     if (tid < d) {
         float t = 0.0f;
         for (int q = 0; q < parts; ++q) t += s_o[q * d + tid];
-        dst[tid] = t;
+        publish(dst + tid, t);
     }
-}
-
-// One workgroup per head: out = sum_c f_c o_c / sum_c f_c l_c with f_c = exp(m_c - max m) over the chunks that hold
-// rows 0 .. pos.  The chunks' maxima and sums are read one per thread; the factors go through LDS.
-__global__ __launch_bounds__(kAttnThreads) void attn_merge_kernel(const AttnArgs p) {
-    __shared__ float s_f[kAttnThreads];
-    __shared__ float s_red[kAttnWaves];
-    const int tid = threadIdx.x, head = blockIdx.x, wave = tid / kWave, lane = tid % kWave;
-    const int d = p.head_dim;
-    const int pos = *p.pos;
-    if (pos < 0 || pos >= p.max_pos) return;            // uniform
-    const int used = pos / kChunk + 1;                   // chunks that hold rows 0 .. pos
-    const float* src = p.scratch + (int64_t)head * p.chunks * (d + 2);
-    float m = -INFINITY;
-    for (int c = tid; c < used; c += kAttnThreads) m = fmaxf(m, src[c * (d + 2) + d]);
-    for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
-    if (lane == 0) s_red[wave] = m;
+    __shared__ unsigned int s_ticket;
+    if (tid == 0) s_ticket = sink;                      // a use of the returned values: the deposits are returning atomics
+    __syncthreads();                                    // every wave waits for its memory operations here, so the deposits
+                                                        // have all returned (and s_o, s_w have been read)
+    if (alone) {
+        attn_merge<false>(p, head, 1, s_o, s_w);
+        return;
+    }
+    unsigned int* counter = reinterpret_cast<unsigned int*>(p.scratch + (int64_t)p.n_heads * p.chunks * (d + 2)) + head;
+    if (tid == 0) s_ticket = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
-    m = fmaxf(fmaxf(s_red[0], s_red[1]), fmaxf(s_red[2], s_red[3]));
-    static_assert(kAttnWaves == 4, "four partial maxima");
-    float l = 0.0f, o = 0.0f;
-    for (int c0 = 0; c0 < used; c0 += kAttnThreads) {   // one pass unless the context exceeds 256 chunks
-        __syncthreads();                                // s_f and s_red of the previous pass have been read
-        const int c = c0 + tid;
-        float f = 0.0f, fl = 0.0f;
-        if (c < used) {
-            f = expf(src[c * (d + 2) + d] - m);
-            fl = f * src[c * (d + 2) + d + 1];
-        }
-        s_f[tid] = f;
-        fl = wave_sum_f(fl);
-        if (lane == 0) s_red[wave] = fl;
-        __syncthreads();
-        l += (s_red[0] + s_red[1]) + (s_red[2] + s_red[3]);
-        const int n = min(kAttnThreads, used - c0);
-        if (tid < d) {
-#pragma unroll 4
-            for (int i = 0; i < n; ++i) o += s_f[i] * src[(c0 + i) * (d + 2) + tid];
-        }
-    }
-    if (tid < d) p.out[head * d + tid] = o / l;
+    if (s_ticket != (unsigned)(used - 1)) return;       // uniform
+    attn_merge<true>(p, head, used, s_o, s_w);
+    if (tid == 0) __hip_atomic_store(counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 __global__ void pos_advance_kernel(int32_t* pos) {
@@ -582,9 +615,6 @@ hipError_t launch_attn_decode(const bl_attn_args& a, hipStream_t s) {
     p.n_heads = a.n_heads; p.head_dim = a.head_dim; p.max_pos = a.max_pos; p.chunks = attn_chunks(a.max_pos);
     if (a.head_dim % 8 == 0) attn_chunk_kernel<8><<<dim3((unsigned)a.n_heads, (unsigned)p.chunks), dim3(kAttnThreads), 0, s>>>(p);
     else attn_chunk_kernel<4><<<dim3((unsigned)a.n_heads, (unsigned)p.chunks), dim3(kAttnThreads), 0, s>>>(p);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    attn_merge_kernel<<<dim3((unsigned)a.n_heads), dim3(kAttnThreads), 0, s>>>(p);
     return hipGetLastError();
 }
 

@@ -5,14 +5,14 @@ Every arithmetic step runs in the library's kernels; this module owns buffers (t
 the order of the launches:
 
     decode_norm_batch(q, k, v)   h' = h + delta of the previous layer; the three products of rmsnorm(h', g_in)
-    attn_decode                  rotary embedding, cache append, attention (two launches)
+    attn_decode                  rotary embedding, cache append, attention
     decode_norm_batch(o)         the product of rmsnorm(attention output, g_attn)
     decode_norm_batch(gate, up)  h'' = h' + o; the two products of rmsnorm(h'', g_post)
     norm_quant(GATED, g_ffn)     q4 = quantize(rmsnorm(silu(gate) * up))
     gemv_batch(down)             -> delta for the next layer
 
-(7 launches; rows that the folded form does not take -- over 16384 elements or not a multiple of 8 -- go through
-bl_norm_quant + bl_gemv_batch instead: 10 launches.)
+(6 launches; rows that the folded form does not take -- over 16384 elements or not a multiple of 8 -- go through
+bl_norm_quant + bl_gemv_batch instead: 9 launches.)
 
 Shapes follow Appendix A of arXiv 2410.16144 (hidden size, intermediate size, layers, heads); the block
 itself is the LLaMA-like one of BitNet b1.58, which the paper does not spell out.
@@ -73,7 +73,7 @@ class Attention:
         self.n_heads, self.head_dim, self.max_pos = n_heads, head_dim, max_pos
         self.k_cache = torch.zeros((max_pos, hidden), dtype=torch.bfloat16, device=dev)
         self.v_cache = torch.zeros((max_pos, hidden), dtype=torch.bfloat16, device=dev)
-        self.scratch = torch.empty(B.bl_attn_scratch_bytes(n_heads, head_dim, max_pos), dtype=torch.uint8, device=dev)
+        self.scratch = torch.zeros(B.bl_attn_scratch_bytes(n_heads, head_dim, max_pos), dtype=torch.uint8, device=dev)
         self.out = out if out is not None else torch.empty((1, hidden), dtype=torch.float32, device=dev)
         for t in (q_lin, k_lin, v_lin, self.out):
             assert t.dtype == torch.float32 and t.numel() == hidden and t.is_contiguous()
@@ -171,12 +171,12 @@ class DecoderLayer:
 
     def launch(self):
         w = self.w
-        if self.fold:      # 7 launches: three products with the norm in their quantizer, attention (2), gate, down
+        if self.fold:      # 6 launches: three products with the norm in their quantizer, attention, gate, down
             self.qkv.launch()
             self.attn.launch()
             self.o.launch()
             self.gate_up.launch()
-        else:              # 10 launches
+        else:              # 9 launches
             norm_quant(B.BL_NORM_RESIDUAL, w.g_in, self.eps, a=self.delta_in, h=self.h, out=self.q1)
             self.qkv.launch()
             self.attn.launch()

@@ -213,7 +213,7 @@ def test_decoder_block_validation():
     assert _st(B.bl_rope_table, P, 64, 16, 0.0) == B.BL_ERR_SHAPE
     assert _st(B.bl_rope_table, P + 4, 64, 16, 10000.0) == B.BL_ERR_ALIGN
     assert B.bl_attn_scratch_bytes(32, 102, 512) == 0                # head_dim not a multiple of 4
-    assert B.bl_attn_scratch_bytes(32, 128, 513) == 32 * 9 * 130 * 4
+    assert B.bl_attn_scratch_bytes(32, 128, 513) == 32 * 9 * 130 * 4 + 32 * 4
     assert B.bl_attn_scratch_bytes(0, 128, 512) == 0 and B.bl_attn_scratch_bytes(1, 264, 512) == 0
     good = [P] * 9 + [4, 64, 100]
     def attn(i, v):
