@@ -434,14 +434,29 @@ def extra_decoder_tokens(torch, models, max_pos=512, tokens=64):
             def run():
                 for t in range(tokens):
                     stack.h.copy_(x[t])
-                    stack.graph.replay()
-            stack.pos.fill_(start)
+                    stack.step()
+            stack.set_position(start)
             run()                      # untimed pass (also brings the clocks up)
-            stack.pos.fill_(start)
+            stack.set_position(start)
             ms, _ = timed(torch, run)
             assert int(stack.pos[0]) == start + tokens and bool(torch.isfinite(stack.y).all())
             row[label] = {"ms_per_token": round(ms / tokens, 4), "tokens_per_s": round(tokens * 1e3 / ms, 1),
                           "us_per_layer": round(ms * 1e3 / tokens / n_layers, 2)}
+        if name in ("700M", "7B", "70B") and PowerSampler().read() is not None:
+            # the sizes of the paper's energy table (Section 3): socket power while tokens are decoded back to back
+            with PowerSampler() as ps:
+                t0, n = time.perf_counter(), 0
+                while time.perf_counter() - t0 < 2.0:
+                    stack.set_position(0)
+                    run()
+                    torch.cuda.synchronize()
+                    n += tokens
+                dt = time.perf_counter() - t0
+            if ps.samples:
+                watts = sum(ps.samples) / len(ps.samples)
+                row["energy"] = {"socket_power_W_mean": round(watts, 1), "ms_per_token_wall": round(dt / n * 1e3, 4),
+                                 "J_per_token": round(watts * dt / n, 4),
+                                 "note": "whole-board socket power x wall time per token, positions 0..%d, host launch gaps included" % (tokens - 1)}
         rows.append(row)
         del stack
         torch.cuda.empty_cache()

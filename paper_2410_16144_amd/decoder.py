@@ -213,6 +213,13 @@ class DecoderStack:
             delta, h_in = layer.delta_out, layer.h_out
         self.h_last = h_in
         self.graph = None
+        self._next_pos = 0      # host-side mirror of self.pos, to refuse a token beyond the cache
+
+    def set_position(self, pos: int):
+        """Continue at position `pos` (the caches must hold rows 0 .. pos-1)."""
+        assert 0 <= pos <= self.max_pos
+        self.pos.fill_(pos)
+        self._next_pos = pos
 
     def launch(self):
         """All launches of one token on the current stream: the layers, the last residual add with the final
@@ -233,7 +240,7 @@ class DecoderStack:
         self.launch()
         torch.cuda.synchronize()
         self.h.copy_(h0)
-        self.pos.copy_(pos0)
+        self.pos.copy_(pos0)   # the warm-up token does not count: _next_pos is untouched
         s = torch.cuda.Stream()
         s.wait_stream(torch.cuda.current_stream())
         self.graph = torch.cuda.CUDAGraph()
@@ -244,6 +251,11 @@ class DecoderStack:
         return self.graph
 
     def step(self):
+        """One token: self.h holds its input; returns self.y.  Raises once the cache is full (the kernels themselves
+        do nothing for a position outside the cache)."""
+        if self._next_pos >= self.max_pos:
+            raise RuntimeError("the key/value cache holds %d positions and is full" % self.max_pos)
+        self._next_pos += 1
         if self.graph is not None:
             self.graph.replay()
         else:

@@ -433,3 +433,19 @@ def test_token_loop_against_oracle(dev, mods, hidden, ffn, n_heads, n_layers, us
         for i, layer in enumerate(stack.layers):
             got_v = layer.attn.v_cache[pos].float().cpu().numpy().astype(np.float64)
             assert np.linalg.norm(got_v - vcs[i][pos]) <= 5e-2 * np.linalg.norm(vcs[i][pos])
+
+
+def test_stack_refuses_a_token_beyond_the_cache(dev, mods):
+    B, dec, ops = mods
+    layers, g_final = _make_layers(65000, 64, 128, 1)
+    stack = dec.DecoderStack(_to_device(layers, dev, dec, ops), _t(g_final, dev), 2, 3, dev)
+    for _ in range(3):
+        stack.step()
+    torch.cuda.synchronize()
+    assert int(stack.pos[0]) == 3
+    with pytest.raises(RuntimeError):
+        stack.step()
+    stack.set_position(1)
+    stack.step()
+    torch.cuda.synchronize()
+    assert int(stack.pos[0]) == 2
