@@ -347,7 +347,8 @@ def _run_norm_decode(dev, mods, r, K, Ns, with_delta, use_workspace):
 @pytest.mark.parametrize("K,Ns,with_delta,use_workspace", [
     (200, (70,), True, False), (768, (768, 768, 768), True, True), (1536, (1536,), False, True),
     (3200, (3200, 3200, 3200), True, True), (4096, (11008, 11008), True, True), (8192, (8192, 8192, 8192), True, True),
-    (8192, (8192,), False, False), (16384, (640,), True, True), (4096, (4096,), False, True), (8, (3,), True, False)])
+    (8192, (8192,), False, False), (16384, (640,), True, True), (4096, (4096,), False, True), (8, (3,), True, False),
+    (8192, (45568,), True, True)])   # the last: one of the 100B shape's gate/up matrices (Appendix A)
 def test_decode_norm_batch_parity(dev, mods, K, Ns, with_delta, use_workspace):
     """RMSNorm folded into the fused quantizer: codes, scale and sums against the oracle's quantizer on
     z = (x + delta) * gamma formed with the same two fp32 operations; the scale carries the norm's scalar; the
