@@ -103,9 +103,25 @@ bl_status bl_norm_quant(const bl_norm_quant_args *args, void *stream);
  *   packed_dev, desc, out_dev [N], acc_dev (optional), q_dev [Kp] / a_scale_dev [1] / q_sum_dev [1]
  *               (optional copies of the quantizer's results): as in bl_decode_item with M = 1
  *   workspace_dev: as for bl_gemv_batch (may be NULL)
+ *
+ * Two further forms, for the feed-forward half of the block (all items of a launch take the same forms):
+ *
+ *   Gated epilogue (glu_gamma_dev != NULL).  The packed matrix holds the GATE and UP projections interleaved by
+ *   32 rows: rows 64 b .. 64 b + 31 are gate rows 32 b .. 32 b + 31, rows 64 b + 32 .. 64 b + 63 the up rows of
+ *   the same 32 outputs (N = 2 F, F a multiple of 32; desc->w_scale is the gate matrix's scale, w_scale_up the up
+ *   matrix's).  Instead of the 2 F products the launch writes
+ *       out[n]    = silu(gate[n]) * up[n] * glu_gamma[n],   n < F      (out_dev: F floats)
+ *       ss_out[b] = sum over n in [32 b, 32 b + 32) of (silu(gate[n]) * up[n])^2      (ss_out_dev: F / 32 floats)
+ *   i.e. the feed-forward product already multiplied by the weight of the norm that follows it, and that norm's
+ *   sum of squares in pieces.  acc_dev, if given, still receives the 2 F raw sums.
+ *
+ *   Pre-multiplied row (gamma_dev == NULL, ss_in_dev != NULL): x_dev is such an `out`, ss_in_dev [ss_count] such
+ *   pieces: the row is quantized as it is and r = 1 / sqrt(sum(pieces) / K + eps) multiplies the scale.
+ *   delta_dev and h_out_dev must be NULL.
+ *
  * Errors: BL_ERR_NULL, BL_ERR_COUNT, BL_ERR_LAYOUT, BL_ERR_SHAPE (also K not a multiple of 8 or beyond
- *         BL_DECODE_NORM_MAX_K, h_out_dev equal to x_dev or delta_dev), BL_ERR_BUF_SMALL, BL_ERR_ALIGN,
- *         BL_ERR_HIP.
+ *         BL_DECODE_NORM_MAX_K, h_out_dev equal to x_dev or delta_dev, items of different forms, N not a multiple
+ *         of 64 with the gated epilogue, ss_count < 1), BL_ERR_BUF_SMALL, BL_ERR_ALIGN, BL_ERR_HIP.
  */
 #define BL_DECODE_NORM_MAX_K 16384
 
@@ -122,6 +138,11 @@ typedef struct bl_decode_norm_item {
     int8_t               *q_dev;
     float                *a_scale_dev;
     int32_t              *q_sum_dev;
+    const float          *ss_in_dev;       /* pre-multiplied row */
+    int32_t               ss_count;
+    float                 w_scale_up;      /* gated epilogue */
+    const float          *glu_gamma_dev;
+    float                *ss_out_dev;
 } bl_decode_norm_item;
 
 bl_status bl_decode_norm_batch(const bl_decode_norm_item *items, int32_t count, void *workspace_dev,

@@ -103,7 +103,9 @@ class DecodeNormItem(ctypes.Structure):
     _fields_ = [("x_dev", ctypes.c_void_p), ("delta_dev", ctypes.c_void_p), ("h_out_dev", ctypes.c_void_p),
                 ("gamma_dev", ctypes.c_void_p), ("eps", ctypes.c_float), ("packed_dev", ctypes.c_void_p),
                 ("desc", ctypes.POINTER(PackedDesc)), ("out_dev", ctypes.c_void_p), ("acc_dev", ctypes.c_void_p),
-                ("q_dev", ctypes.c_void_p), ("a_scale_dev", ctypes.c_void_p), ("q_sum_dev", ctypes.c_void_p)]
+                ("q_dev", ctypes.c_void_p), ("a_scale_dev", ctypes.c_void_p), ("q_sum_dev", ctypes.c_void_p),
+                ("ss_in_dev", ctypes.c_void_p), ("ss_count", ctypes.c_int32), ("w_scale_up", ctypes.c_float),
+                ("glu_gamma_dev", ctypes.c_void_p), ("ss_out_dev", ctypes.c_void_p)]
 
 
 _lib = None
@@ -339,14 +341,17 @@ def bl_pos_advance(pos_dev: int, stream: int = 0):
 
 
 def make_decode_norm_items(items):
-    """items: iterable of (x_dev, delta_dev, h_out_dev, gamma_dev, eps, packed_dev, desc, out_dev, acc_dev, q_dev,
-    a_scale_dev, q_sum_dev); 0 for an absent optional pointer.  Returns a ctypes array that keeps the descriptors alive."""
+    """items: iterable of dicts with the fields of bl_decode_norm_item without the _dev suffix (x, gamma, eps, packed,
+    desc, out required as the form demands; the rest optional: 0 / absent = NULL).  Returns a ctypes array that keeps
+    the descriptors alive."""
     items = list(items)
     arr = (DecodeNormItem * len(items))()
-    for i, (x, dl, ho, g, eps, pk, desc, out, acc, q, a, sm) in enumerate(items):
-        arr[i] = DecodeNormItem(x or None, dl or None, ho or None, g or None, eps, pk or None, ctypes.pointer(desc),
-                                out or None, acc or None, q or None, a or None, sm or None)
-    arr._descs = [it[6] for it in items]
+    for i, it in enumerate(items):
+        g = lambda k: it.get(k) or None
+        arr[i] = DecodeNormItem(g("x"), g("delta"), g("h_out"), g("gamma"), it.get("eps", 0.0), g("packed"),
+                                ctypes.pointer(it["desc"]), g("out"), g("acc"), g("q"), g("a_scale"), g("q_sum"),
+                                g("ss_in"), it.get("ss_count", 0), it.get("w_scale_up", 0.0), g("glu_gamma"), g("ss_out"))
+    arr._descs = [it["desc"] for it in items]
     return arr
 
 

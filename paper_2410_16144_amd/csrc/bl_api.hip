@@ -357,14 +357,23 @@ bl_status bl_decode_norm_batch(const bl_decode_norm_item* items, int32_t count, 
     int64_t max_Kp = 0;
     for (int i = 0; i < count; ++i) {
         const bl_decode_norm_item& it = items[i];
-        if (!it.x_dev || !it.gamma_dev || !it.packed_dev || !it.desc || !it.out_dev) return BL_ERR_NULL;
+        if (!it.x_dev || !it.packed_dev || !it.desc || !it.out_dev) return BL_ERR_NULL;
+        if (!it.gamma_dev && !it.ss_in_dev) return BL_ERR_NULL;            // one of the two forms of the norm
+        if (it.glu_gamma_dev && !it.ss_out_dev) return BL_ERR_NULL;
         bl_status s = check_desc(it.desc);
         if (s != BL_OK) return s;
         if (it.desc->K % 8 != 0 || it.desc->K > BL_DECODE_NORM_MAX_K) return BL_ERR_SHAPE;
         if (it.h_out_dev && (it.h_out_dev == it.x_dev || it.h_out_dev == it.delta_dev)) return BL_ERR_SHAPE;
+        if (!it.gamma_dev && (it.delta_dev || it.h_out_dev || it.ss_count < 1)) return BL_ERR_SHAPE;
+        if (it.gamma_dev && it.ss_in_dev) return BL_ERR_SHAPE;
+        if ((it.gamma_dev != nullptr) != (items[0].gamma_dev != nullptr) ||
+            (it.glu_gamma_dev != nullptr) != (items[0].glu_gamma_dev != nullptr))
+            return BL_ERR_SHAPE;                                           // one form per launch
+        if (it.glu_gamma_dev && it.desc->N % BL_TILE_N != 0) return BL_ERR_SHAPE;
         if (!aligned(it.x_dev, 16) || !aligned(it.gamma_dev, 16) || !aligned(it.delta_dev, 16) || !aligned(it.h_out_dev, 16) ||
             !aligned(it.packed_dev, 16) || !aligned(it.out_dev, 4) || !aligned(it.acc_dev, 4) || !aligned(it.q_dev, 16) ||
-            !aligned(it.a_scale_dev, 4) || !aligned(it.q_sum_dev, 4))
+            !aligned(it.a_scale_dev, 4) || !aligned(it.q_sum_dev, 4) || !aligned(it.ss_in_dev, 4) ||
+            !aligned(it.glu_gamma_dev, 4) || !aligned(it.ss_out_dev, 4))
             return BL_ERR_ALIGN;
         bl::DecodeProblem& p = b.p[i];
         p = make_decode_problem(it.packed_dev, it.desc, it.out_dev, it.acc_dev);
@@ -378,6 +387,11 @@ bl_status bl_decode_norm_batch(const bl_decode_norm_item* items, int32_t count, 
         p.delta = it.delta_dev;
         p.h_out = it.h_out_dev;
         p.eps = it.eps;
+        p.ss_in = it.ss_in_dev;
+        p.ss_count = it.ss_count;
+        p.glu_gamma = it.glu_gamma_dev;
+        p.ss_out = it.ss_out_dev;
+        p.w_scale2 = it.w_scale_up;
         if (it.desc->Kp > max_Kp) max_Kp = it.desc->Kp;
     }
     if (bl::decode_lds_bytes(1, max_Kp, true) > (size_t)bl::kMaxDecodeLds) return BL_ERR_SHAPE;

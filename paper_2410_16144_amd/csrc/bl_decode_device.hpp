@@ -295,6 +295,14 @@ __device__ __forceinline__ float norm_fold(Raw8<false>& r0, Raw8<false>& r1, con
     return ss;
 }
 
+// The row arrives multiplied by its norm weight already and sum(x^2) in `count` pieces: this holder thread's share of
+// the pieces (the holder waves' shares then meet in LDS like the sums of norm_fold).
+__device__ __forceinline__ float norm_pieces(const float* __restrict__ pieces, int count, int tid, int holders) {
+    float ss = 0.0f;
+    for (int i = tid; i < count; i += holders) ss += pieces[i];
+    return ss;
+}
+
 // The norm's scalar from the holder waves' partial sums (every thread computes the same value).
 __device__ __forceinline__ float norm_scalar(const float* s_ss, int holding_waves, int K, float eps) {
     float total = 0.0f;

@@ -22,11 +22,12 @@ namespace {
 constexpr int kSkMaxRb = 32;   // row blocks one chunk may touch (LDS: 256 bytes each)
 constexpr int kSumBits = 40;   // low bits of a workspace word that hold the partial sum
 
-// LAYOUT 2: TL2-coded tiles (plain form only).  NORM: RMSNorm folded into the fused quantizer (fp32 rows only).
-template <int U, bool FUSED, bool XBF16, int LAYOUT = 1, bool NORM = false>
+// LAYOUT 2: TL2-coded tiles (plain form only).  NORM (fp32 rows only): 1 = RMSNorm folded into the fused quantizer,
+// 2 = the row is already multiplied by its norm weight and sum(x^2) arrives in pieces.
+template <int U, bool FUSED, bool XBF16, int LAYOUT = 1, int NORM = 0>
 __global__ __launch_bounds__(kThreads, 8) void decode_sk_kernel(BL_FIRST_WG_PARAMS, const DecodeBatch b) {
     static_assert(LAYOUT == 1 || (LAYOUT == 2 && !FUSED), "the TL2 layout has the plain form only");
-    static_assert(!NORM || (FUSED && !XBF16 && LAYOUT == 1), "the norm is folded into the fused quantizer of fp32 rows");
+    static_assert(NORM == 0 || (FUSED && !XBF16 && LAYOUT == 1), "the norm is folded into the fused quantizer of fp32 rows");
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     __shared__ int tl2_lut[LAYOUT == 2 ? 32 : 1];
 
@@ -69,7 +70,7 @@ __global__ __launch_bounds__(kThreads, 8) void decode_sk_kernel(BL_FIRST_WG_PARA
     };
     auto load_batch = [&](int i0) { load_part(i0, 0, U); };
     // tiles that go in flight ahead of the quantizer (register budget; the norm form also holds gamma and delta)
-    constexpr int kEarly = NORM ? U / 4 : U > 4 ? U / 2 : U;
+    constexpr int kEarly = NORM == 1 ? U / 4 : U > 4 ? U / 2 : U;
 
     int qsum = 0;
     float scale = 0.0f;
@@ -94,7 +95,11 @@ __global__ __launch_bounds__(kThreads, 8) void decode_sk_kernel(BL_FIRST_WG_PARA
                 const int k0 = tid * 8, k1 = k0 + holders * 8;
                 const bool h0 = k0 < p.K, h1 = k1 < p.K;
                 Raw8<XBF16> r0 = load_raw8<XBF16>(p.x, h0 ? k0 : 0), r1 = load_raw8<XBF16>(p.x, h1 ? k1 : 0);
-                if constexpr (NORM) {
+                if constexpr (NORM == 2) {
+                    load_part(0, 0, kEarly);
+                    const float ss = wave_sum_f(norm_pieces(p.ss_in, p.ss_count, tid, holders));
+                    if (lane == 0) s_ss[wave] = ss;
+                } else if constexpr (NORM == 1) {
                     {
                         const Raw8<false> g0 = load_raw8<false>(p.gamma, h0 ? k0 : 0), g1 = load_raw8<false>(p.gamma, h1 ? k1 : 0);
                         Raw8<false> d0 = g0, d1 = g1;
@@ -128,7 +133,7 @@ __global__ __launch_bounds__(kThreads, 8) void decode_sk_kernel(BL_FIRST_WG_PARA
         }
         for (int w16 = 0; w16 < holding_waves; ++w16) qsum += s_i[w16];
         scale = s_f[kWaves];
-        if constexpr (NORM) scale *= norm_scalar(s_ss, holding_waves, p.K, p.eps);
+        if constexpr (NORM != 0) scale *= norm_scalar(s_ss, holding_waves, p.K, p.eps);
         if (blk == p.first_wg) {   // optional copy-out of the quantizer's results
             if (p.q_out) {
                 for (int i = tid; i < Kp / 4; i += kThreads)
@@ -200,7 +205,7 @@ __global__ __launch_bounds__(kThreads, 8) void decode_sk_kernel(BL_FIRST_WG_PARA
     }
 }
 
-template <int U, bool FUSED, bool XBF16, int LAYOUT = 1, bool NORM = false>
+template <int U, bool FUSED, bool XBF16, int LAYOUT = 1, int NORM = 0>
 hipError_t launch_sk(const DecodeBatch& b, size_t lds, hipStream_t s) {
     static LdsCeiling ceiling;
     auto kernel = &decode_sk_kernel<U, FUSED, XBF16, LAYOUT, NORM>;
@@ -235,6 +240,7 @@ int64_t split_launches() { return g_split_launches; }
 // uses the row-block kernels): tiny launches, shapes whose chunks would touch too many row blocks.
 bool plan_decode_split(DecodeBatch& b, bool fused, int& tiles_per_wave) {
     if (g_split < 0 || !b.ws) return false;
+    if (b.p[0].glu_gamma) return false;   // the gated epilogue pairs lanes of one wave: whole row blocks only
     const int cus = compute_unit_count();
     if (cus <= 0) return false;
     int64_t T[BL_MAX_BATCH], total = 0;
@@ -315,7 +321,8 @@ hipError_t launch_decode_split(const DecodeBatch& b, int tiles_per_wave, bool fu
     if (b.layout == 2) return small ? launch_sk<4, false, true, 2>(b, lds, s) : launch_sk<8, false, true, 2>(b, lds, s);
     if (!fused) return small ? launch_sk<4, false, true>(b, lds, s) : launch_sk<8, false, true>(b, lds, s);
     if (bf16) return small ? launch_sk<4, true, true>(b, lds, s) : launch_sk<8, true, true>(b, lds, s);
-    if (b.p[0].gamma) return small ? launch_sk<4, true, false, 1, true>(b, lds, s) : launch_sk<8, true, false, 1, true>(b, lds, s);
+    if (b.p[0].gamma) return small ? launch_sk<4, true, false, 1, 1>(b, lds, s) : launch_sk<8, true, false, 1, 1>(b, lds, s);
+    if (b.p[0].ss_in) return small ? launch_sk<4, true, false, 1, 2>(b, lds, s) : launch_sk<8, true, false, 1, 2>(b, lds, s);
     return small ? launch_sk<4, true, false>(b, lds, s) : launch_sk<8, true, false>(b, lds, s);
 }
 

@@ -67,8 +67,6 @@ __device__ __forceinline__ void store4(float* row, int k, int K, const float (&v
     }
 }
 
-__device__ __forceinline__ float silu(float t) { return t / (1.0f + expf(-t)); }
-
 // Thread t holds elements 4 (t + 1024 i) .. + 3, i = 0 .. NV-1.
 template <int MODE, int NV, bool VEC>
 __global__ __launch_bounds__(kNormThreads) void norm_quant_kernel(const NormArgs p) {

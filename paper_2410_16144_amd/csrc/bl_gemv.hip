@@ -27,9 +27,12 @@ namespace {
 
 // XBF16: dtype of the raw activations (fused form only).  LAYOUT 2: tiles of the TL2-coded layout (one token, plain
 // form): same streaming structure, tl2_tile_mac instead of tile_mac, no sum(q) correction.
-template <int M, bool FUSED, bool XBF16, int LAYOUT = 1, bool NORM = false>   // NORM: RMSNorm folded into the fused quantizer
+// NORM (one token, fp32 rows): 1 = RMSNorm folded into the fused quantizer, 2 = the row is already multiplied by its norm
+// weight and sum(x^2) arrives in pieces.  GLU: gated epilogue (see DecodeProblem).
+template <int M, bool FUSED, bool XBF16, int LAYOUT = 1, int NORM = 0, bool GLU = false>
 __global__ __launch_bounds__(kThreads, 8) void decode_kernel(BL_FIRST_WG_PARAMS, const DecodeBatch b) {
-    static_assert(!NORM || (M == 1 && FUSED && !XBF16 && LAYOUT == 1), "the norm is folded into the one-token fused quantizer of fp32 rows");
+    static_assert(NORM == 0 || (M == 1 && FUSED && !XBF16 && LAYOUT == 1), "the norm is folded into the one-token fused quantizer of fp32 rows");
+    static_assert(!GLU || (M == 1 && LAYOUT == 1), "the gated epilogue is for one token");
     static_assert(LAYOUT == 1 || (LAYOUT == 2 && M == 1 && !FUSED), "the TL2 layout has the one-token plain form only");
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     __shared__ int tl2_lut[LAYOUT == 2 ? 32 : 1];
@@ -90,7 +93,12 @@ __global__ __launch_bounds__(kThreads, 8) void decode_kernel(BL_FIRST_WG_PARAMS,
                 // quantizer's wait for x leaves them outstanding); the other half follows the quantizer, which
                 // keeps its register footprint small
                 bool folded = false;
-                if constexpr (NORM) {
+                if constexpr (NORM == 2) {
+                    if (tid < holders) {   // uniform per wave
+                        const float ss = wave_sum_f(norm_pieces(p.ss_in, p.ss_count, tid, holders));
+                        if (lane == 0) s_ss[wave] = ss;
+                    }
+                } else if constexpr (NORM == 1) {
                     if (tid < holders) {   // uniform per wave
                         const Raw8<false> g0 = load_raw8<false>(p.gamma, h0 ? k0 : 0), g1 = load_raw8<false>(p.gamma, h1 ? k1 : 0);
                         Raw8<false> d0 = g0, d1 = g1;
@@ -105,9 +113,9 @@ __global__ __launch_bounds__(kThreads, 8) void decode_kernel(BL_FIRST_WG_PARAMS,
                         if (lane == 0) s_ss[wave] = ss;
                     }
                 }
-                if (!folded && !NORM) load_part(ks, 0, kInFlight / 2);
+                if (!folded && NORM != 1) load_part(ks, 0, kInFlight / 2);
                 quantize_row_from_regs<XBF16>(r0, r1, h0, h1, k0, k1, holders, p.K, Kp, lds_q, s_f, s_i, tid, lane, wave);
-                load_part(ks, NORM ? 0 : kInFlight / 2, kInFlight);
+                load_part(ks, NORM == 1 ? 0 : kInFlight / 2, kInFlight);
             }
         } else {
             // general form: quantize first (its loads would otherwise have to wait for the weight tiles too)
@@ -162,7 +170,7 @@ __global__ __launch_bounds__(kThreads, 8) void decode_kernel(BL_FIRST_WG_PARAMS,
 #pragma unroll
             for (int w16 = 0; w16 < kWaves; ++w16) qsum += s_i[m * kWaves + w16];
             scale = s_f[M * kWaves + m];
-            if constexpr (NORM) scale *= norm_scalar(s_ss, row_threads(p.K) / kWave, p.K, p.eps);
+            if constexpr (NORM != 0) scale *= norm_scalar(s_ss, row_threads(p.K) / kWave, p.K, p.eps);
             if (wg == 0 && wave == m % G && lane == 0) {
                 if (p.a_scale_out) p.a_scale_out[m] = scale;
                 if (p.q_sum_out) p.q_sum_out[m] = qsum;
@@ -173,7 +181,20 @@ __global__ __launch_bounds__(kThreads, 8) void decode_kernel(BL_FIRST_WG_PARAMS,
         }
         int v = -qsum;
         for (int g = 0; g < G; ++g) v += red[((wave - ks + g) * M + m) * kWave + lane];
-        if (active && row < p.N) {
+        if constexpr (GLU) {
+            // lanes 0-31: gate rows, lanes 32-63: the up rows of the same 32 outputs (the whole wave is here: ks == 0)
+            const float val = (float)v * ((lane < 32 ? p.w_scale : p.w_scale2) * scale);
+            const float up = __shfl_xor(val, 32);
+            const int n = rb * 32 + (lane & 31);
+            float x = 0.0f;
+            if (lane < 32 && active && n < p.N / 2) {
+                x = silu(val) * up;
+                p.out[n] = x * p.glu_gamma[n];
+            }
+            const float ss = wave_sum_f(x * x);
+            if (lane == 0 && active) p.ss_out[rb] = ss;
+            if (p.acc && active && row < p.N) p.acc[row] = v;
+        } else if (active && row < p.N) {
             p.out[(int64_t)m * p.N + row] = (float)v * (p.w_scale * scale);
             if (p.acc) p.acc[(int64_t)m * p.N + row] = v;
         }
@@ -489,8 +510,17 @@ hipError_t launch_decode(const DecodeBatch& batch, int M, bool fused, hipStream_
     if (!fused) return launch_m<0, true>(b, M, lds, s);
     if (b.p[0].gamma) {   // RMSNorm folded into the quantizer: one token, fp32 rows (checked by the entry point)
         if (M != 1 || bf16) return hipErrorInvalidValue;
+        if (b.p[0].glu_gamma) {
+            static LdsCeiling ceiling;
+            return launch_kernel(&decode_kernel<1, true, false, 1, 1, true>, ceiling, b, lds, s);
+        }
         static LdsCeiling ceiling;
-        return launch_kernel(&decode_kernel<1, true, false, 1, true>, ceiling, b, lds, s);
+        return launch_kernel(&decode_kernel<1, true, false, 1, 1>, ceiling, b, lds, s);
+    }
+    if (b.p[0].ss_in) {   // the row is already multiplied by its norm weight; sum(x^2) in pieces
+        if (M != 1 || bf16) return hipErrorInvalidValue;
+        static LdsCeiling ceiling;
+        return launch_kernel(&decode_kernel<1, true, false, 1, 2>, ceiling, b, lds, s);
     }
     return bf16 ? launch_m<1, true>(b, M, lds, s) : launch_m<1, false>(b, M, lds, s);
 }

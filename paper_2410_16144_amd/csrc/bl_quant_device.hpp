@@ -44,6 +44,8 @@ __device__ __forceinline__ float wave_sum_f(float v) {   // a fixed tree: the sa
 }
 #undef BL_DPP
 
+__device__ __forceinline__ float silu(float t) { return t / (1.0f + expf(-t)); }
+
 // q = clip(round_half_even(v * inv), -128, 127)
 __device__ __forceinline__ int quant_one(float v, float inv) {
     float r = rintf(v * inv);

@@ -90,32 +90,65 @@ class Attention:
 
 class NormDecodeGroup:
     """A prepared bl_decode_norm_batch launch: RMSNorm (with an optional residual add) folded into the quantizer of
-    the products that consume the normalised row.  weights share x / delta / gamma; h_out receives x + delta."""
+    the products that consume the normalised row.  weights share x / delta / gamma; h_out receives x + delta.
 
-    def __init__(self, weights, x: torch.Tensor, gamma: torch.Tensor, eps: float = EPS, delta: Optional[torch.Tensor] = None,
-                 h_out: Optional[torch.Tensor] = None, want_acc: bool = False, want_quant: bool = False, use_workspace=True):
+    pieces (with gamma None): x is already multiplied by its norm weight and `pieces` holds sum(x^2) in parts (what a
+    gated launch leaves behind).  glu=(w_scale_up, glu_gamma): the one weight is gate and up interleaved
+    (pack_gate_up); the launch writes silu(gate) * up * glu_gamma to outs[0] ([1, F]) and the parts of
+    sum((silu(gate) * up)^2) to self.pieces ([F / 32])."""
+
+    def __init__(self, weights, x: torch.Tensor, gamma: Optional[torch.Tensor], eps: float = EPS,
+                 delta: Optional[torch.Tensor] = None, h_out: Optional[torch.Tensor] = None, want_acc: bool = False,
+                 want_quant: bool = False, use_workspace=True, pieces: Optional[torch.Tensor] = None, glu=None):
         assert 1 <= len(weights) <= B.BL_MAX_BATCH
         dev = x.device
         K = weights[0].K
         for t in (x, delta, h_out, gamma):
             assert t is None or (t.dtype == torch.float32 and t.numel() == K and t.is_contiguous())
-        assert all(w.K == K for w in weights)
+        assert all(w.K == K for w in weights) and (gamma is None) != (pieces is None)
         self.workspace_ptr = ops._workspace_ptr(use_workspace, dev)
-        self.outs = [torch.empty((1, w.N), dtype=torch.float32, device=dev) for w in weights]
+        if glu is not None:
+            assert len(weights) == 1 and weights[0].N % 64 == 0
+            w_scale_up, glu_gamma = glu
+            F = weights[0].N // 2
+            assert glu_gamma.dtype == torch.float32 and glu_gamma.numel() == F and glu_gamma.is_contiguous()
+            self.outs = [torch.empty((1, F), dtype=torch.float32, device=dev)]
+            self.pieces = torch.empty((F // 32,), dtype=torch.float32, device=dev)
+        else:
+            self.outs = [torch.empty((1, w.N), dtype=torch.float32, device=dev) for w in weights]
+            self.pieces = None
         self.accs = [torch.empty((1, w.N), dtype=torch.int32, device=dev) for w in weights] if want_acc else None
         self.quants = [ops.alloc_quant(1, K, dev) for _ in weights] if want_quant else None
-        self._keep = (weights, x, gamma, delta, h_out)
+        self._keep = (weights, x, gamma, delta, h_out, pieces, glu)
         ptr = lambda t: t.data_ptr() if t is not None else 0
-        self.items = B.make_decode_norm_items(
-            (x.data_ptr(), ptr(delta), ptr(h_out) if i == 0 else 0, gamma.data_ptr(), eps, w.blob.data_ptr(), w.desc,
-             self.outs[i].data_ptr(), self.accs[i].data_ptr() if want_acc else 0,
-             self.quants[i].q.data_ptr() if want_quant else 0, self.quants[i].a_scale.data_ptr() if want_quant else 0,
-             self.quants[i].q_sum.data_ptr() if want_quant else 0)
-            for i, w in enumerate(weights))
+        items = []
+        for i, w in enumerate(weights):
+            it = dict(x=x.data_ptr(), delta=ptr(delta), h_out=ptr(h_out) if i == 0 else 0, gamma=ptr(gamma), eps=eps,
+                      packed=w.blob.data_ptr(), desc=w.desc, out=self.outs[i].data_ptr(),
+                      acc=self.accs[i].data_ptr() if want_acc else 0)
+            if want_quant:
+                it.update(q=self.quants[i].q.data_ptr(), a_scale=self.quants[i].a_scale.data_ptr(),
+                          q_sum=self.quants[i].q_sum.data_ptr())
+            if pieces is not None:
+                it.update(ss_in=pieces.data_ptr(), ss_count=int(pieces.numel()))
+            if glu is not None:
+                it.update(w_scale_up=float(glu[0]), glu_gamma=glu[1].data_ptr(), ss_out=self.pieces.data_ptr())
+            items.append(it)
+        self.items = B.make_decode_norm_items(items)
 
     def launch(self):
         B.bl_decode_norm_batch(self.items, self.workspace_ptr, _stream())
         return self.outs
+
+
+def pack_gate_up(w_gate: torch.Tensor, w_up: torch.Tensor, s_gate: float) -> ops.PackedWeight:
+    """Gate and up projections ([F, K] int8 ternary each, F a multiple of 32) as ONE packed matrix of 2 F rows, interleaved
+    by 32: row block b holds gate rows 32 b .. 32 b + 31, then the up rows of the same outputs -- the operand of a gated
+    launch (NormDecodeGroup(glu=...)).  The descriptor carries the gate matrix's scale; the up matrix's goes with glu."""
+    F, K = w_gate.shape
+    assert w_up.shape == (F, K) and F % 32 == 0
+    both = torch.stack([w_gate.reshape(F // 32, 32, K), w_up.reshape(F // 32, 32, K)], dim=1).reshape(2 * F, K)
+    return ops.pack_ternary(both.contiguous(), s_gate)
 
 
 def can_fold_norm(K: int) -> bool:
@@ -124,11 +157,12 @@ def can_fold_norm(K: int) -> bool:
 
 @dataclass
 class LayerWeights:
-    proj: Dict[str, ops.PackedWeight]     # 'q','k','v','o','gate','up','down'
+    proj: Dict[str, ops.PackedWeight]     # 'q','k','v','o','gate','up','down'; optionally 'gate_up' (pack_gate_up)
     g_in: torch.Tensor
     g_attn: torch.Tensor
     g_post: torch.Tensor
     g_ffn: torch.Tensor
+    s_up: float = 0.0                     # the up matrix's scale, for 'gate_up'
 
 
 class DecoderLayer:
@@ -144,7 +178,7 @@ class DecoderLayer:
                  use_workspace=True, fold_norm: Optional[bool] = None):
         dev = h_in.device
         hidden = int(h_in.shape[1])
-        ffn = w.proj["gate"].N
+        ffn = w.proj["down"].K
         assert h_in.shape == (1, hidden) and h_alt.shape == (1, hidden) and hidden % n_heads == 0
         self.w, self.eps, self.delta_in = w, eps, delta_in
         self.fold = can_fold_norm(hidden) if fold_norm is None else fold_norm
@@ -157,21 +191,33 @@ class DecoderLayer:
                                        h_out=h_mid if delta_in is not None else None, use_workspace=use_workspace)
             self.attn = Attention(n_heads, hidden // n_heads, max_pos, *self.qkv.outs, pos, table)
             self.o = NormDecodeGroup([w.proj["o"]], self.attn.out, w.g_attn, eps, use_workspace=use_workspace)
-            self.gate_up = NormDecodeGroup([w.proj["gate"], w.proj["up"]], h_mid, w.g_post, eps, delta=self.o.outs[0],
-                                           h_out=self.h_out, use_workspace=use_workspace)
+            # the gated form: gate and up interleaved in one matrix, silu(gate) * up * g_ffn out of the launch's epilogue,
+            # and the down projection quantizes that row as it is (rows short enough to live in registers)
+            self.gated = "gate_up" in w.proj and can_fold_norm(ffn)
+            if self.gated:
+                self.gate_up = NormDecodeGroup([w.proj["gate_up"]], h_mid, w.g_post, eps, delta=self.o.outs[0],
+                                               h_out=self.h_out, use_workspace=use_workspace, glu=(w.s_up, w.g_ffn))
+                self.down = NormDecodeGroup([w.proj["down"]], self.gate_up.outs[0], None, eps,
+                                            pieces=self.gate_up.pieces, use_workspace=use_workspace)
+            else:
+                self.gate_up = NormDecodeGroup([w.proj["gate"], w.proj["up"]], h_mid, w.g_post, eps, delta=self.o.outs[0],
+                                               h_out=self.h_out, use_workspace=use_workspace)
         else:
+            assert "gate" in w.proj, "the layer holds gate and up interleaved only: that form needs the folded norm"
+            self.gated = False
             self.h, self.h_out = h_in, h_in                           # separate norm launches update the stream in place
             self.q1, self.q2, self.q3 = (ops.alloc_quant(1, hidden, dev) for _ in range(3))
             self.qkv = ops.GemvGroup([w.proj[n] for n in "qkv"], [self.q1] * 3, use_workspace=use_workspace)
             self.attn = Attention(n_heads, hidden // n_heads, max_pos, *self.qkv.outs, pos, table)
             self.o = ops.GemvGroup([w.proj["o"]], [self.q2], use_workspace=use_workspace)
             self.gate_up = ops.GemvGroup([w.proj["gate"], w.proj["up"]], [self.q3] * 2, use_workspace=use_workspace)
-        self.down = ops.GemvGroup([w.proj["down"]], [self.q4], use_workspace=use_workspace)
+        if not (self.fold and self.gated):
+            self.down = ops.GemvGroup([w.proj["down"]], [self.q4], use_workspace=use_workspace)
         self.delta_out = self.down.outs[0]
 
     def launch(self):
         w = self.w
-        if self.fold:      # 6 launches: three products with the norm in their quantizer, attention, gate, down
+        if self.fold:      # 5 launches with the gated form, else 6 (the gated norm on its own)
             self.qkv.launch()
             self.attn.launch()
             self.o.launch()
@@ -184,8 +230,9 @@ class DecoderLayer:
             self.o.launch()
             norm_quant(B.BL_NORM_RESIDUAL, w.g_post, self.eps, a=self.o.outs[0], h=self.h, out=self.q3)
             self.gate_up.launch()
-        norm_quant(B.BL_NORM_GATED, w.g_ffn, self.eps, a=self.gate_up.outs[0], b=self.gate_up.outs[1], out=self.q4,
-                   scratch=self.norm_scratch)
+        if not self.gated:
+            norm_quant(B.BL_NORM_GATED, w.g_ffn, self.eps, a=self.gate_up.outs[0], b=self.gate_up.outs[1], out=self.q4,
+                       scratch=self.norm_scratch)
         self.down.launch()
         return self.delta_out
 
@@ -264,7 +311,7 @@ class DecoderStack:
 
 
 def make_stack(name: str, max_pos: int, device, config: int = 7, n_layers: Optional[int] = None,
-               use_workspace=True) -> DecoderStack:
+               use_workspace=True, gated: bool = True) -> DecoderStack:
     """A dummy model of Appendix A's shape `name` (as in the paper: random ternary weights, drawn on the device from
     the seed rule of synth.seed_for), norm weights uniform in [0.5, 1.5]."""
     from . import synth
@@ -281,7 +328,16 @@ def make_stack(name: str, max_pos: int, device, config: int = 7, n_layers: Optio
             del wd
         g.manual_seed(synth.seed_for(config, i, 8))
         gam = [torch.rand(k, device=device, generator=g) + 0.5 for k in (hidden, hidden, hidden, ffn)]
-        ws.append(LayerWeights(proj, *gam))
+        s_up = 0.0
+        if gated and can_fold_norm(ffn) and can_fold_norm(hidden) and ffn % 32 == 0:
+            # the interleaved matrix replaces the two separate ones (same weights, drawn again from their seeds)
+            pj = {p.name: p for p in synth.layer_projections(hidden, ffn)}
+            wg = synth.ternary_weights_device(synth.seed_for(config, i, 4), pj["gate"].N, pj["gate"].K, device)
+            wu = synth.ternary_weights_device(synth.seed_for(config, i, 5), pj["up"].N, pj["up"].K, device)
+            proj["gate_up"] = pack_gate_up(wg, wu, proj["gate"].desc.w_scale)
+            s_up = float(proj["up"].desc.w_scale)
+            del wg, wu, proj["gate"], proj["up"]
+        ws.append(LayerWeights(proj, *gam, s_up=s_up))
     g.manual_seed(synth.seed_for(config, n_layers, 8))
     return DecoderStack(ws, torch.rand(hidden, device=device, generator=g) + 0.5, synth.PAPER_HEADS[name], max_pos, device,
                         use_workspace=use_workspace)

@@ -32,7 +32,7 @@ def test_struct_layout_matches_header():
     assert ctypes.sizeof(B.DecodeItem) == 80 and B.DecodeItem.packed_dev.offset == 24
     assert ctypes.sizeof(B.NormQuantArgs) == 104 and B.NormQuantArgs.eps.offset == 56 and B.NormQuantArgs.q_dev.offset == 64
     assert ctypes.sizeof(B.AttnArgs) == 88 and B.AttnArgs.n_heads.offset == 72
-    assert ctypes.sizeof(B.DecodeNormItem) == 96 and B.DecodeNormItem.packed_dev.offset == 40
+    assert ctypes.sizeof(B.DecodeNormItem) == 128 and B.DecodeNormItem.packed_dev.offset == 40 and B.DecodeNormItem.glu_gamma_dev.offset == 112
 
 
 def test_padding_and_descriptor():
@@ -230,20 +230,27 @@ def test_decoder_block_validation():
 def test_decode_norm_batch_validation():
     P = 0x10000
     d = B.bl_packed_desc_init(128, 256, 0.5)
-    ok = [P, P, P + 0x1000, P, 1e-5, P, d, P, 0, 0, 0, 0]
-    def call(i=None, v=None, desc=None, count_items=1, ws=0):
-        a = list(ok)
-        if i is not None:
-            a[i] = v
-        if desc is not None:
-            a[6] = desc
-        return _st(B.bl_decode_norm_batch, B.make_decode_norm_items([tuple(a)] * count_items), ws)
-    for i in (0, 3, 5, 7):
-        assert call(i, 0) == B.BL_ERR_NULL
-    assert call(2, P) == B.BL_ERR_SHAPE                                   # h_out on top of x (and of delta)
+    ok = dict(x=P, delta=P, h_out=P + 0x1000, gamma=P, eps=1e-5, packed=P, desc=d, out=P)
+    def call(count_items=1, ws=0, **kw):
+        return _st(B.bl_decode_norm_batch, B.make_decode_norm_items([dict(ok, **kw)] * count_items), ws)
+    for k in ("x", "packed", "out"):
+        assert call(**{k: 0}) == B.BL_ERR_NULL
+    assert call(gamma=0) == B.BL_ERR_NULL                                  # neither form of the norm
+    assert call(h_out=P) == B.BL_ERR_SHAPE                                 # h_out on top of x (and of delta)
     assert call(desc=B.bl_packed_desc_init(128, 100, 0.5)) == B.BL_ERR_SHAPE            # K not a multiple of 8
     assert call(desc=B.bl_packed_desc_init(128, B.BL_DECODE_NORM_MAX_K + 8, 0.5)) == B.BL_ERR_SHAPE
-    assert call(0, P + 8) == B.BL_ERR_ALIGN and call(3, P + 4) == B.BL_ERR_ALIGN and call(1, P + 4) == B.BL_ERR_ALIGN
+    assert call(x=P + 8) == B.BL_ERR_ALIGN and call(gamma=P + 4) == B.BL_ERR_ALIGN and call(delta=P + 4) == B.BL_ERR_ALIGN
     assert call(count_items=9) == B.BL_ERR_COUNT
     assert call(ws=P + 16) == B.BL_ERR_ALIGN
     assert call(desc=B.bl_tl2_desc_init(128, 256, 0.5)) == B.BL_ERR_LAYOUT
+    # the pre-multiplied row: no gamma, pieces instead; no residual add with it
+    pre = dict(gamma=0, delta=0, h_out=0, ss_in=P, ss_count=4)
+    assert call(**dict(pre, ss_count=0)) == B.BL_ERR_SHAPE
+    assert call(**dict(pre, delta=P)) == B.BL_ERR_SHAPE
+    assert call(ss_in=P, ss_count=4) == B.BL_ERR_SHAPE                     # both forms at once
+    assert call(**dict(pre, ss_in=P + 2)) == B.BL_ERR_ALIGN
+    # the gated epilogue: wants its pieces' destination and whole row blocks
+    assert call(glu_gamma=P) == B.BL_ERR_NULL
+    assert call(glu_gamma=P, ss_out=P, desc=B.bl_packed_desc_init(96, 256, 0.5)) == B.BL_ERR_SHAPE
+    mixed = B.make_decode_norm_items([dict(ok), dict(ok, glu_gamma=P, ss_out=P)])
+    assert _st(B.bl_decode_norm_batch, mixed, 0) == B.BL_ERR_SHAPE

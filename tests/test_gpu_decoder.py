@@ -244,11 +244,14 @@ def _make_layers(seed, hidden, ffn, n_layers):
     return layers, r.uniform(0.5, 1.5, hidden).astype(np.float32)
 
 
-def _to_device(layers, dev, dec, ops):
+def _to_device(layers, dev, dec, ops, gated=False):
     out = []
     for l in layers:
         proj = {n: ops.pack_ternary(_t(l[n], dev), float(l["s_" + n])) for n in ("q", "k", "v", "o", "gate", "up", "down")}
-        out.append(dec.LayerWeights(proj, *(_t(l[g], dev) for g in ("g_in", "g_attn", "g_post", "g_ffn"))))
+        if gated:
+            proj["gate_up"] = dec.pack_gate_up(_t(l["gate"], dev), _t(l["up"], dev), float(l["s_gate"]))
+        out.append(dec.LayerWeights(proj, *(_t(l[g], dev) for g in ("g_in", "g_attn", "g_post", "g_ffn")),
+                                    s_up=float(l["s_up"])))
     return out
 
 
@@ -389,18 +392,73 @@ def test_decode_norm_batch_zero_row(dev, mods):
     assert not out.any() and float(grp.quants[0].a_scale[0]) == 0.0 and not grp.quants[0].q.any()
 
 
+@pytest.mark.parametrize("K,F,with_delta", [(768, 3072, True), (4096, 12032, True), (1536, 4096, False), (64, 32, True),
+                                          (3200, 8640, True)])
+def test_gated_launch_and_its_consumer(dev, mods, K, F, with_delta):
+    """Gate and up interleaved in one matrix: the launch's epilogue leaves silu(gate) * up * g_ffn and the pieces of
+    sum((silu(gate) * up)^2); the down projection quantizes that row as it is.  Integer sums exact; the gate and up
+    values reproduced with the kernel's own two fp32 products; the rest within fp32 tolerance of the fp64 formulas."""
+    B, dec, ops = mods
+    r = _rng(81000 + K + F)
+    wg, wu, wd = synth.ternary_weights(r, F, K), synth.ternary_weights(r, F, K), synth.ternary_weights(r, 200, F)
+    sg, su, sd = (float(synth.draw_w_scale(r)) for _ in range(3))
+    x = synth.activations(r, 1, K, outlier_frac=0.01)
+    delta = synth.activations(r, 1, K) if with_delta else None
+    g_post, g_ffn = (r.uniform(0.5, 1.5, n).astype(np.float32) for n in (K, F))
+    pw = dec.pack_gate_up(_t(wg, dev), _t(wu, dev), sg)
+    assert pw.N == 2 * F
+    h_out = torch.empty((1, K), device=dev) if with_delta else None
+    up_grp = dec.NormDecodeGroup([pw], _t(x, dev), _t(g_post, dev), 1e-5, delta=_t(delta, dev) if with_delta else None,
+                                 h_out=h_out, want_acc=True, want_quant=True, glu=(su, _t(g_ffn, dev)))
+    z_t = up_grp.launch()[0]
+    down = dec.NormDecodeGroup([ops.pack_ternary(_t(wd, dev), sd)], z_t, None, 1e-5, pieces=up_grp.pieces, want_acc=True,
+                               want_quant=True)
+    out = down.launch()[0].cpu().numpy()[0]
+    torch.cuda.synchronize()
+    # the gated launch
+    xp = x + delta if with_delta else x
+    q, a_z, _ = oracle.quant_act(xp * g_post)
+    np.testing.assert_array_equal(up_grp.quants[0].q.cpu().numpy()[:, :K], q)
+    acc = up_grp.accs[0].cpu().numpy()[0].reshape(F // 32, 2, 32)
+    np.testing.assert_array_equal(acc[:, 0, :].reshape(F), oracle.matmul_i32(q, wg)[0])
+    np.testing.assert_array_equal(acc[:, 1, :].reshape(F), oracle.matmul_i32(q, wu)[0])
+    a_got = up_grp.quants[0].a_scale.cpu().numpy()[0]
+    gate = acc[:, 0, :].reshape(F).astype(np.float32) * (np.float32(sg) * a_got)      # the kernel's two fp32 products
+    up = acc[:, 1, :].reshape(F).astype(np.float32) * (np.float32(su) * a_got)
+    prod = D.gated_ffn_input(gate, up)
+    z = z_t.cpu().numpy()[0]
+    assert np.abs(z - prod * g_ffn).max() <= 3e-6 * np.abs(prod * g_ffn).max()
+    pieces = up_grp.pieces.cpu().numpy()
+    want_pieces = (prod ** 2).reshape(F // 32, 32).sum(axis=1)
+    assert np.all(np.abs(pieces - want_pieces) <= 1e-5 * want_pieces.max())
+    # the consumer: codes of z as it is, the scalar from the pieces
+    qz, az, sz = oracle.quant_act(z[None, :])
+    np.testing.assert_array_equal(down.quants[0].q.cpu().numpy()[:, :F], qz)
+    np.testing.assert_array_equal(down.quants[0].q_sum.cpu().numpy(), sz)
+    r64 = 1.0 / np.sqrt(np.sum(pieces.astype(np.float64)) / F + 1e-5)
+    a_d = float(down.quants[0].a_scale[0])
+    assert abs(a_d - float(az[0]) * r64) <= 3e-6 * float(az[0]) * r64
+    acc_d = oracle.matmul_i32(qz, wd)
+    np.testing.assert_array_equal(down.accs[0].cpu().numpy(), acc_d)
+    np.testing.assert_allclose(out, oracle.dequant(acc_d, np.float32(sd), np.float32([a_d]))[0], rtol=1e-6)
+    # ... and against the textbook order: normalise silu(gate) * up, then quantize -- codes differ at ties only
+    _codes_close(down.quants[0].q.cpu().numpy(), D.rmsnorm(prod, g_ffn, 1e-5), F)
+
+
 @pytest.mark.parametrize("hidden,ffn,n_heads,n_layers,use_graph,fold", [
     (768, 3072, 12, 2, False, True), (1536, 4096, 16, 2, True, True), (200, 328, 5, 3, True, True),
-    (768, 3072, 12, 2, False, False), (1536, 4096, 16, 3, True, False)])
+    (768, 3072, 12, 2, False, False), (1536, 4096, 16, 3, True, False), (768, 3072, 12, 2, True, "gated"),
+    (200, 320, 5, 3, False, "gated")])
 def test_token_loop_against_oracle(dev, mods, hidden, ffn, n_heads, n_layers, use_graph, fold):
     """Tokens through a small stack (125M- and 700M-shape layers of Appendix A): the final-normalised hidden state and
     the caches against the oracle's layer step, token after token; the captured graph gives the eager bits."""
     B, dec, ops = mods
     max_pos, n_tokens = 8, 5
     layers, g_final = _make_layers(61000 + hidden, hidden, ffn, n_layers)
-    stack = dec.DecoderStack(_to_device(layers, dev, dec, ops), _t(g_final, dev), n_heads, max_pos, dev, fold_norm=fold)
-    assert all(l.fold == fold for l in stack.layers)
-    eager = (dec.DecoderStack(_to_device(layers, dev, dec, ops), _t(g_final, dev), n_heads, max_pos, dev, fold_norm=fold)
+    gated, fold = fold == "gated", bool(fold)
+    stack = dec.DecoderStack(_to_device(layers, dev, dec, ops, gated), _t(g_final, dev), n_heads, max_pos, dev, fold_norm=fold)
+    assert all(l.fold == fold and l.gated == gated for l in stack.layers)
+    eager = (dec.DecoderStack(_to_device(layers, dev, dec, ops, gated), _t(g_final, dev), n_heads, max_pos, dev, fold_norm=fold)
              if use_graph else None)
     if use_graph:
         stack.capture()
