@@ -39,7 +39,12 @@ extern "C" {
 typedef enum bl_norm_mode {
     BL_NORM_PLAIN = 0,      /* x = a                                                  */
     BL_NORM_RESIDUAL = 1,   /* x = h + a (a may be NULL: x = h); h is overwritten by x */
-    BL_NORM_GATED = 2       /* x = silu(a) * b, silu(t) = t / (1 + exp(-t))            */
+    BL_NORM_GATED = 2,      /* x = silu(a) * b, silu(t) = t / (1 + exp(-t))            */
+    BL_NORM_PREMULTIPLIED = 3 /* a = x * gamma already, with `pieces` pairs (sum(x^2), max|a|) in
+                                 scratch_dev (what a gated bl_decode_norm_batch launch leaves)
+                                 FOLLOWED BY one 8-byte word that is zero before the first call
+                                 (every call leaves it zero; the slices' sum(q) meet in it):
+                                 y = a * r.  One token (M = 1), any K, one launch; gamma_dev unused */
 } bl_norm_mode;
 
 /*
@@ -81,6 +86,7 @@ typedef struct bl_norm_quant_args {
     int32_t     *q_sum_dev;
     float       *y_dev;
     void        *scratch_dev;
+    int32_t      pieces;        /* BL_NORM_PREMULTIPLIED: pairs (sum, max) at the head of scratch_dev */
 } bl_norm_quant_args;
 
 bl_status bl_norm_quant(const bl_norm_quant_args *args, void *stream);
@@ -111,13 +117,15 @@ bl_status bl_norm_quant(const bl_norm_quant_args *args, void *stream);
  *   the same 32 outputs (N = 2 F, F a multiple of 32; desc->w_scale is the gate matrix's scale, w_scale_up the up
  *   matrix's).  Instead of the 2 F products the launch writes
  *       out[n]    = silu(gate[n]) * up[n] * glu_gamma[n],   n < F      (out_dev: F floats)
- *       ss_out[b] = sum over n in [32 b, 32 b + 32) of (silu(gate[n]) * up[n])^2      (ss_out_dev: F / 32 floats)
+ *       ss_out[b] = (sum over n in [32 b, 32 b + 32) of (silu(gate[n]) * up[n])^2, max over them of |out[n]|)
+ *                                                             (ss_out_dev: F / 32 pairs of floats, 8-byte aligned)
  *   i.e. the feed-forward product already multiplied by the weight of the norm that follows it, and that norm's
- *   sum of squares in pieces.  acc_dev, if given, still receives the 2 F raw sums.
+ *   sum of squares (and the row's absmax) in pieces.  acc_dev, if given, still receives the 2 F raw sums.
  *
  *   Pre-multiplied row (gamma_dev == NULL, ss_in_dev != NULL): x_dev is such an `out`, ss_in_dev [ss_count] such
- *   pieces: the row is quantized as it is and r = 1 / sqrt(sum(pieces) / K + eps) multiplies the scale.
- *   delta_dev and h_out_dev must be NULL.
+ *   pairs: the row is quantized as it is and r = 1 / sqrt(sum of the pieces' sums / K + eps) multiplies the
+ *   scale.  delta_dev and h_out_dev must be NULL.  (A row too long for this entry point takes the same pieces
+ *   through bl_norm_quant, mode BL_NORM_PREMULTIPLIED, and bl_gemv_batch.)
  *
  * Errors: BL_ERR_NULL, BL_ERR_COUNT, BL_ERR_LAYOUT, BL_ERR_SHAPE (also K not a multiple of 8 or beyond
  *         BL_DECODE_NORM_MAX_K, h_out_dev equal to x_dev or delta_dev, items of different forms, N not a multiple

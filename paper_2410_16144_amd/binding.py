@@ -39,7 +39,7 @@ BL_NORM_MAX_K = 49152
 BL_NORM_SCRATCH_BYTES = 256
 BL_ATTN_MAX_HEAD_DIM = 256
 BL_ATTN_CHUNK = 64
-BL_NORM_PLAIN, BL_NORM_RESIDUAL, BL_NORM_GATED = 0, 1, 2
+BL_NORM_PLAIN, BL_NORM_RESIDUAL, BL_NORM_GATED, BL_NORM_PREMULTIPLIED = 0, 1, 2, 3
 BL_DECODE_NORM_MAX_K = 16384
 
 
@@ -87,7 +87,7 @@ class NormQuantArgs(ctypes.Structure):
                 ("a_dev", ctypes.c_void_p), ("b_dev", ctypes.c_void_p), ("h_dev", ctypes.c_void_p),
                 ("gamma_dev", ctypes.c_void_p), ("eps", ctypes.c_float), ("q_dev", ctypes.c_void_p),
                 ("a_scale_dev", ctypes.c_void_p), ("q_sum_dev", ctypes.c_void_p), ("y_dev", ctypes.c_void_p),
-                ("scratch_dev", ctypes.c_void_p)]
+                ("scratch_dev", ctypes.c_void_p), ("pieces", ctypes.c_int32)]
 
 
 class AttnArgs(ctypes.Structure):
@@ -308,9 +308,9 @@ def bl_tl2_gemv_batch(items, workspace_dev: int = 0, stream: int = 0):
 
 def make_norm_quant_args(mode: int, M: int, K: int, gamma_dev: int, eps: float, a_dev: int = 0, b_dev: int = 0,
                          h_dev: int = 0, q_dev: int = 0, a_scale_dev: int = 0, q_sum_dev: int = 0, Kp: int = 0,
-                         y_dev: int = 0, scratch_dev: int = 0) -> NormQuantArgs:
+                         y_dev: int = 0, scratch_dev: int = 0, pieces: int = 0) -> NormQuantArgs:
     return NormQuantArgs(mode, M, K, Kp, a_dev or None, b_dev or None, h_dev or None, gamma_dev or None, eps,
-                         q_dev or None, a_scale_dev or None, q_sum_dev or None, y_dev or None, scratch_dev or None)
+                         q_dev or None, a_scale_dev or None, q_sum_dev or None, y_dev or None, scratch_dev or None, pieces)
 
 
 def bl_norm_quant(args: NormQuantArgs, stream: int = 0):

@@ -328,16 +328,20 @@ bl_status bl_gemm(const void* packed_dev, const bl_packed_desc* d, const int8_t*
 }
 
 bl_status bl_norm_quant(const bl_norm_quant_args* a, void* stream) {
-    if (!a || !a->gamma_dev) return BL_ERR_NULL;
+    if (!a || (!a->gamma_dev && a->mode != BL_NORM_PREMULTIPLIED)) return BL_ERR_NULL;
     const bool quantize = a->q_dev != nullptr;
     if (quantize != (a->a_scale_dev != nullptr) || (!quantize && a->q_sum_dev)) return BL_ERR_NULL;
     switch (a->mode) {
         case BL_NORM_PLAIN: if (!a->a_dev) return BL_ERR_NULL; break;
         case BL_NORM_RESIDUAL: if (!a->h_dev) return BL_ERR_NULL; break;
         case BL_NORM_GATED: if (!a->a_dev || !a->b_dev) return BL_ERR_NULL; break;
+        case BL_NORM_PREMULTIPLIED:
+            if (!a->a_dev || !a->scratch_dev) return BL_ERR_NULL;
+            if (a->pieces < 1 || a->M != 1 || a->K > BL_MAX_K) return BL_ERR_SHAPE;
+            break;
         default: return BL_ERR_SHAPE;
     }
-    if (a->M < 1 || a->K < 1 || a->K > BL_NORM_MAX_K) return BL_ERR_SHAPE;
+    if (a->M < 1 || a->K < 1 || (a->K > BL_NORM_MAX_K && a->mode != BL_NORM_PREMULTIPLIED)) return BL_ERR_SHAPE;
     if (quantize && (a->Kp < a->K || a->Kp % 4 != 0 || a->Kp > BL_MAX_K)) return BL_ERR_SHAPE;
     if (!aligned(a->a_dev, 4) || !aligned(a->b_dev, 4) || !aligned(a->h_dev, 4) || !aligned(a->gamma_dev, 4) ||
         !aligned(a->q_dev, 4) || !aligned(a->a_scale_dev, 4) || !aligned(a->q_sum_dev, 4) || !aligned(a->y_dev, 4) ||
@@ -372,8 +376,8 @@ bl_status bl_decode_norm_batch(const bl_decode_norm_item* items, int32_t count, 
         if (it.glu_gamma_dev && it.desc->N % BL_TILE_N != 0) return BL_ERR_SHAPE;
         if (!aligned(it.x_dev, 16) || !aligned(it.gamma_dev, 16) || !aligned(it.delta_dev, 16) || !aligned(it.h_out_dev, 16) ||
             !aligned(it.packed_dev, 16) || !aligned(it.out_dev, 4) || !aligned(it.acc_dev, 4) || !aligned(it.q_dev, 16) ||
-            !aligned(it.a_scale_dev, 4) || !aligned(it.q_sum_dev, 4) || !aligned(it.ss_in_dev, 4) ||
-            !aligned(it.glu_gamma_dev, 4) || !aligned(it.ss_out_dev, 4))
+            !aligned(it.a_scale_dev, 4) || !aligned(it.q_sum_dev, 4) || !aligned(it.ss_in_dev, 8) ||
+            !aligned(it.glu_gamma_dev, 4) || !aligned(it.ss_out_dev, 8))
             return BL_ERR_ALIGN;
         bl::DecodeProblem& p = b.p[i];
         p = make_decode_problem(it.packed_dev, it.desc, it.out_dev, it.acc_dev);
@@ -387,10 +391,10 @@ bl_status bl_decode_norm_batch(const bl_decode_norm_item* items, int32_t count, 
         p.delta = it.delta_dev;
         p.h_out = it.h_out_dev;
         p.eps = it.eps;
-        p.ss_in = it.ss_in_dev;
+        p.ss_in = reinterpret_cast<const float2*>(it.ss_in_dev);
         p.ss_count = it.ss_count;
         p.glu_gamma = it.glu_gamma_dev;
-        p.ss_out = it.ss_out_dev;
+        p.ss_out = reinterpret_cast<float2*>(it.ss_out_dev);
         p.w_scale2 = it.w_scale_up;
         if (it.desc->Kp > max_Kp) max_Kp = it.desc->Kp;
     }

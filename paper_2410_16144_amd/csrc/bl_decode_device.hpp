@@ -297,9 +297,9 @@ __device__ __forceinline__ float norm_fold(Raw8<false>& r0, Raw8<false>& r1, con
 
 // The row arrives multiplied by its norm weight already and sum(x^2) in `count` pieces: this holder thread's share of
 // the pieces (the holder waves' shares then meet in LDS like the sums of norm_fold).
-__device__ __forceinline__ float norm_pieces(const float* __restrict__ pieces, int count, int tid, int holders) {
+__device__ __forceinline__ float norm_pieces(const float2* __restrict__ pieces, int count, int tid, int holders) {
     float ss = 0.0f;
-    for (int i = tid; i < count; i += holders) ss += pieces[i];
+    for (int i = tid; i < count; i += holders) ss += pieces[i].x;   // .y, the pieces' absmax, is for consumers that cannot hold the row
     return ss;
 }
 

@@ -38,6 +38,7 @@ struct NormArgs {
     int32_t*     q_sum;
     float*       y;
     float2*      scratch;   // wide form: per row kWideMaxSlices x (sum of squares, absmax of x * gamma)
+    int32_t      pieces;    // pre-multiplied form: pairs in scratch (read only)
     int32_t      K, Kp;
     float        eps;
 };
@@ -204,7 +205,7 @@ static_assert(kWideMaxSlices * sizeof(float2) <= BL_NORM_SCRATCH_BYTES, "a row's
 
 template <int MODE, bool VEC>
 __device__ __forceinline__ void wide_inputs(const NormArgs& p, int64_t row, int k, int K, bool second_pass, float (&x)[4]) {
-    if constexpr (MODE == BL_NORM_PLAIN) {
+    if constexpr (MODE == BL_NORM_PLAIN || MODE == BL_NORM_PREMULTIPLIED) {
         load4<VEC>(p.a + row, k, K, x);
     } else if constexpr (MODE == BL_NORM_RESIDUAL) {
         load4<VEC>(p.h + row, k, K, x);
@@ -261,12 +262,29 @@ __global__ __launch_bounds__(kWideThreads) void norm_wide_quant_kernel(const Nor
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
     const int K = p.K, slice = blockIdx.x, slices = gridDim.x;
     const int64_t row = (int64_t)blockIdx.y * K;
-    const float2* part = p.scratch + (int64_t)blockIdx.y * kWideMaxSlices;
     float total = 0.0f, amax_z = 0.0f;
-    for (int g = 0; g < slices; ++g) {      // the same order in every workgroup
-        const float2 f = part[g];
-        total += f.x;
-        amax_z = fmaxf(amax_z, f.y);
+    if constexpr (MODE == BL_NORM_PREMULTIPLIED) {
+        // the pieces of a gated launch, hundreds of them: every workgroup adds them up the same way (thread t takes
+        // pieces t, t + 256, ...; lanes, then waves) and so arrives at the same bits
+        __shared__ float s_tot[kWideThreads / kWave], s_amax[kWideThreads / kWave];
+        for (int i = tid; i < p.pieces; i += kWideThreads) {
+            const float2 f = p.scratch[i];
+            total += f.x;
+            amax_z = fmaxf(amax_z, f.y);
+        }
+        total = wave_sum_f(total);
+        amax_z = wave_max(amax_z);
+        if (lane == 0) { s_tot[wave] = total; s_amax[wave] = amax_z; }
+        __syncthreads();
+        total = (s_tot[0] + s_tot[1]) + (s_tot[2] + s_tot[3]);
+        amax_z = fmaxf(fmaxf(s_amax[0], s_amax[1]), fmaxf(s_amax[2], s_amax[3]));
+    } else {
+        const float2* part = p.scratch + (int64_t)blockIdx.y * kWideMaxSlices;
+        for (int g = 0; g < slices; ++g) {      // the same order in every workgroup
+            const float2 f = part[g];
+            total += f.x;
+            amax_z = fmaxf(amax_z, f.y);
+        }
     }
     const float r = 1.0f / sqrtf(total / (float)K + p.eps);
     float inv, scale;
@@ -276,13 +294,13 @@ __global__ __launch_bounds__(kWideThreads) void norm_wide_quant_kernel(const Nor
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
         const int k = slice * kWideSlice + (tid + i * kWideThreads) * 4;
-        float x[4], g[4];
-        load4<VEC>(p.gamma, k, K, g);
+        float x[4], g[4] = {1.0f, 1.0f, 1.0f, 1.0f};
+        if constexpr (MODE != BL_NORM_PREMULTIPLIED) load4<VEC>(p.gamma, k, K, g);
         wide_inputs<MODE, VEC>(p, row, k, K, true, x);
         uint32_t word = 0;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            x[j] = (x[j] * g[j]) * r;
+            x[j] = MODE == BL_NORM_PREMULTIPLIED ? x[j] * r : (x[j] * g[j]) * r;
             const int v = quant_one(x[j], inv);
             sum += v;
             word |= (uint32_t)(v & 0xff) << (8 * j);
@@ -297,9 +315,35 @@ __global__ __launch_bounds__(kWideThreads) void norm_wide_quant_kernel(const Nor
     if (lane == 0) s_sum[wave] = sum;
     __syncthreads();
     if (tid == 0) {
-        if (p.q_sum) atomicAdd(p.q_sum + blockIdx.y, (s_sum[0] + s_sum[1]) + (s_sum[2] + s_sum[3]));
+        const int part = (s_sum[0] + s_sum[1]) + (s_sum[2] + s_sum[3]);
+        if constexpr (MODE == BL_NORM_PREMULTIPLIED) {
+            // no earlier launch of this call could zero sum(q), so the slices meet in one 64-bit word behind the
+            // pieces: slice count in the high bits, signed sum in the low 40; the slice that completes the count
+            // writes the total and puts the word back to zero (it is zero before the first call)
+            if (p.q_sum) {
+                unsigned long long* word = reinterpret_cast<unsigned long long*>(p.scratch + p.pieces);
+                const unsigned long long add = (1ull << 40) + (unsigned long long)(long long)part;
+                const unsigned long long now =
+                    __hip_atomic_fetch_add(word, add, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + add;
+                const long long sum = (long long)(now << 24) >> 24;
+                if ((long long)((now - (unsigned long long)sum) >> 40) == slices) {
+                    p.q_sum[0] = (int)sum;
+                    __hip_atomic_store(word, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
+        } else if (p.q_sum) {
+            atomicAdd(p.q_sum + blockIdx.y, part);
+        }
         if (slice == 0) p.a_scale[blockIdx.y] = scale;
     }
+}
+
+// The pre-multiplied form: the figures of the first launch are there already (a gated product's epilogue left them).
+hipError_t launch_norm_premultiplied(const NormArgs& p, bool vec, hipStream_t s) {
+    const dim3 grid((unsigned)((p.K + kWideSlice - 1) / kWideSlice), 1u), block(kWideThreads);
+    if (vec) norm_wide_quant_kernel<BL_NORM_PREMULTIPLIED, true><<<grid, block, 0, s>>>(p);
+    else norm_wide_quant_kernel<BL_NORM_PREMULTIPLIED, false><<<grid, block, 0, s>>>(p);
+    return hipGetLastError();
 }
 
 template <int MODE>
@@ -578,6 +622,8 @@ hipError_t launch_norm_quant(const bl_norm_quant_args& a, hipStream_t s) {
     p.scratch = static_cast<float2*>(a.scratch_dev);
     auto ok16 = [](const void* ptr) { return (reinterpret_cast<uintptr_t>(ptr) & 15) == 0; };
     const bool vec = a.K % 4 == 0 && ok16(a.a_dev) && ok16(a.b_dev) && ok16(a.h_dev) && ok16(a.gamma_dev) && ok16(a.y_dev);
+    p.pieces = a.pieces;
+    if (a.mode == BL_NORM_PREMULTIPLIED) return launch_norm_premultiplied(p, vec, s);
     if (a.scratch_dev && a.K >= kWideMinK && a.M <= 65535) {
         switch (a.mode) {
             case BL_NORM_PLAIN: return launch_norm_wide<BL_NORM_PLAIN>(p, a.M, vec, s);

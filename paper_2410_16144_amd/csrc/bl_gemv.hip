@@ -186,13 +186,14 @@ __global__ __launch_bounds__(kThreads, 8) void decode_kernel(BL_FIRST_WG_PARAMS,
             const float val = (float)v * ((lane < 32 ? p.w_scale : p.w_scale2) * scale);
             const float up = __shfl_xor(val, 32);
             const int n = rb * 32 + (lane & 31);
-            float x = 0.0f;
+            float x = 0.0f, z = 0.0f;
             if (lane < 32 && active && n < p.N / 2) {
                 x = silu(val) * up;
-                p.out[n] = x * p.glu_gamma[n];
+                z = x * p.glu_gamma[n];
+                p.out[n] = z;
             }
-            const float ss = wave_sum_f(x * x);
-            if (lane == 0 && active) p.ss_out[rb] = ss;
+            const float ss = wave_sum_f(x * x), zmax = wave_max(fabsf(z));
+            if (lane == 0 && active) p.ss_out[rb] = make_float2(ss, zmax);
             if (p.acc && active && row < p.N) p.acc[row] = v;
         } else if (active && row < p.N) {
             p.out[(int64_t)m * p.N + row] = (float)v * (p.w_scale * scale);

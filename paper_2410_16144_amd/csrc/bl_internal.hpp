@@ -53,13 +53,13 @@ struct DecodeProblem {
     float*         h_out;        // optional [K]: receives x + delta (written by the problem's first workgroup)
     float          eps;
     // ... or the row arrives already multiplied by its norm weight, with sum(x^2) in pieces (the gated epilogue below)
-    const float*   ss_in;        // [ss_count] partial sums of squares; null unless this form
+    const float2*  ss_in;        // [ss_count] pieces (sum of squares, absmax) as the gated epilogue leaves them; null unless this form
     int32_t        ss_count;
     // gated epilogue (row-block kernel, one token): the matrix holds gate and up rows interleaved by 32, lanes 0-31 of a
     // row block the gate rows, lanes 32-63 the up rows of the same 32 outputs; out[n] = silu(gate) * up * glu_gamma[n],
-    // ss_out[row block] = sum over its 32 outputs of (silu(gate) * up)^2
+    // ss_out[row block] = (sum over its 32 outputs of (silu(gate) * up)^2, max over them of |out|)
     const float*   glu_gamma;    // [N / 2]; null: plain epilogue
-    float*         ss_out;       // [row_blocks]
+    float2*        ss_out;       // [row_blocks]
     float          w_scale2;     // the up rows' weight scale (w_scale: the gate rows')
 };
 

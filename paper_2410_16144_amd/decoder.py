@@ -33,25 +33,29 @@ def _stream() -> int:
     return torch.cuda.current_stream().cuda_stream
 
 
-def norm_quant(mode: int, gamma: torch.Tensor, eps: float = EPS, a: Optional[torch.Tensor] = None,
+def norm_quant(mode: int, gamma: Optional[torch.Tensor], eps: float = EPS, a: Optional[torch.Tensor] = None,
                b: Optional[torch.Tensor] = None, h: Optional[torch.Tensor] = None, out: Optional[ops.QuantAct] = None,
-               y: Optional[torch.Tensor] = None, quantize: bool = True, scratch: Optional[torch.Tensor] = None):
+               y: Optional[torch.Tensor] = None, quantize: bool = True, scratch: Optional[torch.Tensor] = None,
+               pieces: int = 0):
     """bl_norm_quant on [M,K] fp32 tensors.  Returns the QuantAct (None if quantize is False).  scratch: a uint8
     tensor of M * BL_NORM_SCRATCH_BYTES bytes lets long rows spread over several workgroups."""
     ref = h if mode == B.BL_NORM_RESIDUAL else a
     M, K = ref.shape
     for t in (a, b, h, y):
         assert t is None or (t.is_cuda and t.dtype == torch.float32 and t.shape == (M, K) and t.is_contiguous())
-    assert gamma.dtype == torch.float32 and gamma.shape == (K,) and gamma.is_contiguous()
-    assert scratch is None or scratch.numel() * scratch.element_size() >= M * B.BL_NORM_SCRATCH_BYTES
+    if mode == B.BL_NORM_PREMULTIPLIED:   # scratch: `pieces` pairs from a gated launch and the 8-byte word behind them
+        assert gamma is None and scratch.numel() * scratch.element_size() >= 8 * pieces + 8
+    else:
+        assert gamma.dtype == torch.float32 and gamma.shape == (K,) and gamma.is_contiguous()
+        assert scratch is None or scratch.numel() * scratch.element_size() >= M * B.BL_NORM_SCRATCH_BYTES
     if quantize and out is None:
         out = ops.alloc_quant(M, K, ref.device)
     ptr = lambda t: t.data_ptr() if t is not None else 0
     args = B.make_norm_quant_args(
-        mode, M, K, gamma.data_ptr(), eps, a_dev=ptr(a), b_dev=ptr(b), h_dev=ptr(h),
+        mode, M, K, ptr(gamma), eps, a_dev=ptr(a), b_dev=ptr(b), h_dev=ptr(h),
         q_dev=out.q.data_ptr() if quantize else 0, a_scale_dev=out.a_scale.data_ptr() if quantize else 0,
         q_sum_dev=out.q_sum.data_ptr() if quantize else 0, Kp=int(out.q.shape[1]) if quantize else 0, y_dev=ptr(y),
-        scratch_dev=ptr(scratch))
+        scratch_dev=ptr(scratch), pieces=pieces)
     B.bl_norm_quant(args, _stream())
     return out if quantize else None
 
@@ -93,9 +97,9 @@ class NormDecodeGroup:
     the products that consume the normalised row.  weights share x / delta / gamma; h_out receives x + delta.
 
     pieces (with gamma None): x is already multiplied by its norm weight and `pieces` holds sum(x^2) in parts (what a
-    gated launch leaves behind).  glu=(w_scale_up, glu_gamma): the one weight is gate and up interleaved
-    (pack_gate_up); the launch writes silu(gate) * up * glu_gamma to outs[0] ([1, F]) and the parts of
-    sum((silu(gate) * up)^2) to self.pieces ([F / 32])."""
+    gated launch leaves behind: its .pieces tensor).  glu=(w_scale_up, glu_gamma): the one weight is gate and up
+    interleaved (pack_gate_up); the launch writes silu(gate) * up * glu_gamma to outs[0] ([1, F]) and per 32 outputs
+    the pair (sum((silu(gate) * up)^2), max|out|) to self.pieces ([F / 32 + 1, 2]; the last row stays zero)."""
 
     def __init__(self, weights, x: torch.Tensor, gamma: Optional[torch.Tensor], eps: float = EPS,
                  delta: Optional[torch.Tensor] = None, h_out: Optional[torch.Tensor] = None, want_acc: bool = False,
@@ -113,7 +117,8 @@ class NormDecodeGroup:
             F = weights[0].N // 2
             assert glu_gamma.dtype == torch.float32 and glu_gamma.numel() == F and glu_gamma.is_contiguous()
             self.outs = [torch.empty((1, F), dtype=torch.float32, device=dev)]
-            self.pieces = torch.empty((F // 32,), dtype=torch.float32, device=dev)
+            # F / 32 pairs (sum of squares, absmax), then the zero word a long row's quantizer wants behind them
+            self.pieces = torch.zeros((F // 32 + 1, 2), dtype=torch.float32, device=dev)
         else:
             self.outs = [torch.empty((1, w.N), dtype=torch.float32, device=dev) for w in weights]
             self.pieces = None
@@ -130,7 +135,7 @@ class NormDecodeGroup:
                 it.update(q=self.quants[i].q.data_ptr(), a_scale=self.quants[i].a_scale.data_ptr(),
                           q_sum=self.quants[i].q_sum.data_ptr())
             if pieces is not None:
-                it.update(ss_in=pieces.data_ptr(), ss_count=int(pieces.numel()))
+                it.update(ss_in=pieces.data_ptr(), ss_count=int(pieces.shape[0]) - 1)
             if glu is not None:
                 it.update(w_scale_up=float(glu[0]), glu_gamma=glu[1].data_ptr(), ss_out=self.pieces.data_ptr())
             items.append(it)
@@ -193,12 +198,16 @@ class DecoderLayer:
             self.o = NormDecodeGroup([w.proj["o"]], self.attn.out, w.g_attn, eps, use_workspace=use_workspace)
             # the gated form: gate and up interleaved in one matrix, silu(gate) * up * g_ffn out of the launch's epilogue,
             # and the down projection quantizes that row as it is (rows short enough to live in registers)
-            self.gated = "gate_up" in w.proj and can_fold_norm(ffn)
+            self.gated = "gate_up" in w.proj
             if self.gated:
                 self.gate_up = NormDecodeGroup([w.proj["gate_up"]], h_mid, w.g_post, eps, delta=self.o.outs[0],
                                                h_out=self.h_out, use_workspace=use_workspace, glu=(w.s_up, w.g_ffn))
-                self.down = NormDecodeGroup([w.proj["down"]], self.gate_up.outs[0], None, eps,
-                                            pieces=self.gate_up.pieces, use_workspace=use_workspace)
+                self.down_folded = can_fold_norm(ffn)
+                if self.down_folded:
+                    self.down = NormDecodeGroup([w.proj["down"]], self.gate_up.outs[0], None, eps,
+                                                pieces=self.gate_up.pieces, use_workspace=use_workspace)
+                else:   # a row too long for the product's quantizer: one launch of its own, from the same pieces
+                    self.down = ops.GemvGroup([w.proj["down"]], [self.q4], use_workspace=use_workspace)
             else:
                 self.gate_up = NormDecodeGroup([w.proj["gate"], w.proj["up"]], h_mid, w.g_post, eps, delta=self.o.outs[0],
                                                h_out=self.h_out, use_workspace=use_workspace)
@@ -233,6 +242,9 @@ class DecoderLayer:
         if not self.gated:
             norm_quant(B.BL_NORM_GATED, w.g_ffn, self.eps, a=self.gate_up.outs[0], b=self.gate_up.outs[1], out=self.q4,
                        scratch=self.norm_scratch)
+        elif not self.down_folded:
+            norm_quant(B.BL_NORM_PREMULTIPLIED, None, self.eps, a=self.gate_up.outs[0], out=self.q4,
+                       scratch=self.gate_up.pieces, pieces=int(self.gate_up.pieces.shape[0]) - 1)
         self.down.launch()
         return self.delta_out
 
@@ -329,7 +341,7 @@ def make_stack(name: str, max_pos: int, device, config: int = 7, n_layers: Optio
         g.manual_seed(synth.seed_for(config, i, 8))
         gam = [torch.rand(k, device=device, generator=g) + 0.5 for k in (hidden, hidden, hidden, ffn)]
         s_up = 0.0
-        if gated and can_fold_norm(ffn) and can_fold_norm(hidden) and ffn % 32 == 0:
+        if gated and can_fold_norm(hidden) and ffn % 32 == 0:
             # the interleaved matrix replaces the two separate ones (same weights, drawn again from their seeds)
             pj = {p.name: p for p in synth.layer_projections(hidden, ffn)}
             wg = synth.ternary_weights_device(synth.seed_for(config, i, 4), pj["gate"].N, pj["gate"].K, device)

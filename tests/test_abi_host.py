@@ -30,7 +30,7 @@ def test_struct_layout_matches_header():
     assert ctypes.sizeof(B.GemvItem) == 56
     assert ctypes.sizeof(B.QuantItem) == 64 and B.QuantItem.q_dev.offset == 40
     assert ctypes.sizeof(B.DecodeItem) == 80 and B.DecodeItem.packed_dev.offset == 24
-    assert ctypes.sizeof(B.NormQuantArgs) == 104 and B.NormQuantArgs.eps.offset == 56 and B.NormQuantArgs.q_dev.offset == 64
+    assert ctypes.sizeof(B.NormQuantArgs) == 112 and B.NormQuantArgs.eps.offset == 56 and B.NormQuantArgs.q_dev.offset == 64
     assert ctypes.sizeof(B.AttnArgs) == 88 and B.AttnArgs.n_heads.offset == 72
     assert ctypes.sizeof(B.DecodeNormItem) == 128 and B.DecodeNormItem.packed_dev.offset == 40 and B.DecodeNormItem.glu_gamma_dev.offset == 112
 
@@ -198,7 +198,7 @@ def test_decoder_block_validation():
     assert norm(mode=B.BL_NORM_GATED, b_dev=0) == B.BL_ERR_NULL
     assert norm(a_scale_dev=0) == B.BL_ERR_NULL                      # q without its scale
     assert norm(q_dev=0, a_scale_dev=0) == B.BL_ERR_NULL             # q_sum without q
-    assert norm(mode=3) == B.BL_ERR_SHAPE
+    assert norm(mode=4) == B.BL_ERR_SHAPE
     assert norm(M=0) == B.BL_ERR_SHAPE
     assert norm(K=0) == B.BL_ERR_SHAPE
     assert norm(K=B.BL_NORM_MAX_K + 1, Kp=B.BL_NORM_MAX_K + 4) == B.BL_ERR_SHAPE
@@ -207,6 +207,9 @@ def test_decoder_block_validation():
     assert norm(a_dev=P + 2) == B.BL_ERR_ALIGN
     assert norm(q_dev=P + 1) == B.BL_ERR_ALIGN
     assert norm(scratch_dev=P + 4) == B.BL_ERR_ALIGN
+    pre = dict(mode=B.BL_NORM_PREMULTIPLIED, gamma_dev=0, scratch_dev=P, pieces=8)
+    assert norm(**dict(pre, scratch_dev=0)) == B.BL_ERR_NULL and norm(**dict(pre, pieces=0)) == B.BL_ERR_SHAPE
+    assert norm(**dict(pre, M=2)) == B.BL_ERR_SHAPE and norm(**dict(pre, a_dev=0)) == B.BL_ERR_NULL
     assert _st(B.bl_rope_table, 0, 64, 16, 10000.0) == B.BL_ERR_NULL
     assert _st(B.bl_rope_table, P, 63, 16, 10000.0) == B.BL_ERR_SHAPE
     assert _st(B.bl_rope_table, P, 64, 0, 10000.0) == B.BL_ERR_SHAPE
@@ -248,7 +251,7 @@ def test_decode_norm_batch_validation():
     assert call(**dict(pre, ss_count=0)) == B.BL_ERR_SHAPE
     assert call(**dict(pre, delta=P)) == B.BL_ERR_SHAPE
     assert call(ss_in=P, ss_count=4) == B.BL_ERR_SHAPE                     # both forms at once
-    assert call(**dict(pre, ss_in=P + 2)) == B.BL_ERR_ALIGN
+    assert call(**dict(pre, ss_in=P + 4)) == B.BL_ERR_ALIGN
     # the gated epilogue: wants its pieces' destination and whole row blocks
     assert call(glu_gamma=P) == B.BL_ERR_NULL
     assert call(glu_gamma=P, ss_out=P, desc=B.bl_packed_desc_init(96, 256, 0.5)) == B.BL_ERR_SHAPE

@@ -393,7 +393,7 @@ def test_decode_norm_batch_zero_row(dev, mods):
 
 
 @pytest.mark.parametrize("K,F,with_delta", [(768, 3072, True), (4096, 12032, True), (1536, 4096, False), (64, 32, True),
-                                          (3200, 8640, True)])
+                                          (3200, 8640, True), (512, 20000, True), (8192, 45568, False)])
 def test_gated_launch_and_its_consumer(dev, mods, K, F, with_delta):
     """Gate and up interleaved in one matrix: the launch's epilogue leaves silu(gate) * up * g_ffn and the pieces of
     sum((silu(gate) * up)^2); the down projection quantizes that row as it is.  Integer sums exact; the gate and up
@@ -411,9 +411,21 @@ def test_gated_launch_and_its_consumer(dev, mods, K, F, with_delta):
     up_grp = dec.NormDecodeGroup([pw], _t(x, dev), _t(g_post, dev), 1e-5, delta=_t(delta, dev) if with_delta else None,
                                  h_out=h_out, want_acc=True, want_quant=True, glu=(su, _t(g_ffn, dev)))
     z_t = up_grp.launch()[0]
-    down = dec.NormDecodeGroup([ops.pack_ternary(_t(wd, dev), sd)], z_t, None, 1e-5, pieces=up_grp.pieces, want_acc=True,
-                               want_quant=True)
-    out = down.launch()[0].cpu().numpy()[0]
+    pwd = ops.pack_ternary(_t(wd, dev), sd)
+    folded_down = dec.can_fold_norm(F)
+    if folded_down:
+        down = dec.NormDecodeGroup([pwd], z_t, None, 1e-5, pieces=up_grp.pieces, want_acc=True, want_quant=True)
+        out = down.launch()[0].cpu().numpy()[0]
+        down_q, down_acc = down.quants[0], down.accs[0]
+    else:   # a row too long for the product's quantizer: bl_norm_quant on the same pieces, twice (the word behind
+            # the pieces must be back at zero), then the plain product
+        y_t = torch.empty((1, F), device=dev)
+        for _ in range(2):
+            down_q = ops.alloc_quant(1, F, dev)
+            down_q.q_sum.fill_(777)
+            dec.norm_quant(B.BL_NORM_PREMULTIPLIED, None, 1e-5, a=z_t, out=down_q, y=y_t, scratch=up_grp.pieces, pieces=F // 32)
+        out_t, down_acc = ops.gemv(pwd, down_q, want_acc=True)
+        out = out_t.cpu().numpy()[0]
     torch.cuda.synchronize()
     # the gated launch
     xp = x + delta if with_delta else x
@@ -428,21 +440,30 @@ def test_gated_launch_and_its_consumer(dev, mods, K, F, with_delta):
     prod = D.gated_ffn_input(gate, up)
     z = z_t.cpu().numpy()[0]
     assert np.abs(z - prod * g_ffn).max() <= 3e-6 * np.abs(prod * g_ffn).max()
-    pieces = up_grp.pieces.cpu().numpy()
+    pairs = up_grp.pieces.cpu().numpy()
+    assert not pairs[-1].any()                                          # the word behind the pieces is (back at) zero
+    pieces, maxima = pairs[:-1, 0], pairs[:-1, 1]
     want_pieces = (prod ** 2).reshape(F // 32, 32).sum(axis=1)
     assert np.all(np.abs(pieces - want_pieces) <= 1e-5 * want_pieces.max())
-    # the consumer: codes of z as it is, the scalar from the pieces
-    qz, az, sz = oracle.quant_act(z[None, :])
-    np.testing.assert_array_equal(down.quants[0].q.cpu().numpy()[:, :F], qz)
-    np.testing.assert_array_equal(down.quants[0].q_sum.cpu().numpy(), sz)
+    np.testing.assert_array_equal(maxima, np.abs(z).reshape(F // 32, 32).max(axis=1))
     r64 = 1.0 / np.sqrt(np.sum(pieces.astype(np.float64)) / F + 1e-5)
-    a_d = float(down.quants[0].a_scale[0])
-    assert abs(a_d - float(az[0]) * r64) <= 3e-6 * float(az[0]) * r64
+    a_d = float(down_q.a_scale[0])
+    if folded_down:   # the consumer quantizes z as it is; the scalar from the pieces goes into the scale
+        qz, az, sz = oracle.quant_act(z[None, :])
+        assert abs(a_d - float(az[0]) * r64) <= 3e-6 * float(az[0]) * r64
+    else:             # ... or forms y = z * r and quantizes that: codes against the oracle's quantizer on the kernel's own y
+        y = y_t.cpu().numpy()
+        assert np.abs(y[0] - z.astype(np.float64) * r64).max() <= 3e-6 * np.abs(z).max() * r64
+        qz, az, sz = oracle.quant_act(y)
+        assert a_d == float(az[0])
+    np.testing.assert_array_equal(down_q.q.cpu().numpy()[:, :F], qz)
+    assert not down_q.q.cpu().numpy()[:, F:].any()
+    np.testing.assert_array_equal(down_q.q_sum.cpu().numpy(), sz)
     acc_d = oracle.matmul_i32(qz, wd)
-    np.testing.assert_array_equal(down.accs[0].cpu().numpy(), acc_d)
+    np.testing.assert_array_equal(down_acc.cpu().numpy(), acc_d)
     np.testing.assert_allclose(out, oracle.dequant(acc_d, np.float32(sd), np.float32([a_d]))[0], rtol=1e-6)
     # ... and against the textbook order: normalise silu(gate) * up, then quantize -- codes differ at ties only
-    _codes_close(down.quants[0].q.cpu().numpy(), D.rmsnorm(prod, g_ffn, 1e-5), F)
+    _codes_close(down_q.q.cpu().numpy(), D.rmsnorm(prod, g_ffn, 1e-5), F)
 
 
 @pytest.mark.parametrize("hidden,ffn,n_heads,n_layers,use_graph,fold", [
