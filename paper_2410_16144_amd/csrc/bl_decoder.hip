@@ -420,12 +420,11 @@ __device__ __forceinline__ float read_published(float* at) {
                                                   __HIP_MEMORY_SCOPE_AGENT));
 }
 
-template <bool ACROSS>   // ACROSS: the figures come from other workgroups of this launch
 __device__ __forceinline__ void attn_merge(const AttnArgs& p, int head, int used, float* s_f, float* s_red) {
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
     const int d = p.head_dim;
     float* base = p.scratch + (int64_t)head * p.chunks * (d + 2);
-    const auto src = [&](int i) { return ACROSS ? read_published(base + i) : base[i]; };
+    const auto src = [&](int i) { return read_published(base + i); };
     float m = -INFINITY;
     for (int c = tid; c < used; c += kAttnThreads) m = fmaxf(m, src(c * (d + 2) + d));
     for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
@@ -557,9 +556,9 @@ __global__ __launch_bounds__(kAttnThreads) void attn_chunk_kernel(const AttnArgs
     const bool alone = used == 1;                       // uniform
     float* dst = p.scratch + ((int64_t)head * p.chunks + chunk) * (d + 2);
     unsigned int sink = 0;
+    __shared__ float s_l;
     const auto publish = [&](float* at, float v) {
-        if (alone) *at = v;
-        else sink ^= __hip_atomic_exchange(reinterpret_cast<unsigned int*>(at), __float_as_uint(v), __ATOMIC_RELAXED,
+        sink ^= __hip_atomic_exchange(reinterpret_cast<unsigned int*>(at), __float_as_uint(v), __ATOMIC_RELAXED,
                                            __HIP_MEMORY_SCOPE_AGENT);
     };
     if (tid < kWave) {                                  // wave 0: one row per lane
@@ -574,8 +573,12 @@ __global__ __launch_bounds__(kAttnThreads) void attn_chunk_kernel(const AttnArgs
         s_w[tid] = w;
         const float l = wave_sum_f(w);
         if (tid == 0) {
-            publish(dst + d, m);
-            publish(dst + d + 1, l);
+            if (alone) {
+                s_l = l;        // the only chunk: its sum divides the weighted values below, nothing is deposited
+            } else {
+                publish(dst + d, m);
+                publish(dst + d + 1, l);
+            }
         }
     }
     __syncthreads();
@@ -590,21 +593,19 @@ __global__ __launch_bounds__(kAttnThreads) void attn_chunk_kernel(const AttnArgs
     if (tid < d) {
         float t = 0.0f;
         for (int q = 0; q < parts; ++q) t += s_o[q * d + tid];
-        publish(dst + tid, t);
+        if (alone) p.out[head * d + tid] = t / s_l;
+        else publish(dst + tid, t);
     }
+    if (alone) return;                                  // uniform
     __shared__ unsigned int s_ticket;
     if (tid == 0) s_ticket = sink;                      // a use of the returned values: the deposits are returning atomics
     __syncthreads();                                    // every wave waits for its memory operations here, so the deposits
                                                         // have all returned (and s_o, s_w have been read)
-    if (alone) {
-        attn_merge<false>(p, head, 1, s_o, s_w);
-        return;
-    }
     unsigned int* counter = reinterpret_cast<unsigned int*>(p.scratch + (int64_t)p.n_heads * p.chunks * (d + 2)) + head;
     if (tid == 0) s_ticket = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
     if (s_ticket != (unsigned)(used - 1)) return;       // uniform
-    attn_merge<true>(p, head, used, s_o, s_w);
+    attn_merge(p, head, used, s_o, s_w);
     if (tid == 0) __hip_atomic_store(counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 

@@ -113,9 +113,10 @@ __global__ __launch_bounds__(kThreads, 8) void decode_kernel(BL_FIRST_WG_PARAMS,
                         if (lane == 0) s_ss[wave] = ss;
                     }
                 }
-                if (!folded && NORM != 1) load_part(ks, 0, kInFlight / 2);
+                // (the waves that hold gamma and delta as well have no registers for early tiles; the others do)
+                if (!folded) load_part(ks, 0, kInFlight / 2);
                 quantize_row_from_regs<XBF16>(r0, r1, h0, h1, k0, k1, holders, p.K, Kp, lds_q, s_f, s_i, tid, lane, wave);
-                load_part(ks, NORM == 1 ? 0 : kInFlight / 2, kInFlight);
+                load_part(ks, folded ? 0 : kInFlight / 2, kInFlight);
             }
         } else {
             // general form: quantize first (its loads would otherwise have to wait for the weight tiles too)
