@@ -597,6 +597,9 @@ def main():
             torch.cuda.empty_cache()
         extra["prefill"] = [extra_prefill(torch, m, k, n, use_graph) for m in (512, 2048)
                             for (k, n) in ((4096, 11008), (11008, 4096))]
+        torch.cuda.empty_cache()
+        # whole-model token rate, the paper's own unit, on three of Appendix A's shapes (all twelve: --only tokens)
+        extra["decoder_tokens"] = extra_decoder_tokens(torch, ["700M", "7B", "30B"])
         result["extra"] = extra
 
     print(json.dumps(result))
