@@ -529,3 +529,30 @@ def test_stack_refuses_a_token_beyond_the_cache(dev, mods):
     stack.step()
     torch.cuda.synchronize()
     assert int(stack.pos[0]) == 2
+
+
+def test_long_token_loop_graph_equals_eager_across_chunk_boundaries(dev, mods):
+    """140 tokens through a small stack, as replays of one captured graph and as eager launches: the same bits on
+    every token, across the 64- and 128-row chunk boundaries of the attention kernel (whose per-head ticket counters
+    must be back at zero after every launch), and finite throughout."""
+    B, dec, ops = mods
+    hidden, ffn, n_heads, n_layers, max_pos, n_tokens = 256, 512, 4, 2, 160, 140
+    layers, g_final = _make_layers(66000, hidden, ffn, n_layers)
+    a = dec.DecoderStack(_to_device(layers, dev, dec, ops, True), _t(g_final, dev), n_heads, max_pos, dev)
+    b = dec.DecoderStack(_to_device(layers, dev, dec, ops, True), _t(g_final, dev), n_heads, max_pos, dev)
+    a.capture()
+    x = torch.randn((n_tokens, 1, hidden), device=dev, generator=torch.Generator(device=dev).manual_seed(5))
+    for t in range(n_tokens):
+        a.h.copy_(x[t])
+        b.h.copy_(x[t])
+        ya, yb = a.step(), b.step()
+        if t in (0, 63, 64, 65, 127, 128, 129, n_tokens - 1):
+            torch.cuda.synchronize()
+            assert torch.equal(ya, yb) and bool(torch.isfinite(ya).all()), t
+    torch.cuda.synchronize()
+    for la, lb in zip(a.layers, b.layers):
+        assert torch.equal(la.attn.k_cache.view(torch.int16), lb.attn.k_cache.view(torch.int16))
+        assert torch.equal(la.attn.v_cache.view(torch.int16), lb.attn.v_cache.view(torch.int16))
+        counters = la.attn.scratch[-4 * n_heads:].view(torch.int32)
+        assert not counters.any()
+    assert int(a.pos[0]) == n_tokens == int(b.pos[0])
