@@ -233,6 +233,10 @@ typedef struct {
  * BL_ERR_DTYPE).  `workspace_dev`: as for bl_gemv_batch (may be NULL).
  * Limit: M * Kp (+ 5 KiB per token) must fit the kernel's 128 KiB of
  * on-chip memory, else BL_ERR_SHAPE; use the two-call sequence then.
+ * Every workgroup quantizes all M rows for itself, so the saving shrinks as M
+ * grows: measured on MI355X (7B-shape layer) the fused launch wins up to
+ * M = 2, is even at 4 and loses at 8 (28.8 against 18.1 us) to
+ * bl_quant_act_batch + bl_gemv_batch.
  * Pointer alignment as for bl_quant_act / bl_gemv.
  * Errors: BL_ERR_NULL, BL_ERR_COUNT, BL_ERR_M_RANGE, BL_ERR_DTYPE,
  *         BL_ERR_LAYOUT, BL_ERR_SHAPE, BL_ERR_BUF_SMALL, BL_ERR_ALIGN, BL_ERR_HIP.
