@@ -4,15 +4,17 @@ include/bitlinear_decoder.h plus the launch sequence of a layer.
 Every arithmetic step runs in the library's kernels; this module owns buffers (torch tensors) and
 the order of the launches:
 
-    decode_norm_batch(q, k, v)   h' = h + delta of the previous layer; the three products of rmsnorm(h', g_in)
-    attn_decode                  rotary embedding, cache append, attention
-    decode_norm_batch(o)         the product of rmsnorm(attention output, g_attn)
-    decode_norm_batch(gate, up)  h'' = h' + o; the two products of rmsnorm(h'', g_post)
-    norm_quant(GATED, g_ffn)     q4 = quantize(rmsnorm(silu(gate) * up))
-    gemv_batch(down)             -> delta for the next layer
+    decode_norm_batch(q, k, v)    h' = h + delta of the previous layer; the three products of rmsnorm(h', g_in)
+    attn_decode                   rotary embedding, cache append, attention
+    decode_norm_batch(o)          the product of rmsnorm(attention output, g_attn)
+    decode_norm_batch(gate_up)    h'' = h' + o; gate and up (interleaved in one matrix) of rmsnorm(h'', g_post); the
+                                  epilogue leaves z = silu(gate) * up * g_ffn and the pieces of sum((silu(gate) * up)^2)
+    decode_norm_batch(down)       the product of z quantized as it is, the norm's scalar from the pieces
+                                  -> delta for the next layer
 
-(6 launches; rows that the folded form does not take -- over 16384 elements or not a multiple of 8 -- go through
-bl_norm_quant + bl_gemv_batch instead: 9 launches.)
+(5 launches.  A feed-forward row over 16384 elements is quantized by bl_norm_quant from the same pieces, in front of a
+plain bl_gemv_batch: 6.  Layers whose gate and up matrices are packed separately run bl_norm_quant on silu(gate) * up
+instead: 6; hidden sizes that the folded form does not take go through bl_norm_quant + bl_gemv_batch throughout: 9.)
 
 Shapes follow Appendix A of arXiv 2410.16144 (hidden size, intermediate size, layers, heads); the block
 itself is the LLaMA-like one of BitNet b1.58, which the paper does not spell out.
