@@ -557,7 +557,7 @@ def main():
                    "spread_over_replays": spread},
         "roofline": {"bound": "hbm", "achieved": round(value, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(value / HBM_PEAK_GBS, 4), "traffic": load_traffic("decode_kernel_3b_layer_m1"),
-                     "kernel": "decode_sk_kernel<8, true, true, 1> (fused quantize + 7 GEMVs of one layer per launch, "
+                     "kernel": "decode_sk_kernel<8, true, true, 1, 0> (fused quantize + 7 GEMVs of one layer per launch, "
                                "equal tile shares per workgroup)",
                      "avg_launch_us": round(kernel_us, 3), "bytes_per_launch": packed_bytes},
     }
