@@ -463,6 +463,36 @@ def extra_decoder_tokens(torch, models, max_pos=512, tokens=64):
     return rows
 
 
+def decoder_cpu_baseline(name="700M", seconds=5.0):
+    """The decoder oracle as it stands (numpy fp64 around the C oracle's products), timed on the host on ONE layer of
+    the `name` shape, token after token for about `seconds`; the whole model is that times its layer count."""
+    import numpy as np
+    import oracle
+    from oracle import decoder as D
+    from paper_2410_16144_amd import synth
+    hidden, ffn, n_layers = synth.PAPER_MODELS[name]
+    r = synth.rng_for(synth.seed_for(7, 0, 0))
+    layer = {}
+    for p in synth.layer_projections(hidden, ffn):
+        layer[p.name] = synth.ternary_weights(r, p.N, p.K)
+        layer["s_" + p.name] = synth.draw_w_scale(r)
+    for g, k in (("g_in", hidden), ("g_attn", hidden), ("g_post", hidden), ("g_ffn", ffn)):
+        layer[g] = r.uniform(0.5, 1.5, k)
+    max_pos = 64
+    kc, vc = np.zeros((max_pos, hidden)), np.zeros((max_pos, hidden))
+    h = r.standard_normal(hidden)
+    D.decoder_layer_step(h, 0, layer, kc, vc, synth.PAPER_HEADS[name])
+    n, t0 = 0, time.perf_counter()
+    while time.perf_counter() - t0 < seconds:
+        D.decoder_layer_step(h, 1 + n % (max_pos - 1), layer, kc, vc, synth.PAPER_HEADS[name])
+        n += 1
+    dt = time.perf_counter() - t0
+    return {"model": name, "kind": "oracle", "cores": oracle.num_threads(), "ms_per_layer": round(dt / n * 1e3, 3),
+            "tokens_per_s_whole_model": round(n / dt / n_layers, 2),
+            "sample": "%d tokens through one %s-shape layer (positions 1..%d, again and again), %.1f s of CPU work; x %d "
+                      "layers" % (n, name, max_pos - 1, dt, n_layers)}
+
+
 def extra_full_100b(torch, use_graph):
     """All 80 layers of the 100B-shape model resident (36.99 GB packed); one token = 80 fused launches."""
     from paper_2410_16144_amd.decode_layer import make_layer
@@ -519,7 +549,8 @@ def main():
                 "paper100b": lambda: extra_decode_shape(torch, "Appendix-A 100B", 8192, 45568, 1, 6, 120, use_graph),
                 "config1": lambda: extra_config1(torch, use_graph),
                 "appendixa": lambda: extra_appendix_a(torch, use_graph),
-                "tokens": lambda: extra_decoder_tokens(torch, args.models.split(",") if args.models else None),
+                "tokens": lambda: {"gpu": extra_decoder_tokens(torch, args.models.split(",") if args.models else None),
+                                   "cpu_baseline": None if args.no_cpu else decoder_cpu_baseline()},
                 "tl2": lambda: extra_tl2(torch, use_graph),
                 }[args.only]()
         print(json.dumps({args.only: sect}))
