@@ -477,6 +477,13 @@ __global__ __launch_bounds__(kAttnThreads) void attn_chunk_kernel(const AttnArgs
     const int head = blockIdx.x, chunk = blockIdx.y;
     const int d = p.head_dim, half = d / 2;
     const int hidden = p.n_heads * d;
+    // the token's projections do not depend on the position: requested before the position is waited for
+    float qa = 0.0f, qb = 0.0f, ka = 0.0f, kb = 0.0f, va = 0.0f, vb = 0.0f;
+    if (tid < half) {
+        qa = p.q_lin[head * d + tid]; qb = p.q_lin[head * d + tid + half];
+        ka = p.k_lin[head * d + tid]; kb = p.k_lin[head * d + tid + half];
+        va = p.v_lin[head * d + tid]; vb = p.v_lin[head * d + tid + half];
+    }
     const int pos = *p.pos;
     if (pos < 0 || pos >= p.max_pos) return;            // uniform
     const int j0 = chunk * kChunk;
@@ -503,13 +510,11 @@ __global__ __launch_bounds__(kAttnThreads) void attn_chunk_kernel(const AttnArgs
     const float scale = 1.0f / sqrtf((float)d);
     if (tid < half) {
         const float2 cs = p.rope[(int64_t)pos * half + tid];
-        const float a = p.q_lin[head * d + tid], b = p.q_lin[head * d + tid + half];
-        s_q[tid] = (a * cs.x - b * cs.y) * scale;
-        s_q[tid + half] = (a * cs.y + b * cs.x) * scale;
+        s_q[tid] = (qa * cs.x - qb * cs.y) * scale;
+        s_q[tid + half] = (qa * cs.y + qb * cs.x) * scale;
         if (owner) {
-            const float ka = p.k_lin[head * d + tid], kb = p.k_lin[head * d + tid + half];
             const uint16_t k0 = f32_to_bf16(ka * cs.x - kb * cs.y), k1 = f32_to_bf16(ka * cs.y + kb * cs.x);
-            const uint16_t v0 = f32_to_bf16(p.v_lin[head * d + tid]), v1 = f32_to_bf16(p.v_lin[head * d + tid + half]);
+            const uint16_t v0 = f32_to_bf16(va), v1 = f32_to_bf16(vb);
             uint16_t* krow = p.k_cache + (int64_t)pos * hidden + head * d;
             uint16_t* vrow = p.v_cache + (int64_t)pos * hidden + head * d;
             krow[tid] = k0; krow[tid + half] = k1;
