@@ -41,7 +41,7 @@ def parse_args():
     ap.add_argument("--full-100b", action="store_true",
                     help="extra: build all 80 layers of the 100B-shape model (37 GB packed) and time a whole token")
     ap.add_argument("--models", default="", help="with --only tokens: comma-separated Appendix-A model names (default: all 12)")
-    ap.add_argument("--only", default="", help="run only one extra section (copy|prefill|decode7b|decode100b|paper100b|config1|appendixa|tokens|tl2) and print it")
+    ap.add_argument("--only", default="", help="run only one extra section (copy|prefill|decode7b|decode100b|paper100b|config1|appendixa|tokens|prompt|tl2) and print it")
     return ap.parse_args()
 
 
@@ -463,6 +463,33 @@ def extra_decoder_tokens(torch, models, max_pos=512, tokens=64):
     return rows
 
 
+def extra_prompt(torch, models, M=512, max_pos=1024):
+    """Prompt processing through the same decoder block: M tokens at once, every product one bl_gemm over the M rows,
+    attention as bl_attn_prefill (eager launches).  Prompt tokens per second, first at positions 0..M-1, then for a
+    second piece at M..2M-1."""
+    from paper_2410_16144_amd import decoder, synth
+    dev = torch.device("cuda:0")
+    rows = []
+    for name in models or ["700M", "7B"]:
+        hidden, ffn, n_layers = synth.PAPER_MODELS[name]
+        stack = decoder.make_stack(name, max_pos, dev, gated=False)
+        x = torch.randn((2 * M, hidden), device=dev, generator=torch.Generator(device=dev).manual_seed(2))
+        row = {"model": name, "hidden": hidden, "ffn": ffn, "layers": n_layers, "prompt_tokens": M}
+        for label, start in (("positions_0", 0), ("positions_%d" % M, M)):
+            piece = x[start:start + M].contiguous()
+            stack.set_position(start)
+            stack.prefill(piece)           # untimed pass
+            stack.set_position(start)
+            ms, wall = timed(torch, lambda: stack.prefill(piece))
+            assert bool(torch.isfinite(stack.layers[-1].attn.v_cache[start + M - 1].float()).all())
+            row[label] = {"ms": round(ms, 3), "prompt_tokens_per_s": round(M * 1e3 / ms, 1),
+                          "us_per_layer": round(ms * 1e3 / n_layers, 1), "wall_ms": round(wall, 3)}
+        rows.append(row)
+        del stack
+        torch.cuda.empty_cache()
+    return rows
+
+
 def decoder_cpu_baseline(name="700M", seconds=5.0):
     """The decoder oracle as it stands (numpy fp64 around the C oracle's products), timed on the host on ONE layer of
     the `name` shape, token after token for about `seconds`; the whole model is that times its layer count."""
@@ -551,6 +578,7 @@ def main():
                 "appendixa": lambda: extra_appendix_a(torch, use_graph),
                 "tokens": lambda: {"gpu": extra_decoder_tokens(torch, args.models.split(",") if args.models else None),
                                    "cpu_baseline": None if args.no_cpu else decoder_cpu_baseline()},
+                "prompt": lambda: extra_prompt(torch, args.models.split(",") if args.models else None),
                 "tl2": lambda: extra_tl2(torch, use_graph),
                 }[args.only]()
         print(json.dumps({args.only: sect}))

@@ -207,6 +207,40 @@ uint64_t bl_attn_scratch_bytes(int32_t n_heads, int32_t head_dim, int32_t max_po
 
 bl_status bl_attn_decode(const bl_attn_args *args, void *stream);
 
+/*
+ * Attention for M consecutive tokens at positions pos0 .. pos0 + M - 1 (a prompt, or a piece of one): token m attends
+ * to cache rows 0 .. pos0 + m.  Two launches: the M keys (rotated) and values go into the cache, rounded to bf16 as
+ * bl_attn_decode rounds them; then one bl_attn_decode-style workgroup per (head, 64 cache rows, token).  Per token
+ * the results are those of M bl_attn_decode calls in order.
+ *   q_lin_dev, k_lin_dev, v_lin_dev   [M, n_heads * head_dim] fp32, rows contiguous
+ *   out_dev                           [M, n_heads * head_dim] fp32
+ *   pos0, M                           host values; 0 <= pos0, pos0 + M <= max_pos, 1 <= M <= 65535
+ *   scratch_dev                       bl_attn_prefill_scratch_bytes(...) bytes, 16-byte aligned, zero-filled before
+ *                                     the first call (every call leaves its counters zero)
+ *   rope_table_dev, k_cache_dev, v_cache_dev, n_heads, head_dim, max_pos: as in bl_attn_args
+ * Errors: BL_ERR_NULL, BL_ERR_SHAPE, BL_ERR_ALIGN, BL_ERR_HIP.
+ */
+typedef struct bl_attn_prefill_args {
+    const float *q_lin_dev;
+    const float *k_lin_dev;
+    const float *v_lin_dev;
+    const float *rope_table_dev;
+    uint16_t    *k_cache_dev;
+    uint16_t    *v_cache_dev;
+    float       *out_dev;
+    void        *scratch_dev;
+    int32_t      n_heads;
+    int32_t      head_dim;
+    int32_t      max_pos;
+    int32_t      pos0;
+    int32_t      M;
+} bl_attn_prefill_args;
+
+/* Bytes of bl_attn_prefill_args.scratch_dev for tokens pos0 .. pos0 + M - 1; 0 if a shape is out of range. */
+uint64_t bl_attn_prefill_scratch_bytes(int32_t n_heads, int32_t head_dim, int32_t pos0, int32_t M);
+
+bl_status bl_attn_prefill(const bl_attn_prefill_args *args, void *stream);
+
 /* *pos_dev += 1 on the device (one thread), so that the token loop's position lives in the
  * graph's own memory.  Errors: BL_ERR_NULL, BL_ERR_ALIGN, BL_ERR_HIP. */
 bl_status bl_pos_advance(int32_t *pos_dev, void *stream);

@@ -32,7 +32,7 @@ DECLARED_SYMBOLS = (
     "bl_padded_k", "bl_padded_n", "bl_packed_desc_init", "bl_pack_ternary", "bl_unpack_ternary",
     "bl_quant_act", "bl_quant_act_batch", "bl_gemv", "bl_gemv_batch", "bl_decode_batch", "bl_gemm", "bl_set_tuning", "bl_get_stat", "bl_status_str", "bl_last_hip_error", "bl_version",
     "bl_tl2_padded_k", "bl_tl2_desc_init", "bl_tl2_pack", "bl_tl2_unpack", "bl_tl2_gemv", "bl_tl2_gemv_batch",
-    "bl_norm_quant", "bl_rope_table", "bl_attn_scratch_bytes", "bl_attn_decode", "bl_pos_advance", "bl_decode_norm_batch",
+    "bl_norm_quant", "bl_rope_table", "bl_attn_scratch_bytes", "bl_attn_decode", "bl_pos_advance", "bl_decode_norm_batch", "bl_attn_prefill", "bl_attn_prefill_scratch_bytes",
 )
 
 BL_NORM_MAX_K = 49152
@@ -108,6 +108,14 @@ class DecodeNormItem(ctypes.Structure):
                 ("glu_gamma_dev", ctypes.c_void_p), ("ss_out_dev", ctypes.c_void_p)]
 
 
+class AttnPrefillArgs(ctypes.Structure):
+    """Mirror of bl_attn_prefill_args."""
+    _fields_ = [("q_lin_dev", ctypes.c_void_p), ("k_lin_dev", ctypes.c_void_p), ("v_lin_dev", ctypes.c_void_p),
+                ("rope_table_dev", ctypes.c_void_p), ("k_cache_dev", ctypes.c_void_p), ("v_cache_dev", ctypes.c_void_p),
+                ("out_dev", ctypes.c_void_p), ("scratch_dev", ctypes.c_void_p), ("n_heads", ctypes.c_int32),
+                ("head_dim", ctypes.c_int32), ("max_pos", ctypes.c_int32), ("pos0", ctypes.c_int32), ("M", ctypes.c_int32)]
+
+
 _lib = None
 
 
@@ -153,6 +161,9 @@ def lib():
     l.bl_attn_decode.argtypes = [ctypes.POINTER(AttnArgs), vp]
     l.bl_pos_advance.argtypes = [vp, vp]
     l.bl_decode_norm_batch.argtypes = [ctypes.POINTER(DecodeNormItem), i32, vp, vp]
+    l.bl_attn_prefill.argtypes = [ctypes.POINTER(AttnPrefillArgs), vp]
+    l.bl_attn_prefill_scratch_bytes.argtypes = [i32, i32, i32, i32]
+    l.bl_attn_prefill_scratch_bytes.restype = ctypes.c_uint64
     l.bl_set_tuning.argtypes = [ctypes.c_char_p, i32]
     l.bl_get_stat.argtypes = [ctypes.c_char_p]
     l.bl_get_stat.restype = i64
@@ -163,7 +174,7 @@ def lib():
     for name in ("bl_packed_desc_init", "bl_pack_ternary", "bl_unpack_ternary", "bl_quant_act", "bl_quant_act_batch", "bl_gemv",
                  "bl_gemv_batch", "bl_decode_batch", "bl_gemm", "bl_set_tuning", "bl_tl2_desc_init", "bl_tl2_pack",
                  "bl_tl2_unpack", "bl_tl2_gemv", "bl_tl2_gemv_batch", "bl_norm_quant", "bl_rope_table", "bl_attn_decode",
-                 "bl_pos_advance", "bl_decode_norm_batch"):
+                 "bl_pos_advance", "bl_decode_norm_batch", "bl_attn_prefill"):
         getattr(l, name).restype = ctypes.c_int
     _lib = l
     return l
@@ -334,6 +345,17 @@ def make_attn_args(q_lin_dev: int, k_lin_dev: int, v_lin_dev: int, pos_dev: int,
 
 def bl_attn_decode(args: AttnArgs, stream: int = 0):
     _check(lib().bl_attn_decode(ctypes.byref(args), stream), "bl_attn_decode")
+
+
+def bl_attn_prefill_scratch_bytes(n_heads: int, head_dim: int, pos0: int, M: int) -> int:
+    return int(lib().bl_attn_prefill_scratch_bytes(n_heads, head_dim, pos0, M))
+
+
+def bl_attn_prefill(q_lin_dev: int, k_lin_dev: int, v_lin_dev: int, rope_table_dev: int, k_cache_dev: int, v_cache_dev: int,
+                    out_dev: int, scratch_dev: int, n_heads: int, head_dim: int, max_pos: int, pos0: int, M: int, stream: int = 0):
+    args = AttnPrefillArgs(q_lin_dev or None, k_lin_dev or None, v_lin_dev or None, rope_table_dev or None, k_cache_dev or None,
+                           v_cache_dev or None, out_dev or None, scratch_dev or None, n_heads, head_dim, max_pos, pos0, M)
+    _check(lib().bl_attn_prefill(ctypes.byref(args), stream), "bl_attn_prefill")
 
 
 def bl_pos_advance(pos_dev: int, stream: int = 0):

@@ -438,6 +438,30 @@ bl_status bl_attn_decode(const bl_attn_args* a, void* stream) {
     return hip_status(bl::launch_attn_decode(*a, static_cast<hipStream_t>(stream)));
 }
 
+static bool prefill_shape_ok(int32_t n_heads, int32_t head_dim, int32_t pos0, int32_t M) {
+    return pos0 >= 0 && M >= 1 && M <= 65535 && (int64_t)pos0 + M <= INT32_MAX / 2 && attn_shape_ok(n_heads, head_dim, pos0 + M);
+}
+
+uint64_t bl_attn_prefill_scratch_bytes(int32_t n_heads, int32_t head_dim, int32_t pos0, int32_t M) {
+    if (!prefill_shape_ok(n_heads, head_dim, pos0, M)) return 0;
+    const uint64_t per_query = (uint64_t)n_heads * (uint64_t)bl::attn_chunks(pos0 + M) * (uint64_t)(head_dim + 2) + (uint64_t)n_heads;
+    return per_query * (uint64_t)M * sizeof(float);
+}
+
+bl_status bl_attn_prefill(const bl_attn_prefill_args* a, void* stream) {
+    if (!a || !a->q_lin_dev || !a->k_lin_dev || !a->v_lin_dev || !a->rope_table_dev || !a->k_cache_dev || !a->v_cache_dev ||
+        !a->out_dev || !a->scratch_dev)
+        return BL_ERR_NULL;
+    if (!prefill_shape_ok(a->n_heads, a->head_dim, a->pos0, a->M) || !attn_shape_ok(a->n_heads, a->head_dim, a->max_pos) ||
+        a->pos0 + a->M > a->max_pos)
+        return BL_ERR_SHAPE;
+    if (!aligned(a->q_lin_dev, 4) || !aligned(a->k_lin_dev, 4) || !aligned(a->v_lin_dev, 4) || !aligned(a->rope_table_dev, 8) ||
+        !aligned(a->k_cache_dev, 16) || !aligned(a->v_cache_dev, 16) || !aligned(a->out_dev, 4) || !aligned(a->scratch_dev, 16))
+        return BL_ERR_ALIGN;
+    drop_stale_hip_error();
+    return hip_status(bl::launch_attn_prefill(*a, static_cast<hipStream_t>(stream)));
+}
+
 bl_status bl_pos_advance(int32_t* pos_dev, void* stream) {
     if (!pos_dev) return BL_ERR_NULL;
     if (!aligned(pos_dev, 4)) return BL_ERR_ALIGN;

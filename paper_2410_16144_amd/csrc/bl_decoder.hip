@@ -387,8 +387,12 @@ struct AttnArgs {
     uint16_t*      k_cache;
     uint16_t*      v_cache;
     float*         out;
-    float*         scratch;     // [n_heads][chunks][head_dim + 2]: weighted values, running maximum, weight sum
+    float*         scratch;     // per query [n_heads][chunks][head_dim + 2] (weighted values, maximum, sum), then n_heads counters
     int32_t        n_heads, head_dim, max_pos, chunks;
+    // several consecutive tokens (a prompt): pos is null, query z has position pos0 + z, its own row of q_lin and out
+    // and its own part of scratch; keys and values are in the cache already (kv_append_kernel)
+    int32_t        pos0;
+    int64_t        scratch_stride;   // floats per query
 };
 
 __device__ __forceinline__ uint16_t f32_to_bf16(float f) {   // nearest, ties to even; finite inputs
@@ -420,10 +424,11 @@ __device__ __forceinline__ float read_published(float* at) {
                                                   __HIP_MEMORY_SCOPE_AGENT));
 }
 
-__device__ __forceinline__ void attn_merge(const AttnArgs& p, int head, int used, float* s_f, float* s_red) {
+__device__ __forceinline__ void attn_merge(const AttnArgs& p, float* scratch, float* out, int head, int used, float* s_f,
+                                           float* s_red) {
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
     const int d = p.head_dim;
-    float* base = p.scratch + (int64_t)head * p.chunks * (d + 2);
+    float* base = scratch + (int64_t)head * p.chunks * (d + 2);
     const auto src = [&](int i) { return read_published(base + i); };
     float m = -INFINITY;
     for (int c = tid; c < used; c += kAttnThreads) m = fmaxf(m, src(c * (d + 2) + d));
@@ -452,7 +457,7 @@ __device__ __forceinline__ void attn_merge(const AttnArgs& p, int head, int used
             for (int i = 0; i < n; ++i) o += s_f[i] * src((c0 + i) * (d + 2) + tid);
         }
     }
-    if (tid < d) p.out[head * d + tid] = o / l;
+    if (tid < d) out[head * d + tid] = o / l;
 }
 
 // One (head, chunk of 64 cache rows) per workgroup.  The chunk's keys and values (64 x head_dim bf16 each) are
@@ -477,19 +482,26 @@ __global__ __launch_bounds__(kAttnThreads) void attn_chunk_kernel(const AttnArgs
     const int head = blockIdx.x, chunk = blockIdx.y;
     const int d = p.head_dim, half = d / 2;
     const int hidden = p.n_heads * d;
+    const int query = blockIdx.z;                       // 0 unless a prompt's tokens are processed together
+    const bool appended = p.pos == nullptr;             // uniform: the prompt form, keys and values already cached
+    const float* q_lin = p.q_lin + (int64_t)query * hidden;
+    float* out = p.out + (int64_t)query * hidden;
+    float* scratch = p.scratch + (int64_t)query * p.scratch_stride;
     // the token's projections do not depend on the position: requested before the position is waited for
     float qa = 0.0f, qb = 0.0f, ka = 0.0f, kb = 0.0f, va = 0.0f, vb = 0.0f;
     if (tid < half) {
-        qa = p.q_lin[head * d + tid]; qb = p.q_lin[head * d + tid + half];
-        ka = p.k_lin[head * d + tid]; kb = p.k_lin[head * d + tid + half];
-        va = p.v_lin[head * d + tid]; vb = p.v_lin[head * d + tid + half];
+        qa = q_lin[head * d + tid]; qb = q_lin[head * d + tid + half];
+        if (!appended) {
+            ka = p.k_lin[head * d + tid]; kb = p.k_lin[head * d + tid + half];
+            va = p.v_lin[head * d + tid]; vb = p.v_lin[head * d + tid + half];
+        }
     }
-    const int pos = *p.pos;
+    const int pos = appended ? p.pos0 + query : *p.pos;
     if (pos < 0 || pos >= p.max_pos) return;            // uniform
     const int j0 = chunk * kChunk;
     if (j0 > pos) return;                               // uniform: nothing cached this far yet
     const int rows = min(kChunk, pos + 1 - j0);
-    const bool owner = pos < j0 + kChunk;               // uniform: this chunk holds the token's own row
+    const bool owner = !appended && pos < j0 + kChunk;  // uniform: this chunk holds the row this launch appends
     const int lanes_per_row = d / W;
     const int total = kChunk * lanes_per_row;           // a multiple of 64: the guards below are uniform per wave
 
@@ -530,7 +542,7 @@ __global__ __launch_bounds__(kAttnThreads) void attn_chunk_kernel(const AttnArgs
         const int v = tid + i * kAttnThreads;
         if (v < total) {
             const int row = v / lanes_per_row, c = v - row * lanes_per_row;
-            const bool own = j0 + row == pos;
+            const bool own = owner && j0 + row == pos;   // this launch appends that row: its values are in LDS
             float k[W];
             unpack_bf16<W>(kv[i], k);
             float acc = 0.0f;
@@ -559,7 +571,7 @@ __global__ __launch_bounds__(kAttnThreads) void attn_chunk_kernel(const AttnArgs
     // (a device-wide fence here cost 8-35 us per layer).
     const int used = pos / kChunk + 1;                  // workgroups of this head that get this far
     const bool alone = used == 1;                       // uniform
-    float* dst = p.scratch + ((int64_t)head * p.chunks + chunk) * (d + 2);
+    float* dst = scratch + ((int64_t)head * p.chunks + chunk) * (d + 2);
     unsigned int sink = 0;
     __shared__ float s_l;
     const auto publish = [&](float* at, float v) {
@@ -598,7 +610,7 @@ __global__ __launch_bounds__(kAttnThreads) void attn_chunk_kernel(const AttnArgs
     if (tid < d) {
         float t = 0.0f;
         for (int q = 0; q < parts; ++q) t += s_o[q * d + tid];
-        if (alone) p.out[head * d + tid] = t / s_l;
+        if (alone) out[head * d + tid] = t / s_l;
         else publish(dst + tid, t);
     }
     if (alone) return;                                  // uniform
@@ -606,12 +618,31 @@ __global__ __launch_bounds__(kAttnThreads) void attn_chunk_kernel(const AttnArgs
     if (tid == 0) s_ticket = sink;                      // a use of the returned values: the deposits are returning atomics
     __syncthreads();                                    // every wave waits for its memory operations here, so the deposits
                                                         // have all returned (and s_o, s_w have been read)
-    unsigned int* counter = reinterpret_cast<unsigned int*>(p.scratch + (int64_t)p.n_heads * p.chunks * (d + 2)) + head;
+    unsigned int* counter = reinterpret_cast<unsigned int*>(scratch + (int64_t)p.n_heads * p.chunks * (d + 2)) + head;
     if (tid == 0) s_ticket = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
     if (s_ticket != (unsigned)(used - 1)) return;       // uniform
-    attn_merge(p, head, used, s_o, s_w);
+    attn_merge(p, scratch, out, head, used, s_o, s_w);
     if (tid == 0) __hip_atomic_store(counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// A prompt's keys and values into the cache, ahead of its attention: one (token, head) per workgroup, the rotation and
+// rounding of attn_chunk_kernel's own append.
+__global__ __launch_bounds__(128) void kv_append_kernel(const AttnArgs p) {
+    const int tid = threadIdx.x, token = blockIdx.x, head = blockIdx.y;
+    const int d = p.head_dim, half = d / 2, hidden = p.n_heads * d;
+    const int pos = p.pos0 + token;
+    if (tid >= half || pos < 0 || pos >= p.max_pos) return;
+    const float2 cs = p.rope[(int64_t)pos * half + tid];
+    const float* k_lin = p.k_lin + (int64_t)token * hidden + head * d;
+    const float* v_lin = p.v_lin + (int64_t)token * hidden + head * d;
+    const float ka = k_lin[tid], kb = k_lin[tid + half];
+    uint16_t* krow = p.k_cache + (int64_t)pos * hidden + head * d;
+    uint16_t* vrow = p.v_cache + (int64_t)pos * hidden + head * d;
+    krow[tid] = f32_to_bf16(ka * cs.x - kb * cs.y);
+    krow[tid + half] = f32_to_bf16(ka * cs.y + kb * cs.x);
+    vrow[tid] = f32_to_bf16(v_lin[tid]);
+    vrow[tid + half] = f32_to_bf16(v_lin[tid + half]);
 }
 
 __global__ void pos_advance_kernel(int32_t* pos) {
@@ -663,8 +694,33 @@ hipError_t launch_attn_decode(const bl_attn_args& a, hipStream_t s) {
     p.k_cache = a.k_cache_dev; p.v_cache = a.v_cache_dev; p.out = a.out_dev;
     p.scratch = static_cast<float*>(a.scratch_dev);
     p.n_heads = a.n_heads; p.head_dim = a.head_dim; p.max_pos = a.max_pos; p.chunks = attn_chunks(a.max_pos);
+    p.pos0 = 0; p.scratch_stride = 0;
     if (a.head_dim % 8 == 0) attn_chunk_kernel<8><<<dim3((unsigned)a.n_heads, (unsigned)p.chunks), dim3(kAttnThreads), 0, s>>>(p);
     else attn_chunk_kernel<4><<<dim3((unsigned)a.n_heads, (unsigned)p.chunks), dim3(kAttnThreads), 0, s>>>(p);
+    return hipGetLastError();
+}
+
+int64_t attn_scratch_floats(int n_heads, int head_dim, int max_pos) {   // per query
+    return (int64_t)n_heads * attn_chunks(max_pos) * (head_dim + 2) + n_heads;
+}
+
+hipError_t launch_attn_prefill(const bl_attn_prefill_args& a, hipStream_t s) {
+    AttnArgs p;
+    p.q_lin = a.q_lin_dev; p.k_lin = a.k_lin_dev; p.v_lin = a.v_lin_dev; p.pos = nullptr;
+    p.rope = reinterpret_cast<const float2*>(a.rope_table_dev);
+    p.k_cache = a.k_cache_dev; p.v_cache = a.v_cache_dev; p.out = a.out_dev;
+    p.scratch = static_cast<float*>(a.scratch_dev);
+    p.n_heads = a.n_heads; p.head_dim = a.head_dim; p.max_pos = a.max_pos;
+    p.pos0 = a.pos0;
+    // a prompt's queries never look beyond its last token: chunks up to that one only
+    p.chunks = attn_chunks(a.pos0 + a.M);
+    p.scratch_stride = (int64_t)a.n_heads * p.chunks * (a.head_dim + 2) + a.n_heads;
+    kv_append_kernel<<<dim3((unsigned)a.M, (unsigned)a.n_heads), dim3(128), 0, s>>>(p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const dim3 grid((unsigned)a.n_heads, (unsigned)p.chunks, (unsigned)a.M);
+    if (a.head_dim % 8 == 0) attn_chunk_kernel<8><<<grid, dim3(kAttnThreads), 0, s>>>(p);
+    else attn_chunk_kernel<4><<<grid, dim3(kAttnThreads), 0, s>>>(p);
     return hipGetLastError();
 }
 

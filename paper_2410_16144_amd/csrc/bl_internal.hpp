@@ -143,6 +143,7 @@ hipError_t launch_rope_table(float* table, int head_dim, int max_pos, double the
 int attn_chunks(int max_pos);
 hipError_t launch_attn_decode(const ::bl_attn_args& a, hipStream_t s);
 hipError_t launch_pos_advance(int32_t* pos, hipStream_t s);
+hipError_t launch_attn_prefill(const ::bl_attn_prefill_args& a, hipStream_t s);
 
 // Launch-shape overrides for experiments (0 = choose automatically).
 void set_gemv_waves(int waves);

@@ -257,3 +257,21 @@ def test_decode_norm_batch_validation():
     assert call(glu_gamma=P, ss_out=P, desc=B.bl_packed_desc_init(96, 256, 0.5)) == B.BL_ERR_SHAPE
     mixed = B.make_decode_norm_items([dict(ok), dict(ok, glu_gamma=P, ss_out=P)])
     assert _st(B.bl_decode_norm_batch, mixed, 0) == B.BL_ERR_SHAPE
+
+
+def test_attn_prefill_validation():
+    P = 0x10000
+    ok = [P] * 8 + [4, 64, 100, 10, 20]
+    def call(i, v):
+        a = list(ok)
+        a[i] = v
+        return _st(B.bl_attn_prefill, *a)
+    for i in range(8):
+        assert call(i, 0) == B.BL_ERR_NULL
+    assert call(8, 0) == B.BL_ERR_SHAPE and call(9, 62) == B.BL_ERR_SHAPE and call(12, 0) == B.BL_ERR_SHAPE
+    assert call(11, -1) == B.BL_ERR_SHAPE and call(11, 90) == B.BL_ERR_SHAPE            # pos0 + M beyond the cache
+    assert call(4, P + 8) == B.BL_ERR_ALIGN and call(7, P + 4) == B.BL_ERR_ALIGN
+    assert B.bl_attn_prefill_scratch_bytes(4, 64, 10, 20) == 20 * (4 * 1 * 66 + 4) * 4
+    assert B.bl_attn_prefill_scratch_bytes(4, 64, 60, 10) == 10 * (4 * 2 * 66 + 4) * 4
+    assert B.bl_attn_prefill_scratch_bytes(4, 64, 0, 0) == 0 and B.bl_attn_prefill_scratch_bytes(4, 62, 0, 5) == 0
+    assert ctypes.sizeof(B.AttnPrefillArgs) == 88

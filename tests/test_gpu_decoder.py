@@ -556,3 +556,87 @@ def test_long_token_loop_graph_equals_eager_across_chunk_boundaries(dev, mods):
         counters = la.attn.scratch[-4 * n_heads:].view(torch.int32)
         assert not counters.any()
     assert int(a.pos[0]) == n_tokens == int(b.pos[0])
+
+
+@pytest.mark.parametrize("n_heads,head_dim,max_pos,pos0,M", [(3, 64, 300, 0, 70), (3, 64, 300, 130, 100), (20, 128, 80, 5, 9),
+                                                           (5, 40, 70, 0, 70), (2, 256, 200, 63, 2)])
+def test_attn_prefill_parity(dev, mods, n_heads, head_dim, max_pos, pos0, M):
+    """A prompt's attention: token m against cache rows 0 .. pos0 + m.  The appended rows as in the one-token call; every
+    token's output against the fp64 softmax over the cache as stored; and bit for bit what M one-token calls give."""
+    B, dec, ops = mods
+    hidden = n_heads * head_dim
+    r = _rng(95000 + hidden + M)
+    table = dec.rope_table(head_dim, max_pos, dev)
+    kc = _bf16(r.standard_normal((max_pos, hidden)))
+    vc = _bf16(r.standard_normal((max_pos, hidden)))
+    lin = [3.0 * r.standard_normal((M, hidden)).astype(np.float32) for _ in range(3)]
+    lin_t = [_t(v, dev) for v in lin]
+    k_cache = _bits_as_bf16_tensor(synth.to_bf16_bits(kc), dev).clone()
+    v_cache = _bits_as_bf16_tensor(synth.to_bf16_bits(vc), dev).clone()
+    out = torch.empty((M, hidden), device=dev)
+    scratch = torch.zeros(B.bl_attn_prefill_scratch_bytes(n_heads, head_dim, pos0, M), dtype=torch.uint8, device=dev)
+    for _ in range(2):   # twice: the counters in the scratch memory must be back at zero
+        B.bl_attn_prefill(lin_t[0].data_ptr(), lin_t[1].data_ptr(), lin_t[2].data_ptr(), table.data_ptr(), k_cache.data_ptr(),
+                          v_cache.data_ptr(), out.data_ptr(), scratch.data_ptr(), n_heads, head_dim, max_pos, pos0, M,
+                          torch.cuda.current_stream().cuda_stream)
+    # the same tokens one at a time
+    one = [torch.empty((1, hidden), device=dev) for _ in range(3)]
+    pos_t = torch.zeros(1, dtype=torch.int32, device=dev)
+    att = dec.Attention(n_heads, head_dim, max_pos, *one, pos_t, table)
+    att.k_cache.copy_(_bits_as_bf16_tensor(synth.to_bf16_bits(kc), dev))
+    att.v_cache.copy_(_bits_as_bf16_tensor(synth.to_bf16_bits(vc), dev))
+    outs = []
+    for m in range(M):
+        for t, v in zip(one, lin_t):
+            t.copy_(v[m:m + 1])
+        pos_t.fill_(pos0 + m)
+        outs.append(att.launch().clone())
+    torch.cuda.synchronize()
+    assert torch.equal(k_cache.view(torch.int16), att.k_cache.view(torch.int16))
+    assert torch.equal(v_cache.view(torch.int16), att.v_cache.view(torch.int16))
+    assert torch.equal(out, torch.cat(outs))
+    assert not scratch.view(torch.int32).view(M, -1)[:, -n_heads:].any()
+    kc64, vc64 = k_cache.float().cpu().numpy().astype(np.float64), v_cache.float().cpu().numpy().astype(np.float64)
+    got = out.cpu().numpy()
+    for m in sorted({0, M // 2, M - 1}):
+        want = D.attention_decode(D.rope(lin[0][m], pos0 + m, n_heads), kc64[:pos0 + m + 1], vc64[:pos0 + m + 1], n_heads)
+        assert np.abs(got[m] - want).max() <= 2e-5 * max(1.0, np.abs(want).max())
+    want_k = D.round_to_bf16(D.rope(lin[1][M - 1], pos0 + M - 1, n_heads))
+    assert np.all(np.abs(kc64[pos0 + M - 1] - want_k) <= np.maximum(np.abs(want_k), 1e-30) * 2.0 ** -7)
+
+
+def test_prompt_then_tokens(dev, mods):
+    """A prompt in two pieces through DecoderStack.prefill (products as bl_gemm over all rows), then single tokens: the
+    caches and hidden states are those of the same tokens taken one at a time through the unfolded one-token path
+    (same kernels for norms and attention, bl_gemv for the products) bit for bit, and follow the oracle."""
+    B, dec, ops = mods
+    hidden, ffn, n_heads, n_layers, max_pos = 256, 512, 4, 2, 160
+    layers, g_final = _make_layers(67000, hidden, ffn, n_layers)
+    a = dec.DecoderStack(_to_device(layers, dev, dec, ops), _t(g_final, dev), n_heads, max_pos, dev, fold_norm=False)
+    b = dec.DecoderStack(_to_device(layers, dev, dec, ops), _t(g_final, dev), n_heads, max_pos, dev, fold_norm=False)
+    x = torch.randn((103, hidden), device=dev, generator=torch.Generator(device=dev).manual_seed(9))
+    ya = torch.cat([a.prefill(x[:70].contiguous()), a.prefill(x[70:100].contiguous())])
+    yb = []
+    for t in range(103):
+        b.h.copy_(x[t:t + 1])
+        yb.append(b.step().clone())
+        if t >= 100:
+            a.h.copy_(x[t:t + 1])
+            ya = torch.cat([ya, a.step()])
+    torch.cuda.synchronize()
+    assert int(a.pos[0]) == 103 == int(b.pos[0])
+    assert torch.equal(ya, torch.cat(yb))
+    for la, lb in zip(a.layers, b.layers):
+        assert torch.equal(la.attn.k_cache.view(torch.int16), lb.attn.k_cache.view(torch.int16))
+        assert torch.equal(la.attn.v_cache.view(torch.int16), lb.attn.v_cache.view(torch.int16))
+    # the oracle, token by token, on the first tokens
+    kcs = [np.zeros((max_pos, hidden)) for _ in layers]
+    vcs = [np.zeros((max_pos, hidden)) for _ in layers]
+    xs = x.cpu().numpy()
+    for t in range(6):
+        h = xs[t].astype(np.float64)
+        for i, l in enumerate(layers):
+            h = D.decoder_layer_step(h, t, l, kcs[i], vcs[i], n_heads)
+        want = D.rmsnorm(h, g_final, 1e-5)
+        got = ya[t].cpu().numpy().astype(np.float64)
+        assert np.linalg.norm(got - want) <= 5e-2 * np.linalg.norm(want)
