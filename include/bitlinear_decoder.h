@@ -35,6 +35,7 @@ extern "C" {
 #define BL_NORM_SCRATCH_BYTES 256 /* per token row, for bl_norm_quant_args.scratch_dev            */
 #define BL_ATTN_MAX_HEAD_DIM 256
 #define BL_ATTN_CHUNK 64        /* cache positions per workgroup of the attention kernel  */
+#define BL_ATTN_BLOCK_MAX_HEAD_DIM 128 /* bl_attn_prefill: head sizes up to this go through the matrix cores */
 
 typedef enum bl_norm_mode {
     BL_NORM_PLAIN = 0,      /* x = a                                                  */
@@ -210,13 +211,18 @@ bl_status bl_attn_decode(const bl_attn_args *args, void *stream);
 /*
  * Attention for M consecutive tokens at positions pos0 .. pos0 + M - 1 (a prompt, or a piece of one): token m attends
  * to cache rows 0 .. pos0 + m.  Two launches: the M keys (rotated) and values go into the cache, rounded to bf16 as
- * bl_attn_decode rounds them; then one bl_attn_decode-style workgroup per (head, 64 cache rows, token).  Per token
- * the results are those of M bl_attn_decode calls in order.
+ * bl_attn_decode rounds them (the same bits); then the attention.  Head sizes up to BL_ATTN_BLOCK_MAX_HEAD_DIM take one
+ * workgroup per (head, 64 tokens) that forms scores and weighted values on the matrix cores, with the fp32 queries
+ * and softmax weights each entered as the sum of two bf16 numbers (relative error below 2^-17 per factor, fp32
+ * accumulation): the outputs agree with M bl_attn_decode calls to about 1e-5 of the output's scale, not bit for bit.
+ * Larger head sizes take one bl_attn_decode-style workgroup per (head, 64 cache rows, token), and there the results
+ * are those of M bl_attn_decode calls in order.
  *   q_lin_dev, k_lin_dev, v_lin_dev   [M, n_heads * head_dim] fp32, rows contiguous
  *   out_dev                           [M, n_heads * head_dim] fp32
  *   pos0, M                           host values; 0 <= pos0, pos0 + M <= max_pos, 1 <= M <= 65535
  *   scratch_dev                       bl_attn_prefill_scratch_bytes(...) bytes, 16-byte aligned, zero-filled before
- *                                     the first call (every call leaves its counters zero)
+ *                                     the first call (every call leaves its counters zero); 16 bytes that are not
+ *                                     touched for head sizes up to BL_ATTN_BLOCK_MAX_HEAD_DIM
  *   rope_table_dev, k_cache_dev, v_cache_dev, n_heads, head_dim, max_pos: as in bl_attn_args
  * Errors: BL_ERR_NULL, BL_ERR_SHAPE, BL_ERR_ALIGN, BL_ERR_HIP.
  */

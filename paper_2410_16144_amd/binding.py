@@ -39,6 +39,7 @@ BL_NORM_MAX_K = 49152
 BL_NORM_SCRATCH_BYTES = 256
 BL_ATTN_MAX_HEAD_DIM = 256
 BL_ATTN_CHUNK = 64
+BL_ATTN_BLOCK_MAX_HEAD_DIM = 128
 BL_NORM_PLAIN, BL_NORM_RESIDUAL, BL_NORM_GATED, BL_NORM_PREMULTIPLIED = 0, 1, 2, 3
 BL_DECODE_NORM_MAX_K = 16384
 

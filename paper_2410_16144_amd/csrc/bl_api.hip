@@ -444,6 +444,7 @@ static bool prefill_shape_ok(int32_t n_heads, int32_t head_dim, int32_t pos0, in
 
 uint64_t bl_attn_prefill_scratch_bytes(int32_t n_heads, int32_t head_dim, int32_t pos0, int32_t M) {
     if (!prefill_shape_ok(n_heads, head_dim, pos0, M)) return 0;
+    if (head_dim <= BL_ATTN_BLOCK_MAX_HEAD_DIM) return 16;   // the matrix-core kernel keeps everything in registers and LDS
     const uint64_t per_query = (uint64_t)n_heads * (uint64_t)bl::attn_chunks(pos0 + M) * (uint64_t)(head_dim + 2) + (uint64_t)n_heads;
     return per_query * (uint64_t)M * sizeof(float);
 }

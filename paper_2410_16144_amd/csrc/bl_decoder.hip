@@ -645,6 +645,240 @@ __global__ __launch_bounds__(128) void kv_append_kernel(const AttnArgs p) {
     vrow[tid + half] = f32_to_bf16(v_lin[tid + half]);
 }
 
+// A prompt's attention on the matrix cores: one workgroup per (head, block of 64 consecutive prompt tokens), 16 queries
+// per wave.  The block walks the cache's 64-row chunks up to its last token's; per chunk a wave forms its 16 x 64
+// scores S = Q K^T and then O += P V with 16x16x32 bf16 products, keeping the running maximum, sum and output of
+// every query in registers (the usual rescaling by 2^(old maximum - new maximum); the scores carry log2(e), so the
+// weights are plain powers of two).  Keys and values are bf16 in the cache already; the fp32 queries enter as the
+// sum of three bf16 numbers (the value rounded, then the remainder, then its remainder: all 24 bits, since a score's
+// error is multiplied by the scores' size) and the weights, which lie in [0, 1], as the sum of two (about 17 bits);
+// each part takes one product, and everything is accumulated in fp32.  Operand layouts of the product, per lane: A
+// holds row lane%16 and eight consecutive contraction indices chosen by lane/16, B holds column lane%16 and the same
+// eight indices, the result holds rows 4*(lane/16) .. +3 of column lane%16.  The contraction index has to be the
+// register-contiguous one on both sides: K rows serve as they are, V is transposed on its way into LDS, and the
+// weights pass through LDS (each wave its own part) to turn from the result layout into the A layout.
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kBlockQ = 64;          // queries per workgroup
+constexpr int kBlockThreads = 256;   // four waves of 16 queries
+
+__device__ __forceinline__ f32x4 mfma_bf16(const s16x8& a, const s16x8& b, const f32x4& c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
+// max / sum over the 16 lanes of a row of the wave, on the vector ALU's lane rotations; every lane gets the result
+#define BL_ROW_ROR(x, n) __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, (x)), 0x120 + (n), 0xf, 0xf, false))
+__device__ __forceinline__ float row16_max(float v) {
+    v = fmaxf(v, BL_ROW_ROR(v, 8));
+    v = fmaxf(v, BL_ROW_ROR(v, 4));
+    v = fmaxf(v, BL_ROW_ROR(v, 2));
+    return fmaxf(v, BL_ROW_ROR(v, 1));
+}
+__device__ __forceinline__ float row16_sum(float v) {
+    v += BL_ROW_ROR(v, 8);
+    v += BL_ROW_ROR(v, 4);
+    v += BL_ROW_ROR(v, 2);
+    return v + BL_ROW_ROR(v, 1);
+}
+
+template <int D16>   // head_dim rounded up to 16, in sixteens; the columns beyond head_dim are zero
+__global__ __launch_bounds__(kBlockThreads) void attn_block_kernel(const AttnArgs p, const int M) {
+    constexpr int D32 = (D16 + 1) / 2;   // steps of the scores' contraction over the head's elements
+    constexpr int kKS = 32 * D32 + 8;    // bf16 elements per key row in LDS: 16 bytes of padding spread the rows over the banks
+    constexpr int kVS = kChunk + 8;      // the same for a row of the transposed values
+    constexpr int kPS = kChunk + 4;      // floats per row of weights
+    __shared__ __align__(16) uint16_t s_k[kChunk * kKS];
+    __shared__ __align__(16) uint16_t s_vt[16 * D16 * kVS];
+    __shared__ __align__(16) float s_p[kBlockThreads / kWave][16][kPS];
+    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+    // a later block walks more chunks: those are launched first
+    const int head = blockIdx.x, block = (int)(gridDim.y - 1 - blockIdx.y);
+    const int d = p.head_dim, half = d / 2, hidden = p.n_heads * d;
+    const int l16 = lane % 16, g = lane / 16;
+    const int m_last = min(block * kBlockQ + kBlockQ - 1, M - 1);      // the block's last token
+    const int last_pos = p.pos0 + M - 1;                               // the last cached row
+
+    for (int i = tid; i < kChunk * kKS; i += kBlockThreads) s_k[i] = 0;
+    for (int i = tid; i < 16 * D16 * kVS; i += kBlockThreads) s_vt[i] = 0;
+
+    // the wave's queries, rotated, scaled by log2(e) / sqrt(head_dim), as A operands: row l16, elements 32 ks + 8 g .. + 7
+    s16x8 q_hi[D32], q_mid[D32], q_lo[D32];
+    {
+        const int m = min(block * kBlockQ + wave * 16 + l16, M - 1);   // rows beyond the prompt repeat its last one
+        const float* q = p.q_lin + (int64_t)m * hidden + head * d;
+        const float2* cs_row = p.rope + (int64_t)(p.pos0 + m) * half;
+        const float scale = 1.4426950408889634f / sqrtf((float)d);
+#pragma unroll
+        for (int ks = 0; ks < D32; ++ks) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int e = 32 * ks + 8 * g + j;
+                float v = 0.0f;
+                if (e < half) {
+                    const float2 cs = cs_row[e];
+                    v = (q[e] * cs.x - q[e + half] * cs.y) * scale;
+                } else if (e < d) {
+                    const float2 cs = cs_row[e - half];
+                    v = (q[e - half] * cs.y + q[e] * cs.x) * scale;
+                }
+                const uint16_t hi = f32_to_bf16(v);
+                const float r1 = v - bf16_to_f32(hi);
+                const uint16_t mid = f32_to_bf16(r1);
+                const uint16_t lo = f32_to_bf16(r1 - bf16_to_f32(mid));
+                q_hi[ks][j] = (short)hi; q_mid[ks][j] = (short)mid; q_lo[ks][j] = (short)lo;
+            }
+        }
+    }
+
+    f32x4 o[D16];
+#pragma unroll
+    for (int t = 0; t < D16; ++t) o[t] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+    float run_m[4], run_l[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { run_m[i] = -INFINITY; run_l[i] = 0.0f; }
+    const int q_pos0 = p.pos0 + block * kBlockQ + wave * 16 + 4 * g;   // position of result row 0 of this lane
+
+    // A chunk's keys and values travel cache -> registers -> LDS in pieces of 4 rows x 4 elements (head_dim is a
+    // multiple of 4), 8 x 8 pieces per wave and step: the values are transposed inside the piece, so that either matrix
+    // is written as 8-byte words, two lanes to a bank at worst.  The next chunk's pieces are requested before this
+    // one's products start, so that their way from memory is covered by the arithmetic.
+    constexpr int kSteps = (2 * ((D16 + 1) / 2) + 3) / 4;   // wave steps: 2 row halves x ceil(elements / 32), over 4 waves
+    const int c_count = d / 4, c_blocks = (c_count + 7) / 8;
+    const int c_last = (p.pos0 + m_last) / kChunk;
+    uint2 kreg[kSteps][4], vreg[kSteps][4];
+    const auto piece = [&](int i, int& c, int& rg) {       // false: nothing to do in this step
+        const int wt = wave + 4 * i;
+        const int cb = wt % c_blocks, rb = wt / c_blocks;
+        c = cb * 8 + lane % 8;
+        rg = rb * 8 + lane / 8;
+        return rb < 2 && c < c_count;
+    };
+    const auto request = [&](int chunk) {
+        const int j0 = chunk * kChunk;
+#pragma unroll
+        for (int i = 0; i < kSteps; ++i) {
+            int c, rg;
+            if (piece(i, c, rg)) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int64_t at = (int64_t)min(j0 + 4 * rg + j, last_pos) * hidden + head * d + c * 4;
+                    kreg[i][j] = *reinterpret_cast<const uint2*>(p.k_cache + at);
+                    vreg[i][j] = *reinterpret_cast<const uint2*>(p.v_cache + at);
+                }
+            }
+        }
+    };
+    request(0);
+    for (int chunk = 0; chunk <= c_last; ++chunk) {
+        const int j0 = chunk * kChunk;
+        __syncthreads();                               // the previous chunk's tiles have been used (and the zero fill is done)
+#pragma unroll
+        for (int i = 0; i < kSteps; ++i) {
+            int c, rg;
+            if (piece(i, c, rg)) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) *reinterpret_cast<uint2*>(s_k + (4 * rg + j) * kKS + c * 4) = kreg[i][j];
+                const uint2* v = vreg[i];
+                uint2 t[4];
+                t[0] = make_uint2((v[0].x & 0xffffu) | (v[1].x << 16), (v[2].x & 0xffffu) | (v[3].x << 16));
+                t[1] = make_uint2((v[0].x >> 16) | (v[1].x & 0xffff0000u), (v[2].x >> 16) | (v[3].x & 0xffff0000u));
+                t[2] = make_uint2((v[0].y & 0xffffu) | (v[1].y << 16), (v[2].y & 0xffffu) | (v[3].y << 16));
+                t[3] = make_uint2((v[0].y >> 16) | (v[1].y & 0xffff0000u), (v[2].y >> 16) | (v[3].y & 0xffff0000u));
+#pragma unroll
+                for (int e = 0; e < 4; ++e) *reinterpret_cast<uint2*>(s_vt + (c * 4 + e) * kVS + 4 * rg) = t[e];
+            }
+        }
+        if (chunk < c_last) request(chunk + 1);
+        __syncthreads();
+
+        // scores of the wave's 16 queries against the chunk's 64 keys: four 16 x 16 tiles
+        f32x4 sc[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) sc[t] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int ks = 0; ks < D32; ++ks) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const s16x8 b = *reinterpret_cast<const s16x8*>(s_k + (16 * t + l16) * kKS + 32 * ks + 8 * g);
+                sc[t] = mfma_bf16(q_lo[ks], b, sc[t]);
+                sc[t] = mfma_bf16(q_mid[ks], b, sc[t]);
+                sc[t] = mfma_bf16(q_hi[ks], b, sc[t]);
+            }
+        }
+        // a query sees the keys up to its own position; chunk 0 holds key 0, which every query sees, so the running
+        // maximum is finite from there on
+        float f[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float mx = -INFINITY;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                if (j0 + 16 * t + l16 > q_pos0 + i) sc[t][i] = -INFINITY;
+                mx = fmaxf(mx, sc[t][i]);
+            }
+            const float m_new = fmaxf(run_m[i], row16_max(mx));
+            f[i] = __builtin_amdgcn_exp2f(run_m[i] - m_new);
+            float sum = 0.0f;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const float w = __builtin_amdgcn_exp2f(sc[t][i] - m_new);
+                sum += w;
+                s_p[wave][4 * g + i][16 * t + l16] = w;
+            }
+            run_l[i] = run_l[i] * f[i] + row16_sum(sum);
+            run_m[i] = m_new;
+        }
+#pragma unroll
+        for (int t = 0; t < D16; ++t)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) o[t][i] *= f[i];
+        // the weights are read back by this wave only: LDS serves a wave's requests in their order
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            const float4 w0 = *reinterpret_cast<const float4*>(&s_p[wave][l16][32 * ks + 8 * g]);
+            const float4 w1 = *reinterpret_cast<const float4*>(&s_p[wave][l16][32 * ks + 8 * g + 4]);
+            const float w[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
+            s16x8 w_hi, w_lo;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const uint16_t hi = f32_to_bf16(w[j]);
+                w_hi[j] = (short)hi;
+                w_lo[j] = (short)f32_to_bf16(w[j] - bf16_to_f32(hi));
+            }
+#pragma unroll
+            for (int t = 0; t < D16; ++t) {
+                const s16x8 b = *reinterpret_cast<const s16x8*>(s_vt + (16 * t + l16) * kVS + 32 * ks + 8 * g);
+                o[t] = mfma_bf16(w_lo, b, o[t]);
+                o[t] = mfma_bf16(w_hi, b, o[t]);
+            }
+        }
+    }
+
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int m = block * kBlockQ + wave * 16 + 4 * g + i;
+        if (m >= M) continue;
+        float* out = p.out + (int64_t)m * hidden + head * d;
+        const float inv = 1.0f / run_l[i];
+#pragma unroll
+        for (int t = 0; t < D16; ++t)
+            if (16 * t + l16 < d) out[16 * t + l16] = o[t][i] * inv;
+    }
+}
+
+template <int D16>
+hipError_t launch_attn_block(const AttnArgs& p, int M, hipStream_t s) {
+    const dim3 grid((unsigned)p.n_heads, (unsigned)((M + kBlockQ - 1) / kBlockQ));
+    attn_block_kernel<D16><<<grid, dim3(kBlockThreads), 0, s>>>(p, M);
+    return hipGetLastError();
+}
+
 __global__ void pos_advance_kernel(int32_t* pos) {
     if (threadIdx.x == 0) *pos = *pos + 1;
 }
@@ -718,6 +952,19 @@ hipError_t launch_attn_prefill(const bl_attn_prefill_args& a, hipStream_t s) {
     kv_append_kernel<<<dim3((unsigned)a.M, (unsigned)a.n_heads), dim3(128), 0, s>>>(p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
+    // head sizes up to 128 take the matrix-core kernel (a block of 64 tokens per workgroup); larger ones go token by token
+    static_assert(BL_ATTN_BLOCK_MAX_HEAD_DIM == 128, "the dispatch below covers head sizes up to 8 sixteens");
+    switch ((a.head_dim + 15) / 16) {
+        case 1: return launch_attn_block<1>(p, a.M, s);
+        case 2: return launch_attn_block<2>(p, a.M, s);
+        case 3: return launch_attn_block<3>(p, a.M, s);
+        case 4: return launch_attn_block<4>(p, a.M, s);
+        case 5: return launch_attn_block<5>(p, a.M, s);
+        case 6: return launch_attn_block<6>(p, a.M, s);
+        case 7: return launch_attn_block<7>(p, a.M, s);
+        case 8: return launch_attn_block<8>(p, a.M, s);
+        default: break;
+    }
     const dim3 grid((unsigned)a.n_heads, (unsigned)p.chunks, (unsigned)a.M);
     if (a.head_dim % 8 == 0) attn_chunk_kernel<8><<<grid, dim3(kAttnThreads), 0, s>>>(p);
     else attn_chunk_kernel<4><<<grid, dim3(kAttnThreads), 0, s>>>(p);

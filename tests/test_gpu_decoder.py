@@ -558,11 +558,21 @@ def test_long_token_loop_graph_equals_eager_across_chunk_boundaries(dev, mods):
     assert int(a.pos[0]) == n_tokens == int(b.pos[0])
 
 
+# A prompt's attention against the fp64 softmax.  Head sizes up to 128 go through the matrix cores with the fp32 queries
+# and weights as sums of two bf16 numbers: each carries a relative error below 2^-17 (the remainder of a nearest bf16 is
+# below 2^-9 of the value and is itself rounded to 2^-9 of that, plus the fp32 subtraction), so a score is off by at
+# most 2^-17 sum|q_i k_i| / sqrt(d) -- a few 1e-5 at the value range used here (queries of spread 3) -- which moves
+# every weight by that relative amount, and the weights' own split adds 2^-17 once more.
+PREFILL_BLOCK_TOL = 2e-5
+
+
 @pytest.mark.parametrize("n_heads,head_dim,max_pos,pos0,M", [(3, 64, 300, 0, 70), (3, 64, 300, 130, 100), (20, 128, 80, 5, 9),
-                                                           (5, 40, 70, 0, 70), (2, 256, 200, 63, 2)])
+                                                           (5, 40, 70, 0, 70), (2, 256, 200, 63, 2), (4, 100, 400, 37, 300),
+                                                           (2, 120, 200, 0, 130), (2, 48, 100, 10, 64), (1, 16, 70, 63, 1)])
 def test_attn_prefill_parity(dev, mods, n_heads, head_dim, max_pos, pos0, M):
-    """A prompt's attention: token m against cache rows 0 .. pos0 + m.  The appended rows as in the one-token call; every
-    token's output against the fp64 softmax over the cache as stored; and bit for bit what M one-token calls give."""
+    """A prompt's attention: token m against cache rows 0 .. pos0 + m.  The appended rows as in the one-token call, bit
+    for bit; every token's output against the fp64 softmax over the cache as stored, and against what M one-token calls
+    give (bit for bit where the head size takes the same kernel, above 128)."""
     B, dec, ops = mods
     hidden = n_heads * head_dim
     r = _rng(95000 + hidden + M)
@@ -594,21 +604,32 @@ def test_attn_prefill_parity(dev, mods, n_heads, head_dim, max_pos, pos0, M):
     torch.cuda.synchronize()
     assert torch.equal(k_cache.view(torch.int16), att.k_cache.view(torch.int16))
     assert torch.equal(v_cache.view(torch.int16), att.v_cache.view(torch.int16))
-    assert torch.equal(out, torch.cat(outs))
-    assert not scratch.view(torch.int32).view(M, -1)[:, -n_heads:].any()
+    stepwise = torch.cat(outs)
+    if head_dim > 128:
+        assert torch.equal(out, stepwise)
+    tol = 2e-5 if head_dim > 128 else PREFILL_BLOCK_TOL
+    assert float((out - stepwise).abs().max()) <= tol * max(1.0, float(stepwise.abs().max()))
+    if head_dim > 128:
+        assert not scratch.view(torch.int32).view(M, -1)[:, -n_heads:].any()
+    else:
+        assert scratch.numel() == 16 and not scratch.any()
     kc64, vc64 = k_cache.float().cpu().numpy().astype(np.float64), v_cache.float().cpu().numpy().astype(np.float64)
     got = out.cpu().numpy()
-    for m in sorted({0, M // 2, M - 1}):
+    worst = 0.0
+    for m in range(M):
         want = D.attention_decode(D.rope(lin[0][m], pos0 + m, n_heads), kc64[:pos0 + m + 1], vc64[:pos0 + m + 1], n_heads)
-        assert np.abs(got[m] - want).max() <= 2e-5 * max(1.0, np.abs(want).max())
+        err = np.abs(got[m] - want).max() / max(1.0, np.abs(want).max())
+        worst = max(worst, err)
+        assert err <= tol, (m, err)
+    print(f"attn_prefill heads={n_heads} d={head_dim} pos0={pos0} M={M}: worst error {worst:.2e}", flush=True)
     want_k = D.round_to_bf16(D.rope(lin[1][M - 1], pos0 + M - 1, n_heads))
     assert np.all(np.abs(kc64[pos0 + M - 1] - want_k) <= np.maximum(np.abs(want_k), 1e-30) * 2.0 ** -7)
 
 
 def test_prompt_then_tokens(dev, mods):
-    """A prompt in two pieces through DecoderStack.prefill (products as bl_gemm over all rows), then single tokens: the
-    caches and hidden states are those of the same tokens taken one at a time through the unfolded one-token path
-    (same kernels for norms and attention, bl_gemv for the products) bit for bit, and follow the oracle."""
+    """A prompt in two pieces through DecoderStack.prefill (products as bl_gemm over all rows, attention on the matrix
+    cores), then single tokens: the caches and hidden states follow those of the same tokens taken one at a time through
+    the unfolded one-token path, and the oracle."""
     B, dec, ops = mods
     hidden, ffn, n_heads, n_layers, max_pos = 256, 512, 4, 2, 160
     layers, g_final = _make_layers(67000, hidden, ffn, n_layers)
@@ -625,10 +646,13 @@ def test_prompt_then_tokens(dev, mods):
             ya = torch.cat([ya, a.step()])
     torch.cuda.synchronize()
     assert int(a.pos[0]) == 103 == int(b.pos[0])
-    assert torch.equal(ya, torch.cat(yb))
-    for la, lb in zip(a.layers, b.layers):
-        assert torch.equal(la.attn.k_cache.view(torch.int16), lb.attn.k_cache.view(torch.int16))
-        assert torch.equal(la.attn.v_cache.view(torch.int16), lb.attn.v_cache.view(torch.int16))
+    yb = torch.cat(yb)
+    # the prompt's attention sums in another order than the one-token kernel: the first layer's cache rows are the same
+    # bits, everything behind an attention agrees to the bound of the end-to-end comparisons
+    assert torch.equal(a.layers[0].attn.k_cache.view(torch.int16), b.layers[0].attn.k_cache.view(torch.int16))
+    assert torch.equal(a.layers[0].attn.v_cache.view(torch.int16), b.layers[0].attn.v_cache.view(torch.int16))
+    assert float(torch.linalg.norm(ya - yb)) <= 5e-2 * float(torch.linalg.norm(yb))
+    assert bool(torch.isfinite(ya).all())
     # the oracle, token by token, on the first tokens
     kcs = [np.zeros((max_pos, hidden)) for _ in layers]
     vcs = [np.zeros((max_pos, hidden)) for _ in layers]
