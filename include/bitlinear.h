@@ -43,7 +43,7 @@ typedef enum {
     BL_ERR_DTYPE = 6,       /* unknown bl_dtype                                   */
     BL_ERR_LAYOUT = 7,      /* descriptor version is not BL_LAYOUT_VERSION        */
     BL_ERR_HIP = 8,         /* the HIP runtime refused the launch                 */
-    BL_ERR_COUNT = 9        /* bl_gemv_batch: count outside 1..BL_MAX_BATCH       */
+    BL_ERR_COUNT = 9        /* a batch call's count is outside its range          */
 } bl_status;
 
 typedef enum { BL_F32 = 0, BL_BF16 = 1 } bl_dtype;
@@ -55,6 +55,7 @@ typedef enum { BL_F32 = 0, BL_BF16 = 1 } bl_dtype;
 #define BL_MAX_GEMV_M 8
 #define BL_MAX_BATCH 8
 #define BL_MAX_GEMM_M 4194304
+#define BL_MAX_GEMM_BATCH 4
 #define BL_MAX_SPLIT_WGS 2048   /* most workgroups of a work-balanced decode launch     */
 #define BL_WORKSPACE_BYTES (BL_MAX_SPLIT_WGS * 64 * 8)   /* 1 MiB, see bl_gemv_batch   */
 
@@ -252,6 +253,17 @@ bl_status bl_decode_batch(const bl_decode_item *items, int32_t count, int64_t M,
 bl_status bl_gemm(const void *packed_dev, const bl_packed_desc *d, const int8_t *q_dev,
                   const float *a_scale_dev, const int32_t *q_sum_dev, int64_t M,
                   float *out_dev, int32_t *acc_dev, void *stream);
+
+/*
+ * `count` independent bl_gemm problems (1..BL_MAX_GEMM_BATCH, all over the same
+ * M) in ONE kernel launch: e.g. the Q/K/V projections or gate/up of a decoder
+ * layer over a prompt of a few hundred tokens, where one product alone gives
+ * every compute unit a single workgroup.  Items are validated like bl_gemm
+ * calls; results are identical to `count` separate
+ * calls.  `items` is a host array, read during the call.
+ * Errors: those of bl_gemm, and BL_ERR_COUNT.
+ */
+bl_status bl_gemm_batch(const bl_gemv_item *items, int32_t count, int64_t M, void *stream);
 
 /* ---- A 1.78-bit layout on the paper's TL2 code --------------------------
  *

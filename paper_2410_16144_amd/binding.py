@@ -21,6 +21,7 @@ BL_TILE_K = 64
 BL_MAX_K = 1048576
 BL_MAX_GEMV_M = 8
 BL_MAX_BATCH = 8
+BL_MAX_GEMM_BATCH = 4
 BL_MAX_SPLIT_WGS = 2048
 BL_WORKSPACE_BYTES = BL_MAX_SPLIT_WGS * 64 * 8
 BL_MAX_GEMM_M = 4194304
@@ -30,7 +31,7 @@ BL_TL2_LAYOUT_VERSION = 2
 # every symbol include/bitlinear.h and include/bitlinear_decoder.h declare
 DECLARED_SYMBOLS = (
     "bl_padded_k", "bl_padded_n", "bl_packed_desc_init", "bl_pack_ternary", "bl_unpack_ternary",
-    "bl_quant_act", "bl_quant_act_batch", "bl_gemv", "bl_gemv_batch", "bl_decode_batch", "bl_gemm", "bl_set_tuning", "bl_get_stat", "bl_status_str", "bl_last_hip_error", "bl_version",
+    "bl_quant_act", "bl_quant_act_batch", "bl_gemv", "bl_gemv_batch", "bl_decode_batch", "bl_gemm", "bl_gemm_batch", "bl_set_tuning", "bl_get_stat", "bl_status_str", "bl_last_hip_error", "bl_version",
     "bl_tl2_padded_k", "bl_tl2_desc_init", "bl_tl2_pack", "bl_tl2_unpack", "bl_tl2_gemv", "bl_tl2_gemv_batch",
     "bl_norm_quant", "bl_rope_table", "bl_attn_scratch_bytes", "bl_attn_decode", "bl_pos_advance", "bl_decode_norm_batch", "bl_attn_prefill", "bl_attn_prefill_scratch_bytes",
 )
@@ -146,6 +147,7 @@ def lib():
     l.bl_quant_act_batch.argtypes = [ctypes.POINTER(QuantItem), i32, vp]
     l.bl_gemv.argtypes = [vp, dp, vp, vp, vp, i64, vp, vp, vp]
     l.bl_gemv_batch.argtypes = [ctypes.POINTER(GemvItem), i32, i64, vp, vp]
+    l.bl_gemm_batch.argtypes = [ctypes.POINTER(GemvItem), i32, i64, vp]
     l.bl_decode_batch.argtypes = [ctypes.POINTER(DecodeItem), i32, i64, vp, vp]
     l.bl_gemm.argtypes = [vp, dp, vp, vp, vp, i64, vp, vp, vp]
     l.bl_tl2_padded_k.argtypes = [i64]
@@ -175,7 +177,7 @@ def lib():
     for name in ("bl_packed_desc_init", "bl_pack_ternary", "bl_unpack_ternary", "bl_quant_act", "bl_quant_act_batch", "bl_gemv",
                  "bl_gemv_batch", "bl_decode_batch", "bl_gemm", "bl_set_tuning", "bl_tl2_desc_init", "bl_tl2_pack",
                  "bl_tl2_unpack", "bl_tl2_gemv", "bl_tl2_gemv_batch", "bl_norm_quant", "bl_rope_table", "bl_attn_decode",
-                 "bl_pos_advance", "bl_decode_norm_batch", "bl_attn_prefill"):
+                 "bl_pos_advance", "bl_decode_norm_batch", "bl_attn_prefill", "bl_gemm_batch"):
         getattr(l, name).restype = ctypes.c_int
     _lib = l
     return l
@@ -260,6 +262,13 @@ def bl_gemv_batch(items, M: int, workspace_dev: int = 0, stream: int = 0):
     if not isinstance(items, ctypes.Array):
         items = make_gemv_items(items)
     _check(lib().bl_gemv_batch(items, len(items), M, workspace_dev or None, stream or None), "bl_gemv_batch")
+
+
+def bl_gemm_batch(items, M: int, stream: int = 0):
+    """items: a ctypes GemvItem array from make_gemv_items (or an iterable of tuples), at most BL_MAX_GEMM_BATCH."""
+    if not isinstance(items, ctypes.Array):
+        items = make_gemv_items(items)
+    _check(lib().bl_gemm_batch(items, len(items), M, stream or None), "bl_gemm_batch")
 
 
 def make_decode_items(items):

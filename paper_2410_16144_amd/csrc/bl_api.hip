@@ -327,6 +327,22 @@ bl_status bl_gemm(const void* packed_dev, const bl_packed_desc* d, const int8_t*
     return hip_status(bl::launch_gemm(p, M, static_cast<hipStream_t>(stream)));
 }
 
+bl_status bl_gemm_batch(const bl_gemv_item* items, int32_t count, int64_t M, void* stream) {
+    if (!items) return BL_ERR_NULL;
+    if (count < 1 || count > BL_MAX_GEMM_BATCH) return BL_ERR_COUNT;
+    if (M < 1 || M > BL_MAX_GEMM_M) return BL_ERR_SHAPE;
+    bl::GemmProblem ps[BL_MAX_GEMM_BATCH];
+    for (int i = 0; i < count; ++i) {
+        const bl_gemv_item& it = items[i];
+        bl_status s = check_product_args(it.packed_dev, it.desc, it.q_dev, it.a_scale_dev, it.q_sum_dev, M, it.out_dev,
+                                         it.acc_dev);
+        if (s != BL_OK) return s;
+        ps[i] = make_problem(it.packed_dev, it.desc, it.q_dev, it.a_scale_dev, it.q_sum_dev, it.out_dev, it.acc_dev);
+    }
+    drop_stale_hip_error();
+    return hip_status(bl::launch_gemm_batch(ps, count, M, static_cast<hipStream_t>(stream)));
+}
+
 bl_status bl_norm_quant(const bl_norm_quant_args* a, void* stream) {
     if (!a || (!a->gamma_dev && a->mode != BL_NORM_PREMULTIPLIED)) return BL_ERR_NULL;
     const bool quantize = a->q_dev != nullptr;

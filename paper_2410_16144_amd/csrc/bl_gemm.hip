@@ -52,8 +52,9 @@ __device__ __forceinline__ v4i expand_codes(uint32_t word) {
 
 constexpr int kXcds = 8;   // workgroup i runs on accelerator die i % 8, each die with its own L2
 
+// One workgroup's tile of one product: tokens 32*MB*tile_y .. and the weight rows of N position tile_x.
 template <int MB, int H, int WK>
-__global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmProblem p, const int M, const int gx) {
+__device__ __forceinline__ void gemm_tile(const GemmProblem& p, const int M, const int tile_x, const int tile_y) {
     static_assert(WK == 1 || (WK == 2 && MB % 2 == 0), "K groups exchange halves of the token tile");
     static_assert(H >= 2 && H <= 4, "32-row blocks per wave");
     constexpr int NT = (H + 1) / 2;       // packed 64-row tiles a wave loads per step
@@ -78,13 +79,6 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmProblem p, const
     const int KC = p.KC;
     const int steps = (KC + WK - 1) / WK;             // step i covers packed tiles WK*i .. WK*i + WK-1, one per K group
     const int wave_n = wave % WN, kg = wave / WN;     // position along N, K group
-    // Workgroup index -> tile, so that the die (index % 8) depends on the N position only: every die keeps ITS
-    // slice of the packed weights in its L2 for the whole launch, and consecutive workgroups (all dies) walk through
-    // the same token rows at the same time.  The grid is padded to a multiple of 8 along N.
-    const int gxh = (gx + kXcds - 1) / kXcds;
-    const int rest = blockIdx.x / kXcds;
-    const int tile_x = (rest % gxh) * kXcds + blockIdx.x % kXcds, tile_y = rest / gxh;
-    if (tile_x >= gx) return;                         // padding workgroup (uniform)
     const int m0 = tile_y * BM;
     const int row0 = (tile_x * WN + wave_n) * H * 32; // this wave's first row of W
     const int rb0 = row0 / kTileN;                    // the packed tile that row lies in
@@ -329,24 +323,65 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmProblem p, const
     }
 }
 
+// Workgroup index -> tile, so that the die (index % 8) depends on the N position only: every die keeps ITS slice of
+// the packed weights in its L2 for the whole launch, and consecutive workgroups (all dies) walk through the same
+// token rows at the same time.  The grid is padded to a multiple of 8 along N; false for a padding workgroup.
+__device__ __forceinline__ bool tile_of_workgroup(int gx, int& tile_x, int& tile_y) {
+    const int gxh = (gx + kXcds - 1) / kXcds;
+    const int rest = blockIdx.x / kXcds;
+    tile_x = (rest % gxh) * kXcds + blockIdx.x % kXcds;
+    tile_y = rest / gxh;
+    return tile_x < gx;
+}
+
+template <int MB, int H, int WK>
+__global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmProblem p, const int M, const int gx) {
+    int tile_x, tile_y;
+    if (!tile_of_workgroup(gx, tile_x, tile_y)) return;   // uniform
+    gemm_tile<MB, H, WK>(p, M, tile_x, tile_y);
+}
+
+// Several products over the same M in one launch: their N positions side by side, `end[i]` the first position behind
+// product i (INT32_MAX behind the last one in use).
+struct GemmBatch {
+    GemmProblem p[kMaxGemmBatch];
+    int32_t     end[kMaxGemmBatch];
+};
+
+template <int MB, int H, int WK>
+__global__ __launch_bounds__(256, 2) void gemm_batch_kernel(const GemmBatch b, const int M, const int gx) {
+    int tile_x, tile_y;
+    if (!tile_of_workgroup(gx, tile_x, tile_y)) return;   // uniform
+    int item = 0, first = 0;
+#pragma unroll
+    for (int i = 0; i + 1 < kMaxGemmBatch; ++i)
+        if (tile_x >= b.end[i]) { item = i + 1; first = b.end[i]; }
+    gemm_tile<MB, H, WK>(b.p[item], M, tile_x - first, tile_y);
+}
+
 int g_force_mb = 0;
+
+// wave tile = (32*MB) tokens x (32*H) weight rows; workgroup = 4 waves, 4/WK along N and WK along K.
+// Choice by workgroup count: 64 x 128 wave tiles (half the LDS traffic per MFMA) when the grid still gives
+// every compute unit two workgroups; 64 x 64 otherwise; and the K-split form when even that grid would
+// leave compute units without work.  Forced value: 100*(WK-1) + 10*MB + H.  `rows`: padded weight rows of the launch.
+void choose_tile(int64_t M, int64_t rows, int& mb, int& h, int& wk) {
+    const int64_t tiles_m = (M + 63) / 64;
+    const auto wgs = [&](int wn, int hh) { return tiles_m * ((rows + wn * hh * 32 - 1) / (wn * hh * 32)); };
+    mb = 2; h = 2; wk = 1;
+    if (wgs(4, 4) >= 512) h = 4;
+    else if (wgs(4, 2) < 256) wk = 2;
+    if (g_force_mb) { wk = g_force_mb / 100 + 1; mb = g_force_mb / 10 % 10; h = g_force_mb % 10; }
+}
 
 }  // namespace
 
 void set_gemm_mb(int mb) { g_force_mb = mb; }
 
 hipError_t launch_gemm(const GemmProblem& p, int64_t M, hipStream_t s) {
-    // wave tile = (32*MB) tokens x (32*H) weight rows; workgroup = 4 waves, 4/WK along N and WK along K.
-    // Choice by workgroup count: 64 x 128 wave tiles (half the LDS traffic per MFMA) when the grid still gives
-    // every compute unit two workgroups; 64 x 64 otherwise; and the K-split form when even that grid would
-    // leave compute units without work.  Forced value: 100*(WK-1) + 10*MB + H.
-    const int64_t tiles_m = (M + 63) / 64;
     const int64_t rows = (int64_t)p.row_blocks * kTileN;
-    const auto wgs = [&](int wn, int h) { return tiles_m * ((rows + wn * h * 32 - 1) / (wn * h * 32)); };
-    int mb = 2, h = 2, wk = 1;
-    if (wgs(4, 4) >= 512) h = 4;
-    else if (wgs(4, 2) < 256) wk = 2;
-    if (g_force_mb) { wk = g_force_mb / 100 + 1; mb = g_force_mb / 10 % 10; h = g_force_mb % 10; }
+    int mb, h, wk;
+    choose_tile(M, rows, mb, h, wk);
     const int wn = kWaves / wk;
     const int64_t gx = (rows + wn * h * 32 - 1) / (wn * h * 32);
     const int64_t gy = (M + 32 * mb - 1) / (32 * mb);
@@ -362,6 +397,39 @@ hipError_t launch_gemm(const GemmProblem& p, int64_t M, hipStream_t s) {
         case 24: gemm_kernel<2, 4, 1><<<grid, block, 0, s>>>(p, (int)M, igx); break;
         case 122: gemm_kernel<2, 2, 2><<<grid, block, 0, s>>>(p, (int)M, igx); break;
         case 124: gemm_kernel<2, 4, 2><<<grid, block, 0, s>>>(p, (int)M, igx); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_gemm_batch(const GemmProblem* ps, int count, int64_t M, hipStream_t s) {
+    if (count == 1) return launch_gemm(ps[0], M, s);
+    if (count < 1 || count > kMaxGemmBatch) return hipErrorInvalidValue;
+    int64_t rows = 0;
+    for (int i = 0; i < count; ++i) rows += (int64_t)ps[i].row_blocks * kTileN;
+    int mb, h, wk;
+    choose_tile(M, rows, mb, h, wk);
+    const int wn = kWaves / wk;
+    GemmBatch b;
+    int64_t gx = 0;
+    for (int i = 0; i < kMaxGemmBatch; ++i) {
+        b.p[i] = ps[i < count ? i : count - 1];
+        if (i < count) gx += ((int64_t)ps[i].row_blocks * kTileN + wn * h * 32 - 1) / (wn * h * 32);
+        b.end[i] = i + 1 < count ? (int32_t)gx : INT32_MAX;
+    }
+    const int64_t gy = (M + 32 * mb - 1) / (32 * mb);
+    const int64_t wgs_total = (gx + kXcds - 1) / kXcds * kXcds * gy;
+    if (wgs_total > INT32_MAX) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)wgs_total), block(256);
+    const int igx = (int)gx;
+    switch (100 * (wk - 1) + 10 * mb + h) {
+        case 12: gemm_batch_kernel<1, 2, 1><<<grid, block, 0, s>>>(b, (int)M, igx); break;
+        case 14: gemm_batch_kernel<1, 4, 1><<<grid, block, 0, s>>>(b, (int)M, igx); break;
+        case 22: gemm_batch_kernel<2, 2, 1><<<grid, block, 0, s>>>(b, (int)M, igx); break;
+        case 23: gemm_batch_kernel<2, 3, 1><<<grid, block, 0, s>>>(b, (int)M, igx); break;
+        case 24: gemm_batch_kernel<2, 4, 1><<<grid, block, 0, s>>>(b, (int)M, igx); break;
+        case 122: gemm_batch_kernel<2, 2, 2><<<grid, block, 0, s>>>(b, (int)M, igx); break;
+        case 124: gemm_batch_kernel<2, 4, 2><<<grid, block, 0, s>>>(b, (int)M, igx); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

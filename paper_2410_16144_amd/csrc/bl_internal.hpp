@@ -131,6 +131,8 @@ int compute_unit_count();   // of the current device; 0 if unknown
 bool plan_decode_split(DecodeBatch& b, bool fused, int& tiles_per_wave);   // false: the balanced form does not apply
 hipError_t launch_decode_split(const DecodeBatch& b, int tiles_per_wave, bool fused, hipStream_t s);
 hipError_t launch_gemm(const GemmProblem& p, int64_t M, hipStream_t s);
+constexpr int kMaxGemmBatch = BL_MAX_GEMM_BATCH;
+hipError_t launch_gemm_batch(const GemmProblem* ps, int count, int64_t M, hipStream_t s);   // 1 <= count <= kMaxGemmBatch
 hipError_t launch_tl2_pack(const int8_t* w, int64_t N, int64_t K, int64_t Np, int64_t Kp, uint32_t* packed,
                            int32_t* bad_count, hipStream_t s);
 hipError_t launch_tl2_unpack(const uint32_t* packed, int64_t N, int64_t K, int64_t Np, int64_t Kp, int8_t* w,

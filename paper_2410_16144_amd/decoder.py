@@ -313,8 +313,9 @@ class DecoderStack:
 
     def prefill(self, x: torch.Tensor) -> torch.Tensor:
         """A prompt (or a piece of one): x [M, hidden] fp32, the inputs of M consecutive tokens starting at the present
-        position.  Every product runs as ONE bl_gemm over the M rows, the norms as M-row bl_norm_quant launches, the
-        attention as bl_attn_prefill; eager launches, buffers sized to M on the spot.  Fills the caches, advances the
+        position.  Every product runs as a bl_gemm over the M rows (q, k, v in one launch, gate and up in one), the
+        norms as M-row bl_norm_quant launches, the attention as bl_attn_prefill; eager launches, buffers sized to M on
+        the spot.  Fills the caches, advances the
         position by M and returns the final-normalised hidden states [M, hidden].  The layers must hold gate and up
         as separate matrices (the interleaved one serves the one-token launches only)."""
         M, hidden = x.shape
@@ -334,13 +335,13 @@ class DecoderStack:
             ffn = w.proj["down"].K
             wide = torch.empty(M * B.BL_NORM_SCRATCH_BYTES, dtype=torch.uint8, device=dev)
             q1 = norm_quant(B.BL_NORM_RESIDUAL, w.g_in, self.eps, a=delta, h=H)
-            ql, kl, vl = (ops.gemm(w.proj[n], q1) for n in "qkv")
+            ql, kl, vl = ops.gemm_batch([w.proj[n] for n in "qkv"], q1)
             B.bl_attn_prefill(ql.data_ptr(), kl.data_ptr(), vl.data_ptr(), self.table.data_ptr(), layer.attn.k_cache.data_ptr(),
                               layer.attn.v_cache.data_ptr(), A.data_ptr(), scratch.data_ptr(), self.n_heads, d, self.max_pos,
                               pos0, M, _stream())
             o = ops.gemm(w.proj["o"], norm_quant(B.BL_NORM_PLAIN, w.g_attn, self.eps, a=A))
             q3 = norm_quant(B.BL_NORM_RESIDUAL, w.g_post, self.eps, a=o, h=H)
-            gate, up = ops.gemm(w.proj["gate"], q3), ops.gemm(w.proj["up"], q3)
+            gate, up = ops.gemm_batch([w.proj["gate"], w.proj["up"]], q3)
             q4 = norm_quant(B.BL_NORM_GATED, w.g_ffn, self.eps, a=gate, b=up, out=ops.alloc_quant(M, ffn, dev), scratch=wide)
             delta = ops.gemm(w.proj["down"], q4)
         norm_quant(B.BL_NORM_RESIDUAL, self.g_final, self.eps, a=delta, h=H, y=Y, quantize=False)

@@ -161,6 +161,17 @@ def gemm(pw: PackedWeight, qa: QuantAct, out: Optional[torch.Tensor] = None, wan
     return _product(B.bl_gemm, pw, qa, out, want_acc)
 
 
+def gemm_batch(pws, qa: QuantAct):
+    """Several prefill products over the same quantized activations in ONE launch (bl_gemm_batch): a list of fp32
+    outputs [M, N_i], each identical to gemm(pw_i, qa)."""
+    M, dev = qa.M, qa.q.device
+    assert 1 <= len(pws) <= B.BL_MAX_GEMM_BATCH and all(pw.K == qa.K for pw in pws)
+    outs = [torch.empty((M, pw.N), dtype=torch.float32, device=dev) for pw in pws]
+    B.bl_gemm_batch([(pw.blob.data_ptr(), pw.desc, qa.q.data_ptr(), qa.a_scale.data_ptr(), qa.q_sum.data_ptr(), o.data_ptr(), 0)
+                     for pw, o in zip(pws, outs)], M, _stream())
+    return outs
+
+
 _workspaces = {}
 
 

@@ -98,6 +98,13 @@ def test_argument_validation_happens_before_any_launch():
     assert B.lib().bl_gemv_batch(items, 0, 1, None, None) == B.BL_ERR_COUNT
     assert B.lib().bl_gemv_batch(items, 9, 1, None, None) == B.BL_ERR_COUNT
     assert B.lib().bl_gemv_batch(None, 1, 1, None, None) == B.BL_ERR_NULL
+    assert B.lib().bl_gemm_batch(items, 0, 1, None) == B.BL_ERR_COUNT
+    assert B.lib().bl_gemm_batch(items, B.BL_MAX_GEMM_BATCH + 1, 1, None) == B.BL_ERR_COUNT
+    assert B.lib().bl_gemm_batch(None, 1, 1, None) == B.BL_ERR_NULL
+    assert B.lib().bl_gemm_batch(items, 1, 0, None) == B.BL_ERR_SHAPE
+    assert B.lib().bl_gemm_batch(items, 1, B.BL_MAX_GEMM_M + 1, None) == B.BL_ERR_SHAPE
+    assert B.lib().bl_gemm_batch(B.make_gemv_items([(P, d, P, P, P, P, 0), (P, d, 0, P, P, P, 0)]), 2, 1, None) == B.BL_ERR_NULL
+    assert B.lib().bl_gemm_batch(B.make_gemv_items([(P, d, P, P, P, P, 0), (P + 8, d, P, P, P, P, 0)]), 2, 1, None) == B.BL_ERR_ALIGN
     # fused decode
     ditems = B.make_decode_items([(P, B.BL_BF16, 128, P, d, P, 0, 0, 0, 0)])
     lib = B.lib()

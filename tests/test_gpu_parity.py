@@ -597,6 +597,40 @@ def test_gemm_determinism(dev, ops):
         assert torch.equal(acc, acc2) and torch.equal(out, out2)
 
 
+@pytest.mark.parametrize("tile", [0, 12, 14, 22, 23, 24, 122, 124])
+def test_gemm_batch_parity(dev, ops, tile):
+    """Several products over the same activations in one launch: int32 sums equal to the oracle's, outputs and sums
+    bit for bit those of separate bl_gemm calls -- products of different N (ragged, one below a workgroup's rows), the
+    batch's ends, every wave tile."""
+    from paper_2410_16144_amd import binding
+    M, K = 150, 832
+    ns = [1000, 70, 704, 330]
+    x = _problem(5100 + tile, M, K, 64)[2]
+    qa = ops.quant_act(_to_dev_bf16(x, dev) if x.dtype == np.uint16 else torch.from_numpy(x).to(dev))
+    q_ref, a_ref, _ = oracle.quant_act(x)
+    ws = [_problem(5200 + tile + i, 1, K, n, p_zero=0.4, outl=0.01)[:2] for i, n in enumerate(ns)]
+    pws = [ops.pack_ternary(torch.from_numpy(w).to(dev), float(s)) for w, s in ws]
+    binding.bl_set_tuning("gemm_mb", tile)
+    try:
+        for count in (4, 2, 1):
+            outs = [torch.empty((M, pw.N), device=dev) for pw in pws[:count]]
+            accs = [torch.empty((M, pw.N), dtype=torch.int32, device=dev) for pw in pws[:count]]
+            binding.bl_gemm_batch([(pw.blob.data_ptr(), pw.desc, qa.q.data_ptr(), qa.a_scale.data_ptr(), qa.q_sum.data_ptr(),
+                                    o.data_ptr(), a.data_ptr()) for pw, o, a in zip(pws, outs, accs)], M,
+                                  torch.cuda.current_stream().cuda_stream)
+            torch.cuda.synchronize()
+            for (w, s), pw, o, a in zip(ws, pws, outs, accs):
+                acc_ref = oracle.matmul_i32(q_ref, w)
+                assert np.array_equal(a.cpu().numpy(), acc_ref)
+                _check_out(o, acc_ref, s, a_ref)
+                o1, a1 = ops.gemm(pw, qa, want_acc=True)
+                assert torch.equal(o, o1) and torch.equal(a, a1)
+    finally:
+        binding.bl_set_tuning("gemm_mb", 0)
+    outs = ops.gemm_batch(pws[:3], qa)
+    assert all(torch.equal(o, ops.gemm(pw, qa)) for o, pw in zip(outs, pws))
+
+
 def _launch_gemm(ops, pw, qa, out, acc):
     from paper_2410_16144_amd import binding
     binding.bl_gemm(pw.blob.data_ptr(), pw.desc, qa.q.data_ptr(), qa.a_scale.data_ptr(), qa.q_sum.data_ptr(),
