@@ -217,7 +217,7 @@ bl_status bl_attn_decode(const bl_attn_args *args, void *stream);
  * accumulation): the outputs agree with M bl_attn_decode calls to about 1e-5 of the output's scale, not bit for bit.
  * Larger head sizes take one bl_attn_decode-style workgroup per (head, 64 cache rows, token), and there the results
  * are those of M bl_attn_decode calls in order.
- *   q_lin_dev, k_lin_dev, v_lin_dev   [M, n_heads * head_dim] fp32, rows contiguous
+ *   q_lin_dev, k_lin_dev, v_lin_dev   [M, n_heads * head_dim] fp32, rows contiguous; k_lin_dev and v_lin_dev 8-byte aligned
  *   out_dev                           [M, n_heads * head_dim] fp32
  *   pos0, M                           host values; 0 <= pos0, pos0 + M <= max_pos, 1 <= M <= 65535
  *   scratch_dev                       bl_attn_prefill_scratch_bytes(...) bytes, 16-byte aligned, zero-filled before

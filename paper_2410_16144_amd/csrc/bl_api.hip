@@ -472,7 +472,7 @@ bl_status bl_attn_prefill(const bl_attn_prefill_args* a, void* stream) {
     if (!prefill_shape_ok(a->n_heads, a->head_dim, a->pos0, a->M) || !attn_shape_ok(a->n_heads, a->head_dim, a->max_pos) ||
         a->pos0 + a->M > a->max_pos)
         return BL_ERR_SHAPE;
-    if (!aligned(a->q_lin_dev, 4) || !aligned(a->k_lin_dev, 4) || !aligned(a->v_lin_dev, 4) || !aligned(a->rope_table_dev, 8) ||
+    if (!aligned(a->q_lin_dev, 4) || !aligned(a->k_lin_dev, 8) || !aligned(a->v_lin_dev, 8) || !aligned(a->rope_table_dev, 8) ||
         !aligned(a->k_cache_dev, 16) || !aligned(a->v_cache_dev, 16) || !aligned(a->out_dev, 4) || !aligned(a->scratch_dev, 16))
         return BL_ERR_ALIGN;
     drop_stale_hip_error();

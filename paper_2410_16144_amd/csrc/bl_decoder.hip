@@ -626,23 +626,31 @@ __global__ __launch_bounds__(kAttnThreads) void attn_chunk_kernel(const AttnArgs
     if (tid == 0) __hip_atomic_store(counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// A prompt's keys and values into the cache, ahead of its attention: one (token, head) per workgroup, the rotation and
-// rounding of attn_chunk_kernel's own append.
-__global__ __launch_bounds__(128) void kv_append_kernel(const AttnArgs p) {
-    const int tid = threadIdx.x, token = blockIdx.x, head = blockIdx.y;
-    const int d = p.head_dim, half = d / 2, hidden = p.n_heads * d;
+// A prompt's keys and values into the cache, ahead of its attention: one token per workgroup, the rotation and
+// rounding of attn_chunk_kernel's own append.  A thread takes two neighbouring elements of a head's lower half and
+// their partners in the upper half (head_dim is a multiple of 4), so that it loads 8 bytes and stores 4 at a time.
+__global__ __launch_bounds__(256) void kv_append_kernel(const AttnArgs p) {
+    const int token = blockIdx.x;
+    const int d = p.head_dim, half = d / 2, quarter = half / 2, hidden = p.n_heads * d;
     const int pos = p.pos0 + token;
-    if (tid >= half || pos < 0 || pos >= p.max_pos) return;
-    const float2 cs = p.rope[(int64_t)pos * half + tid];
-    const float* k_lin = p.k_lin + (int64_t)token * hidden + head * d;
-    const float* v_lin = p.v_lin + (int64_t)token * hidden + head * d;
-    const float ka = k_lin[tid], kb = k_lin[tid + half];
-    uint16_t* krow = p.k_cache + (int64_t)pos * hidden + head * d;
-    uint16_t* vrow = p.v_cache + (int64_t)pos * hidden + head * d;
-    krow[tid] = f32_to_bf16(ka * cs.x - kb * cs.y);
-    krow[tid + half] = f32_to_bf16(ka * cs.y + kb * cs.x);
-    vrow[tid] = f32_to_bf16(v_lin[tid]);
-    vrow[tid + half] = f32_to_bf16(v_lin[tid + half]);
+    if (pos < 0 || pos >= p.max_pos) return;
+    const float* k_lin = p.k_lin + (int64_t)token * hidden;
+    const float* v_lin = p.v_lin + (int64_t)token * hidden;
+    uint32_t* krow = reinterpret_cast<uint32_t*>(p.k_cache + (int64_t)pos * hidden);
+    uint32_t* vrow = reinterpret_cast<uint32_t*>(p.v_cache + (int64_t)pos * hidden);
+    const float2* cs_row = p.rope + (int64_t)pos * half;
+    const auto pack = [](float lo, float hi) { return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16); };
+    for (int i = threadIdx.x; i < p.n_heads * quarter; i += 256) {
+        const int head = i / quarter, t = 2 * (i - head * quarter);
+        const int lo = head * d + t, hi = lo + half;                    // even element indices
+        const float2 ka = *reinterpret_cast<const float2*>(k_lin + lo), kb = *reinterpret_cast<const float2*>(k_lin + hi);
+        const float2 va = *reinterpret_cast<const float2*>(v_lin + lo), vb = *reinterpret_cast<const float2*>(v_lin + hi);
+        const float2 c0 = cs_row[t], c1 = cs_row[t + 1];
+        krow[lo / 2] = pack(ka.x * c0.x - kb.x * c0.y, ka.y * c1.x - kb.y * c1.y);
+        krow[hi / 2] = pack(ka.x * c0.y + kb.x * c0.x, ka.y * c1.y + kb.y * c1.x);
+        vrow[lo / 2] = pack(va.x, va.y);
+        vrow[hi / 2] = pack(vb.x, vb.y);
+    }
 }
 
 // A prompt's attention on the matrix cores: one workgroup per (head, block of 64 consecutive prompt tokens), 16 queries
@@ -663,6 +671,10 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kBlockQ = 64;          // queries per workgroup
 constexpr int kBlockThreads = 256;   // four waves of 16 queries
+
+// nearest-even bf16 of a finite float, by the hardware's conversion
+__device__ __forceinline__ short bf16_bits(float v) { return __builtin_bit_cast(short, (__bf16)v); }
+__device__ __forceinline__ float bf16_value(short b) { return __uint_as_float((uint32_t)(uint16_t)b << 16); }
 
 __device__ __forceinline__ f32x4 mfma_bf16(const s16x8& a, const s16x8& b, const f32x4& c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
@@ -700,8 +712,11 @@ __global__ __launch_bounds__(kBlockThreads) void attn_block_kernel(const AttnArg
     const int m_last = min(block * kBlockQ + kBlockQ - 1, M - 1);      // the block's last token
     const int last_pos = p.pos0 + M - 1;                               // the last cached row
 
-    for (int i = tid; i < kChunk * kKS; i += kBlockThreads) s_k[i] = 0;
-    for (int i = tid; i < 16 * D16 * kVS; i += kBlockThreads) s_vt[i] = 0;
+    // the padding beyond head_dim (key columns up to a multiple of 32, value rows up to a multiple of 16) must read as zero
+    if (d != 32 * D32)
+        for (int i = tid; i < kChunk * kKS / 2; i += kBlockThreads) reinterpret_cast<uint32_t*>(s_k)[i] = 0;
+    if (d != 16 * D16)
+        for (int i = tid; i < 16 * D16 * kVS / 2; i += kBlockThreads) reinterpret_cast<uint32_t*>(s_vt)[i] = 0;
 
     // the wave's queries, rotated, scaled by log2(e) / sqrt(head_dim), as A operands: row l16, elements 32 ks + 8 g .. + 7
     s16x8 q_hi[D32], q_mid[D32], q_lo[D32];
@@ -714,20 +729,18 @@ __global__ __launch_bounds__(kBlockThreads) void attn_block_kernel(const AttnArg
         for (int ks = 0; ks < D32; ++ks) {
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
+                // element e of the rotated query: pairs (e, e + half); no branches, so that all loads go out together
                 const int e = 32 * ks + 8 * g + j;
-                float v = 0.0f;
-                if (e < half) {
-                    const float2 cs = cs_row[e];
-                    v = (q[e] * cs.x - q[e + half] * cs.y) * scale;
-                } else if (e < d) {
-                    const float2 cs = cs_row[e - half];
-                    v = (q[e - half] * cs.y + q[e] * cs.x) * scale;
-                }
-                const uint16_t hi = f32_to_bf16(v);
-                const float r1 = v - bf16_to_f32(hi);
-                const uint16_t mid = f32_to_bf16(r1);
-                const uint16_t lo = f32_to_bf16(r1 - bf16_to_f32(mid));
-                q_hi[ks][j] = (short)hi; q_mid[ks][j] = (short)mid; q_lo[ks][j] = (short)lo;
+                const bool low = e < half, valid = e < d;
+                const int ea = valid ? (low ? e : e - half) : 0;
+                const float a = q[ea], b = q[ea + half];
+                const float2 cs = cs_row[ea];
+                float v = low ? a * cs.x - b * cs.y : a * cs.y + b * cs.x;
+                v = valid ? v * scale : 0.0f;
+                const short hi = bf16_bits(v);
+                const float r1 = v - bf16_value(hi);
+                const short mid = bf16_bits(r1);
+                q_hi[ks][j] = hi; q_mid[ks][j] = mid; q_lo[ks][j] = bf16_bits(r1 - bf16_value(mid));
             }
         }
     }
@@ -738,7 +751,8 @@ __global__ __launch_bounds__(kBlockThreads) void attn_block_kernel(const AttnArg
     float run_m[4], run_l[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) { run_m[i] = -INFINITY; run_l[i] = 0.0f; }
-    const int q_pos0 = p.pos0 + block * kBlockQ + wave * 16 + 4 * g;   // position of result row 0 of this lane
+    const int q_wave0 = p.pos0 + block * kBlockQ + wave * 16;          // position of the wave's first query
+    const int q_pos0 = q_wave0 + 4 * g;                                // position of result row 0 of this lane
 
     // A chunk's keys and values travel cache -> registers -> LDS in pieces of 4 rows x 4 elements (head_dim is a
     // multiple of 4), 8 x 8 pieces per wave and step: the values are transposed inside the piece, so that either matrix
@@ -793,31 +807,38 @@ __global__ __launch_bounds__(kBlockThreads) void attn_block_kernel(const AttnArg
         if (chunk < c_last) request(chunk + 1);
         __syncthreads();
 
-        // scores of the wave's 16 queries against the chunk's 64 keys: four 16 x 16 tiles
+        // a wave whose queries all lie before this chunk has nothing to add (the block's last chunks; uniform per wave)
+        if (j0 > q_wave0 + 15) continue;
+        // scores of the wave's 16 queries against the chunk's 64 keys: four 16 x 16 tiles; consecutive products go to
+        // different tiles, so that none waits for the one before it
         f32x4 sc[4];
 #pragma unroll
         for (int t = 0; t < 4; ++t) sc[t] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
         for (int ks = 0; ks < D32; ++ks) {
+            s16x8 b[4];
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const s16x8 b = *reinterpret_cast<const s16x8*>(s_k + (16 * t + l16) * kKS + 32 * ks + 8 * g);
-                sc[t] = mfma_bf16(q_lo[ks], b, sc[t]);
-                sc[t] = mfma_bf16(q_mid[ks], b, sc[t]);
-                sc[t] = mfma_bf16(q_hi[ks], b, sc[t]);
-            }
+            for (int t = 0; t < 4; ++t) b[t] = *reinterpret_cast<const s16x8*>(s_k + (16 * t + l16) * kKS + 32 * ks + 8 * g);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) sc[t] = mfma_bf16(q_lo[ks], b[t], sc[t]);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) sc[t] = mfma_bf16(q_mid[ks], b[t], sc[t]);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) sc[t] = mfma_bf16(q_hi[ks], b[t], sc[t]);
         }
-        // a query sees the keys up to its own position; chunk 0 holds key 0, which every query sees, so the running
-        // maximum is finite from there on
+        // a query sees the keys up to its own position (only the chunks around the wave's own positions need the
+        // test); chunk 0 holds key 0, which every query sees, so the running maximum is finite from there on
+        if (j0 + kChunk - 1 > q_wave0) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+                    if (j0 + 16 * t + l16 > q_pos0 + i) sc[t][i] = -INFINITY;
+        }
         float f[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            float mx = -INFINITY;
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                if (j0 + 16 * t + l16 > q_pos0 + i) sc[t][i] = -INFINITY;
-                mx = fmaxf(mx, sc[t][i]);
-            }
+            float mx = fmaxf(fmaxf(sc[0][i], sc[1][i]), fmaxf(sc[2][i], sc[3][i]));
             const float m_new = fmaxf(run_m[i], row16_max(mx));
             f[i] = __builtin_amdgcn_exp2f(run_m[i] - m_new);
             float sum = 0.0f;
@@ -847,16 +868,16 @@ __global__ __launch_bounds__(kBlockThreads) void attn_block_kernel(const AttnArg
             s16x8 w_hi, w_lo;
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                const uint16_t hi = f32_to_bf16(w[j]);
-                w_hi[j] = (short)hi;
-                w_lo[j] = (short)f32_to_bf16(w[j] - bf16_to_f32(hi));
+                w_hi[j] = bf16_bits(w[j]);
+                w_lo[j] = bf16_bits(w[j] - bf16_value(w_hi[j]));
             }
+            s16x8 b[D16];
 #pragma unroll
-            for (int t = 0; t < D16; ++t) {
-                const s16x8 b = *reinterpret_cast<const s16x8*>(s_vt + (16 * t + l16) * kVS + 32 * ks + 8 * g);
-                o[t] = mfma_bf16(w_lo, b, o[t]);
-                o[t] = mfma_bf16(w_hi, b, o[t]);
-            }
+            for (int t = 0; t < D16; ++t) b[t] = *reinterpret_cast<const s16x8*>(s_vt + (16 * t + l16) * kVS + 32 * ks + 8 * g);
+#pragma unroll
+            for (int t = 0; t < D16; ++t) o[t] = mfma_bf16(w_lo, b[t], o[t]);
+#pragma unroll
+            for (int t = 0; t < D16; ++t) o[t] = mfma_bf16(w_hi, b[t], o[t]);
         }
     }
 
@@ -949,7 +970,7 @@ hipError_t launch_attn_prefill(const bl_attn_prefill_args& a, hipStream_t s) {
     // a prompt's queries never look beyond its last token: chunks up to that one only
     p.chunks = attn_chunks(a.pos0 + a.M);
     p.scratch_stride = (int64_t)a.n_heads * p.chunks * (a.head_dim + 2) + a.n_heads;
-    kv_append_kernel<<<dim3((unsigned)a.M, (unsigned)a.n_heads), dim3(128), 0, s>>>(p);
+    kv_append_kernel<<<dim3((unsigned)a.M), dim3(256), 0, s>>>(p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     // head sizes up to 128 take the matrix-core kernel (a block of 64 tokens per workgroup); larger ones go token by token

@@ -278,6 +278,7 @@ def test_attn_prefill_validation():
     assert call(8, 0) == B.BL_ERR_SHAPE and call(9, 62) == B.BL_ERR_SHAPE and call(12, 0) == B.BL_ERR_SHAPE
     assert call(11, -1) == B.BL_ERR_SHAPE and call(11, 90) == B.BL_ERR_SHAPE            # pos0 + M beyond the cache
     assert call(4, P + 8) == B.BL_ERR_ALIGN and call(7, P + 4) == B.BL_ERR_ALIGN
+    assert call(1, P + 4) == B.BL_ERR_ALIGN and call(2, P + 4) == B.BL_ERR_ALIGN
     assert B.bl_attn_prefill_scratch_bytes(4, 160, 10, 20) == 20 * (4 * 1 * 162 + 4) * 4
     assert B.bl_attn_prefill_scratch_bytes(4, 160, 60, 10) == 10 * (4 * 2 * 162 + 4) * 4
     assert B.bl_attn_prefill_scratch_bytes(4, 64, 60, 10) == 16 == B.bl_attn_prefill_scratch_bytes(4, 128, 0, 1)
