@@ -464,9 +464,9 @@ def extra_decoder_tokens(torch, models, max_pos=512, tokens=64):
 
 
 def extra_prompt(torch, models, M=512, max_pos=1024):
-    """Prompt processing through the same decoder block: M tokens at once, every product one bl_gemm over the M rows,
-    attention as bl_attn_prefill (eager launches).  Prompt tokens per second, first at positions 0..M-1, then for a
-    second piece at M..2M-1."""
+    """Prompt processing through the same decoder block: M tokens at once, the products as bl_gemm / bl_gemm_batch over
+    the M rows, attention as bl_attn_prefill (eager launches).  Prompt tokens per second, first at positions 0..M-1,
+    then for a second piece at M..2M-1."""
     from paper_2410_16144_amd import decoder, synth
     dev = torch.device("cuda:0")
     rows = []
@@ -659,6 +659,9 @@ def main():
         torch.cuda.empty_cache()
         # whole-model token rate, the paper's own unit, on three of Appendix A's shapes (all twelve: --only tokens)
         extra["decoder_tokens"] = extra_decoder_tokens(torch, ["700M", "7B", "30B"])
+        torch.cuda.empty_cache()
+        # and the same block over a prompt of 512 tokens at once (more shapes: --only prompt --models ...)
+        extra["decoder_prompt"] = extra_prompt(torch, ["7B"])
         result["extra"] = extra
 
     print(json.dumps(result))
