@@ -327,15 +327,18 @@ bl_status bl_tl2_gemv_batch(const bl_gemv_item *items, int32_t count, void *work
                             void *stream);
 
 /*
- * Launch-shape override for experiments and sweeps; process-wide, not thread-safe, never
- * changes results.  Keys: "gemv_waves" = waves of the decode kernel that share one
+ * Launch-shape override for experiments and sweeps; process-wide, not thread-safe; the integer
+ * and fp32 results of the products never change.  Keys: "gemv_waves" = waves of the decode kernel that share one
  * 64-row block (1, 2, 4, 8, 16; 0 = automatic); "decode_split" = work-balanced one-token launches: -1 never,
  * 0 automatic (by launch size), n = 1..8 always with n workgroups per compute unit when a
  * workspace is given and the launch has at least 8 tiles per workgroup; "decode_path" = 0 automatic
  * (dot-product kernel for M = 1, matrix-core kernel for M >= 2), 1 = always the
  * dot-product kernel, 2 = always the matrix-core kernel; "decode_stage" = 1 keeps the matrix-core kernel
  * from staging the quantized activations in on-chip memory (0 = stage when they fit); "gemm_mb" = wave tile of the prefill kernel as
- * 10*MB + H, i.e. (32*MB) tokens x (32*H) weight rows: 12, 14, 22, 23, 24, or 122 / 124 for the K-split forms of 22 / 24 (0 = automatic).  Errors: BL_ERR_NULL, BL_ERR_SHAPE (unknown key/value).
+ * 10*MB + H, i.e. (32*MB) tokens x (32*H) weight rows: 12, 14, 22, 23, 24, or 122 / 124 for the K-split forms of 22 / 24 (0 = automatic);
+ * "attn_groups" = workgroups per head of bl_attn_decode (0 = automatic, else 1..65535, capped at the cache's chunks) -- the one
+ * key that moves results, within that call's tolerance: it decides which chunks are folded together before the merge.
+ * Errors: BL_ERR_NULL, BL_ERR_SHAPE (unknown key/value).
  */
 bl_status bl_set_tuning(const char *key, int32_t value);
 

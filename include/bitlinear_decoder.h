@@ -182,9 +182,11 @@ bl_status bl_rope_table(float *table_dev, int32_t head_dim, int32_t max_pos, dou
  *                                     the partial results of the workgroups that share a head and one
  *                                     ticket counter per head, which the call puts back to zero).  Calls
  *                                     that may overlap in time must not share it.
- * One launch: (n_heads x ceil(max_pos / BL_ATTN_CHUNK)) workgroups, each over at most BL_ATTN_CHUNK cache
- * rows (those beyond p exit at once); the workgroup of a head that finishes last merges the head's
- * partial results -- it is told so by the ticket it draws; no workgroup waits for another.
+ * One launch: n_heads x G workgroups, G = min(ceil(max_pos / BL_ATTN_CHUNK), ceil(1024 / n_heads)); a head's
+ * workgroup y walks the chunks y, y + G, ... of BL_ATTN_CHUNK cache rows up to row p (one chunk each while
+ * p < 64 G; workgroups with nothing to walk exit at once) and keeps one running maximum, sum and weighted
+ * values; the workgroup of a head that finishes last merges the head's partial results -- it is told so by
+ * the ticket it draws; no workgroup waits for another.
  * head_dim must be a multiple of 4 (4 .. BL_ATTN_MAX_HEAD_DIM).
  * Errors: BL_ERR_NULL, BL_ERR_SHAPE, BL_ERR_ALIGN, BL_ERR_HIP.
  */

@@ -520,6 +520,11 @@ bl_status bl_set_tuning(const char* key, int32_t value) {
         bl::set_gemm_mb(value);
         return BL_OK;
     }
+    if (strcmp(key, "attn_groups") == 0) {
+        if (value < 0 || value > 65535) return BL_ERR_SHAPE;
+        bl::set_attn_groups(value);
+        return BL_OK;
+    }
     if (strcmp(key, "decode_split") == 0) {
         if (value < -1 || value > 8) return BL_ERR_SHAPE;
         bl::set_decode_split(value);

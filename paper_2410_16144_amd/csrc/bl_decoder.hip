@@ -420,8 +420,7 @@ __device__ __forceinline__ void unpack_bf16(const typename CacheVec<W>::type& u,
 // A value another workgroup of this launch has published (see publish below): read where it was deposited, by an
 // atomic that returns the old value and adds nothing.
 __device__ __forceinline__ float read_published(float* at) {
-    return __uint_as_float(__hip_atomic_fetch_add(reinterpret_cast<unsigned int*>(at), 0u, __ATOMIC_RELAXED,
-                                                  __HIP_MEMORY_SCOPE_AGENT));
+    return __uint_as_float(__hip_atomic_load(reinterpret_cast<unsigned int*>(at), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
 }
 
 __device__ __forceinline__ void attn_merge(const AttnArgs& p, float* scratch, float* out, int head, int used, float* s_f,
@@ -466,16 +465,18 @@ __device__ __forceinline__ void attn_merge(const AttnArgs& p, float* scratch, fl
 // rounded and appended).  Scores: every thread multiplies its W key values with the query's and leaves the partial
 // sum in LDS, one thread per row adds the head_dim / W partials.  The chunk's softmax is one wavefront.  The
 // values go to LDS as they are; thread (element, part) then adds its rows' weighted values.
-template <int W>
+// MAXD: the largest head size of this instance (128 or 256) -- registers and LDS are sized by it, and the smaller one
+// lets twice as many workgroups share a compute unit.
+template <int W, int MAXD>
 __global__ __launch_bounds__(kAttnThreads) void attn_chunk_kernel(const AttnArgs p) {
     typedef typename CacheVec<W>::type vec_t;
-    constexpr int kMaxLanesPerRow = BL_ATTN_MAX_HEAD_DIM / W;                 // 32 (W = 8) or 64 (W = 4)
-    constexpr int kVecs = kChunk * kMaxLanesPerRow / kAttnThreads;            // requests per thread at most: 8 / 16
-    __shared__ __attribute__((aligned(16))) float s_q[BL_ATTN_MAX_HEAD_DIM];  // rotated query / sqrt(head_dim)
-    __shared__ __attribute__((aligned(16))) float s_newk[BL_ATTN_MAX_HEAD_DIM];   // the token's own key and value as cached
-    __shared__ __attribute__((aligned(16))) float s_newv[BL_ATTN_MAX_HEAD_DIM];
+    constexpr int kMaxLanesPerRow = MAXD / W;
+    constexpr int kVecs = kChunk * kMaxLanesPerRow / kAttnThreads;            // requests per thread at most
+    __shared__ __attribute__((aligned(16))) float s_q[MAXD];                  // rotated query / sqrt(head_dim)
+    __shared__ __attribute__((aligned(16))) float s_newk[MAXD];               // the token's own key and value as cached
+    __shared__ __attribute__((aligned(16))) float s_newv[MAXD];
     __shared__ float s_part[kChunk * (kMaxLanesPerRow + 1)];
-    __shared__ __attribute__((aligned(16))) uint16_t s_v[kChunk * BL_ATTN_MAX_HEAD_DIM];
+    __shared__ __attribute__((aligned(16))) uint16_t s_v[kChunk * MAXD];
     __shared__ float s_w[kChunk];
     __shared__ float s_o[kAttnThreads];
     const int tid = threadIdx.x;
@@ -498,26 +499,32 @@ __global__ __launch_bounds__(kAttnThreads) void attn_chunk_kernel(const AttnArgs
     }
     const int pos = appended ? p.pos0 + query : *p.pos;
     if (pos < 0 || pos >= p.max_pos) return;            // uniform
-    const int j0 = chunk * kChunk;
-    if (j0 > pos) return;                               // uniform: nothing cached this far yet
-    const int rows = min(kChunk, pos + 1 - j0);
-    const bool owner = !appended && pos < j0 + kChunk;  // uniform: this chunk holds the row this launch appends
+    // Workgroup y of a head takes the chunks y, y + G, y + 2G, ... (G = workgroups per head in this launch) that hold
+    // rows up to the token's: one chunk each while the context is short, several once it outgrows the launch -- then
+    // a workgroup folds its chunks into ONE running maximum, sum and weighted values before it deposits anything.
+    const int groups = (int)gridDim.y;
+    const int last_chunk = pos / kChunk;
+    if (chunk > last_chunk) return;                     // uniform: nothing cached this far yet
+    const bool owner = !appended && last_chunk % groups == chunk;   // uniform: one of this workgroup's chunks holds the row this launch appends
     const int lanes_per_row = d / W;
     const int total = kChunk * lanes_per_row;           // a multiple of 64: the guards below are uniform per wave
 
     // rows beyond the token's are read as the token's row (always inside the cache) and never used; the token's own
     // row may be read while this workgroup writes it and is replaced by the values kept in LDS
     vec_t kv[kVecs], vv[kVecs];
+    const auto request = [&](int c) {
 #pragma unroll
-    for (int i = 0; i < kVecs; ++i) {
-        const int v = tid + i * kAttnThreads;
-        if (v < total) {
-            const int row = v / lanes_per_row, c = v - row * lanes_per_row;
-            const int64_t at = (int64_t)min(j0 + row, pos) * hidden + head * d + c * W;
-            kv[i] = *reinterpret_cast<const vec_t*>(p.k_cache + at);
-            vv[i] = *reinterpret_cast<const vec_t*>(p.v_cache + at);
+        for (int i = 0; i < kVecs; ++i) {
+            const int v = tid + i * kAttnThreads;
+            if (v < total) {
+                const int row = v / lanes_per_row, cc = v - row * lanes_per_row;
+                const int64_t at = (int64_t)min(c * kChunk + row, pos) * hidden + head * d + cc * W;
+                kv[i] = *reinterpret_cast<const vec_t*>(p.k_cache + at);
+                vv[i] = *reinterpret_cast<const vec_t*>(p.v_cache + at);
+            }
         }
-    }
+    };
+    request(chunk);
 
     const float scale = 1.0f / sqrtf((float)d);
     if (tid < half) {
@@ -535,83 +542,98 @@ __global__ __launch_bounds__(kAttnThreads) void attn_chunk_kernel(const AttnArgs
             s_newv[tid] = bf16_to_f32(v0); s_newv[tid + half] = bf16_to_f32(v1);
         }
     }
-    __syncthreads();
 
+    __shared__ float s_m, s_l;                          // the current chunk's maximum and sum
+    float run_m = -INFINITY, run_l = 0.0f, run_o = 0.0f;   // over the chunks so far (run_o: element tid, tid < d)
+    const int parts = kAttnThreads / d;                 // >= 1: head_dim <= 256
+    const int part = tid / d, e = tid - part * d;
+    for (int c = chunk; c <= last_chunk; c += groups) {
+        const int j0 = c * kChunk;
+        const int rows = min(kChunk, pos + 1 - j0);
+        const bool holds_token = owner && c == last_chunk;   // uniform
+        __syncthreads();                                // s_q and the token's row are there; the previous chunk's LDS has been read
 #pragma unroll
-    for (int i = 0; i < kVecs; ++i) {
-        const int v = tid + i * kAttnThreads;
-        if (v < total) {
-            const int row = v / lanes_per_row, c = v - row * lanes_per_row;
-            const bool own = owner && j0 + row == pos;   // this launch appends that row: its values are in LDS
-            float k[W];
-            unpack_bf16<W>(kv[i], k);
-            float acc = 0.0f;
+        for (int i = 0; i < kVecs; ++i) {
+            const int v = tid + i * kAttnThreads;
+            if (v < total) {
+                const int row = v / lanes_per_row, cc = v - row * lanes_per_row;
+                const bool own = holds_token && j0 + row == pos;   // this launch appends that row: its values are in LDS
+                float k[W];
+                unpack_bf16<W>(kv[i], k);
+                float acc = 0.0f;
 #pragma unroll
-            for (int e = 0; e < W; ++e) acc += s_q[c * W + e] * (own ? s_newk[c * W + e] : k[e]);
-            s_part[row * (lanes_per_row + 1) + c] = acc;
-            // values: to LDS as cached (the token's own row from the rounded values of this launch)
-            vec_t out = vv[i];
-            if (own) {
-                uint32_t* w = reinterpret_cast<uint32_t*>(&out);
+                for (int x = 0; x < W; ++x) acc += s_q[cc * W + x] * (own ? s_newk[cc * W + x] : k[x]);
+                s_part[row * (lanes_per_row + 1) + cc] = acc;
+                // values: to LDS as cached (the token's own row from the rounded values of this launch)
+                vec_t val = vv[i];
+                if (own) {
+                    uint32_t* w = reinterpret_cast<uint32_t*>(&val);
 #pragma unroll
-                for (int e = 0; e < W / 2; ++e)
-                    w[e] = (__float_as_uint(s_newv[c * W + 2 * e]) >> 16) | (__float_as_uint(s_newv[c * W + 2 * e + 1]) & 0xffff0000u);
+                    for (int x = 0; x < W / 2; ++x)
+                        w[x] = (__float_as_uint(s_newv[cc * W + 2 * x]) >> 16) | (__float_as_uint(s_newv[cc * W + 2 * x + 1]) & 0xffff0000u);
+                }
+                *reinterpret_cast<vec_t*>(s_v + row * d + cc * W) = val;
             }
-            *reinterpret_cast<vec_t*>(s_v + row * d + c * W) = out;
         }
-    }
-    __syncthreads();
+        if (c + groups <= last_chunk) request(c + groups);   // the next chunk travels while this one is worked on
+        __syncthreads();
 
-    // The head's chunks are merged by whichever of its workgroups finishes last.  Nobody waits for anybody: every
+        if (tid < kWave) {                              // wave 0: one row per lane
+            float score = -INFINITY;
+            if (tid < rows) {
+                score = 0.0f;
+                for (int cc = 0; cc < lanes_per_row; ++cc) score += s_part[tid * (lanes_per_row + 1) + cc];
+            }
+            float m = score;
+            for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
+            const float w = tid < rows ? expf(score - m) : 0.0f;
+            s_w[tid] = w;
+            const float l = wave_sum_f(w);
+            if (tid == 0) { s_m = m; s_l = l; }
+        }
+        __syncthreads();
+
+        float o = 0.0f;
+        if (part < parts)
+            for (int t = part; t < rows; t += parts) o += s_w[t] * bf16_to_f32(s_v[t * d + e]);
+        s_o[tid] = o;
+        __syncthreads();
+        // fold the chunk into the running figures: with one chunk the factors are 0 and 1, and the chunk's own
+        // figures come out unchanged
+        const float m_new = fmaxf(run_m, s_m);
+        const float f_run = expf(run_m - m_new), f_c = expf(s_m - m_new);
+        if (tid < d) {
+            float t = 0.0f;
+            for (int q = 0; q < parts; ++q) t += s_o[q * d + tid];
+            run_o = run_o * f_run + t * f_c;
+        }
+        run_l = run_l * f_run + s_l * f_c;
+        run_m = m_new;
+    }
+
+    // The head's workgroups are merged by whichever of them finishes last.  Nobody waits for anybody: every
     // workgroup DEPOSITS its figures with atomics that return the old value (so their completion can be waited for,
     // and they are performed where every compute unit's atomics meet, not in a cache of this die), then draws a
     // ticket from the head's counter the same way; the one that draws the last ticket reads all deposits, again with
-    // returning atomics, merges, and puts the counter back to zero for the next launch.  Data that crosses
+    // atomics, merges, and puts the counter back to zero for the next launch.  Data that crosses
     // workgroups inside this launch travels through atomics only -- no cache write-back or invalidation is involved
     // (a device-wide fence here cost 8-35 us per layer).
-    const int used = pos / kChunk + 1;                  // workgroups of this head that get this far
+    const int used = min(groups, last_chunk + 1);       // workgroups of this head that get this far
     const bool alone = used == 1;                       // uniform
     float* dst = scratch + ((int64_t)head * p.chunks + chunk) * (d + 2);
     unsigned int sink = 0;
-    __shared__ float s_l;
     const auto publish = [&](float* at, float v) {
         sink ^= __hip_atomic_exchange(reinterpret_cast<unsigned int*>(at), __float_as_uint(v), __ATOMIC_RELAXED,
                                            __HIP_MEMORY_SCOPE_AGENT);
     };
-    if (tid < kWave) {                                  // wave 0: one row per lane
-        float score = -INFINITY;
-        if (tid < rows) {
-            score = 0.0f;
-            for (int c = 0; c < lanes_per_row; ++c) score += s_part[tid * (lanes_per_row + 1) + c];
-        }
-        float m = score;
-        for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
-        const float w = tid < rows ? expf(score - m) : 0.0f;
-        s_w[tid] = w;
-        const float l = wave_sum_f(w);
+    if (alone) {
+        if (tid < d) out[head * d + tid] = run_o / run_l;   // the only workgroup: nothing is deposited
+    } else {
+        if (tid < d) publish(dst + tid, run_o);
         if (tid == 0) {
-            if (alone) {
-                s_l = l;        // the only chunk: its sum divides the weighted values below, nothing is deposited
-            } else {
-                publish(dst + d, m);
-                publish(dst + d + 1, l);
-            }
+            publish(dst + d, run_m);
+            publish(dst + d + 1, run_l);
         }
-    }
-    __syncthreads();
-
-    const int parts = kAttnThreads / d;                 // >= 1: head_dim <= 256
-    const int part = tid / d, e = tid - part * d;
-    float o = 0.0f;
-    if (part < parts)
-        for (int t = part; t < rows; t += parts) o += s_w[t] * bf16_to_f32(s_v[t * d + e]);
-    s_o[tid] = o;
-    __syncthreads();
-    if (tid < d) {
-        float t = 0.0f;
-        for (int q = 0; q < parts; ++q) t += s_o[q * d + tid];
-        if (alone) out[head * d + tid] = t / s_l;
-        else publish(dst + tid, t);
     }
     if (alone) return;                                  // uniform
     __shared__ unsigned int s_ticket;
@@ -906,6 +928,9 @@ __global__ void pos_advance_kernel(int32_t* pos) {
 
 }  // namespace
 
+constexpr int kAttnTargetWorkgroups = 1024;   // of bl_attn_decode: four per compute unit, what its registers let one hold (measured best)
+int g_attn_groups = 0;                        // forced workgroups per head (0: automatic)
+
 hipError_t launch_norm_quant(const bl_norm_quant_args& a, hipStream_t s) {
     NormArgs p;
     p.a = a.a_dev; p.b = a.b_dev; p.h = a.h_dev; p.gamma = a.gamma_dev;
@@ -942,6 +967,17 @@ hipError_t launch_rope_table(float* table, int head_dim, int max_pos, double the
 
 int attn_chunks(int max_pos) { return (max_pos + kChunk - 1) / kChunk; }
 
+static void launch_attn_chunks(const AttnArgs& p, const dim3& grid, hipStream_t s) {
+    const dim3 block(kAttnThreads);
+    if (p.head_dim % 8 == 0) {
+        if (p.head_dim <= 128) attn_chunk_kernel<8, 128><<<grid, block, 0, s>>>(p);
+        else attn_chunk_kernel<8, BL_ATTN_MAX_HEAD_DIM><<<grid, block, 0, s>>>(p);
+    } else {
+        if (p.head_dim <= 128) attn_chunk_kernel<4, 128><<<grid, block, 0, s>>>(p);
+        else attn_chunk_kernel<4, BL_ATTN_MAX_HEAD_DIM><<<grid, block, 0, s>>>(p);
+    }
+}
+
 hipError_t launch_attn_decode(const bl_attn_args& a, hipStream_t s) {
     AttnArgs p;
     p.q_lin = a.q_lin_dev; p.k_lin = a.k_lin_dev; p.v_lin = a.v_lin_dev; p.pos = a.pos_dev;
@@ -950,10 +986,16 @@ hipError_t launch_attn_decode(const bl_attn_args& a, hipStream_t s) {
     p.scratch = static_cast<float*>(a.scratch_dev);
     p.n_heads = a.n_heads; p.head_dim = a.head_dim; p.max_pos = a.max_pos; p.chunks = attn_chunks(a.max_pos);
     p.pos0 = 0; p.scratch_stride = 0;
-    if (a.head_dim % 8 == 0) attn_chunk_kernel<8><<<dim3((unsigned)a.n_heads, (unsigned)p.chunks), dim3(kAttnThreads), 0, s>>>(p);
-    else attn_chunk_kernel<4><<<dim3((unsigned)a.n_heads, (unsigned)p.chunks), dim3(kAttnThreads), 0, s>>>(p);
+    // Workgroups per head: one per chunk while that keeps the launch within a few workgroups per compute unit; a longer
+    // cache is walked by that many workgroups, several chunks each (a deposit per workgroup, not per chunk).
+    int groups = g_attn_groups > 0 ? g_attn_groups : (kAttnTargetWorkgroups + a.n_heads - 1) / a.n_heads;
+    if (groups > p.chunks) groups = p.chunks;
+    const dim3 grid((unsigned)a.n_heads, (unsigned)groups);
+    launch_attn_chunks(p, grid, s);
     return hipGetLastError();
 }
+
+void set_attn_groups(int groups) { g_attn_groups = groups; }
 
 int64_t attn_scratch_floats(int n_heads, int head_dim, int max_pos) {   // per query
     return (int64_t)n_heads * attn_chunks(max_pos) * (head_dim + 2) + n_heads;
@@ -987,8 +1029,7 @@ hipError_t launch_attn_prefill(const bl_attn_prefill_args& a, hipStream_t s) {
         default: break;
     }
     const dim3 grid((unsigned)a.n_heads, (unsigned)p.chunks, (unsigned)a.M);
-    if (a.head_dim % 8 == 0) attn_chunk_kernel<8><<<grid, dim3(kAttnThreads), 0, s>>>(p);
-    else attn_chunk_kernel<4><<<grid, dim3(kAttnThreads), 0, s>>>(p);
+    launch_attn_chunks(p, grid, s);
     return hipGetLastError();
 }
 

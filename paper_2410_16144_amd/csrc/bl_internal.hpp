@@ -149,6 +149,7 @@ hipError_t launch_attn_prefill(const ::bl_attn_prefill_args& a, hipStream_t s);
 
 // Launch-shape overrides for experiments (0 = choose automatically).
 void set_gemv_waves(int waves);
+void set_attn_groups(int groups);   // bl_attn_decode's workgroups per head; 0 automatic
 void set_gemm_mb(int mb);         // 0 automatic, else 100*(WK-1) + 10*MB + NB (see launch_gemm)
 void set_decode_stage(int v);     // 1: the matrix-core decode kernel never stages activations in LDS
 void set_decode_split(int v);     // -1 never split row blocks over workgroups, 0 automatic, n: n workgroups per compute unit

@@ -132,6 +132,9 @@ def test_argument_validation_happens_before_any_launch():
     assert _st(B.bl_set_tuning, "decode_split", 9) == B.BL_ERR_SHAPE
     assert _st(B.bl_set_tuning, "decode_split", -2) == B.BL_ERR_SHAPE
     B.bl_set_tuning("decode_split", 0)
+    assert _st(B.bl_set_tuning, "attn_groups", -1) == B.BL_ERR_SHAPE and _st(B.bl_set_tuning, "attn_groups", 65536) == B.BL_ERR_SHAPE
+    B.bl_set_tuning("attn_groups", 7)
+    B.bl_set_tuning("attn_groups", 0)
     assert B.bl_get_stat("nonsense") == -1 and B.bl_get_stat("split_launches") >= 0
     assert _st(B.bl_set_tuning, "nonsense", 1) == B.BL_ERR_SHAPE
     assert _st(B.bl_set_tuning, "gemv_waves", 3) == B.BL_ERR_SHAPE

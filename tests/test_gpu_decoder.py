@@ -203,6 +203,44 @@ def test_attn_decode_parity(dev, mods, n_heads, head_dim, max_pos, positions):
     np.testing.assert_array_equal(got_all[untouched], synth.to_bf16_bits(kc)[untouched])
 
 
+@pytest.mark.parametrize("groups", [1, 2, 3, 5])
+@pytest.mark.parametrize("n_heads,head_dim", [(3, 64), (2, 100), (1, 256)])
+def test_attn_decode_several_chunks_per_workgroup(dev, mods, groups, n_heads, head_dim):
+    """A cache longer than the launch has workgroups for: each of a head's `groups` workgroups walks every groups-th
+    chunk and folds them into one running maximum, sum and weighted values before the merge.  Positions that put the
+    appended row into the first, a middle and the last chunk a workgroup walks, a ragged last chunk, one chunk only;
+    every output against the fp64 softmax over the cache as stored, the counters back at zero."""
+    B, dec, ops = mods
+    max_pos, hidden = 700, n_heads * head_dim
+    r = _rng(53000 + hidden + groups)
+    table = dec.rope_table(head_dim, max_pos, dev)
+    q_t, k_t, v_t = (torch.empty((1, hidden), device=dev) for _ in range(3))
+    pos_t = torch.zeros(1, dtype=torch.int32, device=dev)
+    att = dec.Attention(n_heads, head_dim, max_pos, q_t, k_t, v_t, pos_t, table)
+    kc = _bf16(r.standard_normal((max_pos, hidden)))
+    vc = _bf16(r.standard_normal((max_pos, hidden)))
+    att.k_cache.copy_(_bits_as_bf16_tensor(synth.to_bf16_bits(kc), dev))
+    att.v_cache.copy_(_bits_as_bf16_tensor(synth.to_bf16_bits(vc), dev))
+    kc64, vc64 = kc.astype(np.float64), vc.astype(np.float64)
+    B.bl_set_tuning("attn_groups", groups)
+    try:
+        for pos in (0, 63, 64, 130, 320, 447, 448, 640, 699):
+            ql, kl, vl = (3.0 * r.standard_normal(hidden).astype(np.float32) for _ in range(3))
+            q_t.copy_(_t(ql[None], dev)); k_t.copy_(_t(kl[None], dev)); v_t.copy_(_t(vl[None], dev))
+            pos_t.fill_(pos)
+            out = att.launch()
+            torch.cuda.synchronize()
+            kc64[pos] = att.k_cache[pos].float().cpu().numpy().astype(np.float64)
+            vc64[pos] = att.v_cache[pos].float().cpu().numpy().astype(np.float64)
+            np.testing.assert_array_equal(att.v_cache[pos].view(torch.int16).cpu().numpy().view(np.uint16), synth.to_bf16_bits(vl))
+            want = D.attention_decode(D.rope(ql, pos, n_heads), kc64[:pos + 1], vc64[:pos + 1], n_heads)
+            got = out.cpu().numpy()[0]
+            assert np.abs(got - want).max() <= 2e-5 * max(1.0, np.abs(want).max()), (pos, float(np.abs(got - want).max()))
+            assert not att.scratch[-4 * n_heads:].view(torch.int32).any()
+    finally:
+        B.bl_set_tuning("attn_groups", 0)
+
+
 def test_attn_decode_out_of_range_position_does_nothing(dev, mods):
     B, dec, ops = mods
     n_heads, head_dim, max_pos = 2, 64, 16
