@@ -41,7 +41,7 @@ def parse_args():
     ap.add_argument("--full-100b", action="store_true",
                     help="extra: build all 80 layers of the 100B-shape model (37 GB packed) and time a whole token")
     ap.add_argument("--models", default="", help="with --only tokens: comma-separated Appendix-A model names (default: all 12)")
-    ap.add_argument("--only", default="", help="run only one extra section (copy|prefill|decode7b|decode100b|paper100b|config1|appendixa|tokens|prompt|tl2) and print it")
+    ap.add_argument("--only", default="", help="run only one extra section (copy|prefill|decode7b|decode100b|paper100b|config1|appendixa|tokens|tokens8k|prompt|tl2) and print it")
     return ap.parse_args()
 
 
@@ -578,6 +578,7 @@ def main():
                 "appendixa": lambda: extra_appendix_a(torch, use_graph),
                 "tokens": lambda: {"gpu": extra_decoder_tokens(torch, args.models.split(",") if args.models else None),
                                    "cpu_baseline": None if args.no_cpu else decoder_cpu_baseline()},
+                "tokens8k": lambda: extra_decoder_tokens(torch, args.models.split(",") if args.models else ["7B"], max_pos=8192),
                 "prompt": lambda: extra_prompt(torch, args.models.split(",") if args.models else None),
                 "tl2": lambda: extra_tl2(torch, use_graph),
                 }[args.only]()
@@ -659,6 +660,9 @@ def main():
         torch.cuda.empty_cache()
         # whole-model token rate, the paper's own unit, on three of Appendix A's shapes (all twelve: --only tokens)
         extra["decoder_tokens"] = extra_decoder_tokens(torch, ["700M", "7B", "30B"])
+        torch.cuda.empty_cache()
+        # a long context: the same loop on a cache of 8192 positions, timed at its start and at its end
+        extra["decoder_tokens_8k_cache"] = extra_decoder_tokens(torch, ["7B"], max_pos=8192)
         torch.cuda.empty_cache()
         # and the same block over a prompt of 512 tokens at once (more shapes: --only prompt --models ...)
         extra["decoder_prompt"] = extra_prompt(torch, ["7B"])
