@@ -241,6 +241,64 @@ def test_attn_decode_several_chunks_per_workgroup(dev, mods, groups, n_heads, he
         B.bl_set_tuning("attn_groups", 0)
 
 
+def test_attn_decode_long_context_as_launched(dev, mods):
+    """The 7B shape's attention (32 heads of 128) on a cache of 4096 positions, in the launch configuration the token
+    loop uses: 32 workgroups per head, two chunks each near the end of the cache.  Sampled positions against the fp64
+    softmax."""
+    B, dec, ops = mods
+    n_heads, head_dim, max_pos = 32, 128, 4096
+    hidden = n_heads * head_dim
+    r = _rng(54000)
+    table = dec.rope_table(head_dim, max_pos, dev)
+    q_t, k_t, v_t = (torch.empty((1, hidden), device=dev) for _ in range(3))
+    pos_t = torch.zeros(1, dtype=torch.int32, device=dev)
+    att = dec.Attention(n_heads, head_dim, max_pos, q_t, k_t, v_t, pos_t, table)
+    g = torch.Generator(device=dev).manual_seed(54001)
+    att.k_cache.copy_(torch.randn((max_pos, hidden), device=dev, generator=g))
+    att.v_cache.copy_(torch.randn((max_pos, hidden), device=dev, generator=g))
+    for pos in (2047, 2048, 3000, 4095):
+        ql, kl, vl = (3.0 * r.standard_normal(hidden).astype(np.float32) for _ in range(3))
+        q_t.copy_(_t(ql[None], dev)); k_t.copy_(_t(kl[None], dev)); v_t.copy_(_t(vl[None], dev))
+        pos_t.fill_(pos)
+        out = att.launch()
+        torch.cuda.synchronize()
+        kc64 = att.k_cache[:pos + 1].float().cpu().numpy().astype(np.float64)
+        vc64 = att.v_cache[:pos + 1].float().cpu().numpy().astype(np.float64)
+        want = D.attention_decode(D.rope(ql, pos, n_heads), kc64, vc64, n_heads)
+        got = out.cpu().numpy()[0]
+        assert np.abs(got - want).max() <= 2e-5 * max(1.0, np.abs(want).max()), (pos, float(np.abs(got - want).max()))
+    assert not att.scratch[-4 * n_heads:].view(torch.int32).any()
+
+
+def test_attn_prefill_long_prompt_sampled(dev, mods):
+    """A piece of 1000 tokens behind 700 cached ones (8 heads of 128: 16 blocks of 64 tokens per head, up to 27 chunks
+    each): sampled tokens against the fp64 softmax over the cache as stored."""
+    B, dec, ops = mods
+    n_heads, head_dim, max_pos, pos0, M = 8, 128, 1700, 700, 1000
+    hidden = n_heads * head_dim
+    r = _rng(54100)
+    table = dec.rope_table(head_dim, max_pos, dev)
+    g = torch.Generator(device=dev).manual_seed(54101)
+    k_cache = torch.randn((max_pos, hidden), device=dev, generator=g).to(torch.bfloat16)
+    v_cache = torch.randn((max_pos, hidden), device=dev, generator=g).to(torch.bfloat16)
+    lin = [3.0 * r.standard_normal((M, hidden)).astype(np.float32) for _ in range(3)]
+    lin_t = [_t(v, dev) for v in lin]
+    out = torch.empty((M, hidden), device=dev)
+    scratch = torch.zeros(B.bl_attn_prefill_scratch_bytes(n_heads, head_dim, pos0, M), dtype=torch.uint8, device=dev)
+    B.bl_attn_prefill(lin_t[0].data_ptr(), lin_t[1].data_ptr(), lin_t[2].data_ptr(), table.data_ptr(), k_cache.data_ptr(),
+                      v_cache.data_ptr(), out.data_ptr(), scratch.data_ptr(), n_heads, head_dim, max_pos, pos0, M,
+                      torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    kc64, vc64 = k_cache.float().cpu().numpy().astype(np.float64), v_cache.float().cpu().numpy().astype(np.float64)
+    got = out.cpu().numpy()
+    assert np.isfinite(got).all()
+    for m in (0, 63, 64, 500, 959, 960, 999):
+        want = D.attention_decode(D.rope(lin[0][m], pos0 + m, n_heads), kc64[:pos0 + m + 1], vc64[:pos0 + m + 1], n_heads)
+        assert np.abs(got[m] - want).max() <= PREFILL_BLOCK_TOL * max(1.0, np.abs(want).max()), m
+    want_v = synth.to_bf16_bits(lin[2][M - 1])
+    np.testing.assert_array_equal(v_cache[pos0 + M - 1].view(torch.int16).cpu().numpy().view(np.uint16), want_v)
+
+
 def test_attn_decode_out_of_range_position_does_nothing(dev, mods):
     B, dec, ops = mods
     n_heads, head_dim, max_pos = 2, 64, 16
