@@ -363,14 +363,19 @@ int g_force_mb = 0;
 
 // wave tile = (32*MB) tokens x (32*H) weight rows; workgroup = 4 waves, 4/WK along N and WK along K.
 // Choice by workgroup count: 64 x 128 wave tiles (half the LDS traffic per MFMA) when the grid still gives
-// every compute unit two workgroups; 64 x 64 otherwise; and the K-split form when even that grid would
+// every compute unit two workgroups; 64 x 64 otherwise; and 32 x 64 or the K-split form when even that grid would
 // leave compute units without work.  Forced value: 100*(WK-1) + 10*MB + H.  `rows`: padded weight rows of the launch.
 void choose_tile(int64_t M, int64_t rows, int& mb, int& h, int& wk) {
     const int64_t tiles_m = (M + 63) / 64;
     const auto wgs = [&](int wn, int hh) { return tiles_m * ((rows + wn * hh * 32 - 1) / (wn * hh * 32)); };
     mb = 2; h = 2; wk = 1;
     if (wgs(4, 4) >= 512) h = 4;
-    else if (wgs(4, 2) < 256) wk = 2;
+    else if (wgs(4, 2) < 256) {
+        // too few workgroups either way: 32-token tiles from 128 tokens up (measured 5-8 % ahead of the K split on
+        // shapes from 1536^2 to 8192^2), the K split below
+        if (M >= 128) mb = 1;
+        else wk = 2;
+    }
     if (g_force_mb) { wk = g_force_mb / 100 + 1; mb = g_force_mb / 10 % 10; h = g_force_mb % 10; }
 }
 
