@@ -182,7 +182,7 @@ bl_status bl_rope_table(float *table_dev, int32_t head_dim, int32_t max_pos, dou
  *                                     the partial results of the workgroups that share a head and one
  *                                     ticket counter per head, which the call puts back to zero).  Calls
  *                                     that may overlap in time must not share it.
- * One launch: n_heads x G workgroups, G = min(ceil(max_pos / BL_ATTN_CHUNK), ceil(1024 / n_heads)); a head's
+ * One launch: n_heads x G workgroups, G = min(ceil(max_pos / BL_ATTN_CHUNK), ceil(1024 / n_heads), 32); a head's
  * workgroup y walks the chunks y, y + G, ... of BL_ATTN_CHUNK cache rows up to row p (one chunk each while
  * p < 64 G; workgroups with nothing to walk exit at once) and keeps one running maximum, sum and weighted
  * values; the workgroup of a head that finishes last merges the head's partial results -- it is told so by

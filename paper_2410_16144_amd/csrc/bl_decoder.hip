@@ -459,12 +459,12 @@ __device__ __forceinline__ void attn_merge(const AttnArgs& p, float* scratch, fl
     if (tid < d) out[head * d + tid] = o / l;
 }
 
-// One (head, chunk of 64 cache rows) per workgroup.  The chunk's keys and values (64 x head_dim bf16 each) are
-// requested first, W values per thread and request, consecutive threads on consecutive addresses of a row; while
-// they travel the query is rotated (and, in the chunk that holds the token's own row, key and value are rotated,
-// rounded and appended).  Scores: every thread multiplies its W key values with the query's and leaves the partial
-// sum in LDS, one thread per row adds the head_dim / W partials.  The chunk's softmax is one wavefront.  The
-// values go to LDS as they are; thread (element, part) then adds its rows' weighted values.
+// A chunk is 64 cache rows.  Its keys and values (64 x head_dim bf16 each) are requested as W values per thread and
+// request, MAXD / W consecutive lanes on one row; while they travel the query is rotated (and, in the chunk that
+// holds the token's own row, key and value are rotated, rounded and appended).  A wave keeps everything about its 16
+// rows to itself: the partial dot products of a row meet by lane exchanges, the wave takes its own maximum, weights
+// and sum, multiplies its value vectors in registers and adds them up across its rows by lane exchanges again; only
+// the four waves' figures (maximum, sum, head_dim weighted values each) meet in LDS.  Two barriers per chunk.
 // MAXD: the largest head size of this instance (128 or 256) -- registers and LDS are sized by it, and the smaller one
 // lets twice as many workgroups share a compute unit.
 template <int W, int MAXD>
@@ -475,10 +475,10 @@ __global__ __launch_bounds__(kAttnThreads) void attn_chunk_kernel(const AttnArgs
     __shared__ __attribute__((aligned(16))) float s_q[MAXD];                  // rotated query / sqrt(head_dim)
     __shared__ __attribute__((aligned(16))) float s_newk[MAXD];               // the token's own key and value as cached
     __shared__ __attribute__((aligned(16))) float s_newv[MAXD];
-    __shared__ float s_part[kChunk * (kMaxLanesPerRow + 1)];
-    __shared__ __attribute__((aligned(16))) uint16_t s_v[kChunk * MAXD];
-    __shared__ float s_w[kChunk];
-    __shared__ float s_o[kAttnThreads];
+    __shared__ float s_ow[kAttnWaves][MAXD];            // per wave: weighted values of its rows
+    __shared__ float s_mw[kAttnWaves], s_lw[kAttnWaves];   // per wave: maximum and sum
+    __shared__ float s_w[kChunk];                       // the merge's partial results
+    __shared__ float s_o[kAttnThreads];                 // the merge's factors
     const int tid = threadIdx.x;
     const int head = blockIdx.x, chunk = blockIdx.y;
     const int d = p.head_dim, half = d / 2;
@@ -506,25 +506,27 @@ __global__ __launch_bounds__(kAttnThreads) void attn_chunk_kernel(const AttnArgs
     const int last_chunk = pos / kChunk;
     if (chunk > last_chunk) return;                     // uniform: nothing cached this far yet
     const bool owner = !appended && last_chunk % groups == chunk;   // uniform: one of this workgroup's chunks holds the row this launch appends
-    const int lanes_per_row = d / W;
-    const int total = kChunk * lanes_per_row;           // a multiple of 64: the guards below are uniform per wave
+    constexpr int L = kMaxLanesPerRow;                  // lanes per cache row: a power of two; those beyond head_dim / W idle
+    constexpr int kRowsPerStep = kAttnThreads / L;      // rows the workgroup takes per request
+    const int lane = tid % kWave, wave = tid / kWave;
+    const int grp = tid / L, cc = tid % L;
+    const bool active = cc * W < d;
 
     // rows beyond the token's are read as the token's row (always inside the cache) and never used; the token's own
     // row may be read while this workgroup writes it and is replaced by the values kept in LDS
     vec_t kv[kVecs], vv[kVecs];
-    const auto request = [&](int c) {
+    const auto request = [&](int c, bool keys) {
 #pragma unroll
         for (int i = 0; i < kVecs; ++i) {
-            const int v = tid + i * kAttnThreads;
-            if (v < total) {
-                const int row = v / lanes_per_row, cc = v - row * lanes_per_row;
-                const int64_t at = (int64_t)min(c * kChunk + row, pos) * hidden + head * d + cc * W;
-                kv[i] = *reinterpret_cast<const vec_t*>(p.k_cache + at);
-                vv[i] = *reinterpret_cast<const vec_t*>(p.v_cache + at);
+            if (active) {
+                const int64_t at = (int64_t)min(c * kChunk + grp + i * kRowsPerStep, pos) * hidden + head * d + cc * W;
+                if (keys) kv[i] = *reinterpret_cast<const vec_t*>(p.k_cache + at);
+                else vv[i] = *reinterpret_cast<const vec_t*>(p.v_cache + at);
             }
         }
     };
-    request(chunk);
+    request(chunk, true);
+    request(chunk, false);
 
     const float scale = 1.0f / sqrtf((float)d);
     if (tid < half) {
@@ -543,71 +545,82 @@ __global__ __launch_bounds__(kAttnThreads) void attn_chunk_kernel(const AttnArgs
         }
     }
 
-    __shared__ float s_m, s_l;                          // the current chunk's maximum and sum
     float run_m = -INFINITY, run_l = 0.0f, run_o = 0.0f;   // over the chunks so far (run_o: element tid, tid < d)
-    const int parts = kAttnThreads / d;                 // >= 1: head_dim <= 256
-    const int part = tid / d, e = tid - part * d;
     for (int c = chunk; c <= last_chunk; c += groups) {
         const int j0 = c * kChunk;
         const int rows = min(kChunk, pos + 1 - j0);
         const bool holds_token = owner && c == last_chunk;   // uniform
-        __syncthreads();                                // s_q and the token's row are there; the previous chunk's LDS has been read
+        const bool more = c + groups <= last_chunk;          // uniform
+        __syncthreads();                                // s_q and the token's row are there; the previous chunk's figures have been read
+        float score[kVecs];
 #pragma unroll
         for (int i = 0; i < kVecs; ++i) {
-            const int v = tid + i * kAttnThreads;
-            if (v < total) {
-                const int row = v / lanes_per_row, cc = v - row * lanes_per_row;
-                const bool own = holds_token && j0 + row == pos;   // this launch appends that row: its values are in LDS
+            const int row = grp + i * kRowsPerStep;
+            const bool own = holds_token && j0 + row == pos;   // this launch appends that row: its values are in LDS
+            float acc = 0.0f;
+            if (active) {
                 float k[W];
                 unpack_bf16<W>(kv[i], k);
-                float acc = 0.0f;
 #pragma unroll
                 for (int x = 0; x < W; ++x) acc += s_q[cc * W + x] * (own ? s_newk[cc * W + x] : k[x]);
-                s_part[row * (lanes_per_row + 1) + cc] = acc;
-                // values: to LDS as cached (the token's own row from the rounded values of this launch)
-                vec_t val = vv[i];
-                if (own) {
-                    uint32_t* w = reinterpret_cast<uint32_t*>(&val);
+            }
 #pragma unroll
-                    for (int x = 0; x < W / 2; ++x)
-                        w[x] = (__float_as_uint(s_newv[cc * W + 2 * x]) >> 16) | (__float_as_uint(s_newv[cc * W + 2 * x + 1]) & 0xffff0000u);
-                }
-                *reinterpret_cast<vec_t*>(s_v + row * d + cc * W) = val;
+            for (int off = 1; off < L; off <<= 1) acc += __shfl_xor(acc, off);
+            score[i] = row < rows ? acc : -INFINITY;
+        }
+        if (more) request(c + groups, true);            // the next chunk travels while this one is worked on
+        float m_w = score[0];
+#pragma unroll
+        for (int i = 1; i < kVecs; ++i) m_w = fmaxf(m_w, score[i]);
+#pragma unroll
+        for (int off = L; off < kWave; off <<= 1) m_w = fmaxf(m_w, __shfl_xor(m_w, off));
+        float l_w = 0.0f, o_w[W];
+#pragma unroll
+        for (int x = 0; x < W; ++x) o_w[x] = 0.0f;
+#pragma unroll
+        for (int i = 0; i < kVecs; ++i) {
+            const int row = grp + i * kRowsPerStep;
+            const bool own = holds_token && j0 + row == pos;
+            const float w = m_w == -INFINITY ? 0.0f : expf(score[i] - m_w);   // a wave without rows adds nothing
+            l_w += w;
+            if (active) {
+                float v[W];
+                unpack_bf16<W>(vv[i], v);
+#pragma unroll
+                for (int x = 0; x < W; ++x) o_w[x] += w * (own ? s_newv[cc * W + x] : v[x]);
             }
         }
-        if (c + groups <= last_chunk) request(c + groups);   // the next chunk travels while this one is worked on
-        __syncthreads();
-
-        if (tid < kWave) {                              // wave 0: one row per lane
-            float score = -INFINITY;
-            if (tid < rows) {
-                score = 0.0f;
-                for (int cc = 0; cc < lanes_per_row; ++cc) score += s_part[tid * (lanes_per_row + 1) + cc];
-            }
-            float m = score;
-            for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
-            const float w = tid < rows ? expf(score - m) : 0.0f;
-            s_w[tid] = w;
-            const float l = wave_sum_f(w);
-            if (tid == 0) { s_m = m; s_l = l; }
+        if (more) request(c + groups, false);
+#pragma unroll
+        for (int off = L; off < kWave; off <<= 1) {
+            l_w += __shfl_xor(l_w, off);
+#pragma unroll
+            for (int x = 0; x < W; ++x) o_w[x] += __shfl_xor(o_w[x], off);
         }
+        if (lane < L && active) {
+#pragma unroll
+            for (int x = 0; x < W; ++x) s_ow[wave][cc * W + x] = o_w[x];
+        }
+        if (lane == 0) { s_mw[wave] = m_w; s_lw[wave] = l_w; }
         __syncthreads();
-
-        float o = 0.0f;
-        if (part < parts)
-            for (int t = part; t < rows; t += parts) o += s_w[t] * bf16_to_f32(s_v[t * d + e]);
-        s_o[tid] = o;
-        __syncthreads();
-        // fold the chunk into the running figures: with one chunk the factors are 0 and 1, and the chunk's own
-        // figures come out unchanged
-        const float m_new = fmaxf(run_m, s_m);
-        const float f_run = expf(run_m - m_new), f_c = expf(s_m - m_new);
+        // the four waves' figures into the chunk's, and the chunk into the running ones
+        static_assert(kAttnWaves == 4, "four waves' figures");
+        const float m_c = fmaxf(fmaxf(s_mw[0], s_mw[1]), fmaxf(s_mw[2], s_mw[3]));   // finite: the chunk has a row
+        float f_w[kAttnWaves], l_c = 0.0f;
+#pragma unroll
+        for (int q = 0; q < kAttnWaves; ++q) {
+            f_w[q] = s_mw[q] == -INFINITY ? 0.0f : expf(s_mw[q] - m_c);
+            l_c += f_w[q] * s_lw[q];
+        }
+        const float m_new = fmaxf(run_m, m_c);
+        const float f_run = expf(run_m - m_new), f_c = expf(m_c - m_new);
         if (tid < d) {
             float t = 0.0f;
-            for (int q = 0; q < parts; ++q) t += s_o[q * d + tid];
+#pragma unroll
+            for (int q = 0; q < kAttnWaves; ++q) t += f_w[q] * s_ow[q][tid];
             run_o = run_o * f_run + t * f_c;
         }
-        run_l = run_l * f_run + s_l * f_c;
+        run_l = run_l * f_run + l_c * f_c;
         run_m = m_new;
     }
 
@@ -928,7 +941,8 @@ __global__ void pos_advance_kernel(int32_t* pos) {
 
 }  // namespace
 
-constexpr int kAttnTargetWorkgroups = 1024;   // of bl_attn_decode: four per compute unit, what its registers let one hold (measured best)
+constexpr int kAttnTargetWorkgroups = 1024;   // of bl_attn_decode: four per compute unit (measured best on 32 heads of 128)
+constexpr int kAttnMaxGroups = 32;            // per head, however few heads there are (16 heads of 96: 32 beat 64)
 int g_attn_groups = 0;                        // forced workgroups per head (0: automatic)
 
 hipError_t launch_norm_quant(const bl_norm_quant_args& a, hipStream_t s) {
@@ -988,7 +1002,7 @@ hipError_t launch_attn_decode(const bl_attn_args& a, hipStream_t s) {
     p.pos0 = 0; p.scratch_stride = 0;
     // Workgroups per head: one per chunk while that keeps the launch within a few workgroups per compute unit; a longer
     // cache is walked by that many workgroups, several chunks each (a deposit per workgroup, not per chunk).
-    int groups = g_attn_groups > 0 ? g_attn_groups : (kAttnTargetWorkgroups + a.n_heads - 1) / a.n_heads;
+    int groups = g_attn_groups > 0 ? g_attn_groups : min(kAttnMaxGroups, (kAttnTargetWorkgroups + a.n_heads - 1) / a.n_heads);
     if (groups > p.chunks) groups = p.chunks;
     const dim3 grid((unsigned)a.n_heads, (unsigned)groups);
     launch_attn_chunks(p, grid, s);
