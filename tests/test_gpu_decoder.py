@@ -204,7 +204,7 @@ def test_attn_decode_parity(dev, mods, n_heads, head_dim, max_pos, positions):
 
 
 @pytest.mark.parametrize("groups", [1, 2, 3, 5])
-@pytest.mark.parametrize("n_heads,head_dim", [(3, 64), (2, 100), (1, 256)])
+@pytest.mark.parametrize("n_heads,head_dim", [(3, 64), (2, 100), (1, 256), (2, 132), (5, 4)])
 def test_attn_decode_several_chunks_per_workgroup(dev, mods, groups, n_heads, head_dim):
     """A cache longer than the launch has workgroups for: each of a head's `groups` workgroups walks every groups-th
     chunk and folds them into one running maximum, sum and weighted values before the merge.  Positions that put the
