@@ -488,6 +488,18 @@ def test_decode_norm_batch_zero_row(dev, mods):
     assert not out.any() and float(grp.quants[0].a_scale[0]) == 0.0 and not grp.quants[0].q.any()
 
 
+@pytest.mark.parametrize("waves", [4, 8, 16])
+def test_gated_launch_with_forced_waves_per_row_block(dev, mods, waves):
+    """The gated epilogue when a workgroup holds one, two or four row blocks."""
+    B, dec, ops = mods
+    B.bl_set_tuning("gemv_waves", waves)
+    try:
+        test_gated_launch_and_its_consumer(dev, mods, 4096, 12032, True)
+        test_gated_launch_and_its_consumer(dev, mods, 768, 3072, False)
+    finally:
+        B.bl_set_tuning("gemv_waves", 0)
+
+
 @pytest.mark.parametrize("K,F,with_delta", [(768, 3072, True), (4096, 12032, True), (1536, 4096, False), (64, 32, True),
                                           (3200, 8640, True), (512, 20000, True), (8192, 45568, False)])
 def test_gated_launch_and_its_consumer(dev, mods, K, F, with_delta):
