@@ -676,7 +676,8 @@ PREFILL_BLOCK_TOL = 2e-5
 
 @pytest.mark.parametrize("n_heads,head_dim,max_pos,pos0,M", [(3, 64, 300, 0, 70), (3, 64, 300, 130, 100), (20, 128, 80, 5, 9),
                                                            (5, 40, 70, 0, 70), (2, 256, 200, 63, 2), (4, 100, 400, 37, 300),
-                                                           (2, 120, 200, 0, 130), (2, 48, 100, 10, 64), (1, 16, 70, 63, 1)])
+                                                           (2, 120, 200, 0, 130), (2, 48, 100, 10, 64), (1, 16, 70, 63, 1), (3, 4, 140, 5, 130),
+                                                           (2, 36, 90, 0, 65)])
 def test_attn_prefill_parity(dev, mods, n_heads, head_dim, max_pos, pos0, M):
     """A prompt's attention: token m against cache rows 0 .. pos0 + m.  The appended rows as in the one-token call, bit
     for bit; every token's output against the fp64 softmax over the cache as stored, and against what M one-token calls
