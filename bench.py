@@ -41,7 +41,7 @@ def parse_args():
     ap.add_argument("--full-100b", action="store_true",
                     help="extra: build all 80 layers of the 100B-shape model (37 GB packed) and time a whole token")
     ap.add_argument("--models", default="", help="with --only tokens: comma-separated Appendix-A model names (default: all 12)")
-    ap.add_argument("--only", default="", help="run only one extra section (copy|prefill|decode7b|decode100b|paper100b|config1|appendixa|tokens|tokens8k|prompt|tl2) and print it")
+    ap.add_argument("--only", default="", help="run only one extra section (copy|prefill|decode7b|decode100b|paper100b|config1|appendixa|tokens|tokens8k|prompt|prompt2k|tl2) and print it")
     return ap.parse_args()
 
 
@@ -580,6 +580,7 @@ def main():
                                    "cpu_baseline": None if args.no_cpu else decoder_cpu_baseline()},
                 "tokens8k": lambda: extra_decoder_tokens(torch, args.models.split(",") if args.models else ["7B"], max_pos=8192),
                 "prompt": lambda: extra_prompt(torch, args.models.split(",") if args.models else None),
+                "prompt2k": lambda: extra_prompt(torch, args.models.split(",") if args.models else ["7B"], M=2048, max_pos=4096),
                 "tl2": lambda: extra_tl2(torch, use_graph),
                 }[args.only]()
         print(json.dumps({args.only: sect}))
