@@ -287,3 +287,14 @@ def test_attn_prefill_validation():
     assert B.bl_attn_prefill_scratch_bytes(4, 64, 60, 10) == 16 == B.bl_attn_prefill_scratch_bytes(4, 128, 0, 1)
     assert B.bl_attn_prefill_scratch_bytes(4, 64, 0, 0) == 0 and B.bl_attn_prefill_scratch_bytes(4, 62, 0, 5) == 0
     assert ctypes.sizeof(B.AttnPrefillArgs) == 88
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py is a one-GPU program: any other --gpus value ends with a message and a non-zero status before
+    anything touches a device."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
