@@ -451,12 +451,12 @@ static void plan_decode(DecodeBatch& b, int tiles_per_wave) {
             if (total >= cus || widest < 0) break;
             ++b.p[widest].wlog2;
         }
-        // The gated launch quantizes its input in every workgroup.  With between one and two row blocks per compute
-        // unit some units get two workgroups and the rest one: two row blocks per workgroup take the same two turns
-        // with half the workgroups.
+        // The gated launch quantizes its input in every workgroup.  With more row blocks than compute units, two row
+        // blocks per workgroup halve the workgroups and their quantizations; between one and two row blocks per unit
+        // they also even out the turns (some units had two workgroups, the rest one).
         for (int i = 0; i < b.count; ++i) {
             DecodeProblem& p = b.p[i];
-            if (b.count == 1 && p.glu_gamma && p.wlog2 == 4 && p.row_blocks > cus && p.row_blocks <= 2 * cus) p.wlog2 = 3;
+            if (b.count == 1 && p.glu_gamma && p.wlog2 == 4 && p.row_blocks > cus) p.wlog2 = 3;
         }
     }
     for (int i = 0; i < b.count; ++i) work[i] = (int64_t)(kWaves >> b.p[i].wlog2) * b.p[i].KC;   // tiles per workgroup
