@@ -41,6 +41,7 @@ _lib.orc_quant_act.argtypes = [_vp, ctypes.c_int, _i64, _i64, _i64, _vp, _i64, _
 _lib.orc_matmul_i32.argtypes = [_vp, _i64, _i64, _i64, _vp, _i64, _vp]
 _lib.orc_matmul_i32_cols.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _i64, _vp]
 _lib.orc_dequant.argtypes = [_vp, _i64, _i64, _f32, _vp, _vp]
+_lib.orc_bitlinear.argtypes = [_vp, ctypes.c_int, _i64, _i64, _i64, _vp, _i64, _f32, _vp, _vp, _vp, _vp]
 _lib.orc_tl1_gemv_i32.argtypes = [_vp, _i64, _vp, _i64, _vp]
 _lib.orc_tl2_gemv_i32.argtypes = [_vp, _i64, _vp, _i64, _vp]
 _lib.orc_tl2_encode_rows.argtypes = [_vp, _i64, _i64, _vp]
@@ -196,6 +197,28 @@ def bitlinear(x, w, w_scale):
     acc = matmul_i32(q, w)
     out = dequant(acc, w_scale, a)
     return {"q": q, "a_scale": a, "q_sum": s, "acc": acc, "out": out}
+
+
+def bitlinear_whole(x, w, w_scale):
+    """The C oracle's one-call forward (orc_bitlinear): quantize, integer product, dequantize inside one C
+    function.  Returns dict(q, a_scale, acc, out); must agree bit for bit with bitlinear()."""
+    x = np.ascontiguousarray(x)
+    if x.dtype == np.float32:
+        is_bf16 = 0
+    elif x.dtype == np.uint16:
+        is_bf16 = 1
+    else:
+        raise TypeError("activations must be float32 or uint16 (bf16 bits)")
+    w = _c(w, np.int8)
+    m, k = x.shape
+    n, k2 = w.shape
+    assert k == k2
+    q = np.empty((m, k), np.int8)
+    a = np.empty((m,), np.float32)
+    acc = np.empty((m, n), np.int32)
+    out = np.empty((m, n), np.float32)
+    _lib.orc_bitlinear(_p(x), is_bf16, m, k, k, _p(w), n, float(np.float32(w_scale)), _p(q), _p(a), _p(acc), _p(out))
+    return {"q": q, "a_scale": a, "acc": acc, "out": out}
 
 
 def tl1_gemv_i32(q_row, w):

@@ -103,11 +103,14 @@ def make_inputs(seed: int, hidden: int, ffn: int, M: int, device, outlier_frac: 
 
 
 def make_layer(config: int, layer: int, hidden: int, ffn: int, M: int, device, p_zero: Optional[float],
-               outlier_frac: float, host: bool = False):
+               outlier_frac: float, host: bool = False, keep_rows=None):
     """Build one synthetic layer.  host=True draws everything with numpy on the host (and also
-    returns the host copies, for the oracle); host=False draws on the device."""
+    returns the host copies, for the oracle); host=False draws on the device.  keep_rows (device
+    draw only): per projection an index array; those rows of the DRAWN int8 matrix are copied to the
+    host before the matrix is freed and returned as {"w_rows": [...], "w_scale": [...]}, so that a
+    parity test can feed the oracle the weights as drawn rather than as unpacked."""
     projs = synth.layer_projections(hidden, ffn)
-    weights, host_w, scales = [], [], []
+    weights, host_w, scales, kept = [], [], [], []
     for i, p in enumerate(projs):
         seed = synth.seed_for(config, layer, i)
         rng = synth.rng_for(seed)
@@ -118,6 +121,8 @@ def make_layer(config: int, layer: int, hidden: int, ffn: int, M: int, device, p
             wd = torch.from_numpy(w).to(device)
         else:
             wd = synth.ternary_weights_device(seed, p.N, p.K, device, p_zero=p_zero)
+            if keep_rows is not None:
+                kept.append(wd[torch.as_tensor(np.asarray(keep_rows[i]), device=device)].cpu().numpy())
         weights.append(ops.pack_ternary(wd, scale))
         scales.append(np.float32(scale))
         del wd
@@ -125,4 +130,6 @@ def make_layer(config: int, layer: int, hidden: int, ffn: int, M: int, device, p
     lay = DecodeLayer(hidden, ffn, M, device, weights, xs)
     if host:
         return lay, {"w": host_w, "w_scale": scales, "x_bits": bits}
+    if keep_rows is not None:
+        return lay, {"w_rows": kept, "w_scale": scales}
     return lay, None

@@ -143,11 +143,15 @@ def test_config5_100b_whole_layer_fused_launch(dev, ops):
 
 @pytest.mark.parametrize("layer_index", [1, 79])
 def test_config5_100b_device_drawn_layers_sampled_rows(dev, ops, layer_index):
-    """Layers drawn on the device (as the 37 GB benchmark model is): the weights come back through
-    bl_unpack_ternary, and 64 seeded output rows per matrix plus the first and last row are checked
-    against the oracle, which computes those rows one by one."""
+    """Layers drawn on the device (as the 37 GB benchmark model is): 64 seeded rows per matrix plus the
+    first and last row of the DRAWN int8 matrix are copied to the host before the matrix is packed and
+    freed; the oracle computes those outputs one by one from them.  Second assertion: the same rows
+    come back unchanged through bl_unpack_ternary."""
     from paper_2410_16144_amd.decode_layer import INPUT_OF, make_layer
-    layer, _ = make_layer(5, layer_index, 12288, 33792, 1, dev, None, 0.0)
+    rng = synth.rng_for(synth.seed_for(5, layer_index, 8))
+    projs = synth.layer_projections(12288, 33792)
+    rows_of = [np.unique(np.concatenate([rng.integers(0, p.N, 64), [0, p.N - 1]])) for p in projs]
+    layer, drawn = make_layer(5, layer_index, 12288, 33792, 1, dev, None, 0.0, keep_rows=rows_of)
     layer.step_fused()
     torch.cuda.synchronize()
     fused = [o.cpu().numpy().copy() for o in layer.outs]
@@ -157,15 +161,16 @@ def test_config5_100b_device_drawn_layers_sampled_rows(dev, ops, layer_index):
     torch.cuda.synchronize()
     x_bits = [x.view(torch.int16).cpu().numpy().view(np.uint16) for x in layer.xs]
     refs_q = [oracle.quant_act(b) for b in x_bits]
-    rng = synth.rng_for(synth.seed_for(5, layer_index, 8))
     for i, p in enumerate(layer.projs):
         q, a, s = refs_q[INPUT_OF[p.name]]
-        rows = np.unique(np.concatenate([rng.integers(0, p.N, 64), [0, p.N - 1]]))
-        w_rows = ops.unpack_ternary(layer.weights[i])[torch.from_numpy(rows).to(dev)].cpu().numpy()
-        assert set(np.unique(w_rows)) <= {-1, 0, 1}
+        rows, w_rows = rows_of[i], drawn["w_rows"][i]
+        assert w_rows.shape == (rows.size, p.K) and set(np.unique(w_rows)) <= {-1, 0, 1}
         acc_ref = oracle.matmul_i32(q, np.ascontiguousarray(w_rows))
-        w_scale = np.float32(layer.weights[i].desc.w_scale)
+        w_scale = drawn["w_scale"][i]
+        assert w_scale == np.float32(layer.weights[i].desc.w_scale)
         for got in (fused[i], layer.outs[i].cpu().numpy()):
             _check_out(got[:, rows], acc_ref, w_scale, a)
+        back = ops.unpack_ternary(layer.weights[i])[torch.from_numpy(rows).to(dev)].cpu().numpy()
+        assert np.array_equal(back, w_rows)
     del layer
     torch.cuda.empty_cache()

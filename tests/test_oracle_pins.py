@@ -365,6 +365,37 @@ def test_dequant_definition():
     assert np.allclose(out, ref, rtol=3 * 2.0 ** -24, atol=0)
 
 
+def test_whole_forward_hand_case_and_brute_force():
+    # the one-call forward of the C oracle (quantize -> integer product -> dequantize inside one function)
+    # hand-worked row: amax = 4, inv = 31.75 exactly, q = [32, -64, 16, 127], a_scale = 4/127
+    x = np.array([[1.0, -2.0, 0.5, 4.0]], np.float32)
+    w = np.array([[1, 1, 1, 1], [1, 0, -1, 0], [0, 0, 0, -1]], np.int8)     # N = 3, K = 4
+    r = oracle.bitlinear_whole(x, w, np.float32(0.5))
+    assert r["q"].tolist() == [[32, -64, 16, 127]]
+    assert r["a_scale"][0] == np.float32(4.0) / np.float32(127.0)
+    assert r["acc"].tolist() == [[111, 16, -127]]
+    s = np.float32(0.5) * (np.float32(4.0) / np.float32(127.0))            # halving is exact
+    assert r["out"].tolist() == [[float(np.float32(111) * s), float(np.float32(16) * s), float(np.float32(-127) * s)]]
+    assert r["out"][0, 2] == np.float32(-2.0)                               # -127 * 0.5 * 4/127 up to its two roundings
+    # bf16 input, strided operand shapes (N != K), against exact integer and float64 brute force
+    rng = synth.rng_for(31)
+    for M, K, N in ((1, 1, 1), (2, 67, 9), (3, 33, 8)):
+        wt = synth.ternary_weights(rng, N, K)
+        ws = synth.draw_w_scale(rng)
+        xb = synth.to_bf16_bits(synth.activations(rng, M, K, outlier_frac=0.05))
+        r = oracle.bitlinear_whole(xb, wt, ws)
+        xf = synth.bf16_bits_to_f32(xb).astype(np.float64)
+        amax = np.abs(xf).max(axis=1)
+        assert np.all(np.abs(r["q"]).max(axis=1) == 127) and np.allclose(r["a_scale"], amax / 127, rtol=2.0 ** -23)
+        assert np.array_equal(r["acc"], (r["q"].astype(np.int64) @ wt.astype(np.int64).T).astype(np.int32))
+        ref = (r["q"].astype(np.float64) * r["a_scale"].astype(np.float64)[:, None]) @ (wt.astype(np.float64) * np.float64(ws)).T
+        assert np.allclose(r["out"], ref, rtol=1e-6, atol=0.0)
+        # and it is the three-call composition, bit for bit
+        c = oracle.bitlinear(xb, wt, ws)
+        for key in ("q", "a_scale", "acc", "out"):
+            assert np.array_equal(r[key], c[key]), key
+
+
 # ---------------------------------------------------------------- the paper's LUT kernels agree
 
 @pytest.mark.parametrize("K", [1, 2, 3, 7, 64, 65, 129, 200])
