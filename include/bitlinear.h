@@ -43,7 +43,8 @@ typedef enum {
     BL_ERR_DTYPE = 6,       /* unknown bl_dtype                                   */
     BL_ERR_LAYOUT = 7,      /* descriptor version is not BL_LAYOUT_VERSION        */
     BL_ERR_HIP = 8,         /* the HIP runtime refused the launch                 */
-    BL_ERR_COUNT = 9        /* a batch call's count is outside its range          */
+    BL_ERR_COUNT = 9,       /* a batch call's count is outside its range          */
+    BL_ERR_WORKSPACE = 10   /* bl_gemv_batch_static: launch exceeds the static scratch */
 } bl_status;
 
 typedef enum { BL_F32 = 0, BL_BF16 = 1 } bl_dtype;
@@ -58,6 +59,8 @@ typedef enum { BL_F32 = 0, BL_BF16 = 1 } bl_dtype;
 #define BL_MAX_GEMM_BATCH 4
 #define BL_MAX_SPLIT_WGS 2048   /* most workgroups of a work-balanced decode launch     */
 #define BL_WORKSPACE_BYTES (BL_MAX_SPLIT_WGS * 64 * 8)   /* 1 MiB, see bl_gemv_batch   */
+#define BL_STATIC_WS_WGS 1024   /* workgroups the static scratch of bl_gemv_batch_static serves */
+#define BL_STATIC_WS_BYTES (BL_STATIC_WS_WGS * 64 * 8)   /* 512 KiB per GPU              */
 
 /*
  * Host-side description of one packed ternary matrix.  Plain data; copy it,
@@ -208,6 +211,29 @@ typedef struct {
  */
 bl_status bl_gemv_batch(const bl_gemv_item *items, int32_t count, int64_t M, void *workspace_dev,
                         void *stream);
+
+/*
+ * bl_gemv_batch for callers that cannot hand over a workspace and must not
+ * allocate one: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  Same arguments, validation and results as
+ * bl_gemv_batch(items, count, M, workspace, stream) with a workspace; the
+ * workspace is a static device array inside the library, BL_STATIC_WS_BYTES
+ * (512 KiB) on every GPU the library is used on, held until the process ends.
+ * The call allocates and frees nothing and synchronizes nothing.
+ *   - Limit: a work-balanced launch uses 64 words of scratch per workgroup; a
+ *     launch planned with more than BL_STATIC_WS_WGS workgroups (possible only
+ *     through bl_set_tuning("decode_split", n) on a large device) is refused
+ *     with BL_ERR_WORKSPACE and nothing is launched.
+ *   - The first call on a device looks up that device's copy of the array and
+ *     clears it with a small kernel on `stream`; make that first call outside
+ *     graph capture.  Every launch leaves the array all zero again.
+ *   - All calls on one GPU share that GPU's array: calls that may overlap in
+ *     time on one GPU (different streams) race; use bl_gemv_batch with
+ *     separate workspaces for those.  After an aborted launch the array may
+ *     be dirty for the rest of the process.
+ * Errors: those of bl_gemv_batch, and BL_ERR_WORKSPACE.
+ */
+bl_status bl_gemv_batch_static(const bl_gemv_item *items, int32_t count, int64_t M, void *stream);
 
 /* One problem of the fused decode launch. */
 typedef struct {

@@ -13,7 +13,7 @@ LIB_PATH = os.path.join(HERE, "libbitlinear.so")
 
 BL_OK = 0
 BL_ERR_NULL, BL_ERR_SHAPE, BL_ERR_M_RANGE, BL_ERR_BUF_SMALL, BL_ERR_ALIGN = 1, 2, 3, 4, 5
-BL_ERR_DTYPE, BL_ERR_LAYOUT, BL_ERR_HIP, BL_ERR_COUNT = 6, 7, 8, 9
+BL_ERR_DTYPE, BL_ERR_LAYOUT, BL_ERR_HIP, BL_ERR_COUNT, BL_ERR_WORKSPACE = 6, 7, 8, 9, 10
 BL_F32, BL_BF16 = 0, 1
 BL_LAYOUT_VERSION = 1
 BL_TILE_N = 64
@@ -24,6 +24,8 @@ BL_MAX_BATCH = 8
 BL_MAX_GEMM_BATCH = 4
 BL_MAX_SPLIT_WGS = 2048
 BL_WORKSPACE_BYTES = BL_MAX_SPLIT_WGS * 64 * 8
+BL_STATIC_WS_WGS = 1024
+BL_STATIC_WS_BYTES = BL_STATIC_WS_WGS * 64 * 8
 BL_MAX_GEMM_M = 4194304
 BL_TL2_TILE_K = 72
 BL_TL2_LAYOUT_VERSION = 2
@@ -31,7 +33,7 @@ BL_TL2_LAYOUT_VERSION = 2
 # every symbol include/bitlinear.h and include/bitlinear_decoder.h declare
 DECLARED_SYMBOLS = (
     "bl_padded_k", "bl_padded_n", "bl_packed_desc_init", "bl_pack_ternary", "bl_unpack_ternary",
-    "bl_quant_act", "bl_quant_act_batch", "bl_gemv", "bl_gemv_batch", "bl_decode_batch", "bl_gemm", "bl_gemm_batch", "bl_set_tuning", "bl_get_stat", "bl_status_str", "bl_last_hip_error", "bl_version",
+    "bl_quant_act", "bl_quant_act_batch", "bl_gemv", "bl_gemv_batch", "bl_gemv_batch_static", "bl_decode_batch", "bl_gemm", "bl_gemm_batch", "bl_set_tuning", "bl_get_stat", "bl_status_str", "bl_last_hip_error", "bl_version",
     "bl_tl2_padded_k", "bl_tl2_desc_init", "bl_tl2_pack", "bl_tl2_unpack", "bl_tl2_gemv", "bl_tl2_gemv_batch",
     "bl_norm_quant", "bl_rope_table", "bl_attn_scratch_bytes", "bl_attn_decode", "bl_pos_advance", "bl_decode_norm_batch", "bl_attn_prefill", "bl_attn_prefill_scratch_bytes",
 )
@@ -147,6 +149,7 @@ def lib():
     l.bl_quant_act_batch.argtypes = [ctypes.POINTER(QuantItem), i32, vp]
     l.bl_gemv.argtypes = [vp, dp, vp, vp, vp, i64, vp, vp, vp]
     l.bl_gemv_batch.argtypes = [ctypes.POINTER(GemvItem), i32, i64, vp, vp]
+    l.bl_gemv_batch_static.argtypes = [ctypes.POINTER(GemvItem), i32, i64, vp]
     l.bl_gemm_batch.argtypes = [ctypes.POINTER(GemvItem), i32, i64, vp]
     l.bl_decode_batch.argtypes = [ctypes.POINTER(DecodeItem), i32, i64, vp, vp]
     l.bl_gemm.argtypes = [vp, dp, vp, vp, vp, i64, vp, vp, vp]
@@ -177,7 +180,7 @@ def lib():
     for name in ("bl_packed_desc_init", "bl_pack_ternary", "bl_unpack_ternary", "bl_quant_act", "bl_quant_act_batch", "bl_gemv",
                  "bl_gemv_batch", "bl_decode_batch", "bl_gemm", "bl_set_tuning", "bl_tl2_desc_init", "bl_tl2_pack",
                  "bl_tl2_unpack", "bl_tl2_gemv", "bl_tl2_gemv_batch", "bl_norm_quant", "bl_rope_table", "bl_attn_decode",
-                 "bl_pos_advance", "bl_decode_norm_batch", "bl_attn_prefill", "bl_gemm_batch"):
+                 "bl_pos_advance", "bl_decode_norm_batch", "bl_attn_prefill", "bl_gemm_batch", "bl_gemv_batch_static"):
         getattr(l, name).restype = ctypes.c_int
     _lib = l
     return l
@@ -262,6 +265,13 @@ def bl_gemv_batch(items, M: int, workspace_dev: int = 0, stream: int = 0):
     if not isinstance(items, ctypes.Array):
         items = make_gemv_items(items)
     _check(lib().bl_gemv_batch(items, len(items), M, workspace_dev or None, stream or None), "bl_gemv_batch")
+
+
+def bl_gemv_batch_static(items, M: int, stream: int = 0):
+    """bl_gemv_batch with the workspace in the library's static device array (nothing allocated, nothing passed)."""
+    if not isinstance(items, ctypes.Array):
+        items = make_gemv_items(items)
+    _check(lib().bl_gemv_batch_static(items, len(items), M, stream or None), "bl_gemv_batch_static")
 
 
 def bl_gemm_batch(items, M: int, stream: int = 0):

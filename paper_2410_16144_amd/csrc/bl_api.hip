@@ -256,14 +256,12 @@ static bl::DecodeProblem make_decode_problem(const void* packed, const bl_packed
     return p;
 }
 
-bl_status bl_gemv_batch(const bl_gemv_item* items, int32_t count, int64_t M, void* workspace_dev, void* stream) {
+// Validation and problem set-up shared by bl_gemv_batch and bl_gemv_batch_static (no HIP call).
+static bl_status fill_gemv_batch(const bl_gemv_item* items, int32_t count, int64_t M, bl::DecodeBatch& b) {
     if (!items) return BL_ERR_NULL;
     if (count < 1 || count > BL_MAX_BATCH) return BL_ERR_COUNT;
     if (M < 1 || M > BL_MAX_GEMV_M) return BL_ERR_M_RANGE;
-    if (workspace_dev && !aligned(workspace_dev, 256)) return BL_ERR_ALIGN;
-    bl::DecodeBatch b;
     memset(&b, 0, sizeof b);
-    b.ws = static_cast<unsigned long long*>(workspace_dev);
     for (int i = 0; i < count; ++i) {
         const bl_gemv_item& it = items[i];
         bl_status s = check_product_args(it.packed_dev, it.desc, it.q_dev, it.a_scale_dev, it.q_sum_dev, M,
@@ -275,7 +273,75 @@ bl_status bl_gemv_batch(const bl_gemv_item* items, int32_t count, int64_t M, voi
         b.p[i].q_sum = it.q_sum_dev;
     }
     b.count = count;
+    return BL_OK;
+}
+
+bl_status bl_gemv_batch(const bl_gemv_item* items, int32_t count, int64_t M, void* workspace_dev, void* stream) {
+    bl::DecodeBatch b;
+    const bl_status st = fill_gemv_batch(items, count, M, b);
+    if (st != BL_OK) return st;
+    if (workspace_dev && !aligned(workspace_dev, 256)) return BL_ERR_ALIGN;
+    b.ws = static_cast<unsigned long long*>(workspace_dev);
     drop_stale_hip_error();
+    return hip_status(bl::launch_decode(b, (int)M, false, static_cast<hipStream_t>(stream)));
+}
+
+}  // extern "C"
+
+// ---- bl_gemv_batch_static: the workspace of the work-balanced launch in a static device array -----------------
+namespace {
+
+// Each GPU the library runs on holds its own copy of this array, at its own address, until the process ends.  In
+// host code the NAME is only a stand-in for hipGetSymbolAddress: kernels, fills and copies take the per-device
+// pointer looked up below, never the name.
+__device__ __align__(256) unsigned long long scratch[BL_STATIC_WS_WGS * BL_TILE_N];
+
+constexpr int kMaxScratchDevices = 64;
+unsigned long long* g_scratch_ptr[kMaxScratchDevices];   // per device ordinal; null until that device's first call
+
+__global__ void scratch_clear_kernel(unsigned long long* ws, int words) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < words) ws[i] = 0ull;
+}
+
+// The current device's copy of `scratch`; on a device's first call its address is looked up and the array is
+// cleared by a small kernel on `s` (a fill kernel, not a memset node: the caller's stream may be under capture).
+hipError_t scratch_for_current_device(hipStream_t s, unsigned long long** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxScratchDevices) return hipErrorInvalidDevice;
+    unsigned long long* ptr = __atomic_load_n(&g_scratch_ptr[dev], __ATOMIC_ACQUIRE);
+    if (!ptr) {
+        e = hipGetSymbolAddress(reinterpret_cast<void**>(&ptr), HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!ptr) return hipErrorInvalidSymbol;
+        constexpr int words = BL_STATIC_WS_WGS * BL_TILE_N;
+        scratch_clear_kernel<<<dim3((words + 255) / 256), dim3(256), 0, s>>>(ptr, words);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        __atomic_store_n(&g_scratch_ptr[dev], ptr, __ATOMIC_RELEASE);
+    }
+    *out = ptr;
+    return hipSuccess;
+}
+
+}  // namespace
+
+extern "C" {
+
+bl_status bl_gemv_batch_static(const bl_gemv_item* items, int32_t count, int64_t M, void* stream) {
+    bl::DecodeBatch b;
+    const bl_status st = fill_gemv_batch(items, count, M, b);
+    if (st != BL_OK) return st;
+    drop_stale_hip_error();
+    unsigned long long* ws = nullptr;
+    const hipError_t e = scratch_for_current_device(static_cast<hipStream_t>(stream), &ws);
+    if (e != hipSuccess) return hip_status(e);
+    b.ws = ws;
+    // the balanced form would use 64 words per workgroup: more workgroups than the array holds is an error here,
+    // not a silent change of kernel
+    if (M == 1 && bl::decode_split_grid(b, false) > BL_STATIC_WS_WGS) return BL_ERR_WORKSPACE;
     return hip_status(bl::launch_decode(b, (int)M, false, static_cast<hipStream_t>(stream)));
 }
 
@@ -498,6 +564,7 @@ const char* bl_status_str(bl_status s) {
         case BL_ERR_LAYOUT: return "unknown packed layout version";
         case BL_ERR_HIP: return "HIP launch failed";
         case BL_ERR_COUNT: return "batch count outside 1..8";
+        case BL_ERR_WORKSPACE: return "the launch needs more scratch than the library's static array holds";
     }
     return "unknown status";
 }

@@ -236,18 +236,18 @@ int compute_unit_count() {
 void set_decode_split(int v) { g_split = v; }
 int64_t split_launches() { return g_split_launches; }
 
-// Plans the balanced launch.  Returns false when the balanced form does not apply (the caller then
-// uses the row-block kernels): tiny launches, shapes whose chunks would touch too many row blocks.
-bool plan_decode_split(DecodeBatch& b, bool fused, int& tiles_per_wave) {
-    if (g_split < 0 || !b.ws) return false;
-    if (b.p[0].glu_gamma) return false;   // the gated epilogue pairs lanes of one wave: whole row blocks only
+// The workgroups a balanced launch of this batch would have (each uses 64 workspace words), or 0 when the balanced
+// form is not chosen by launch size (the caller then uses the row-block kernels).  Shapes only: no side effects.
+int decode_split_grid(const DecodeBatch& b, bool fused) {
+    if (g_split < 0 || !b.ws) return 0;
+    if (b.p[0].glu_gamma) return 0;   // the gated epilogue pairs lanes of one wave: whole row blocks only
     const int cus = compute_unit_count();
-    if (cus <= 0) return false;
-    int64_t T[BL_MAX_BATCH], total = 0;
+    if (cus <= 0) return 0;
+    int64_t total = 0;
     for (int i = 0; i < b.count; ++i) {
-        T[i] = (int64_t)b.p[i].row_blocks * b.p[i].KC;
-        if (T[i] > (1 << 30)) return false;
-        total += T[i];
+        const int64_t t = (int64_t)b.p[i].row_blocks * b.p[i].KC;
+        if (t > (1 << 30)) return 0;
+        total += t;
     }
     // Measured on MI355X (decoder layers of 0.7B to 100B shapes): equal shares pay off between about 100 and 400
     // tiles per compute unit; below, the launch is latency-bound either way, above, many small workgroups
@@ -259,20 +259,33 @@ bool plan_decode_split(DecodeBatch& b, bool fused, int& tiles_per_wave) {
         // unit the balanced form stays the faster one on the largest layers too (100B-shape layer: 81 against 85 us)
         mult = 2;
     } else if (mult == 0) {
-        if (per_cu > 400) return false;
+        if (per_cu > 400) return 0;
         if (per_cu < (fused ? 100 : 32)) {
             // small launches: worth it only where whole row blocks cannot even occupy every compute unit
             int64_t row_blocks = 0;
             for (int i = 0; i < b.count; ++i) row_blocks += b.p[i].row_blocks;
-            if (row_blocks >= cus || per_cu < 8) return false;
+            if (row_blocks >= cus || per_cu < 8) return 0;
             mult = 1;
         } else {
             mult = (!fused && per_cu <= 250) ? 2 : 1;
         }
     }
-    const int grid = cus * mult;
-    if (grid > BL_MAX_SPLIT_WGS || b.count > grid) return false;
-    if (total < (int64_t)grid * 8) return false;   // under 8 tiles per workgroup: nothing to balance
+    const int64_t grid = (int64_t)cus * mult;
+    if (grid > BL_MAX_SPLIT_WGS || b.count > grid) return 0;
+    if (total < grid * 8) return 0;   // under 8 tiles per workgroup: nothing to balance
+    return (int)grid;
+}
+
+// Plans the balanced launch.  Returns false when the balanced form does not apply (the caller then
+// uses the row-block kernels): tiny launches, shapes whose chunks would touch too many row blocks.
+bool plan_decode_split(DecodeBatch& b, bool fused, int& tiles_per_wave) {
+    const int grid = decode_split_grid(b, fused);
+    if (grid <= 0) return false;
+    int64_t T[BL_MAX_BATCH], total = 0;
+    for (int i = 0; i < b.count; ++i) {
+        T[i] = (int64_t)b.p[i].row_blocks * b.p[i].KC;
+        total += T[i];
+    }
     int g[BL_MAX_BATCH], used = 0;
     for (int i = 0; i < b.count; ++i) {
         g[i] = (int)(T[i] * grid / total);

@@ -128,6 +128,7 @@ hipError_t launch_quant(const QuantBatch& b, hipStream_t s);
 size_t decode_lds_bytes(int M, int64_t max_Kp, bool fused);
 hipError_t launch_decode(const DecodeBatch& b, int M, bool fused, hipStream_t s);
 int compute_unit_count();   // of the current device; 0 if unknown
+int decode_split_grid(const DecodeBatch& b, bool fused);   // workgroups of the balanced form for this batch; 0: not chosen
 bool plan_decode_split(DecodeBatch& b, bool fused, int& tiles_per_wave);   // false: the balanced form does not apply
 hipError_t launch_decode_split(const DecodeBatch& b, int tiles_per_wave, bool fused, hipStream_t s);
 hipError_t launch_gemm(const GemmProblem& p, int64_t M, hipStream_t s);
