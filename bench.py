@@ -1,18 +1,19 @@
 #!/usr/bin/env python3
 """Benchmark of the BitLinear hot path on one MI355X.
 
-Default workload: the 3B-shape decoder layer at M=1 (hidden 3200, FFN 8640; ternary weights with
-P(0)=0.4, per-matrix scale; bf16 activations ~N(0,1) with 1% outliers x20).  One "step" is one pass
-of the decode hot path over one layer: the per-token absmax int8 quantization of the layer's inputs
-and its 7 ternary x int8 GEMVs, issued as ONE fused launch (bl_decode_batch).  Successive steps walk
-through `--layers` distinct layers (>= 1 GiB of packed weights in total) so that every step streams
-its weights from HBM, not from the 256 MB Infinity Cache.  Inputs are resident in HBM before the
-timed region starts; the K timed steps are replayed from one HIP graph so that host launch overhead
-is outside the measurement.
+Default workload (the largest single-GPU configuration): the 100B-shape model's token decode at M=1 -- 80 layers
+with hidden 12288 and FFN 33792, 7 ternary x int8 GEMVs per layer, all 36.99 GB of 2-bit packed weights resident in
+HBM.  One "step" is one token: 80 launches of the fused kernel (bl_decode_batch: the per-token absmax int8
+quantization of a layer's four inputs and its 7 GEMVs in one launch), captured as ONE HIP graph and replayed; every
+layer has its own weights, so every step streams all of them from HBM.  Inputs are resident in HBM before the timed
+region starts.
 
-Prints ONE JSON line (metric = packed-weight GB/s of the decode GEMVs) with the dominant kernel's
-roofline and the CPU oracle timed beside it.  Other launch variants, the 7B- and 100B-shape decode
-layers and the prefill GEMM (TOPS against the int8 MFMA peak) are nested under "extra".
+Prints ONE JSON line: metric = packed-weight GB/s of the decode GEMVs, with the dominant kernel's roofline and the
+CPU oracle timed beside it (one full layer on the host cores, all cores and one thread; the whole token is that
+times 80, stated as extrapolated).  The other benchmark configurations (1536^2 matrix, 3B-shape layer, 7B-shape
+layer at M = 1, 4, 8, the prefill products, the paper's own 100B shape) are nested under "extra", each with its own
+roofline and cpu_baseline; so are the measured ceilings (a register-only MFMA loop, a read-only streaming kernel)
+and the whole-model token loop in the paper's unit.
 """
 import argparse
 import json
@@ -31,17 +32,16 @@ INT8_PEAK_TOPS = 5000.0     # MI355X dense int8 MFMA, published
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=2000)
-    ap.add_argument("--warmup", type=int, default=200)
-    ap.add_argument("--layers", type=int, default=40, help="distinct layers to rotate through")
+    ap.add_argument("--steps", type=int, default=100, help="timed steps (tokens of the 100B-shape model)")
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--layers", type=int, default=40, help="distinct 3B-shape layers to rotate through (extra.config2)")
+    ap.add_argument("--model-layers", type=int, default=80, help="layers of the headline model (80 = the configuration)")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-extra", action="store_true", help="skip the extra sections")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
-    ap.add_argument("--cpu-seconds", type=float, default=10.0)
-    ap.add_argument("--full-100b", action="store_true",
-                    help="extra: build all 80 layers of the 100B-shape model (37 GB packed) and time a whole token")
+    ap.add_argument("--cpu-seconds", type=float, default=8.0, help="CPU work of the headline's oracle baseline")
     ap.add_argument("--models", default="", help="with --only tokens: comma-separated Appendix-A model names (default: all 12)")
-    ap.add_argument("--only", default="", help="run only one extra section (copy|prefill|decode7b|decode100b|paper100b|config1|appendixa|tokens|tokens8k|prompt|prompt2k|tl2) and print it")
+    ap.add_argument("--only", default="", help="run only one extra section (copy|ceilings|prefill|config1|config2|config3|decode100b|paper100b|appendixa|tokens|tokens8k|prompt|prompt2k|tl2) and print it")
     return ap.parse_args()
 
 
@@ -116,8 +116,21 @@ def check_layer_against_oracle(torch, np, oracle, layer, host):
             assert np.all(np.abs(got - ref) <= 1e-6 * np.abs(ref)), "out mismatch " + p.name
 
 
-def cpu_baseline(np, oracle, host, projs, packed_bytes, seconds):
-    """The oracle as it stands, timed on the host cores, on repeated passes over ONE layer."""
+def _passes(fn, seconds):
+    """Repeat fn() for about `seconds` (at least once); returns (count, elapsed seconds)."""
+    n, t0 = 0, time.perf_counter()
+    while True:
+        fn()
+        n += 1
+        dt = time.perf_counter() - t0
+        if dt >= seconds:
+            return n, dt
+
+
+def cpu_layer_baseline(oracle, host, projs, packed_bytes, seconds, what, model_layers=None):
+    """The oracle as it stands, timed on the host cores on repeated passes over ONE layer (its 4 quantizations, 7
+    integer products and 7 dequantizations, whatever M the inputs have): all cores first, then one thread.  The rate
+    is quoted on the packed 2-bit byte count, like the GPU value (the oracle itself reads unpacked int8 weights)."""
     from paper_2410_16144_amd.decode_layer import INPUT_OF
 
     def one_pass():
@@ -127,19 +140,74 @@ def cpu_baseline(np, oracle, host, projs, packed_bytes, seconds):
             acc = oracle.matmul_i32(q, host["w"][i])
             oracle.dequant(acc, host["w_scale"][i], a)
 
-    one_pass()
-    n, t0 = 0, time.perf_counter()
-    while True:
-        one_pass()
-        n += 1
-        dt = time.perf_counter() - t0
-        if dt >= seconds:
-            break
-    return {"value": round(packed_bytes * n / dt / 1e9, 3), "unit": "GB/s", "cores": oracle.num_threads(),
-            "kind": "oracle", "ms_per_step": round(dt / n * 1e3, 3),
-            "sample": "%d full passes over one 3B-shape layer (4 quantizations + 7 GEMVs, M=1), %.1f s of CPU "
-                      "work; the oracle reads unpacked int8 weights, the rate is quoted on the same packed "
-                      "2-bit byte count as the GPU value" % (n, dt)}
+    cores = oracle.num_threads()
+    one_pass()                                   # pages the weights in
+    n, dt = _passes(one_pass, seconds)
+    res = {"value": round(packed_bytes * n / dt / 1e9, 3), "unit": "GB/s", "cores": cores, "kind": "oracle",
+           "ms_per_layer": round(dt / n * 1e3, 3),
+           "sample": "%d full passes over one %s (4 quantizations + 7 products), %.1f s of CPU work on %d threads; the "
+                     "oracle reads unpacked int8 weights, the rate is quoted on the same packed 2-bit byte count as "
+                     "the GPU value" % (n, what, dt, cores)}
+    oracle.set_num_threads(1)
+    try:
+        n1, dt1 = _passes(one_pass, max(1.0, seconds / 4))
+    finally:
+        oracle.set_num_threads(cores)
+    res["one_thread"] = {"value": round(packed_bytes * n1 / dt1 / 1e9, 3), "unit": "GB/s", "cores": 1,
+                         "ms_per_layer": round(dt1 / n1 * 1e3, 3), "passes": n1}
+    if model_layers:
+        res["ms_per_step"] = round(dt / n * 1e3 * model_layers, 1)
+        res["one_thread"]["ms_per_step"] = round(dt1 / n1 * 1e3 * model_layers, 1)
+        res["sample"] += "; ONE layer timed, the %d-layer token is that x %d, extrapolated" % (model_layers, model_layers)
+    else:
+        res["ms_per_step"] = res["ms_per_layer"]
+    return res
+
+
+def cpu_prefill_baseline(np, oracle, M, K, N):
+    """The oracle on one prefill product of the benchmark's shape (host-drawn operands of the same distributions):
+    quantization + integer product + dequantization.  All cores on the full M (once); one thread on a sample of 32
+    token rows, scaled to M (the oracle's work is linear in the rows)."""
+    from paper_2410_16144_amd import synth
+    rng = synth.rng_for(synth.seed_for(4, 1, 0 if K == 4096 else 1))
+    w = synth.ternary_weights(rng, N, K)
+    bits = synth.to_bf16_bits(synth.activations(rng, M, K))
+
+    def product(b):
+        q, a, _ = oracle.quant_act(b)
+        oracle.dequant(oracle.matmul_i32(q, w), np.float32(0.02), a)
+
+    cores = oracle.num_threads()
+    product(bits[:16])
+    t0 = time.perf_counter()
+    product(bits)
+    dt = time.perf_counter() - t0
+    ops = 2.0 * M * K * N
+    rows1 = 32
+    oracle.set_num_threads(1)
+    try:
+        t0 = time.perf_counter()
+        product(bits[:rows1])
+        dt1 = (time.perf_counter() - t0) * M / rows1
+    finally:
+        oracle.set_num_threads(cores)
+    return {"value": round(ops / dt / 1e12, 4), "unit": "TOP/s", "cores": cores, "kind": "oracle", "ms_per_step": round(dt * 1e3, 1),
+            "sample": "the whole product once (M=%d K=%d N=%d: quantization, integer product, dequantization), %.1f s on "
+                      "%d threads" % (M, K, N, dt, cores),
+            "one_thread": {"value": round(ops / dt1 / 1e12, 4), "unit": "TOP/s", "cores": 1, "ms_per_step": round(dt1 * 1e3, 1),
+                           "sample": "%d of the %d token rows timed, scaled to all rows" % (rows1, M)}}
+
+
+def hbm_roofline(kernel, bytes_per_launch, launch_us, traffic=None):
+    gbs = bytes_per_launch / launch_us / 1e3
+    return {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": traffic, "kernel": kernel,
+            "avg_launch_us": round(launch_us, 3), "bytes_per_launch": int(bytes_per_launch)}
+
+
+def last_kernel():
+    from paper_2410_16144_amd import binding
+    return binding.bl_last_kernel()
 
 
 def extra_copy(torch):
@@ -172,6 +240,7 @@ def extra_prefill(torch, M, K, N, use_graph=True, iters=100):
     usq = msq * 1e3 / iters
     for _ in range(3):
         ops.gemm(pw, qa, out)
+    kernel = last_kernel()
     ms, _, mode = run_steps(torch, [lambda: ops.gemm(pw, qa, out)], iters, use_graph)
     us = ms * 1e3 / iters
     tops = 2.0 * M * K * N / us / 1e6
@@ -199,29 +268,51 @@ def extra_prefill(torch, M, K, N, use_graph=True, iters=100):
     return {"workload": "prefill M=%d K=%d N=%d" % (M, K, N), "gemm_us": round(us, 2), "quant_act_us": round(usq, 2),
             "launch": mode, "gemm_us_on_all_zero_activations": us_zero, "vendor_library_dense_int8_gemm_us": lib_us,
             "roofline": {"bound": "mfma", "achieved": round(tops / 1e3, 4), "peak": INT8_PEAK_TOPS / 1e3,
-                         "unit": "POP/s", "frac": round(tops / INT8_PEAK_TOPS, 4), "ops_per_launch": 2 * M * K * N},
+                         "unit": "POP/s", "frac": round(tops / INT8_PEAK_TOPS, 4), "traffic": None, "kernel": kernel,
+                         "avg_launch_us": round(us, 2), "ops_per_launch": 2 * M * K * N},
             "tops_including_quant_act": round(2.0 * M * K * N / (us + usq) / 1e6, 1)}
 
 
-def extra_decode_shape(torch, name, hidden, ffn, M, layers, steps, use_graph):
-    """Layer decode on another model shape: fused launch for M=1; for M>1 one bl_quant_act per
-    input followed by one grouped matrix-core GEMV launch (both variants reported)."""
+def extra_decode_shape(torch, name, hidden, ffn, M, layers, steps, use_graph, config=5, p_zero=None, outliers=0.0,
+                       cpu_seconds=0.0, dependency_ordered=False):
+    """Layer decode on one model shape, `layers` distinct layers rotated so that every launch reads HBM.  Variants:
+    the fused launch (quantize + 7 products in one kernel), one grouped quantization launch + one grouped product
+    launch, four quantization launches + one grouped product launch, and the grouped product launch alone.  The
+    `roofline` block is the best variant that INCLUDES the quantization (the hot path is both steps), quoted on its
+    product kernel; cpu_seconds > 0 adds the oracle on the same layer (layer 0 is then drawn on the host)."""
     from paper_2410_16144_amd.decode_layer import make_layer
     dev = torch.device("cuda:0")
-    ls = [make_layer(5, i, hidden, ffn, M, dev, None, 0.0)[0] for i in range(layers)]
+    host = None
+    ls = []
+    for i in range(layers):
+        l, h = make_layer(config, i, hidden, ffn, M, dev, p_zero, outliers, host=(i == 0 and cpu_seconds > 0))
+        ls.append(l)
+        host = h if i == 0 else host
     pb = ls[0].packed_bytes
     res = {"workload": "%s layer decode M=%d (hidden %d, ffn %d), %d distinct layers rotated"
                        % (name, M, hidden, ffn, layers), "packed_bytes_per_layer": pb}
-    for label, attr in (("fused_1_launch", "step_fused"), ("grouped_quant_plus_grouped_gemv", "step_two_launches"),
-                        ("quant_x4_plus_grouped_gemv", "step_single_launch"), ("grouped_gemv_only", None)):
+    variants = [("fused_1_launch", "step_fused"), ("grouped_quant_plus_grouped_gemv", "step_two_launches"),
+                ("quant_x4_plus_grouped_gemv", "step_single_launch"), ("grouped_gemv_only", None)]
+    if dependency_ordered:
+        variants.append(("fused_dependency_ordered_4_launches", "step_fused_dependency_ordered"))
+    best = None
+    for label, attr in variants:
         fns = [getattr(l, attr) if attr else l.group_all.launch for l in ls]
         for f in fns[:2]:
             f()
+        kernel = last_kernel()
         ms, _, mode = run_steps(torch, fns, steps, use_graph)
         us = ms * 1e3 / steps
         res[label] = {"us_per_layer": round(us, 2), "GBps": round(pb / us / 1e3, 1),
-                      "frac_of_hbm_peak": round(pb / us / 1e3 / HBM_PEAK_GBS, 4)}
+                      "frac_of_hbm_peak": round(pb / us / 1e3 / HBM_PEAK_GBS, 4), "product_kernel": kernel}
+        if attr in ("step_fused", "step_two_launches") and (best is None or us < best[1]):
+            best = (label, us, kernel)
     res["launch"] = mode
+    res["roofline"] = hbm_roofline(best[2], pb, best[1])
+    res["roofline"]["sequence"] = best[0] + " (quantization included; avg_launch_us is the whole sequence)"
+    if cpu_seconds > 0:
+        import oracle
+        res["cpu_baseline"] = cpu_layer_baseline(oracle, host, ls[0].projs, pb, cpu_seconds, "%s layer at M=%d" % (name, M))
     return res
 
 
@@ -286,17 +377,22 @@ def extra_tl2(torch, use_graph):
     return {"single_matrices": rows, "layers_one_launch": layers}
 
 
-def extra_config1(torch, use_graph):
-    """The smallest case: one 1536x1536 matrix (0.59 MB packed), fp32 activations, M=1.  Launch-latency
-    bound; reported cold (rotating through 1 GiB of copies) and cache-resident (one copy)."""
+def extra_config1(torch, use_graph, cpu_seconds=1.0):
+    """The smallest case: one 1536x1536 matrix (0.59 MB packed), fp32 activations, M=1, uniform ternary weights with
+    scale 0.02.  Launch-latency bound; reported cold (rotating through 1 GiB of copies) and cache-resident (one copy)."""
+    import numpy as np
     from paper_2410_16144_amd import ops, synth
     dev = torch.device("cuda:0")
     N = K = 1536
     nb = N * K // 4
     copies = (1 << 30) // nb // 8 + 1    # 8 distinct matrices, each stored this many times: over 1 GiB in all
-    base = [ops.pack_ternary(synth.ternary_weights_device(100 + i, N, K, dev), 0.02) for i in range(8)]
+    rng = synth.rng_for(synth.seed_for(1))
+    w0 = synth.ternary_weights(rng, N, K)
+    x0 = synth.activations(rng, 1, K)
+    base = [ops.pack_ternary(torch.from_numpy(w0).to(dev), 0.02)]
+    base += [ops.pack_ternary(synth.ternary_weights_device(100 + i, N, K, dev), 0.02) for i in range(1, 8)]
     pws = [ops.PackedWeight(b.blob.clone(), b.desc) for _ in range(copies) for b in base]
-    x = torch.randn((1, K), device=dev, dtype=torch.float32)
+    x = torch.from_numpy(x0).to(dev)
     qa = ops.quant_act(x)
     out = torch.empty((1, N), dtype=torch.float32, device=dev)
     plain = [ops.GemvGroup([pw], [qa], [out]) for pw in pws]
@@ -304,12 +400,36 @@ def extra_config1(torch, use_graph):
     res = {"workload": "one 1536x1536 matrix, M=1, fp32 activations (%d copies = %.1f GiB rotated when cold)"
                        % (len(pws), len(pws) * nb / 2**30), "packed_bytes": nb}
     steps = 2 * len(pws)
+    kernels = {}
     for label, fns in (("gemv_cold", [g.launch for g in plain]), ("gemv_cache_resident", [plain[0].launch]),
                        ("fused_cold", [g.launch for g in fused]), ("fused_cache_resident", [fused[0].launch])):
         fns[0]()
+        kernels[label] = last_kernel()
         ms, _, _ = run_steps(torch, fns, steps, use_graph)
         us = ms * 1e3 / steps
         res[label] = {"us": round(us, 2), "GBps": round(nb / us / 1e3, 1)}
+    res["roofline"] = hbm_roofline(kernels["fused_cold"], nb, res["fused_cold"]["us"])
+    res["roofline"]["sequence"] = "fused_cold (quantize + product in one launch, weights from HBM)"
+    if cpu_seconds > 0:
+        import oracle
+
+        def one_pass():
+            q, a, _ = oracle.quant_act(x0)
+            oracle.dequant(oracle.matmul_i32(q, w0), np.float32(0.02), a)
+
+        cores = oracle.num_threads()
+        one_pass()
+        n, dt = _passes(one_pass, cpu_seconds)
+        oracle.set_num_threads(1)
+        try:
+            n1, dt1 = _passes(one_pass, cpu_seconds)
+        finally:
+            oracle.set_num_threads(cores)
+        res["cpu_baseline"] = {"value": round(nb * n / dt / 1e9, 3), "unit": "GB/s", "cores": cores, "kind": "oracle",
+                               "ms_per_step": round(dt / n * 1e3, 4),
+                               "sample": "%d full passes (quantization + product + dequantization), %.1f s" % (n, dt),
+                               "one_thread": {"value": round(nb * n1 / dt1 / 1e9, 3), "unit": "GB/s", "cores": 1,
+                                              "ms_per_step": round(dt1 / n1 * 1e3, 4)}}
     return res
 
 
@@ -347,28 +467,34 @@ class PowerSampler:
         self._thread.join()
 
 
-def energy_per_token(torch, fns, tokens_per_replay, seconds=3.0):
+def energy_per_token(torch, fns, tokens_per_replay, seconds=3.0, graph=True):
     """Section 3's energy metric on this board: mean socket power while whole tokens are decoded back to back
-    for `seconds`, times the time per token.  Returns None where the power sensor is not readable."""
+    for `seconds`, times the time per token.  Returns None where the power sensor is not readable.  graph=False:
+    `fns` are called as they are (e.g. one function that replays a captured token)."""
     idle = PowerSampler().read()
     if idle is None:
         return None
-    g = torch.cuda.CUDAGraph()
-    side = torch.cuda.Stream()
-    side.wait_stream(torch.cuda.current_stream())
-    with torch.cuda.stream(side):
-        with torch.cuda.graph(g, stream=side):
-            for f in fns:
-                f()
-    torch.cuda.synchronize()
-    g.replay()
+    g = None
+    if graph:
+        g = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(g, stream=side):
+                for f in fns:
+                    f()
+        torch.cuda.synchronize()
+        fns = [g.replay]
+    for f in fns:
+        f()
     torch.cuda.synchronize()
     with PowerSampler() as ps:
         t0 = time.perf_counter()
         n = 0
         while time.perf_counter() - t0 < seconds:
             for _ in range(20):
-                g.replay()
+                for f in fns:
+                    f()
             torch.cuda.synchronize()
             n += 20
         dt = time.perf_counter() - t0
@@ -520,25 +646,149 @@ def decoder_cpu_baseline(name="700M", seconds=5.0):
                       "layers" % (n, name, max_pos - 1, dt, n_layers)}
 
 
-def extra_full_100b(torch, use_graph):
-    """All 80 layers of the 100B-shape model resident (36.99 GB packed); one token = 80 fused launches."""
+def extra_ceilings(torch, use_graph):
+    """The two measured denominators beside the published peaks: a register-only loop of v_mfma_i32_32x32x32_i8 (what the
+    matrix cores deliver with nothing in the way, with and without the prefill kernel's in-register code expansion, at
+    one and two waves per SIMD), and a read-only 128-bit streaming kernel over buffers of the decode launches' sizes,
+    each launch on a buffer that was not read recently (HBM, not the memory-side cache).  The probes are a library of
+    their own (tests/ceilings), not part of libbitlinear.so."""
+    import ctypes
+    path = os.path.join(ROOT, "tests", "ceilings", "libceilings.so")
+    if not os.path.exists(path):
+        raise RuntimeError("tests/ceilings/libceilings.so is not built: run __graft_entry__.build()")
+    lib = ctypes.CDLL(path)
+    vp = ctypes.c_void_p
+    lib.ceil_mfma_loop.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, vp]
+    lib.ceil_stream_read.argtypes = [vp, ctypes.c_int64, vp, ctypes.c_int, ctypes.c_int, ctypes.c_int, vp]
+    dev = torch.device("cuda:0")
+    cus = torch.cuda.get_device_properties(dev).multi_processor_count
+    sink = torch.zeros(1024, dtype=torch.int32, device=dev)
+
+    def stream():
+        return int(torch.cuda.current_stream().cuda_stream)
+
+    def check(rc):
+        if rc != 0:
+            raise RuntimeError("ceilings probe launch failed: hipError %d" % rc)
+
+    res = {"mfma_loop": [], "stream_read": []}
+    ops_iter = lib.ceil_mfma_ops_per_wave_iter()
+    for expand in (0, 1):
+        for waves_per_simd in (1, 2):
+            blocks, iters = cus * waves_per_simd, 4000
+            fn = lambda: check(lib.ceil_mfma_loop(expand, blocks, iters, sink.data_ptr(), stream()))
+            fn()
+            ms, _, _ = run_steps(torch, [fn], 20, use_graph)       # ~0.1 s sustained before the timed replay
+            pops = ops_iter * 4.0 * blocks * iters * 20 / (ms * 1e-3) / 1e15
+            res["mfma_loop"].append({"operands": "expanded from 2-bit codes in registers (7 VALU ops per operand)" if expand
+                                     else "loop constants", "waves_per_simd": waves_per_simd, "POPs": round(pops, 3),
+                                     "frac_of_published_peak": round(pops * 1e3 / INT8_PEAK_TOPS, 4)})
+    for label, nbytes, copies in (("3B-shape layer", 30976000, 40), ("7B-shape layer", 50593792, 24),
+                                  ("100B-shape layer", 462422016, 6), ("1 GiB", 1 << 30, 3)):
+        nbytes = nbytes // 1024 * 1024
+        bufs = [torch.empty(nbytes, dtype=torch.uint8, device=dev).fill_(i + 1) for i in range(copies)]
+        best = None
+        for wgs_per_cu, threads, unroll in ((1, 1024, 8), (2, 1024, 8), (2, 1024, 4), (4, 512, 8), (2, 512, 16), (8, 256, 8)):
+            fns = [(lambda b=b: check(lib.ceil_stream_read(b.data_ptr(), nbytes, sink.data_ptr(), cus * wgs_per_cu, threads,
+                                                           unroll, stream()))) for b in bufs]
+            fns[0]()
+            steps = max(2 * copies, int(2e9 // nbytes))
+            ms, _, _ = run_steps(torch, fns, steps, use_graph)
+            us = ms * 1e3 / steps
+            if best is None or us < best[0]:
+                best = (us, wgs_per_cu, threads, unroll)
+        us, wgs_per_cu, threads, unroll = best
+        res["stream_read"].append({"buffer": label, "bytes": nbytes, "copies_rotated": copies, "us": round(us, 2),
+                                   "GBps": round(nbytes / us / 1e3, 1), "frac_of_published_peak": round(nbytes / us / 1e3 / HBM_PEAK_GBS, 4),
+                                   "launch": "%d workgroups per CU x %d threads, %d loads in flight" % (wgs_per_cu, threads, unroll)})
+        del bufs
+        torch.cuda.empty_cache()
+    return res
+
+
+def headline_100b(torch, np, args, use_graph):
+    """The timed region of the default run: the 100B-shape model, all layers resident, one token per step."""
+    import oracle
     from paper_2410_16144_amd.decode_layer import make_layer
     dev = torch.device("cuda:0")
-    ls = []
-    for i in range(80):
-        ls.append(make_layer(5, i, 12288, 33792, 1, dev, None, 0.0)[0])
-        torch.cuda.synchronize()
-    total = sum(l.packed_bytes for l in ls)
-    out = {"workload": "100B-shape token decode, M=1: 80 layers x 7 GEMVs, all weights resident", "packed_bytes": total}
-    for label, attr in (("fused", "step_fused"), ("quant_plus_grouped_gemv", "step_single_launch")):
-        fns = [getattr(l, attr) for l in ls]
+    hidden, ffn, n_layers = 12288, 33792, args.model_layers
+    t_build = time.perf_counter()
+    # layer 0 is drawn on the host so that the oracle sees the same bits; the rest on the device
+    layer0, host = make_layer(5, 0, hidden, ffn, 1, dev, None, 0.0, host=True)
+    layers = [layer0]
+    for i in range(1, n_layers):
+        layers.append(make_layer(5, i, hidden, ffn, 1, dev, None, 0.0)[0])
+        if i % 10 == 9:
+            torch.cuda.synchronize()
+            print("bench: %d of %d layers packed (%.0f s)" % (i + 1, n_layers, time.perf_counter() - t_build), file=sys.stderr, flush=True)
+    torch.cuda.synchronize()
+    layer_bytes = layer0.packed_bytes
+    total = layer_bytes * n_layers
+    check_layer_against_oracle(torch, np, oracle, layer0, host)
+    print("bench: layer 0 agrees with the oracle (bit-exact q / acc, out within 1e-6)", file=sys.stderr, flush=True)
+
+    fns = [l.step_fused for l in layers]
+
+    def token():
         for f in fns:
             f()
-        ms, _, _ = run_steps(torch, fns, 80 * 3, use_graph)
-        out[label] = {"ms_per_token": round(ms / 3, 4), "GBps": round(total / (ms / 3) / 1e6, 1),
-                      "frac_of_hbm_peak": round(total / (ms / 3) / 1e6 / HBM_PEAK_GBS, 4)}
-    out["energy"] = energy_per_token(torch, [l.step_fused for l in ls], 1)
-    return out
+
+    for _ in range(args.warmup):
+        token()
+    kernel = last_kernel()
+    torch.cuda.synchronize()
+    if use_graph:
+        g = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(g, stream=side):
+                token()
+        torch.cuda.synchronize()
+        step, mode = g.replay, "hip-graph (one graph of %d launches per token)" % n_layers
+        t0 = time.perf_counter()
+        while time.perf_counter() - t0 < 0.05:      # untimed replays: one-time upload costs, clocks
+            g.replay()
+            torch.cuda.synchronize()
+    else:
+        step, mode = token, "eager"
+
+    def run(count):
+        for _ in range(count):
+            step()
+
+    ms, wall_ms = timed(torch, lambda: run(args.steps))
+    ms_per_step = ms / args.steps
+    more = sorted([ms_per_step] + [timed(torch, lambda: run(min(args.steps, 20)))[0] / min(args.steps, 20) for _ in range(4)])
+    spread = {"replays": len(more), "ms_per_step_min": round(more[0], 5), "ms_per_step_median": round(more[len(more) // 2], 5),
+              "ms_per_step_max": round(more[-1], 5)}
+    value = total / (ms_per_step * 1e-3) / 1e9
+    launch_us = ms_per_step * 1e3 / n_layers      # the step is n_layers launches of ONE kernel, back to back
+    result = {
+        "metric": "ternary x int8 GEMV packed-weight GB/s", "value": round(value, 1), "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+        "config": {"workload": "100B-shape full-model token decode, M=1: %d layers (hidden 12288, ffn 33792), per layer the "
+                               "absmax int8 quantization of its 4 inputs + 7 ternary GEMVs in one fused launch; "
+                               "%.2f GB of 2-bit packed weights resident, every layer its own; one step = one token"
+                               % (n_layers, total / 1e9),
+                   "launch": mode, "packed_bytes_per_step": total, "tokens_per_s_gemv_only": round(1e3 / ms_per_step, 1),
+                   "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4), "wall_ms_timed_region": round(wall_ms, 3),
+                   "spread_over_replays": spread, "build_s": round(time.perf_counter() - t_build, 1)},
+        "roofline": hbm_roofline(kernel, layer_bytes, launch_us, load_traffic("decode_kernel_100b_layer_m1_fused")),
+    }
+    result["roofline"]["launches_per_step"] = n_layers
+    if not args.no_cpu:
+        result["cpu_baseline"] = cpu_layer_baseline(oracle, host, layer0.projs, layer_bytes, args.cpu_seconds,
+                                                    "100B-shape layer at M=1", model_layers=n_layers)
+    energy = None
+    if use_graph and not args.no_extra:
+        energy = energy_per_token(torch, [g.replay], 1, graph=False)
+    del layers, fns, layer0, host
+    if use_graph:
+        del g
+    torch.cuda.empty_cache()
+    return result, energy
 
 
 def load_traffic(kernel_key):
@@ -550,6 +800,43 @@ def load_traffic(kernel_key):
         return json.load(f).get(kernel_key)
 
 
+def sections(torch, np, args, use_graph):
+    """The extra sections by name (each is also `--only <name>`)."""
+    models = args.models.split(",") if args.models else None
+    cpu = 0.0 if args.no_cpu else 2.0
+
+    def prefill():
+        rows = []
+        for m in (512, 2048):
+            for (k, n) in ((4096, 11008), (11008, 4096)):
+                row = extra_prefill(torch, m, k, n, use_graph)
+                if not args.no_cpu:
+                    import oracle
+                    row["cpu_baseline"] = cpu_prefill_baseline(np, oracle, m, k, n)
+                rows.append(row)
+        return rows
+
+    return {
+        "copy": lambda: extra_copy(torch),
+        "ceilings": lambda: extra_ceilings(torch, use_graph),
+        "config1": lambda: extra_config1(torch, use_graph, cpu_seconds=cpu / 2),
+        "config2": lambda: extra_decode_shape(torch, "3B-shape", 3200, 8640, 1, args.layers, 2000, use_graph, config=2, p_zero=0.4,
+                                              outliers=0.01, cpu_seconds=cpu, dependency_ordered=True),
+        "config3": lambda: [extra_decode_shape(torch, "7B-shape", 4096, 11008, m, 24, 480, use_graph, config=3, cpu_seconds=cpu)
+                            for m in (1, 4, 8)],
+        "prefill": prefill,
+        "decode100b": lambda: extra_decode_shape(torch, "100B-shape", 12288, 33792, 1, 6, 120, use_graph),
+        "paper100b": lambda: extra_decode_shape(torch, "Appendix-A 100B", 8192, 45568, 1, 6, 120, use_graph),
+        "appendixa": lambda: extra_appendix_a(torch, use_graph),
+        "tokens": lambda: {"gpu": extra_decoder_tokens(torch, models),
+                           "cpu_baseline": None if args.no_cpu else decoder_cpu_baseline()},
+        "tokens8k": lambda: extra_decoder_tokens(torch, models or ["7B"], max_pos=8192),
+        "prompt": lambda: extra_prompt(torch, models),
+        "prompt2k": lambda: extra_prompt(torch, models or ["7B"], M=2048, max_pos=4096),
+        "tl2": lambda: extra_tl2(torch, use_graph),
+    }
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -559,114 +846,34 @@ def main():
     import numpy as np
     import torch
     from paper_2410_16144_amd import binding
-    from paper_2410_16144_amd.decode_layer import make_layer
 
     binding.lib()  # raises if the HIP library is not built; there is no fallback
     assert torch.cuda.is_available(), "bench.py needs a GPU"
-    dev = torch.device("cuda:0")
     use_graph = not args.no_graph
+    sect = sections(torch, np, args, use_graph)
 
     if args.only:
-        sect = {"copy": lambda: extra_copy(torch),
-                "prefill": lambda: [extra_prefill(torch, m, k, n, use_graph) for m in (512, 2048)
-                                    for (k, n) in ((4096, 11008), (11008, 4096))],
-                "decode7b": lambda: [extra_decode_shape(torch, "7B-shape", 4096, 11008, m, 24, 480, use_graph)
-                                     for m in (1, 4, 8)],
-                "decode100b": lambda: extra_decode_shape(torch, "100B-shape", 12288, 33792, 1, 6, 120, use_graph),
-                "paper100b": lambda: extra_decode_shape(torch, "Appendix-A 100B", 8192, 45568, 1, 6, 120, use_graph),
-                "config1": lambda: extra_config1(torch, use_graph),
-                "appendixa": lambda: extra_appendix_a(torch, use_graph),
-                "tokens": lambda: {"gpu": extra_decoder_tokens(torch, args.models.split(",") if args.models else None),
-                                   "cpu_baseline": None if args.no_cpu else decoder_cpu_baseline()},
-                "tokens8k": lambda: extra_decoder_tokens(torch, args.models.split(",") if args.models else ["7B"], max_pos=8192),
-                "prompt": lambda: extra_prompt(torch, args.models.split(",") if args.models else None),
-                "prompt2k": lambda: extra_prompt(torch, args.models.split(",") if args.models else ["7B"], M=2048, max_pos=4096),
-                "tl2": lambda: extra_tl2(torch, use_graph),
-                }[args.only]()
-        print(json.dumps({args.only: sect}))
+        print(json.dumps({args.only: sect[args.only]()}))
         return
 
-    hidden, ffn, M = 3200, 8640, 1
-    # layer 0 is drawn on the host so that the oracle sees the same bits; the rest on the device
-    layer0, host = make_layer(2, 0, hidden, ffn, M, dev, 0.4, 0.01, host=True)
-    layers = [layer0] + [make_layer(2, i, hidden, ffn, M, dev, 0.4, 0.01)[0] for i in range(1, args.layers)]
-    packed_bytes = layer0.packed_bytes
-    torch.cuda.synchronize()
-
-    import oracle
-    check_layer_against_oracle(torch, np, oracle, layer0, host)
-
-    # ---- the timed region: exactly --steps steps after --warmup untimed ones
-    fns = [l.step_fused for l in layers]
-    for i in range(args.warmup):
-        fns[i % len(fns)]()
-    spread = {}
-    ms, wall_ms, mode = run_steps(torch, fns, args.steps, use_graph, spread)
-    ms_per_step = ms / args.steps
-    value = packed_bytes / (ms_per_step * 1e-3) / 1e9
-    # the step IS one launch of the dominant kernel, so its average launch duration is the step time
-    kernel_us = ms_per_step * 1e3
-    result = {
-        "metric": "ternary x int8 GEMV packed-weight GB/s", "value": round(value, 1), "unit": "GB/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 6),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
-        "config": {"workload": "3B-shape decoder layer decode, M=1: absmax int8 quantization of the layer's inputs + "
-                               "7 ternary GEMVs (hidden 3200, ffn 8640) per step in one fused launch, %d distinct "
-                               "layers rotated (%.2f GB packed)" % (len(layers), packed_bytes * len(layers) / 1e9),
-                   "launch": mode, "packed_bytes_per_step": packed_bytes,
-                   "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4), "wall_ms_timed_region": round(wall_ms, 3),
-                   "spread_over_replays": spread},
-        "roofline": {"bound": "hbm", "achieved": round(value, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(value / HBM_PEAK_GBS, 4), "traffic": load_traffic("decode_kernel_3b_layer_m1"),
-                     "kernel": "decode_sk_kernel<8, true, true, 1, 0> (fused quantize + 7 GEMVs of one layer per launch, "
-                               "equal tile shares per workgroup)",
-                     "avg_launch_us": round(kernel_us, 3), "bytes_per_launch": packed_bytes},
-    }
-
-    if not args.no_cpu:
-        result["cpu_baseline"] = cpu_baseline(np, oracle, host, layer0.projs, packed_bytes, args.cpu_seconds)
+    # ---- the timed region: exactly --steps tokens of the 100B-shape model after --warmup untimed ones
+    result, energy = headline_100b(torch, np, args, use_graph)
 
     if not args.no_extra:
         extra = {}
-        variants = {}
-        for label, attr in (("fused_dependency_ordered_4_launches", "step_fused_dependency_ordered"),
-                            ("grouped_quant_plus_grouped_gemv", "step_two_launches"),
-                            ("quant_x4_plus_grouped_gemv", "step_single_launch"),
-                            ("quant_x4_plus_7_gemv_launches", "step_separate")):
-            vms, _, _ = run_steps(torch, [getattr(l, attr) for l in layers], args.steps, use_graph)
-            variants[label] = {"us_per_step": round(vms * 1e3 / args.steps, 3),
-                               "GBps": round(packed_bytes / (vms / args.steps) / 1e6, 1)}
-        gms, _, _ = run_steps(torch, [l.group_all.launch for l in layers], args.steps, use_graph)
-        variants["grouped_gemv_kernel_only"] = {"us_per_step": round(gms * 1e3 / args.steps, 3),
-                                                "GBps": round(packed_bytes / (gms / args.steps) / 1e6, 1)}
-        extra["decode_3b_launch_variants"] = variants
-        del layers, fns, layer0
-        torch.cuda.empty_cache()
-        extra["copy_1GiB"] = extra_copy(torch)
-        torch.cuda.empty_cache()
-        extra["decode_7b"] = [extra_decode_shape(torch, "7B-shape", 4096, 11008, m, 24, 480, use_graph)
-                              for m in (1, 4, 8)]
-        torch.cuda.empty_cache()
-        extra["decode_100b_layer"] = extra_decode_shape(torch, "100B-shape", 12288, 33792, 1, 6, 120, use_graph)
-        torch.cuda.empty_cache()
-        extra["decode_paper_100b_layer"] = extra_decode_shape(torch, "Appendix-A 100B", 8192, 45568, 1, 6, 120, use_graph)
-        torch.cuda.empty_cache()
-        extra["config1_1536"] = extra_config1(torch, use_graph)
-        torch.cuda.empty_cache()
-        if args.full_100b:
-            extra["decode_100b_token"] = extra_full_100b(torch, use_graph)
+        if energy is not None:
+            extra["energy_100b_token"] = energy
+        # the other benchmark configurations, each with its own roofline and cpu_baseline; then the measured ceilings,
+        # the paper's own 100B shape, and the whole-model token loop in the paper's unit on three of Appendix A's shapes
+        for name, key in (("config1", "config1_1536"), ("config2", "config2_3b_layer"), ("config3", "config3_7b_layer"),
+                          ("prefill", "config4_prefill"), ("ceilings", "ceilings"), ("copy", "copy_1GiB"),
+                          ("paper100b", "decode_paper_100b_layer")):
+            t0 = time.perf_counter()
+            extra[key] = sect[name]()
             torch.cuda.empty_cache()
-        extra["prefill"] = [extra_prefill(torch, m, k, n, use_graph) for m in (512, 2048)
-                            for (k, n) in ((4096, 11008), (11008, 4096))]
-        torch.cuda.empty_cache()
-        # whole-model token rate, the paper's own unit, on three of Appendix A's shapes (all twelve: --only tokens)
+            print("bench: section %s done (%.0f s)" % (name, time.perf_counter() - t0), file=sys.stderr, flush=True)
         extra["decoder_tokens"] = extra_decoder_tokens(torch, ["700M", "7B", "30B"])
         torch.cuda.empty_cache()
-        # a long context: the same loop on a cache of 8192 positions, timed at its start and at its end
-        extra["decoder_tokens_8k_cache"] = extra_decoder_tokens(torch, ["7B"], max_pos=8192)
-        torch.cuda.empty_cache()
-        # and the same block over a prompt of 512 tokens at once (more shapes: --only prompt --models ...)
-        extra["decoder_prompt"] = extra_prompt(torch, ["7B"])
         result["extra"] = extra
 
     print(json.dumps(result))

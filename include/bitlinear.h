@@ -379,6 +379,12 @@ const char *bl_status_str(bl_status s);
  * the thread's last launch succeeded).  Static string owned by the HIP runtime. */
 const char *bl_last_hip_error(void);
 
+/* Which kernel the calling thread's most recent decode or prefill product call launched: the
+ * template instance and the grid, e.g. "decode_kernel<1, 1, 1, 1, 0, 0> grid=2112" (the name rocprofv3 shows
+ * for it).  "" before the first such call.  Points into thread-local storage, valid until the
+ * thread's next call of this function.  For tools that label what they time. */
+const char *bl_last_kernel(void);
+
 /* Library version string (static). */
 const char *bl_version(void);
 

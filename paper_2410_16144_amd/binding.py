@@ -33,7 +33,7 @@ BL_TL2_LAYOUT_VERSION = 2
 # every symbol include/bitlinear.h and include/bitlinear_decoder.h declare
 DECLARED_SYMBOLS = (
     "bl_padded_k", "bl_padded_n", "bl_packed_desc_init", "bl_pack_ternary", "bl_unpack_ternary",
-    "bl_quant_act", "bl_quant_act_batch", "bl_gemv", "bl_gemv_batch", "bl_gemv_batch_static", "bl_decode_batch", "bl_gemm", "bl_gemm_batch", "bl_set_tuning", "bl_get_stat", "bl_status_str", "bl_last_hip_error", "bl_version",
+    "bl_quant_act", "bl_quant_act_batch", "bl_gemv", "bl_gemv_batch", "bl_gemv_batch_static", "bl_decode_batch", "bl_gemm", "bl_gemm_batch", "bl_set_tuning", "bl_get_stat", "bl_status_str", "bl_last_hip_error", "bl_last_kernel", "bl_version",
     "bl_tl2_padded_k", "bl_tl2_desc_init", "bl_tl2_pack", "bl_tl2_unpack", "bl_tl2_gemv", "bl_tl2_gemv_batch",
     "bl_norm_quant", "bl_rope_table", "bl_attn_scratch_bytes", "bl_attn_decode", "bl_pos_advance", "bl_decode_norm_batch", "bl_attn_prefill", "bl_attn_prefill_scratch_bytes",
 )
@@ -177,6 +177,7 @@ def lib():
     l.bl_status_str.restype = ctypes.c_char_p
     l.bl_version.restype = ctypes.c_char_p
     l.bl_last_hip_error.restype = ctypes.c_char_p
+    l.bl_last_kernel.restype = ctypes.c_char_p
     for name in ("bl_packed_desc_init", "bl_pack_ternary", "bl_unpack_ternary", "bl_quant_act", "bl_quant_act_batch", "bl_gemv",
                  "bl_gemv_batch", "bl_decode_batch", "bl_gemm", "bl_set_tuning", "bl_tl2_desc_init", "bl_tl2_pack",
                  "bl_tl2_unpack", "bl_tl2_gemv", "bl_tl2_gemv_batch", "bl_norm_quant", "bl_rope_table", "bl_attn_decode",
@@ -403,6 +404,10 @@ def bl_decode_norm_batch(items, workspace_dev: int = 0, stream: int = 0):
 
 def bl_set_tuning(key: str, value: int):
     _check(lib().bl_set_tuning(key.encode(), int(value)), "bl_set_tuning")
+
+
+def bl_last_kernel() -> str:
+    return lib().bl_last_kernel().decode()
 
 
 def bl_get_stat(key: str) -> int:

@@ -104,6 +104,23 @@ def build_abi_check() -> str:
     return ABI_CHECK_BIN
 
 
+CEILINGS_SRC = os.path.join(os.path.dirname(HERE), "tests", "ceilings", "ceilings.hip")
+CEILINGS_LIB = os.path.join(os.path.dirname(HERE), "tests", "ceilings", "libceilings.so")
+
+
+def build_ceilings() -> str:
+    """The measured-ceiling probes of bench.py (a register-only MFMA loop, a read-only streaming kernel): a library of
+    their own under tests/, not linked into libbitlinear.so."""
+    tmp = CEILINGS_LIB + ".tmp.%d" % os.getpid()
+    subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+                           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+                           "-Wno-unused-command-line-argument", CEILINGS_SRC, "-o", tmp,
+                           "-no-hip-rt", "-L", _hip_runtime_dir(), "-lamdhip64"], stderr=subprocess.DEVNULL)
+    os.replace(tmp, CEILINGS_LIB)
+    return CEILINGS_LIB
+
+
 if __name__ == "__main__":
     print(build(force=True, verbose=True))
     print(build_abi_check())
+    print(build_ceilings())

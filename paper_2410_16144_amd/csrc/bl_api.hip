@@ -1,5 +1,6 @@
 // C-ABI entry points: host-side validation, then one kernel launch each.
 // No entry point allocates, frees or synchronizes.
+#include <stdio.h>
 #include <string.h>
 
 #include "bl_internal.hpp"
@@ -55,6 +56,7 @@ bl::GemmProblem make_problem(const void* packed, const bl_packed_desc* d, const 
 }
 
 thread_local hipError_t t_last_hip_error = hipSuccess;
+thread_local char t_kernel_text[160];
 
 inline bl_status hip_status(hipError_t e) {
     t_last_hip_error = e;
@@ -67,6 +69,8 @@ inline bl_status hip_status(hipError_t e) {
 inline void drop_stale_hip_error() { (void)hipGetLastError(); }
 
 }  // namespace
+
+thread_local bl::KernelNote bl::t_kernel_note;
 
 extern "C" {
 
@@ -611,6 +615,26 @@ int64_t bl_get_stat(const char* key) {
 }
 
 const char* bl_last_hip_error(void) { return hipGetErrorString(t_last_hip_error); }
+
+const char* bl_last_kernel(void) {
+    const bl::KernelNote& n = bl::t_kernel_note;
+    if (!n.fmt) return "";
+    // the note's format: %d = next value as a number, %b = next value as true / false (as profilers print the name)
+    char* out = t_kernel_text;
+    char* const end = t_kernel_text + sizeof t_kernel_text - 24;
+    int next = 0;
+    for (const char* f = n.fmt; *f && out < end; ++f) {
+        if (f[0] == '%' && (f[1] == 'd' || f[1] == 'b') && next < 6) {
+            const int v = n.v[next++];
+            out += f[1] == 'd' ? snprintf(out, 16, "%d", v) : snprintf(out, 16, "%s", v ? "true" : "false");
+            ++f;
+        } else {
+            *out++ = *f;
+        }
+    }
+    snprintf(out, 24, " grid=%d", n.grid);
+    return t_kernel_text;
+}
 
 const char* bl_version(void) { return "bitlinear-gfx950 0.2 (layouts 1, 2)"; }
 

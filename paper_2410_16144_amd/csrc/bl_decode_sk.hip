@@ -212,6 +212,7 @@ hipError_t launch_sk(const DecodeBatch& b, size_t lds, hipStream_t s) {
     const hipError_t e = ceiling.ensure(reinterpret_cast<const void*>(kernel));
     if (e != hipSuccess) return e;
     const FirstWgs first(b);
+    note_kernel("decode_sk_kernel<%d, %b, %b, %d, %d>", b.total_wgs, U, FUSED, XBF16, LAYOUT, NORM);
     kernel<<<dim3((unsigned)b.total_wgs), dim3(kThreads), lds, s>>>(BL_FIRST_WG_ARGS(first), b);
     return hipGetLastError();
 }

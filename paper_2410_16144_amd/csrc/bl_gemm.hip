@@ -394,6 +394,7 @@ hipError_t launch_gemm(const GemmProblem& p, int64_t M, hipStream_t s) {
     if (wgs_total > INT32_MAX) return hipErrorInvalidValue;
     const dim3 grid((unsigned)wgs_total), block(256);
     const int igx = (int)gx;
+    note_kernel("gemm_kernel<%d, %d, %d>", (int)wgs_total, mb, h, wk);
     switch (100 * (wk - 1) + 10 * mb + h) {
         case 12: gemm_kernel<1, 2, 1><<<grid, block, 0, s>>>(p, (int)M, igx); break;
         case 14: gemm_kernel<1, 4, 1><<<grid, block, 0, s>>>(p, (int)M, igx); break;
@@ -427,6 +428,7 @@ hipError_t launch_gemm_batch(const GemmProblem* ps, int count, int64_t M, hipStr
     if (wgs_total > INT32_MAX) return hipErrorInvalidValue;
     const dim3 grid((unsigned)wgs_total), block(256);
     const int igx = (int)gx;
+    note_kernel("gemm_batch_kernel<%d, %d, %d>", (int)wgs_total, mb, h, wk);
     switch (100 * (wk - 1) + 10 * mb + h) {
         case 12: gemm_batch_kernel<1, 2, 1><<<grid, block, 0, s>>>(b, (int)M, igx); break;
         case 14: gemm_batch_kernel<1, 4, 1><<<grid, block, 0, s>>>(b, (int)M, igx); break;

@@ -377,6 +377,8 @@ hipError_t launch_kernel(Kernel kernel, LdsCeiling& ceiling, const DecodeBatch& 
 template <int M, int KIND, bool XBF16>
 hipError_t launch_one(const DecodeBatch& b, size_t lds_bytes, hipStream_t s) {
     static LdsCeiling attr_set;   // one per instantiation, i.e. per kernel
+    if constexpr (KIND <= 1) note_kernel("decode_kernel<%d, %b, %b, 1, 0, false>", b.total_wgs, M, KIND, KIND == 0 || XBF16);
+    else note_kernel("decode_mfma_kernel<%d, %d, %b>", b.total_wgs, M, KIND - 2, KIND != 4 || XBF16);
     if constexpr (KIND == 0) return launch_kernel(&decode_kernel<M, false, true>, attr_set, b, lds_bytes, s);
     else if constexpr (KIND == 1) return launch_kernel(&decode_kernel<M, true, XBF16>, attr_set, b, lds_bytes, s);
     else if constexpr (KIND == 2) return launch_kernel(&decode_mfma_kernel<M, 0, true>, attr_set, b, lds_bytes, s);
@@ -489,6 +491,7 @@ hipError_t launch_decode(const DecodeBatch& batch, int M, bool fused, hipStream_
         if (plan_decode_split(b, false, tiles_per_wave)) return launch_decode_split(b, tiles_per_wave, false, s);
         plan_decode(b, kInFlight);
         static LdsCeiling ceiling;
+        note_kernel("decode_kernel<1, false, true, 2, 0, false>", b.total_wgs);
         return launch_kernel(&decode_kernel<1, false, true, 2>, ceiling, b, lds_bytes_for(1, 0, false), s);
     }
     int64_t max_Kp = 0;
@@ -521,14 +524,17 @@ hipError_t launch_decode(const DecodeBatch& batch, int M, bool fused, hipStream_
         if (M != 1 || bf16) return hipErrorInvalidValue;
         if (b.p[0].glu_gamma) {
             static LdsCeiling ceiling;
+            note_kernel("decode_kernel<1, true, false, 1, 1, true>", b.total_wgs);
             return launch_kernel(&decode_kernel<1, true, false, 1, 1, true>, ceiling, b, lds, s);
         }
         static LdsCeiling ceiling;
+        note_kernel("decode_kernel<1, true, false, 1, 1, false>", b.total_wgs);
         return launch_kernel(&decode_kernel<1, true, false, 1, 1>, ceiling, b, lds, s);
     }
     if (b.p[0].ss_in) {   // the row is already multiplied by its norm weight; sum(x^2) in pieces
         if (M != 1 || bf16) return hipErrorInvalidValue;
         static LdsCeiling ceiling;
+        note_kernel("decode_kernel<1, true, false, 1, 2, false>", b.total_wgs);
         return launch_kernel(&decode_kernel<1, true, false, 1, 2>, ceiling, b, lds, s);
     }
     return bf16 ? launch_m<1, true>(b, M, lds, s) : launch_m<1, false>(b, M, lds, s);

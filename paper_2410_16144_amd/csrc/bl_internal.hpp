@@ -148,6 +148,21 @@ hipError_t launch_attn_decode(const ::bl_attn_args& a, hipStream_t s);
 hipError_t launch_pos_advance(int32_t* pos, hipStream_t s);
 hipError_t launch_attn_prefill(const ::bl_attn_prefill_args& a, hipStream_t s);
 
+// The calling thread's most recent product launch: kernel template instance and grid, for tools that label what they
+// time (bl_last_kernel).  Only the pieces are stored at launch time; the text is formatted on request.
+struct KernelNote {
+    const char* fmt = nullptr;   // printf format over v[0..5]
+    int v[6] = {0, 0, 0, 0, 0, 0};
+    int grid = 0;
+};
+extern thread_local KernelNote t_kernel_note;
+inline void note_kernel(const char* fmt, int grid, int a = 0, int b = 0, int c = 0, int d = 0, int e = 0, int f = 0) {
+    t_kernel_note.fmt = fmt;
+    t_kernel_note.grid = grid;
+    t_kernel_note.v[0] = a; t_kernel_note.v[1] = b; t_kernel_note.v[2] = c;
+    t_kernel_note.v[3] = d; t_kernel_note.v[4] = e; t_kernel_note.v[5] = f;
+}
+
 // Launch-shape overrides for experiments (0 = choose automatically).
 void set_gemv_waves(int waves);
 void set_attn_groups(int groups);   // bl_attn_decode's workgroups per head; 0 automatic
