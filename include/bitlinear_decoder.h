@@ -158,6 +158,19 @@ bl_status bl_decode_norm_batch(const bl_decode_norm_item *items, int32_t count, 
                                void *stream);
 
 /*
+ * The operand of the gated epilogue from its two matrices: gate and up ([F, K] int8 ternary each, row-major, F a
+ * multiple of 32) go into ONE packed matrix of N = 2 F rows, interleaved by 32 -- packed row block b holds gate rows
+ * 32 b .. 32 b + 31 in its rows 0-31 and up rows 32 b .. 32 b + 31 in its rows 32-63 (Section 2's offline weight
+ * transformation, Table 1's codes, in the tiled layout of bl_pack_ternary).
+ *   d           descriptor from bl_packed_desc_init(2 F, K, w_scale of the GATE matrix); the up matrix's scale is
+ *               passed to the launch (bl_decode_norm_item.w_scale_up)
+ *   packed_dev, bad_count_dev, stream   as for bl_pack_ternary
+ * Errors: those of bl_pack_ternary; BL_ERR_SHAPE if d->N is not a multiple of 64.
+ */
+bl_status bl_pack_gate_up(const int8_t *gate_dev, const int8_t *up_dev, const bl_packed_desc *d, void *packed_dev,
+                          int32_t *bad_count_dev, void *stream);
+
+/*
  * Rotary table for bl_attn_decode, computed on the GPU in fp64 and rounded to fp32:
  *   table[(p * head_dim/2 + i) * 2 + {0, 1}] = {cos, sin}(p * theta^(-2 i / head_dim)),
  *   p = 0 .. max_pos-1, i = 0 .. head_dim/2 - 1.   table_dev: max_pos * head_dim floats.
@@ -215,8 +228,8 @@ bl_status bl_attn_decode(const bl_attn_args *args, void *stream);
  * to cache rows 0 .. pos0 + m.  Two launches: the M keys (rotated) and values go into the cache, rounded to bf16 as
  * bl_attn_decode rounds them (the same bits); then the attention.  Head sizes up to BL_ATTN_BLOCK_MAX_HEAD_DIM take one
  * workgroup per (head, 64 tokens) that forms scores and weighted values on the matrix cores, with the fp32 queries
- * and softmax weights each entered as the sum of two bf16 numbers (relative error below 2^-17 per factor, fp32
- * accumulation): the outputs agree with M bl_attn_decode calls to about 1e-5 of the output's scale, not bit for bit.
+ * entered as the sum of three bf16 numbers (all 24 bits) and the softmax weights, which lie in [0, 1], as the sum of
+ * two (relative error below 2^-17), fp32 accumulation: the outputs agree with M bl_attn_decode calls to about 1e-5 of the output's scale, not bit for bit.
  * Larger head sizes take one bl_attn_decode-style workgroup per (head, 64 cache rows, token), and there the results
  * are those of M bl_attn_decode calls in order.
  *   q_lin_dev, k_lin_dev, v_lin_dev   [M, n_heads * head_dim] fp32, rows contiguous; k_lin_dev and v_lin_dev 8-byte aligned

@@ -35,7 +35,7 @@ DECLARED_SYMBOLS = (
     "bl_padded_k", "bl_padded_n", "bl_packed_desc_init", "bl_pack_ternary", "bl_unpack_ternary",
     "bl_quant_act", "bl_quant_act_batch", "bl_gemv", "bl_gemv_batch", "bl_gemv_batch_static", "bl_decode_batch", "bl_gemm", "bl_gemm_batch", "bl_set_tuning", "bl_get_stat", "bl_status_str", "bl_last_hip_error", "bl_last_kernel", "bl_version",
     "bl_tl2_padded_k", "bl_tl2_desc_init", "bl_tl2_pack", "bl_tl2_unpack", "bl_tl2_gemv", "bl_tl2_gemv_batch",
-    "bl_norm_quant", "bl_rope_table", "bl_attn_scratch_bytes", "bl_attn_decode", "bl_pos_advance", "bl_decode_norm_batch", "bl_attn_prefill", "bl_attn_prefill_scratch_bytes",
+    "bl_norm_quant", "bl_rope_table", "bl_attn_scratch_bytes", "bl_attn_decode", "bl_pos_advance", "bl_decode_norm_batch", "bl_pack_gate_up", "bl_attn_prefill", "bl_attn_prefill_scratch_bytes",
 )
 
 BL_NORM_MAX_K = 49152
@@ -145,6 +145,7 @@ def lib():
     l.bl_packed_desc_init.argtypes = [i64, i64, ctypes.c_float, dp]
     l.bl_pack_ternary.argtypes = [vp, dp, vp, vp, vp]
     l.bl_unpack_ternary.argtypes = [vp, dp, vp, vp]
+    l.bl_pack_gate_up.argtypes = [vp, vp, dp, vp, vp, vp]
     l.bl_quant_act.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, vp, vp, vp]
     l.bl_quant_act_batch.argtypes = [ctypes.POINTER(QuantItem), i32, vp]
     l.bl_gemv.argtypes = [vp, dp, vp, vp, vp, i64, vp, vp, vp]
@@ -181,7 +182,7 @@ def lib():
     for name in ("bl_packed_desc_init", "bl_pack_ternary", "bl_unpack_ternary", "bl_quant_act", "bl_quant_act_batch", "bl_gemv",
                  "bl_gemv_batch", "bl_decode_batch", "bl_gemm", "bl_set_tuning", "bl_tl2_desc_init", "bl_tl2_pack",
                  "bl_tl2_unpack", "bl_tl2_gemv", "bl_tl2_gemv_batch", "bl_norm_quant", "bl_rope_table", "bl_attn_decode",
-                 "bl_pos_advance", "bl_decode_norm_batch", "bl_attn_prefill", "bl_gemm_batch", "bl_gemv_batch_static"):
+                 "bl_pos_advance", "bl_decode_norm_batch", "bl_attn_prefill", "bl_gemm_batch", "bl_gemv_batch_static", "bl_pack_gate_up"):
         getattr(l, name).restype = ctypes.c_int
     _lib = l
     return l
@@ -217,6 +218,11 @@ def bl_packed_desc_init(N: int, K: int, w_scale: float) -> PackedDesc:
 def bl_pack_ternary(w_dev: int, desc: PackedDesc, packed_dev: int, bad_count_dev: int = 0, stream: int = 0):
     _check(lib().bl_pack_ternary(w_dev, ctypes.byref(desc), packed_dev, bad_count_dev or None, stream or None),
            "bl_pack_ternary")
+
+
+def bl_pack_gate_up(gate_dev: int, up_dev: int, desc: PackedDesc, packed_dev: int, bad_count_dev: int = 0, stream: int = 0):
+    _check(lib().bl_pack_gate_up(gate_dev, up_dev, ctypes.byref(desc), packed_dev, bad_count_dev or None, stream or None),
+           "bl_pack_gate_up")
 
 
 def bl_unpack_ternary(packed_dev: int, desc: PackedDesc, w_dev: int, stream: int = 0):

@@ -105,7 +105,19 @@ bl_status bl_pack_ternary(const int8_t* w_dev, const bl_packed_desc* d, void* pa
     if (s != BL_OK) return s;
     if (!aligned(packed_dev, 16) || (bad_count_dev && !aligned(bad_count_dev, 4))) return BL_ERR_ALIGN;
     drop_stale_hip_error();
-    return hip_status(bl::launch_pack(w_dev, d->N, d->K, d->Np, d->Kp, static_cast<uint32_t*>(packed_dev),
+    return hip_status(bl::launch_pack(w_dev, nullptr, d->N, d->K, d->Np, d->Kp, static_cast<uint32_t*>(packed_dev),
+                                      bad_count_dev, static_cast<hipStream_t>(stream)));
+}
+
+bl_status bl_pack_gate_up(const int8_t* gate_dev, const int8_t* up_dev, const bl_packed_desc* d, void* packed_dev,
+                          int32_t* bad_count_dev, void* stream) {
+    if (!gate_dev || !up_dev || !d || !packed_dev) return BL_ERR_NULL;
+    bl_status s = check_desc(d);
+    if (s != BL_OK) return s;
+    if (d->N % BL_TILE_N != 0) return BL_ERR_SHAPE;   // 2 F rows, F a multiple of 32
+    if (!aligned(packed_dev, 16) || (bad_count_dev && !aligned(bad_count_dev, 4))) return BL_ERR_ALIGN;
+    drop_stale_hip_error();
+    return hip_status(bl::launch_pack(gate_dev, up_dev, d->N, d->K, d->Np, d->Kp, static_cast<uint32_t*>(packed_dev),
                                       bad_count_dev, static_cast<hipStream_t>(stream)));
 }
 

@@ -353,23 +353,12 @@ __device__ __forceinline__ void wait_lds_copy() {
 }
 
 // ---- matrix-core operand helpers (2..8 tokens) ----------------------------------------------
-typedef int v4i __attribute__((ext_vector_type(4)));
-
 __device__ __forceinline__ void regroup16(const uint4& w, uint32_t (&t)[4]) {
     auto s02 = __builtin_amdgcn_permlane32_swap(w.x, w.z, false, false);
     auto s13 = __builtin_amdgcn_permlane32_swap(w.y, w.w, false, false);
     auto a = __builtin_amdgcn_permlane16_swap(s02[0], s13[0], false, false);
     auto c = __builtin_amdgcn_permlane16_swap(s02[1], s13[1], false, false);
     t[0] = a[0]; t[1] = a[1]; t[2] = c[0]; t[3] = c[1];
-}
-
-__device__ __forceinline__ v4i expand_codes(uint32_t word) {
-    v4i r;
-    r[0] = (int)(word & 0x03030303u);
-    r[1] = (int)((word >> 2) & 0x03030303u);
-    r[2] = (int)((word >> 4) & 0x03030303u);
-    r[3] = (int)((word >> 6) & 0x03030303u);
-    return r;
 }
 
 }  // namespace bl

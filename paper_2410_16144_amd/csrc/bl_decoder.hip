@@ -417,8 +417,8 @@ __device__ __forceinline__ void unpack_bf16(const typename CacheVec<W>::type& u,
 
 // One head's chunks merged by one workgroup: out = sum_c f_c o_c / sum_c f_c l_c with f_c = exp(m_c - max m) over the
 // chunks that hold rows 0 .. pos.  The chunks' maxima and sums are read one per thread; the factors go through LDS.
-// A value another workgroup of this launch has published (see publish below): read where it was deposited, by an
-// atomic that returns the old value and adds nothing.
+// A value another workgroup of this launch has published (see publish below): read where it was deposited, by a
+// device-scope atomic load (it does not take its value from this die's cache).
 __device__ __forceinline__ float read_published(float* at) {
     return __uint_as_float(__hip_atomic_load(reinterpret_cast<unsigned int*>(at), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
 }
@@ -586,8 +586,11 @@ __global__ __launch_bounds__(kAttnThreads) void attn_chunk_kernel(const AttnArgs
             if (active) {
                 float v[W];
                 unpack_bf16<W>(vv[i], v);
+                // rows beyond the token's are selected out, not multiplied out: their registers hold whatever the cache
+                // held before (row `pos` is requested before this launch writes it; a caller's cache need not be finite)
+                const bool counts = row < rows;
 #pragma unroll
-                for (int x = 0; x < W; ++x) o_w[x] += w * (own ? s_newv[cc * W + x] : v[x]);
+                for (int x = 0; x < W; ++x) o_w[x] += counts ? w * (own ? s_newv[cc * W + x] : v[x]) : 0.0f;
             }
         }
         if (more) request(c + groups, false);
@@ -625,12 +628,15 @@ __global__ __launch_bounds__(kAttnThreads) void attn_chunk_kernel(const AttnArgs
     }
 
     // The head's workgroups are merged by whichever of them finishes last.  Nobody waits for anybody: every
-    // workgroup DEPOSITS its figures with atomics that return the old value (so their completion can be waited for,
-    // and they are performed where every compute unit's atomics meet, not in a cache of this die), then draws a
-    // ticket from the head's counter the same way; the one that draws the last ticket reads all deposits, again with
-    // atomics, merges, and puts the counter back to zero for the next launch.  Data that crosses
-    // workgroups inside this launch travels through atomics only -- no cache write-back or invalidation is involved
-    // (a device-wide fence here cost 8-35 us per layer).
+    // workgroup DEPOSITS its figures with device-scope atomic exchanges (performed where every compute unit's atomics
+    // meet, not in a cache of this die), then draws a ticket from the head's counter the same way; the one that draws
+    // the last ticket reads all deposits with device-scope loads, merges, and puts the counter back to zero for the
+    // next launch.  Data that crosses workgroups inside this launch travels through these operations only -- no cache
+    // write-back or invalidation is involved (a device-wide fence here cost 8-35 us per layer).
+    // What orders a deposit before the ticket: the exchange RETURNS a value, so it is counted as outstanding until
+    // it has been performed; EVERY publishing wave waits for its own outstanding memory operations (vmcnt(0), below)
+    // before the barrier, and the ticket is drawn after the barrier.  A workgroup barrier alone does not wait for
+    // memory operations in flight, so the wait is explicit, and it is in every wave, not only in the one that draws.
     const int used = min(groups, last_chunk + 1);       // workgroups of this head that get this far
     const bool alone = used == 1;                       // uniform
     float* dst = scratch + ((int64_t)head * p.chunks + chunk) * (d + 2);
@@ -650,9 +656,10 @@ __global__ __launch_bounds__(kAttnThreads) void attn_chunk_kernel(const AttnArgs
     }
     if (alone) return;                                  // uniform
     __shared__ unsigned int s_ticket;
-    if (tid == 0) s_ticket = sink;                      // a use of the returned values: the deposits are returning atomics
-    __syncthreads();                                    // every wave waits for its memory operations here, so the deposits
-                                                        // have all returned (and s_o, s_w have been read)
+    // every lane consumes what its exchanges returned (so they stay returning atomics) and waits until none of this
+    // wave's memory operations is outstanding
+    asm volatile("s_waitcnt vmcnt(0)" ::"v"(sink) : "memory");
+    __syncthreads();                                    // all deposits of this workgroup have been performed (and s_o, s_w read)
     unsigned int* counter = reinterpret_cast<unsigned int*>(scratch + (int64_t)p.n_heads * p.chunks * (d + 2)) + head;
     if (tid == 0) s_ticket = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();

@@ -30,25 +30,16 @@
 // their results dropped in the epilogue) so that the accumulators never leave their registers.
 #include <type_traits>
 
+#include "bl_gemm_ring.hpp"
 #include "bl_internal.hpp"
 
 namespace bl {
 
 namespace {
 
-typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int kWaves = 4;         // waves per workgroup
-
-__device__ __forceinline__ v4i expand_codes(uint32_t word) {
-    v4i r;
-    r[0] = (int)(word & 0x03030303u);
-    r[1] = (int)((word >> 2) & 0x03030303u);
-    r[2] = (int)((word >> 4) & 0x03030303u);
-    r[3] = (int)((word >> 6) & 0x03030303u);
-    return r;
-}
 
 constexpr int kXcds = 8;   // workgroup i runs on accelerator die i % 8, each die with its own L2
 
@@ -57,15 +48,14 @@ template <int MB, int H, int WK>
 __device__ __forceinline__ void gemm_tile(const GemmProblem& p, const int M, const int tile_x, const int tile_y) {
     static_assert(WK == 1 || (WK == 2 && MB % 2 == 0), "K groups exchange halves of the token tile");
     static_assert(H >= 2 && H <= 4, "32-row blocks per wave");
-    constexpr int NT = (H + 1) / 2;       // packed 64-row tiles a wave loads per step
+    using Ring = GemmRing<MB, H, WK>;     // ring depths and wait counts: bl_gemm_ring.hpp, checked by a host-side model
+    constexpr int NT = Ring::kNT;         // packed 64-row tiles a wave loads per step
     constexpr int WN = kWaves / WK;       // waves along N
     constexpr int BM = 32 * MB;
     constexpr int kTileBytesA = BM * kTileK;        // unpadded: 64 bytes per token row
     constexpr int kStageBytes = WK * kTileBytesA;   // one activation tile per K group
-    constexpr int kStages = WK == 1 ? 8 : 6;        // LDS ring (6 x 8 KiB with two K groups: static LDS ends at 64 KiB)
-    constexpr int kLead = 4;                        // the tile of step i + kLead is requested during step i
-    static_assert(kLead >= 3, "the prologue waits for all but the last requested tile");
-    static_assert(kStages >= kLead + 1, "a stage is rewritten only after the barrier that ended its last read");
+    constexpr int kStages = Ring::kStages;          // LDS ring (6 x 8 KiB with two K groups: static LDS ends at 64 KiB)
+    constexpr int kLead = Ring::kLead;              // the tile of step i + kLead is requested during step i
     static_assert(BM <= 64, "one 4 KiB slab per 256 threads");
     constexpr int kExchangeBytes = WK == 1 ? 0 : WN * (MB / 2) * H * 16 * 64 * 4;   // one direction at a time
     constexpr int kLdsBytes = kStages * kStageBytes > kExchangeBytes ? kStages * kStageBytes : kExchangeBytes;
@@ -115,13 +105,12 @@ __device__ __forceinline__ void gemm_tile(const GemmProblem& p, const int M, con
             }
         }
     };
-    // The barrier that ends step i publishes the tile of step i+2, requested during step i+2-kLead; every load
-    // a thread issued in the kLead-2 steps since then may still be in flight (steps i >= 1; the prologue itself
-    // waits for tile 2).
-    constexpr int kYounger = (kLead - 2) * (WK + NT);
-    static_assert(kYounger < 16, "fits the low vmcnt field");
-    auto publish = [&]() {
-        __builtin_amdgcn_s_waitcnt(0x0f70 | kYounger);   // vmcnt(kYounger); LDS and scalar counters untouched
+    // The barrier that ends step i publishes the tile of step i+2, requested during step i+2-kLead: the wait in front
+    // of it names how many younger vector memory operations of this thread may still be in flight (Ring::kYounger in
+    // the main loop, Ring::kYoungerTail in the unrolled tail, whose weight loads the compiler removes as dead).
+    auto publish = [&](auto tail) {
+        constexpr int kAllowed = decltype(tail)::value ? Ring::kYoungerTail : Ring::kYounger;
+        __builtin_amdgcn_s_waitcnt(0x0f70 | kAllowed);   // vmcnt(kAllowed); LDS and scalar counters untouched
         __builtin_amdgcn_s_barrier();
     };
     const int op_row = lane & 31, op_g = lane >> 5;
@@ -166,17 +155,14 @@ __device__ __forceinline__ void gemm_tile(const GemmProblem& p, const int M, con
     // Register ring of packed weight tiles, steps i .. i+kWR-1, indexed by compile-time phases.  Eight deep where the
     // registers allow: the compiler's own wait for a weight tile (it counts the weight loads it can see) then
     // leaves the newest 6 loads in flight, which also covers the activation tiles requested since.
-    constexpr int kWR = NT == 1 ? 8 : 4;
+    constexpr int kWR = Ring::kWR;
     WTiles w[kWR];
 #pragma unroll
     for (int j = 0; j < kWR - 1; ++j) w[j] = wload(j);
 #pragma unroll
     for (int j = 0; j < kLead; ++j) request_tile(j);
-    // Tiles 0, 1 AND 2 have landed; only the youngest may still be in flight.  Tile 2 has to be waited for here: the
-    // barrier that ends step 0 is meant to publish it, but publish() counts the loads of a steady-state step behind
-    // it (requests alternate with weight loads), and the prologue's requests come back to back, so after step 0
-    // there are NT fewer loads behind tile 2 than publish() allows to be outstanding.
-    __builtin_amdgcn_s_waitcnt(0x0f70 | ((kLead - 3) * WK));
+    // Tiles 0, 1 AND 2 have landed; only the youngest requests may still be in flight (see Ring::kPrologueWait).
+    __builtin_amdgcn_s_waitcnt(0x0f70 | Ring::kPrologueWait);
     __syncthreads();                                            // also publishes s_scale / s_qsum
     v4i a_lo[2][MB], a_hi[MB];
     lread_half(0, 0, a_lo[0]);
@@ -226,7 +212,7 @@ __device__ __forceinline__ void gemm_tile(const GemmProblem& p, const int M, con
     // from the current LDS stage and expanded; while the second half runs, the first-half operands of the NEXT
     // step are read from the next stage (published by the barrier that ended the previous step) and expanded.
     // P = step mod 8 picks the register-ring slots at compile time; the LDS stage index is scalar arithmetic.
-    auto step = [&](auto phase, int kc) {
+    auto step = [&](auto phase, auto tail, int kc) {
         constexpr int P = decltype(phase)::value;
         const int st = kc % kStages, st1 = (kc + 1) % kStages;
         request_tile(kc + kLead);
@@ -243,9 +229,11 @@ __device__ __forceinline__ void gemm_tile(const GemmProblem& p, const int M, con
         mfma_half(a_hi, b_hi);
         interleave();
         __builtin_amdgcn_sched_barrier(0);
-        publish();
+        publish(tail);
     };
-#define BL_STEP(P, KC) step(std::integral_constant<int, P>{}, KC)
+    static_assert(Ring::kUnroll == 8, "the main loop below is written out for eight phases");
+#define BL_STEP(P, KC) step(std::integral_constant<int, P>{}, std::false_type{}, KC)
+#define BL_TAIL_STEP(P, KC) step(std::integral_constant<int, P>{}, std::true_type{}, KC)
     int kc = 0;
     for (; kc + 8 <= steps; kc += 8) {
         BL_STEP(0, kc);
@@ -257,14 +245,15 @@ __device__ __forceinline__ void gemm_tile(const GemmProblem& p, const int M, con
         BL_STEP(6, kc + 6);
         BL_STEP(7, kc + 7);
     }
-    if (kc < steps) BL_STEP(0, kc);
-    if (kc + 1 < steps) BL_STEP(1, kc + 1);
-    if (kc + 2 < steps) BL_STEP(2, kc + 2);
-    if (kc + 3 < steps) BL_STEP(3, kc + 3);
-    if (kc + 4 < steps) BL_STEP(4, kc + 4);
-    if (kc + 5 < steps) BL_STEP(5, kc + 5);
-    if (kc + 6 < steps) BL_STEP(6, kc + 6);
+    if (kc < steps) BL_TAIL_STEP(0, kc);
+    if (kc + 1 < steps) BL_TAIL_STEP(1, kc + 1);
+    if (kc + 2 < steps) BL_TAIL_STEP(2, kc + 2);
+    if (kc + 3 < steps) BL_TAIL_STEP(3, kc + 3);
+    if (kc + 4 < steps) BL_TAIL_STEP(4, kc + 4);
+    if (kc + 5 < steps) BL_TAIL_STEP(5, kc + 5);
+    if (kc + 6 < steps) BL_TAIL_STEP(6, kc + 6);
 #undef BL_STEP
+#undef BL_TAIL_STEP
 
     __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): the tiles requested beyond the end have landed too
     if constexpr (WK == 2) {

@@ -20,6 +20,7 @@
 // 0x0c0c0c0c gives four codes times 4 (still int8), so a word costs 1 shift + 4 ands + 4 dot4 per
 // token, the x4 group being kept in its own accumulator and divided out exactly at the end.
 #include "bl_decode_device.hpp"
+#include "bl_gemm_ring.hpp"
 
 namespace bl {
 
@@ -275,7 +276,7 @@ __global__ __launch_bounds__(kThreads, 8) void decode_mfma_kernel(BL_FIRST_WG_PA
         // activations first, straight into LDS (loads retire in order: waiting for them leaves the weight tiles in flight)
         copy_to_lds_async(p.q, (uint32_t)(uintptr_t)(__attribute__((address_space(3))) int8_t*)lds_q, M * Kp / 16, tid, wave);
         load_batch(ks);
-        wait_lds_copy<U>();
+        wait_lds_copy<LdsCopyWait<U>::kYounger>();   // the U weight tiles just requested may stay in flight; the copy may not
         __syncthreads();
     } else if constexpr (!kTilesAfterQuant) {
         load_batch(ks);   // waves without a row block load (valid) block 0: no branch, exact wait counts

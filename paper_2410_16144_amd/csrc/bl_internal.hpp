@@ -13,6 +13,18 @@ constexpr int kTileK = BL_TILE_K;            // k per packed tile
 constexpr int kTileBytes = kTileN * kTileK / 4;  // 1 KiB: one 128-bit load per lane
 constexpr int kWave = 64;
 
+// 16 two-bit codes of a packed word -> 16 int8 (one matrix-core operand register quadruple): byte b of element j is
+// the code at bits [8 b + 2 j, 8 b + 2 j + 1], i.e. k-offset 4 j + b of the word.
+typedef int v4i __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ v4i expand_codes(uint32_t word) {
+    v4i r;
+    r[0] = (int)(word & 0x03030303u);
+    r[1] = (int)((word >> 2) & 0x03030303u);
+    r[2] = (int)((word >> 4) & 0x03030303u);
+    r[3] = (int)((word >> 6) & 0x03030303u);
+    return r;
+}
+
 // One prefill product as the kernel sees it (all device pointers).
 struct GemmProblem {
     const uint4*   packed;
@@ -120,8 +132,8 @@ struct LdsCeiling {
 };
 
 // Launchers (each returns the hipError_t of its launch).
-hipError_t launch_pack(const int8_t* w, int64_t N, int64_t K, int64_t Np, int64_t Kp, uint32_t* packed,
-                       int32_t* bad_count, hipStream_t s);
+hipError_t launch_pack(const int8_t* w, const int8_t* w_up /* null: plain; else gate/up interleaved by 32 */, int64_t N,
+                       int64_t K, int64_t Np, int64_t Kp, uint32_t* packed, int32_t* bad_count, hipStream_t s);
 hipError_t launch_unpack(const uint32_t* packed, int64_t N, int64_t K, int64_t Np, int64_t Kp, int8_t* w,
                          hipStream_t s);
 hipError_t launch_quant(const QuantBatch& b, hipStream_t s);

@@ -22,16 +22,23 @@ __device__ __forceinline__ void word_coords(int64_t word, int64_t KC, int64_t& r
     k0 = kc * kTileK + s * 16;
 }
 
-__global__ __launch_bounds__(256) void pack_kernel(const int8_t* __restrict__ w, int64_t N, int64_t K, int64_t KC,
-                                                   int64_t words, uint32_t* __restrict__ packed,
+// w_up == nullptr: rows of the packed matrix are rows of w.  Otherwise the gated form's interleave: packed row block b holds
+// rows 32 b .. 32 b + 31 of w (gate) in its rows 0-31 and the same rows of w_up in its rows 32-63; N counts packed rows.
+__global__ __launch_bounds__(256) void pack_kernel(const int8_t* __restrict__ w, const int8_t* __restrict__ w_up, int64_t N,
+                                                   int64_t K, int64_t KC, int64_t words, uint32_t* __restrict__ packed,
                                                    int32_t* __restrict__ bad_count) {
     int64_t word = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (word >= words) return;
     int64_t row, k0;
     word_coords(word, KC, row, k0);
+    const bool in_matrix = row < N;
+    if (w_up) {
+        if (row & 32) w = w_up;
+        row = (row >> 6) * 32 + (row & 31);
+    }
     uint32_t out = 0;
     int bad = 0;
-    const bool fast = row < N && k0 + 16 <= K && ((reinterpret_cast<uintptr_t>(w) + row * K + k0) & 15) == 0;
+    const bool fast = in_matrix && k0 + 16 <= K && ((reinterpret_cast<uintptr_t>(w) + row * K + k0) & 15) == 0;
     if (fast) {
         uint4 v = *reinterpret_cast<const uint4*>(w + row * K + k0);
         uint32_t src[4] = {v.x, v.y, v.z, v.w};
@@ -48,7 +55,7 @@ __global__ __launch_bounds__(256) void pack_kernel(const int8_t* __restrict__ w,
 #pragma unroll
         for (int t = 0; t < 16; ++t) {
             int val = 0;  // padding weight
-            if (row < N && k0 + t < K) {
+            if (in_matrix && k0 + t < K) {
                 val = w[row * K + k0 + t];
                 if (val < -1 || val > 1) { val = 0; ++bad; }
             }
@@ -78,12 +85,12 @@ __global__ __launch_bounds__(256) void unpack_kernel(const uint32_t* __restrict_
 
 }  // namespace
 
-hipError_t launch_pack(const int8_t* w, int64_t N, int64_t K, int64_t Np, int64_t Kp, uint32_t* packed,
+hipError_t launch_pack(const int8_t* w, const int8_t* w_up, int64_t N, int64_t K, int64_t Np, int64_t Kp, uint32_t* packed,
                        int32_t* bad_count, hipStream_t s) {
     int64_t words = Np * Kp / 16;
     int64_t blocks = (words + 255) / 256;
     if (blocks > INT32_MAX) return hipErrorInvalidValue;
-    pack_kernel<<<dim3((unsigned)blocks), dim3(256), 0, s>>>(w, N, K, Kp / kTileK, words, packed, bad_count);
+    pack_kernel<<<dim3((unsigned)blocks), dim3(256), 0, s>>>(w, w_up, N, K, Kp / kTileK, words, packed, bad_count);
     return hipGetLastError();
 }
 

@@ -153,9 +153,12 @@ def pack_gate_up(w_gate: torch.Tensor, w_up: torch.Tensor, s_gate: float) -> ops
     by 32: row block b holds gate rows 32 b .. 32 b + 31, then the up rows of the same outputs -- the operand of a gated
     launch (NormDecodeGroup(glu=...)).  The descriptor carries the gate matrix's scale; the up matrix's goes with glu."""
     F, K = w_gate.shape
-    assert w_up.shape == (F, K) and F % 32 == 0
-    both = torch.stack([w_gate.reshape(F // 32, 32, K), w_up.reshape(F // 32, 32, K)], dim=1).reshape(2 * F, K)
-    return ops.pack_ternary(both.contiguous(), s_gate)
+    assert w_up.shape == (F, K) and F % 32 == 0 and w_gate.is_contiguous() and w_up.is_contiguous()
+    assert w_gate.dtype == torch.int8 and w_up.dtype == torch.int8 and w_gate.is_cuda and w_up.is_cuda
+    desc = B.bl_packed_desc_init(2 * F, K, s_gate)
+    blob = torch.empty(int(desc.bytes), dtype=torch.uint8, device=w_gate.device)
+    B.bl_pack_gate_up(w_gate.data_ptr(), w_up.data_ptr(), desc, blob.data_ptr(), 0, _stream())
+    return ops.PackedWeight(blob, desc)
 
 
 def can_fold_norm(K: int) -> bool:

@@ -1,0 +1,138 @@
+// Host-side model of the vector-memory wait counts in the prefill kernel (csrc/bl_gemm.hip) and in the matrix-core
+// decode kernel's activation copy (csrc/bl_gemv.hip).  No GPU, no HIP: the constants come from the header the kernels
+// use (csrc/bl_gemm_ring.hpp); the issue order is restated here from the kernels' text.
+//
+// Machine model (the ISA's): every vector memory operation a thread issues -- ordinary loads and global -> LDS loads
+// alike -- counts in ONE counter and completes in issue order; "s_waitcnt vmcnt(n)" returns when at most n of the
+// thread's operations are outstanding, i.e. all but its n youngest have completed.  A global -> LDS tile is readable
+// by the workgroup after a barrier that every thread passed after ITS part of the tile had completed.  All threads
+// of a loader wave run the same sequence, so one thread is modelled; waves that load no activations only take barriers.
+//
+// Checked, for every instantiation <MB, H, WK> the library launches and every step count up to kMaxSteps:
+//   1. whenever a step reads an activation tile from LDS, a barrier lies between that tile's completion and the read;
+//   2. whenever a request overwrites an LDS stage, a barrier lies between the last read of the stage's old tile and it;
+//   3. both hold when the compiler keeps the tail's weight loads and when it removes them (their values are dead).
+// With "--old-tail" the tail uses the main loop's count, the form the kernel had before: the model must then FAIL for
+// some step count (the planted mistake the test suite looks for).
+#include <cstdio>
+#include <cstring>
+#include <vector>
+
+#include "bl_gemm_ring.hpp"
+
+namespace {
+
+constexpr int kMaxSteps = 48;
+
+struct Thread {
+    // one entry per issued operation: the activation tile it brings (>= 0) or -1 for a weight load
+    std::vector<int> issued;
+    int completed = 0;                 // operations [0, completed) have completed
+    std::vector<int> landed_at;        // per tile: index of the barrier after which it is readable, -1 not yet
+    std::vector<bool> done;            // per tile: this thread's part has completed
+    int barriers = 0;
+    void issue(int tile) { issued.push_back(tile); }
+    void wait(int allowed) {           // s_waitcnt vmcnt(allowed)
+        const int must = (int)issued.size() - allowed;
+        for (; completed < must; ++completed)
+            if (issued[completed] >= 0) done[issued[completed]] = true;
+    }
+    void barrier() {
+        ++barriers;
+        for (size_t t = 0; t < done.size(); ++t)
+            if (done[t] && landed_at[t] < 0) landed_at[t] = barriers;
+    }
+};
+
+template <int MB, int H, int WK>
+bool check(int steps, bool drop_tail_weights, bool old_tail, bool verbose) {
+    using R = bl::GemmRing<MB, H, WK>;
+    const int tiles = steps + R::kLead + 1;            // requests run past the end (clamped addresses, never read)
+    Thread t;
+    t.landed_at.assign(tiles, -1);
+    t.done.assign(tiles, false);
+    std::vector<int> last_read_barrier(tiles, -1);     // barriers passed when the tile was last read
+    std::vector<int> stage_tile(R::kStages, -1);
+    bool ok = true;
+    auto fail = [&](const char* what, int step, int tile) {
+        ok = false;
+        if (verbose)
+            std::printf("  <%d,%d,%d> steps=%d drop=%d: %s at step %d, tile %d\n", MB, H, WK, steps, (int)drop_tail_weights, what, step, tile);
+    };
+    auto request = [&](int step, int tile) {
+        const int stage = tile % R::kStages;
+        const int old = stage_tile[stage];
+        if (old >= 0 && last_read_barrier[old] >= t.barriers) fail("stage overwritten before its last read was fenced", step, tile);
+        stage_tile[stage] = tile;
+        for (int g = 0; g < WK; ++g) t.issue(tile);
+    };
+    auto read = [&](int step, int tile) {
+        if (tile >= steps) return;                     // beyond the end: the kernel reads it but never uses it
+        if (t.landed_at[tile] < 0 || t.landed_at[tile] > t.barriers) fail("tile read before it was published", step, tile);
+        last_read_barrier[tile] = t.barriers;
+    };
+    // prologue: weight tiles of steps 0 .. kWR-2, then the requests of tiles 0 .. kLead-1, wait, barrier, first read
+    for (int j = 0; j < R::kWR - 1; ++j)
+        for (int n = 0; n < R::kNT; ++n) t.issue(-1);
+    for (int j = 0; j < R::kLead; ++j) request(-1, j);
+    t.wait(R::kPrologueWait);
+    t.barrier();
+    read(-1, 0);                                       // first half of tile 0
+    const int whole = steps / R::kUnroll * R::kUnroll;
+    for (int i = 0; i < steps; ++i) {
+        const bool tail = i >= whole;
+        request(i, i + R::kLead);
+        read(i, i);                                    // second half of this step's tile
+        if (!(tail && drop_tail_weights))
+            for (int n = 0; n < R::kNT; ++n) t.issue(-1);
+        read(i, i + 1);                                // first half of the next step's tile
+        t.wait(tail && !old_tail ? R::kYoungerTail : R::kYounger);
+        t.barrier();
+    }
+    return ok;
+}
+
+template <int MB, int H, int WK>
+int sweep(bool old_tail, bool verbose) {
+    int bad = 0;
+    for (int steps = 1; steps <= kMaxSteps; ++steps)
+        for (int drop = 0; drop < 2; ++drop)
+            if (!check<MB, H, WK>(steps, drop != 0, old_tail, verbose)) ++bad;
+    return bad;
+}
+
+// decode copy: C copy operations (global -> LDS), then U weight tiles, then vmcnt(LdsCopyWait<U>::kYounger), barrier, reads
+template <int U>
+int copy_check() {
+    int bad = 0;
+    for (int copies = 0; copies <= 8; ++copies) {
+        Thread t;
+        t.landed_at.assign(1, -1);
+        t.done.assign(1, copies == 0);                 // a thread without a share has nothing outstanding
+        for (int c = 0; c < copies; ++c) t.issue(0);
+        for (int u = 0; u < U; ++u) t.issue(-1);
+        t.wait(bl::LdsCopyWait<U>::kYounger);
+        t.barrier();
+        if (t.landed_at[0] != 1) ++bad;
+    }
+    return bad;
+}
+
+}  // namespace
+
+int main(int argc, char** argv) {
+    const bool old_tail = argc > 1 && std::strcmp(argv[1], "--old-tail") == 0;
+    const bool verbose = argc > 2 || (argc > 1 && !old_tail);
+    int bad = 0;
+    // every form launch_gemm / launch_gemm_batch can choose
+    bad += sweep<1, 2, 1>(old_tail, verbose);
+    bad += sweep<1, 4, 1>(old_tail, verbose);
+    bad += sweep<2, 2, 1>(old_tail, verbose);
+    bad += sweep<2, 3, 1>(old_tail, verbose);
+    bad += sweep<2, 4, 1>(old_tail, verbose);
+    bad += sweep<2, 2, 2>(old_tail, verbose);
+    bad += sweep<2, 4, 2>(old_tail, verbose);
+    bad += copy_check<4>() + copy_check<6>();
+    std::printf("%s: %d failing cases\n", old_tail ? "old tail count" : "current counts", bad);
+    return bad == 0 ? 0 : 1;
+}

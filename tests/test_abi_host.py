@@ -93,6 +93,17 @@ def test_argument_validation_happens_before_any_launch():
     bad = B.bl_packed_desc_init(128, 128, 0.5)
     bad.Kp = 192
     assert _st(B.bl_gemm, P, bad, P, P, P, 1, P) == B.BL_ERR_SHAPE
+    # the gated form's packer: both matrices, 2 F rows with F a multiple of 32
+    assert _st(B.bl_pack_gate_up, P, 0, d, P) == B.BL_ERR_NULL
+    assert _st(B.bl_pack_gate_up, P, P, B.bl_packed_desc_init(96, 128, 0.5), P) == B.BL_ERR_SHAPE
+    assert _st(B.bl_pack_gate_up, P, P, d, P + 8) == B.BL_ERR_ALIGN
+    # the static-workspace variant validates like bl_gemv_batch, before it touches the device
+    items = B.make_gemv_items([(P, d, P, P, P, P, 0)])
+    assert B.lib().bl_gemv_batch_static(items, 0, 1, None) == B.BL_ERR_COUNT
+    assert B.lib().bl_gemv_batch_static(items, 1, 9, None) == B.BL_ERR_M_RANGE
+    assert B.lib().bl_gemv_batch_static(None, 1, 1, None) == B.BL_ERR_NULL
+    assert B.lib().bl_gemv_batch_static(B.make_gemv_items([(P, d, P + 4, P, P, P, 0)]), 1, 1, None) == B.BL_ERR_ALIGN
+    assert B.status_str(B.BL_ERR_WORKSPACE) != B.status_str(99)
     # batch count
     items = B.make_gemv_items([(P, d, P, P, P, P, 0)])
     assert B.lib().bl_gemv_batch(items, 0, 1, None, None) == B.BL_ERR_COUNT

@@ -204,7 +204,7 @@ def test_attn_decode_parity(dev, mods, n_heads, head_dim, max_pos, positions):
 
 
 @pytest.mark.parametrize("groups", [1, 2, 3, 5])
-@pytest.mark.parametrize("n_heads,head_dim", [(3, 64), (2, 100), (1, 256), (2, 132), (5, 4)])
+@pytest.mark.parametrize("n_heads,head_dim", [(3, 64), (2, 100), (1, 256), (2, 132), (5, 4), (3, 128), (2, 256)])
 def test_attn_decode_several_chunks_per_workgroup(dev, mods, groups, n_heads, head_dim):
     """A cache longer than the launch has workgroups for: each of a head's `groups` workgroups walks every groups-th
     chunk and folds them into one running maximum, sum and weighted values before the merge.  Positions that put the
@@ -237,6 +237,44 @@ def test_attn_decode_several_chunks_per_workgroup(dev, mods, groups, n_heads, he
             got = out.cpu().numpy()[0]
             assert np.abs(got - want).max() <= 2e-5 * max(1.0, np.abs(want).max()), (pos, float(np.abs(got - want).max()))
             assert not att.scratch[-4 * n_heads:].view(torch.int32).any()
+    finally:
+        B.bl_set_tuning("attn_groups", 0)
+
+
+@pytest.mark.parametrize("pattern", [0x7FC0, 0x7F80, 0xFF80])
+@pytest.mark.parametrize("n_heads,head_dim,groups", [(3, 64, 0), (2, 128, 3), (1, 256, 2)])
+def test_attn_decode_cache_rows_beyond_the_token_may_hold_anything(dev, mods, pattern, n_heads, head_dim, groups):
+    """The caches are the caller's memory and only rows 0 .. pos have ever been written: the rows from `pos` on hold
+    NaN or infinity patterns here (row `pos` too, until this launch appends it).  Outputs must be those of the fp64
+    softmax over rows 0 .. pos, untouched by what lies behind them."""
+    B, dec, ops = mods
+    max_pos, hidden = 200, n_heads * head_dim
+    r = _rng(54000 + hidden + pattern)
+    table = dec.rope_table(head_dim, max_pos, dev)
+    q_t, k_t, v_t = (torch.empty((1, hidden), device=dev) for _ in range(3))
+    pos_t = torch.zeros(1, dtype=torch.int32, device=dev)
+    att = dec.Attention(n_heads, head_dim, max_pos, q_t, k_t, v_t, pos_t, table)
+    kc = _bf16(r.standard_normal((max_pos, hidden)))
+    vc = _bf16(r.standard_normal((max_pos, hidden)))
+    B.bl_set_tuning("attn_groups", groups)
+    try:
+        for pos in (0, 5, 63, 64, 100, 191):
+            kb, vb = synth.to_bf16_bits(kc), synth.to_bf16_bits(vc)
+            kb[pos:], vb[pos:] = pattern, pattern
+            att.k_cache.copy_(_bits_as_bf16_tensor(kb, dev))
+            att.v_cache.copy_(_bits_as_bf16_tensor(vb, dev))
+            ql, kl, vl = (3.0 * r.standard_normal(hidden).astype(np.float32) for _ in range(3))
+            q_t.copy_(_t(ql[None], dev)); k_t.copy_(_t(kl[None], dev)); v_t.copy_(_t(vl[None], dev))
+            pos_t.fill_(pos)
+            out = att.launch()
+            torch.cuda.synchronize()
+            kc64, vc64 = kc[:pos + 1].astype(np.float64), vc[:pos + 1].astype(np.float64)
+            kc64[pos] = att.k_cache[pos].float().cpu().numpy().astype(np.float64)
+            vc64[pos] = att.v_cache[pos].float().cpu().numpy().astype(np.float64)
+            want = D.attention_decode(D.rope(ql, pos, n_heads), kc64, vc64, n_heads)
+            got = out.cpu().numpy()[0]
+            assert np.all(np.isfinite(got)), pos
+            assert np.abs(got - want).max() <= 2e-5 * max(1.0, np.abs(want).max()), (pos, float(np.abs(got - want).max()))
     finally:
         B.bl_set_tuning("attn_groups", 0)
 
@@ -486,6 +524,34 @@ def test_decode_norm_batch_zero_row(dev, mods):
     out = grp.launch()[0]
     torch.cuda.synchronize()
     assert not out.any() and float(grp.quants[0].a_scale[0]) == 0.0 and not grp.quants[0].q.any()
+
+
+@pytest.mark.parametrize("F,K", [(32, 64), (96, 200), (4096, 1536), (224, 3200)])
+def test_pack_gate_up_layout(dev, mods, F, K):
+    """bl_pack_gate_up is bl_pack_ternary of the two matrices interleaved by 32 rows: unpacking gives gate rows
+    32 b .. 32 b + 31 in rows 64 b .. 64 b + 31 and the up rows of the same outputs behind them; non-ternary inputs
+    of either matrix are counted and stored as 0."""
+    B, dec, ops = mods
+    r = _rng(56000 + F + K)
+    wg, wu = synth.ternary_weights(r, F, K), synth.ternary_weights(r, F, K, p_zero=0.5)
+    pw = dec.pack_gate_up(_t(wg, dev), _t(wu, dev), 0.03)
+    back = ops.unpack_ternary(pw).cpu().numpy().reshape(F // 32, 2, 32, K)
+    np.testing.assert_array_equal(back[:, 0].reshape(F, K), wg)
+    np.testing.assert_array_equal(back[:, 1].reshape(F, K), wu)
+    both = np.stack([wg.reshape(F // 32, 32, K), wu.reshape(F // 32, 32, K)], axis=1).reshape(2 * F, K)
+    ref = ops.pack_ternary(_t(both, dev), 0.03)
+    assert torch.equal(ref.blob, pw.blob)
+    wg2, wu2 = wg.copy(), wu.copy()
+    wg2[0, 0], wu2[F - 1, K - 1], wu2[3, 1] = 2, -2, 77
+    bad = torch.zeros(1, dtype=torch.int32, device=dev)
+    desc = B.bl_packed_desc_init(2 * F, K, 0.03)
+    blob = torch.empty(int(desc.bytes), dtype=torch.uint8, device=dev)
+    wg2_d, wu2_d = _t(wg2, dev), _t(wu2, dev)
+    B.bl_pack_gate_up(wg2_d.data_ptr(), wu2_d.data_ptr(), desc, blob.data_ptr(), bad.data_ptr(),
+                      int(torch.cuda.current_stream().cuda_stream))
+    assert int(bad[0]) == 3
+    back = ops.unpack_ternary(ops.PackedWeight(blob, desc)).cpu().numpy().reshape(F // 32, 2, 32, K)
+    assert back[0, 0, 0, 0] == 0 and back[-1, 1, -1, -1] == 0 and back[0, 1, 3, 1] == 0
 
 
 @pytest.mark.parametrize("waves", [4, 8, 16])
