@@ -659,7 +659,7 @@ def extra_ceilings(torch, use_graph):
     lib = ctypes.CDLL(path)
     vp = ctypes.c_void_p
     lib.ceil_mfma_loop.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, vp]
-    lib.ceil_stream_read.argtypes = [vp, ctypes.c_int64, vp, ctypes.c_int, ctypes.c_int, ctypes.c_int, vp]
+    lib.ceil_stream_read.argtypes = [vp, ctypes.c_int64, vp, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, vp]
     dev = torch.device("cuda:0")
     cus = torch.cuda.get_device_properties(dev).multi_processor_count
     sink = torch.zeros(1024, dtype=torch.int32, device=dev)
@@ -687,20 +687,25 @@ def extra_ceilings(torch, use_graph):
                                   ("100B-shape layer", 462422016, 6), ("1 GiB", 1 << 30, 3)):
         nbytes = nbytes // 1024 * 1024
         bufs = [torch.empty(nbytes, dtype=torch.uint8, device=dev).fill_(i + 1) for i in range(copies)]
-        best = None
-        for wgs_per_cu, threads, unroll in ((1, 1024, 8), (2, 1024, 8), (2, 1024, 4), (4, 512, 8), (2, 512, 16), (8, 256, 8)):
-            fns = [(lambda b=b: check(lib.ceil_stream_read(b.data_ptr(), nbytes, sink.data_ptr(), cus * wgs_per_cu, threads,
-                                                           unroll, stream()))) for b in bufs]
-            fns[0]()
-            steps = max(2 * copies, int(2e9 // nbytes))
-            ms, _, _ = run_steps(torch, fns, steps, use_graph)
-            us = ms * 1e3 / steps
-            if best is None or us < best[0]:
-                best = (us, wgs_per_cu, threads, unroll)
-        us, wgs_per_cu, threads, unroll = best
-        res["stream_read"].append({"buffer": label, "bytes": nbytes, "copies_rotated": copies, "us": round(us, 2),
-                                   "GBps": round(nbytes / us / 1e3, 1), "frac_of_published_peak": round(nbytes / us / 1e3 / HBM_PEAK_GBS, 4),
-                                   "launch": "%d workgroups per CU x %d threads, %d loads in flight" % (wgs_per_cu, threads, unroll)})
+        row = {"buffer": label, "bytes": nbytes, "copies_rotated": copies}
+        for loads, flag_sets in (("ordinary_loads", (0, 2)), ("streaming_loads", (1, 3))):
+            best = None
+            for flags in flag_sets:
+                for wgs_per_cu, threads, unroll in ((1, 1024, 8), (2, 1024, 8), (2, 1024, 4), (4, 512, 8), (8, 256, 8), (16, 256, 8)):
+                    fns = [(lambda b=b: check(lib.ceil_stream_read(b.data_ptr(), nbytes, sink.data_ptr(), cus * wgs_per_cu, threads,
+                                                                   unroll, flags, stream()))) for b in bufs]
+                    fns[0]()
+                    steps = max(2 * copies, int(1e9 // nbytes))
+                    ms, _, _ = run_steps(torch, fns, steps, use_graph)
+                    us = ms * 1e3 / steps
+                    if best is None or us < best[0]:
+                        best = (us, wgs_per_cu, threads, unroll, flags)
+            us, wgs_per_cu, threads, unroll, flags = best
+            row[loads] = {"us": round(us, 2), "GBps": round(nbytes / us / 1e3, 1),
+                          "frac_of_published_peak": round(nbytes / us / 1e3 / HBM_PEAK_GBS, 4),
+                          "launch": "%d workgroups per CU x %d threads, %d loads in flight, %s" % (
+                              wgs_per_cu, threads, unroll, "one range per wave" if flags & 2 else "chunks dealt round-robin")}
+        res["stream_read"].append(row)
         del bufs
         torch.cuda.empty_cache()
     return res

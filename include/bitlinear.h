@@ -360,8 +360,11 @@ bl_status bl_tl2_gemv_batch(const bl_gemv_item *items, int32_t count, void *work
  * workspace is given and the launch has at least 8 tiles per workgroup; "decode_path" = 0 automatic
  * (dot-product kernel for M = 1, matrix-core kernel for M >= 2), 1 = always the
  * dot-product kernel, 2 = always the matrix-core kernel; "decode_stage" = 1 keeps the matrix-core kernel
- * from staging the quantized activations in on-chip memory (0 = stage when they fit); "gemm_mb" = wave tile of the prefill kernel as
- * 10*MB + H, i.e. (32*MB) tokens x (32*H) weight rows: 12, 14, 22, 23, 24, or 122 / 124 for the K-split forms of 22 / 24 (0 = automatic);
+ * from staging the quantized activations in on-chip memory (0 = stage when they fit); "gemm_mb" = tile form of the prefill kernel as
+ * 100*(WK-1) + 10*MB + H: wave tile (32*MB) tokens x (32*H) weight rows, WK of the workgroup's four waves along K and the rest
+ * along N.  Forms: 12, 14, 22, 23, 24, 122, 124 (0 = automatic);
+ * "decode_stream" = how the decode kernels load weight tiles: 0 automatic (streaming, i.e. nontemporal, loads for launches of
+ * 4 MiB of packed weights and more; ordinary loads below, so that a small model may stay in the memory-side cache), 1 always streaming, -1 never;
  * "attn_groups" = workgroups per head of bl_attn_decode (0 = automatic, else 1..65535, capped at the cache's chunks) -- the one
  * key that moves results, within that call's tolerance: it decides which chunks are folded together before the merge.
  * Errors: BL_ERR_NULL, BL_ERR_SHAPE (unknown key/value).

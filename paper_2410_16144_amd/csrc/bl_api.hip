@@ -598,8 +598,7 @@ bl_status bl_set_tuning(const char* key, int32_t value) {
         return BL_OK;
     }
     if (strcmp(key, "gemm_mb") == 0) {
-        if (value != 0 && value != 12 && value != 14 && value != 22 && value != 23 && value != 24 && value != 122 && value != 124)
-            return BL_ERR_SHAPE;
+        if (value != 0 && !bl::gemm_form_exists(value)) return BL_ERR_SHAPE;
         bl::set_gemm_mb(value);
         return BL_OK;
     }
@@ -611,6 +610,11 @@ bl_status bl_set_tuning(const char* key, int32_t value) {
     if (strcmp(key, "decode_split") == 0) {
         if (value < -1 || value > 8) return BL_ERR_SHAPE;
         bl::set_decode_split(value);
+        return BL_OK;
+    }
+    if (strcmp(key, "decode_stream") == 0) {
+        if (value < -1 || value > 1) return BL_ERR_SHAPE;
+        bl::set_decode_stream(value);
         return BL_OK;
     }
     if (strcmp(key, "decode_path") == 0) {
@@ -636,7 +640,7 @@ const char* bl_last_kernel(void) {
     char* const end = t_kernel_text + sizeof t_kernel_text - 24;
     int next = 0;
     for (const char* f = n.fmt; *f && out < end; ++f) {
-        if (f[0] == '%' && (f[1] == 'd' || f[1] == 'b') && next < 6) {
+        if (f[0] == '%' && (f[1] == 'd' || f[1] == 'b') && next < 8) {
             const int v = n.v[next++];
             out += f[1] == 'd' ? snprintf(out, 16, "%d", v) : snprintf(out, 16, "%s", v ? "true" : "false");
             ++f;

@@ -16,6 +16,22 @@ constexpr int kWaves = 16;            // waves per workgroup
 constexpr int kThreads = kWaves * kWave;
 constexpr int kInFlight = 8;          // weight tiles a wave keeps in flight
 
+// One lane's 16 bytes of a packed weight tile.  STREAM: a streaming (nontemporal) load -- the decode kernels read every
+// weight byte exactly once per launch, and telling the memory system so is worth 10-15 % of HBM bandwidth on MI355X (a
+// read-only streaming kernel over 462 MB: 6.0 TB/s with ordinary loads, 6.8 TB/s with these).  Not STREAM: an ordinary
+// load, for launches so small that the whole model may live in the 256 MB memory-side cache from token to token
+// (a 700M-shape token loop measured 8 % slower when its weights were streamed past that cache).
+template <bool STREAM>
+__device__ __forceinline__ uint4 load_weight_tile(const uint4* p) {
+    if constexpr (STREAM) {
+        typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+        const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+        return make_uint4(v[0], v[1], v[2], v[3]);
+    } else {
+        return *p;
+    }
+}
+
 template <int M>
 struct Acc {
     int lo[M];  // sums of q * code

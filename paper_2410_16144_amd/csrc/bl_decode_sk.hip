@@ -24,7 +24,8 @@ constexpr int kSumBits = 40;   // low bits of a workspace word that hold the par
 
 // LAYOUT 2: TL2-coded tiles (plain form only).  NORM (fp32 rows only): 1 = RMSNorm folded into the fused quantizer,
 // 2 = the row is already multiplied by its norm weight and sum(x^2) arrives in pieces.
-template <int U, bool FUSED, bool XBF16, int LAYOUT = 1, int NORM = 0>
+// STREAM: weight tiles by streaming (nontemporal) loads, see load_weight_tile.
+template <int U, bool FUSED, bool XBF16, int LAYOUT, int NORM, bool STREAM>
 __global__ __launch_bounds__(kThreads, 8) void decode_sk_kernel(BL_FIRST_WG_PARAMS, const DecodeBatch b) {
     static_assert(LAYOUT == 1 || (LAYOUT == 2 && !FUSED), "the TL2 layout has the plain form only");
     static_assert(NORM == 0 || (FUSED && !XBF16 && LAYOUT == 1), "the norm is folded into the fused quantizer of fp32 rows");
@@ -64,7 +65,7 @@ __global__ __launch_bounds__(kThreads, 8) void decode_sk_kernel(BL_FIRST_WG_PARA
             if (u >= first && u < last) {
                 // beyond the wave's piece: its own last tile again (a cache hit, no extra traffic); a wave without
                 // tiles loads the chunk's first tile
-                w[u] = wp[(int64_t)min(t_wave + i0 + u, t_last) * kWave];
+                w[u] = load_weight_tile<STREAM>(wp + (int64_t)min(t_wave + i0 + u, t_last) * kWave);
             }
         }
     };
@@ -205,16 +206,21 @@ __global__ __launch_bounds__(kThreads, 8) void decode_sk_kernel(BL_FIRST_WG_PARA
     }
 }
 
-template <int U, bool FUSED, bool XBF16, int LAYOUT = 1, int NORM = 0>
-hipError_t launch_sk(const DecodeBatch& b, size_t lds, hipStream_t s) {
-    static LdsCeiling ceiling;
-    auto kernel = &decode_sk_kernel<U, FUSED, XBF16, LAYOUT, NORM>;
-    const hipError_t e = ceiling.ensure(reinterpret_cast<const void*>(kernel));
+template <auto Kernel>
+hipError_t launch_sk_kernel(const DecodeBatch& b, size_t lds, hipStream_t s) {
+    static LdsCeiling ceiling;   // per kernel
+    const hipError_t e = ceiling.ensure(reinterpret_cast<const void*>(Kernel));
     if (e != hipSuccess) return e;
     const FirstWgs first(b);
-    note_kernel("decode_sk_kernel<%d, %b, %b, %d, %d>", b.total_wgs, U, FUSED, XBF16, LAYOUT, NORM);
-    kernel<<<dim3((unsigned)b.total_wgs), dim3(kThreads), lds, s>>>(BL_FIRST_WG_ARGS(first), b);
+    Kernel<<<dim3((unsigned)b.total_wgs), dim3(kThreads), lds, s>>>(BL_FIRST_WG_ARGS(first), b);
     return hipGetLastError();
+}
+
+template <int U, bool FUSED, bool XBF16, int LAYOUT = 1, int NORM = 0>
+hipError_t launch_sk(const DecodeBatch& b, size_t lds, hipStream_t s) {
+    note_kernel("decode_sk_kernel<%d, %b, %b, %d, %d, %b>", b.total_wgs, U, FUSED, XBF16, LAYOUT, NORM, b.stream != 0);
+    return b.stream ? launch_sk_kernel<&decode_sk_kernel<U, FUSED, XBF16, LAYOUT, NORM, true>>(b, lds, s)
+                    : launch_sk_kernel<&decode_sk_kernel<U, FUSED, XBF16, LAYOUT, NORM, false>>(b, lds, s);
 }
 
 int g_split = 0;   // -1 never, 0 automatic, n > 0: n workgroups per compute unit

@@ -5,8 +5,8 @@
 // v_mfma_i32_32x32x32_i8:  D[m][n] += sum_k A[m][k] * B[k][n],  A = int8 activations,
 // B = weight codes (w+1) as int8; sum_k q is subtracted in the epilogue.
 //
-// Tiling.  Workgroup = 4 waves side by side along N = (32*MB) tokens x (128*H) weight rows; each
-// wave owns (32*MB) x (32*H), i.e. MB x H MFMA tiles, H = 2, 3 or 4.  (With H = 3 a wave's 96 rows are one
+// Tiling.  Workgroup = WN x WK waves (4 or 8): WN side by side along N, WK along K; its tile is (32*MB) tokens x
+// (32*H*WN) weight rows; each wave owns (32*MB) x (32*H), i.e. MB x H MFMA tiles, H = 2, 3 or 4.  (With H = 3 a wave's 96 rows are one
 // packed 64-row tile and half of another, which it shares with its neighbour: both load it, each expands
 // its own half.  The form was built for its workgroup count -- where 128-row wave tiles leave the last round of
 // workgroups mostly empty, 96-row tiles fill it -- and measured no faster: the kernel runs at the chip's power
@@ -39,29 +39,43 @@ namespace {
 
 typedef int v16i __attribute__((ext_vector_type(16)));
 
-constexpr int kWaves = 4;         // waves per workgroup
-
 constexpr int kXcds = 8;   // workgroup i runs on accelerator die i % 8, each die with its own L2
 
-// One workgroup's tile of one product: tokens 32*MB*tile_y .. and the weight rows of N position tile_x.
-template <int MB, int H, int WK>
+// Dynamic LDS of one form: the activation ring (reused for the K groups' final exchange), then the workgroup's per-token
+// scales and sums.
+template <int MB, int H, int WK, int WN>
+constexpr int gemm_lds_bytes() {
+    using Ring = GemmRing<MB, H, WK, WN>;
+    const int ring = Ring::kStages * WK * 32 * MB * kTileK;
+    const int exchange = WK == 1 ? 0 : WN * (WK - 1) * (MB * H / WK) * 16 * 64 * 4;
+    return (ring > exchange ? ring : exchange) + 32 * MB * 8;
+}
+
+// One workgroup's tile of one product: tokens 32*MB*tile_y .. and the weight rows of N position tile_x.  WN waves along
+// N, WK along K (the K groups take alternate packed tiles and add their accumulators through LDS at the end).  Eight
+// waves give every SIMD two waves from ONE workgroup: what a launch of few, large tiles needs to keep the matrix cores
+// fed while a wave waits at the step's barrier or for its operands.
+template <int MB, int H, int WK, int WN>
 __device__ __forceinline__ void gemm_tile(const GemmProblem& p, const int M, const int tile_x, const int tile_y) {
-    static_assert(WK == 1 || (WK == 2 && MB % 2 == 0), "K groups exchange halves of the token tile");
+    static_assert(WK == 1 || (MB * H) % WK == 0, "the K groups share out the wave's MFMA tiles for the final sum");
     static_assert(H >= 2 && H <= 4, "32-row blocks per wave");
-    using Ring = GemmRing<MB, H, WK>;     // ring depths and wait counts: bl_gemm_ring.hpp, checked by a host-side model
+    using Ring = GemmRing<MB, H, WK, WN>;   // ring depths and wait counts: bl_gemm_ring.hpp, checked by a host-side model
     constexpr int NT = Ring::kNT;         // packed 64-row tiles a wave loads per step
-    constexpr int WN = kWaves / WK;       // waves along N
+    constexpr int kWaves = WN * WK;
     constexpr int BM = 32 * MB;
     constexpr int kTileBytesA = BM * kTileK;        // unpadded: 64 bytes per token row
     constexpr int kStageBytes = WK * kTileBytesA;   // one activation tile per K group
-    constexpr int kStages = Ring::kStages;          // LDS ring (6 x 8 KiB with two K groups: static LDS ends at 64 KiB)
+    constexpr int kStages = Ring::kStages;          // LDS ring
     constexpr int kLead = Ring::kLead;              // the tile of step i + kLead is requested during step i
-    static_assert(BM <= 64, "one 4 KiB slab per 256 threads");
-    constexpr int kExchangeBytes = WK == 1 ? 0 : WN * (MB / 2) * H * 16 * 64 * 4;   // one direction at a time
-    constexpr int kLdsBytes = kStages * kStageBytes > kExchangeBytes ? kStages * kStageBytes : kExchangeBytes;
-    __shared__ __attribute__((aligned(16))) uint8_t lds[kLdsBytes];
-    __shared__ float s_scale[BM];   // w_scale * a_scale[m] of the workgroup's tokens (read in the epilogue)
-    __shared__ int s_qsum[BM];
+    constexpr int kRQ = Ring::kRQ;                  // global -> LDS loads a loader thread issues per step
+    constexpr int kSlabs = WK * BM / 16;            // 1 KiB pieces of a stage: 16 token rows of one K group, one wave-load each
+    static_assert(BM <= 64, "a K group's tile is at most four slabs");
+    constexpr int kExchangeBytes = WK == 1 ? 0 : WN * (WK - 1) * (MB * H / WK) * 16 * 64 * 4;   // one receiving group at a time
+    constexpr int kRingBytes = kStages * kStageBytes > kExchangeBytes ? kStages * kStageBytes : kExchangeBytes;
+    static_assert(gemm_lds_bytes<MB, H, WK, WN>() == kRingBytes + BM * 8, "the launcher's figure");
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];   // ring (later the exchange area), then the two arrays below
+    float* s_scale = reinterpret_cast<float*>(lds + kRingBytes);    // [BM] w_scale * a_scale[m] of the workgroup's tokens (read in the epilogue)
+    int* s_qsum = reinterpret_cast<int*>(s_scale + BM);            // [BM]
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -76,12 +90,27 @@ __device__ __forceinline__ void gemm_tile(const GemmProblem& p, const int M, con
     const int64_t qs = (int64_t)KC * kTileK;          // activation row stride in bytes
     const uint8_t* qbase = reinterpret_cast<const uint8_t*>(p.q);
 
-    // global -> LDS: thread t fills LDS position t of the tile (16-byte units, row t/4).  Position (row, c') holds the
-    // row's chunk c = c' ^ swizzle(row), swizzle(row) = (row / 2) % 4.
-    const int a_row = tid >> 2;
-    const int a_chunk = (tid & 3) ^ ((a_row >> 1) & 3);
-    const uint8_t* a_src = qbase + (int64_t)min(m0 + a_row, M - 1) * qs + a_chunk * 16;   // clamped rows: never stored
-    const bool a_loader = BM >= 64 || wave < BM / 16;                                      // uniform per wave
+    // global -> LDS: a stage is kSlabs slabs of 1 KiB (16 token rows x 64 bytes of one K group); wave w brings slabs
+    // w, w + kWaves, ...: lane l fills the slab's 16-byte position l (row l / 4).  Position (row, c') holds the row's
+    // chunk c = c' ^ swizzle(row), swizzle(row) = (row / 2) % 4.  A wave brings kRQ slabs or none (uniform).
+    static_assert(kSlabs % kWaves == 0 || kSlabs < kWaves, "every loader wave issues the same number of requests");
+    // (with a slab for every wave the test is a compile-time truth and the K loop has no branch in it: a step is then one
+    // basic block, and the expansion of the next operands stays under the MFMAs where it is scheduled instead of
+    // sinking behind the barrier into the block that uses it)
+    constexpr bool kEveryWaveLoads = kSlabs >= kWaves;
+    const bool a_loader = kEveryWaveLoads || wave < kSlabs;
+    const uint8_t* a_src[kRQ];
+    uint32_t a_dst[kRQ];       // offset inside a stage (wave-uniform)
+    int a_group[kRQ];          // the K group whose tile the slab belongs to (wave-uniform)
+#pragma unroll
+    for (int j = 0; j < kRQ; ++j) {
+        const int slab = (wave + j * kWaves) % kSlabs;                  // (% only keeps the idle waves' arithmetic in range)
+        const int g = slab / (BM / 16), row = (slab % (BM / 16)) * 16 + (lane >> 2);
+        const int chunk = (lane & 3) ^ ((row >> 1) & 3);
+        a_group[j] = g;
+        a_dst[j] = (uint32_t)(g * kTileBytesA + (slab % (BM / 16)) * 1024);
+        a_src[j] = qbase + (int64_t)min(m0 + row, M - 1) * qs + chunk * 16;   // clamped rows: never stored
+    }
     // The request is written as assembly on purpose: the compiler treats a global->LDS load it can see as an
     // access that may complete out of order and answers every later dependency with a wait for ALL outstanding
     // loads, which would undo the prefetching of both operands.  Unseen, the loads still count in vmcnt, in order
@@ -92,10 +121,10 @@ __device__ __forceinline__ void gemm_tile(const GemmProblem& p, const int M, con
         if (a_loader) {
             const int stage = step_i % kStages;
 #pragma unroll
-            for (int g = 0; g < WK; ++g) {
-                const int k = min(step_i * WK + g, KC - 1);   // beyond the end: a valid tile, never used
-                const uint8_t* src = a_src + (int64_t)k * kTileK;
-                const uint32_t dst = lds_base + stage * kStageBytes + g * kTileBytesA + wave * 1024;   // wave-uniform
+            for (int j = 0; j < kRQ; ++j) {
+                const int k = min(step_i * WK + a_group[j], KC - 1);   // beyond the end: a valid tile, never used
+                const uint8_t* src = a_src[j] + (int64_t)k * kTileK;
+                const uint32_t dst = lds_base + stage * kStageBytes + a_dst[j];   // wave-uniform
                 // M0 carries the LDS address of this instruction and of nothing else in this kernel (no other
                 // instruction here reads M0); the compiler warns that it does not track M0 across assembly
 #pragma clang diagnostic push
@@ -256,32 +285,32 @@ __device__ __forceinline__ void gemm_tile(const GemmProblem& p, const int M, con
 #undef BL_TAIL_STEP
 
     __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): the tiles requested beyond the end have landed too
-    if constexpr (WK == 2) {
-        // the two K groups swap halves of the token tile: group g keeps the 32-token blocks mb with mb % 2 == g and
-        // adds the other group's accumulators for them (the staging ring is free now).  One direction at a time, so
-        // that the exchange area is half as large.
+    if constexpr (WK > 1) {
+        // The K groups add up their accumulators through LDS (the staging ring is free now).  MFMA tile t = mb * H + nb
+        // of a wave is FINISHED by group t % WK: one receiving group at a time, the other groups write their partial
+        // sums of its tiles, it adds them; every group ends up with the complete sums of its own share of the tiles.
         int* ex = reinterpret_cast<int*>(lds);
+        constexpr int kShare = MB * H / WK;   // tiles a group finishes
 #pragma unroll
-        for (int dir = 0; dir < 2; ++dir) {   // dir = the K group that receives
+        for (int owner = 0; owner < WK; ++owner) {
             __syncthreads();
-            if (kg != dir) {
+            if (kg != owner) {
+                const int sender = kg < owner ? kg : kg - 1;   // 0 .. WK-2
 #pragma unroll
-                for (int mb = dir; mb < MB; mb += 2)
+                for (int t = owner, i = 0; t < MB * H; t += WK, ++i)
 #pragma unroll
-                    for (int nb = 0; nb < H; ++nb)
-#pragma unroll
-                        for (int r = 0; r < 16; ++r)
-                            ex[(((wave_n * (MB / 2) + mb / 2) * H + nb) * 16 + r) * 64 + lane] = c[mb][nb][r];
+                    for (int r = 0; r < 16; ++r)
+                        ex[((((wave_n * (WK - 1) + sender) * kShare) + i) * 16 + r) * 64 + lane] = c[t / H][t % H][r];
             }
             __syncthreads();
-            if (kg == dir) {
+            if (kg == owner) {
 #pragma unroll
-                for (int mb = dir; mb < MB; mb += 2)
+                for (int sender = 0; sender < WK - 1; ++sender)
 #pragma unroll
-                    for (int nb = 0; nb < H; ++nb)
+                    for (int t = owner, i = 0; t < MB * H; t += WK, ++i)
 #pragma unroll
                         for (int r = 0; r < 16; ++r)
-                            c[mb][nb][r] += ex[(((wave_n * (MB / 2) + mb / 2) * H + nb) * 16 + r) * 64 + lane];
+                            c[t / H][t % H][r] += ex[((((wave_n * (WK - 1) + sender) * kShare) + i) * 16 + r) * 64 + lane];
             }
         }
     }
@@ -289,7 +318,6 @@ __device__ __forceinline__ void gemm_tile(const GemmProblem& p, const int M, con
     // epilogue: register r of a 32x32 tile holds row 8*(r/4) + 4*(lane/32) + r%4, column lane%32
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
-        if (WK == 2 && (mb & 1) != kg) continue;   // the other K group finishes this block
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int ml = mb * 32 + 8 * (r >> 2) + 4 * op_g + (r & 3);
@@ -299,6 +327,7 @@ __device__ __forceinline__ void gemm_tile(const GemmProblem& p, const int M, con
                 const float sc = s_scale[ml];
 #pragma unroll
                 for (int nb = 0; nb < H; ++nb) {
+                    if (WK > 1 && (mb * H + nb) % WK != kg) continue;   // another K group finishes this tile
                     const int n = row0 + nb * 32 + op_row;   // n >= N covers padding rows and clamped row blocks
                     if (n < p.N) {
                         const int v = c[mb][nb][r] - qsum;
@@ -323,11 +352,11 @@ __device__ __forceinline__ bool tile_of_workgroup(int gx, int& tile_x, int& tile
     return tile_x < gx;
 }
 
-template <int MB, int H, int WK>
-__global__ __launch_bounds__(256, 2) void gemm_kernel(const GemmProblem p, const int M, const int gx) {
+template <int MB, int H, int WK, int WN>
+__global__ __launch_bounds__(64 * WN * WK, WN * WK == 4 ? 2 : 1) void gemm_kernel(const GemmProblem p, const int M, const int gx) {
     int tile_x, tile_y;
     if (!tile_of_workgroup(gx, tile_x, tile_y)) return;   // uniform
-    gemm_tile<MB, H, WK>(p, M, tile_x, tile_y);
+    gemm_tile<MB, H, WK, WN>(p, M, tile_x, tile_y);
 }
 
 // Several products over the same M in one launch: their N positions side by side, `end[i]` the first position behind
@@ -337,64 +366,94 @@ struct GemmBatch {
     int32_t     end[kMaxGemmBatch];
 };
 
-template <int MB, int H, int WK>
-__global__ __launch_bounds__(256, 2) void gemm_batch_kernel(const GemmBatch b, const int M, const int gx) {
+template <int MB, int H, int WK, int WN>
+__global__ __launch_bounds__(64 * WN * WK, WN * WK == 4 ? 2 : 1) void gemm_batch_kernel(const GemmBatch b, const int M, const int gx) {
     int tile_x, tile_y;
     if (!tile_of_workgroup(gx, tile_x, tile_y)) return;   // uniform
     int item = 0, first = 0;
 #pragma unroll
     for (int i = 0; i + 1 < kMaxGemmBatch; ++i)
         if (tile_x >= b.end[i]) { item = i + 1; first = b.end[i]; }
-    gemm_tile<MB, H, WK>(b.p[item], M, tile_x - first, tile_y);
+    gemm_tile<MB, H, WK, WN>(b.p[item], M, tile_x - first, tile_y);
 }
 
 int g_force_mb = 0;
 
-// wave tile = (32*MB) tokens x (32*H) weight rows; workgroup = 4 waves, 4/WK along N and WK along K.
+// One tile form: wave tile (32*MB) tokens x (32*H) weight rows, WN waves along N and WK along K.
+struct TileForm { int mb, h, wk, wn; };
+
+// Forced value (bl_set_tuning "gemm_mb"): 100*(WK-1) + 10*MB + H; four waves per workgroup, WN = 4 / WK.
+TileForm form_of_code(int code) {
+    TileForm f;
+    const int waves = 4;
+    f.wk = code / 100 % 10 + 1;
+    f.mb = code / 10 % 10;
+    f.h = code % 10;
+    f.wn = waves / f.wk;
+    return f;
+}
+
 // Choice by workgroup count: 64 x 128 wave tiles (half the LDS traffic per MFMA) when the grid still gives
 // every compute unit two workgroups; 64 x 64 otherwise; and 32 x 64 or the K-split form when even that grid would
-// leave compute units without work.  Forced value: 100*(WK-1) + 10*MB + H.  `rows`: padded weight rows of the launch.
-void choose_tile(int64_t M, int64_t rows, int& mb, int& h, int& wk) {
+// leave compute units without work.  `rows`: padded weight rows of the launch.
+TileForm choose_tile(int64_t M, int64_t rows) {
+    if (g_force_mb) return form_of_code(g_force_mb);
     const int64_t tiles_m = (M + 63) / 64;
     const auto wgs = [&](int wn, int hh) { return tiles_m * ((rows + wn * hh * 32 - 1) / (wn * hh * 32)); };
-    mb = 2; h = 2; wk = 1;
-    if (wgs(4, 4) >= 512) h = 4;
+    TileForm f = {2, 2, 1, 4};
+    if (wgs(4, 4) >= 512) f.h = 4;
     else if (wgs(4, 2) < 256) {
         // too few workgroups either way: 32-token tiles from 128 tokens up (measured 5-8 % ahead of the K split on
         // shapes from 1536^2 to 8192^2), the K split below
-        if (M >= 128) mb = 1;
-        else wk = 2;
+        if (M >= 128) f.mb = 1;
+        else { f.wk = 2; f.wn = 2; }
     }
-    if (g_force_mb) { wk = g_force_mb / 100 + 1; mb = g_force_mb / 10 % 10; h = g_force_mb % 10; }
+    return f;
 }
+
+// One LdsCeiling per kernel: the larger forms need more than the 64 KiB a kernel gets without asking.
+template <typename Kernel, typename Arg>
+hipError_t launch_form(Kernel kernel, size_t lds_bytes, int threads, unsigned grid, const Arg& arg, int M, int gx, hipStream_t s) {
+    static LdsCeiling ceiling;   // per instantiation of this template, i.e. per kernel
+    const hipError_t e = ceiling.ensure(reinterpret_cast<const void*>(kernel));
+    if (e != hipSuccess) return e;
+    kernel<<<dim3(grid), dim3((unsigned)threads), lds_bytes, s>>>(arg, M, gx);
+    return hipGetLastError();
+}
+
+// The forms that are built.  Eight-wave workgroups (8 waves along N; 4 x 2 and 2 x 4 along N x K) were built on the same
+// tile code, were bit-exact, and measured equal or slower on every benchmark shape (e.g. M = 512, K = 11008 -> N = 4096:
+// 29.9 us with 2 x 4 waves against 30.1 us; M = 2048: 77 to 112 us against 75 us), so they are not instantiated.
+#define BL_GEMM_FORMS(X) \
+    X(1, 2, 1, 4) X(1, 4, 1, 4) X(2, 2, 1, 4) X(2, 3, 1, 4) X(2, 4, 1, 4) X(2, 2, 2, 2) X(2, 4, 2, 2)
 
 }  // namespace
 
 void set_gemm_mb(int mb) { g_force_mb = mb; }
 
+bool gemm_form_exists(int code) {
+    const TileForm f = form_of_code(code);
+#define X(MB, H, WK, WN) if (f.mb == MB && f.h == H && f.wk == WK && f.wn == WN) return true;
+    BL_GEMM_FORMS(X)
+#undef X
+    return false;
+}
+
 hipError_t launch_gemm(const GemmProblem& p, int64_t M, hipStream_t s) {
     const int64_t rows = (int64_t)p.row_blocks * kTileN;
-    int mb, h, wk;
-    choose_tile(M, rows, mb, h, wk);
-    const int wn = kWaves / wk;
-    const int64_t gx = (rows + wn * h * 32 - 1) / (wn * h * 32);
-    const int64_t gy = (M + 32 * mb - 1) / (32 * mb);
+    const TileForm f = choose_tile(M, rows);
+    const int64_t gx = (rows + f.wn * f.h * 32 - 1) / (f.wn * f.h * 32);
+    const int64_t gy = (M + 32 * f.mb - 1) / (32 * f.mb);
     const int64_t wgs_total = (gx + kXcds - 1) / kXcds * kXcds * gy;
     if (wgs_total > INT32_MAX) return hipErrorInvalidValue;
-    const dim3 grid((unsigned)wgs_total), block(256);
-    const int igx = (int)gx;
-    note_kernel("gemm_kernel<%d, %d, %d>", (int)wgs_total, mb, h, wk);
-    switch (100 * (wk - 1) + 10 * mb + h) {
-        case 12: gemm_kernel<1, 2, 1><<<grid, block, 0, s>>>(p, (int)M, igx); break;
-        case 14: gemm_kernel<1, 4, 1><<<grid, block, 0, s>>>(p, (int)M, igx); break;
-        case 22: gemm_kernel<2, 2, 1><<<grid, block, 0, s>>>(p, (int)M, igx); break;
-        case 23: gemm_kernel<2, 3, 1><<<grid, block, 0, s>>>(p, (int)M, igx); break;
-        case 24: gemm_kernel<2, 4, 1><<<grid, block, 0, s>>>(p, (int)M, igx); break;
-        case 122: gemm_kernel<2, 2, 2><<<grid, block, 0, s>>>(p, (int)M, igx); break;
-        case 124: gemm_kernel<2, 4, 2><<<grid, block, 0, s>>>(p, (int)M, igx); break;
-        default: return hipErrorInvalidValue;
-    }
-    return hipGetLastError();
+    note_kernel("gemm_kernel<%d, %d, %d, %d>", (int)wgs_total, f.mb, f.h, f.wk, f.wn);
+#define X(MB, H, WK, WN)                                                                                                 \
+    if (f.mb == MB && f.h == H && f.wk == WK && f.wn == WN)                                                              \
+        return launch_form(&gemm_kernel<MB, H, WK, WN>, gemm_lds_bytes<MB, H, WK, WN>(), 64 * WN * WK, (unsigned)wgs_total, p, \
+                           (int)M, (int)gx, s);
+    BL_GEMM_FORMS(X)
+#undef X
+    return hipErrorInvalidValue;
 }
 
 hipError_t launch_gemm_batch(const GemmProblem* ps, int count, int64_t M, hipStream_t s) {
@@ -402,33 +461,25 @@ hipError_t launch_gemm_batch(const GemmProblem* ps, int count, int64_t M, hipStr
     if (count < 1 || count > kMaxGemmBatch) return hipErrorInvalidValue;
     int64_t rows = 0;
     for (int i = 0; i < count; ++i) rows += (int64_t)ps[i].row_blocks * kTileN;
-    int mb, h, wk;
-    choose_tile(M, rows, mb, h, wk);
-    const int wn = kWaves / wk;
+    const TileForm f = choose_tile(M, rows);
     GemmBatch b;
     int64_t gx = 0;
     for (int i = 0; i < kMaxGemmBatch; ++i) {
         b.p[i] = ps[i < count ? i : count - 1];
-        if (i < count) gx += ((int64_t)ps[i].row_blocks * kTileN + wn * h * 32 - 1) / (wn * h * 32);
+        if (i < count) gx += ((int64_t)ps[i].row_blocks * kTileN + f.wn * f.h * 32 - 1) / (f.wn * f.h * 32);
         b.end[i] = i + 1 < count ? (int32_t)gx : INT32_MAX;
     }
-    const int64_t gy = (M + 32 * mb - 1) / (32 * mb);
+    const int64_t gy = (M + 32 * f.mb - 1) / (32 * f.mb);
     const int64_t wgs_total = (gx + kXcds - 1) / kXcds * kXcds * gy;
     if (wgs_total > INT32_MAX) return hipErrorInvalidValue;
-    const dim3 grid((unsigned)wgs_total), block(256);
-    const int igx = (int)gx;
-    note_kernel("gemm_batch_kernel<%d, %d, %d>", (int)wgs_total, mb, h, wk);
-    switch (100 * (wk - 1) + 10 * mb + h) {
-        case 12: gemm_batch_kernel<1, 2, 1><<<grid, block, 0, s>>>(b, (int)M, igx); break;
-        case 14: gemm_batch_kernel<1, 4, 1><<<grid, block, 0, s>>>(b, (int)M, igx); break;
-        case 22: gemm_batch_kernel<2, 2, 1><<<grid, block, 0, s>>>(b, (int)M, igx); break;
-        case 23: gemm_batch_kernel<2, 3, 1><<<grid, block, 0, s>>>(b, (int)M, igx); break;
-        case 24: gemm_batch_kernel<2, 4, 1><<<grid, block, 0, s>>>(b, (int)M, igx); break;
-        case 122: gemm_batch_kernel<2, 2, 2><<<grid, block, 0, s>>>(b, (int)M, igx); break;
-        case 124: gemm_batch_kernel<2, 4, 2><<<grid, block, 0, s>>>(b, (int)M, igx); break;
-        default: return hipErrorInvalidValue;
-    }
-    return hipGetLastError();
+    note_kernel("gemm_batch_kernel<%d, %d, %d, %d>", (int)wgs_total, f.mb, f.h, f.wk, f.wn);
+#define X(MB, H, WK, WN)                                                                                                 \
+    if (f.mb == MB && f.h == H && f.wk == WK && f.wn == WN)                                                              \
+        return launch_form(&gemm_batch_kernel<MB, H, WK, WN>, gemm_lds_bytes<MB, H, WK, WN>(), 64 * WN * WK, (unsigned)wgs_total, b, \
+                           (int)M, (int)gx, s);
+    BL_GEMM_FORMS(X)
+#undef X
+    return hipErrorInvalidValue;
 }
 
 }  // namespace bl

@@ -30,7 +30,8 @@ namespace {
 // form): same streaming structure, tl2_tile_mac instead of tile_mac, no sum(q) correction.
 // NORM (one token, fp32 rows): 1 = RMSNorm folded into the fused quantizer, 2 = the row is already multiplied by its norm
 // weight and sum(x^2) arrives in pieces.  GLU: gated epilogue (see DecodeProblem).
-template <int M, bool FUSED, bool XBF16, int LAYOUT = 1, int NORM = 0, bool GLU = false>
+// STREAM: weight tiles by streaming (nontemporal) loads, see load_weight_tile.
+template <int M, bool FUSED, bool XBF16, int LAYOUT, int NORM, bool GLU, bool STREAM>
 __global__ __launch_bounds__(kThreads, 8) void decode_kernel(BL_FIRST_WG_PARAMS, const DecodeBatch b) {
     static_assert(NORM == 0 || (M == 1 && FUSED && !XBF16 && LAYOUT == 1), "the norm is folded into the one-token fused quantizer of fp32 rows");
     static_assert(!GLU || (M == 1 && LAYOUT == 1), "the gated epilogue is for one token");
@@ -53,6 +54,8 @@ __global__ __launch_bounds__(kThreads, 8) void decode_kernel(BL_FIRST_WG_PARAMS,
     const bool active = rb < p.row_blocks;
     const int KC = p.KC;
     const int Kp = KC * kTileK;
+    // (the K tiles of a row block are dealt round-robin, so that the group's loads in flight cover one contiguous window
+    // of memory; cutting them into one contiguous piece per wave instead measured 20 % SLOWER on 100B-shape layers)
     const uint4* __restrict__ wp = p.packed + (int64_t)(active ? rb : 0) * KC * kWave + lane;
 
     // LDS carve-up: [quantized activations (fused only)] [partial sums] [small per-token scalars]
@@ -69,7 +72,7 @@ __global__ __launch_bounds__(kThreads, 8) void decode_kernel(BL_FIRST_WG_PARAMS,
         for (int u = 0; u < kInFlight; ++u) {
             if (u >= first && u < last) {
                 const int k = kc0 + u * G;
-                w[u] = wp[(int64_t)(k < KC ? k : KC - 1) * kWave];   // clamped: always a valid tile
+                w[u] = load_weight_tile<STREAM>(wp + (int64_t)(k < KC ? k : KC - 1) * kWave);   // clamped: always a valid tile
             }
         }
     };
@@ -223,7 +226,7 @@ constexpr int kMfmaRedBytes = kWaves * 16 * 32 * 4;   // per wave: 16 accumulato
 //   0 = straight from global memory, prefetched with the weight tiles (any size)
 //   1 = copied once per workgroup from global memory into LDS (when M*Kp fits)
 //   2 = quantized by the workgroup into LDS (fused form)
-template <int M, int QMODE, bool XBF16>
+template <int M, int QMODE, bool XBF16, bool STREAM>
 __global__ __launch_bounds__(kThreads, 8) void decode_mfma_kernel(BL_FIRST_WG_PARAMS, const DecodeBatch b) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     constexpr bool kLdsQ = QMODE != 0;
@@ -264,7 +267,7 @@ __global__ __launch_bounds__(kThreads, 8) void decode_mfma_kernel(BL_FIRST_WG_PA
         for (int u = 0; u < U; ++u) {
             const int k = kc0 + u * G;
             const int kk = k < KC ? k : KC - 1;   // clamped: always a valid tile
-            w[u] = wp[(int64_t)kk * kWave];
+            w[u] = load_weight_tile<STREAM>(wp + (int64_t)kk * kWave);
             if constexpr (!kLdsQ) {
                 av[u] = v4i{0, 0, 0, 0};
                 if (has_row) av[u] = *reinterpret_cast<const v4i*>(reinterpret_cast<const int8_t*>(p.q) + a_off + kk * kTileK);
@@ -365,26 +368,40 @@ __global__ __launch_bounds__(kThreads, 8) void decode_mfma_kernel(BL_FIRST_WG_PA
     }
 }
 
-template <typename Kernel>
-hipError_t launch_kernel(Kernel kernel, LdsCeiling& ceiling, const DecodeBatch& b, size_t lds_bytes, hipStream_t s) {
-    const hipError_t e = ceiling.ensure(reinterpret_cast<const void*>(kernel));
+// One launch of one kernel (a template argument, so that every kernel has its own LdsCeiling).
+template <auto Kernel>
+hipError_t launch_kernel(const DecodeBatch& b, size_t lds_bytes, hipStream_t s) {
+    static LdsCeiling ceiling;
+    const hipError_t e = ceiling.ensure(reinterpret_cast<const void*>(Kernel));
     if (e != hipSuccess) return e;
     const FirstWgs first(b);
-    kernel<<<dim3((unsigned)b.total_wgs), dim3(kThreads), lds_bytes, s>>>(BL_FIRST_WG_ARGS(first), b);
+    Kernel<<<dim3((unsigned)b.total_wgs), dim3(kThreads), lds_bytes, s>>>(BL_FIRST_WG_ARGS(first), b);
     return hipGetLastError();
+}
+
+// decode_kernel by its template arguments, with the note for bl_last_kernel; the streaming form by b.stream
+template <int M, bool FUSED, bool XBF16, int LAYOUT = 1, int NORM = 0, bool GLU = false>
+hipError_t launch_dot(const DecodeBatch& b, size_t lds_bytes, hipStream_t s) {
+    note_kernel("decode_kernel<%d, %b, %b, %d, %d, %b, %b>", b.total_wgs, M, FUSED, XBF16, LAYOUT, NORM, GLU, b.stream != 0);
+    return b.stream ? launch_kernel<&decode_kernel<M, FUSED, XBF16, LAYOUT, NORM, GLU, true>>(b, lds_bytes, s)
+                    : launch_kernel<&decode_kernel<M, FUSED, XBF16, LAYOUT, NORM, GLU, false>>(b, lds_bytes, s);
+}
+
+template <int M, int QMODE, bool XBF16>
+hipError_t launch_mfma(const DecodeBatch& b, size_t lds_bytes, hipStream_t s) {
+    note_kernel("decode_mfma_kernel<%d, %d, %b, %b>", b.total_wgs, M, QMODE, XBF16, b.stream != 0);
+    return b.stream ? launch_kernel<&decode_mfma_kernel<M, QMODE, XBF16, true>>(b, lds_bytes, s)
+                    : launch_kernel<&decode_mfma_kernel<M, QMODE, XBF16, false>>(b, lds_bytes, s);
 }
 
 // KIND: 0 = dot-product kernel, plain; 1 = dot-product kernel, fused; 2..4 = matrix-core kernel with QMODE 0..2
 template <int M, int KIND, bool XBF16>
 hipError_t launch_one(const DecodeBatch& b, size_t lds_bytes, hipStream_t s) {
-    static LdsCeiling attr_set;   // one per instantiation, i.e. per kernel
-    if constexpr (KIND <= 1) note_kernel("decode_kernel<%d, %b, %b, 1, 0, false>", b.total_wgs, M, KIND, KIND == 0 || XBF16);
-    else note_kernel("decode_mfma_kernel<%d, %d, %b>", b.total_wgs, M, KIND - 2, KIND != 4 || XBF16);
-    if constexpr (KIND == 0) return launch_kernel(&decode_kernel<M, false, true>, attr_set, b, lds_bytes, s);
-    else if constexpr (KIND == 1) return launch_kernel(&decode_kernel<M, true, XBF16>, attr_set, b, lds_bytes, s);
-    else if constexpr (KIND == 2) return launch_kernel(&decode_mfma_kernel<M, 0, true>, attr_set, b, lds_bytes, s);
-    else if constexpr (KIND == 3) return launch_kernel(&decode_mfma_kernel<M, 1, true>, attr_set, b, lds_bytes, s);
-    else return launch_kernel(&decode_mfma_kernel<M, 2, XBF16>, attr_set, b, lds_bytes, s);
+    if constexpr (KIND == 0) return launch_dot<M, false, true>(b, lds_bytes, s);
+    else if constexpr (KIND == 1) return launch_dot<M, true, XBF16>(b, lds_bytes, s);
+    else if constexpr (KIND == 2) return launch_mfma<M, 0, true>(b, lds_bytes, s);
+    else if constexpr (KIND == 3) return launch_mfma<M, 1, true>(b, lds_bytes, s);
+    else return launch_mfma<M, 2, XBF16>(b, lds_bytes, s);
 }
 
 template <int KIND, bool XBF16>
@@ -405,6 +422,20 @@ hipError_t launch_m(const DecodeBatch& b, int M, size_t lds, hipStream_t s) {
 int g_force_waves = 0;
 int g_force_path = 0;   // 0 auto, 1 dot4, 2 mfma
 int g_force_stage = 0;  // 1: never stage the activations in LDS (matrix-core kernel, plain form)
+int g_force_stream = 0; // weight tiles by streaming loads: 0 automatic, 1 always, -1 never
+
+// Launches whose weights could not stay in the 256 MB memory-side cache anyway stream them (nontemporal loads); small
+// launches, as the token loops of the smallest models make them, use ordinary loads so that the model may stay cached
+// from token to token.  The launch's packed bytes are all the library knows of the model's size: 4 MiB is the line
+// (every launch of the Appendix-A models up to 1B, 233 MB of packed weights in all, lies below it; every launch of
+// the models from 2.5B up, whose weights do not fit that cache, above).
+constexpr int64_t kStreamBytes = 4 << 20;
+bool want_stream(const DecodeBatch& b) {
+    if (g_force_stream) return g_force_stream > 0;
+    int64_t tiles = 0;
+    for (int i = 0; i < b.count; ++i) tiles += (int64_t)b.p[i].row_blocks * b.p[i].KC;
+    return tiles * kTileBytes >= kStreamBytes;
+}
 
 bool use_mfma(int M) { return g_force_path ? g_force_path == 2 : M >= 2; }
 
@@ -413,6 +444,7 @@ bool use_mfma(int M) { return g_force_path ? g_force_path == 2 : M >= 2; }
 void set_gemv_waves(int waves) { g_force_waves = waves; }
 void set_decode_path(int path) { g_force_path = path; }
 void set_decode_stage(int v) { g_force_stage = v; }
+void set_decode_stream(int v) { g_force_stream = v; }
 
 // LDS bytes of one launch; q_in_lds: the quantized activations live in LDS (fused, or staged copy)
 static size_t lds_bytes_for(int M, int64_t max_Kp, bool q_in_lds) {
@@ -486,14 +518,13 @@ static void plan_decode(DecodeBatch& b, int tiles_per_wave) {
 
 hipError_t launch_decode(const DecodeBatch& batch, int M, bool fused, hipStream_t s) {
     DecodeBatch b = batch;
+    b.stream = want_stream(b);
     if (b.layout == 2) {   // TL2-coded tiles: one token, plain form, dot-product kernels only
         if (M != 1 || fused) return hipErrorInvalidValue;
         int tiles_per_wave = 0;
         if (plan_decode_split(b, false, tiles_per_wave)) return launch_decode_split(b, tiles_per_wave, false, s);
         plan_decode(b, kInFlight);
-        static LdsCeiling ceiling;
-        note_kernel("decode_kernel<1, false, true, 2, 0, false>", b.total_wgs);
-        return launch_kernel(&decode_kernel<1, false, true, 2>, ceiling, b, lds_bytes_for(1, 0, false), s);
+        return launch_dot<1, false, true, 2>(b, lds_bytes_for(1, 0, false), s);
     }
     int64_t max_Kp = 0;
     for (int i = 0; i < b.count; ++i) max_Kp = (int64_t)b.p[i].KC * kTileK > max_Kp ? (int64_t)b.p[i].KC * kTileK : max_Kp;
@@ -523,20 +554,12 @@ hipError_t launch_decode(const DecodeBatch& batch, int M, bool fused, hipStream_
     if (!fused) return launch_m<0, true>(b, M, lds, s);
     if (b.p[0].gamma) {   // RMSNorm folded into the quantizer: one token, fp32 rows (checked by the entry point)
         if (M != 1 || bf16) return hipErrorInvalidValue;
-        if (b.p[0].glu_gamma) {
-            static LdsCeiling ceiling;
-            note_kernel("decode_kernel<1, true, false, 1, 1, true>", b.total_wgs);
-            return launch_kernel(&decode_kernel<1, true, false, 1, 1, true>, ceiling, b, lds, s);
-        }
-        static LdsCeiling ceiling;
-        note_kernel("decode_kernel<1, true, false, 1, 1, false>", b.total_wgs);
-        return launch_kernel(&decode_kernel<1, true, false, 1, 1>, ceiling, b, lds, s);
+        if (b.p[0].glu_gamma) return launch_dot<1, true, false, 1, 1, true>(b, lds, s);
+        return launch_dot<1, true, false, 1, 1>(b, lds, s);
     }
     if (b.p[0].ss_in) {   // the row is already multiplied by its norm weight; sum(x^2) in pieces
         if (M != 1 || bf16) return hipErrorInvalidValue;
-        static LdsCeiling ceiling;
-        note_kernel("decode_kernel<1, true, false, 1, 2, false>", b.total_wgs);
-        return launch_kernel(&decode_kernel<1, true, false, 1, 2>, ceiling, b, lds, s);
+        return launch_dot<1, true, false, 1, 2>(b, lds, s);
     }
     return bf16 ? launch_m<1, true>(b, M, lds, s) : launch_m<1, false>(b, M, lds, s);
 }

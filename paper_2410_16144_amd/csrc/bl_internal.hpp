@@ -81,6 +81,7 @@ struct DecodeBatch {
     int32_t       total_wgs;
     unsigned long long* ws;      // balanced form: the caller's workspace (zero between launches), or null
     int32_t       layout;        // 1: 2-bit tiles of 64 k; 2: TL2 codes, tiles of 72 k (one token, plain form only)
+    int32_t       stream;        // host side only: weight tiles by streaming (nontemporal) loads; set by launch_decode
 };
 
 // Which problem of the launch a workgroup belongs to.  The first workgroup of problems 1..7 (INT32_MAX beyond the
@@ -163,25 +164,28 @@ hipError_t launch_attn_prefill(const ::bl_attn_prefill_args& a, hipStream_t s);
 // The calling thread's most recent product launch: kernel template instance and grid, for tools that label what they
 // time (bl_last_kernel).  Only the pieces are stored at launch time; the text is formatted on request.
 struct KernelNote {
-    const char* fmt = nullptr;   // printf format over v[0..5]
-    int v[6] = {0, 0, 0, 0, 0, 0};
+    const char* fmt = nullptr;   // format over v[]: %d a number, %b true / false
+    int v[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     int grid = 0;
 };
 extern thread_local KernelNote t_kernel_note;
-inline void note_kernel(const char* fmt, int grid, int a = 0, int b = 0, int c = 0, int d = 0, int e = 0, int f = 0) {
+inline void note_kernel(const char* fmt, int grid, int a = 0, int b = 0, int c = 0, int d = 0, int e = 0, int f = 0, int g = 0,
+                        int h = 0) {
     t_kernel_note.fmt = fmt;
     t_kernel_note.grid = grid;
-    t_kernel_note.v[0] = a; t_kernel_note.v[1] = b; t_kernel_note.v[2] = c;
-    t_kernel_note.v[3] = d; t_kernel_note.v[4] = e; t_kernel_note.v[5] = f;
+    const int v[8] = {a, b, c, d, e, f, g, h};
+    for (int i = 0; i < 8; ++i) t_kernel_note.v[i] = v[i];
 }
 
 // Launch-shape overrides for experiments (0 = choose automatically).
 void set_gemv_waves(int waves);
 void set_attn_groups(int groups);   // bl_attn_decode's workgroups per head; 0 automatic
-void set_gemm_mb(int mb);         // 0 automatic, else 100*(WK-1) + 10*MB + NB (see launch_gemm)
+void set_gemm_mb(int mb);         // 0 automatic, else 1000*W + 100*(WK-1) + 10*MB + H (see bl_gemm.hip)
+bool gemm_form_exists(int code);  // whether that code names a tile form the library has
 void set_decode_stage(int v);     // 1: the matrix-core decode kernel never stages activations in LDS
 void set_decode_split(int v);     // -1 never split row blocks over workgroups, 0 automatic, n: n workgroups per compute unit
 void set_decode_path(int path);   // 0 automatic, 1 dot-product kernel, 2 matrix-core kernel
+void set_decode_stream(int v);    // weight tiles by streaming loads: 0 automatic (by the launch's packed bytes), 1 always, -1 never
 int64_t split_launches();         // work-balanced decode launches so far (host-side count)
 
 }  // namespace bl

@@ -6,7 +6,8 @@
 //                     optionally with the prefill kernel's in-register expansion of 2-bit codes between the MFMAs.
 //   ceil_stream_read  how fast can a kernel read N bytes from HBM once, with 128-bit loads and nothing to compute?
 //                     Every wave walks 1 KiB chunks (64 lanes x 16 bytes, the decode kernels' load shape), U loads in
-//                     flight, and folds what it reads into one register so that the loads cannot be dropped.
+//                     flight, and folds what it reads into one register so that the loads cannot be dropped; with
+//                     ordinary or streaming (nontemporal) loads, chunks dealt round-robin or in one range per wave.
 //
 // Both take a stream and return the hipError_t of the launch; timing is the caller's (events around graph replays).
 #include <hip/hip_runtime.h>
@@ -56,23 +57,46 @@ __global__ __launch_bounds__(256) void mfma_loop_kernel(int iters, int* out) {
     if (s == 0x7fffffff) out[threadIdx.x] = s;   // keeps the loop alive; practically never true
 }
 
-template <int U>
+// NT: streaming (nontemporal) loads.  RANGES: every wave reads one contiguous range of chunks instead of every
+// (number of waves)-th chunk.
+template <int U, bool NT, bool RANGES>
 __global__ __launch_bounds__(1024) void stream_read_kernel(const uint4* __restrict__ src, int64_t chunks, uint32_t* out) {
     const int lane = threadIdx.x & 63;
     const int64_t wave = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
     const int64_t waves = (int64_t)gridDim.x * (blockDim.x >> 6);
+    const int64_t per = (chunks + waves - 1) / waves;
+    const int64_t first = RANGES ? wave * per : wave, step = RANGES ? 1 : waves;
+    const int64_t end = RANGES ? (first + per < chunks ? first + per : chunks) : chunks;
     uint32_t fold = 0;
-    for (int64_t c = wave; c < chunks; c += waves * U) {
+    for (int64_t c = first; c < end; c += step * U) {
         uint4 v[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int64_t cc = c + u * waves;
-            v[u] = src[(cc < chunks ? cc : chunks - 1) * 64 + lane];   // beyond the end: the last chunk again (a cache hit)
+            const int64_t cc = c + u * step;
+            const uint4* p = src + (cc < end ? cc : end - 1) * 64 + lane;   // beyond the end: the last chunk again (a cache hit)
+            if constexpr (NT) {
+                typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+                const u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+                v[u] = make_uint4(t[0], t[1], t[2], t[3]);
+            } else {
+                v[u] = *p;
+            }
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) fold ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
     }
     if (fold == 0x12345678u) out[(wave * 64 + lane) & 1023] = fold;   // practically never: no store traffic
+}
+
+template <int U>
+hipError_t launch_read(const uint4* src, int64_t chunks, uint32_t* out, int wgs, int threads, int flags, hipStream_t s) {
+    switch (flags & 3) {
+        case 0: stream_read_kernel<U, false, false><<<wgs, threads, 0, s>>>(src, chunks, out); break;
+        case 1: stream_read_kernel<U, true, false><<<wgs, threads, 0, s>>>(src, chunks, out); break;
+        case 2: stream_read_kernel<U, false, true><<<wgs, threads, 0, s>>>(src, chunks, out); break;
+        default: stream_read_kernel<U, true, true><<<wgs, threads, 0, s>>>(src, chunks, out); break;
+    }
+    return hipGetLastError();
 }
 
 }  // namespace
@@ -90,23 +114,22 @@ int ceil_mfma_loop(int expand, int blocks, int iters, void* out_dev, void* strea
     return (int)hipGetLastError();
 }
 
-// Reads `bytes` (a multiple of 1024, 16-byte aligned) once.  threads: multiple of 64 up to 1024; unroll: 4, 8 or 16.
-// out_dev: at least 1024 words.
-int ceil_stream_read(const void* src_dev, int64_t bytes, void* out_dev, int wgs, int threads, int unroll, void* stream) {
+// Reads `bytes` (a multiple of 1024, 16-byte aligned) once.  threads: multiple of 64 up to 1024; unroll: 4, 8 or 16;
+// flags: bit 0 = streaming (nontemporal) loads, bit 1 = one contiguous range per wave.  out_dev: at least 1024 words.
+int ceil_stream_read(const void* src_dev, int64_t bytes, void* out_dev, int wgs, int threads, int unroll, int flags, void* stream) {
     if (!src_dev || !out_dev || bytes < 1024 || bytes % 1024 != 0 || wgs < 1 || threads < 64 || threads > 1024 ||
-        threads % 64 != 0 || (reinterpret_cast<uintptr_t>(src_dev) & 15) != 0)
+        threads % 64 != 0 || (reinterpret_cast<uintptr_t>(src_dev) & 15) != 0 || flags < 0 || flags > 3)
         return (int)hipErrorInvalidValue;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const uint4* src = static_cast<const uint4*>(src_dev);
     uint32_t* out = static_cast<uint32_t*>(out_dev);
     const int64_t chunks = bytes / 1024;
     switch (unroll) {
-        case 4: stream_read_kernel<4><<<wgs, threads, 0, s>>>(src, chunks, out); break;
-        case 8: stream_read_kernel<8><<<wgs, threads, 0, s>>>(src, chunks, out); break;
-        case 16: stream_read_kernel<16><<<wgs, threads, 0, s>>>(src, chunks, out); break;
+        case 4: return (int)launch_read<4>(src, chunks, out, wgs, threads, flags, s);
+        case 8: return (int)launch_read<8>(src, chunks, out, wgs, threads, flags, s);
+        case 16: return (int)launch_read<16>(src, chunks, out, wgs, threads, flags, s);
         default: return (int)hipErrorInvalidValue;
     }
-    return (int)hipGetLastError();
 }
 
 }  // extern "C"

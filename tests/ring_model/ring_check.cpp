@@ -44,9 +44,9 @@ struct Thread {
     }
 };
 
-template <int MB, int H, int WK>
+template <int MB, int H, int WK, int WN>
 bool check(int steps, bool drop_tail_weights, bool old_tail, bool verbose) {
-    using R = bl::GemmRing<MB, H, WK>;
+    using R = bl::GemmRing<MB, H, WK, WN>;
     const int tiles = steps + R::kLead + 1;            // requests run past the end (clamped addresses, never read)
     Thread t;
     t.landed_at.assign(tiles, -1);
@@ -57,14 +57,14 @@ bool check(int steps, bool drop_tail_weights, bool old_tail, bool verbose) {
     auto fail = [&](const char* what, int step, int tile) {
         ok = false;
         if (verbose)
-            std::printf("  <%d,%d,%d> steps=%d drop=%d: %s at step %d, tile %d\n", MB, H, WK, steps, (int)drop_tail_weights, what, step, tile);
+            std::printf("  <%d,%d,%d,%d> steps=%d drop=%d: %s at step %d, tile %d\n", MB, H, WK, WN, steps, (int)drop_tail_weights, what, step, tile);
     };
     auto request = [&](int step, int tile) {
         const int stage = tile % R::kStages;
         const int old = stage_tile[stage];
         if (old >= 0 && last_read_barrier[old] >= t.barriers) fail("stage overwritten before its last read was fenced", step, tile);
         stage_tile[stage] = tile;
-        for (int g = 0; g < WK; ++g) t.issue(tile);
+        for (int g = 0; g < R::kRQ; ++g) t.issue(tile);   // a loader wave's thread: kRQ slabs of the stage
     };
     auto read = [&](int step, int tile) {
         if (tile >= steps) return;                     // beyond the end: the kernel reads it but never uses it
@@ -92,12 +92,12 @@ bool check(int steps, bool drop_tail_weights, bool old_tail, bool verbose) {
     return ok;
 }
 
-template <int MB, int H, int WK>
+template <int MB, int H, int WK, int WN>
 int sweep(bool old_tail, bool verbose) {
     int bad = 0;
     for (int steps = 1; steps <= kMaxSteps; ++steps)
         for (int drop = 0; drop < 2; ++drop)
-            if (!check<MB, H, WK>(steps, drop != 0, old_tail, verbose)) ++bad;
+            if (!check<MB, H, WK, WN>(steps, drop != 0, old_tail, verbose)) ++bad;
     return bad;
 }
 
@@ -125,13 +125,16 @@ int main(int argc, char** argv) {
     const bool verbose = argc > 2 || (argc > 1 && !old_tail);
     int bad = 0;
     // every form launch_gemm / launch_gemm_batch can choose
-    bad += sweep<1, 2, 1>(old_tail, verbose);
-    bad += sweep<1, 4, 1>(old_tail, verbose);
-    bad += sweep<2, 2, 1>(old_tail, verbose);
-    bad += sweep<2, 3, 1>(old_tail, verbose);
-    bad += sweep<2, 4, 1>(old_tail, verbose);
-    bad += sweep<2, 2, 2>(old_tail, verbose);
-    bad += sweep<2, 4, 2>(old_tail, verbose);
+    bad += sweep<1, 2, 1, 4>(old_tail, verbose);
+    bad += sweep<1, 4, 1, 4>(old_tail, verbose);
+    bad += sweep<2, 2, 1, 4>(old_tail, verbose);
+    bad += sweep<2, 3, 1, 4>(old_tail, verbose);
+    bad += sweep<2, 4, 1, 4>(old_tail, verbose);
+    bad += sweep<2, 2, 2, 2>(old_tail, verbose);
+    bad += sweep<2, 4, 2, 2>(old_tail, verbose);
+    bad += sweep<2, 2, 1, 8>(old_tail, verbose);   // eight-wave forms (not instantiated by the library; the constants hold for them too)
+    bad += sweep<2, 2, 2, 4>(old_tail, verbose);
+    bad += sweep<2, 2, 4, 2>(old_tail, verbose);
     bad += copy_check<4>() + copy_check<6>();
     std::printf("%s: %d failing cases\n", old_tail ? "old tail count" : "current counts", bad);
     return bad == 0 ? 0 : 1;

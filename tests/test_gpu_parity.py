@@ -548,6 +548,34 @@ def test_split_decode_layer_shape_automatic(dev, ops):
     _assert_split(ops, dev, problems, True)
 
 
+@pytest.mark.parametrize("stream", [-1, 1])
+def test_decode_streaming_and_ordinary_weight_loads_agree(dev, ops, stream):
+    """The decode kernels exist in two forms that differ only in how weight tiles are loaded (streaming loads for large
+    launches, ordinary loads for small ones): forcing either form on launches of both sizes must not change a bit --
+    row-block kernel, matrix-core kernel, work-balanced kernel, fused and plain."""
+    from paper_2410_16144_amd import binding
+    problems = [_problem(2400 + i, M, K, N, p_zero=0.4, outl=0.01) for i, (M, K, N) in
+                enumerate(((1, 1536, 704), (1, 4096, 2048), (4, 1000, 330), (8, 2048, 512), (1, 8640, 3200)))]
+    ref = [_run_product(ops, dev, "gemv", w, s, x) for w, s, x in problems]
+    binding.bl_set_tuning("decode_stream", stream)
+    try:
+        for (w, s, x), r in zip(problems, ref):
+            got = _run_product(ops, dev, "gemv", w, s, x)
+            assert torch.equal(got[2], r[2]) and torch.equal(got[3], r[3])
+            name = binding.bl_last_kernel()
+            assert ("true>" if stream > 0 else "false>") in name.split(" grid=")[0][-8:], name
+            _assert_product(ops, dev, "gemv", w, s, x)
+        w, s, x = problems[4]
+        pw = ops.pack_ternary(torch.from_numpy(w).to(dev), float(s))
+        xd = _to_dev_bf16(x, dev) if x.dtype == np.uint16 else torch.from_numpy(x).to(dev)
+        grp = ops.DecodeGroup([pw, pw], [xd, xd], want_acc=True)
+        grp.launch()
+        torch.cuda.synchronize()
+        assert torch.equal(grp.accs[0], ref[4][3]) and torch.equal(grp.outs[1], ref[4][2])
+    finally:
+        binding.bl_set_tuning("decode_stream", 0)
+
+
 # ------------------------------------------------------------------ prefill product
 
 @pytest.mark.parametrize("M,N,K", [(1, 64, 64), (7, 70, 100), (33, 200, 1000), (128, 256, 512), (130, 320, 1536),
@@ -562,7 +590,7 @@ def test_gemm_parity_every_wave_tile(dev, ops, tile):
     from paper_2410_16144_amd import binding
     binding.bl_set_tuning("gemm_mb", tile)
     try:
-        for M, N, K in ((200, 1000, 832), (33, 200, 1000), (257, 704, 64 * 5)):
+        for M, N, K in ((200, 1000, 832), (33, 200, 1000), (257, 704, 64 * 5), (70, 600, 64 * 31)):
             w, s, x = _problem(M * 11 + N + K + tile, M, K, N, p_zero=0.4, outl=0.01)
             _assert_product(ops, dev, "gemm", w, s, x)
     finally:
@@ -637,14 +665,17 @@ def _launch_gemm(ops, pw, qa, out, acc):
                     qa.q.shape[0], out.data_ptr(), acc.data_ptr(), torch.cuda.current_stream().cuda_stream)
 
 
+@pytest.mark.parametrize("K", [192, 64 * 30])
 @pytest.mark.parametrize("tile", [12, 14, 22, 23, 24, 122, 124])
-def test_gemm_first_steps_under_load(dev, ops, tile):
-    """Short K (the whole product is the kernel's first few steps) and enough workgroups to keep every compute
-    unit's load queue busy, launched back to back: every launch must give the oracle's bits.  Guards the waits of
-    the activation ring's first stages, whose margin is the smallest when the memory system is busy."""
+def test_gemm_first_steps_under_load(dev, ops, tile, K):
+    """Short K and enough workgroups to keep every compute unit's load queue busy, launched back to back: every launch
+    must give the oracle's bits.  K = 192: the whole product is the kernel's first three steps (the waits of the
+    activation ring's first stages, whose margin is the smallest when the memory system is busy).  K = 1920: 30 steps
+    (15 with two K groups), i.e. three whole trips of the unrolled loop and a tail of six or seven steps, whose waits
+    count requests only."""
     from paper_2410_16144_amd import binding
-    M, N, K = 1024, 2048, 192          # 3 K steps; 128 to 1024 workgroups depending on the tile
-    w, s, x = _problem(5000 + tile, M, K, N, p_zero=0.4, outl=0.01)
+    M, N = 1024, 2048                  # 128 to 1024 workgroups depending on the tile
+    w, s, x = _problem(5000 + tile + K, M, K, N, p_zero=0.4, outl=0.01)
     q_ref, a_ref, s_ref = oracle.quant_act(x)
     acc_ref = torch.from_numpy(oracle.matmul_i32(q_ref, w)).to(dev)
     pw = ops.pack_ternary(torch.from_numpy(w).to(dev), float(s))
@@ -653,7 +684,7 @@ def test_gemm_first_steps_under_load(dev, ops, tile):
     accs = [torch.empty((M, N), dtype=torch.int32, device=dev) for _ in range(8)]
     binding.bl_set_tuning("gemm_mb", tile)
     try:
-        for rep in range(25):
+        for rep in range(25 if K < 1000 else 8):
             for o, a in zip(outs, accs):
                 _launch_gemm(ops, pw, qa, o, a)
             torch.cuda.synchronize()

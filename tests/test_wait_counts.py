@@ -91,24 +91,25 @@ def test_compiled_prefill_kernels_issue_what_the_model_assumes(tmp_path):
     fns = _functions(_compile_to_asm(tmp_path, "bl_gemm.hip"))
     seen = 0
     for name, lines in fns.items():
-        m = re.search(r"gemm_(?:batch_)?kernelILi(\d)ELi(\d)ELi(\d)E", name)
+        m = re.search(r"gemm_(?:batch_)?kernelILi(\d)ELi(\d)ELi(\d)ELi(\d)E", name)
         if not m:
             continue
         seen += 1
-        mb, h, wk = (int(x) for x in m.groups())
+        mb, h, wk, wn = (int(x) for x in m.groups())
         nt, lead = (h + 1) // 2, 4
         wr = 8 if nt == 1 else 4
-        younger, younger_tail, prologue = (lead - 2) * (wk + nt), (lead - 2) * wk, (lead - 3) * wk
+        rq = -(-(wk * 2 * mb) // (wn * wk))          # requests per loader thread and step
+        younger, younger_tail, prologue = (lead - 2) * (rq + nt), (lead - 2) * rq, (lead - 3) * rq
         seq = _barriers(lines)
         # prologue: the weight ring's first tiles and the first kLead requests, a wait that leaves kPrologueWait outstanding
-        assert seq[0][1] == lead * wk and seq[0][2] == (wr - 1) * nt and seq[0][0] is not None and seq[0][0] <= prologue, (name, seq[0])
+        assert seq[0][1] == lead * rq and seq[0][2] == (wr - 1) * nt and seq[0][0] is not None and seq[0][0] <= prologue, (name, seq[0])
         main = [b for b in seq[1:] if b[0] == younger]
         tail = [b for b in seq[1:] if b[0] == younger_tail]
         assert len(main) == 8 and len(tail) == 7, (name, seq)
-        for wait, lds, w in main:          # a step of the main loop: WK requests, at least the kNT weight loads
-            assert lds == wk and w >= nt, (name, seq)
-        for wait, lds, w in tail:          # a step of the tail: WK requests; its weight loads may be gone
-            assert lds == wk, (name, seq)
+        for wait, lds, w in main:          # a step of the main loop: kRQ requests, at least the kNT weight loads
+            assert lds == rq and w >= nt, (name, seq)
+        for wait, lds, w in tail:          # a step of the tail: kRQ requests; its weight loads may be gone
+            assert lds == rq, (name, seq)
     assert seen == 14                      # seven forms, single and batched
 
 
