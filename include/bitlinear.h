@@ -260,10 +260,24 @@ typedef struct {
  * BL_ERR_DTYPE).  `workspace_dev`: as for bl_gemv_batch (may be NULL).
  * Limit: M * Kp (+ 5 KiB per token) must fit the kernel's 128 KiB of
  * on-chip memory, else BL_ERR_SHAPE; use the two-call sequence then.
- * Every workgroup quantizes all M rows for itself, so the saving shrinks as M
- * grows: measured on MI355X (7B-shape layer) the fused launch wins up to
- * M = 2, is even at 4 and loses at 8 (28.8 against 18.1 us) to
- * bl_quant_act_batch + bl_gemv_batch.
+ * From two tokens up there are two forms.  With a workspace AND q_dev, a_scale_dev,
+ * q_sum_dev given for every item (vector-loadable rows: K and ldx multiples of 8,
+ * x_dev 16-byte aligned), every DISTINCT input -- items that name the same x_dev,
+ * ldx, K and the same three buffers -- is quantized once, by the launch's leading
+ * workgroups, one token row each, and published through those buffers; the other
+ * workgroups request their first weight tiles and then wait, a bounded number of
+ * polls, for their input's rows.  A workgroup whose polls run out goes on with
+ * whatever the buffers hold, so that every kernel ends, and sets the 32-bit word
+ * 256 bytes before the workspace's end to 1: results of such a launch are
+ * garbage and the workspace must be zeroed again (it never happened in testing
+ * other than forced through bl_set_tuning("decode_wait_limit", 1)).  Otherwise
+ * every workgroup quantizes all M rows for itself, which is bound by the vector
+ * ALU.  Measured on MI355X (7B-shape layer, 7 products on 4 inputs): M = 4 / 8:
+ * publishing 17.5 / 18.2 us, every workgroup for itself 17.7 / 27.6 us,
+ * bl_quant_act_batch + bl_gemv_batch 16.8 / 16.7 us -- the hand-over between
+ * workgroups (device-scope stores, their acknowledgement, the counter, the poll,
+ * the re-read) costs about what a kernel boundary costs, so the two-call sequence
+ * stays the one to prefer from about 4 tokens up.
  * Pointer alignment as for bl_quant_act / bl_gemv.
  * Errors: BL_ERR_NULL, BL_ERR_COUNT, BL_ERR_M_RANGE, BL_ERR_DTYPE,
  *         BL_ERR_LAYOUT, BL_ERR_SHAPE, BL_ERR_BUF_SMALL, BL_ERR_ALIGN, BL_ERR_HIP.
@@ -363,6 +377,8 @@ bl_status bl_tl2_gemv_batch(const bl_gemv_item *items, int32_t count, void *work
  * from staging the quantized activations in on-chip memory (0 = stage when they fit); "gemm_mb" = tile form of the prefill kernel as
  * 100*(WK-1) + 10*MB + H: wave tile (32*MB) tokens x (32*H) weight rows, WK of the workgroup's four waves along K and the rest
  * along N.  Forms: 12, 14, 22, 23, 24, 122, 124 (0 = automatic);
+ * "decode_publish" = fused launches of 2..8 tokens: 0 = quantize every distinct input once and publish it when the call allows it (see
+ * bl_decode_batch), -1 = never; "decode_wait_limit" = polls before a waiting workgroup of that form gives up (0 = the default, 262144);
  * "decode_stream" = how the decode kernels load weight tiles: 0 automatic (streaming, i.e. nontemporal, loads for launches of
  * 4 MiB of packed weights and more; ordinary loads below, so that a small model may stay in the memory-side cache), 1 always streaming, -1 never;
  * "attn_groups" = workgroups per head of bl_attn_decode (0 = automatic, else 1..65535, capped at the cache's chunks) -- the one

@@ -612,6 +612,16 @@ bl_status bl_set_tuning(const char* key, int32_t value) {
         bl::set_decode_split(value);
         return BL_OK;
     }
+    if (strcmp(key, "decode_publish") == 0) {
+        if (value < -1 || value > 0) return BL_ERR_SHAPE;
+        bl::set_decode_publish(value);
+        return BL_OK;
+    }
+    if (strcmp(key, "decode_wait_limit") == 0) {
+        if (value < 0) return BL_ERR_SHAPE;
+        bl::set_decode_wait_limit(value);
+        return BL_OK;
+    }
     if (strcmp(key, "decode_stream") == 0) {
         if (value < -1 || value > 1) return BL_ERR_SHAPE;
         bl::set_decode_stream(value);

@@ -222,12 +222,124 @@ constexpr int kMfmaInFlightDirect = 4;                 // ... when it is prefetc
 constexpr int kMfmaInFlightLds = 6;                    // weight tiles in flight when the A operand is in LDS
 constexpr int kMfmaRedBytes = kWaves * 16 * 32 * 4;   // per wave: 16 accumulator registers x 32 useful lanes
 
+// ---- publishing form: every distinct input is quantized ONCE per launch -------------------------------------------
+// The fused matrix-core kernel above makes every workgroup quantize all M token rows for itself, which is bound by the
+// vector ALU from a few tokens on.  In the publishing form the launch's FIRST workgroups are quantizers, one per
+// (distinct input, token row): each writes its row's int8 values, scale and sum to the caller's buffers with
+// device-scope stores (they go through to memory, past this die's cache), waits until those stores have completed,
+// and adds one to its input's "rows ready" counter.  All other workgroups request their first weight tiles, then
+// wait -- a bounded number of polls -- until their input's counter says M, and read the rows like a launch that was
+// given quantized activations.  Workgroups are dispatched in index order, so the quantizers are running before any
+// waiter can occupy a compute unit: nobody waits for a workgroup that has no place to run.  A waiter whose polls run
+// out sets the status word and goes on with whatever the buffers hold (every wave reaches the kernel's end); the
+// last waiter past its wait puts the counters back to zero.
+template <bool BF16>
+__device__ __forceinline__ void publish_row(const DecodeBatch& b, int M, int blk, float* s_f, int* s_i) {
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
+    const int input = blk / M, m = blk - input * M;
+    const DecodeProblem& p = b.p[b.pub_src[input]];
+    const int K = p.K, Kp = p.KC * kTileK;
+    const char* row = static_cast<const char*>(p.x) + (int64_t)m * p.ldx * (BF16 ? 2 : 4);
+    unsigned long long* qrow = reinterpret_cast<unsigned long long*>(p.q_out + (int64_t)m * Kp);
+    const bool in_regs = K <= 2 * kThreads * 8;   // uniform: two vectors per thread hold the row between the passes
+    const int k0 = tid * 8, k1 = k0 + kThreads * 8;
+    Raw8<BF16> r0 = {}, r1 = {};
+    float amax = 0.0f;
+    if (in_regs) {
+        r0 = load_raw8<BF16>(row, k0 < K ? k0 : 0);
+        r1 = load_raw8<BF16>(row, k1 < K ? k1 : 0);
+        float v[8];
+        unpack_raw8<BF16>(r0, v);
+        if (k0 < K) amax = absmax8(v);
+        unpack_raw8<BF16>(r1, v);
+        if (k1 < K) amax = fmaxf(amax, absmax8(v));
+    } else {
+        amax = thread_absmax<BF16, true>(row, K, tid, kThreads);
+    }
+    amax = wave_max(amax);
+    if (lane == 0) s_f[wave] = amax;
+    __syncthreads();
+    amax = s_f[0];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) amax = fmaxf(amax, s_f[w]);
+    float inv, scale;
+    quant_scales(amax, inv, scale);
+    int sum = 0;
+    const auto put = [&](int k, const float (&v)[8]) {
+        uint32_t lo, hi;
+        sum += quantize8_packed(v, inv, lo, hi);
+        __hip_atomic_store(qrow + k / 8, (unsigned long long)lo | ((unsigned long long)hi << 32), __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+    };
+    if (in_regs) {
+        float v[8];
+        unpack_raw8<BF16>(r0, v);
+        if (k0 < K) put(k0, v);
+        unpack_raw8<BF16>(r1, v);
+        if (k1 < K) put(k1, v);
+    } else {
+        for (int k = tid * 8; k < K; k += kThreads * 8) {
+            float v[8];
+            load8<BF16>(row, k, v);
+            put(k, v);
+        }
+    }
+    for (int k = K + tid * 8; k < Kp; k += kThreads * 8)   // layout padding (K is a multiple of 8 in this form)
+        __hip_atomic_store(qrow + k / 8, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    sum = wave_sum(sum);
+    if (lane == 0) s_i[wave] = sum;
+    __syncthreads();
+    if (tid == 0) {
+        int total = 0;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) total += s_i[w];
+        __hip_atomic_store(p.a_scale_out + m, scale, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(p.q_sum_out + m, total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    // every thread's stores have been performed before the workgroup says so: stores count as outstanding vector
+    // memory operations until they are acknowledged, and a workgroup barrier alone does not wait for them
+    __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0)
+    __syncthreads();
+    if (tid < kPubCopies)
+        __hip_atomic_fetch_add(b.pub_ctr + kPubReady + (input * kPubCopies + tid) * kPubStride, 1u, __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// The waiters' side: thread 0 polls, everybody leaves together.
+__device__ __forceinline__ void wait_for_published_rows(const DecodeBatch& b, int M, int input, int tid) {
+    if (tid == 0) {
+        unsigned int* ready = b.pub_ctr + kPubReady + (input * kPubCopies + (int)(blockIdx.x % kPubCopies)) * kPubStride;
+        int polls = 0;
+        unsigned int have = __hip_atomic_load(ready, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        while (have < (unsigned)M && ++polls < b.pub_limit) {
+            __builtin_amdgcn_s_sleep(8);
+            have = __hip_atomic_load(ready, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        if (have < (unsigned)M) __hip_atomic_store(b.pub_ctr + kPubStatus, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+}
+
+// At the END of a waiting workgroup (thread 0, nobody waits for it): count the workgroups that are through; the last one
+// puts the counters back to zero.  Not at the wait itself: a returning update of ONE word by every workgroup at the
+// moment the rows become ready queued them up for 8 us.
+__device__ __forceinline__ void leave_published_launch(const DecodeBatch& b) {
+    const unsigned int past = __hip_atomic_fetch_add(b.pub_ctr + kPubDone, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1;
+    if (past == (unsigned)(b.total_wgs - b.pub_rows)) {   // every waiter is past its wait: counters back to zero
+        for (int i = 0; i < BL_MAX_BATCH * kPubCopies; ++i)
+            __hip_atomic_store(b.pub_ctr + kPubReady + i * kPubStride, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(b.pub_ctr + kPubDone, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
 // QMODE: where the int8 activations (the A operand) come from
 //   0 = straight from global memory, prefetched with the weight tiles (any size)
 //   1 = copied once per workgroup from global memory into LDS (when M*Kp fits)
 //   2 = quantized by the workgroup into LDS (fused form)
-template <int M, int QMODE, bool XBF16, bool STREAM>
+// PUB: the publishing form (QMODE 0 or 1; XBF16 is then the dtype of the raw activations the quantizers read).
+template <int M, int QMODE, bool XBF16, bool STREAM, bool PUB = false>
 __global__ __launch_bounds__(kThreads, 8) void decode_mfma_kernel(BL_FIRST_WG_PARAMS, const DecodeBatch b) {
+    static_assert(!PUB || QMODE == 0 || QMODE == 1, "waiters read published rows like given ones");
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     constexpr bool kLdsQ = QMODE != 0;
     constexpr int U = kLdsQ ? kMfmaInFlightLds : kMfmaInFlightDirect;   // weight tiles in flight per wave
@@ -239,7 +351,14 @@ __global__ __launch_bounds__(kThreads, 8) void decode_mfma_kernel(BL_FIRST_WG_PA
     const int lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int blk = blockIdx.x;
-    const DecodeProblem& p = b.p[BL_PROBLEM_OF(blk)];
+    if constexpr (PUB) {
+        if (blk < b.pub_rows) {   // uniform: a quantizer workgroup
+            float* q_f = reinterpret_cast<float*>(smem);
+            publish_row<XBF16>(b, M, blk, q_f, reinterpret_cast<int*>(q_f + kWaves));
+            return;
+        }
+    }
+    const DecodeProblem& p = b.p[BL_PROBLEM_OF(blk)];   // (the problems' first workgroups lie behind the quantizers)
     const int wg = blk - p.first_wg;
 
     const int wlog2 = p.wlog2, G = 1 << wlog2;
@@ -262,20 +381,34 @@ __global__ __launch_bounds__(kThreads, 8) void decode_mfma_kernel(BL_FIRST_WG_PA
 
     uint4 w[U];
     v4i av[kLdsQ ? 1 : U];
-    auto load_batch = [&](int kc0) {
+    auto load_batch_part = [&](int kc0, bool weights, bool activations) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int k = kc0 + u * G;
             const int kk = k < KC ? k : KC - 1;   // clamped: always a valid tile
-            w[u] = load_weight_tile<STREAM>(wp + (int64_t)kk * kWave);
+            if (weights) w[u] = load_weight_tile<STREAM>(wp + (int64_t)kk * kWave);
             if constexpr (!kLdsQ) {
-                av[u] = v4i{0, 0, 0, 0};
-                if (has_row) av[u] = *reinterpret_cast<const v4i*>(reinterpret_cast<const int8_t*>(p.q) + a_off + kk * kTileK);
+                if (activations) {
+                    av[u] = v4i{0, 0, 0, 0};
+                    if (has_row) av[u] = *reinterpret_cast<const v4i*>(reinterpret_cast<const int8_t*>(p.q) + a_off + kk * kTileK);
+                }
             }
         }
     };
+    auto load_batch = [&](int kc0) { load_batch_part(kc0, true, true); };
 
-    if constexpr (QMODE == 1) {
+    if constexpr (PUB) {
+        // the weight tiles do not depend on the token: they are on their way while the quantizers work
+        load_batch_part(ks, true, false);
+        wait_for_published_rows(b, M, p.input, tid);
+        if constexpr (QMODE == 1) {
+            copy_to_lds_async(p.q, (uint32_t)(uintptr_t)(__attribute__((address_space(3))) int8_t*)lds_q, M * Kp / 16, tid, wave);
+            wait_lds_copy<0>();   // the copy is this thread's youngest request: everything has landed, the tiles too
+            __syncthreads();
+        } else {
+            load_batch_part(ks, false, true);
+        }
+    } else if constexpr (QMODE == 1) {
         // activations first, straight into LDS (loads retire in order: waiting for them leaves the weight tiles in flight)
         copy_to_lds_async(p.q, (uint32_t)(uintptr_t)(__attribute__((address_space(3))) int8_t*)lds_q, M * Kp / 16, tid, wave);
         load_batch(ks);
@@ -358,6 +491,9 @@ __global__ __launch_bounds__(kThreads, 8) void decode_mfma_kernel(BL_FIRST_WG_PA
             }
         }
     }
+    if constexpr (PUB) {
+        if (tid == 0) leave_published_launch(b);
+    }
     if constexpr (QMODE == 2) {
         if (wg == 0 && tid < M) {   // optional copy-out of the quantizer's scalars
             int qsum = 0;
@@ -394,14 +530,25 @@ hipError_t launch_mfma(const DecodeBatch& b, size_t lds_bytes, hipStream_t s) {
                     : launch_kernel<&decode_mfma_kernel<M, QMODE, XBF16, false>>(b, lds_bytes, s);
 }
 
-// KIND: 0 = dot-product kernel, plain; 1 = dot-product kernel, fused; 2..4 = matrix-core kernel with QMODE 0..2
+template <int M, int QMODE, bool XBF16>
+hipError_t launch_pub(const DecodeBatch& b, size_t lds_bytes, hipStream_t s) {
+    note_kernel("decode_mfma_kernel<%d, %d, %b, %b, true>", b.total_wgs, M, QMODE, XBF16, b.stream != 0);
+    return b.stream ? launch_kernel<&decode_mfma_kernel<M, QMODE, XBF16, true, true>>(b, lds_bytes, s)
+                    : launch_kernel<&decode_mfma_kernel<M, QMODE, XBF16, false, true>>(b, lds_bytes, s);
+}
+
+// KIND: 0 = dot-product kernel, plain; 1 = dot-product kernel, fused; 2..4 = matrix-core kernel with QMODE 0..2;
+// 5, 6 = publishing form of the matrix-core kernel with QMODE 0, 1
 template <int M, int KIND, bool XBF16>
 hipError_t launch_one(const DecodeBatch& b, size_t lds_bytes, hipStream_t s) {
     if constexpr (KIND == 0) return launch_dot<M, false, true>(b, lds_bytes, s);
     else if constexpr (KIND == 1) return launch_dot<M, true, XBF16>(b, lds_bytes, s);
     else if constexpr (KIND == 2) return launch_mfma<M, 0, true>(b, lds_bytes, s);
     else if constexpr (KIND == 3) return launch_mfma<M, 1, true>(b, lds_bytes, s);
-    else return launch_mfma<M, 2, XBF16>(b, lds_bytes, s);
+    else if constexpr (KIND == 4) return launch_mfma<M, 2, XBF16>(b, lds_bytes, s);
+    else if constexpr (M == 1) return hipErrorInvalidValue;   // the publishing form is for 2..8 tokens
+    else if constexpr (KIND == 5) return launch_pub<M, 0, XBF16>(b, lds_bytes, s);
+    else return launch_pub<M, 1, XBF16>(b, lds_bytes, s);
 }
 
 template <int KIND, bool XBF16>
@@ -423,6 +570,49 @@ int g_force_waves = 0;
 int g_force_path = 0;   // 0 auto, 1 dot4, 2 mfma
 int g_force_stage = 0;  // 1: never stage the activations in LDS (matrix-core kernel, plain form)
 int g_force_stream = 0; // weight tiles by streaming loads: 0 automatic, 1 always, -1 never
+int g_publish = 0;      // publishing form of fused launches of 2..8 tokens: 0 when possible, -1 never
+int g_wait_limit = 0;   // polls before a waiter gives up; 0: kDefaultWaitLimit
+constexpr int kDefaultWaitLimit = 1 << 18;   // a poll is a round trip to memory plus a short sleep, about a microsecond
+
+// Whether a fused launch can take the publishing form: a workspace for the counters, vector-loadable rows, and
+// buffers for the quantized rows of every problem (that is where they are published).
+bool can_publish(const DecodeBatch& b, int M) {
+    if (g_publish < 0 || M < 2 || !b.ws) return false;
+    for (int i = 0; i < b.count; ++i) {
+        const DecodeProblem& p = b.p[i];
+        if (!p.q_out || !p.a_scale_out || !p.q_sum_out || !(p.x_flags & 2) || p.gamma || p.ss_in || p.glu_gamma) return false;
+    }
+    return true;
+}
+
+// Numbers the distinct inputs (same rows, same destination buffers) and puts the quantizers in front of the grid.
+void plan_publish(DecodeBatch& b, int M) {
+    int inputs = 0;
+    for (int i = 0; i < b.count; ++i) {
+        DecodeProblem& p = b.p[i];
+        int found = -1;
+        for (int j = 0; j < inputs && found < 0; ++j) {
+            const DecodeProblem& o = b.p[b.pub_src[j]];
+            if (o.x == p.x && o.ldx == p.ldx && o.K == p.K && o.x_flags == p.x_flags && o.q_out == p.q_out &&
+                o.a_scale_out == p.a_scale_out && o.q_sum_out == p.q_sum_out)
+                found = j;
+        }
+        if (found < 0) {
+            found = inputs;
+            b.pub_src[inputs++] = i;
+        }
+        p.input = found;
+        // the waiters read what the quantizers publish
+        p.q = reinterpret_cast<const int32_t*>(p.q_out);
+        p.a_scale = p.a_scale_out;
+        p.q_sum = p.q_sum_out;
+    }
+    b.pub_rows = inputs * M;
+    for (int i = 0; i < b.count; ++i) b.p[i].first_wg += b.pub_rows;
+    b.total_wgs += b.pub_rows;
+    b.pub_limit = g_wait_limit > 0 ? g_wait_limit : kDefaultWaitLimit;
+    b.pub_ctr = reinterpret_cast<unsigned int*>(reinterpret_cast<char*>(b.ws) + BL_WORKSPACE_BYTES - kPubBytes);
+}
 
 // Launches whose weights could not stay in the 256 MB memory-side cache anyway stream them (nontemporal loads); small
 // launches, as the token loops of the smallest models make them, use ordinary loads so that the model may stay cached
@@ -445,6 +635,8 @@ void set_gemv_waves(int waves) { g_force_waves = waves; }
 void set_decode_path(int path) { g_force_path = path; }
 void set_decode_stage(int v) { g_force_stage = v; }
 void set_decode_stream(int v) { g_force_stream = v; }
+void set_decode_publish(int v) { g_publish = v; }
+void set_decode_wait_limit(int v) { g_wait_limit = v; }
 
 // LDS bytes of one launch; q_in_lds: the quantized activations live in LDS (fused, or staged copy)
 static size_t lds_bytes_for(int M, int64_t max_Kp, bool q_in_lds) {
@@ -530,6 +722,17 @@ hipError_t launch_decode(const DecodeBatch& batch, int M, bool fused, hipStream_
     for (int i = 0; i < b.count; ++i) max_Kp = (int64_t)b.p[i].KC * kTileK > max_Kp ? (int64_t)b.p[i].KC * kTileK : max_Kp;
     const bool bf16 = b.p[0].x_flags & 1;   // the fused form requires one activation dtype per launch
     if (use_mfma(M)) {
+        if (fused && can_publish(b, M)) {
+            // every distinct input quantized once by a leading workgroup; the rest of the launch is the plain form
+            const bool staged = (size_t)M * max_Kp <= (size_t)kMaxStagedBytes && g_force_stage != 1;
+            // twice the tiles per wave of the plain form: half the workgroups, so that (nearly) all of them are resident
+            // from the start and wait ONCE, together, instead of a second round paying start-up, wait and copy again
+            plan_decode(b, 2 * (staged ? kMfmaInFlightLds : kMfmaInFlightDirect));
+            plan_publish(b, M);
+            const size_t lds = lds_bytes_for(M, max_Kp, staged);
+            if (staged) return bf16 ? launch_m<6, true>(b, M, lds, s) : launch_m<6, false>(b, M, lds, s);
+            return bf16 ? launch_m<5, true>(b, M, lds, s) : launch_m<5, false>(b, M, lds, s);
+        }
         if (fused) {
             const size_t lds = lds_bytes_for(M, max_Kp, true);
             if (lds > (size_t)kMaxDecodeLds) return hipErrorInvalidValue;

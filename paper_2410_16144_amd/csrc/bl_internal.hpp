@@ -58,6 +58,7 @@ struct DecodeProblem {
     int32_t        wlog2;        // log2(waves that share one row block)
     int32_t        first_wg;     // first workgroup of this problem in the grid
     int32_t        chunk;        // balanced form: tiles per workgroup
+    int32_t        input;        // publishing form: which distinct input this problem reads
     // fused form with RMSNorm (one token, fp32 x, K <= 16384): activations = quantize((x + delta) * gamma); the norm's
     // scalar 1 / sqrt(mean((x + delta)^2) + eps) multiplies the activation scale instead of every element
     const float*   gamma;        // [K]; null: no norm
@@ -82,7 +83,25 @@ struct DecodeBatch {
     unsigned long long* ws;      // balanced form: the caller's workspace (zero between launches), or null
     int32_t       layout;        // 1: 2-bit tiles of 64 k; 2: TL2 codes, tiles of 72 k (one token, plain form only)
     int32_t       stream;        // host side only: weight tiles by streaming (nontemporal) loads; set by launch_decode
+    // publishing form (2..8 tokens, fused): the launch's first pub_rows workgroups quantize one token row of one distinct
+    // input each and publish it; the others wait for their input's rows (see decode_mfma_kernel)
+    int32_t       pub_rows;      // 0: not this form
+    int32_t       pub_limit;     // polls before a waiting workgroup gives up
+    int32_t       pub_src[BL_MAX_BATCH];   // distinct input i -> a problem that reads it
+    unsigned int* pub_ctr;       // counters in the caller's workspace: see kPub* below
 };
+
+// DecodeBatch::pub_ctr: the last kPubBytes of the workspace, all zero between launches like the rest of it.  Hundreds
+// of waiting workgroups polling ONE word queue up at one memory channel in front of the very update they are waiting
+// for (measured: a 13 us launch took 33), so every "rows ready" counter exists in kPubCopies copies, kPubStride words
+// apart: a quantizer adds to all of them, a waiter polls the copy of its workgroup index.
+constexpr int kPubCopies = 16;
+constexpr int kPubStride = 64;                                   // words: 256 bytes between copies
+constexpr int kPubReady = 0;                                     // [input][copy]: word (input * kPubCopies + copy) * kPubStride
+constexpr int kPubDone = BL_MAX_BATCH * kPubCopies * kPubStride; // waiting workgroups that have got past their wait
+constexpr int kPubStatus = kPubDone + kPubStride;                // set to 1 by a workgroup whose wait gave up; sticky
+constexpr int kPubBytes = (kPubStatus + kPubStride) * 4;
+static_assert(kPubBytes <= BL_WORKSPACE_BYTES / 4, "the counters live in the workspace's tail");
 
 // Which problem of the launch a workgroup belongs to.  The first workgroup of problems 1..7 (INT32_MAX beyond the
 // launch's count) LEADS the argument list of the decode and quantization kernels as seven scalars, because their files are
@@ -185,6 +204,8 @@ bool gemm_form_exists(int code);  // whether that code names a tile form the lib
 void set_decode_stage(int v);     // 1: the matrix-core decode kernel never stages activations in LDS
 void set_decode_split(int v);     // -1 never split row blocks over workgroups, 0 automatic, n: n workgroups per compute unit
 void set_decode_path(int path);   // 0 automatic, 1 dot-product kernel, 2 matrix-core kernel
+void set_decode_publish(int v);   // fused launches of 2..8 tokens quantize each input once and publish it: 0 when possible, -1 never
+void set_decode_wait_limit(int v);   // polls before a waiting workgroup gives up (0: the default)
 void set_decode_stream(int v);    // weight tiles by streaming loads: 0 automatic (by the launch's packed bytes), 1 always, -1 never
 int64_t split_launches();         // work-balanced decode launches so far (host-side count)
 

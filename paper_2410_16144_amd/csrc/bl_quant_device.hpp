@@ -139,6 +139,20 @@ __device__ __forceinline__ int quantize8(const float (&v)[8], float inv, int8_t*
     return sum;
 }
 
+// The same, the 8 bytes returned instead of stored.
+__device__ __forceinline__ int quantize8_packed(const float (&v)[8], float inv, uint32_t& lo, uint32_t& hi) {
+    lo = hi = 0;
+    int sum = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int a = quant_one(v[i], inv), b = quant_one(v[4 + i], inv);
+        sum += a + b;
+        lo |= (uint32_t)(a & 0xff) << (8 * i);
+        hi |= (uint32_t)(b & 0xff) << (8 * i);
+    }
+    return sum;
+}
+
 template <bool BF16>
 __device__ __forceinline__ float load1(const void* row, int k) {
     if constexpr (BF16) return bf16_to_f32(static_cast<const uint16_t*>(row)[k]);

@@ -267,12 +267,23 @@ class DecodeGroup:
             torch.empty((self.M, w.N), dtype=torch.float32, device=dev) for w in weights]
         self.accs = [torch.empty((self.M, w.N), dtype=torch.int32, device=dev) for w in weights] if want_acc else None
         self.quants = [alloc_quant(self.M, w.K, dev) for w in weights] if want_quant else None
+        # From two tokens up the library quantizes every distinct input ONCE per launch and publishes the rows through
+        # the items' quantization buffers (see bl_decode_batch): give it such buffers, one set per distinct input.
+        pub = self.quants
+        if pub is None and self.M >= 2 and self.workspace_ptr:
+            shared = {}
+            for w, x in zip(self.weights, self.xs):
+                key = (x.data_ptr(), x.stride(0), w.K)
+                if key not in shared:
+                    shared[key] = alloc_quant(self.M, w.K, dev)
+            pub = [shared[(x.data_ptr(), x.stride(0), w.K)] for w, x in zip(self.weights, self.xs)]
+        self.published = pub
         self.items = B.make_decode_items(
             (x.data_ptr(), _dtype_code(x), x.stride(0), w.blob.data_ptr(), w.desc, o.data_ptr(),
              self.accs[i].data_ptr() if want_acc else 0,
-             self.quants[i].q.data_ptr() if want_quant else 0,
-             self.quants[i].a_scale.data_ptr() if want_quant else 0,
-             self.quants[i].q_sum.data_ptr() if want_quant else 0)
+             pub[i].q.data_ptr() if pub else 0,
+             pub[i].a_scale.data_ptr() if pub else 0,
+             pub[i].q_sum.data_ptr() if pub else 0)
             for i, (w, x, o) in enumerate(zip(self.weights, self.xs, self.outs)))
 
     def launch(self):

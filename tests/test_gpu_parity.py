@@ -446,6 +446,83 @@ def test_fused_decode_equals_two_call_sequence(dev, ops):
     assert torch.equal(grp.quants[0].q_sum, qa.q_sum)
 
 
+@pytest.mark.parametrize("publish", [0, -1])
+@pytest.mark.parametrize("M", [2, 3, 4, 5, 6, 7, 8])
+def test_fused_decode_publishing_and_requantizing_forms(dev, ops, M, publish):
+    """Fused launches of 2..8 tokens: with a workspace and quantization buffers every distinct input is quantized once
+    by a leading workgroup and published (publish = 0); otherwise, or when forbidden (publish = -1), every workgroup
+    quantizes for itself.  Both against the oracle, a batch of mixed shapes (one long-K problem that is fetched per
+    tile at M = 8), and the workspace -- counters and status word included -- all zero afterwards."""
+    from paper_2410_16144_amd import binding
+    shapes = [(320, 640), (128, 640), (640, 320), (200, 1000), (1000, 200), (192, 64 * 131)]
+    binding.bl_set_tuning("decode_publish", publish)
+    try:
+        _assert_fused(ops, dev, [_problem(6100 + i + M, M, K, N, outl=0.01) for i, (N, K) in enumerate(shapes)], M)
+        name = binding.bl_last_kernel()
+        assert name.startswith("decode_mfma_kernel<%d, " % M)
+        assert (name.split(" grid=")[0].count(",") == 4) == (publish == 0), name     # the publishing form's name has a fifth argument
+    finally:
+        binding.bl_set_tuning("decode_publish", 0)
+    assert not ops.workspace(dev).any()
+
+
+def test_fused_decode_publishing_shared_inputs_like_a_layer(dev, ops):
+    """Seven products on four inputs, as a decoder layer has them, M = 4 and 8: without quantization outputs the binding
+    hands over one set of buffers per distinct input, so four inputs are quantized, not seven; results equal the
+    quantize-then-multiply sequence bit for bit, launch after launch."""
+    from paper_2410_16144_amd import binding
+    from paper_2410_16144_amd.decode_layer import INPUT_OF, make_layer
+    for M in (4, 8):
+        layer, host = make_layer(3, 0, 1024, 2752, M, dev, None, 0.0, host=True)
+        for rep in range(3):
+            for o in layer.outs:
+                o.zero_()
+            layer.step_fused()
+            name = binding.bl_last_kernel()
+            torch.cuda.synchronize()
+            assert name.split(" grid=")[0].count(",") == 4, name
+            fused = [o.clone() for o in layer.outs]
+            layer.step_two_launches()
+            torch.cuda.synchronize()
+            for a, b_ in zip(fused, layer.outs):
+                assert torch.equal(a, b_)
+        refs_q = [oracle.quant_act(b_) for b_ in host["x_bits"]]
+        for i, p in enumerate(layer.projs):
+            q, a, s = refs_q[INPUT_OF[p.name]]
+            _check_out(fused[i], oracle.matmul_i32(q, host["w"][i]), host["w_scale"][i], a)
+        assert len({id(q) for q in layer.fused_all.published}) == 4
+    assert not ops.workspace(dev).any()
+
+
+def test_fused_decode_publishing_wait_gives_up_and_every_kernel_exits(dev, ops):
+    """The waiters' polls are bounded.  With the limit forced down to one poll from the host they give up long before the
+    quantizers have published: the launch must still end (every wave reaches the exit), must say so in the status
+    word, and the same buffers must serve a correct launch once the workspace has been zeroed again."""
+    from paper_2410_16144_amd import binding
+    M = 4
+    probs = [_problem(6200 + i, M, K, N, outl=0.01) for i, (N, K) in enumerate([(2048, 4096), (1024, 4096), (4096, 2048)])]
+    weights = [ops.pack_ternary(torch.from_numpy(w).to(dev), float(s)) for w, s, x in probs]
+    xs = [_to_dev_bf16(x, dev) for w, s, x in probs]
+    ws = torch.zeros(binding.BL_WORKSPACE_BYTES, dtype=torch.uint8, device=dev)
+    grp = ops.DecodeGroup(weights, xs, want_acc=True, want_quant=True, use_workspace=ws)
+    binding.bl_set_tuning("decode_wait_limit", 1)
+    try:
+        grp.launch()
+        torch.cuda.synchronize()            # returns: nobody is left waiting
+    finally:
+        binding.bl_set_tuning("decode_wait_limit", 0)
+    words = ws.view(torch.int32)
+    assert int(words[-64]) == 1, "a waiter that gave up must leave the status word (the workspace's last 256 bytes) set"
+    ws.zero_()
+    grp.launch()
+    torch.cuda.synchronize()
+    for i, (w, s, x) in enumerate(probs):
+        q_ref, a_ref, s_ref = oracle.quant_act(x)
+        _assert_quant_equal(grp.quants[i], (q_ref, a_ref, s_ref), w.shape[1])
+        assert np.array_equal(grp.accs[i].cpu().numpy(), oracle.matmul_i32(q_ref, w))
+    assert not ws.any()
+
+
 # ------------------------------------------------------------------ work-balanced decode (workspace)
 
 @pytest.fixture

@@ -118,10 +118,12 @@ def test_compiled_decode_copy_waits_for_the_copy_only(tmp_path):
     fns = _functions(_compile_to_asm(tmp_path, "bl_gemv.hip", ("-mllvm", "-amdgpu-kernarg-preload-count=7")))
     seen = 0
     for name, lines in fns.items():
-        if not re.search(r"decode_mfma_kernelILi\dELi1E", name):     # QMODE 1: activations copied into LDS
+        # QMODE 1 (activations copied into LDS), either kind of weight load, not the publishing form (which issues
+        # the copy last and waits for everything)
+        if not re.search(r"decode_mfma_kernelILi\dELi1ELb\dELb\dELb0E", name):
             continue
         seen += 1
         first = _barriers(lines)[0]
         # the copy's requests, then exactly the 6 weight tiles of the first batch, and a wait that lets those 6 fly
         assert first[1] >= 1 and first[2] == 6 and first[0] == 6, (name, first)
-    assert seen == 8
+    assert seen == 16
