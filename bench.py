@@ -40,6 +40,9 @@ def parse_args():
     ap.add_argument("--no-extra", action="store_true", help="skip the extra sections")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--cpu-seconds", type=float, default=8.0, help="CPU work of the headline's oracle baseline")
+    ap.add_argument("--profiler-run", action="store_true",
+                    help="few launches per measurement (no clock ramp, no spread): for a profiler that collects counters "
+                         "and slows every dispatch; the times such a run prints are not results")
     ap.add_argument("--models", default="", help="with --only tokens: comma-separated Appendix-A model names (default: all 12)")
     ap.add_argument("--only", default="", help="run only one extra section (copy|ceilings|prefill|config1|config2|config3|decode100b|paper100b|appendixa|tokens|tokens8k|prompt|prompt2k|tl2) and print it")
     return ap.parse_args()
@@ -58,18 +61,25 @@ def timed(torch, fn):
     return e0.elapsed_time(e1), wall
 
 
+PROFILER_RUN = False   # --profiler-run: at most 100 steps, one untimed replay and one timed one per measurement, no spread
+
+
 def run_steps(torch, step_fns, count, use_graph, stats=None):
     """Time exactly `count` steps (step i = step_fns[i % len]).  With use_graph the steps are
     captured once into a HIP graph (one replay = all `count` steps) so that host launch overhead
     is out of the timed region; the replay itself is what is timed."""
     n = len(step_fns)
+    scale = 1.0
+    if PROFILER_RUN and count > 100:    # the caller divides by its own count
+        scale, count = count / 100.0, 100
 
     def eager():
         for i in range(count):
             step_fns[i % n]()
 
     if not use_graph:
-        return timed(torch, eager) + ("eager",)
+        ms, wall = timed(torch, eager)
+        return ms * scale, wall, "eager"
     g = torch.cuda.CUDAGraph()
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
@@ -80,19 +90,19 @@ def run_steps(torch, step_fns, count, use_graph, stats=None):
     # untimed replays: the first pays one-time upload costs, and the GPU needs some tens of milliseconds of
     # sustained work to reach its steady clocks (a 2 ms burst of the prefill kernel measures 25 % slower)
     t0 = time.perf_counter()
-    for _ in range(50):
+    for _ in range(1 if PROFILER_RUN else 50):
         g.replay()
         torch.cuda.synchronize()
         if time.perf_counter() - t0 > 0.05:
             break
     ms, wall = timed(torch, g.replay)
-    if stats is not None:   # further replays of the same K steps: spread of the per-step time
+    if stats is not None and not PROFILER_RUN:   # further replays of the same K steps: spread of the per-step time
         more = sorted([ms] + [timed(torch, g.replay)[0] for _ in range(4)])
         stats.update({"replays": len(more), "ms_per_step_min": round(more[0] / count, 6),
                       "ms_per_step_median": round(more[len(more) // 2] / count, 6),
                       "ms_per_step_max": round(more[-1] / count, 6)})
     del g
-    return ms, wall, "hip-graph"
+    return ms * scale, wall, "hip-graph"
 
 
 def check_layer_against_oracle(torch, np, oracle, layer, host):
@@ -248,7 +258,7 @@ def extra_prefill(torch, M, K, N, use_graph=True, iters=100):
     # bits stop toggling.  The gap to the real-data time is what the chip's power limit (lower sustained clock)
     # costs this kernel; it is reported beside the headline, never instead of it
     us_zero = None
-    if M >= 2048:
+    if True:
         qz = ops.quant_act(torch.zeros_like(x))
         ops.gemm(pw, qz, out)
         msz, _, _ = run_steps(torch, [lambda: ops.gemm(pw, qz, out)], iters, use_graph)
@@ -855,6 +865,8 @@ def main():
     binding.lib()  # raises if the HIP library is not built; there is no fallback
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     use_graph = not args.no_graph
+    global PROFILER_RUN
+    PROFILER_RUN = args.profiler_run
     sect = sections(torch, np, args, use_graph)
 
     if args.only:
