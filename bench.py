@@ -852,6 +852,32 @@ def sections(torch, np, args, use_graph):
     }
 
 
+def against_measured_ceilings(result, extra):
+    """Beside every roofline's `frac` (of the PUBLISHED peak): `frac_of_measured_ceiling`, the same launch against what the
+    committed probes reached in this run -- the read-only streaming kernel on a buffer of the same size (decode) or the
+    register-only matrix-core loop with in-register expansion at two waves per SIMD (prefill)."""
+    c = extra.get("ceilings")
+    if not c:
+        return
+    read_us = {r["buffer"]: r["streaming_loads"]["us"] for r in c["stream_read"]}
+    mfma = max(r["POPs"] for r in c["mfma_loop"] if r["operands"].startswith("expanded"))
+
+    def decode(block, buffer):
+        r = block.get("roofline")
+        if r and buffer in read_us:
+            r["frac_of_measured_ceiling"] = round(read_us[buffer] / r["avg_launch_us"], 4)
+            r["measured_ceiling"] = "read-only streaming kernel over %s: %.2f us" % (buffer, read_us[buffer])
+
+    decode(result, "100B-shape layer")
+    decode(extra.get("config2_3b_layer", {}), "3B-shape layer")
+    for block in extra.get("config3_7b_layer", []):
+        decode(block, "7B-shape layer")
+    for row in extra.get("config4_prefill", []):
+        r = row["roofline"]
+        r["frac_of_measured_ceiling"] = round(r["achieved"] / mfma, 4)
+        r["measured_ceiling"] = "register-only MFMA loop with in-register expansion: %.2f POP/s" % mfma
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -891,6 +917,7 @@ def main():
             print("bench: section %s done (%.0f s)" % (name, time.perf_counter() - t0), file=sys.stderr, flush=True)
         extra["decoder_tokens"] = extra_decoder_tokens(torch, ["700M", "7B", "30B"])
         torch.cuda.empty_cache()
+        against_measured_ceilings(result, extra)
         result["extra"] = extra
 
     print(json.dumps(result))
