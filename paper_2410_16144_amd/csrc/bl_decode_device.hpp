@@ -139,13 +139,61 @@ __device__ __forceinline__ void tl2_tile_mac(const uint4& w, const int32_t* __re
 // General form: the rows are read twice (the second read hits L1/L2).  Both passes walk the rows R at a
 // time with the R loads of a step issued together, so a pass costs one memory round trip per step
 // instead of one per row.
-template <int M, bool BF16, bool VEC>
+// LONG (one token): rows of up to kLongVectors * 8192 elements take the single-read path below.
+template <int M, bool BF16, bool VEC, bool LONG = false>
 __device__ __forceinline__ void quantize_rows_to_lds(const DecodeProblem& p, int8_t* lds_q, float* s_f, int* s_i,
                                                      int tid, int lane, int wave) {
     const int K = p.K, Kp = p.KC * kTileK;
     const char* x = static_cast<const char*>(p.x);
     const int64_t row_bytes = p.ldx * (BF16 ? 2 : 4);
     constexpr int R = !VEC ? 1 : M < (BF16 ? 4 : 2) ? M : (BF16 ? 4 : 2);   // rows whose vectors are in registers together
+    // One token with a long row (the 100B-shape down projection: 33792 elements): all of a thread's vectors are requested
+    // together and stay in registers between the two passes -- ONE memory round trip where the loops below take one per
+    // 8192 elements and pass, ten for such a row, during which the workgroup streams no weights.
+    constexpr int kLongVectors = BF16 ? 5 : 3;        // per thread: 20 (bf16) or 24 (fp32) registers
+    if constexpr (M == 1 && VEC && LONG) {
+        if (K <= kLongVectors * kThreads * 8) {       // uniform
+            Raw8<BF16> r[kLongVectors];
+            float am = 0.0f;
+#pragma unroll
+            for (int j = 0; j < kLongVectors; ++j) {
+                const int k = (tid + j * kThreads) * 8;
+                r[j] = load_raw8<BF16>(x, k < K ? k : 0);   // beyond the row: a valid address, the values unused
+            }
+#pragma unroll
+            for (int j = 0; j < kLongVectors; ++j) {
+                if ((tid + j * kThreads) * 8 < K) {
+                    float v[8];
+                    unpack_raw8<BF16>(r[j], v);
+                    am = fmaxf(am, absmax8(v));
+                }
+            }
+            am = wave_max(am);
+            if (lane == 0) s_f[wave] = am;
+            __syncthreads();
+            am = s_f[0];
+#pragma unroll
+            for (int w = 1; w < kWaves; ++w) am = fmaxf(am, s_f[w]);
+            float inv, scale;
+            quant_scales(am, inv, scale);
+            if (tid == 0) s_f[kWaves] = scale;
+            int sum = 0;
+#pragma unroll
+            for (int j = 0; j < kLongVectors; ++j) {
+                const int k = (tid + j * kThreads) * 8;
+                if (k < K) {
+                    float v[8];
+                    unpack_raw8<BF16>(r[j], v);
+                    sum += quantize8(v, inv, lds_q + k);
+                }
+            }
+            for (int k = K + tid; k < Kp; k += kThreads) lds_q[k] = 0;   // layout padding
+            sum = wave_sum(sum);
+            if (lane == 0) s_i[wave] = sum;
+            __syncthreads();
+            return;
+        }
+    }
     float amax[M];
 #pragma unroll
     for (int m = 0; m < M; ++m) amax[m] = 0.0f;

@@ -128,7 +128,7 @@ __global__ __launch_bounds__(kThreads, 8) void decode_sk_kernel(BL_FIRST_WG_PARA
                 __syncthreads();
             }
         } else {
-            if (vec) quantize_rows_to_lds<1, XBF16, true>(p, lds_q, s_f, s_i, tid, lane, wave);
+            if (vec) quantize_rows_to_lds<1, XBF16, true, true>(p, lds_q, s_f, s_i, tid, lane, wave);
             else quantize_rows_to_lds<1, XBF16, false>(p, lds_q, s_f, s_i, tid, lane, wave);
             load_batch(0);
         }

@@ -124,7 +124,7 @@ __global__ __launch_bounds__(kThreads, 8) void decode_kernel(BL_FIRST_WG_PARAMS,
             }
         } else {
             // general form: quantize first (its loads would otherwise have to wait for the weight tiles too)
-            if (vec) quantize_rows_to_lds<M, XBF16, true>(p, lds_q, s_f, s_i, tid, lane, wave);
+            if (vec) quantize_rows_to_lds<M, XBF16, true, M == 1>(p, lds_q, s_f, s_i, tid, lane, wave);
             else quantize_rows_to_lds<M, XBF16, false>(p, lds_q, s_f, s_i, tid, lane, wave);
             load_batch(ks);   // waves without a row block load (valid) block 0: no branch, exact wait counts
         }
