@@ -370,8 +370,8 @@ bl_status bl_tl2_gemv_batch(const bl_gemv_item *items, int32_t count, void *work
  * Launch-shape override for experiments and sweeps; process-wide, not thread-safe; the integer
  * and fp32 results of the products never change.  Keys: "gemv_waves" = waves of the decode kernel that share one
  * 64-row block (1, 2, 4, 8, 16; 0 = automatic); "decode_split" = work-balanced one-token launches: -1 never,
- * 0 automatic (by launch size), n = 1..8 always with n workgroups per compute unit when a
- * workspace is given and the launch has at least 8 tiles per workgroup; "decode_path" = 0 automatic
+ * 0 automatic (by launch size; never for the gated launch of bl_decode_norm_batch), n = 1..8 always with n workgroups per
+ * compute unit when a workspace is given and the launch has at least 8 tiles per workgroup; "decode_path" = 0 automatic
  * (dot-product kernel for M = 1, matrix-core kernel for M >= 2), 1 = always the
  * dot-product kernel, 2 = always the matrix-core kernel; "decode_stage" = 1 keeps the matrix-core kernel
  * from staging the quantized activations in on-chip memory (0 = stage when they fit); "gemm_mb" = tile form of the prefill kernel as

@@ -25,9 +25,12 @@ constexpr int kSumBits = 40;   // low bits of a workspace word that hold the par
 // LAYOUT 2: TL2-coded tiles (plain form only).  NORM (fp32 rows only): 1 = RMSNorm folded into the fused quantizer,
 // 2 = the row is already multiplied by its norm weight and sum(x^2) arrives in pieces.
 // STREAM: weight tiles by streaming (nontemporal) loads, see load_weight_tile.
-template <int U, bool FUSED, bool XBF16, int LAYOUT, int NORM, bool STREAM>
+// GLU (with NORM 1): gated epilogue (see DecodeProblem).  It pairs lanes l and l + 32 of a row block, so ONE wave must
+// finish all 64 rows of a shared row block: see the epilogue.
+template <int U, bool FUSED, bool XBF16, int LAYOUT, int NORM, bool STREAM, bool GLU = false>
 __global__ __launch_bounds__(kThreads, 8) void decode_sk_kernel(BL_FIRST_WG_PARAMS, const DecodeBatch b) {
     static_assert(LAYOUT == 1 || (LAYOUT == 2 && !FUSED), "the TL2 layout has the plain form only");
+    static_assert(!GLU || NORM == 1, "the gated epilogue comes with the folded norm");
     static_assert(NORM == 0 || (FUSED && !XBF16 && LAYOUT == 1), "the norm is folded into the fused quantizer of fp32 rows");
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     __shared__ int tl2_lut[LAYOUT == 2 ? 32 : 1];
@@ -188,17 +191,55 @@ __global__ __launch_bounds__(kThreads, 8) void decode_sk_kernel(BL_FIRST_WG_PARA
         bool last = true;
         if (t_first < a || t_end > e) {   // uniform: the row block is shared with other workgroups
             const int cnt = min(e, t_end) - max(a, t_first);
-            unsigned long long* slot = b.ws + (int64_t)(p.first_wg + t_first / p.chunk) * kWave + lane;
+            const int owner = p.first_wg + t_first / p.chunk;   // the workgroup that holds the block's first tile
+            unsigned long long* slot = b.ws + (int64_t)owner * kWave + lane;
             const unsigned long long add = ((unsigned long long)cnt << kSumBits) + (unsigned long long)(long long)v;
-            const unsigned long long now =
+            unsigned long long now =
                 __hip_atomic_fetch_add(slot, add, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + add;
-            const long long sum = (long long)(now << (64 - kSumBits)) >> (64 - kSumBits);
-            last = (long long)((now - (unsigned long long)sum) >> kSumBits) == KC;
-            total = (int)sum;
-            if (last) __hip_atomic_store(slot, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if constexpr (GLU) {
+                // Per-row counts cannot serve here: the 64 words lie in four cache lines, so two depositors may each be
+                // last on some of them, and the gated epilogue needs ONE wave with all 64 rows.  So: deposit (a
+                // returning operation: it has been performed where every die sees it once its value is back), wait
+                // for all 64 to return, THEN draw a ticket of `cnt` tiles from one word per row block.  Whoever's
+                // ticket completes the block's KC tiles reads the 64 sums -- every depositor's were performed before
+                // its ticket -- and puts words and ticket back to zero.  Nobody waits for anybody.
+                asm volatile("s_waitcnt vmcnt(0)" ::"v"(now) : "memory");
+                unsigned int* ticket = reinterpret_cast<unsigned int*>(reinterpret_cast<char*>(b.ws) + BL_WORKSPACE_BYTES - kPubBytes) + owner;
+                unsigned int drawn = 0;
+                if (lane == 0) drawn = __hip_atomic_fetch_add(ticket, (unsigned)cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + (unsigned)cnt;
+                last = __builtin_amdgcn_readfirstlane(drawn) == (unsigned)KC;   // uniform
+                if (last) {
+                    now = __hip_atomic_load(slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    __hip_atomic_store(slot, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    if (lane == 0) __hip_atomic_store(ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+                total = (int)((long long)(now << (64 - kSumBits)) >> (64 - kSumBits));
+            } else {
+                const long long sum = (long long)(now << (64 - kSumBits)) >> (64 - kSumBits);
+                last = (long long)((now - (unsigned long long)sum) >> kSumBits) == KC;
+                total = (int)sum;
+                if (last) __hip_atomic_store(slot, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
         }
         const int row = r * kTileN + lane;
-        if (last && row < p.N) {
+        if constexpr (GLU) {
+            if (last) {   // uniform: the whole wave holds the block's 64 complete sums
+                total -= qsum;
+                // lanes 0-31: gate rows, lanes 32-63: the up rows of the same 32 outputs
+                const float val = (float)total * ((lane < 32 ? p.w_scale : p.w_scale2) * scale);
+                const float up = __shfl_xor(val, 32);
+                const int n = r * 32 + (lane & 31);
+                float x = 0.0f, z = 0.0f;
+                if (lane < 32 && n < p.N / 2) {
+                    x = silu(val) * up;
+                    z = x * p.glu_gamma[n];
+                    p.out[n] = z;
+                }
+                const float ss = wave_sum_f(x * x), zmax = wave_max(fabsf(z));
+                if (lane == 0) p.ss_out[r] = make_float2(ss, zmax);
+                if (p.acc && row < p.N) p.acc[row] = total;
+            }
+        } else if (last && row < p.N) {
             total -= qsum;
             p.out[row] = (float)total * (p.w_scale * scale);
             if (p.acc) p.acc[row] = total;
@@ -216,11 +257,11 @@ hipError_t launch_sk_kernel(const DecodeBatch& b, size_t lds, hipStream_t s) {
     return hipGetLastError();
 }
 
-template <int U, bool FUSED, bool XBF16, int LAYOUT = 1, int NORM = 0>
+template <int U, bool FUSED, bool XBF16, int LAYOUT = 1, int NORM = 0, bool GLU = false>
 hipError_t launch_sk(const DecodeBatch& b, size_t lds, hipStream_t s) {
-    note_kernel("decode_sk_kernel<%d, %b, %b, %d, %d, %b>", b.total_wgs, U, FUSED, XBF16, LAYOUT, NORM, b.stream != 0);
-    return b.stream ? launch_sk_kernel<&decode_sk_kernel<U, FUSED, XBF16, LAYOUT, NORM, true>>(b, lds, s)
-                    : launch_sk_kernel<&decode_sk_kernel<U, FUSED, XBF16, LAYOUT, NORM, false>>(b, lds, s);
+    note_kernel("decode_sk_kernel<%d, %b, %b, %d, %d, %b, %b>", b.total_wgs, U, FUSED, XBF16, LAYOUT, NORM, b.stream != 0, GLU);
+    return b.stream ? launch_sk_kernel<&decode_sk_kernel<U, FUSED, XBF16, LAYOUT, NORM, true, GLU>>(b, lds, s)
+                    : launch_sk_kernel<&decode_sk_kernel<U, FUSED, XBF16, LAYOUT, NORM, false, GLU>>(b, lds, s);
 }
 
 int g_split = 0;   // -1 never, 0 automatic, n > 0: n workgroups per compute unit
@@ -247,7 +288,11 @@ int64_t split_launches() { return g_split_launches; }
 // form is not chosen by launch size (the caller then uses the row-block kernels).  Shapes only: no side effects.
 int decode_split_grid(const DecodeBatch& b, bool fused) {
     if (g_split < 0 || !b.ws) return 0;
-    if (b.p[0].glu_gamma) return 0;   // the gated epilogue pairs lanes of one wave: whole row blocks only
+    const bool glu = b.p[0].glu_gamma != nullptr;
+    // The gated launch takes the balanced form only when it is forced (bl_set_tuning "decode_split" > 0): measured on the
+    // gate/up launches of the twelve Appendix-A shapes it is ahead on two (3.8B: 7.3 -> 6.1 us, 30B: 13.1 -> 12.4) and
+    // behind on the rest (7B: 8.3 -> 10.2), where the row-block kernel with two row blocks per workgroup streams as fast.
+    if (glu && (b.count != 1 || g_split == 0)) return 0;
     const int cus = compute_unit_count();
     if (cus <= 0) return 0;
     int64_t total = 0;
@@ -278,6 +323,8 @@ int decode_split_grid(const DecodeBatch& b, bool fused) {
         }
     }
     const int64_t grid = (int64_t)cus * mult;
+    // (the gated form keeps one ticket word per workgroup in the workspace's tail, behind the sums)
+    if (glu && grid * kWave * 8 > BL_WORKSPACE_BYTES - kPubBytes) return 0;
     if (grid > BL_MAX_SPLIT_WGS || b.count > grid) return 0;
     if (total < grid * 8) return 0;   // under 8 tiles per workgroup: nothing to balance
     return (int)grid;
@@ -341,6 +388,8 @@ hipError_t launch_decode_split(const DecodeBatch& b, int tiles_per_wave, bool fu
     if (b.layout == 2) return small ? launch_sk<4, false, true, 2>(b, lds, s) : launch_sk<8, false, true, 2>(b, lds, s);
     if (!fused) return small ? launch_sk<4, false, true>(b, lds, s) : launch_sk<8, false, true>(b, lds, s);
     if (bf16) return small ? launch_sk<4, true, true>(b, lds, s) : launch_sk<8, true, true>(b, lds, s);
+    if (b.p[0].gamma && b.p[0].glu_gamma)
+        return small ? launch_sk<4, true, false, 1, 1, true>(b, lds, s) : launch_sk<8, true, false, 1, 1, true>(b, lds, s);
     if (b.p[0].gamma) return small ? launch_sk<4, true, false, 1, 1>(b, lds, s) : launch_sk<8, true, false, 1, 1>(b, lds, s);
     if (b.p[0].ss_in) return small ? launch_sk<4, true, false, 1, 2>(b, lds, s) : launch_sk<8, true, false, 1, 2>(b, lds, s);
     return small ? launch_sk<4, true, false>(b, lds, s) : launch_sk<8, true, false>(b, lds, s);

@@ -572,6 +572,30 @@ def test_gated_launch_and_its_consumer(dev, mods, K, F, with_delta):
     """Gate and up interleaved in one matrix: the launch's epilogue leaves silu(gate) * up * g_ffn and the pieces of
     sum((silu(gate) * up)^2); the down projection quantizes that row as it is.  Integer sums exact; the gate and up
     values reproduced with the kernel's own two fp32 products; the rest within fp32 tolerance of the fp64 formulas."""
+    _gated_case(dev, mods, K, F, with_delta)
+
+
+@pytest.mark.parametrize("split", [1, 2, 3])
+@pytest.mark.parametrize("K,F,with_delta", [(4096, 12032, True), (1536, 9216, False), (2560, 6912, True), (64, 32, True),
+                                          (5120, 13824, True), (192, 2080, False)])
+def test_gated_launch_work_balanced(dev, mods, split, K, F, with_delta):
+    """The same launch in the work-balanced form (forced: `split` workgroups per compute unit): row blocks cut across
+    workgroups are finished by whichever of them draws the block's last ticket, all 64 rows in one wave.  Run twice, so
+    that the second launch finds the workspace as the first left it; the launch taken is the balanced one."""
+    B, dec, ops = mods
+    B.bl_set_tuning("decode_split", split)
+    try:
+        before = B.bl_get_stat("split_launches")
+        for _ in range(2):
+            _gated_case(dev, mods, K, F, with_delta)
+        if K * F >= 2048 * 2048 * split:   # at least 8 tiles per workgroup: the balanced form is planned
+            assert B.bl_get_stat("split_launches") > before
+        assert not ops.workspace(dev).any(), "the workspace must be left zero"
+    finally:
+        B.bl_set_tuning("decode_split", 0)
+
+
+def _gated_case(dev, mods, K, F, with_delta):
     B, dec, ops = mods
     r = _rng(81000 + K + F)
     wg, wu, wd = synth.ternary_weights(r, F, K), synth.ternary_weights(r, F, K), synth.ternary_weights(r, 200, F)
