@@ -54,8 +54,6 @@ __global__ __launch_bounds__(kThreads, 8) void decode_kernel(BL_FIRST_WG_PARAMS,
     const bool active = rb < p.row_blocks;
     const int KC = p.KC;
     const int Kp = KC * kTileK;
-    // (the K tiles of a row block are dealt round-robin, so that the group's loads in flight cover one contiguous window
-    // of memory; cutting them into one contiguous piece per wave instead measured 20 % SLOWER on 100B-shape layers)
     const uint4* __restrict__ wp = p.packed + (int64_t)(active ? rb : 0) * KC * kWave + lane;
 
     // LDS carve-up: [quantized activations (fused only)] [partial sums] [small per-token scalars]
@@ -67,18 +65,28 @@ __global__ __launch_bounds__(kThreads, 8) void decode_kernel(BL_FIRST_WG_PARAMS,
 
     // first batch of weight tiles goes in flight before anything else
     uint4 w[kInFlight];
+    // How the G waves of a row block share its KC tiles.  Fused form: dealt round-robin (wave ks takes tiles ks, ks + G,
+    // ...), so that the group's loads in flight cover one contiguous window of memory.  Plain one-token form: one
+    // contiguous piece per wave -- measured 1.6 to 3.1 % faster there on 70B- and 100B-shape layers (100B shape: 72.0 ->
+    // 70.4 us), and 0.6 to 2 % SLOWER in the fused form, which therefore keeps the deal.
+    constexpr bool kPieces = !FUSED && M == 1 && LAYOUT == 1;
+    const int k_per = (KC + G - 1) >> wlog2;
+    const int k_begin = min(ks * k_per, KC - 1);                                     // a valid tile also for a wave without any
+    const int k_end = kPieces ? max(min(k_begin + k_per, KC), k_begin + 1) : KC;     // one past this wave's last tile
+    const bool has_tiles = !kPieces || ks * k_per < KC;
+    const int k_start = kPieces ? k_begin : ks, k_stride = kPieces ? 1 : G;
     auto load_part = [&](int kc0, int first, int last) {
 #pragma unroll
         for (int u = 0; u < kInFlight; ++u) {
             if (u >= first && u < last) {
-                const int k = kc0 + u * G;
-                w[u] = load_weight_tile<STREAM>(wp + (int64_t)(k < KC ? k : KC - 1) * kWave);   // clamped: always a valid tile
+                const int k = kc0 + u * k_stride;
+                w[u] = load_weight_tile<STREAM>(wp + (int64_t)(k < k_end ? k : k_end - 1) * kWave);   // clamped: always a valid tile
             }
         }
     };
     auto load_batch = [&](int kc0) { load_part(kc0, 0, kInFlight); };
     if constexpr (!FUSED) {
-        load_batch(ks);   // waves without a row block load (valid) block 0: no branch, exact wait counts
+        load_batch(k_start);   // waves without a row block load (valid) block 0: no branch, exact wait counts
     } else {
         const bool vec = p.x_flags & 2;
         bool fast = false;
@@ -118,15 +126,15 @@ __global__ __launch_bounds__(kThreads, 8) void decode_kernel(BL_FIRST_WG_PARAMS,
                     }
                 }
                 // (the waves that hold gamma and delta as well have no registers for early tiles; the others do)
-                if (!folded) load_part(ks, 0, kInFlight / 2);
+                if (!folded) load_part(k_start, 0, kInFlight / 2);
                 quantize_row_from_regs<XBF16>(r0, r1, h0, h1, k0, k1, holders, p.K, Kp, lds_q, s_f, s_i, tid, lane, wave);
-                load_part(ks, folded ? 0 : kInFlight / 2, kInFlight);
+                load_part(k_start, folded ? 0 : kInFlight / 2, kInFlight);
             }
         } else {
             // general form: quantize first (its loads would otherwise have to wait for the weight tiles too)
             if (vec) quantize_rows_to_lds<M, XBF16, true, M == 1>(p, lds_q, s_f, s_i, tid, lane, wave);
             else quantize_rows_to_lds<M, XBF16, false>(p, lds_q, s_f, s_i, tid, lane, wave);
-            load_batch(ks);   // waves without a row block load (valid) block 0: no branch, exact wait counts
+            load_batch(k_start);   // waves without a row block load (valid) block 0: no branch, exact wait counts
         }
         if (wg == 0 && p.q_out) {   // optional copy-out of the quantized activations
             for (int i = tid; i < M * Kp / 4; i += kThreads)
@@ -143,11 +151,11 @@ __global__ __launch_bounds__(kThreads, 8) void decode_kernel(BL_FIRST_WG_PARAMS,
     }
 
     if (active) {
-        for (int kc0 = ks;;) {
+        for (int kc0 = k_start;;) {
 #pragma unroll
             for (int u = 0; u < kInFlight; ++u) {
-                const int k = kc0 + u * G;
-                if (k < KC) {
+                const int k = kc0 + u * k_stride;
+                if (k < k_end && has_tiles) {
                     if constexpr (LAYOUT == 2) tl2_tile_mac(w[u], p.q + k * kTl2QWords, tl2_lut, a.lo[0]);
                     else if constexpr (FUSED) tile_mac<M>(w[u], reinterpret_cast<const int32_t*>(lds_q) + k * 16, Kp / 4, a);
                     else tile_mac<M>(w[u], p.q + k * 16, Kp / 4, a);
@@ -156,8 +164,8 @@ __global__ __launch_bounds__(kThreads, 8) void decode_kernel(BL_FIRST_WG_PARAMS,
                 // opposite: the next tile's table lookups under this tile's dot products)
                 if constexpr (LAYOUT == 1) __builtin_amdgcn_sched_barrier(0);
             }
-            kc0 += G * kInFlight;
-            if (kc0 >= KC) break;
+            kc0 += k_stride * kInFlight;
+            if (kc0 >= k_end) break;
             load_batch(kc0);
         }
     }
